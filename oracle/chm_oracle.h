@@ -1,0 +1,106 @@
+/*
+ * CPU oracle for post-failure execution-plan scoring (Chameleon, arXiv 2508.21613).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This is the slow, plain, single-threaded definition of
+ * what the HIP library computes.  It shares no code, header, table or helper with
+ * the HIP path and must never be called from it.  Only tests, the smoke check and
+ * the CPU-baseline leg of the benchmark may load it.
+ *
+ * What each function follows:
+ *   - plan tuple (policy, layer distribution, data distribution, failed-node
+ *     distribution): Definition 1 ("State") of the Performance Modeling section.
+ *   - 1F1B dependency recurrence: Estimator subsection, eq. (transition):
+ *     start(i,j) = max(end(i,j-1), end(f1(i), f2(j))) with f1(i)=i-1 for a forward
+ *     and i+1 for a backward, f2 = same micro-batch.
+ *   - step time of several pipelines = max over pipelines: Estimator subsection,
+ *     the equation after eq. (original_step_time).
+ *   - data rerouting penalty: eq. (recycle_step_time) and (recycle_step_time_multi).
+ *   - batch distribution over pipelines: Planner subsection, "Batch Distribution".
+ *   - OOM filter: Planner "Layer Distribution" + Memory Estimator.
+ *   - transition time = restart constant + weight transfer: Estimator subsection,
+ *     paragraph on dynamic parallelism; negligible for rerouting.
+ *   - argmin with first-strict-minimum: Algorithm 1, get_execution_plan.
+ *
+ * Pure conventions with no counterpart in the paper ("parity unpinned": only
+ * self-consistency can be tested): plan index order, the fault-free layout P0,
+ * the Q16 rounding rule, the redundant-computation load model, the linear cost
+ * horizon*t_step + t_trans, and the default constants.
+ */
+#ifndef CHM_ORACLE_H
+#define CHM_ORACLE_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum { ORC_OK = 0, ORC_ERR_ARG = -1, ORC_ERR_RANGE = -2, ORC_ERR_OVERFLOW = -3,
+       ORC_ERR_UNRECOVERABLE = -4, ORC_ERR_NO_FEASIBLE = -5 };
+
+enum { ORC_MAX_L = 128, ORC_MAX_PP = 32, ORC_MAX_DP = 16, ORC_MAX_M = 256, ORC_MAX_FAILED = 4 };
+
+#define ORC_INF INT64_MAX
+
+typedef struct {
+  int32_t L, PP, DP, M;
+  const int32_t *fwd_us, *bwd_us, *mem_mib;   /* [L] */
+  const uint32_t *speed_q16;                  /* [DP*PP] node id = d*PP+s; NULL = all 65536 */
+  int32_t n_failed;
+  const int32_t *failed_nodes;                /* [n_failed] */
+  int32_t comm_us, mem_cap_mib, reroute_cap, horizon_steps;
+  int32_t reconf_us[3];
+  int32_t xfer_us_per_mib;
+} orc_desc;
+
+typedef struct { uint64_t offset, n_part, n_reroute; int32_t stages, strategy; } orc_family;
+typedef struct { int32_t n_families; orc_family fam[3]; uint64_t n_plans; } orc_space;
+
+typedef struct {
+  uint64_t index; int64_t cost; int32_t strategy, stages;
+  uint8_t cuts[32];            /* cuts[0..stages-2] = c_1 < ... < c_k                      */
+  int32_t n_affected;          /* affected stages (ascending) for the rerouting family     */
+  int32_t affected_stage[4];
+  uint16_t reroute[4][16];     /* reroute[a][d] = extra micro-batches on replica d (0 for a failed node) */
+} orc_plan;
+
+/* --- building blocks, exposed so that tests can pin each one on its own ---------------- */
+uint64_t orc_binom(int32_t n, int32_t k);                       /* saturates at UINT64_MAX */
+uint64_t orc_partition_rank(int32_t k, const uint8_t *cuts);
+int      orc_partition_unrank(int32_t L, int32_t k, uint64_t rank, uint8_t *cuts);
+uint64_t orc_reroute_count(int32_t parts, int32_t total, int32_t cap);
+int      orc_reroute_unrank(int32_t parts, int32_t total, int32_t cap, uint64_t rank, uint16_t *r);
+uint64_t orc_reroute_rank(int32_t parts, int32_t total, int32_t cap, const uint16_t *r);
+int64_t  orc_scale_q16(int64_t x, uint32_t q);
+int64_t  orc_makespan_1f1b(int32_t S, const int64_t *F, const int64_t *B, int32_t M);
+/* MiB of [a,b) not already held by a node that held [a0,b0); pw = prefix sums of mem, length L+1 */
+int64_t  orc_missing_interval(const int64_t *pw, int32_t a, int32_t b, int32_t a0, int32_t b0);
+void     orc_distribute_batch(int32_t D, int32_t total, const int32_t *nodes, int32_t *out);
+void     orc_layout_p0(int32_t L, int32_t S, int32_t *bounds /* [S+1] */);
+
+/* --- scenario level ------------------------------------------------------------------- */
+typedef struct orc_scenario orc_scenario;
+int  orc_open(const orc_desc *d, orc_scenario **out);
+void orc_close(orc_scenario *s);
+int  orc_plan_space(const orc_scenario *s, orc_space *out);
+int  orc_decode(const orc_scenario *s, uint64_t index, orc_plan *out);
+/* cost of one explicit plan (no ranking involved): strategy 0/1/2, stage bounds via cuts,
+ * reroute[a*16+d] for the rerouting family.  ORC_INF when memory-infeasible. */
+int  orc_plan_cost(const orc_scenario *s, int32_t strategy, int32_t k, const uint8_t *cuts,
+                   const uint16_t *reroute, int64_t *cost);
+int  orc_score(const orc_scenario *s, uint64_t first, uint64_t count, int64_t *costs);
+int  orc_score_ranks(const orc_scenario *s, int32_t strategy, const uint64_t *part_ranks,
+                     uint64_t n, int64_t *costs);
+/* exhaustive argmin; the rerouting family is searched stage by stage (its penalty is a
+ * sum of independent per-stage terms), which gives the same answer as the joint sweep. */
+int  orc_search(const orc_scenario *s, uint32_t strategy_mask, orc_plan *best);
+/* the same over a sub-range of partition ranks of one family (for bounded timing runs);
+ * *evals receives the number of (partition, reroute vector) evaluations done. */
+int  orc_search_range(const orc_scenario *s, int32_t strategy, uint64_t part_first,
+                      uint64_t part_count, orc_plan *best, uint64_t *evals);
+/* plain joint sweep over every index in [first, first+count): slow, for tiny cases */
+int  orc_search_joint(const orc_scenario *s, uint64_t first, uint64_t count, orc_plan *best);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -1,0 +1,157 @@
+"""Seeded synthetic failure scenarios (inputs only; none of the method's arithmetic).
+
+The paper profiles per-layer times and memory of Llama-2 7B on its own cluster
+(Evaluation, Experimental Setup); this path consumes only such tables, so tables
+drawn from fixed distributions stand in for the profiled ones.  Every number comes
+from a counter-based generator (a 64-bit mix of seed, stream and position), so the
+same call always gives the same arrays, and both the HIP library and the CPU oracle
+are handed these very arrays.
+"""
+import numpy as np
+
+_M64 = (1 << 64) - 1
+
+DEFAULTS = dict(horizon_steps=2048, reconf_us=(0, 8_000_000, 0), xfer_us_per_mib=100, reroute_cap=0)
+BASE_SEED = 20250821
+
+
+def _mix(seed, stream, n):
+    """n 64-bit words: splitmix64 finaliser over (seed, stream, counter)."""
+    i = np.arange(n, dtype=np.uint64)
+    with np.errstate(over="ignore"):
+        z = (np.uint64(seed & _M64) * np.uint64(0x9E3779B97F4A7C15)
+             + np.uint64(stream & _M64) * np.uint64(0xD1B54A32D192ED03)
+             + (i + np.uint64(1)) * np.uint64(0x8CB92BA72F3D8DD7))
+        z ^= z >> np.uint64(30)
+        z *= np.uint64(0xBF58476D1CE4E5B9)
+        z ^= z >> np.uint64(27)
+        z *= np.uint64(0x94D049BB133111EB)
+        z ^= z >> np.uint64(31)
+    return z
+
+
+def uniform01(seed, stream, n):
+    """doubles in [0,1) with 53 random bits"""
+    return (_mix(seed, stream, n) >> np.uint64(11)).astype(np.float64) * (1.0 / (1 << 53))
+
+
+def randint(seed, stream, n, lo, hi):
+    """integers uniform on [lo, hi] (inclusive)"""
+    return (lo + np.floor(uniform01(seed, stream, n) * (hi - lo + 1))).astype(np.int64)
+
+
+def normal(seed, stream, n):
+    """standard normals by Box-Muller in double precision"""
+    u1 = 1.0 - uniform01(seed, stream, n)          # (0,1]
+    u2 = uniform01(seed, stream + 1000003, n)
+    return np.sqrt(-2.0 * np.log(u1)) * np.cos(2.0 * np.pi * u2)
+
+
+def layer_tables(seed, L, dist="uniform", mem_lo=400, mem_hi=600):
+    """per-layer forward / backward time (int32 us) and memory (int32 MiB)"""
+    if dist == "uniform":
+        fwd = randint(seed, 1, L, 800, 1200)
+    elif dist == "lognormal":
+        fwd = np.rint(1000.0 * np.exp(0.3 * normal(seed, 1, L))).astype(np.int64)
+    else:
+        raise ValueError(dist)
+    u = 0.9 + 0.2 * uniform01(seed, 2, L)
+    bwd = np.rint(2.0 * fwd * u).astype(np.int64)
+    mem = randint(seed, 3, L, mem_lo, mem_hi)
+    return fwd.astype(np.int32), bwd.astype(np.int32), mem.astype(np.int32)
+
+
+def speed_factors(seed, D, S, lo=0.85, hi=1.15):
+    """per-node time multipliers in Q16 (65536 = nominal), node id = d*S + s"""
+    u = lo + (hi - lo) * uniform01(seed, 4, D * S)
+    return np.rint(u * 65536.0).astype(np.uint32)
+
+
+def scenario(L, PP, DP, M, fwd, bwd, mem, failed, comm_us, mem_cap_mib, speed=None, **kw):
+    sc = dict(L=L, PP=PP, DP=DP, M=M, fwd_us=fwd, bwd_us=bwd, mem_mib=mem, speed_q16=speed,
+              failed_nodes=[int(x) for x in failed], comm_us=comm_us, mem_cap_mib=mem_cap_mib)
+    sc.update(DEFAULTS)
+    sc.update(kw)
+    sc["reconf_us"] = tuple(int(x) for x in sc["reconf_us"])
+    return sc
+
+
+def config1(seed=BASE_SEED + 1):
+    """Tiny exhaustive: L=32, PP=4, DP=2, M=8, one failed node picked uniformly."""
+    fwd, bwd, mem = layer_tables(seed, 32)
+    failed = randint(seed, 5, 1, 0, 4 * 2 - 1)
+    return scenario(32, 4, 2, 8, fwd, bwd, mem, failed, 150, 8000)
+
+
+def config2(seed=BASE_SEED + 2):
+    """32-card shape: L=48, PP=8, DP=4, M=16, one failed node."""
+    fwd, bwd, mem = layer_tables(seed, 48)
+    failed = randint(seed, 5, 1, 0, 8 * 4 - 1)
+    return scenario(48, 8, 4, 16, fwd, bwd, mem, failed, 200, 12000)
+
+
+def config3(seed=BASE_SEED + 3):
+    """Heterogeneous rerouting: L=40, PP=4, DP=8, M=32, two failed nodes in different
+    stages (and different replicas), Q16 speed factors, at most M/2 extra micro-batches per peer."""
+    fwd, bwd, mem = layer_tables(seed, 40)
+    s = randint(seed, 5, 2, 0, 3)
+    d = randint(seed, 6, 2, 0, 7)
+    s1 = int(s[0]); s2 = int(s[1]) if s[1] != s[0] else (int(s[0]) + 1) % 4
+    d1 = int(d[0]); d2 = int(d[1]) if d[1] != d[0] else (int(d[0]) + 1) % 8
+    failed = [d1 * 4 + s1, d2 * 4 + s2]
+    return scenario(40, 4, 8, 32, fwd, bwd, mem, failed, 150, 10000,
+                    speed=speed_factors(seed, 8, 4), reroute_cap=16)
+
+
+def config4(seed=BASE_SEED + 4):
+    """Large random batch: L=96, PP=16, DP=2, M=64, one failure, lognormal layer times;
+    the plans are explicit random partitions (see random_partitions)."""
+    fwd, bwd, mem = layer_tables(seed, 96, dist="lognormal", mem_lo=300, mem_hi=900)
+    failed = randint(seed, 5, 1, 0, 16 * 2 - 1)
+    return scenario(96, 16, 2, 64, fwd, bwd, mem, failed, 200, 6000)
+
+
+def config5_tables(seed=BASE_SEED + 5):
+    return layer_tables(seed, 40)
+
+
+def config5_failure_sets():
+    """all 32 single and 496 double node failures of the 8x4 grid"""
+    sets = [[a] for a in range(32)]
+    sets += [[a, b] for a in range(32) for b in range(a + 1, 32)]
+    return sets
+
+
+def config5(failed, seed=BASE_SEED + 5):
+    """Failure sweep: L=40, PP=8, DP=4, M=16, one shared table, a given failure set."""
+    fwd, bwd, mem = config5_tables(seed)
+    return scenario(40, 8, 4, 16, fwd, bwd, mem, failed, 200, 10000)
+
+
+def random_partitions(seed, stream, n, L, k):
+    """n partitions, each k distinct cut points drawn without replacement from 1..L-1 and
+    sorted; returned as an (n, k) uint8 array.  Duplicates between partitions are kept."""
+    keys = _mix(seed, stream, n * (L - 1)).reshape(n, L - 1)
+    order = np.argsort(keys, axis=1, kind="stable")[:, :k]
+    return (np.sort(order, axis=1) + 1).astype(np.uint8)
+
+
+def small_random(seed, L=None, PP=None, DP=None, M=None, n_failed=None, hetero=None, cap=None):
+    """a small random scenario for parity tests (shape drawn from the seed unless given)"""
+    r = randint(seed, 11, 8, 0, 1 << 30)
+    PP = PP if PP is not None else 2 + int(r[0] % 4)
+    L = L if L is not None else PP + 1 + int(r[1] % 8)
+    DP = DP if DP is not None else 2 + int(r[2] % 3)
+    M = M if M is not None else 1 + int(r[3] % 9)
+    n_failed = n_failed if n_failed is not None else 1 + int(r[4] % 2)
+    hetero = hetero if hetero is not None else bool(r[5] % 2)
+    fwd, bwd, mem = layer_tables(seed, L)
+    nodes = np.argsort(_mix(seed, 12, DP * PP), kind="stable")[:n_failed]
+    speed = speed_factors(seed, DP, PP) if hetero else None
+    total = int(mem.sum())
+    mem_cap = int(total * (1.6 + 0.1 * int(r[6] % 8)) / PP)
+    kw = {}
+    if cap is not None:
+        kw["reroute_cap"] = cap
+    return scenario(L, PP, DP, M, fwd, bwd, mem, sorted(int(x) for x in nodes), 100 + int(r[7] % 100), mem_cap,
+                    speed=speed, **kw)

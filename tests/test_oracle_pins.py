@@ -1,0 +1,426 @@
+"""Pins of the CPU oracle against what the paper and the mathematics fix (no GPU).
+
+Each test is chosen so that a plausible slip in the oracle (a dropped term, a wrong sign
+or index, a swapped operand, an off-by-one in a rank) fails it.
+"""
+import itertools
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2508_21613_amd import synth
+from tests import ref_model as R
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def golden():
+    out = {}
+    with open(os.path.join(HERE, "golden", "paper_examples.txt")) as fh:
+        for line in fh:
+            line = line.split("#")[0].strip()
+            if line:
+                k, v = line.split("=")
+                out[k.strip()] = v.strip()
+    return out
+
+
+def uniform_scenario(S, D, M, per_stage, f, b, failed, comm=0, cap=10 ** 6, **kw):
+    L = S * per_stage
+    return synth.scenario(L, S, D, M, np.full(L, f, np.int32), np.full(L, b, np.int32),
+                          np.full(L, 1, np.int32), failed, comm, cap, **kw)
+
+
+def even_cuts(S, per_stage):
+    return [per_stage * j for j in range(1, S)]
+
+
+# ----------------------------------------------------------------------------- pipeline time
+def test_uniform_pipeline_matches_closed_form():
+    """Estimator, eq. (original_step_time), for every S<=16, M<=64 (also M < S and S = 1)"""
+    for S in range(1, 17):
+        for M in range(1, 65):
+            assert O.makespan_1f1b([700] * S, [1900] * S, M) == (S + M - 1) * 2600
+
+
+def test_paper_example_values():
+    g = golden()
+    assert O.makespan_1f1b([1000] * 8, [2000] * 8, 16) == int(g["step_uniform_8_16_1000_2000"])
+
+
+def test_makespan_equals_longest_path_of_explicit_graph():
+    rng = np.random.default_rng(7)
+    for _ in range(150):
+        S, M = int(rng.integers(1, 7)), int(rng.integers(1, 9))
+        F = [int(x) for x in rng.integers(1, 50, S)]
+        B = [int(x) for x in rng.integers(1, 90, S)]
+        assert O.makespan_1f1b(F, B, M) == R.dag_makespan(F, B, M), (F, B, M)
+
+
+def test_makespan_lower_bounds_and_monotonicity():
+    rng = np.random.default_rng(11)
+    for _ in range(200):
+        S, M = int(rng.integers(1, 10)), int(rng.integers(1, 20))
+        F = rng.integers(1, 3000, S)
+        B = rng.integers(1, 6000, S)
+        T = O.makespan_1f1b(F, B, M)
+        assert T >= M * int((F + B).max())            # the busiest stage runs M forwards and M backwards
+        assert T >= int(F.sum() + B.sum())            # one micro-batch crosses every stage twice
+        assert T <= (S + M - 1) * (int(F.max()) + int(B.max()))
+        s = int(rng.integers(0, S))
+        F2, B2 = F.copy(), B.copy()
+        (F2 if rng.integers(2) else B2)[s] += int(rng.integers(1, 500))
+        assert O.makespan_1f1b(F2, B2, M) >= T
+
+
+def test_single_stage_and_single_microbatch():
+    assert O.makespan_1f1b([5], [9], 7) == 7 * 14
+    assert O.makespan_1f1b([3, 4, 5], [6, 7, 8], 1) == 3 + 4 + 5 + 6 + 7 + 8
+
+
+def test_removing_a_stage_can_lengthen_the_fixed_order():
+    """the 1F1B order is fixed, so a shorter pipeline is not always faster: every pipeline
+    has to be evaluated.  Values checked by hand against the explicit graph."""
+    full = O.makespan_1f1b([9, 2, 9], [8, 5, 4], 4)
+    short = O.makespan_1f1b([9, 9], [8, 4], 4)
+    assert (full, short) == (R.dag_makespan([9, 2, 9], [8, 5, 4], 4), R.dag_makespan([9, 9], [8, 4], 4))
+    assert short > full
+
+
+# ----------------------------------------------------------------------------- ranks
+@pytest.mark.parametrize("L,k", [(5, 0), (5, 1), (6, 3), (9, 4), (12, 2), (10, 9)])
+def test_partition_rank_is_a_bijection_in_colex_order(L, k):
+    ref = R.colex_partitions(L, k)
+    assert len(ref) == math.comb(L - 1, k) == O.binom(L - 1, k)
+    for rank, cuts in enumerate(ref):
+        assert O.partition_unrank(L, k, rank) == list(cuts)
+        assert O.partition_rank(cuts) == rank
+
+
+def test_partition_rank_ends_and_large_values():
+    for L, k in [(48, 7), (96, 15), (40, 7), (128, 9)]:
+        n = math.comb(L - 1, k)
+        assert O.binom(L - 1, k) == n
+        assert O.partition_unrank(L, k, 0) == list(range(1, k + 1))
+        assert O.partition_unrank(L, k, n - 1) == list(range(L - k, L))
+        with pytest.raises(O.OracleError):
+            O.partition_unrank(L, k, n)
+        rng = np.random.default_rng(L * 100 + k)
+        for _ in range(200):
+            r = int(rng.integers(0, n, dtype=np.uint64)) if n < 2 ** 63 else int(rng.integers(0, 2 ** 62))
+            cuts = O.partition_unrank(L, k, r)
+            assert all(1 <= a < b <= L - 1 for a, b in zip(cuts, cuts[1:])) and 1 <= cuts[0]
+            assert sum(math.comb(c - 1, i + 1) for i, c in enumerate(cuts)) == r
+    assert O.binom(95, 15) == 110375347398090219
+
+
+def capped_count(parts, total, cap):
+    """inclusion-exclusion count of vectors with entries in [0,cap] and a given sum"""
+    return sum((-1) ** j * math.comb(parts, j) * math.comb(total - j * (cap + 1) + parts - 1, parts - 1)
+               for j in range(parts + 1) if total - j * (cap + 1) >= 0)
+
+
+def test_reroute_counts():
+    assert O.reroute_count(3, 16, 0) == math.comb(18, 2) == 153
+    assert O.reroute_count(2, 32, 0) == 33
+    assert O.reroute_count(7, 32, 16) == capped_count(7, 32, 16) == 2380833
+    assert O.reroute_count(6, 64, 16) == capped_count(6, 64, 16)
+    assert O.reroute_count(3, 10, 3) == 0                  # 3 peers x cap 3 cannot take 10
+    assert O.reroute_count(1, 5, 0) == 1
+    for p, n, cap in itertools.product(range(1, 5), range(0, 9), (0, 1, 2, 5)):
+        want = math.comb(n + p - 1, p - 1) if cap == 0 else capped_count(p, n, cap)
+        assert O.reroute_count(p, n, cap) == want
+
+
+@pytest.mark.parametrize("parts,total,cap", [(3, 6, 0), (3, 6, 3), (4, 5, 2), (2, 9, 0), (1, 4, 0), (5, 3, 1)])
+def test_reroute_rank_is_lexicographic(parts, total, cap):
+    ref = R.reroute_vectors(parts, total, cap)
+    assert len(ref) == O.reroute_count(parts, total, cap)
+    for rank, v in enumerate(ref):
+        assert O.reroute_unrank(parts, total, cap, rank) == list(v)
+        assert O.reroute_rank(parts, total, cap, v) == rank
+    with pytest.raises(O.OracleError):
+        O.reroute_unrank(parts, total, cap, len(ref))
+
+
+# ----------------------------------------------------------------------------- small pieces
+def test_q16_scaling_rounds_half_up():
+    assert O.scale_q16(1000, 65536) == 1000
+    assert O.scale_q16(1, 32768) == 1          # 0.5 rounds up
+    assert O.scale_q16(1, 32767) == 0
+    assert O.scale_q16(3, 98304) == 5          # 4.5 -> 5
+    assert O.scale_q16(288000, 75367) == (288000 * 75367 + 32768) // 65536
+    rng = np.random.default_rng(3)
+    for _ in range(200):
+        x, q = int(rng.integers(0, 10 ** 7)), int(rng.integers(1, 1 << 20))
+        assert O.scale_q16(x, q) == math.floor(x * q / 65536 + 0.5) == R.scale(x, q)
+
+
+def test_weight_transfer_example_from_the_paper():
+    g = golden()
+    unit = [1] * 9                               # layers 1..9 -> indices 0..8, unit size
+    assert O.missing_interval(unit, 0, 2, 0, 3) == int(g["transfer_123_to_12"])
+    assert O.missing_interval(unit, 2, 4, 0, 3) == int(g["transfer_123_to_34"])
+    assert O.missing_interval(unit, 4, 6, 0, 3) == 2      # disjoint: everything is fetched
+    assert O.missing_interval([5, 7, 11, 13], 1, 4, 0, 2) == 11 + 13
+    p0 = O.layout_p0(9, 4)
+    assert [b - a for a, b in zip(p0, p0[1:])] == [int(x) for x in g["layout_9_over_4"].split(",")]
+    assert O.layout_p0(48, 8) == list(range(0, 49, 6))
+
+
+def test_batch_distribution_rule():
+    assert O.distribute_batch(64, [8, 8, 8, 7]) == [17, 17, 16, 14]   # floor shares 16,16,16,14 + 2 left over
+    assert O.distribute_batch(16, [4, 3]) == [10, 6]                  # 9,6 and one left over
+    assert O.distribute_batch(3, [8, 8, 1]) == [1, 1, 1]              # 1,1,0 +1 -> 2,1,0 -> refill the empty one
+    assert O.distribute_batch(64, [8, 8, 8, 8]) == [16] * 4
+    for nodes in ([5, 3, 2], [7, 7, 6, 1], [2, 9]):
+        for total in (len(nodes), 10, 33):
+            out = O.distribute_batch(total, nodes)
+            assert sum(out) == total and min(out) >= 1
+            assert out == R.distribute(total, nodes)
+
+
+# ----------------------------------------------------------------------------- scenario level
+def test_fault_free_even_split_gives_the_closed_form_with_comm():
+    """(M+S-1)(f+b) + (S-1) comm for uniform stages, both surviving-strategy families"""
+    S, D, M, per, f, b, comm = 8, 4, 16, 6, 1000, 2000, 200
+    sc = uniform_scenario(S, D, M, per, f, b, [], comm=comm, reconf_us=(0, 0, 0), horizon_steps=1)
+    s = O.Scenario(sc)
+    assert [fam["strategy"] for fam in s.families] == [0, 2]
+    want = (M + S - 1) * per * (f + b) + (S - 1) * comm
+    assert want == 23 * 18000 + 7 * 200
+    assert s.plan_cost(2, even_cuts(S, per)) == want
+    # redundant computation doubles every node's load
+    assert s.plan_cost(0, even_cuts(S, per)) == (M + S - 1) * 2 * per * (f + b) + (S - 1) * comm
+
+
+def test_single_failure_rerouting_closed_form():
+    g = golden()
+    S, D, M, f, b = 8, 5, 16, 1000, 2000
+    sc = uniform_scenario(S, D, M, 1, f, b, [2 * S + 3], reconf_us=(0, 0, 0), horizon_steps=1, xfer_us_per_mib=0)
+    s = O.Scenario(sc)
+    fam = s.family(2)
+    assert fam["n_reroute"] == math.comb(M + D - 2, D - 2)
+    rr = [[4, 4, 0, 4, 4] + [0] * 11]                    # even split over the four peers (replica 2 failed)
+    assert s.plan_cost(2, even_cuts(S, 1), rr) == int(g["step_reroute_8_16_5_1000_2000"])
+    # an uneven split waits for the most loaded peer
+    assert s.plan_cost(2, even_cuts(S, 1), [[16, 0, 0, 0, 0] + [0] * 11]) == (S + M - 1 + 16) * (f + b)
+    rc, best = s.search(1 << 2)
+    assert rc == 0 and best["cost"] == int(g["step_reroute_8_16_5_1000_2000"])
+    assert best["reroute"][0][:5] == [4, 4, 0, 4, 4]
+
+
+def test_multi_failure_rerouting_closed_form():
+    g = golden()
+    S, D, M, f, b = 4, 4, 12, 1000, 2000
+    failed = [0 * S + 0, 1 * S + 2, 3 * S + 2]            # F = (1,0,2,0)
+    sc = uniform_scenario(S, D, M, 1, f, b, failed, reconf_us=(0, 0, 0), horizon_steps=1)
+    s = O.Scenario(sc)
+    rr = [[0, 4, 4, 4], [12, 0, 12, 0]]
+    assert s.plan_cost(2, even_cuts(S, 1), rr) == int(g["step_reroute_multi_4_12_4"])
+    rc, best = s.search(1 << 2)
+    assert rc == 0 and best["cost"] == int(g["step_reroute_multi_4_12_4"])
+    assert best["affected_stage"] == [0, 2]
+    assert [best["reroute"][0][:4], best["reroute"][1][:4]] == rr
+
+
+def test_stage_without_peers_cannot_be_rerouted():
+    S, D = 4, 2
+    sc = uniform_scenario(S, D, 8, 2, 10, 20, [0 * S + 1, 1 * S + 1])
+    s = O.Scenario(sc)
+    assert s.family(2) is None                                # every replica lost stage 1
+    assert s.family(1) is not None and s.family(1)["stages"] == 3
+    rc, _ = s.search(1 << 2)
+    assert rc == O.ERR_UNRECOVERABLE
+    with pytest.raises(O.OracleError):
+        s.plan_cost(2, even_cuts(S, 2))
+
+
+def test_strategy_availability_rules():
+    S, D = 4, 3
+    # adjacent failures in one pipeline: the successor copy is lost as well
+    s = O.Scenario(uniform_scenario(S, D, 8, 2, 10, 20, [1, 2]))
+    assert s.family(0) is None and s.family(1)["stages"] == 2
+    # ring adjacency: stage 0's copy lives on stage S-1
+    s = O.Scenario(uniform_scenario(S, D, 8, 2, 10, 20, [0, 3]))
+    assert s.family(0) is None
+    # different survivor counts: no common re-partition
+    s = O.Scenario(uniform_scenario(S, D, 8, 2, 10, 20, [0, 2, 5]))
+    assert s.family(1) is None and s.family(0) is not None
+    # capped rerouting that cannot absorb the orphans
+    s = O.Scenario(uniform_scenario(S, D, 8, 2, 10, 20, [0], reroute_cap=3))
+    assert s.family(2) is None
+    s = O.Scenario(uniform_scenario(S, D, 8, 2, 10, 20, [0], reroute_cap=4))
+    assert s.family(2)["n_reroute"] == 1
+
+
+def test_argument_and_overflow_errors():
+    sc = uniform_scenario(4, 2, 8, 2, 10, 20, [0])
+    for key, val in [("L", 0), ("PP", 33), ("DP", 17), ("M", 257), ("failed_nodes", [0, 0]), ("failed_nodes", [8]),
+                     ("horizon_steps", 0), ("mem_cap_mib", 0), ("comm_us", -1)]:
+        bad = dict(sc)
+        bad[key] = val
+        with pytest.raises(O.OracleError) as e:
+            O.Scenario(bad)
+        assert e.value.code == O.ERR_ARG
+    bad = dict(sc)
+    bad["fwd_us"] = np.zeros(8, np.int32)
+    with pytest.raises(O.OracleError):
+        O.Scenario(bad)
+    big = uniform_scenario(16, 16, 256, 8, 2 ** 30, 2 ** 30, [0], horizon_steps=2 ** 31 - 1)
+    with pytest.raises(O.OracleError) as e:
+        O.Scenario(big)
+    assert e.value.code == O.ERR_OVERFLOW
+    wide = synth.scenario(128, 32, 2, 4, np.ones(128, np.int32), np.ones(128, np.int32), np.ones(128, np.int32),
+                          [0], 0, 1000)
+    with pytest.raises(O.OracleError) as e:        # C(127,31) does not fit the index
+        O.Scenario(wide)
+    assert e.value.code == O.ERR_OVERFLOW
+
+
+SMALL = [synth.small_random(1000 + i) for i in range(10)] + [
+    synth.small_random(2000, L=7, PP=3, DP=3, M=4, n_failed=2, hetero=True, cap=3),
+    synth.small_random(2001, L=6, PP=3, DP=4, M=3, n_failed=2, hetero=True, cap=0),
+    synth.small_random(2002, L=8, PP=4, DP=2, M=5, n_failed=1, hetero=False),
+    synth.small_random(2003, L=6, PP=2, DP=3, M=6, n_failed=3, hetero=True, cap=7),
+]
+
+
+@pytest.mark.parametrize("i", range(len(SMALL)))
+def test_every_plan_cost_matches_the_independent_model(i):
+    """brute force on tiny grids: itertools enumeration + explicit-graph longest path"""
+    sc = SMALL[i]
+    model = R.Model(sc)
+    s = O.Scenario(sc)
+    assert [f["strategy"] for f in s.families] == [k for k in range(3) if model.has[k]]
+    want = model.all_costs()
+    assert s.n_plans == len(want)
+    got = s.score(0, s.n_plans)
+    assert [int(x) for x in got] == want
+    # explicit-plan entry and index decoding agree with the enumeration as well
+    step = max(1, s.n_plans // 40)
+    for idx in range(0, s.n_plans, step):
+        p = s.decode(idx)
+        assert p["cost"] == want[idx]
+        rr = p["reroute"] if p["strategy"] == 2 else None
+        assert s.plan_cost(p["strategy"], p["cuts"], rr) == want[idx]
+
+
+@pytest.mark.parametrize("i", range(len(SMALL)))
+def test_search_equals_first_minimum_of_the_joint_sweep(i):
+    """the stage-by-stage rerouting search returns the joint argmin, tie-break included"""
+    s = O.Scenario(SMALL[i])
+    costs = s.score(0, s.n_plans)
+    rc, best = s.search(7)
+    rcj, bestj = s.search_joint()
+    if (costs == O.INF).all():
+        assert rc == rcj == O.ERR_NO_FEASIBLE
+        return
+    assert rc == rcj == 0
+    assert best["index"] == bestj["index"] == int(np.argmin(costs))    # argmin returns the first minimum
+    assert best["cost"] == bestj["cost"] == int(costs.min())
+    assert best == bestj
+    for fam in s.families:                                             # per strategy as well
+        lo, n = fam["offset"], fam["n_part"] * fam["n_reroute"]
+        rc, b = s.search(1 << fam["strategy"])
+        sub = costs[lo:lo + n]
+        if (sub == O.INF).all():
+            assert rc == O.ERR_NO_FEASIBLE
+        else:
+            assert (b["index"], b["cost"]) == (lo + int(np.argmin(sub)), int(sub.min()))
+
+
+def test_ties_go_to_the_lowest_index():
+    # uniform layers, two symmetric re-partitions have equal cost; all-equal reroute weights tie too
+    sc = uniform_scenario(3, 3, 4, 2, 10, 20, [1 * 3 + 1], reconf_us=(0, 0, 0), xfer_us_per_mib=0)
+    s = O.Scenario(sc)
+    costs = s.score(0, s.n_plans)
+    rc, best = s.search(7)
+    assert rc == 0 and best["index"] == int(np.argmin(costs))
+    assert (costs == costs.min()).sum() > 1
+
+
+def test_memory_infeasible_plans_are_never_selected():
+    sc = dict(SMALL[12])
+    s_free = O.Scenario(dict(sc, mem_cap_mib=10 ** 6))
+    _, best_free = s_free.search(1 << 2)
+    bounds = [0] + best_free["cuts"] + [sc["L"]]
+    biggest = max(int(np.sum(sc["mem_mib"][a:b])) for a, b in zip(bounds, bounds[1:]))
+    s_tight = O.Scenario(dict(sc, mem_cap_mib=biggest - 1))
+    costs = s_tight.score(0, s_tight.n_plans)
+    assert costs[best_free["index"]] == O.INF
+    rc, best = s_tight.search(1 << 2)
+    if rc == 0:
+        assert costs[best["index"]] != O.INF and best["index"] != best_free["index"]
+    s_none = O.Scenario(dict(sc, mem_cap_mib=int(max(sc["mem_mib"])) - 1 if max(sc["mem_mib"]) > 1 else 1))
+    rc, best = s_none.search(7)
+    assert rc == O.ERR_NO_FEASIBLE and best["cost"] == O.INF and best["index"] == 2 ** 64 - 1
+
+
+def test_plan_costs_are_monotone_in_every_layer_cost():
+    sc = SMALL[0]
+    base = O.Scenario(sc).score(0, O.Scenario(sc).n_plans)
+    for l in range(sc["L"]):
+        for key in ("fwd_us", "bwd_us"):
+            tab = np.array(sc[key]).copy()
+            tab[l] += 37
+            more = O.Scenario(dict(sc, **{key: tab})).score(0, len(base))
+            assert (more >= base).all()
+
+
+def test_reconfiguration_term_and_horizon_are_linear():
+    sc = dict(SMALL[1], reconf_us=(0, 0, 0), xfer_us_per_mib=0, horizon_steps=1)
+    t = O.Scenario(sc).score(0, O.Scenario(sc).n_plans)
+    sc2 = dict(sc, reconf_us=(11, 22, 33), horizon_steps=5)
+    s2 = O.Scenario(sc2)
+    c = s2.score(0, s2.n_plans)
+    for fam in s2.families:
+        sl = slice(fam["offset"], fam["offset"] + fam["n_part"] * fam["n_reroute"])
+        ok = t[sl] != O.INF
+        assert (c[sl][ok] == 5 * t[sl][ok] + (11, 22, 33)[fam["strategy"]]).all()
+        assert (c[sl][~ok] == O.INF).all()
+    # keeping the fault-free layout moves no weights in the rerouting family
+    s3 = O.Scenario(dict(sc, xfer_us_per_mib=7))
+    cuts0 = O.layout_p0(sc["L"], sc["PP"])[1:-1]
+    p = [0] * 64
+    if s3.family(2):
+        idx = s3.family(2)["offset"] + O.partition_rank(cuts0) * s3.family(2)["n_reroute"]
+        assert s3.score(idx, 1)[0] == t[idx]
+
+
+def test_config_plan_spaces():
+    s1 = O.Scenario(synth.config1())
+    assert [(f["n_part"], f["n_reroute"]) for f in s1.families] == [(4495, 1), (465, 1), (4495, 1)]
+    assert s1.n_plans == 9455
+    s2 = O.Scenario(synth.config2())
+    assert [(f["n_part"], f["n_reroute"]) for f in s2.families] == [(62891499, 1), (10737573, 1), (62891499, 153)]
+    assert s2.n_plans == 62891499 + 10737573 + 62891499 * 153 == 9696028419
+    s3 = O.Scenario(synth.config3())
+    assert s3.family(2)["n_reroute"] == 2380833 ** 2 and s3.family(2)["n_part"] == 9139
+    s4 = O.Scenario(synth.config4())
+    assert s4.family(0)["n_part"] == math.comb(95, 15) and s4.family(1)["n_part"] == math.comb(95, 14)
+    s5 = O.Scenario(synth.config5([3]))
+    assert s5.family(0)["n_part"] == 15380937 and s5.family(2)["n_reroute"] == 153
+
+
+def test_generators_are_reproducible_and_in_range():
+    a, b = synth.config2(), synth.config2()
+    for k in ("fwd_us", "bwd_us", "mem_mib"):
+        assert (a[k] == b[k]).all()
+    assert a["fwd_us"].min() >= 800 and a["fwd_us"].max() <= 1200
+    assert (np.abs(a["bwd_us"] - 2 * a["fwd_us"]) <= 0.1 * 2 * a["fwd_us"] + 1).all()
+    assert a["mem_mib"].min() >= 400 and a["mem_mib"].max() <= 600
+    c3 = synth.config3()
+    q = c3["speed_q16"]
+    assert q.min() >= round(0.85 * 65536) and q.max() <= round(1.15 * 65536)
+    f = c3["failed_nodes"]
+    assert f[0] % 4 != f[1] % 4 and f[0] // 4 != f[1] // 4
+    c4 = synth.config4()
+    assert 850 < np.median(c4["fwd_us"]) < 1150
+    cuts = synth.random_partitions(1, 2, 1000, 96, 15)
+    assert cuts.shape == (1000, 15) and (np.diff(cuts.astype(int), axis=1) > 0).all()
+    assert cuts.min() >= 1 and cuts.max() <= 95
+    assert len(synth.config5_failure_sets()) == 32 + 496
