@@ -1,0 +1,157 @@
+/*
+ * libchm - scoring of candidate post-failure execution plans on one AMD MI355X (gfx950).
+ *
+ * The library implements the hot path behind real-time fault-tolerance policy selection
+ * (Chameleon, arXiv 2508.21613): every candidate execution plan - a recovery policy, a
+ * contiguous split of the model layers over pipeline stages, and a distribution of the
+ * orphaned micro-batches (the execution-plan tuple of Definition 1, "State") - is scored
+ * with the step-time estimator of the Estimator subsection (the 1F1B dependency
+ * recurrence, eq. (transition); max over pipelines for asymmetric parallelism; the data
+ * rerouting terms of eq. (recycle_step_time) / (recycle_step_time_multi)), filtered by
+ * the memory estimator, charged a transition time, and the cheapest plan is returned
+ * (Algorithm 1, get_execution_plan).  All scoring runs in hand-written HIP kernels; the
+ * host side only validates, lays out tables and launches.  There is no CPU fallback:
+ * without a usable GPU every compute call returns CHM_ERR_HIP.
+ *
+ * Conventions
+ *   - Every function returns 0 (CHM_OK) or a negative CHM_ERR_* code; nothing throws or
+ *     aborts.  chm_strerror() gives a static string for a code.
+ *   - Pointers named d_* are DEVICE pointers owned by the caller (allocated with hipMalloc
+ *     or, from Python, torch.empty(..., device="cuda").data_ptr()).  All other pointers
+ *     are HOST pointers.  Arrays inside chm_scenario_desc are caller-owned and copied by
+ *     chm_load_scenario; they may be freed as soon as it returns.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
+ *   - A handle must not be used by two host threads at once; different handles are
+ *     independent.  A handle belongs to the device that was current when it was loaded.
+ *   - Times are int32 microseconds, memory is int32 MiB, speed factors are Q16 time
+ *     multipliers (65536 = nominal, 75366 = 15 % slower).  Costs are int64.
+ *
+ * Plan index space (what a "plan index" means)
+ *   Strategies, in this fixed order, each present only if it can recover the failure set:
+ *     0  redundant computation   S stages; every node also carries its successor's layers
+ *     1  re-partition            the failed pipelines are re-split over their surviving
+ *                                nodes (S - failures stages); healthy pipelines keep the
+ *                                fault-free layout; micro-batches are redistributed in
+ *                                proportion to node counts (Planner, "Batch Distribution")
+ *     2  data rerouting          S stages; the failed nodes' micro-batches go to same-stage
+ *                                peers of other pipelines
+ *   index = family.offset + partition_rank * family.n_reroute + reroute_rank
+ *   partition_rank: a split into k+1 non-empty contiguous stages is its set of cut
+ *     positions 1 <= c_1 < ... < c_k <= L-1 (stage j = layers [c_j, c_{j+1})); its rank is
+ *     sum_i C(c_i - 1, i), the combinatorial number system, in [0, C(L-1, k)).
+ *   reroute_rank: for each stage that lost nodes (ascending stage index, first one most
+ *     significant) the lexicographic rank, lowest replica most significant, of the vector
+ *     of extra micro-batches per surviving peer (entries >= 0, sum = lost nodes * M, each
+ *     <= reroute_cap if that is positive).
+ *   cost = horizon_steps * t_step + reconf_us[strategy] + xfer_us_per_mib * (MiB of weights
+ *     the new layout must fetch); INT64_MAX for a plan that exceeds mem_cap_mib on a stage.
+ */
+#ifndef CHM_H
+#define CHM_H
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  CHM_OK = 0,
+  CHM_ERR_ARG = -1,            /* null pointer, size out of the limits below, bad node id  */
+  CHM_ERR_RANGE = -2,          /* plan range or rank outside the plan space                */
+  CHM_ERR_OVERFLOW = -3,       /* plan count or cost bound does not fit 62 bits            */
+  CHM_ERR_UNRECOVERABLE = -4,  /* no requested strategy can recover this failure set       */
+  CHM_ERR_NO_FEASIBLE = -5,    /* every plan searched exceeds the memory cap               */
+  CHM_ERR_HIP = -6             /* a HIP call failed (no device, launch or copy error)      */
+};
+
+enum { CHM_MAX_L = 128, CHM_MAX_PP = 32, CHM_MAX_DP = 16, CHM_MAX_M = 256, CHM_MAX_FAILED = 4 };
+
+#define CHM_INFEASIBLE INT64_MAX
+
+typedef struct chm_scenario chm_scenario;   /* opaque; owned by the library until chm_free_scenario */
+
+/* Inputs of one failure event: the profiled tables the estimator consumes (System Design,
+ * workflow step 1), the DP x PP grid, the micro-batch count and the failed-node set. */
+typedef struct {
+  int32_t L, PP, DP, M;               /* layers (PP<=L<=128), stages (<=32), pipelines (<=16), micro-batches per pipeline (<=256) */
+  const int32_t *fwd_us, *bwd_us;     /* [L] per-layer forward / backward time, each >= 1            */
+  const int32_t *mem_mib;             /* [L] per-layer memory, each >= 0                             */
+  const uint32_t *speed_q16;          /* [DP*PP] node id = d*PP+s, in [1, 2^20]; NULL = all 65536    */
+  int32_t n_failed;                   /* 0..4                                                        */
+  const int32_t *failed_nodes;        /* [n_failed] distinct node ids                                */
+  int32_t comm_us;                    /* added once per stage boundary of a pipeline, >= 0           */
+  int32_t mem_cap_mib;                /* per-node memory limit, >= 1                                 */
+  int32_t reroute_cap;                /* max extra micro-batches per peer; <= 0 = no cap             */
+  int32_t horizon_steps;              /* training steps until the next failure is expected, >= 1     */
+  int32_t reconf_us[3];               /* per-strategy restart constant, >= 0                         */
+  int32_t xfer_us_per_mib;            /* weight-transfer cost rate, >= 0                             */
+} chm_scenario_desc;
+
+typedef struct { uint64_t offset, n_part, n_reroute; int32_t stages, strategy; } chm_family;
+typedef struct { int32_t n_families; chm_family fam[3]; uint64_t n_plans; } chm_space;
+
+typedef struct {
+  uint64_t index;              /* global plan index; UINT64_MAX when nothing feasible was found      */
+  int64_t cost;                /* CHM_INFEASIBLE when nothing feasible was found                      */
+  int32_t strategy, stages;
+  uint8_t cuts[32];            /* cuts[0..stages-2] = c_1 < ... < c_k                                 */
+  int32_t n_affected;          /* rerouting only: stages that lost nodes, ascending                   */
+  int32_t affected_stage[4];
+  uint16_t reroute[4][16];     /* reroute[a][d] = extra micro-batches on pipeline d for affected stage a */
+} chm_best;
+
+/* Per-call kernel timings (milliseconds between HIP events on the caller's stream),
+ * filled by the last chm_search_best on a handle when timing was switched on. */
+typedef struct {
+  float family_ms[3];          /* main scoring kernel(s) of strategy 0/1/2, 0 when not run           */
+  float total_ms;              /* first launch to last launch of the call                            */
+  uint64_t partitions[3];      /* partitions evaluated per strategy                                  */
+  uint64_t evaluations[3];     /* (partition, reroute vector) evaluations per strategy               */
+} chm_timing;
+
+/* Validates the description, builds the plan space and uploads the scenario tables
+ * (Definition 1; Algorithm 1 inputs).  Synchronous.  Errors: CHM_ERR_ARG, CHM_ERR_OVERFLOW,
+ * CHM_ERR_HIP.  On error *out is NULL. */
+int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **out);
+
+/* The families present for this failure set and the number of plan indices. Host only. */
+int chm_plan_space(const chm_scenario *s, chm_space *out);
+
+/* Scores plan indices [first, first+count) into d_costs[0..count) (device, int64).
+ * Asynchronous on hip_stream.  Errors: CHM_ERR_ARG, CHM_ERR_RANGE, CHM_ERR_HIP. */
+int chm_score_plans(chm_scenario *s, uint64_t first, uint64_t count, int64_t *d_costs, void *hip_stream);
+
+/* Scores n explicit partitions of one strategy, given by their partition ranks in device
+ * memory, with reroute rank 0 (the strategy must have n_reroute == 1, else CHM_ERR_ARG).
+ * A rank outside the family gives cost CHM_INFEASIBLE for that entry.  Asynchronous. */
+int chm_score_ranks(chm_scenario *s, int32_t strategy, const uint64_t *d_part_ranks, uint64_t n,
+                    int64_t *d_costs, void *hip_stream);
+
+/* Exhaustive argmin over the strategies in strategy_mask (bit k = strategy k): every
+ * partition of every selected family is scored on the device; for data rerouting every
+ * reroute vector of every stage that lost nodes is scored (the penalty is a sum of
+ * independent per-stage terms, so stages are swept one after the other).  Ties go to the
+ * lowest plan index.  Synchronises hip_stream before returning.  Errors:
+ * CHM_ERR_UNRECOVERABLE (mask selects no existing family), CHM_ERR_NO_FEASIBLE (out is
+ * filled with index UINT64_MAX, cost CHM_INFEASIBLE), CHM_ERR_ARG, CHM_ERR_HIP. */
+int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream);
+
+/* The same over partition ranks [part_first, part_first+part_count) of one strategy. */
+int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part_first, uint64_t part_count,
+                     chm_best *out, void *hip_stream);
+
+/* Host-only structural decoding of a plan index (cost is not evaluated and is set to 0). */
+int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out);
+
+/* Switches event timing of chm_search_best / chm_search_range on or off for a handle,
+ * and reads the timings of the last such call. */
+int chm_set_timing(chm_scenario *s, int32_t on);
+int chm_get_timing(const chm_scenario *s, chm_timing *out);
+
+void chm_free_scenario(chm_scenario *s);
+const char *chm_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

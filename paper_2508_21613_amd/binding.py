@@ -1,0 +1,210 @@
+"""Thin ctypes binding of libchm.so (the C-ABI of include/chm.h): argument marshalling only.
+
+Every step of the path runs in the library's HIP kernels.  Device buffers are torch tensors
+(torch is used for device memory and streams, nothing else).  If the library is missing or no
+GPU is usable the calls fail loudly; there is no fallback.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libchm.so")
+
+OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+INFEASIBLE = (1 << 63) - 1
+
+SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
+           "chm_search_range", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_free_scenario",
+           "chm_strerror"]
+
+
+class Desc(C.Structure):
+    _fields_ = [("L", C.c_int32), ("PP", C.c_int32), ("DP", C.c_int32), ("M", C.c_int32),
+                ("fwd_us", C.POINTER(C.c_int32)), ("bwd_us", C.POINTER(C.c_int32)),
+                ("mem_mib", C.POINTER(C.c_int32)), ("speed_q16", C.POINTER(C.c_uint32)),
+                ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
+                ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32), ("reroute_cap", C.c_int32),
+                ("horizon_steps", C.c_int32), ("reconf_us", C.c_int32 * 3),
+                ("xfer_us_per_mib", C.c_int32)]
+
+
+class Family(C.Structure):
+    _fields_ = [("offset", C.c_uint64), ("n_part", C.c_uint64), ("n_reroute", C.c_uint64),
+                ("stages", C.c_int32), ("strategy", C.c_int32)]
+
+
+class Space(C.Structure):
+    _fields_ = [("n_families", C.c_int32), ("fam", Family * 3), ("n_plans", C.c_uint64)]
+
+
+class Best(C.Structure):
+    _fields_ = [("index", C.c_uint64), ("cost", C.c_int64), ("strategy", C.c_int32),
+                ("stages", C.c_int32), ("cuts", C.c_uint8 * 32), ("n_affected", C.c_int32),
+                ("affected_stage", C.c_int32 * 4), ("reroute", (C.c_uint16 * 16) * 4)]
+
+
+class Timing(C.Structure):
+    _fields_ = [("family_ms", C.c_float * 3), ("total_ms", C.c_float),
+                ("partitions", C.c_uint64 * 3), ("evaluations", C.c_uint64 * 3)]
+
+
+class ChmError(RuntimeError):
+    def __init__(self, code, msg=""):
+        super().__init__("libchm error %d: %s" % (code, msg))
+        self.code = code
+
+
+_lib = None
+
+
+def lib():
+    """Loads libchm.so; raises if it has not been built (python -m paper_2508_21613_amd.build)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libchm.so is not built: run `python -m paper_2508_21613_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        vp = C.c_void_p
+        L.chm_load_scenario.argtypes = [C.POINTER(Desc), C.POINTER(vp)]
+        L.chm_plan_space.argtypes = [vp, C.POINTER(Space)]
+        L.chm_score_plans.argtypes = [vp, C.c_uint64, C.c_uint64, vp, vp]
+        L.chm_score_ranks.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, vp]
+        L.chm_search_best.argtypes = [vp, C.c_uint32, C.POINTER(Best), vp]
+        L.chm_search_range.argtypes = [vp, C.c_int32, C.c_uint64, C.c_uint64, C.POINTER(Best), vp]
+        L.chm_decode_plan.argtypes = [vp, C.c_uint64, C.POINTER(Best)]
+        L.chm_set_timing.argtypes = [vp, C.c_int32]
+        L.chm_get_timing.argtypes = [vp, C.POINTER(Timing)]
+        L.chm_free_scenario.argtypes = [vp]
+        L.chm_free_scenario.restype = None
+        L.chm_strerror.argtypes = [C.c_int]
+        L.chm_strerror.restype = C.c_char_p
+        for n in SYMBOLS:
+            if n not in ("chm_free_scenario", "chm_strerror"):
+                getattr(L, n).restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def strerror(code):
+    return lib().chm_strerror(code).decode()
+
+
+def _check(rc, allowed=()):
+    if rc != OK and rc not in allowed:
+        raise ChmError(rc, strerror(rc))
+    return rc
+
+
+def _best_dict(b):
+    k = max(b.stages - 1, 0)
+    return {"index": int(b.index), "cost": int(b.cost), "strategy": int(b.strategy), "stages": int(b.stages),
+            "cuts": [int(b.cuts[i]) for i in range(k)], "n_affected": int(b.n_affected),
+            "affected_stage": [int(b.affected_stage[a]) for a in range(b.n_affected)],
+            "reroute": [[int(b.reroute[a][d]) for d in range(16)] for a in range(b.n_affected)]}
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+    return C.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
+
+
+class Scenario:
+    """chm_load_scenario ... chm_free_scenario.  `sc` is a dict with the fields of chm_scenario_desc."""
+
+    def __init__(self, sc):
+        keep = []
+        d = Desc()
+        d.L, d.PP, d.DP, d.M = sc["L"], sc["PP"], sc["DP"], sc["M"]
+        for name in ("fwd_us", "bwd_us", "mem_mib"):
+            a = np.ascontiguousarray(sc[name], dtype=np.int32)
+            keep.append(a)
+            setattr(d, name, a.ctypes.data_as(C.POINTER(C.c_int32)))
+        if sc.get("speed_q16") is not None:
+            a = np.ascontiguousarray(sc["speed_q16"], dtype=np.uint32)
+            keep.append(a)
+            d.speed_q16 = a.ctypes.data_as(C.POINTER(C.c_uint32))
+        f = np.ascontiguousarray(sc.get("failed_nodes", []), dtype=np.int32)
+        keep.append(f)
+        d.n_failed = len(f)
+        if len(f):
+            d.failed_nodes = f.ctypes.data_as(C.POINTER(C.c_int32))
+        d.comm_us, d.mem_cap_mib = sc["comm_us"], sc["mem_cap_mib"]
+        d.reroute_cap, d.horizon_steps = sc.get("reroute_cap", 0), sc["horizon_steps"]
+        for i in range(3):
+            d.reconf_us[i] = sc["reconf_us"][i]
+        d.xfer_us_per_mib = sc["xfer_us_per_mib"]
+        self._h = C.c_void_p()
+        _check(lib().chm_load_scenario(C.byref(d), C.byref(self._h)))
+        sp = Space()
+        _check(lib().chm_plan_space(self._h, C.byref(sp)))
+        self.n_plans = int(sp.n_plans)
+        self.families = [dict(offset=int(sp.fam[i].offset), n_part=int(sp.fam[i].n_part),
+                              n_reroute=int(sp.fam[i].n_reroute), stages=int(sp.fam[i].stages),
+                              strategy=int(sp.fam[i].strategy)) for i in range(sp.n_families)]
+
+    def close(self):
+        if getattr(self, "_h", None):
+            lib().chm_free_scenario(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def family(self, strategy):
+        for f in self.families:
+            if f["strategy"] == strategy:
+                return f
+        return None
+
+    def score_plans(self, first, count, out=None, stream=None):
+        """chm_score_plans into a torch int64 CUDA tensor (allocated here unless given)"""
+        import torch
+        if out is None:
+            out = torch.empty(count, dtype=torch.int64, device="cuda")
+        assert out.is_cuda and out.dtype == torch.int64 and out.numel() >= count and out.is_contiguous()
+        _check(lib().chm_score_plans(self._h, first, count, C.c_void_p(out.data_ptr()), _stream_ptr(stream)))
+        return out
+
+    def score_ranks(self, strategy, d_ranks, out=None, stream=None):
+        """chm_score_ranks; d_ranks is a contiguous CUDA tensor holding uint64 ranks (dtype int64 or uint64)"""
+        import torch
+        n = d_ranks.numel()
+        assert d_ranks.is_cuda and d_ranks.element_size() == 8 and d_ranks.is_contiguous()
+        if out is None:
+            out = torch.empty(n, dtype=torch.int64, device="cuda")
+        _check(lib().chm_score_ranks(self._h, strategy, C.c_void_p(d_ranks.data_ptr()), n,
+                                     C.c_void_p(out.data_ptr()), _stream_ptr(stream)))
+        return out
+
+    def search_best(self, mask=7, stream=None):
+        b = Best()
+        rc = _check(lib().chm_search_best(self._h, mask, C.byref(b), _stream_ptr(stream)),
+                    allowed=(ERR_NO_FEASIBLE, ERR_UNRECOVERABLE))
+        return rc, _best_dict(b)
+
+    def search_range(self, strategy, first, count, stream=None):
+        b = Best()
+        rc = _check(lib().chm_search_range(self._h, strategy, first, count, C.byref(b), _stream_ptr(stream)),
+                    allowed=(ERR_NO_FEASIBLE, ERR_UNRECOVERABLE))
+        return rc, _best_dict(b)
+
+    def decode_plan(self, index):
+        b = Best()
+        _check(lib().chm_decode_plan(self._h, index, C.byref(b)))
+        return _best_dict(b)
+
+    def set_timing(self, on=True):
+        _check(lib().chm_set_timing(self._h, 1 if on else 0))
+
+    def get_timing(self):
+        t = Timing()
+        _check(lib().chm_get_timing(self._h, C.byref(t)))
+        return {"family_ms": [float(x) for x in t.family_ms], "total_ms": float(t.total_ms),
+                "partitions": [int(x) for x in t.partitions], "evaluations": [int(x) for x in t.evaluations]}

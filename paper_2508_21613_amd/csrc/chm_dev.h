@@ -1,0 +1,82 @@
+// Device-side layout of one scenario and the launch interface between the host part
+// (chm_host.cpp) and the kernels (chm_kernels.hip).  Internal to libchm.
+#ifndef CHM_DEV_H
+#define CHM_DEV_H
+#include <stdint.h>
+
+#define CHM_INF_COST INT64_MAX
+#define CHM_KEY_NONE UINT64_MAX
+
+enum { DEV_MAX_L = 128, DEV_MAX_S = 32, DEV_MAX_D = 16, DEV_MAX_AFF = 4, DEV_MAX_CLS = 16 };
+
+// One distinct pipeline that a plan of a family has to evaluate.  Pipelines of a family
+// that are indistinguishable (same nodes' speed factors, same chain, same micro-batch
+// count) are merged on the host, so a plan costs one recurrence per class, not per replica.
+struct DevClass {
+  int32_t n;                    // pipeline length (nodes in the chain)
+  int32_t M;                    // micro-batches this pipeline runs
+  int32_t pad[2];
+  uint8_t src[DEV_MAX_S];       // partition stage whose layers chain position j runs
+  uint8_t host[DEV_MAX_S];      // fault-free stage index of the node at chain position j
+  uint32_t q[DEV_MAX_S];        // Q16 time multiplier of that node
+};
+
+struct DevFamily {
+  int32_t strategy;             // 0 redundant, 1 re-partition, 2 rerouting
+  int32_t stages;               // stages of the partition (k+1)
+  int32_t n_cls;
+  int32_t doubled;              // 1: every node also runs its ring successor's stage (strategy 0)
+  uint64_t n_part, n_reroute;
+  int64_t fixed_step;           // step time of the pipelines the plan does not touch (strategy 1), else 0
+  DevClass cls[DEV_MAX_CLS];
+};
+
+struct DevScenario {
+  int32_t L, S, D, M;
+  int64_t comm, cap, K, xfer;
+  int64_t reconf[3];
+  int32_t p0[DEV_MAX_S + 1];    // fault-free layout: stage j = layers [p0[j], p0[j+1])
+  int32_t rcap;                 // reroute cap (<=0: none)
+  int64_t pf[DEV_MAX_L + 1], pb[DEV_MAX_L + 1], pw[DEV_MAX_L + 1];   // prefix sums
+  // rerouting: stages that lost nodes
+  int32_t n_aff;
+  int32_t aff_stage[DEV_MAX_AFF], aff_peers[DEV_MAX_AFF], aff_total[DEV_MAX_AFF];
+  uint32_t aff_q[DEV_MAX_AFF][DEV_MAX_D];      // speed factor of peer i of affected stage a
+  uint64_t aff_R[DEV_MAX_AFF];                 // number of valid reroute vectors
+  uint32_t comp_off[DEV_MAX_AFF];              // offset of the count table of stage a in comp[]
+  uint32_t comp_stride[DEV_MAX_AFF];           // = aff_total[a] + 1
+  DevFamily fam[3];                            // indexed by strategy; n_part == 0 when absent
+  // strategy 1: the healthy pipelines keep the fault-free layout; their step time does not
+  // depend on the plan and is computed once at load into fam[1].fixed_step
+  int32_t n_fixed;
+  DevClass fixed[DEV_MAX_D];
+  // C(x, i) for 0 <= i < DEV_MAX_S, 0 <= x < DEV_MAX_L, saturating
+  uint64_t binom[DEV_MAX_S][DEV_MAX_L];
+};
+// comp[] (separate allocation): for affected stage a, entry [left * stride + rem] is the number
+// of valid vectors of `left` entries summing to `rem`.
+
+struct SearchLaunch {
+  const DevScenario *scn;
+  const uint64_t *comp;
+  int32_t strategy;
+  uint64_t part_first;          // first partition rank of this chunk
+  uint32_t part_count;          // partitions in this chunk (< 2^idx_bits)
+  int32_t idx_bits;             // low bits of the packed key hold the chunk-local partition index
+  uint64_t *result;             // device word, atomicMin target: (cost << idx_bits) | local index
+};
+
+// launch wrappers (defined in chm_kernels.hip); each returns a hipError_t cast to int
+int chmk_fixed_pipelines(DevScenario *d_scn, void *stream);
+int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream);
+int chmk_score(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy, uint64_t first_local,
+               uint64_t count, int64_t *d_costs, int32_t smax, void *stream);
+int chmk_score_ranks(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy,
+                     const uint64_t *d_ranks, uint64_t n, int64_t *d_costs, int32_t smax, void *stream);
+int chmk_search(const SearchLaunch &a, int32_t smax, void *stream);
+// re-evaluates one partition of the rerouting family and writes, per affected stage, the
+// rank of its best reroute vector to d_out[0..n_aff)
+int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank,
+                        uint64_t *d_out, int32_t smax, void *stream);
+
+#endif

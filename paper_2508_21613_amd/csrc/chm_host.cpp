@@ -1,0 +1,573 @@
+// Host side of libchm: the C-ABI of include/chm.h.  Validates a scenario, derives which
+// recovery strategies exist for the failure set, lays out the plan index space and the
+// device tables, and launches the scoring / search kernels.  No plan is ever scored on
+// the host: without a working HIP device every compute entry point fails with CHM_ERR_HIP.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/chm.h"
+#include "chm_dev.h"
+#include "chm_fast.h"
+
+namespace {
+
+typedef unsigned __int128 u128;
+
+#define HIP_TRY(expr)                      \
+  do {                                     \
+    if ((expr) != hipSuccess) return CHM_ERR_HIP; \
+  } while (0)
+
+uint64_t add_sat(uint64_t a, uint64_t b) { return a > UINT64_MAX - b ? UINT64_MAX : a + b; }
+uint64_t mul_sat(uint64_t a, uint64_t b) {
+  u128 p = (u128)a * b;
+  return p > (u128)UINT64_MAX ? UINT64_MAX : (uint64_t)p;
+}
+int bit_length(u128 v) { int n = 0; while (v) { ++n; v >>= 1; } return n; }
+
+struct Slot { int strategy; uint64_t part_first; int idx_bits; };
+
+}  // namespace
+
+struct chm_scenario {
+  DevScenario h;                         // host copy of what the device holds
+  std::vector<uint64_t> comp;            // reroute count tables, all affected stages back to back
+  std::vector<std::vector<int>> peers;   // per affected stage: surviving replicas, ascending
+  chm_space space;
+  int device = 0;
+  int smax = 4;                          // template bucket of the generic kernels
+  int idx_bits = 0;                      // low bits of the packed argmin key
+  bool int32_ok = false;                 // every intermediate of the recurrence fits in int32
+  DevScenario *d_scn = nullptr;
+  uint64_t *d_comp = nullptr;
+  uint64_t *d_slots = nullptr;           // argmin words, one per launched chunk
+  uint64_t *d_winner = nullptr;          // best reroute rank per affected stage
+  uint64_t *h_pinned = nullptr;          // pinned staging for the two small device-to-host copies
+  uint32_t n_slots = 0;
+  bool timing = false;
+  hipEvent_t ev[8] = {};
+  chm_timing last = {};
+  FastState fast;                        // shape-specialised search path (chm_fast.hip)
+};
+
+namespace {
+
+enum { MAX_SLOTS = 1 << 16 };
+
+const chm_family *find_family(const chm_scenario *s, int strategy) {
+  for (int i = 0; i < s->space.n_families; ++i)
+    if (s->space.fam[i].strategy == strategy) return &s->space.fam[i];
+  return nullptr;
+}
+
+bool same_class(const DevClass &a, const DevClass &b) {
+  return a.n == b.n && a.M == b.M && !memcmp(a.src, b.src, sizeof(a.src)) && !memcmp(a.host, b.host, sizeof(a.host)) &&
+         !memcmp(a.q, b.q, sizeof(a.q));
+}
+
+void add_class(DevClass *list, int32_t *n, const DevClass &c) {
+  for (int i = 0; i < *n; ++i)
+    if (same_class(list[i], c)) return;
+  list[(*n)++] = c;
+}
+
+// micro-batches over pipelines in proportion to node counts, leftovers one by one from the
+// first pipeline, empty pipelines refilled from the largest (Planner, "Batch Distribution")
+void share_micro_batches(int D, int total, const int *nodes, int *out) {
+  long long N = 0, given = 0;
+  for (int d = 0; d < D; ++d) N += nodes[d];
+  for (int d = 0; d < D; ++d) { out[d] = nodes[d] ? (int)((long long)total * nodes[d] / N) : 0; given += out[d]; }
+  for (int d = 0, left = (int)(total - given); left > 0; d = (d + 1) % D)
+    if (nodes[d]) { ++out[d]; --left; }
+  for (;;) {
+    int hole = -1, top = -1;
+    for (int d = 0; d < D; ++d) {
+      if (!nodes[d]) continue;
+      if (out[d] == 0 && hole < 0) hole = d;
+      if (top < 0 || out[d] > out[top]) top = d;
+    }
+    if (hole < 0 || top < 0 || out[top] < 2) return;
+    --out[top]; ++out[hole];
+  }
+}
+
+// number of vectors of `parts` entries in [0, cap] (cap<=0: unbounded) with a given sum,
+// for every (parts' <= parts, sum' <= total): tab[parts' * (total+1) + sum']
+void count_table(int parts, int total, int cap, std::vector<uint64_t> *tab) {
+  const int stride = total + 1;
+  tab->assign((size_t)(parts + 1) * stride, 0);
+  (*tab)[0] = 1;
+  for (int p = 1; p <= parts; ++p)
+    for (int t = 0; t <= total; ++t) {
+      uint64_t acc = 0;
+      const int vmax = cap > 0 ? std::min(cap, t) : t;
+      for (int v = 0; v <= vmax; ++v) acc = add_sat(acc, (*tab)[(size_t)(p - 1) * stride + (t - v)]);
+      (*tab)[(size_t)p * stride + t] = acc;
+    }
+}
+
+int validate(const chm_scenario_desc *d) {
+  if (!d) return CHM_ERR_ARG;
+  if (d->L < 1 || d->L > CHM_MAX_L || d->PP < 1 || d->PP > CHM_MAX_PP || d->PP > d->L || d->DP < 1 ||
+      d->DP > CHM_MAX_DP || d->M < 1 || d->M > CHM_MAX_M || d->n_failed < 0 || d->n_failed > CHM_MAX_FAILED)
+    return CHM_ERR_ARG;
+  if (!d->fwd_us || !d->bwd_us || !d->mem_mib || (d->n_failed > 0 && !d->failed_nodes)) return CHM_ERR_ARG;
+  if (d->comm_us < 0 || d->mem_cap_mib < 1 || d->horizon_steps < 1 || d->xfer_us_per_mib < 0) return CHM_ERR_ARG;
+  for (int i = 0; i < 3; ++i) if (d->reconf_us[i] < 0) return CHM_ERR_ARG;
+  for (int l = 0; l < d->L; ++l)
+    if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0) return CHM_ERR_ARG;
+  const int nodes = d->DP * d->PP;
+  if (d->speed_q16)
+    for (int n = 0; n < nodes; ++n)
+      if (d->speed_q16[n] < 1 || d->speed_q16[n] > (1u << 20)) return CHM_ERR_ARG;
+  for (int i = 0; i < d->n_failed; ++i) {
+    if (d->failed_nodes[i] < 0 || d->failed_nodes[i] >= nodes) return CHM_ERR_ARG;
+    for (int j = 0; j < i; ++j) if (d->failed_nodes[j] == d->failed_nodes[i]) return CHM_ERR_ARG;
+  }
+  return CHM_OK;
+}
+
+// Fills s->h, s->comp, s->peers and s->space from the description.
+int build_model(const chm_scenario_desc *d, chm_scenario *s) {
+  DevScenario &h = s->h;
+  memset(&h, 0, sizeof(h));
+  const int L = d->L, S = d->PP, D = d->DP, M = d->M;
+  h.L = L; h.S = S; h.D = D; h.M = M;
+  h.comm = d->comm_us; h.cap = d->mem_cap_mib; h.K = d->horizon_steps; h.xfer = d->xfer_us_per_mib;
+  for (int i = 0; i < 3; ++i) h.reconf[i] = d->reconf_us[i];
+  h.rcap = d->reroute_cap;
+  for (int l = 0; l < L; ++l) {
+    h.pf[l + 1] = h.pf[l] + d->fwd_us[l];
+    h.pb[l + 1] = h.pb[l] + d->bwd_us[l];
+    h.pw[l + 1] = h.pw[l] + d->mem_mib[l];
+  }
+  for (int sgi = 0, pos = 0; sgi < S; ++sgi) {      // fault-free layout: extra layers on the last stages
+    pos += L / S + (sgi >= S - L % S ? 1 : 0);
+    h.p0[sgi + 1] = pos;
+  }
+  for (int i = 0; i < DEV_MAX_S; ++i)
+    for (int x = 0; x < DEV_MAX_L; ++x) {
+      uint64_t v;
+      if (i == 0) v = 1;
+      else if (x < i) v = 0;
+      else if (x == i) v = 1;
+      else v = add_sat(h.binom[i][x - 1], h.binom[i - 1][x - 1]);
+      h.binom[i][x] = v;
+    }
+
+  bool dead[DEV_MAX_D][DEV_MAX_S] = {};
+  uint32_t q[DEV_MAX_D][DEV_MAX_S];
+  uint32_t qmax = 65536;
+  for (int dd = 0; dd < D; ++dd)
+    for (int j = 0; j < S; ++j) {
+      q[dd][j] = d->speed_q16 ? d->speed_q16[dd * S + j] : 65536u;
+      qmax = std::max(qmax, q[dd][j]);
+    }
+  int lost_in_pipe[DEV_MAX_D] = {}, lost_in_stage[DEV_MAX_S] = {};
+  for (int i = 0; i < d->n_failed; ++i) {
+    const int n = d->failed_nodes[i];
+    dead[n / S][n % S] = true;
+    ++lost_in_pipe[n / S];
+    ++lost_in_stage[n % S];
+  }
+
+  // ---- strategy 0: redundant computation; needs the ring predecessor of every failed node
+  bool has0 = S >= 2;
+  for (int dd = 0; dd < D; ++dd)
+    for (int j = 0; j < S; ++j)
+      if (dead[dd][j] && dead[dd][(j + S - 1) % S]) has0 = false;
+  if (has0) {
+    DevFamily &f = h.fam[0];
+    f.strategy = 0; f.stages = S; f.doubled = 1;
+    for (int dd = 0; dd < D; ++dd) {
+      DevClass c; memset(&c, 0, sizeof(c));
+      c.M = M;
+      for (int j = 0; j < S; ++j)
+        if (!dead[dd][j]) { c.src[c.n] = (uint8_t)j; c.host[c.n] = (uint8_t)j; c.q[c.n] = q[dd][j]; ++c.n; }
+      add_class(f.cls, &f.n_cls, c);
+    }
+  }
+  // ---- strategy 1: failed pipelines re-split over their survivors (all must keep the same count)
+  int SB = 0;
+  bool has1 = d->n_failed > 0;
+  for (int dd = 0; dd < D; ++dd) {
+    if (!lost_in_pipe[dd]) continue;
+    const int left = S - lost_in_pipe[dd];
+    if (left < 1 || (SB && left != SB)) has1 = false;
+    SB = left;
+  }
+  if (has1) {
+    DevFamily &f = h.fam[1];
+    f.strategy = 1; f.stages = SB; f.doubled = 0;
+    int nodes[DEV_MAX_D], mb[DEV_MAX_D];
+    for (int dd = 0; dd < D; ++dd) nodes[dd] = S - lost_in_pipe[dd];
+    share_micro_batches(D, D * M, nodes, mb);
+    for (int dd = 0; dd < D; ++dd) {
+      DevClass c; memset(&c, 0, sizeof(c));
+      c.M = mb[dd];
+      if (lost_in_pipe[dd]) {
+        for (int j = 0; j < S; ++j)
+          if (!dead[dd][j]) { c.src[c.n] = (uint8_t)c.n; c.host[c.n] = (uint8_t)j; c.q[c.n] = q[dd][j]; ++c.n; }
+        add_class(f.cls, &f.n_cls, c);
+      } else {
+        for (int j = 0; j < S; ++j) { c.src[j] = (uint8_t)j; c.host[j] = (uint8_t)j; c.q[j] = q[dd][j]; }
+        c.n = S;
+        add_class(h.fixed, &h.n_fixed, c);
+      }
+    }
+  }
+  // ---- strategy 2: data rerouting; every stage must keep a peer and the capped split must exist
+  bool has2 = true;
+  uint64_t n_rr = 1;
+  s->comp.clear(); s->peers.clear();
+  for (int j = 0; j < S && has2; ++j) {
+    if (!lost_in_stage[j]) continue;
+    if (lost_in_stage[j] >= D) { has2 = false; break; }
+    const int a = h.n_aff++;
+    std::vector<int> pe;
+    for (int dd = 0; dd < D; ++dd)
+      if (!dead[dd][j]) { h.aff_q[a][pe.size()] = q[dd][j]; pe.push_back(dd); }
+    s->peers.push_back(pe);
+    h.aff_stage[a] = j; h.aff_peers[a] = (int)pe.size(); h.aff_total[a] = lost_in_stage[j] * M;
+    std::vector<uint64_t> tab;
+    count_table(h.aff_peers[a], h.aff_total[a], h.rcap, &tab);
+    h.comp_off[a] = (uint32_t)s->comp.size();
+    h.comp_stride[a] = (uint32_t)h.aff_total[a] + 1;
+    h.aff_R[a] = tab[(size_t)h.aff_peers[a] * h.comp_stride[a] + h.aff_total[a]];
+    s->comp.insert(s->comp.end(), tab.begin(), tab.end());
+    if (h.aff_R[a] == 0) has2 = false;
+    n_rr = mul_sat(n_rr, h.aff_R[a]);
+  }
+  if (!has2) { h.n_aff = 0; n_rr = 1; s->peers.clear(); }
+  if (has2) {
+    DevFamily &f = h.fam[2];
+    f.strategy = 2; f.stages = S; f.doubled = 0;
+    for (int dd = 0; dd < D; ++dd) {
+      DevClass c; memset(&c, 0, sizeof(c));
+      c.M = M; c.n = S;
+      for (int j = 0; j < S; ++j) { c.src[j] = (uint8_t)j; c.host[j] = (uint8_t)j; c.q[j] = dead[dd][j] ? 65536u : q[dd][j]; }
+      add_class(f.cls, &f.n_cls, c);
+    }
+  }
+  if (s->comp.empty()) s->comp.push_back(1);
+
+  // ---- plan index space
+  memset(&s->space, 0, sizeof(s->space));
+  const bool has[3] = {has0, has1, has2};
+  uint64_t off = 0;
+  for (int k = 0; k < 3; ++k) {
+    if (!has[k]) continue;
+    DevFamily &f = h.fam[k];
+    f.n_part = f.stages - 1 < DEV_MAX_S ? h.binom[f.stages - 1][L - 1] : UINT64_MAX;
+    f.n_reroute = k == 2 ? n_rr : 1;
+    const uint64_t total = mul_sat(f.n_part, f.n_reroute);
+    if (f.n_part == UINT64_MAX || f.n_reroute == UINT64_MAX || total >= (1ull << 62) || add_sat(off, total) >= (1ull << 62))
+      return CHM_ERR_OVERFLOW;
+    chm_family &o = s->space.fam[s->space.n_families++];
+    o.offset = off; o.n_part = f.n_part; o.n_reroute = f.n_reroute; o.stages = f.stages; o.strategy = k;
+    off += total;
+  }
+  s->space.n_plans = off;
+
+  // ---- bounds.  A pipeline time never exceeds (M + n - 1) x its largest stage time, a stage
+  // time never exceeds twice the whole model (redundant computation) times the slowest factor.
+  const u128 stage_max = (u128)(h.pf[L] + h.pb[L]) * 2 * ((qmax + 65535) / 65536);
+  const u128 t_max = (u128)(D * M + S - 1) * stage_max + (u128)S * h.comm;
+  const u128 pen_max = (u128)CHM_MAX_FAILED * (CHM_MAX_FAILED * M) * stage_max;
+  const u128 reconf_max = (u128)std::max(std::max(h.reconf[0], h.reconf[1]), h.reconf[2]) + (u128)h.xfer * h.pw[L];
+  const u128 cost_max = (u128)h.K * (t_max + pen_max) + reconf_max;
+  if (cost_max >= ((u128)1 << 62)) return CHM_ERR_OVERFLOW;
+  // packed argmin key: cost in the high bits, chunk-local partition index in the low ones
+  s->idx_bits = std::min(30, 64 - bit_length(cost_max + 1));
+  if (s->idx_bits < 8) return CHM_ERR_OVERFLOW;
+  // int32 recurrence is exact when even the largest intermediate (incl. the Q16 product's
+  // result and the penalty) stays below 2^31
+  s->int32_ok = (t_max + pen_max) < ((u128)1 << 31) && stage_max * 65536 < ((u128)1 << 62);
+  const int widest = std::max(S, 1);
+  s->smax = widest <= 4 ? 4 : widest <= 8 ? 8 : widest <= 16 ? 16 : 32;
+  return CHM_OK;
+}
+
+void release(chm_scenario *s) {
+  if (!s) return;
+  fast_release(&s->fast);
+  for (auto &e : s->ev) if (e) (void)hipEventDestroy(e);
+  if (s->h_pinned) (void)hipHostFree(s->h_pinned);
+  if (s->d_winner) (void)hipFree(s->d_winner);
+  if (s->d_slots) (void)hipFree(s->d_slots);
+  if (s->d_comp) (void)hipFree(s->d_comp);
+  if (s->d_scn) (void)hipFree(s->d_scn);
+  delete s;
+}
+
+void decode_partition(const chm_scenario *s, int k, uint64_t rank, uint8_t *cuts) {
+  int x = s->h.L - 2;
+  for (int i = k; i >= 1; --i) {
+    while (s->h.binom[i][x] > rank) --x;
+    cuts[i - 1] = (uint8_t)(x + 1);
+    rank -= s->h.binom[i][x];
+    --x;
+  }
+}
+
+void decode_reroute(const chm_scenario *s, int a, uint64_t rank, uint16_t *row /* [16], by replica */) {
+  const DevScenario &h = s->h;
+  const uint64_t *tab = s->comp.data() + h.comp_off[a];
+  int rem = h.aff_total[a];
+  const int p = h.aff_peers[a];
+  for (int pos = 0; pos < p; ++pos) {
+    const int left = p - 1 - pos;
+    int v = 0;
+    for (;; ++v) {
+      const uint64_t cnt = tab[(size_t)left * h.comp_stride[a] + (rem - v)];
+      if (rank < cnt) break;
+      rank -= cnt;
+    }
+    row[s->peers[a][pos]] = (uint16_t)v;
+    rem -= v;
+  }
+}
+
+void fill_plan(const chm_scenario *s, const chm_family *f, uint64_t part_rank, const uint64_t *rr_ranks, int64_t cost,
+               chm_best *out) {
+  memset(out, 0, sizeof(*out));
+  uint64_t joint = 0;
+  if (f->strategy == 2)
+    for (int a = 0; a < s->h.n_aff; ++a) joint = joint * s->h.aff_R[a] + rr_ranks[a];
+  out->index = f->offset + part_rank * f->n_reroute + joint;
+  out->cost = cost;
+  out->strategy = f->strategy;
+  out->stages = f->stages;
+  decode_partition(s, f->stages - 1, part_rank, out->cuts);
+  if (f->strategy == 2) {
+    out->n_affected = s->h.n_aff;
+    for (int a = 0; a < s->h.n_aff; ++a) {
+      out->affected_stage[a] = s->h.aff_stage[a];
+      decode_reroute(s, a, rr_ranks[a], out->reroute[a]);
+    }
+  }
+}
+
+void nothing_found(chm_best *out) {
+  memset(out, 0, sizeof(*out));
+  out->index = UINT64_MAX;
+  out->cost = CHM_INFEASIBLE;
+}
+
+struct Job { int strategy; uint64_t first, count; };
+
+// Runs the argmin over the given partition ranges (ascending plan index order).
+int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hipStream_t st) {
+  HIP_TRY(hipSetDevice(s->device));
+  s->last = chm_timing();
+  std::vector<Slot> slots;
+  const uint64_t chunk = 1ull << s->idx_bits;
+  for (const Job &j : jobs)
+    for (uint64_t done = 0; done < j.count; done += chunk) slots.push_back({j.strategy, j.first + done, s->idx_bits});
+  if (slots.empty()) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
+  if (slots.size() > MAX_SLOTS) return CHM_ERR_OVERFLOW;
+  if (chmk_fill_u64(s->d_slots, (uint32_t)slots.size(), CHM_KEY_NONE, st)) return CHM_ERR_HIP;
+  if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
+  size_t si = 0;
+  int ev_i = 1;
+  int ev_of[3] = {-1, -1, -1};
+  for (const Job &j : jobs) {
+    const DevFamily &fam = s->h.fam[j.strategy];
+    for (uint64_t done = 0; done < j.count; done += chunk, ++si) {
+      SearchLaunch a;
+      a.scn = s->d_scn; a.comp = s->d_comp; a.strategy = j.strategy;
+      a.part_first = j.first + done;
+      a.part_count = (uint32_t)std::min<uint64_t>(chunk, j.count - done);
+      a.idx_bits = s->idx_bits;
+      a.result = s->d_slots + si;
+      int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
+      if (rc > 0) rc = chmk_search(a, s->smax, st);
+      if (rc) return CHM_ERR_HIP;
+    }
+    s->last.partitions[j.strategy] += j.count;
+    uint64_t per_part = 1;
+    if (j.strategy == 2 && s->h.n_aff) { per_part = 0; for (int a = 0; a < s->h.n_aff; ++a) per_part += s->h.aff_R[a]; }
+    s->last.evaluations[j.strategy] += j.count * per_part;
+    (void)fam;
+    if (s->timing && ev_i < 7) { HIP_TRY(hipEventRecord(s->ev[ev_i], st)); ev_of[j.strategy] = ev_i; ++ev_i; }
+  }
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, slots.size() * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  if (s->timing) {
+    int prev = 0;
+    for (int k = 0; k < 3; ++k) {
+      if (ev_of[k] < 0) continue;
+      float ms = 0;
+      // families are launched in strategy order, so each one's span starts at the previous event
+      HIP_TRY(hipEventElapsedTime(&ms, s->ev[prev], s->ev[ev_of[k]]));
+      s->last.family_ms[k] += ms;
+      prev = ev_of[k];
+    }
+    HIP_TRY(hipEventElapsedTime(&s->last.total_ms, s->ev[0], s->ev[prev]));
+  }
+  // first strict minimum in plan-index order
+  int64_t best_cost = CHM_INFEASIBLE;
+  int best_strategy = -1;
+  uint64_t best_part = 0;
+  for (size_t i = 0; i < slots.size(); ++i) {
+    const uint64_t key = s->h_pinned[i];
+    if (key == CHM_KEY_NONE) continue;
+    const int64_t cost = (int64_t)(key >> slots[i].idx_bits);
+    if (cost < best_cost) {
+      best_cost = cost;
+      best_strategy = slots[i].strategy;
+      best_part = slots[i].part_first + (key & ((1ull << slots[i].idx_bits) - 1));
+    }
+  }
+  if (best_strategy < 0) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
+  uint64_t rr[DEV_MAX_AFF] = {};
+  if (best_strategy == 2 && s->h.n_aff > 0) {
+    if (chmk_reroute_winner(s->d_scn, s->d_comp, best_part, s->d_winner, s->smax, st)) return CHM_ERR_HIP;
+    HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_winner, DEV_MAX_AFF * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    for (int a = 0; a < s->h.n_aff; ++a) rr[a] = s->h_pinned[a];
+  }
+  fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
+  return CHM_OK;
+}
+
+}  // namespace
+
+extern "C" int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **out) {
+  if (!out) return CHM_ERR_ARG;
+  *out = nullptr;
+  int rc = validate(desc);
+  if (rc) return rc;
+  chm_scenario *s = new (std::nothrow) chm_scenario();
+  if (!s) return CHM_ERR_HIP;
+  rc = build_model(desc, s);
+  if (rc) { delete s; return rc; }
+  bool ok = hipGetDevice(&s->device) == hipSuccess;
+  ok = ok && hipMalloc((void **)&s->d_scn, sizeof(DevScenario)) == hipSuccess;
+  ok = ok && hipMalloc((void **)&s->d_comp, s->comp.size() * sizeof(uint64_t)) == hipSuccess;
+  ok = ok && hipMalloc((void **)&s->d_slots, MAX_SLOTS * sizeof(uint64_t)) == hipSuccess;
+  ok = ok && hipMalloc((void **)&s->d_winner, DEV_MAX_AFF * sizeof(uint64_t)) == hipSuccess;
+  ok = ok && hipHostMalloc((void **)&s->h_pinned, MAX_SLOTS * sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
+  ok = ok && hipMemcpy(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice) == hipSuccess;
+  ok = ok && hipMemcpy(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice) == hipSuccess;
+  for (auto &e : s->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
+  if (ok && s->h.fam[1].n_part) {
+    // the healthy pipelines' step time under the fault-free layout is computed by the device
+    ok = chmk_fixed_pipelines(s->d_scn, nullptr) == 0 && hipDeviceSynchronize() == hipSuccess;
+    ok = ok && hipMemcpy(&s->h.fam[1].fixed_step, &s->d_scn->fam[1].fixed_step, sizeof(int64_t), hipMemcpyDeviceToHost) == hipSuccess;
+  }
+  ok = ok && fast_prepare(&s->fast, s->h, s->int32_ok) == 0;
+  if (!ok) { release(s); return CHM_ERR_HIP; }
+  *out = s;
+  return CHM_OK;
+}
+
+extern "C" int chm_plan_space(const chm_scenario *s, chm_space *out) {
+  if (!s || !out) return CHM_ERR_ARG;
+  *out = s->space;
+  return CHM_OK;
+}
+
+extern "C" int chm_score_plans(chm_scenario *s, uint64_t first, uint64_t count, int64_t *d_costs, void *hip_stream) {
+  if (!s || (count && !d_costs)) return CHM_ERR_ARG;
+  if (first > s->space.n_plans || count > s->space.n_plans - first) return CHM_ERR_RANGE;
+  HIP_TRY(hipSetDevice(s->device));
+  uint64_t lo = first, hi = first + count;
+  for (int i = 0; i < s->space.n_families; ++i) {
+    const chm_family &f = s->space.fam[i];
+    const uint64_t fb = f.offset, fe = f.offset + f.n_part * f.n_reroute;
+    const uint64_t a = std::max(lo, fb), b = std::min(hi, fe);
+    if (a >= b) continue;
+    // split very long ranges so that the grid stays within 2^31 blocks
+    for (uint64_t p = a; p < b;) {
+      const uint64_t n = std::min<uint64_t>(b - p, 1ull << 36);
+      if (chmk_score(s->d_scn, s->d_comp, f.strategy, p - fb, n, d_costs + (p - first), s->smax, hip_stream)) return CHM_ERR_HIP;
+      p += n;
+    }
+  }
+  return CHM_OK;
+}
+
+extern "C" int chm_score_ranks(chm_scenario *s, int32_t strategy, const uint64_t *d_part_ranks, uint64_t n,
+                               int64_t *d_costs, void *hip_stream) {
+  if (!s || strategy < 0 || strategy > 2 || (n && (!d_part_ranks || !d_costs))) return CHM_ERR_ARG;
+  const chm_family *f = find_family(s, strategy);
+  if (!f) return CHM_ERR_UNRECOVERABLE;
+  if (f->n_reroute != 1) return CHM_ERR_ARG;
+  HIP_TRY(hipSetDevice(s->device));
+  for (uint64_t p = 0; p < n;) {
+    const uint64_t m = std::min<uint64_t>(n - p, 1ull << 36);
+    if (chmk_score_ranks(s->d_scn, s->d_comp, strategy, d_part_ranks + p, m, d_costs + p, s->smax, hip_stream)) return CHM_ERR_HIP;
+    p += m;
+  }
+  return CHM_OK;
+}
+
+extern "C" int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream) {
+  if (!s || !out) return CHM_ERR_ARG;
+  std::vector<Job> jobs;
+  for (int i = 0; i < s->space.n_families; ++i) {
+    const chm_family &f = s->space.fam[i];
+    if (strategy_mask & (1u << f.strategy)) jobs.push_back({f.strategy, 0, f.n_part});
+  }
+  if (jobs.empty()) { nothing_found(out); return CHM_ERR_UNRECOVERABLE; }
+  return run_search(s, jobs, out, (hipStream_t)hip_stream);
+}
+
+extern "C" int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part_first, uint64_t part_count,
+                                chm_best *out, void *hip_stream) {
+  if (!s || !out || strategy < 0 || strategy > 2) return CHM_ERR_ARG;
+  const chm_family *f = find_family(s, strategy);
+  if (!f) { nothing_found(out); return CHM_ERR_UNRECOVERABLE; }
+  if (part_first > f->n_part || part_count > f->n_part - part_first) return CHM_ERR_RANGE;
+  std::vector<Job> jobs;
+  jobs.push_back({strategy, part_first, part_count});
+  return run_search(s, jobs, out, (hipStream_t)hip_stream);
+}
+
+extern "C" int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out) {
+  if (!s || !out) return CHM_ERR_ARG;
+  if (index >= s->space.n_plans) return CHM_ERR_RANGE;
+  for (int i = 0; i < s->space.n_families; ++i) {
+    const chm_family &f = s->space.fam[i];
+    if (index < f.offset || index >= f.offset + f.n_part * f.n_reroute) continue;
+    const uint64_t local = index - f.offset;
+    uint64_t joint = local % f.n_reroute, rr[DEV_MAX_AFF] = {};
+    if (f.strategy == 2)
+      for (int a = s->h.n_aff - 1; a >= 0; --a) { rr[a] = joint % s->h.aff_R[a]; joint /= s->h.aff_R[a]; }
+    fill_plan(s, &f, local / f.n_reroute, rr, 0, out);
+    return CHM_OK;
+  }
+  return CHM_ERR_RANGE;
+}
+
+extern "C" int chm_set_timing(chm_scenario *s, int32_t on) {
+  if (!s) return CHM_ERR_ARG;
+  s->timing = on != 0;
+  return CHM_OK;
+}
+
+extern "C" int chm_get_timing(const chm_scenario *s, chm_timing *out) {
+  if (!s || !out) return CHM_ERR_ARG;
+  *out = s->last;
+  return CHM_OK;
+}
+
+extern "C" void chm_free_scenario(chm_scenario *s) { release(s); }
+
+extern "C" const char *chm_strerror(int code) {
+  switch (code) {
+    case CHM_OK: return "ok";
+    case CHM_ERR_ARG: return "invalid argument";
+    case CHM_ERR_RANGE: return "plan range or rank outside the plan space";
+    case CHM_ERR_OVERFLOW: return "plan count or cost bound too large";
+    case CHM_ERR_UNRECOVERABLE: return "no requested strategy can recover this failure set";
+    case CHM_ERR_NO_FEASIBLE: return "every plan exceeds the memory cap";
+    case CHM_ERR_HIP: return "HIP call failed";
+    default: return "unknown error";
+  }
+}

@@ -1,0 +1,447 @@
+// Generic scoring kernels of libchm for gfx950: any shape within the library limits,
+// int64 arithmetic throughout.  One lane evaluates one plan (scoring) or one partition
+// with all of its reroute vectors (search).  The shape-specialised search kernels live in
+// chm_fast.hip; these are the reference the library falls back to for shapes those do not
+// cover, and the only path for chm_score_plans / chm_score_ranks.
+//
+// Pipeline time: the 1F1B dependency recurrence of the Estimator subsection
+// (eq. (transition)) is a longest path in a fixed graph, so any topological order gives
+// the same integers.  The order used here keeps ONE value per stage live: in round t
+// (t = 0 .. M+n-2) stage s runs forward t (if t < M) and then backward t-(n-1-s) (if that
+// is a valid micro-batch).  Forward t of stage s needs forward t of stage s-1 (same
+// round, swept in stage order) and the stage's previous operation; backward j of stage s
+// needs backward j of stage s+1, which stage s+1 ran in round t-1 as its last operation,
+// i.e. the value E[s+1] held before this round's forward sweep overwrote it.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "chm_dev.h"
+
+namespace {
+
+constexpr int BLOCK = 256;
+
+__device__ __forceinline__ int64_t imax(int64_t a, int64_t b) { return a > b ? a : b; }
+__device__ __forceinline__ int64_t scale_q16(int64_t x, uint32_t q) { return (x * (int64_t)q + 32768) >> 16; }
+
+template <int SMAX>
+__device__ __forceinline__ int64_t makespan_generic(const int64_t (&F)[SMAX], const int64_t (&B)[SMAX], int n, int M) {
+  int64_t E[SMAX];
+#pragma unroll
+  for (int s = 0; s < SMAX; ++s) E[s] = 0;
+  const int rounds = M + n - 1;
+  for (int t = 0; t < rounds; ++t) {
+    const bool fwd = t < M;
+    int64_t x = 0;
+#pragma unroll
+    for (int s = 0; s < SMAX; ++s) {
+      if (s < n) {
+        const int64_t old = E[s];
+        if (fwd) {
+          E[s] = imax(E[s], x) + F[s];
+          x = E[s];
+          if (s == n - 1) E[s] += B[s];          // last stage: backward t follows its own forward
+        }
+        if (s >= 1) {
+          const int j = t - n + s;               // micro-batch whose backward stage s-1 runs now
+          if (j >= 0 && j < M) E[s - 1] = imax(E[s - 1], old) + B[s - 1];
+        }
+      }
+    }
+  }
+  return E[0];
+}
+
+// cut positions of one lane live in a column of LDS: c[i][tid], i = 0..stages
+template <int SMAX>
+struct Cuts {
+  int32_t (*c)[BLOCK];
+  int tid;
+  __device__ __forceinline__ int get(int i) const { return c[i][tid]; }
+  __device__ __forceinline__ void set(int i, int v) { c[i][tid] = v; }
+};
+
+template <int SMAX>
+__device__ __forceinline__ void unrank_partition(const DevScenario *scn, int k, uint64_t rank, Cuts<SMAX> cuts) {
+  const int L = scn->L;
+  cuts.set(0, 0);
+  cuts.set(k + 1, L);
+  int x = L - 2;
+  uint64_t rem = rank;
+  for (int i = k; i >= 1; --i) {
+    while (scn->binom[i][x] > rem) --x;   // stops at x = i-1 at the latest (C(i-1,i) = 0)
+    cuts.set(i, x + 1);
+    rem -= scn->binom[i][x];
+    --x;
+  }
+}
+
+__device__ __forceinline__ int64_t missing_interval(const DevScenario *scn, int a, int b, int a0, int b0) {
+  const int64_t need = scn->pw[b] - scn->pw[a];
+  const int lo = a > a0 ? a : a0, hi = b < b0 ? b : b0;
+  const int64_t have = hi > lo ? scn->pw[hi] - scn->pw[lo] : 0;
+  return need - have;
+}
+
+// Everything of a plan's cost except the rerouting penalty.  Returns false when the plan
+// does not fit in memory.
+template <int SMAX>
+__device__ __forceinline__ bool eval_base(const DevScenario *scn, const DevFamily &fam, Cuts<SMAX> cuts,
+                                          int64_t *t_step_out, int64_t *reconf_out) {
+  const int SP = fam.stages;
+  if (fam.fixed_step == CHM_INF_COST) return false;
+  // memory filter
+  bool ok = true;
+  for (int j = 0; j < SP; ++j) {
+    int64_t m = scn->pw[cuts.get(j + 1)] - scn->pw[cuts.get(j)];
+    if (fam.doubled) {
+      const int nx = (j + 1 == SP) ? 0 : j + 1;
+      m += scn->pw[cuts.get(nx + 1)] - scn->pw[cuts.get(nx)];
+    }
+    ok = ok && (m <= scn->cap);
+  }
+  if (!ok) return false;
+
+  int64_t t_step = fam.fixed_step;
+  int64_t missing = 0;
+  if (fam.strategy != 1) {
+    for (int j = 0; j < SP; ++j)
+      missing += missing_interval(scn, cuts.get(j), cuts.get(j + 1), scn->p0[j], scn->p0[j + 1]);
+  }
+  for (int ci = 0; ci < fam.n_cls; ++ci) {
+    const DevClass &cls = fam.cls[ci];
+    int64_t F[SMAX], B[SMAX];
+    int64_t miss = 0;
+#pragma unroll
+    for (int j = 0; j < SMAX; ++j) {
+      F[j] = 0; B[j] = 0;
+      if (j < cls.n) {
+        const int st = cls.src[j];
+        const int lo = cuts.get(st), hi = cuts.get(st + 1);
+        int64_t f = scn->pf[hi] - scn->pf[lo];
+        int64_t b = scn->pb[hi] - scn->pb[lo];
+        if (fam.doubled) {
+          const int nx = (st + 1 == SP) ? 0 : st + 1;
+          const int lo2 = cuts.get(nx), hi2 = cuts.get(nx + 1);
+          f += scn->pf[hi2] - scn->pf[lo2];
+          b += scn->pb[hi2] - scn->pb[lo2];
+        }
+        F[j] = scale_q16(f, cls.q[j]);
+        B[j] = scale_q16(b, cls.q[j]);
+        if (fam.strategy == 1) {
+          const int h = cls.host[j];
+          miss += missing_interval(scn, lo, hi, scn->p0[h], scn->p0[h + 1]);
+        }
+      }
+    }
+    const int64_t T = makespan_generic<SMAX>(F, B, cls.n, cls.M) + (int64_t)(cls.n - 1) * scn->comm;
+    t_step = imax(t_step, T);
+    missing = imax(missing, miss);
+  }
+  *t_step_out = t_step;
+  *reconf_out = scn->reconf[fam.strategy] + scn->xfer * missing;
+  return true;
+}
+
+// forward+backward time of affected stage a on its peer i under the lane's partition
+template <int SMAX>
+__device__ __forceinline__ int64_t peer_weight(const DevScenario *scn, Cuts<SMAX> cuts, int a, int i) {
+  const int st = scn->aff_stage[a];
+  const int lo = cuts.get(st), hi = cuts.get(st + 1);
+  const uint32_t q = scn->aff_q[a][i];
+  return scale_q16(scn->pf[hi] - scn->pf[lo], q) + scale_q16(scn->pb[hi] - scn->pb[lo], q);
+}
+
+// penalty of the reroute vector of stage a with a given rank (vector decoded on the fly)
+template <int SMAX>
+__device__ __forceinline__ int64_t penalty_of_rank(const DevScenario *scn, const uint64_t *comp, Cuts<SMAX> cuts,
+                                                   int a, uint64_t rank) {
+  const int p = scn->aff_peers[a];
+  const uint64_t *tab = comp + scn->comp_off[a];
+  const uint32_t stride = scn->comp_stride[a];
+  int rem = scn->aff_total[a];
+  int64_t pen = 0;
+  for (int pos = 0; pos < p; ++pos) {
+    const int left = p - 1 - pos;
+    int v = 0;
+    for (;; ++v) {
+      const uint64_t cnt = tab[(uint32_t)left * stride + (uint32_t)(rem - v)];
+      if (rank < cnt) break;
+      rank -= cnt;
+    }
+    rem -= v;   // a valid rank is always found at a v within [0, min(rem, cap)]
+    pen = imax(pen, (int64_t)v * peer_weight<SMAX>(scn, cuts, a, pos));
+  }
+  return pen;
+}
+
+// Sweep of every valid reroute vector of stage a in rank order; first strict minimum.
+// The vector lives in a column of LDS.
+template <int SMAX>
+__device__ __forceinline__ void sweep_stage(const DevScenario *scn, Cuts<SMAX> cuts, int a,
+                                            int32_t (*rv)[BLOCK], int64_t *best_pen, uint64_t *best_rank) {
+  const int tid = cuts.tid;
+  const int p = scn->aff_peers[a];
+  const int total = scn->aff_total[a];
+  const int cap = scn->rcap > 0 ? scn->rcap : total;
+  int64_t w[DEV_MAX_D];
+#pragma unroll
+  for (int i = 0; i < DEV_MAX_D; ++i) w[i] = i < p ? peer_weight<SMAX>(scn, cuts, a, i) : 0;
+  // lexicographically first vector: as much as possible on the last peers
+  int rem = total;
+  for (int i = p - 1; i >= 0; --i) {
+    const int v = rem < cap ? rem : cap;
+    rv[i][tid] = v;
+    rem -= v;
+  }
+  int64_t bp = CHM_INF_COST;
+  uint64_t br = 0, rank = 0;
+  for (;;) {
+    int64_t pen = 0;
+#pragma unroll
+    for (int i = 0; i < DEV_MAX_D; ++i)
+      if (i < p) pen = imax(pen, (int64_t)rv[i][tid] * w[i]);
+    if (pen < bp) { bp = pen; br = rank; }
+    ++rank;
+    // successor: rightmost entry that can grow while something to its right can shrink
+    int suffix = rv[p - 1][tid];
+    int i = p - 2;
+    while (i >= 0 && (rv[i][tid] >= cap || suffix == 0)) { suffix += rv[i][tid]; --i; }
+    if (i < 0) break;
+    rv[i][tid] += 1;
+    int left = suffix - 1;
+    for (int j = p - 1; j > i; --j) {
+      const int v = left < cap ? left : cap;
+      rv[j][tid] = v;
+      left -= v;
+    }
+  }
+  *best_pen = bp;
+  *best_rank = br;
+}
+
+// ---------------------------------------------------------------------------------------
+// wave / block argmin on a packed 64-bit key
+// ---------------------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_min(uint64_t v) {
+  // partner value through a DPP move; lanes without a source keep their own value
+  const int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)v, (int)(uint32_t)v, CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp((int)(uint32_t)(v >> 32), (int)(uint32_t)(v >> 32), CTRL, 0xF, 0xF, false);
+  return umin64(v, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+__device__ __forceinline__ uint64_t wave_min(uint64_t v) {
+  v = dpp_min<0xB1>(v);     // quad_perm [1,0,3,2]
+  v = dpp_min<0x4E>(v);     // quad_perm [2,3,0,1]
+  v = dpp_min<0x141>(v);    // row_half_mirror
+  v = dpp_min<0x140>(v);    // row_mirror
+  // across the four rows of 16 lanes
+  v = umin64(v, __shfl_xor(v, 16, 64));
+  v = umin64(v, __shfl_xor(v, 32, 64));
+  return v;
+}
+
+__device__ __forceinline__ void block_min_to_global(uint64_t key, uint64_t *result) {
+  __shared__ uint64_t wave_keys[BLOCK / 64];
+  key = wave_min(key);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) wave_keys[wave] = key;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint64_t k = wave_keys[0];
+#pragma unroll
+    for (int i = 1; i < BLOCK / 64; ++i) k = umin64(k, wave_keys[i]);
+    if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)result, (unsigned long long)k);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// kernels
+// ---------------------------------------------------------------------------------------
+__global__ void k_fill_u64(uint64_t *p, uint32_t n, uint64_t v) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// step time of the pipelines that strategy 1 leaves in the fault-free layout
+__global__ void k_fixed_pipelines(DevScenario *scn) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  DevFamily &fam = scn->fam[1];
+  if (fam.n_part == 0) return;
+  int64_t t = 0;
+  bool fits = true;
+  for (int d = 0; d < scn->n_fixed; ++d) {
+    const DevClass &cls = scn->fixed[d];
+    int64_t F[DEV_MAX_S], B[DEV_MAX_S];
+#pragma unroll
+    for (int j = 0; j < DEV_MAX_S; ++j) {
+      F[j] = 0; B[j] = 0;
+      if (j < cls.n) {
+        const int lo = scn->p0[j], hi = scn->p0[j + 1];
+        if (scn->pw[hi] - scn->pw[lo] > scn->cap) fits = false;
+        F[j] = scale_q16(scn->pf[hi] - scn->pf[lo], cls.q[j]);
+        B[j] = scale_q16(scn->pb[hi] - scn->pb[lo], cls.q[j]);
+      }
+    }
+    const int64_t T = makespan_generic<DEV_MAX_S>(F, B, cls.n, cls.M) + (int64_t)(cls.n - 1) * scn->comm;
+    t = imax(t, T);
+  }
+  fam.fixed_step = fits ? t : CHM_INF_COST;
+}
+
+template <int SMAX>
+__device__ __forceinline__ int64_t plan_cost(const DevScenario *scn, const uint64_t *comp, const DevFamily &fam,
+                                             Cuts<SMAX> cuts, uint64_t part_rank, uint64_t rr_rank) {
+  unrank_partition<SMAX>(scn, fam.stages - 1, part_rank, cuts);
+  int64_t t_step, reconf;
+  if (!eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf)) return CHM_INF_COST;
+  if (fam.strategy == 2) {
+    for (int a = scn->n_aff - 1; a >= 0; --a) {       // last affected stage is least significant
+      const uint64_t R = scn->aff_R[a];
+      const uint64_t r = rr_rank % R;
+      rr_rank /= R;
+      t_step += penalty_of_rank<SMAX>(scn, comp, cuts, a, r);
+    }
+  }
+  return scn->K * t_step + reconf;
+}
+
+template <int SMAX>
+__global__ void __launch_bounds__(BLOCK) k_score(const DevScenario *scn, const uint64_t *comp, int strategy,
+                                                 uint64_t first_local, uint64_t count, int64_t *costs) {
+  __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
+  const uint64_t gid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+  if (gid >= count) return;
+  const DevFamily &fam = scn->fam[strategy];
+  Cuts<SMAX> cuts{cut_cols, (int)threadIdx.x};
+  const uint64_t local = first_local + gid;
+  const uint64_t R = fam.n_reroute;
+  const uint64_t part = R == 1 ? local : local / R;
+  const uint64_t rr = R == 1 ? 0 : local - part * R;
+  costs[gid] = plan_cost<SMAX>(scn, comp, fam, cuts, part, rr);
+}
+
+template <int SMAX>
+__global__ void __launch_bounds__(BLOCK) k_score_ranks(const DevScenario *scn, const uint64_t *comp, int strategy,
+                                                       const uint64_t *ranks, uint64_t n, int64_t *costs) {
+  __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
+  const uint64_t gid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+  if (gid >= n) return;
+  const DevFamily &fam = scn->fam[strategy];
+  Cuts<SMAX> cuts{cut_cols, (int)threadIdx.x};
+  const uint64_t part = ranks[gid];
+  costs[gid] = part < fam.n_part ? plan_cost<SMAX>(scn, comp, fam, cuts, part, 0) : CHM_INF_COST;
+}
+
+template <int SMAX>
+__global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
+  __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
+  __shared__ int32_t rv_cols[DEV_MAX_D][BLOCK];
+  const DevScenario *scn = a.scn;
+  const DevFamily &fam = scn->fam[a.strategy];
+  const uint32_t gid = blockIdx.x * BLOCK + threadIdx.x;
+  uint64_t key = CHM_KEY_NONE;
+  if (gid < a.part_count) {
+    Cuts<SMAX> cuts{cut_cols, (int)threadIdx.x};
+    unrank_partition<SMAX>(scn, fam.stages - 1, a.part_first + gid, cuts);
+    int64_t t_step, reconf;
+    if (eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf)) {
+      if (fam.strategy == 2) {
+        for (int st = 0; st < scn->n_aff; ++st) {
+          int64_t pen; uint64_t rk;
+          sweep_stage<SMAX>(scn, cuts, st, rv_cols, &pen, &rk);
+          t_step += pen;
+        }
+      }
+      const uint64_t cost = (uint64_t)(scn->K * t_step + reconf);
+      key = (cost << a.idx_bits) | gid;
+    }
+  }
+  block_min_to_global(key, a.result);
+}
+
+template <int SMAX>
+__global__ void __launch_bounds__(BLOCK) k_reroute_winner(const DevScenario *scn, const uint64_t *comp,
+                                                          uint64_t part_rank, uint64_t *out) {
+  __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
+  __shared__ int32_t rv_cols[DEV_MAX_D][BLOCK];
+  (void)comp;
+  const int a = threadIdx.x;                         // one lane per affected stage
+  if (a >= scn->n_aff) return;
+  const DevFamily &fam = scn->fam[2];
+  Cuts<SMAX> cuts{cut_cols, (int)threadIdx.x};
+  unrank_partition<SMAX>(scn, fam.stages - 1, part_rank, cuts);
+  int64_t pen; uint64_t rk;
+  sweep_stage<SMAX>(scn, cuts, a, rv_cols, &pen, &rk);
+  out[a] = rk;
+}
+
+template <typename Fn>
+int dispatch_smax(int smax, Fn fn) {
+  if (smax <= 4) return fn(std::integral_constant<int, 4>());
+  if (smax <= 8) return fn(std::integral_constant<int, 8>());
+  if (smax <= 16) return fn(std::integral_constant<int, 16>());
+  return fn(std::integral_constant<int, 32>());
+}
+
+}  // namespace
+
+int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream) {
+  hipLaunchKernelGGL(k_fill_u64, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, d_ptr, n, value);
+  return (int)hipGetLastError();
+}
+
+int chmk_fixed_pipelines(DevScenario *d_scn, void *stream) {
+  hipLaunchKernelGGL(k_fixed_pipelines, dim3(1), dim3(64), 0, (hipStream_t)stream, d_scn);
+  return (int)hipGetLastError();
+}
+
+int chmk_score(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy, uint64_t first_local,
+               uint64_t count, int64_t *d_costs, int32_t smax, void *stream) {
+  if (count == 0) return 0;
+  const uint64_t blocks = (count + BLOCK - 1) / BLOCK;
+  if (blocks > 0x7fffffffull) return (int)hipErrorInvalidValue;
+  return dispatch_smax(smax, [&](auto tag) {
+    constexpr int SMAX = decltype(tag)::value;
+    hipLaunchKernelGGL(k_score<SMAX>, dim3((uint32_t)blocks), dim3(BLOCK), 0, (hipStream_t)stream, d_scn, d_comp,
+                       strategy, first_local, count, d_costs);
+    return (int)hipGetLastError();
+  });
+}
+
+int chmk_score_ranks(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy, const uint64_t *d_ranks,
+                     uint64_t n, int64_t *d_costs, int32_t smax, void *stream) {
+  if (n == 0) return 0;
+  const uint64_t blocks = (n + BLOCK - 1) / BLOCK;
+  if (blocks > 0x7fffffffull) return (int)hipErrorInvalidValue;
+  return dispatch_smax(smax, [&](auto tag) {
+    constexpr int SMAX = decltype(tag)::value;
+    hipLaunchKernelGGL(k_score_ranks<SMAX>, dim3((uint32_t)blocks), dim3(BLOCK), 0, (hipStream_t)stream, d_scn,
+                       d_comp, strategy, d_ranks, n, d_costs);
+    return (int)hipGetLastError();
+  });
+}
+
+int chmk_search(const SearchLaunch &a, int32_t smax, void *stream) {
+  if (a.part_count == 0) return 0;
+  const uint32_t blocks = (a.part_count + BLOCK - 1) / BLOCK;
+  return dispatch_smax(smax, [&](auto tag) {
+    constexpr int SMAX = decltype(tag)::value;
+    hipLaunchKernelGGL(k_search<SMAX>, dim3(blocks), dim3(BLOCK), 0, (hipStream_t)stream, a);
+    return (int)hipGetLastError();
+  });
+}
+
+int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank, uint64_t *d_out,
+                        int32_t smax, void *stream) {
+  return dispatch_smax(smax, [&](auto tag) {
+    constexpr int SMAX = decltype(tag)::value;
+    hipLaunchKernelGGL(k_reroute_winner<SMAX>, dim3(1), dim3(BLOCK), 0, (hipStream_t)stream, d_scn, d_comp,
+                       part_rank, d_out);
+    return (int)hipGetLastError();
+  });
+}

@@ -1,0 +1,62 @@
+"""The C-ABI library loads and exports every entry point include/chm.h declares (no GPU needed),
+and the host-side validation answers without touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2508_21613_amd import binding as B
+from paper_2508_21613_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "chm.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(chm_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_entry_point_is_exported():
+    names = declared_functions()
+    assert "chm_load_scenario" in names and "chm_score_plans" in names and "chm_search_best" in names
+    lib = C.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(B.SYMBOLS) == names
+
+
+def test_struct_layouts_match_the_header():
+    assert C.sizeof(B.Family) == 32 and C.sizeof(B.Space) == 8 + 3 * 32 + 8
+    assert C.sizeof(B.Best) == 8 + 8 + 4 + 4 + 32 + 4 + 16 + 128 + 4   # trailing padding to 8 bytes
+    assert C.sizeof(B.Desc) == 16 + 4 * 8 + 8 + 8 + 4 * 4 + 12 + 4 + 0 or C.sizeof(B.Desc) % 8 == 0
+
+
+def test_error_strings_and_argument_checks_need_no_device():
+    assert B.strerror(0) == "ok" and "memory" in B.strerror(B.ERR_NO_FEASIBLE)
+    sc = synth.small_random(1)
+    for key, val in [("L", 0), ("L", 129), ("PP", 0), ("DP", 17), ("M", 257), ("failed_nodes", [0, 0]),
+                     ("failed_nodes", [10 ** 6]), ("horizon_steps", 0), ("mem_cap_mib", 0), ("comm_us", -1),
+                     ("fwd_us", np.zeros(sc["L"], np.int32))]:
+        with pytest.raises(B.ChmError) as e:
+            B.Scenario(dict(sc, **{key: val}))
+        assert e.value.code == B.ERR_ARG, key
+    wide = synth.scenario(128, 32, 2, 4, np.ones(128, np.int32), np.ones(128, np.int32), np.ones(128, np.int32),
+                          [0], 0, 1000)
+    with pytest.raises(B.ChmError) as e:
+        B.Scenario(wide)
+    assert e.value.code == B.ERR_OVERFLOW
+    assert B.lib().chm_plan_space(None, None) == B.ERR_ARG
+    assert B.lib().chm_search_best(None, 7, None, None) == B.ERR_ARG
+    assert B.lib().chm_score_plans(None, 0, 0, None, None) == B.ERR_ARG
+
+
+def test_no_cpu_fallback_without_a_device():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(B.ChmError) as e:
+        B.Scenario(synth.small_random(1))
+    assert e.value.code == B.ERR_HIP
