@@ -1,0 +1,192 @@
+"""Benchmark of the plan-scoring hot path on one MI355X.
+
+A step is one exhaustive chm_search_best over the whole plan space of the 32-card
+configuration (L=48, PP=8, DP=4, M=16, one failed node): unranking, stage sums, memory
+filter, 1F1B recurrence per pipeline class, strategy terms and argmin for every partition
+of the three strategies and every reroute vector.  The scenario tables are resident in
+HBM before the timed region.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X: 256 compute units x 64 int32 lanes per clock x 2.4 GHz (the fp32 vector figure
+# 157.3 TFLOP/s counts a packed fused multiply-add as 4 flops per lane: 157.3 / 4 = 39.3)
+ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+
+
+def algorithmic_ops(fam, feasible):
+    """Integer operations the method needs for one search launch of a strategy (not what the kernel
+    executes).  Every partition: 3 stage sums per stage and the memory compare per stage.  A
+    partition that passes the memory filter in addition: per pipeline class one max and one add
+    per recurrence cell (2 x stages x micro-batches cells), 2 Q16 scalings per stage, the
+    comm add and the max over pipelines; 4 per stage for the weight-fetch volume; 2 for the cost;
+    and per reroute vector one multiply per peer, the max over peers and the compare."""
+    S = fam["stages"]
+    light = 4 * S
+    heavy = sum(4 * n_c * m_c + 2 * n_c + 2 for n_c, m_c in fam["classes"]) + 4 * S + 2
+    heavy += sum(R * 2 * p for R, p in zip(fam["R"], fam["peers"]))
+    return fam["n_part"] * light + feasible * heavy, light, heavy
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--ttb-runs", type=int, default=10)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the plan search runs on a single MI355X and nothing here shards "
+              "across devices; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    def note(msg):
+        print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    import numpy as np
+    import torch
+    from paper_2508_21613_amd import binding as B
+    from paper_2508_21613_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    sc = synth.config2()
+    t0 = time.perf_counter()
+    g = B.Scenario(sc)
+    load_ms = (time.perf_counter() - t0) * 1e3
+    stream = torch.cuda.Stream()
+    n_plans = g.n_plans
+    fams = []
+    for f in g.families:
+        d = dict(f)
+        d["classes"] = g.family_classes(f["strategy"])
+        if f["strategy"] == 2:
+            S, D = sc["PP"], sc["DP"]
+            lost_stage = {}
+            for n in sc["failed_nodes"]:
+                lost_stage[n % S] = lost_stage.get(n % S, 0) + 1
+            d["peers"] = [D - v for _, v in sorted(lost_stage.items())]
+            from math import comb
+            d["R"] = [comb(v * sc["M"] + (D - v) - 1, (D - v) - 1) for _, v in sorted(lost_stage.items())]
+        else:
+            d["peers"], d["R"] = [], []
+        fams.append(d)
+
+    if args.copy_calibration:
+        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            rc, best = g.search_best(7, stream=stream)
+            note("warm-up search %d done" % i)
+        g.set_timing(True)
+        fam_ms = np.zeros(3)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record(stream)
+        for _ in range(args.steps):
+            rc, best = g.search_best(7, stream=stream)
+            fam_ms += np.array(g.get_timing()["family_ms"])
+        ev1.record(stream)
+        stream.synchronize()
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    assert rc == 0
+    ms_per_step = wall * 1e3 / args.steps
+    note("timed %d searches: %.3f ms per search, per strategy %s" % (args.steps, ms_per_step, fam_ms / args.steps))
+    fam_ms /= args.steps
+    timing = g.get_timing()
+
+    # time-to-best-plan: load + search, median over --ttb-runs fresh handles
+    ttb = []
+    for _ in range(args.ttb_runs):
+        t0 = time.perf_counter()
+        g2 = B.Scenario(sc)
+        g2.search_best(7, stream=stream)
+        ttb.append((time.perf_counter() - t0) * 1e3)
+        g2.close()
+    ttb_ms = float(np.median(ttb)) if ttb else None
+    note("time to best plan (load + search): %s ms" % ttb_ms)
+
+    # roofline of the dominant kernel
+    dom = int(np.argmax(fam_ms))
+    fam = [f for f in fams if f["strategy"] == dom][0]
+    ops_launch, ops_light, ops_heavy = algorithmic_ops(fam, timing["feasible"][dom])
+    achieved = ops_launch / (fam_ms[dom] * 1e-3) / 1e12
+    cells = sum(f["n_part"] * sum(2 * n * m for n, m in f["classes"]) for f in fams)
+    n_part_total = sum(f["n_part"] for f in fams)
+
+    out = {
+        "metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
+        "value": n_plans / (ms_per_step * 1e-3),
+        "unit": "plans/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": "config2: L=48 PP=8 DP=4 M=16, 1 failed node, exhaustive search over all 3 strategies",
+                   "plan_indices": n_plans, "partitions": n_part_total, "failed_nodes": sc["failed_nodes"],
+                   "families": [{k: f[k] for k in ("strategy", "stages", "n_part", "n_reroute")} for f in fams]},
+        "time_to_best_plan_ms": ttb_ms, "load_ms": load_ms,
+        "partition_evals_per_s": n_part_total / (ms_per_step * 1e-3),
+        "recurrence_cells_per_s": cells / (ms_per_step * 1e-3),
+        "kernel_ms_per_strategy": [float(x) for x in fam_ms],
+        "best": {"index": best["index"], "cost": best["cost"], "strategy": best["strategy"], "cuts": best["cuts"]},
+        "roofline": {"bound": "alu", "kernel": "search, strategy %d" % dom, "achieved": achieved,
+                     "peak": ALU_PEAK_TOPS, "unit": "TOP/s (int32 lane operations)", "frac": achieved / ALU_PEAK_TOPS,
+                     "traffic": None, "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": ops_launch,
+                     "feasible_partitions": timing["feasible"][dom], "partitions": fam["n_part"],
+                     "algorithmic_ops_per_feasible_partition": ops_light + ops_heavy,
+                     "algorithmic_ops_per_infeasible_partition": ops_light},
+        "feasible_partitions_per_strategy": timing["feasible"],
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        o = O.Scenario(sc)
+        spent = 0.0
+        per_family = []
+        for f in o.families:               # the same three strategies, a slice from the middle of each rank space
+            share = max(0.1, (f["n_part"] * f["n_reroute"]) / o.n_plans * 0.8)
+            budget = args.cpu_seconds * share
+            mid = f["n_part"] // 2
+            n0 = min(500, f["n_part"] - mid)
+            t0 = time.perf_counter()
+            o.search_range(f["strategy"], mid, n0)
+            t_cal = max(time.perf_counter() - t0, 1e-4)
+            n = int(max(n0, min(f["n_part"] - mid, budget * n0 / t_cal)))
+            t0 = time.perf_counter()
+            _, _, ev = o.search_range(f["strategy"], mid, n)
+            t = time.perf_counter() - t0
+            per_family.append((f["strategy"], n, ev, t))
+            note("oracle: strategy %d, %d partitions in %.2f s" % (f["strategy"], n, t))
+            spent += t + t_cal
+        # whole-job rate of the oracle: time it would need for the full space at these per-family rates
+        full_s = sum(t * (o.family(s)["n_part"] / n) for s, n, ev, t in per_family)
+        out["cpu_baseline"] = {"value": o.n_plans / full_s, "unit": "plans/s", "cores": 1, "kind": "oracle",
+                               "sample": "oracle search over %s partitions from the middle of the rank space of strategies %s (%.1f s of CPU work), "
+                                         "extrapolated per strategy to the full space" %
+                                         ([n for _, n, _, _ in per_family], [s for s, _, _, _ in per_family], spent),
+                               "full_space_seconds_estimate": full_s}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

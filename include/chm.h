@@ -107,6 +107,7 @@ typedef struct {
   float total_ms;              /* first launch to last launch of the call                            */
   uint64_t partitions[3];      /* partitions evaluated per strategy                                  */
   uint64_t evaluations[3];     /* (partition, reroute vector) evaluations per strategy               */
+  uint64_t feasible[3];        /* partitions per strategy that passed the memory filter              */
 } chm_timing;
 
 /* Validates the description, builds the plan space and uploads the scenario tables
@@ -147,6 +148,11 @@ int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out);
  * and reads the timings of the last such call. */
 int chm_set_timing(chm_scenario *s, int32_t on);
 int chm_get_timing(const chm_scenario *s, chm_timing *out);
+
+/* The distinct pipelines one plan of a strategy has to evaluate (pipelines with the same
+ * nodes' speed factors, chain and micro-batch count are merged): *n of them (<= 16), each
+ * with length[i] stages and micro_batches[i] micro-batches.  Host only; for work accounting. */
+int chm_family_classes(const chm_scenario *s, int32_t strategy, int32_t *n, int32_t *length, int32_t *micro_batches);
 
 void chm_free_scenario(chm_scenario *s);
 const char *chm_strerror(int code);

@@ -16,7 +16,8 @@ OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HI
 INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
-           "chm_search_range", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_free_scenario",
+           "chm_search_range", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
+           "chm_free_scenario",
            "chm_strerror"]
 
 
@@ -47,7 +48,7 @@ class Best(C.Structure):
 
 class Timing(C.Structure):
     _fields_ = [("family_ms", C.c_float * 3), ("total_ms", C.c_float),
-                ("partitions", C.c_uint64 * 3), ("evaluations", C.c_uint64 * 3)]
+                ("partitions", C.c_uint64 * 3), ("evaluations", C.c_uint64 * 3), ("feasible", C.c_uint64 * 3)]
 
 
 class ChmError(RuntimeError):
@@ -76,6 +77,7 @@ def lib():
         L.chm_decode_plan.argtypes = [vp, C.c_uint64, C.POINTER(Best)]
         L.chm_set_timing.argtypes = [vp, C.c_int32]
         L.chm_get_timing.argtypes = [vp, C.POINTER(Timing)]
+        L.chm_family_classes.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.chm_free_scenario.argtypes = [vp]
         L.chm_free_scenario.restype = None
         L.chm_strerror.argtypes = [C.c_int]
@@ -200,6 +202,13 @@ class Scenario:
         _check(lib().chm_decode_plan(self._h, index, C.byref(b)))
         return _best_dict(b)
 
+    def family_classes(self, strategy):
+        """[(stages, micro-batches)] of the distinct pipelines one plan of the strategy evaluates"""
+        n = C.c_int32()
+        ln, mb = (C.c_int32 * 16)(), (C.c_int32 * 16)()
+        _check(lib().chm_family_classes(self._h, strategy, C.byref(n), ln, mb))
+        return [(int(ln[i]), int(mb[i])) for i in range(n.value)]
+
     def set_timing(self, on=True):
         _check(lib().chm_set_timing(self._h, 1 if on else 0))
 
@@ -207,4 +216,4 @@ class Scenario:
         t = Timing()
         _check(lib().chm_get_timing(self._h, C.byref(t)))
         return {"family_ms": [float(x) for x in t.family_ms], "total_ms": float(t.total_ms),
-                "partitions": [int(x) for x in t.partitions], "evaluations": [int(x) for x in t.evaluations]}
+                "partitions": [int(x) for x in t.partitions], "evaluations": [int(x) for x in t.evaluations], "feasible": [int(x) for x in t.feasible]}

@@ -64,6 +64,7 @@ struct SearchLaunch {
   uint32_t part_count;          // partitions in this chunk (< 2^idx_bits)
   int32_t idx_bits;             // low bits of the packed key hold the chunk-local partition index
   uint64_t *result;             // device word, atomicMin target: (cost << idx_bits) | local index
+  uint64_t *feasible;           // device counter: partitions that passed the memory filter (atomicAdd)
 };
 
 // launch wrappers (defined in chm_kernels.hip); each returns a hipError_t cast to int

@@ -1,10 +1,499 @@
+// Shape-specialised exhaustive search kernels of libchm for gfx950 (wave64, plain VALU
+// integer work: the path is a max-plus recurrence, not a dense contraction, so no MFMA).
+//
+// One lane owns a run of consecutive partition ranks.  It unranks the first one
+// (combinatorial number system), then walks to each next partition with a branch-free
+// successor step, so unranking is amortised over the run.  Everything a plan needs lives
+// in registers: the cut positions, the per-stage sums (read from one LDS table of prefix
+// sums staged once per workgroup), and the recurrence frontier - ONE value per stage, see
+// the evaluation order described in chm_kernels.hip.  The recurrence is unrolled over the
+// (compile-time) pipeline length, so each cell is exactly one v_max_i32 and one v_add_u32.
+// All values are int32: the host only selects these kernels when its load-time bound shows
+// that no intermediate can reach 2^31, in which case the results equal the int64 ones.
+//
+// Data rerouting: after the base step time of a partition, every valid reroute vector of
+// every stage that lost nodes is scored (extra micro-batches x peer stage time, max over
+// peers); the vectors are read from a rank-ordered table through uniform (scalar) loads.
+//
+// Argmin: per lane a running (cost, run position) with strict less-than, so the lowest
+// index wins inside a lane; then a DPP/shuffle wave reduction of the packed 64-bit key
+// (cost << idx_bits | chunk-local partition index), one LDS step per workgroup and one
+// 64-bit atomicMin per workgroup.
 #include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstring>
+#include <vector>
 
 #include "chm_fast.h"
 
-int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok) { (void)f; (void)h; (void)int32_ok; return 0; }
-int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void *stream) {
-  (void)f; (void)h; (void)a; (void)stream;
-  return 1;
+namespace {
+
+constexpr int BLOCK = 256;
+
+__device__ __forceinline__ int imax32(int a, int b) { return a > b ? a : b; }
+__device__ __forceinline__ int imin32(int a, int b) { return a < b ? a : b; }
+
+// (x*q + 32768) >> 16 for 0 <= x < 2^31, q <= 2^20, result < 2^31
+__device__ __forceinline__ int scale32(int x, uint32_t q) {
+  return (int)(((uint64_t)(uint32_t)x * q + 32768u) >> 16);
 }
-void fast_release(FastState *f) { (void)f; }
+
+// 1F1B pipeline time of N stages, M micro-batches; F, B per stage.  Round t: forward t on
+// all stages in stage order, then backward t-(N-1-s) on stage s.
+template <int N>
+__device__ __forceinline__ int makespan32(const int (&F)[N], const int (&B)[N], int M) {
+  int E[N];
+#pragma unroll
+  for (int s = 0; s < N; ++s) E[s] = 0;
+  if (M >= N - 1) {
+    // warm-up rounds 0..N-2: every stage runs a forward, stages >= N-1-t also a backward
+#pragma unroll
+    for (int t = 0; t < N - 1; ++t) {
+      int x = 0;
+#pragma unroll
+      for (int s = 0; s < N; ++s) {
+        const int old = E[s];
+        E[s] = (s == 0 ? E[s] : imax32(E[s], x)) + F[s];
+        x = E[s];
+        if (s == N - 1) E[s] += B[s];
+        if (s >= 1 && s - 1 >= N - 1 - t) E[s - 1] = imax32(E[s - 1], old) + B[s - 1];
+      }
+    }
+    // steady rounds N-1..M-1: one forward and one backward on every stage
+    for (int t = N - 1; t < M; ++t) {
+      int x = 0;
+#pragma unroll
+      for (int s = 0; s < N; ++s) {
+        const int old = E[s];
+        E[s] = (s == 0 ? E[s] : imax32(E[s], x)) + F[s];
+        x = E[s];
+        if (s == N - 1) E[s] += B[s];
+        if (s >= 1) E[s - 1] = imax32(E[s - 1], old) + B[s - 1];
+      }
+    }
+    // cool-down rounds: backwards only, stage s while s <= N-2-u
+#pragma unroll
+    for (int u = 0; u < N - 1; ++u) {
+#pragma unroll
+      for (int s = 0; s < N - 1 - u; ++s) E[s] = imax32(E[s], E[s + 1]) + B[s];
+    }
+  } else {
+    // fewer micro-batches than warm-up slots: same rounds with (uniform) predicates
+    for (int t = 0; t < M + N - 1; ++t) {
+      const bool fwd = t < M;
+      int x = 0;
+#pragma unroll
+      for (int s = 0; s < N; ++s) {
+        const int old = E[s];
+        if (fwd) {
+          E[s] = imax32(E[s], x) + F[s];
+          x = E[s];
+          if (s == N - 1) E[s] += B[s];
+        }
+        if (s >= 1) {
+          const int j = t - N + s;
+          if (j >= 0 && j < M) E[s - 1] = imax32(E[s - 1], old) + B[s - 1];
+        }
+      }
+    }
+  }
+  return E[0];
+}
+
+template <int N>
+__device__ __forceinline__ int class_time(const FastClass &c, int (&F)[N], int (&B)[N]) {
+  if (!c.unit) {
+#pragma unroll
+    for (int j = 0; j < N; ++j) {
+      F[j] = scale32(F[j], c.q[j]);
+      B[j] = scale32(B[j], c.q[j]);
+    }
+  }
+  return makespan32<N>(F, B, c.M) + c.comm_total;
+}
+
+// min over all reroute vectors of one stage of max_i r_i * w_i.  Rows are stored with a
+// stride of 4 (P <= 4) or 8 dwords and the row count is padded to a multiple of 4 with rows
+// that put every orphaned micro-batch on every peer (never better than a valid row), so four
+// rows are fetched by one wide scalar load and scored back to back.
+template <int P>
+__device__ __forceinline__ uint32_t sweep_vectors(const uint32_t *__restrict__ rows, uint32_t n_rows_padded, const uint32_t (&w)[P]) {
+  constexpr int STRIDE = P <= 4 ? 4 : 8;
+  uint32_t best = 0xffffffffu;
+  for (uint32_t r = 0; r < n_rows_padded; r += 4) {
+    const uint32_t *row = rows + (size_t)r * STRIDE;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      uint32_t pen = 0;
+#pragma unroll
+      for (int i = 0; i < P; ++i) {
+        const uint32_t v = __umul24(row[u * STRIDE + i], w[i]);
+        pen = pen > v ? pen : v;
+      }
+      best = best < pen ? best : pen;
+    }
+  }
+  return best;
+}
+
+__device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
+
+template <int CTRL>
+__device__ __forceinline__ uint64_t dpp_min(uint64_t v) {
+  const int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)v, (int)(uint32_t)v, CTRL, 0xF, 0xF, false);
+  const int hi = __builtin_amdgcn_update_dpp((int)(uint32_t)(v >> 32), (int)(uint32_t)(v >> 32), CTRL, 0xF, 0xF, false);
+  return umin64(v, ((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+
+__device__ __forceinline__ uint64_t wave_min(uint64_t v) {
+  v = dpp_min<0xB1>(v);     // quad_perm [1,0,3,2]
+  v = dpp_min<0x4E>(v);     // quad_perm [2,3,0,1]
+  v = dpp_min<0x141>(v);    // row_half_mirror
+  v = dpp_min<0x140>(v);    // row_mirror
+  v = umin64(v, __shfl_xor(v, 16, 64));
+  v = umin64(v, __shfl_xor(v, 32, 64));
+  return v;
+}
+
+struct FastLaunch {
+  SearchLaunch s;
+  const FastTables *tab;
+  const uint32_t *vecs;
+  uint32_t per_lane;            // consecutive partition ranks per lane
+};
+
+template <int SP, int STRAT>
+__global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
+  constexpr int K = SP - 1;
+  __shared__ int4 T[DEV_MAX_L + 1];            // prefix sums: forward, backward, memory
+  __shared__ uint64_t wave_keys[BLOCK / 64];
+  const DevScenario *__restrict__ scn = a.s.scn;
+  const FastFamily &ff = a.tab->fam[STRAT];
+  const int L = scn->L;
+  for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], 0);
+  __syncthreads();
+
+  const uint32_t lane_id = blockIdx.x * BLOCK + threadIdx.x;
+  const uint64_t run_first = (uint64_t)lane_id * a.per_lane;             // chunk-local
+  const uint32_t run_len = run_first >= a.s.part_count ? 0u
+                           : (uint32_t)(a.s.part_count - run_first < a.per_lane ? a.s.part_count - run_first : a.per_lane);
+
+  // cut positions c[1..K]; c[0] = 0 and c[SP] = L are constants
+  int c[SP + 1];
+  c[0] = 0;
+  c[SP] = L;
+  {
+    uint64_t rem = run_len ? a.s.part_first + run_first : 0;   // idle lanes walk from rank 0: always valid cuts
+    int x = L - 2;
+#pragma unroll
+    for (int i = K; i >= 1; --i) {
+      while (scn->binom[i][x] > rem) --x;
+      c[i] = x + 1;
+      rem -= scn->binom[i][x];
+      --x;
+    }
+  }
+
+  const int cap = (int)scn->cap;
+  uint64_t best_cost = ~0ull;
+  uint32_t best_it = 0;
+  uint32_t n_fit = 0;           // wave-uniform count of partitions that pass the memory filter
+
+  for (uint32_t it = 0; it < a.per_lane; ++it) {
+    // ---- stage sums from the LDS prefix table
+    int fs[SP], bs[SP], ms[SP];
+    {
+      int4 lo = make_int4(0, 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < SP; ++j) {
+        const int4 hi = T[c[j + 1]];
+        fs[j] = hi.x - lo.x;
+        bs[j] = hi.y - lo.y;
+        ms[j] = hi.z - lo.z;
+        lo = hi;
+      }
+    }
+    // ---- memory filter
+    int mmax = 0;
+#pragma unroll
+    for (int j = 0; j < SP; ++j) {
+      const int m = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
+      mmax = imax32(mmax, m);
+    }
+    const bool ok = (mmax <= cap) && (it < run_len);
+    const uint64_t ok_mask = __builtin_amdgcn_ballot_w64(ok);
+    n_fit += (uint32_t)__popcll(ok_mask);
+    if (ok_mask != 0) {
+      int t_step = ff.fixed_step;
+      int missing = 0;
+      if (STRAT != 1) {
+        // weights the stage-j node must fetch: stage size minus what it already holds; prefix
+        // sums are monotone, so the prefix at max(a,a0) is the max of the two prefixes
+        int have = 0;
+        int wl = 0;                      // memory prefix at c[j]
+#pragma unroll
+        for (int j = 0; j < SP; ++j) {
+          const int wh = wl + ms[j];
+          have += imax32(0, imin32(wh, ff.w0[j + 1]) - imax32(wl, ff.w0[j]));
+          wl = wh;
+        }
+        missing = ff.w_total - have;
+      }
+      if (STRAT == 0) {
+        int fd[SP], bd[SP];
+#pragma unroll
+        for (int j = 0; j < SP; ++j) {
+          fd[j] = fs[j] + fs[(j + 1) % SP];
+          bd[j] = bs[j] + bs[(j + 1) % SP];
+        }
+        for (int ci = 0; ci < ff.n_cls; ++ci) {
+          const FastClass &cl = ff.cls[ci];
+          int T_c;
+          if (cl.n == SP) {
+            int F[SP], B[SP];
+#pragma unroll
+            for (int j = 0; j < SP; ++j) { F[j] = fd[j]; B[j] = bd[j]; }
+            T_c = class_time<SP>(cl, F, B);
+          } else if (SP >= 2 && cl.n == SP - 1) {
+            constexpr int N = SP >= 2 ? SP - 1 : 1;
+            int F[N], B[N];
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+              const bool before = j < cl.dead0;
+              F[j] = before ? fd[j] : fd[(j + 1) % SP];
+              B[j] = before ? bd[j] : bd[(j + 1) % SP];
+            }
+            T_c = class_time<N>(cl, F, B);
+          } else {
+            constexpr int N = SP >= 3 ? SP - 2 : 1;
+            int F[N], B[N];
+#pragma unroll
+            for (int j = 0; j < N; ++j) {
+              const bool b0 = j < cl.dead0, b1 = j + 1 < cl.dead1;
+              F[j] = b0 ? fd[j] : (b1 ? fd[(j + 1) % SP] : fd[(j + 2) % SP]);
+              B[j] = b0 ? bd[j] : (b1 ? bd[(j + 1) % SP] : bd[(j + 2) % SP]);
+            }
+            T_c = class_time<N>(cl, F, B);
+          }
+          t_step = imax32(t_step, T_c);
+        }
+      } else {
+        for (int ci = 0; ci < ff.n_cls; ++ci) {
+          const FastClass &cl = ff.cls[ci];
+          int F[SP], B[SP];
+#pragma unroll
+          for (int j = 0; j < SP; ++j) { F[j] = fs[j]; B[j] = bs[j]; }
+          t_step = imax32(t_step, class_time<SP>(cl, F, B));
+          if (STRAT == 1) {
+            int have = 0, wl = 0;
+#pragma unroll
+            for (int j = 0; j < SP; ++j) {
+              const int wh = wl + ms[j];
+              have += imax32(0, imin32(wh, cl.whi[j]) - imax32(wl, cl.wlo[j]));
+              wl = wh;
+            }
+            missing = imax32(missing, ff.w_total - have);
+          }
+        }
+      }
+      if (STRAT == 2) {
+        // every reroute vector of every stage that lost nodes
+        for (int st = 0; st < scn->n_aff; ++st) {
+          const int sa = scn->aff_stage[st];
+          int f_st = fs[0], b_st = bs[0];
+#pragma unroll
+          for (int j = 1; j < SP; ++j) {
+            f_st = sa == j ? fs[j] : f_st;
+            b_st = sa == j ? bs[j] : b_st;
+          }
+          const int p = scn->aff_peers[st];
+          const uint32_t *rows = a.vecs + a.tab->vec_off[st];
+          const uint32_t n_rows = a.tab->vec_rows[st];
+          uint32_t pen = 0;
+#define CHM_SWEEP(P)                                                                            \
+  case P: {                                                                                     \
+    uint32_t w[P];                                                                              \
+    _Pragma("unroll") for (int i = 0; i < P; ++i) {                                             \
+      const uint32_t q = scn->aff_q[st][i];                                                     \
+      w[i] = (uint32_t)(scale32(f_st, q) + scale32(b_st, q));                                   \
+    }                                                                                           \
+    pen = sweep_vectors<P>(rows, n_rows, w);                                                    \
+  } break;
+          switch (p) {
+            CHM_SWEEP(1) CHM_SWEEP(2) CHM_SWEEP(3) CHM_SWEEP(4)
+            CHM_SWEEP(5) CHM_SWEEP(6) CHM_SWEEP(7) CHM_SWEEP(8)
+            default: break;
+          }
+#undef CHM_SWEEP
+          t_step += (int)pen;
+        }
+      }
+      const uint64_t cost = (uint64_t)scn->K * (uint32_t)t_step + (uint64_t)scn->reconf[STRAT] +
+                            (uint64_t)scn->xfer * (uint32_t)missing;
+      if (ok && cost < best_cost) { best_cost = cost; best_it = it; }
+    }
+    // ---- next partition in rank order: bump the lowest cut that has room, reset those below
+    {
+      bool done = false;
+#pragma unroll
+      for (int i = 1; i <= K; ++i) {
+        const bool can = c[i] + 1 < c[i + 1];
+        c[i] = done ? c[i] : (can ? c[i] + 1 : i);
+        done = done || can;
+      }
+    }
+  }
+
+  uint64_t key = best_cost == ~0ull ? CHM_KEY_NONE
+                                    : ((best_cost << a.s.idx_bits) | (run_first + best_it));
+  key = wave_min(key);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0 && n_fit) atomicAdd((unsigned long long *)a.s.feasible, (unsigned long long)n_fit);
+  if (lane == 0) wave_keys[wave] = key;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint64_t k = wave_keys[0];
+#pragma unroll
+    for (int i = 1; i < BLOCK / 64; ++i) k = umin64(k, wave_keys[i]);
+    if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)a.s.result, (unsigned long long)k);
+  }
+}
+
+template <int STRAT>
+int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, hipStream_t st) {
+#define CHM_CASE(SPV)                                                                         \
+  case SPV:                                                                                   \
+    hipLaunchKernelGGL((k_fast_search<SPV, STRAT>), dim3(blocks), dim3(BLOCK), 0, st, a);     \
+    return 0;
+  switch (sp) {
+    CHM_CASE(2) CHM_CASE(3) CHM_CASE(4) CHM_CASE(5) CHM_CASE(6) CHM_CASE(7) CHM_CASE(8)
+    CHM_CASE(15) CHM_CASE(16)
+    default: return 1;
+  }
+#undef CHM_CASE
+}
+
+bool stages_covered(int sp) { return (sp >= 2 && sp <= 8) || sp == 15 || sp == 16; }
+
+}  // namespace
+
+int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok) {
+  for (bool &u : f->usable) u = false;
+  if (!int32_ok) return 0;
+  // 24-bit multiplies in the reroute sweep need peer stage times below 2^24
+  uint32_t q_aff = 65536;
+  for (int a = 0; a < h.n_aff; ++a)
+    for (int i = 0; i < h.aff_peers[a]; ++i) q_aff = std::max(q_aff, h.aff_q[a][i]);
+  const bool w24 = (((h.pf[h.L] + h.pb[h.L]) * (int64_t)q_aff) >> 16) + 2 < (1ll << 24);
+  FastTables *t = new FastTables();
+  memset(t, 0, sizeof(*t));
+  std::vector<uint32_t> vecs;
+  for (int k = 0; k < 3; ++k) {
+    const DevFamily &fam = h.fam[k];
+    if (!fam.n_part || !stages_covered(fam.stages)) continue;
+    if (k == 1 && fam.fixed_step == CHM_INF_COST) continue;
+    bool ok = true;
+    FastFamily &ff = t->fam[k];
+    ff.n_cls = fam.n_cls;
+    ff.fixed_step = (int32_t)fam.fixed_step;
+    ff.w_total = (int32_t)h.pw[h.L];
+    for (int j = 0; j <= h.S; ++j) ff.w0[j] = (int32_t)h.pw[h.p0[j]];
+    for (int ci = 0; ci < fam.n_cls && ok; ++ci) {
+      const DevClass &c = fam.cls[ci];
+      FastClass &fc = ff.cls[ci];
+      fc.n = c.n; fc.M = c.M; fc.comm_total = (int32_t)((c.n - 1) * h.comm);
+      fc.dead0 = fc.dead1 = 1 << 20;
+      fc.unit = 1;
+      for (int j = 0; j < c.n; ++j) {
+        fc.q[j] = c.q[j];
+        if (c.q[j] != 65536u) fc.unit = 0;
+        fc.wlo[j] = (int32_t)h.pw[h.p0[c.host[j]]];
+        fc.whi[j] = (int32_t)h.pw[h.p0[c.host[j] + 1]];
+      }
+      if (k == 0) {
+        // which partition stages the chain skips (at most two, the kernel handles no more)
+        int n_dead = 0, dead[DEV_MAX_S];
+        for (int s = 0, j = 0; s < fam.stages; ++s) {
+          if (j < c.n && c.src[j] == s) ++j;
+          else dead[n_dead++] = s;
+        }
+        if (n_dead > 2 || c.n < 1) ok = false;
+        if (n_dead >= 1) fc.dead0 = dead[0];
+        if (n_dead >= 2) fc.dead1 = dead[1];
+      } else if (c.n != fam.stages) {
+        ok = false;
+      }
+    }
+    if (k == 2 && ok) {
+      for (int a = 0; a < h.n_aff && ok; ++a) {
+        const int p = h.aff_peers[a], total = h.aff_total[a];
+        if (p > FAST_MAX_P || h.aff_R[a] > FAST_MAX_R || !w24) { ok = false; break; }
+        const int cap = h.rcap > 0 ? h.rcap : total;
+        while (vecs.size() % 16) vecs.push_back(0);        // 64-byte aligned rows for the wide scalar loads
+        t->vec_off[a] = (uint32_t)vecs.size();
+        // all valid vectors in lexicographic order (first: as much as possible on the last peers)
+        const int stride = p <= 4 ? 4 : 8;
+        std::vector<int> r(p, 0);
+        int rem = total;
+        uint64_t made = 0;
+        for (int i = p - 1; i >= 0; --i) { r[i] = std::min(rem, cap); rem -= r[i]; }
+        for (uint64_t n = 0; n < h.aff_R[a]; ++n) {
+          for (int i = 0; i < stride; ++i) vecs.push_back(i < p ? (uint32_t)r[i] : 0u);
+          ++made;
+          int suffix = r[p - 1], i = p - 2;
+          while (i >= 0 && (r[i] >= cap || suffix == 0)) { suffix += r[i]; --i; }
+          if (i < 0) break;
+          r[i] += 1;
+          int left = suffix - 1;
+          for (int j = p - 1; j > i; --j) { r[j] = std::min(left, cap); left -= r[j]; }
+        }
+        if (made != h.aff_R[a]) ok = false;   // table and count must agree
+        // padding rows: every orphaned micro-batch on every peer, never better than a valid row
+        while (made % 4) {
+          for (int i = 0; i < stride; ++i) vecs.push_back(i < p ? (uint32_t)total : 0u);
+          ++made;
+        }
+        t->vec_rows[a] = (uint32_t)made;
+      }
+    }
+    f->usable[k] = ok;
+  }
+  if (vecs.empty()) vecs.push_back(0);
+  bool up = hipMalloc((void **)&f->d_tables, sizeof(FastTables)) == hipSuccess;
+  up = up && hipMalloc((void **)&f->d_vecs, vecs.size() * sizeof(uint32_t)) == hipSuccess;
+  up = up && hipMemcpy(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice) == hipSuccess;
+  up = up && hipMemcpy(f->d_vecs, vecs.data(), vecs.size() * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
+  delete t;
+  return up ? 0 : 1;
+}
+
+int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void *stream) {
+  if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return 1;
+  if (a.part_count == 0) return 0;
+  FastLaunch fl;
+  fl.s = a;
+  fl.tab = f->d_tables;
+  fl.vecs = f->d_vecs;
+  // enough lanes to fill 256 CUs with several waves per SIMD, runs long enough to amortise unranking
+  const uint64_t lanes_wanted = 256ull * 4 * 8 * 64;
+  uint64_t per = a.part_count / lanes_wanted;
+  per = std::max<uint64_t>(1, std::min<uint64_t>(per, 32));
+  fl.per_lane = (uint32_t)per;
+  const uint64_t lanes = (a.part_count + per - 1) / per;
+  const uint32_t blocks = (uint32_t)((lanes + BLOCK - 1) / BLOCK);
+  const int sp = h.fam[a.strategy].stages;
+  int rc;
+  if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, (hipStream_t)stream);
+  else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, (hipStream_t)stream);
+  else rc = launch_by_stages<2>(sp, fl, blocks, (hipStream_t)stream);
+  if (rc) return rc;
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+void fast_release(FastState *f) {
+  if (f->d_vecs) (void)hipFree(f->d_vecs);
+  if (f->d_tables) (void)hipFree(f->d_tables);
+  f->d_vecs = nullptr;
+  f->d_tables = nullptr;
+}

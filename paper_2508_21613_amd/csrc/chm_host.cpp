@@ -371,6 +371,8 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hip
   if (slots.empty()) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
   if (slots.size() > MAX_SLOTS) return CHM_ERR_OVERFLOW;
   if (chmk_fill_u64(s->d_slots, (uint32_t)slots.size(), CHM_KEY_NONE, st)) return CHM_ERR_HIP;
+  uint64_t *d_count = s->d_slots + slots.size();          // three feasibility counters right behind the slots
+  if (chmk_fill_u64(d_count, 3, 0, st)) return CHM_ERR_HIP;
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;
   int ev_i = 1;
@@ -384,6 +386,7 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hip
       a.part_count = (uint32_t)std::min<uint64_t>(chunk, j.count - done);
       a.idx_bits = s->idx_bits;
       a.result = s->d_slots + si;
+      a.feasible = d_count + j.strategy;
       int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
       if (rc > 0) rc = chmk_search(a, s->smax, st);
       if (rc) return CHM_ERR_HIP;
@@ -395,8 +398,9 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hip
     (void)fam;
     if (s->timing && ev_i < 7) { HIP_TRY(hipEventRecord(s->ev[ev_i], st)); ev_of[j.strategy] = ev_i; ++ev_i; }
   }
-  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, slots.size() * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (slots.size() + 3) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
+  for (int k = 0; k < 3; ++k) s->last.feasible[k] = s->h_pinned[slots.size() + k];
   if (s->timing) {
     int prev = 0;
     for (int k = 0; k < 3; ++k) {
@@ -449,9 +453,9 @@ extern "C" int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **o
   bool ok = hipGetDevice(&s->device) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_scn, sizeof(DevScenario)) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_comp, s->comp.size() * sizeof(uint64_t)) == hipSuccess;
-  ok = ok && hipMalloc((void **)&s->d_slots, MAX_SLOTS * sizeof(uint64_t)) == hipSuccess;
+  ok = ok && hipMalloc((void **)&s->d_slots, (MAX_SLOTS + 3) * sizeof(uint64_t)) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_winner, DEV_MAX_AFF * sizeof(uint64_t)) == hipSuccess;
-  ok = ok && hipHostMalloc((void **)&s->h_pinned, MAX_SLOTS * sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
+  ok = ok && hipHostMalloc((void **)&s->h_pinned, (MAX_SLOTS + 3) * sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
   ok = ok && hipMemcpy(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice) == hipSuccess;
   ok = ok && hipMemcpy(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice) == hipSuccess;
   for (auto &e : s->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
@@ -554,6 +558,16 @@ extern "C" int chm_set_timing(chm_scenario *s, int32_t on) {
 extern "C" int chm_get_timing(const chm_scenario *s, chm_timing *out) {
   if (!s || !out) return CHM_ERR_ARG;
   *out = s->last;
+  return CHM_OK;
+}
+
+extern "C" int chm_family_classes(const chm_scenario *s, int32_t strategy, int32_t *n, int32_t *length,
+                                  int32_t *micro_batches) {
+  if (!s || !n || !length || !micro_batches || strategy < 0 || strategy > 2) return CHM_ERR_ARG;
+  if (!find_family(s, strategy)) return CHM_ERR_UNRECOVERABLE;
+  const DevFamily &f = s->h.fam[strategy];
+  *n = f.n_cls;
+  for (int i = 0; i < f.n_cls; ++i) { length[i] = f.cls[i].n; micro_batches[i] = f.cls[i].M; }
   return CHM_OK;
 }
 

@@ -345,11 +345,13 @@ __global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
   const DevFamily &fam = scn->fam[a.strategy];
   const uint32_t gid = blockIdx.x * BLOCK + threadIdx.x;
   uint64_t key = CHM_KEY_NONE;
+  bool fits = false;
   if (gid < a.part_count) {
     Cuts<SMAX> cuts{cut_cols, (int)threadIdx.x};
     unrank_partition<SMAX>(scn, fam.stages - 1, a.part_first + gid, cuts);
     int64_t t_step, reconf;
-    if (eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf)) {
+    fits = eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf);
+    if (fits) {
       if (fam.strategy == 2) {
         for (int st = 0; st < scn->n_aff; ++st) {
           int64_t pen; uint64_t rk;
@@ -361,6 +363,8 @@ __global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
       key = (cost << a.idx_bits) | gid;
     }
   }
+  const uint64_t n_fit = __popcll(__ballot(fits));
+  if ((threadIdx.x & 63) == 0 && n_fit) atomicAdd((unsigned long long *)a.feasible, (unsigned long long)n_fit);
   block_min_to_global(key, a.result);
 }
 
