@@ -3,7 +3,12 @@
 #define CHM_FAST_H
 #include "chm_dev.h"
 
-enum { FAST_MAX_P = 8, FAST_MAX_R = 4096 };
+enum {
+  FAST_MAX_P = 8,            // peers per affected stage the specialised sweeps are instantiated for
+  FAST_FUSED_R = 4096,       // up to this many reroute vectors (all stages) the sweep runs inside the search kernel
+  FAST_SPLIT_R = 1 << 23,    // up to this many per stage the vectors are tabulated and swept by a kernel of their own
+  FAST_SUB = 1 << 18         // partitions per pass of the split path (bounds its scratch memory)
+};
 
 // One pipeline class in the form the specialised kernels read (all int32).
 struct FastClass {
@@ -33,16 +38,27 @@ struct FastTables {
 
 struct FastState {
   bool usable[3] = {false, false, false};   // per strategy: a specialised kernel covers this scenario
+  bool split = false;                       // rerouting: vectors swept by k_sweep instead of inside the search kernel
+  FastTables h_tables;
   FastTables *d_tables = nullptr;
   uint32_t *d_vecs = nullptr;
+  // scratch of the split path, FAST_SUB partitions at a time
+  uint64_t *d_base = nullptr;               // cost without penalties, ~0 for a partition that does not fit
+  uint32_t *d_weights = nullptr;            // [partition][affected stage][8] peer stage times
+  uint32_t *d_pen = nullptr;                // [partition][4] best penalty per affected stage
+  uint64_t *d_rowkey = nullptr;             // [4] (penalty << 32 | row) of the winning partition
 };
 
 // Decides per strategy whether a specialised kernel applies and uploads its tables.
 // Returns 0, or non-zero on a failed HIP call.
-int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok);
+int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevScenario *d_scn, const uint64_t *d_comp);
 // Launches the specialised search kernel for one chunk.  Returns 0 on success, a positive
 // value when the strategy is not covered (the caller then uses the generic kernel), or a
 // negative value on a HIP error.
 int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void *stream);
+// Rank of the best reroute vector per affected stage of one partition of the rerouting family,
+// written to d_out[0..n_aff).  Same return convention as fast_search.
+int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t part_rank,
+                        uint64_t *d_out, void *stream);
 void fast_release(FastState *f);
 #endif

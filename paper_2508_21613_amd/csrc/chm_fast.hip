@@ -23,6 +23,7 @@
 
 #include <algorithm>
 #include <cstring>
+#include <type_traits>
 #include <vector>
 
 #include "chm_fast.h"
@@ -161,6 +162,10 @@ struct FastLaunch {
   const FastTables *tab;
   const uint32_t *vecs;
   uint32_t per_lane;            // consecutive partition ranks per lane
+  // split rerouting path: instead of sweeping the reroute vectors itself the kernel stores, per
+  // partition, the cost without penalties and the peer stage times (null: fused sweep)
+  uint64_t *base_out;
+  uint32_t *weights_out;
 };
 
 template <int SP, int STRAT>
@@ -297,7 +302,7 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
           }
         }
       }
-      if (STRAT == 2) {
+      if (STRAT == 2 && a.base_out == nullptr) {
         // every reroute vector of every stage that lost nodes
         for (int st = 0; st < scn->n_aff; ++st) {
           const int sa = scn->aff_stage[st];
@@ -329,10 +334,32 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
           t_step += (int)pen;
         }
       }
+      if (STRAT == 2 && a.base_out != nullptr) {
+        // split path: hand the peer stage times of this partition to the sweep kernel
+        if (ok) {
+          uint32_t *wout = a.weights_out + (run_first + it) * (DEV_MAX_AFF * 8);
+          for (int st = 0; st < scn->n_aff; ++st) {
+            const int sa = scn->aff_stage[st];
+            int f_st = fs[0], b_st = bs[0];
+#pragma unroll
+            for (int j = 1; j < SP; ++j) {
+              f_st = sa == j ? fs[j] : f_st;
+              b_st = sa == j ? bs[j] : b_st;
+            }
+            const int p = scn->aff_peers[st];
+            for (int i = 0; i < p; ++i) {
+              const uint32_t q = scn->aff_q[st][i];
+              wout[st * 8 + i] = (uint32_t)(scale32(f_st, q) + scale32(b_st, q));
+            }
+          }
+        }
+      }
       const uint64_t cost = (uint64_t)scn->K * (uint32_t)t_step + (uint64_t)scn->reconf[STRAT] +
                             (uint64_t)scn->xfer * (uint32_t)missing;
       if (ok && cost < best_cost) { best_cost = cost; best_it = it; }
+      if (STRAT == 2 && a.base_out != nullptr && ok) a.base_out[run_first + it] = cost;
     }
+    if (STRAT == 2 && a.base_out != nullptr && !ok && it < run_len) a.base_out[run_first + it] = ~0ull;
     // ---- next partition in rank order: bump the lowest cut that has room, reset those below
     {
       bool done = false;
@@ -347,6 +374,7 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
 
   uint64_t key = best_cost == ~0ull ? CHM_KEY_NONE
                                     : ((best_cost << a.s.idx_bits) | (run_first + best_it));
+  if (STRAT == 2 && a.base_out != nullptr) key = CHM_KEY_NONE;   // the combine kernel takes the argmin
   key = wave_min(key);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0 && n_fit) atomicAdd((unsigned long long *)a.s.feasible, (unsigned long long)n_fit);
@@ -357,6 +385,142 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
 #pragma unroll
     for (int i = 1; i < BLOCK / 64; ++i) k = umin64(k, wave_keys[i]);
     if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)a.s.result, (unsigned long long)k);
+  }
+}
+
+// ---------------------------------------------------------------------------------------
+// reroute vector table and the split rerouting path
+// ---------------------------------------------------------------------------------------
+// Row r of affected stage a = the reroute vector of rank r, decoded from the count table
+// (count[left][remaining] = vectors of `left` entries summing to `remaining`); rows beyond the
+// valid ones put every orphaned micro-batch on every peer (never better than a valid row).
+__global__ void __launch_bounds__(BLOCK) k_make_rows(const DevScenario *__restrict__ scn, const uint64_t *__restrict__ comp,
+                                                     int a, uint32_t *__restrict__ rows, uint32_t n_rows_padded, int stride) {
+  const uint32_t r = blockIdx.x * BLOCK + threadIdx.x;
+  if (r >= n_rows_padded) return;
+  const int p = scn->aff_peers[a];
+  const int total = scn->aff_total[a];
+  uint32_t *row = rows + (size_t)r * stride;
+  if ((uint64_t)r >= scn->aff_R[a]) {
+    for (int i = 0; i < stride; ++i) row[i] = i < p ? (uint32_t)total : 0u;
+    return;
+  }
+  const uint64_t *tab = comp + scn->comp_off[a];
+  const uint32_t cs = scn->comp_stride[a];
+  uint64_t rank = r;
+  int rem = total;
+  for (int pos = 0; pos < stride; ++pos) {
+    int v = 0;
+    if (pos < p) {
+      const int left = p - 1 - pos;
+      for (;; ++v) {
+        const uint64_t cnt = tab[(uint32_t)left * cs + (uint32_t)(rem - v)];
+        if (rank < cnt) break;
+        rank -= cnt;
+      }
+      rem -= v;
+    }
+    row[pos] = (uint32_t)v;
+  }
+}
+
+// best penalty of one affected stage for 256 partitions (one per lane) over one chunk of rows
+template <int P>
+__global__ void __launch_bounds__(BLOCK) k_sweep(const uint32_t *__restrict__ rows, uint32_t n_rows_padded, uint32_t rows_per_chunk,
+                                                 const uint64_t *__restrict__ base, const uint32_t *__restrict__ weights,
+                                                 uint32_t *__restrict__ pen_best, uint32_t part_count, int a) {
+  constexpr int STRIDE = P <= 4 ? 4 : 8;
+  const uint32_t part = blockIdx.x * BLOCK + threadIdx.x;
+  const bool live = part < part_count && base[part < part_count ? part : 0] != ~0ull;
+  if (__builtin_amdgcn_ballot_w64(live) == 0) return;       // a wave of partitions that do not fit
+  uint32_t w[P];
+#pragma unroll
+  for (int i = 0; i < P; ++i) w[i] = live ? weights[(size_t)part * (DEV_MAX_AFF * 8) + a * 8 + i] : 1u;
+  const uint32_t first = blockIdx.y * rows_per_chunk;
+  const uint32_t n = first >= n_rows_padded ? 0u : (n_rows_padded - first < rows_per_chunk ? n_rows_padded - first : rows_per_chunk);
+  const uint32_t pen = sweep_vectors<P>(rows + (size_t)first * STRIDE, n, w);
+  if (live && n) atomicMin(&pen_best[(size_t)part * DEV_MAX_AFF + a], pen);
+}
+
+// cost = cost without penalties + K * sum of the per-stage best penalties; argmin as usual
+__global__ void __launch_bounds__(BLOCK) k_combine(const uint64_t *__restrict__ base, const uint32_t *__restrict__ pen_best,
+                                                   uint32_t part_count, int n_aff, uint64_t K, uint32_t index_base,
+                                                   int idx_bits, uint64_t *result) {
+  __shared__ uint64_t wave_keys[BLOCK / 64];
+  const uint32_t part = blockIdx.x * BLOCK + threadIdx.x;
+  uint64_t key = CHM_KEY_NONE;
+  if (part < part_count && base[part] != ~0ull) {
+    uint64_t pen = 0;
+    for (int a = 0; a < n_aff; ++a) pen += pen_best[(size_t)part * DEV_MAX_AFF + a];
+    key = ((base[part] + K * pen) << idx_bits) | (uint64_t)(index_base + part);
+  }
+  key = wave_min(key);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) wave_keys[wave] = key;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint64_t k = wave_keys[0];
+#pragma unroll
+    for (int i = 1; i < BLOCK / 64; ++i) k = umin64(k, wave_keys[i]);
+    if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)result, (unsigned long long)k);
+  }
+}
+
+// first row with the smallest penalty for ONE partition (weights at weights[a*8 ..]); one lane per
+// four rows, key = penalty << 32 | row, so the lowest rank wins ties
+template <int P>
+__global__ void __launch_bounds__(BLOCK) k_winner_rows(const uint32_t *__restrict__ rows, uint32_t n_rows_valid,
+                                                       const uint32_t *__restrict__ weights, int a, uint64_t *out) {
+  constexpr int STRIDE = P <= 4 ? 4 : 8;
+  __shared__ uint64_t wave_keys[BLOCK / 64];
+  uint32_t w[P];
+#pragma unroll
+  for (int i = 0; i < P; ++i) w[i] = weights[a * 8 + i];
+  const uint32_t r0 = (blockIdx.x * BLOCK + threadIdx.x) * 4;
+  uint64_t key = CHM_KEY_NONE;
+  for (uint32_t r = r0; r < r0 + 4 && r < n_rows_valid; ++r) {
+    uint32_t pen = 0;
+#pragma unroll
+    for (int i = 0; i < P; ++i) {
+      const uint32_t v = __umul24(rows[(size_t)r * STRIDE + i], w[i]);
+      pen = pen > v ? pen : v;
+    }
+    key = umin64(key, ((uint64_t)pen << 32) | r);
+  }
+  key = wave_min(key);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (lane == 0) wave_keys[wave] = key;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    uint64_t k = wave_keys[0];
+#pragma unroll
+    for (int i = 1; i < BLOCK / 64; ++i) k = umin64(k, wave_keys[i]);
+    if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)&out[a], (unsigned long long)k);
+  }
+}
+
+__global__ void k_fill_u32(uint32_t *p, uint32_t n, uint32_t v) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) p[i] = v;
+}
+
+// out[a] = low 32 bits of key[a] (the winning row = reroute rank)
+__global__ void k_keys_to_ranks(const uint64_t *keys, uint64_t *out, int n) {
+  if ((int)threadIdx.x < n) out[threadIdx.x] = keys[threadIdx.x] & 0xffffffffull;
+}
+
+template <typename Fn>
+int by_peers(int p, Fn fn) {
+  switch (p) {
+    case 1: return fn(std::integral_constant<int, 1>());
+    case 2: return fn(std::integral_constant<int, 2>());
+    case 3: return fn(std::integral_constant<int, 3>());
+    case 4: return fn(std::integral_constant<int, 4>());
+    case 5: return fn(std::integral_constant<int, 5>());
+    case 6: return fn(std::integral_constant<int, 6>());
+    case 7: return fn(std::integral_constant<int, 7>());
+    case 8: return fn(std::integral_constant<int, 8>());
+    default: return 1;
   }
 }
 
@@ -378,17 +542,18 @@ bool stages_covered(int sp) { return (sp >= 2 && sp <= 8) || sp == 15 || sp == 1
 
 }  // namespace
 
-int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok) {
+int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevScenario *d_scn, const uint64_t *d_comp) {
   for (bool &u : f->usable) u = false;
+  f->split = false;
   if (!int32_ok) return 0;
   // 24-bit multiplies in the reroute sweep need peer stage times below 2^24
   uint32_t q_aff = 65536;
   for (int a = 0; a < h.n_aff; ++a)
     for (int i = 0; i < h.aff_peers[a]; ++i) q_aff = std::max(q_aff, h.aff_q[a][i]);
   const bool w24 = (((h.pf[h.L] + h.pb[h.L]) * (int64_t)q_aff) >> 16) + 2 < (1ll << 24);
-  FastTables *t = new FastTables();
+  FastTables *t = &f->h_tables;
   memset(t, 0, sizeof(*t));
-  std::vector<uint32_t> vecs;
+  size_t vec_words = 16;
   for (int k = 0; k < 3; ++k) {
     const DevFamily &fam = h.fam[k];
     if (!fam.n_part || !stages_covered(fam.stages)) continue;
@@ -426,55 +591,54 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok) {
       }
     }
     if (k == 2 && ok) {
+      uint64_t r_sum = 0;
       for (int a = 0; a < h.n_aff && ok; ++a) {
-        const int p = h.aff_peers[a], total = h.aff_total[a];
-        if (p > FAST_MAX_P || h.aff_R[a] > FAST_MAX_R || !w24) { ok = false; break; }
-        const int cap = h.rcap > 0 ? h.rcap : total;
-        while (vecs.size() % 16) vecs.push_back(0);        // 64-byte aligned rows for the wide scalar loads
-        t->vec_off[a] = (uint32_t)vecs.size();
-        // all valid vectors in lexicographic order (first: as much as possible on the last peers)
-        const int stride = p <= 4 ? 4 : 8;
-        std::vector<int> r(p, 0);
-        int rem = total;
-        uint64_t made = 0;
-        for (int i = p - 1; i >= 0; --i) { r[i] = std::min(rem, cap); rem -= r[i]; }
-        for (uint64_t n = 0; n < h.aff_R[a]; ++n) {
-          for (int i = 0; i < stride; ++i) vecs.push_back(i < p ? (uint32_t)r[i] : 0u);
-          ++made;
-          int suffix = r[p - 1], i = p - 2;
-          while (i >= 0 && (r[i] >= cap || suffix == 0)) { suffix += r[i]; --i; }
-          if (i < 0) break;
-          r[i] += 1;
-          int left = suffix - 1;
-          for (int j = p - 1; j > i; --j) { r[j] = std::min(left, cap); left -= r[j]; }
-        }
-        if (made != h.aff_R[a]) ok = false;   // table and count must agree
-        // padding rows: every orphaned micro-batch on every peer, never better than a valid row
-        while (made % 4) {
-          for (int i = 0; i < stride; ++i) vecs.push_back(i < p ? (uint32_t)total : 0u);
-          ++made;
-        }
-        t->vec_rows[a] = (uint32_t)made;
+        if (h.aff_peers[a] > FAST_MAX_P || h.aff_R[a] > FAST_SPLIT_R || !w24) { ok = false; break; }
+        const int stride = h.aff_peers[a] <= 4 ? 4 : 8;
+        const uint32_t padded = (uint32_t)((h.aff_R[a] + 3) / 4 * 4);
+        // stages with the same peer count, orphan count and cap share one table
+        int same = -1;
+        for (int b = 0; b < a; ++b)
+          if (h.aff_peers[b] == h.aff_peers[a] && h.aff_total[b] == h.aff_total[a]) same = b;
+        t->vec_rows[a] = padded;
+        if (same >= 0) t->vec_off[a] = t->vec_off[same];
+        else { t->vec_off[a] = (uint32_t)vec_words; vec_words += ((size_t)padded * stride + 15) / 16 * 16; }
+        r_sum += h.aff_R[a];
       }
+      f->split = ok && r_sum > FAST_FUSED_R;
     }
     f->usable[k] = ok;
   }
-  if (vecs.empty()) vecs.push_back(0);
   bool up = hipMalloc((void **)&f->d_tables, sizeof(FastTables)) == hipSuccess;
-  up = up && hipMalloc((void **)&f->d_vecs, vecs.size() * sizeof(uint32_t)) == hipSuccess;
+  up = up && hipMalloc((void **)&f->d_vecs, vec_words * sizeof(uint32_t)) == hipSuccess;
   up = up && hipMemcpy(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice) == hipSuccess;
-  up = up && hipMemcpy(f->d_vecs, vecs.data(), vecs.size() * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
-  delete t;
+  if (up && f->usable[2]) {
+    for (int a = 0; a < h.n_aff; ++a) {
+      const int stride = h.aff_peers[a] <= 4 ? 4 : 8;
+      hipLaunchKernelGGL(k_make_rows, dim3((t->vec_rows[a] + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, nullptr, d_scn, d_comp, a,
+                         f->d_vecs + t->vec_off[a], t->vec_rows[a], stride);
+    }
+    up = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+  }
+  if (up && f->split) {
+    up = up && hipMalloc((void **)&f->d_base, (size_t)FAST_SUB * sizeof(uint64_t)) == hipSuccess;
+    up = up && hipMalloc((void **)&f->d_weights, (size_t)FAST_SUB * DEV_MAX_AFF * 8 * sizeof(uint32_t)) == hipSuccess;
+    up = up && hipMalloc((void **)&f->d_pen, (size_t)FAST_SUB * DEV_MAX_AFF * sizeof(uint32_t)) == hipSuccess;
+  }
+  if (up && f->usable[2]) up = hipMalloc((void **)&f->d_rowkey, DEV_MAX_AFF * sizeof(uint64_t)) == hipSuccess;
   return up ? 0 : 1;
 }
 
-int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void *stream) {
-  if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return 1;
-  if (a.part_count == 0) return 0;
+namespace {
+
+int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uint64_t *base_out, uint32_t *weights_out,
+                  hipStream_t st) {
   FastLaunch fl;
   fl.s = a;
   fl.tab = f->d_tables;
   fl.vecs = f->d_vecs;
+  fl.base_out = base_out;
+  fl.weights_out = weights_out;
   // enough lanes to fill 256 CUs with several waves per SIMD, runs long enough to amortise unranking
   const uint64_t lanes_wanted = 256ull * 4 * 8 * 64;
   uint64_t per = a.part_count / lanes_wanted;
@@ -484,16 +648,98 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
   const uint32_t blocks = (uint32_t)((lanes + BLOCK - 1) / BLOCK);
   const int sp = h.fam[a.strategy].stages;
   int rc;
-  if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, (hipStream_t)stream);
-  else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, (hipStream_t)stream);
-  else rc = launch_by_stages<2>(sp, fl, blocks, (hipStream_t)stream);
+  if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, st);
+  else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, st);
+  else rc = launch_by_stages<2>(sp, fl, blocks, st);
   if (rc) return rc;
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
+}  // namespace
+
+int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void *stream) {
+  if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return 1;
+  if (a.part_count == 0) return 0;
+  hipStream_t st = (hipStream_t)stream;
+  if (!(a.strategy == 2 && f->split)) return launch_search(f, h, a, nullptr, nullptr, st);
+  // split rerouting path, FAST_SUB partitions per pass: base costs and peer stage times, then one
+  // sweep per affected stage over (partition blocks x row chunks), then the combine / argmin
+  const FastTables &t = f->h_tables;
+  for (uint32_t done = 0; done < a.part_count; done += FAST_SUB) {
+    SearchLaunch sub = a;
+    sub.part_first = a.part_first + done;
+    sub.part_count = std::min<uint32_t>(FAST_SUB, a.part_count - done);
+    int rc = launch_search(f, h, sub, f->d_base, f->d_weights, st);
+    if (rc) return rc;
+    const uint32_t n_pen = sub.part_count * DEV_MAX_AFF;
+    hipLaunchKernelGGL(k_fill_u32, dim3((n_pen + 255) / 256), dim3(256), 0, st, f->d_pen, n_pen, 0xffffffffu);
+    const uint32_t bx = (sub.part_count + BLOCK - 1) / BLOCK;
+    for (int s = 0; s < h.n_aff; ++s) {
+      const uint32_t n_rows = t.vec_rows[s];
+      // about 8192 workgroups in total, chunks of at least 1024 rows, multiples of 4
+      uint32_t chunks = std::max<uint32_t>(1, std::min<uint32_t>(8192 / bx + 1, n_rows / 1024 + 1));
+      chunks = std::min<uint32_t>(chunks, 65535);
+      uint32_t per_chunk = (n_rows + chunks - 1) / chunks;
+      per_chunk = (per_chunk + 3) / 4 * 4;
+      chunks = (n_rows + per_chunk - 1) / per_chunk;
+      const uint32_t *rows = f->d_vecs + t.vec_off[s];
+      rc = by_peers(h.aff_peers[s], [&](auto tag) {
+        constexpr int P = decltype(tag)::value;
+        hipLaunchKernelGGL((k_sweep<P>), dim3(bx, chunks), dim3(BLOCK), 0, st, rows, n_rows, per_chunk, f->d_base,
+                           f->d_weights, f->d_pen, sub.part_count, s);
+        return 0;
+      });
+      if (rc) return -1;
+    }
+    hipLaunchKernelGGL(k_combine, dim3(bx), dim3(BLOCK), 0, st, f->d_base, f->d_pen, sub.part_count, h.n_aff,
+                       (uint64_t)h.K, done, a.idx_bits, a.result);
+    if (hipGetLastError() != hipSuccess) return -1;
+  }
+  return 0;
+}
+
+int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t part_rank,
+                        uint64_t *d_out, void *stream) {
+  (void)d_scn;
+  if (!f->usable[2] || !f->split || h.n_aff == 0) return 1;
+  hipStream_t st = (hipStream_t)stream;
+  // peer stage times of the winning partition (one-partition pass of the search kernel in split mode)
+  SearchLaunch one;
+  memset(&one, 0, sizeof(one));
+  one.strategy = 2;
+  one.part_first = part_rank;
+  one.part_count = 1;
+  one.idx_bits = 1;
+  one.result = f->d_rowkey;          // not written in split mode
+  one.feasible = f->d_rowkey;        // counter target: overwritten by the fill below
+  one.scn = d_scn;
+  int rc = launch_search(f, h, one, f->d_base, f->d_weights, st);
+  if (rc) return rc;
+  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, (uint32_t *)f->d_rowkey, 2 * DEV_MAX_AFF, 0xffffffffu);
+  const FastTables &t = f->h_tables;
+  for (int s = 0; s < h.n_aff; ++s) {
+    const uint32_t n_valid = (uint32_t)h.aff_R[s];
+    const uint32_t blocks = ((n_valid + 3) / 4 + BLOCK - 1) / BLOCK;
+    const uint32_t *rows = f->d_vecs + t.vec_off[s];
+    rc = by_peers(h.aff_peers[s], [&](auto tag) {
+      constexpr int P = decltype(tag)::value;
+      hipLaunchKernelGGL((k_winner_rows<P>), dim3(blocks), dim3(BLOCK), 0, st, rows, n_valid, f->d_weights, s, f->d_rowkey);
+      return 0;
+    });
+    if (rc) return -1;
+  }
+  hipLaunchKernelGGL(k_keys_to_ranks, dim3(1), dim3(64), 0, st, f->d_rowkey, d_out, h.n_aff);
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
 void fast_release(FastState *f) {
+  if (f->d_rowkey) (void)hipFree(f->d_rowkey);
+  if (f->d_pen) (void)hipFree(f->d_pen);
+  if (f->d_weights) (void)hipFree(f->d_weights);
+  if (f->d_base) (void)hipFree(f->d_base);
   if (f->d_vecs) (void)hipFree(f->d_vecs);
   if (f->d_tables) (void)hipFree(f->d_tables);
+  f->d_rowkey = nullptr; f->d_pen = nullptr; f->d_weights = nullptr; f->d_base = nullptr;
   f->d_vecs = nullptr;
   f->d_tables = nullptr;
 }

@@ -430,7 +430,9 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hip
   if (best_strategy < 0) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
   uint64_t rr[DEV_MAX_AFF] = {};
   if (best_strategy == 2 && s->h.n_aff > 0) {
-    if (chmk_reroute_winner(s->d_scn, s->d_comp, best_part, s->d_winner, s->smax, st)) return CHM_ERR_HIP;
+    int rc = fast_reroute_winner(&s->fast, s->h, s->d_scn, best_part, s->d_winner, st);
+    if (rc > 0) rc = chmk_reroute_winner(s->d_scn, s->d_comp, best_part, s->d_winner, s->smax, st);
+    if (rc) return CHM_ERR_HIP;
     HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_winner, DEV_MAX_AFF * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     for (int a = 0; a < s->h.n_aff; ++a) rr[a] = s->h_pinned[a];
@@ -464,7 +466,7 @@ extern "C" int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **o
     ok = chmk_fixed_pipelines(s->d_scn, nullptr) == 0 && hipDeviceSynchronize() == hipSuccess;
     ok = ok && hipMemcpy(&s->h.fam[1].fixed_step, &s->d_scn->fam[1].fixed_step, sizeof(int64_t), hipMemcpyDeviceToHost) == hipSuccess;
   }
-  ok = ok && fast_prepare(&s->fast, s->h, s->int32_ok) == 0;
+  ok = ok && fast_prepare(&s->fast, s->h, s->int32_ok, s->d_scn, s->d_comp) == 0;
   if (!ok) { release(s); return CHM_ERR_HIP; }
   *out = s;
   return CHM_OK;
