@@ -128,6 +128,20 @@ int chm_score_plans(chm_scenario *s, uint64_t first, uint64_t count, int64_t *d_
 int chm_score_ranks(chm_scenario *s, int32_t strategy, const uint64_t *d_part_ranks, uint64_t n,
                     int64_t *d_costs, void *hip_stream);
 
+/* Partition ranks of n explicit partitions of one strategy: d_cuts (device, uint8) holds n rows of
+ * (stages-1) cut positions c_1 < ... < c_k; d_part_ranks (device) receives the ranks, UINT64_MAX
+ * for a row that is not strictly increasing within 1..L-1.  Asynchronous on hip_stream. */
+int chm_rank_partitions(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts, uint64_t n,
+                        uint64_t *d_part_ranks, void *hip_stream);
+
+/* Argmin over n explicit partitions of one strategy (partition ranks in device memory): each
+ * partition is scored as in chm_search_best (for data rerouting with every reroute vector).
+ * *position (nullable) receives the first list position that holds the minimum, d_costs
+ * (nullable, device) the cost of every list entry (CHM_INFEASIBLE for a partition that does
+ * not fit or a rank outside the family).  Synchronises hip_stream.  Errors as chm_search_best. */
+int chm_search_ranks(chm_scenario *s, int32_t strategy, const uint64_t *d_part_ranks, uint64_t n,
+                     int64_t *d_costs, chm_best *out, uint64_t *position, void *hip_stream);
+
 /* Exhaustive argmin over the strategies in strategy_mask (bit k = strategy k): every
  * partition of every selected family is scored on the device; for data rerouting every
  * reroute vector of every stage that lost nodes is scored (the penalty is a sum of

@@ -106,6 +106,10 @@ extern "C" uint64_t orc_partition_rank(int32_t k, const uint8_t *cuts) {
   return r;
 }
 
+extern "C" void orc_partition_rank_batch(int32_t k, const uint8_t *cuts, uint64_t n, uint64_t *ranks) {
+  for (uint64_t i = 0; i < n; ++i) ranks[i] = orc_partition_rank(k, cuts + i * (uint64_t)k);
+}
+
 extern "C" int orc_partition_unrank(int32_t L, int32_t k, uint64_t rank, uint8_t *cuts) {
   if (L < 1 || L > ORC_MAX_L || k < 0 || k > L - 1) return ORC_ERR_ARG;
   if (rank >= orc_binom(L - 1, k)) return ORC_ERR_RANGE;

@@ -66,6 +66,7 @@ typedef struct {
 /* --- building blocks, exposed so that tests can pin each one on its own ---------------- */
 uint64_t orc_binom(int32_t n, int32_t k);                       /* saturates at UINT64_MAX */
 uint64_t orc_partition_rank(int32_t k, const uint8_t *cuts);
+void     orc_partition_rank_batch(int32_t k, const uint8_t *cuts, uint64_t n, uint64_t *ranks);  /* cuts[n][k] */
 int      orc_partition_unrank(int32_t L, int32_t k, uint64_t rank, uint8_t *cuts);
 uint64_t orc_reroute_count(int32_t parts, int32_t total, int32_t cap);
 int      orc_reroute_unrank(int32_t parts, int32_t total, int32_t cap, uint64_t rank, uint16_t *r);

@@ -66,6 +66,7 @@ def lib():
         sig = {
             "orc_binom": (C.c_uint64, [C.c_int32, C.c_int32]),
             "orc_partition_rank": (C.c_uint64, [C.c_int32, u8p]),
+            "orc_partition_rank_batch": (None, [C.c_int32, u8p, C.c_uint64, u64p]),
             "orc_partition_unrank": (C.c_int, [C.c_int32, C.c_int32, C.c_uint64, u8p]),
             "orc_reroute_count": (C.c_uint64, [C.c_int32, C.c_int32, C.c_int32]),
             "orc_reroute_unrank": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_uint64, u16p]),
@@ -110,6 +111,14 @@ def binom(n, k):
 def partition_rank(cuts):
     a = np.ascontiguousarray(cuts, dtype=np.uint8)
     return int(lib().orc_partition_rank(len(a), _ptr(a, C.c_uint8)))
+
+
+def partition_rank_batch(cuts):
+    """ranks of an (n, k) uint8 array of cut positions"""
+    a = np.ascontiguousarray(cuts, dtype=np.uint8)
+    out = np.empty(a.shape[0], dtype=np.uint64)
+    lib().orc_partition_rank_batch(a.shape[1], _ptr(a, C.c_uint8), a.shape[0], _ptr(out, C.c_uint64))
+    return out
 
 
 def partition_unrank(L, k, rank):

@@ -65,6 +65,11 @@ struct SearchLaunch {
   int32_t idx_bits;             // low bits of the packed key hold the chunk-local partition index
   uint64_t *result;             // device word, atomicMin target: (cost << idx_bits) | local index
   uint64_t *feasible;           // device counter: partitions that passed the memory filter (atomicAdd)
+  // list mode: partition i of the chunk is ranks[i] (any order, a rank outside the family counts as
+  // infeasible) instead of part_first + i; part_first is then ignored
+  const uint64_t *ranks;
+  // when set, cost i of the chunk (INT64_MAX if infeasible) is also stored to costs_out[i]
+  int64_t *costs_out;
 };
 
 // launch wrappers (defined in chm_kernels.hip); each returns a hipError_t cast to int
@@ -75,6 +80,7 @@ int chmk_score(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strateg
 int chmk_score_ranks(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy,
                      const uint64_t *d_ranks, uint64_t n, int64_t *d_costs, int32_t smax, void *stream);
 int chmk_search(const SearchLaunch &a, int32_t smax, void *stream);
+int chmk_rank_cuts(const DevScenario *d_scn, int k, const uint8_t *d_cuts, uint64_t n, uint64_t *d_ranks, void *stream);
 // re-evaluates one partition of the rerouting family and writes, per affected stage, the
 // rank of its best reroute vector to d_out[0..n_aff)
 int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank,

@@ -188,8 +188,14 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
   int c[SP + 1];
   c[0] = 0;
   c[SP] = L;
+  bool listed_ok = true;
   {
     uint64_t rem = run_len ? a.s.part_first + run_first : 0;   // idle lanes walk from rank 0: always valid cuts
+    if (a.s.ranks != nullptr && run_len) {                       // list mode (one partition per lane)
+      rem = a.s.ranks[run_first];
+      listed_ok = rem < scn->fam[STRAT].n_part;
+      if (!listed_ok) rem = 0;
+    }
     int x = L - 2;
 #pragma unroll
     for (int i = K; i >= 1; --i) {
@@ -226,7 +232,8 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
       const int m = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
       mmax = imax32(mmax, m);
     }
-    const bool ok = (mmax <= cap) && (it < run_len);
+    const bool ok = (mmax <= cap) && (it < run_len) && listed_ok;
+    uint64_t cost = (uint64_t)CHM_INF_COST;
     const uint64_t ok_mask = __builtin_amdgcn_ballot_w64(ok);
     n_fit += (uint32_t)__popcll(ok_mask);
     if (ok_mask != 0) {
@@ -354,12 +361,12 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
           }
         }
       }
-      const uint64_t cost = (uint64_t)scn->K * (uint32_t)t_step + (uint64_t)scn->reconf[STRAT] +
-                            (uint64_t)scn->xfer * (uint32_t)missing;
+      cost = (uint64_t)scn->K * (uint32_t)t_step + (uint64_t)scn->reconf[STRAT] + (uint64_t)scn->xfer * (uint32_t)missing;
       if (ok && cost < best_cost) { best_cost = cost; best_it = it; }
       if (STRAT == 2 && a.base_out != nullptr && ok) a.base_out[run_first + it] = cost;
     }
     if (STRAT == 2 && a.base_out != nullptr && !ok && it < run_len) a.base_out[run_first + it] = ~0ull;
+    if (a.s.costs_out != nullptr && it < run_len) a.s.costs_out[run_first + it] = ok ? (int64_t)cost : CHM_INF_COST;
     // ---- next partition in rank order: bump the lowest cut that has room, reset those below
     {
       bool done = false;
@@ -643,6 +650,7 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   const uint64_t lanes_wanted = 256ull * 4 * 8 * 64;
   uint64_t per = a.part_count / lanes_wanted;
   per = std::max<uint64_t>(1, std::min<uint64_t>(per, 32));
+  if (a.ranks != nullptr || a.costs_out != nullptr) per = 1;     // one partition per lane: coalesced cost stores
   fl.per_lane = (uint32_t)per;
   const uint64_t lanes = (a.part_count + per - 1) / per;
   const uint32_t blocks = (uint32_t)((lanes + BLOCK - 1) / BLOCK);
@@ -662,6 +670,7 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
   if (a.part_count == 0) return 0;
   hipStream_t st = (hipStream_t)stream;
   if (!(a.strategy == 2 && f->split)) return launch_search(f, h, a, nullptr, nullptr, st);
+  if (a.ranks != nullptr || a.costs_out != nullptr) return 1;   // the generic kernel handles lists for this shape
   // split rerouting path, FAST_SUB partitions per pass: base costs and peer stage times, then one
   // sweep per affected stage over (partition blocks x row chunks), then the combine / argmin
   const FastTables &t = f->h_tables;
@@ -710,6 +719,8 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
   one.part_first = part_rank;
   one.part_count = 1;
   one.idx_bits = 1;
+  one.ranks = nullptr;
+  one.costs_out = nullptr;
   one.result = f->d_rowkey;          // not written in split mode
   one.feasible = f->d_rowkey;        // counter target: overwritten by the fill below
   one.scn = d_scn;

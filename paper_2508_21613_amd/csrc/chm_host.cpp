@@ -358,17 +358,25 @@ void nothing_found(chm_best *out) {
   out->cost = CHM_INFEASIBLE;
 }
 
-struct Job { int strategy; uint64_t first, count; };
+// a range of partition ranks [first, first+count) of one strategy, or (ranks != null) a list of
+// `count` partition ranks in device memory; costs (nullable, device) receives one cost per entry
+struct Job { int strategy; uint64_t first, count; const uint64_t *ranks; int64_t *costs; };
 
 // Runs the argmin over the given partition ranges (ascending plan index order).
-int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hipStream_t st) {
+// With out == null the kernels are only launched (asynchronous scoring into the jobs' cost buffers).
+int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint64_t *position, hipStream_t st) {
   HIP_TRY(hipSetDevice(s->device));
   s->last = chm_timing();
   std::vector<Slot> slots;
   const uint64_t chunk = 1ull << s->idx_bits;
   for (const Job &j : jobs)
-    for (uint64_t done = 0; done < j.count; done += chunk) slots.push_back({j.strategy, j.first + done, s->idx_bits});
-  if (slots.empty()) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
+    for (uint64_t done = 0; done < j.count; done += chunk)
+      slots.push_back({j.strategy, (j.ranks ? 0 : j.first) + done, s->idx_bits});
+  if (slots.empty()) {
+    if (!out) return CHM_OK;
+    nothing_found(out);
+    return CHM_ERR_NO_FEASIBLE;
+  }
   if (slots.size() > MAX_SLOTS) return CHM_ERR_OVERFLOW;
   if (chmk_fill_u64(s->d_slots, (uint32_t)slots.size(), CHM_KEY_NONE, st)) return CHM_ERR_HIP;
   uint64_t *d_count = s->d_slots + slots.size();          // three feasibility counters right behind the slots
@@ -387,6 +395,8 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hip
       a.idx_bits = s->idx_bits;
       a.result = s->d_slots + si;
       a.feasible = d_count + j.strategy;
+      a.ranks = j.ranks ? j.ranks + done : nullptr;
+      a.costs_out = j.costs ? j.costs + done : nullptr;
       int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
       if (rc > 0) rc = chmk_search(a, s->smax, st);
       if (rc) return CHM_ERR_HIP;
@@ -398,6 +408,7 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hip
     (void)fam;
     if (s->timing && ev_i < 7) { HIP_TRY(hipEventRecord(s->ev[ev_i], st)); ev_of[j.strategy] = ev_i; ++ev_i; }
   }
+  if (!out) return CHM_OK;
   HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (slots.size() + 3) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   for (int k = 0; k < 3; ++k) s->last.feasible[k] = s->h_pinned[slots.size() + k];
@@ -417,6 +428,11 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hip
   int64_t best_cost = CHM_INFEASIBLE;
   int best_strategy = -1;
   uint64_t best_part = 0;
+  const uint64_t *best_list = nullptr;
+  size_t slot_i = 0;
+  std::vector<const uint64_t *> slot_list;
+  for (const Job &j : jobs)
+    for (uint64_t done = 0; done < j.count; done += chunk) slot_list.push_back(j.ranks);
   for (size_t i = 0; i < slots.size(); ++i) {
     const uint64_t key = s->h_pinned[i];
     if (key == CHM_KEY_NONE) continue;
@@ -425,9 +441,18 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, hip
       best_cost = cost;
       best_strategy = slots[i].strategy;
       best_part = slots[i].part_first + (key & ((1ull << slots[i].idx_bits) - 1));
+      best_list = slot_list[i];
     }
   }
+  (void)slot_i;
   if (best_strategy < 0) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
+  if (best_list) {
+    // list job: best_part is a position in the caller's list; fetch the partition rank behind it
+    if (position) *position = best_part;
+    HIP_TRY(hipMemcpyAsync(s->h_pinned, best_list + best_part, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    HIP_TRY(hipStreamSynchronize(st));
+    best_part = s->h_pinned[0];
+  }
   uint64_t rr[DEV_MAX_AFF] = {};
   if (best_strategy == 2 && s->h.n_aff > 0) {
     int rc = fast_reroute_winner(&s->fast, s->h, s->d_scn, best_part, s->d_winner, st);
@@ -488,6 +513,14 @@ extern "C" int chm_score_plans(chm_scenario *s, uint64_t first, uint64_t count, 
     const uint64_t fb = f.offset, fe = f.offset + f.n_part * f.n_reroute;
     const uint64_t a = std::max(lo, fb), b = std::min(hi, fe);
     if (a >= b) continue;
+    if (f.n_reroute == 1) {
+      // one plan per partition: the search kernels score the range and store every cost
+      std::vector<Job> jobs;
+      jobs.push_back({f.strategy, a - fb, b - a, nullptr, d_costs + (a - first)});
+      const int rc = run_search(s, jobs, nullptr, nullptr, (hipStream_t)hip_stream);
+      if (rc) return rc;
+      continue;
+    }
     // split very long ranges so that the grid stays within 2^31 blocks
     for (uint64_t p = a; p < b;) {
       const uint64_t n = std::min<uint64_t>(b - p, 1ull << 36);
@@ -505,12 +538,31 @@ extern "C" int chm_score_ranks(chm_scenario *s, int32_t strategy, const uint64_t
   if (!f) return CHM_ERR_UNRECOVERABLE;
   if (f->n_reroute != 1) return CHM_ERR_ARG;
   HIP_TRY(hipSetDevice(s->device));
-  for (uint64_t p = 0; p < n;) {
-    const uint64_t m = std::min<uint64_t>(n - p, 1ull << 36);
-    if (chmk_score_ranks(s->d_scn, s->d_comp, strategy, d_part_ranks + p, m, d_costs + p, s->smax, hip_stream)) return CHM_ERR_HIP;
-    p += m;
-  }
+  if (n == 0) return CHM_OK;
+  std::vector<Job> jobs;
+  jobs.push_back({strategy, 0, n, d_part_ranks, d_costs});
+  return run_search(s, jobs, nullptr, nullptr, (hipStream_t)hip_stream);
+}
+
+extern "C" int chm_rank_partitions(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts, uint64_t n,
+                                   uint64_t *d_part_ranks, void *hip_stream) {
+  if (!s || strategy < 0 || strategy > 2 || (n && (!d_cuts || !d_part_ranks))) return CHM_ERR_ARG;
+  const chm_family *f = find_family(s, strategy);
+  if (!f) return CHM_ERR_UNRECOVERABLE;
+  HIP_TRY(hipSetDevice(s->device));
+  if (chmk_rank_cuts(s->d_scn, f->stages - 1, d_cuts, n, d_part_ranks, hip_stream)) return CHM_ERR_HIP;
   return CHM_OK;
+}
+
+extern "C" int chm_search_ranks(chm_scenario *s, int32_t strategy, const uint64_t *d_part_ranks, uint64_t n,
+                                int64_t *d_costs, chm_best *out, uint64_t *position, void *hip_stream) {
+  if (!s || !out || strategy < 0 || strategy > 2 || (n && !d_part_ranks)) return CHM_ERR_ARG;
+  const chm_family *f = find_family(s, strategy);
+  if (!f) { nothing_found(out); return CHM_ERR_UNRECOVERABLE; }
+  if (position) *position = UINT64_MAX;
+  std::vector<Job> jobs;
+  if (n) jobs.push_back({strategy, 0, n, d_part_ranks, d_costs});
+  return run_search(s, jobs, out, position, (hipStream_t)hip_stream);
 }
 
 extern "C" int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream) {
@@ -518,10 +570,10 @@ extern "C" int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best
   std::vector<Job> jobs;
   for (int i = 0; i < s->space.n_families; ++i) {
     const chm_family &f = s->space.fam[i];
-    if (strategy_mask & (1u << f.strategy)) jobs.push_back({f.strategy, 0, f.n_part});
+    if (strategy_mask & (1u << f.strategy)) jobs.push_back({f.strategy, 0, f.n_part, nullptr, nullptr});
   }
   if (jobs.empty()) { nothing_found(out); return CHM_ERR_UNRECOVERABLE; }
-  return run_search(s, jobs, out, (hipStream_t)hip_stream);
+  return run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream);
 }
 
 extern "C" int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part_first, uint64_t part_count,
@@ -531,8 +583,8 @@ extern "C" int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part
   if (!f) { nothing_found(out); return CHM_ERR_UNRECOVERABLE; }
   if (part_first > f->n_part || part_count > f->n_part - part_first) return CHM_ERR_RANGE;
   std::vector<Job> jobs;
-  jobs.push_back({strategy, part_first, part_count});
-  return run_search(s, jobs, out, (hipStream_t)hip_stream);
+  jobs.push_back({strategy, part_first, part_count, nullptr, nullptr});
+  return run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream);
 }
 
 extern "C" int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out) {

@@ -348,9 +348,13 @@ __global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
   bool fits = false;
   if (gid < a.part_count) {
     Cuts<SMAX> cuts{cut_cols, (int)threadIdx.x};
-    unrank_partition<SMAX>(scn, fam.stages - 1, a.part_first + gid, cuts);
-    int64_t t_step, reconf;
-    fits = eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf);
+    const uint64_t part = a.ranks ? a.ranks[gid] : a.part_first + gid;
+    int64_t t_step = 0, reconf = 0;
+    if (part < fam.n_part) {
+      unrank_partition<SMAX>(scn, fam.stages - 1, part, cuts);
+      fits = eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf);
+    }
+    if (a.costs_out && !fits) a.costs_out[gid] = CHM_INF_COST;
     if (fits) {
       if (fam.strategy == 2) {
         for (int st = 0; st < scn->n_aff; ++st) {
@@ -361,6 +365,7 @@ __global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
       }
       const uint64_t cost = (uint64_t)(scn->K * t_step + reconf);
       key = (cost << a.idx_bits) | gid;
+      if (a.costs_out) a.costs_out[gid] = (int64_t)cost;
     }
   }
   const uint64_t n_fit = __popcll(__ballot(fits));
@@ -384,6 +389,25 @@ __global__ void __launch_bounds__(BLOCK) k_reroute_winner(const DevScenario *scn
   out[a] = rk;
 }
 
+// partition rank of explicit cut positions (inverse of unrank_partition); cuts[n][k] row-major.
+// Cuts that are not strictly increasing within 1..L-1 give UINT64_MAX.
+__global__ void __launch_bounds__(BLOCK) k_rank_cuts(const DevScenario *scn, int k, const uint8_t *cuts, uint64_t n,
+                                                     uint64_t *ranks) {
+  const uint64_t gid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+  if (gid >= n) return;
+  const uint8_t *c = cuts + gid * (uint64_t)k;
+  uint64_t r = 0;
+  int prev = 0;
+  bool valid = true;
+  for (int i = 1; i <= k; ++i) {
+    const int ci = c[i - 1];
+    valid = valid && ci > prev && ci <= scn->L - 1;
+    if (valid) r += scn->binom[i][ci - 1];
+    prev = ci;
+  }
+  ranks[gid] = valid ? r : UINT64_MAX;
+}
+
 template <typename Fn>
 int dispatch_smax(int smax, Fn fn) {
   if (smax <= 4) return fn(std::integral_constant<int, 4>());
@@ -401,6 +425,14 @@ int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream) {
 
 int chmk_fixed_pipelines(DevScenario *d_scn, void *stream) {
   hipLaunchKernelGGL(k_fixed_pipelines, dim3(1), dim3(64), 0, (hipStream_t)stream, d_scn);
+  return (int)hipGetLastError();
+}
+
+int chmk_rank_cuts(const DevScenario *d_scn, int k, const uint8_t *d_cuts, uint64_t n, uint64_t *d_ranks, void *stream) {
+  if (n == 0) return 0;
+  const uint64_t blocks = (n + BLOCK - 1) / BLOCK;
+  if (blocks > 0x7fffffffull) return (int)hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_rank_cuts, dim3((uint32_t)blocks), dim3(BLOCK), 0, (hipStream_t)stream, d_scn, k, d_cuts, n, d_ranks);
   return (int)hipGetLastError();
 }
 

@@ -103,12 +103,19 @@ def config3(seed=BASE_SEED + 3):
                     speed=speed_factors(seed, 8, 4), reroute_cap=16)
 
 
-def config4(seed=BASE_SEED + 4):
+# Under the stated cap of 6000 MiB, 99.9 % of uniformly drawn 16-stage partitions of 96 layers have a
+# stage above the cap (the largest of 16 random stages is about 11 layers).  The stated property
+# "about 30 % memory-infeasible" holds at the 70th percentile of the largest stage instead:
+CONFIG4_CAP_30PCT = 12400
+
+
+def config4(seed=BASE_SEED + 4, mem_cap_mib=6000):
     """Large random batch: L=96, PP=16, DP=2, M=64, one failure, lognormal layer times;
-    the plans are explicit random partitions (see random_partitions)."""
+    the plans are explicit random partitions (see random_partitions).  mem_cap_mib=6000 is the
+    stated cap; CONFIG4_CAP_30PCT gives the stated 30 % infeasible fraction."""
     fwd, bwd, mem = layer_tables(seed, 96, dist="lognormal", mem_lo=300, mem_hi=900)
     failed = randint(seed, 5, 1, 0, 16 * 2 - 1)
-    return scenario(96, 16, 2, 64, fwd, bwd, mem, failed, 200, 6000)
+    return scenario(96, 16, 2, 64, fwd, bwd, mem, failed, 200, mem_cap_mib)
 
 
 def config5_tables(seed=BASE_SEED + 5):

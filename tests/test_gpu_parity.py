@@ -223,3 +223,107 @@ def test_error_paths_and_degenerate_cases(B):
         rc, best = g5.search_best(mask)
         assert rc == 0 and best["index"] == lo + int(np.argmin(costs[lo:hi])) and best["cost"] == int(costs[lo:hi].min())
         assert same_plan(best, o5.search(mask)[1])
+
+
+def test_rank_partitions_and_search_over_explicit_lists(B):
+    import torch
+    for sc in (synth.config4(), SMALL[3], SMALL[12], SMALL[24], synth.config2()):
+        o, g = O.Scenario(sc), B.Scenario(sc)
+        for f in o.families:
+            k = f["stages"] - 1
+            if k == 0:
+                continue
+            n = 1500
+            cuts = synth.random_partitions(77, 5 + f["strategy"], n, sc["L"], k)
+            cuts[7] = cuts[3]                                   # duplicates are allowed in a list
+            want_ranks = O.partition_rank_batch(cuts)
+            d_cuts = torch.from_numpy(cuts).cuda()
+            d_ranks = g.rank_partitions(f["strategy"], d_cuts)
+            torch.cuda.synchronize()
+            assert (d_ranks.cpu().numpy().view(np.uint64) == want_ranks).all()
+            # costs of the listed partitions and the first position of their minimum
+            if f["n_reroute"] == 1:
+                want = o.score_ranks(f["strategy"], want_ranks)
+            else:
+                want = np.array([o.search_range(f["strategy"], int(r), 1)[1]["cost"] for r in want_ranks[:200]], dtype=np.int64)
+                d_ranks, want_ranks = d_ranks[:200].contiguous(), want_ranks[:200]
+            costs = torch.empty(len(want), dtype=torch.int64, device="cuda")
+            rc, best, pos = g.search_ranks(f["strategy"], d_ranks, costs=costs)
+            assert (costs.cpu().numpy() == want).all()
+            if (want == O.INF).all():
+                assert rc == B.ERR_NO_FEASIBLE
+                continue
+            assert rc == 0 and pos == int(np.argmin(want)) and best["cost"] == int(want.min())
+            rc_o, best_o, _ = o.search_range(f["strategy"], int(want_ranks[pos]), 1)
+            assert same_plan(best, best_o)
+    # malformed rows and ranks outside the family
+    sc = synth.small_random(2002, L=8, PP=4, DP=2, M=5, n_failed=1, hetero=False)
+    g = B.Scenario(sc)
+    f = g.family(2)
+    assert f["stages"] == 4
+    bad = torch.tensor([[3, 2, 5], [0, 1, 2], [1, 2, 200], [1, 2, 3]], dtype=torch.uint8, device="cuda")
+    r = g.rank_partitions(f["strategy"], bad).cpu().numpy().view(np.uint64)
+    assert (r[:3] == np.uint64(2 ** 64 - 1)).all() and r[3] == 0
+    rc, best, pos = g.search_ranks(f["strategy"], torch.tensor([-1, -1], dtype=torch.int64, device="cuda"))
+    assert rc == B.ERR_NO_FEASIBLE and best["cost"] == B.INFEASIBLE
+
+
+def test_full_size_config4_explicit_batch(B):
+    """2^24 random partitions per strategy: every cost goes through the C-ABI, a seeded sample of
+    them is re-scored by the oracle, and the argmin must be the first minimum of the cost array."""
+    import torch
+    sc = synth.config4(mem_cap_mib=synth.CONFIG4_CAP_30PCT)
+    o, g = O.Scenario(sc), B.Scenario(sc)
+    n, chunk = 1 << 24, 1 << 18
+    rng = np.random.default_rng(9)
+    for strategy, k in ((0, 15), (1, 14), (2, 15)):
+        d_ranks = torch.empty(n, dtype=torch.int64, device="cuda")
+        sample_idx = np.sort(rng.choice(n, 600, replace=False))
+        sample_cuts = np.empty((600, k), dtype=np.uint8)
+        for c0 in range(0, n, chunk):
+            cuts = synth.random_partitions(synth.BASE_SEED + 4, 1000 * strategy + c0 // chunk, chunk, 96, k)
+            g.rank_partitions(strategy, torch.from_numpy(cuts).cuda(), out=d_ranks[c0:c0 + chunk])
+            sel = (sample_idx >= c0) & (sample_idx < c0 + chunk)
+            sample_cuts[sel] = cuts[sample_idx[sel] - c0]
+        print("config4 strategy", strategy, "ranks ready", flush=True)
+        costs = torch.empty(n, dtype=torch.int64, device="cuda")
+        rc, best, pos = g.search_ranks(strategy, d_ranks, costs=costs)
+        h = costs.cpu().numpy()
+        want_ranks = O.partition_rank_batch(sample_cuts)
+        assert (d_ranks.cpu().numpy().view(np.uint64)[sample_idx] == want_ranks).all()
+        assert (h[sample_idx] == o.score_ranks(strategy, want_ranks)).all()
+        print("config4 strategy", strategy, "infeasible fraction", float((h == B.INFEASIBLE).mean()), flush=True)
+        if (h == B.INFEASIBLE).all():
+            assert rc == B.ERR_NO_FEASIBLE
+            continue
+        assert rc == 0 and pos == int(np.argmin(h)) and best["cost"] == int(h.min())
+        assert o.plan_cost(strategy, best["cuts"], best["reroute"] if strategy == 2 else None) == best["cost"]
+        # the plain scoring entry point gives the same numbers
+        again = g.score_ranks(strategy, d_ranks[:100000].contiguous())
+        assert torch.equal(again, costs[:100000])
+
+
+def test_full_size_search_config3_and_config5(B):
+    """whole spaces of the heterogeneous-rerouting shape (two stages lost a node, 2,380,833 capped
+    vectors each) and of a two-failure scenario of the sweep: the winner is re-scored by the oracle
+    and must equal the oracle's argmin over the partitions around it."""
+    for name, sc in (("config3", synth.config3()), ("config5", synth.config5([9, 13])), ("config5", synth.config5([2, 24]))):
+        o, g = O.Scenario(sc), B.Scenario(sc)
+        for f in o.families:
+            rc, best = g.search_best(1 << f["strategy"])
+            print(name, "strategy", f["strategy"], rc, best["index"], best["cost"], flush=True)
+            if rc == B.ERR_NO_FEASIBLE:
+                assert o.search_range(f["strategy"], 0, min(f["n_part"], 3000))[0] == O.ERR_NO_FEASIBLE
+                continue
+            rr = best["reroute"] if f["strategy"] == 2 else None
+            assert o.plan_cost(f["strategy"], best["cuts"], rr) == best["cost"]
+            part = O.partition_rank(best["cuts"])
+            width = 60 if f["n_reroute"] > 10 ** 6 else 4000
+            lo = max(0, part - width // 2)
+            rc_o, best_o, _ = o.search_range(f["strategy"], lo, min(width, f["n_part"] - lo))
+            assert rc_o == 0 and same_plan(best, best_o)
+        rc_all, best_all = g.search_best(7)
+        assert rc_all == 0
+        per = [g.search_best(1 << f["strategy"]) for f in o.families]
+        want = min((b["cost"], b["index"]) for r, b in per if r == 0)
+        assert (best_all["cost"], best_all["index"]) == want
