@@ -16,9 +16,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# MI355X: 256 compute units x 64 int32 lanes per clock x 2.4 GHz (the fp32 vector figure
-# 157.3 TFLOP/s counts a packed fused multiply-add as 4 flops per lane: 157.3 / 4 = 39.3)
-ALU_PEAK_TOPS = 256 * 64 * 2.4e9 / 1e12
+# MI355X VALU: 256 compute units x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6 T int32 lane
+# operations per second (the published fp32 vector figure, 157.3 TFLOP/s, is this rate x 2 flops per
+# fused multiply-add).  Only simple operations (v_add_u32) issue at that rate; v_max_i32 and
+# v_mul_u32_u24, which the path needs, issue at half of it (chm_valu_probe measures both).
+ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
 
 def algorithmic_ops(fam, feasible):
@@ -133,6 +135,9 @@ def main():
     cells = sum(f["n_part"] * sum(2 * n * m for n, m in f["classes"]) for f in fams)
     n_part_total = sum(f["n_part"] for f in fams)
 
+    probes = {name: B.valu_probe(kind, 3000, stream=stream) / 1e12
+              for kind, name in ((0, "v_add_u32"), (1, "v_max_i32"), (2, "max_add_cell_chain"))}
+    note("measured VALU rates (T lane-ops/s): %s" % probes)
     out = {
         "metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
         "value": n_plans / (ms_per_step * 1e-3),
@@ -151,6 +156,8 @@ def main():
         "best": {"index": best["index"], "cost": best["cost"], "strategy": best["strategy"], "cuts": best["cuts"]},
         "roofline": {"bound": "alu", "kernel": "search, strategy %d" % dom, "achieved": achieved,
                      "peak": ALU_PEAK_TOPS, "unit": "TOP/s (int32 lane operations)", "frac": achieved / ALU_PEAK_TOPS,
+                     "measured_valu_rates_tops": probes,
+                     "frac_of_measured_cell_rate": achieved / probes["max_add_cell_chain"],
                      "traffic": None, "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": ops_launch,
                      "feasible_partitions": timing["feasible"][dom], "partitions": fam["n_part"],
                      "algorithmic_ops_per_feasible_partition": ops_light + ops_heavy,

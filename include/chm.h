@@ -168,6 +168,13 @@ int chm_get_timing(const chm_scenario *s, chm_timing *out);
  * with length[i] stages and micro_batches[i] micro-batches.  Host only; for work accounting. */
 int chm_family_classes(const chm_scenario *s, int32_t strategy, int32_t *n, int32_t *length, int32_t *micro_batches);
 
+/* Measures a VALU integer issue rate of the current device with a register-only kernel and
+ * returns executed int32 lane operations per second.  kind 0: independent v_add_u32; kind 1:
+ * independent v_max_i32; kind 2: the recurrence cell (v_max_i32 + v_add_u32 in one dependent
+ * chain per lane).  iters scales the run time (about 1 ms per 1000).  Synchronises hip_stream.
+ * Used by the benchmark to put measured rates beside its nominal roofline peak. */
+int chm_valu_probe(int32_t kind, uint32_t iters, double *lane_ops_per_s, void *hip_stream);
+
 void chm_free_scenario(chm_scenario *s);
 const char *chm_strerror(int code);
 

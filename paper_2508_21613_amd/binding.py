@@ -17,7 +17,7 @@ INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
            "chm_search_range", "chm_search_ranks", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
-           "chm_free_scenario",
+           "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
 
@@ -80,6 +80,7 @@ def lib():
         L.chm_set_timing.argtypes = [vp, C.c_int32]
         L.chm_get_timing.argtypes = [vp, C.POINTER(Timing)]
         L.chm_family_classes.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.chm_valu_probe.argtypes = [C.c_int32, C.c_uint32, C.POINTER(C.c_double), vp]
         L.chm_free_scenario.argtypes = [vp]
         L.chm_free_scenario.restype = None
         L.chm_strerror.argtypes = [C.c_int]
@@ -114,6 +115,13 @@ def _stream_ptr(stream):
         import torch
         return C.c_void_p(torch.cuda.current_stream().cuda_stream)
     return C.c_void_p(stream if isinstance(stream, int) else stream.cuda_stream)
+
+
+def valu_probe(kind, iters=4000, stream=None):
+    """chm_valu_probe: executed int32 lane operations per second of a register-only kernel"""
+    out = C.c_double()
+    _check(lib().chm_valu_probe(kind, iters, C.byref(out), _stream_ptr(stream)))
+    return float(out.value)
 
 
 class Scenario:
