@@ -539,13 +539,13 @@ int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, hipStream_t s
     return 0;
   switch (sp) {
     CHM_CASE(2) CHM_CASE(3) CHM_CASE(4) CHM_CASE(5) CHM_CASE(6) CHM_CASE(7) CHM_CASE(8)
-    CHM_CASE(15) CHM_CASE(16)
+    CHM_CASE(9) CHM_CASE(10) CHM_CASE(11) CHM_CASE(12) CHM_CASE(13) CHM_CASE(14) CHM_CASE(15) CHM_CASE(16)
     default: return 1;
   }
 #undef CHM_CASE
 }
 
-bool stages_covered(int sp) { return (sp >= 2 && sp <= 8) || sp == 15 || sp == 16; }
+bool stages_covered(int sp) { return sp >= 2 && sp <= 16; }
 
 }  // namespace
 

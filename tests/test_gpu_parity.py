@@ -46,7 +46,21 @@ SMALL = [synth.small_random(1000 + i) for i in range(24)] + [
     synth.small_random(2008, L=14, PP=6, DP=4, M=7, n_failed=4, hetero=True, cap=9),
     synth.small_random(2009, L=20, PP=12, DP=2, M=13, n_failed=2, hetero=True),     # > 8 stages
     synth.small_random(2010, L=22, PP=18, DP=2, M=5, n_failed=1, hetero=False),     # > 16 stages
+    synth.small_random(2011, L=16, PP=10, DP=3, M=12, n_failed=2, hetero=True),
+    synth.small_random(2012, L=18, PP=14, DP=2, M=20, n_failed=1, hetero=True),
+    synth.small_random(2013, L=15, PP=11, DP=2, M=4, n_failed=2, hetero=False),     # M < S-1 on the unrolled path
 ]
+
+
+def _two_lost_in_one_pipeline():
+    # pipeline 0 loses stages 1 and 4 (not ring-adjacent): the redundant strategy runs a chain of S-2 nodes
+    fwd, bwd, mem = synth.layer_tables(4242, 13)
+    return synth.scenario(13, 6, 3, 7, fwd, bwd, mem, [1, 4], 120, int(mem.sum() * 2.2 / 6),
+                          speed=synth.speed_factors(4242, 3, 6))
+
+
+SMALL.append(_two_lost_in_one_pipeline())
+SMALL.append(dict(_two_lost_in_one_pipeline(), failed_nodes=[0, 3, 8], M=3))
 
 
 @pytest.mark.parametrize("i", range(len(SMALL)))
