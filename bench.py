@@ -45,6 +45,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--ttb-runs", type=int, default=10)
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config5"],
+                    help="config2 (the 32-card shape) is the benchmark; the others are for profiling")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -64,27 +66,33 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
-    sc = synth.config2()
+    workloads = {
+        "config1": ("config1: L=32 PP=4 DP=2 M=8, 1 failed node", lambda: [synth.config1()]),
+        "config2": ("config2: L=48 PP=8 DP=4 M=16, 1 failed node", lambda: [synth.config2()]),
+        "config3": ("config3: L=40 PP=4 DP=8 M=32, 2 failed nodes, Q16 speed factors, reroute cap 16", lambda: [synth.config3()]),
+        "config5": ("config5: L=40 PP=8 DP=4 M=16, all 32 single and 496 double node failures",
+                    lambda: [synth.config5(fs) for fs in synth.config5_failure_sets()]),
+    }
+    label, make = workloads[args.workload]
+    scenarios = make()
     t0 = time.perf_counter()
-    g = B.Scenario(sc)
+    handles = [B.Scenario(sc) for sc in scenarios]
     load_ms = (time.perf_counter() - t0) * 1e3
+    note("%d scenario(s) loaded in %.1f ms" % (len(handles), load_ms))
     stream = torch.cuda.Stream()
-    n_plans = g.n_plans
-    fams = []
-    for f in g.families:
-        d = dict(f)
-        d["classes"] = g.family_classes(f["strategy"])
-        if f["strategy"] == 2:
-            S, D = sc["PP"], sc["DP"]
-            lost_stage = {}
-            for n in sc["failed_nodes"]:
-                lost_stage[n % S] = lost_stage.get(n % S, 0) + 1
-            d["peers"] = [D - v for _, v in sorted(lost_stage.items())]
-            from math import comb
-            d["R"] = [comb(v * sc["M"] + (D - v) - 1, (D - v) - 1) for _, v in sorted(lost_stage.items())]
-        else:
-            d["peers"], d["R"] = [], []
-        fams.append(d)
+
+    def family_work(g):
+        shape = g.reroute_shape()
+        fams = []
+        for f in g.families:
+            d = dict(f)
+            d["classes"] = g.family_classes(f["strategy"])
+            d["peers"] = [p for p, _ in shape] if f["strategy"] == 2 else []
+            d["R"] = [r for _, r in shape] if f["strategy"] == 2 else []
+            fams.append(d)
+        return fams
+
+    work = [family_work(g) for g in handles]
 
     if args.copy_calibration:
         src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
@@ -94,33 +102,47 @@ def main():
         del src, dst
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
-            rc, best = g.search_best(7, stream=stream)
-            note("warm-up search %d done" % i)
-        g.set_timing(True)
+            for g in handles:
+                g.search_best(7, stream=stream)
+            note("warm-up step %d done" % i)
+        for g in handles:
+            g.set_timing(True)
         fam_ms = np.zeros(3)
         stream.synchronize()
         torch.cuda.synchronize()
-        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         t0 = time.perf_counter()
-        ev0.record(stream)
         for _ in range(args.steps):
-            rc, best = g.search_best(7, stream=stream)
-            fam_ms += np.array(g.get_timing()["family_ms"])
-        ev1.record(stream)
+            for g in handles:
+                rc, best = g.search_best(7, stream=stream)
+                fam_ms += np.array(g.get_timing()["family_ms"])
         stream.synchronize()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
-    assert rc == 0
     ms_per_step = wall * 1e3 / args.steps
-    note("timed %d searches: %.3f ms per search, per strategy %s" % (args.steps, ms_per_step, fam_ms / args.steps))
     fam_ms /= args.steps
-    timing = g.get_timing()
+    note("timed %d steps: %.3f ms per step, kernel ms per strategy %s" % (args.steps, ms_per_step, fam_ms))
 
-    # time-to-best-plan: load + search, median over --ttb-runs fresh handles
+    # work done per step, from the library's own counters of the last search on every handle
+    evaluations = np.zeros(3)
+    feasible = np.zeros(3)
+    ops = np.zeros(3)
+    n_part_total, cells, plan_indices = 0, 0, 0
+    for g, fams in zip(handles, work):
+        tm = g.get_timing()
+        evaluations += np.array(tm["evaluations"], dtype=float)
+        feasible += np.array(tm["feasible"], dtype=float)
+        plan_indices += g.n_plans
+        for f in fams:
+            ops[f["strategy"]] += algorithmic_ops(f, tm["feasible"][f["strategy"]])[0]
+            n_part_total += f["n_part"]
+            cells += f["n_part"] * sum(2 * n * m for n, m in f["classes"])
+    n_plans = float(evaluations.sum())
+
+    # time-to-best-plan: load + search on a fresh handle, median over --ttb-runs (first scenario)
     ttb = []
     for _ in range(args.ttb_runs):
         t0 = time.perf_counter()
-        g2 = B.Scenario(sc)
+        g2 = B.Scenario(scenarios[0])
         g2.search_best(7, stream=stream)
         ttb.append((time.perf_counter() - t0) * 1e3)
         g2.close()
@@ -129,15 +151,14 @@ def main():
 
     # roofline of the dominant kernel
     dom = int(np.argmax(fam_ms))
-    fam = [f for f in fams if f["strategy"] == dom][0]
-    ops_launch, ops_light, ops_heavy = algorithmic_ops(fam, timing["feasible"][dom])
-    achieved = ops_launch / (fam_ms[dom] * 1e-3) / 1e12
-    cells = sum(f["n_part"] * sum(2 * n * m for n, m in f["classes"]) for f in fams)
-    n_part_total = sum(f["n_part"] for f in fams)
+    achieved = ops[dom] / (fam_ms[dom] * 1e-3) / 1e12
+    fam0 = [f for f in work[0] if f["strategy"] == dom]
+    _, ops_light, ops_heavy = algorithmic_ops(fam0[0], 0) if fam0 else (0, 0, 0)
 
     probes = {name: B.valu_probe(kind, 3000, stream=stream) / 1e12
               for kind, name in ((0, "v_add_u32"), (1, "v_max_i32"), (2, "max_add_cell_chain"))}
     note("measured VALU rates (T lane-ops/s): %s" % probes)
+    sc = scenarios[0]
     out = {
         "metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
         "value": n_plans / (ms_per_step * 1e-3),
@@ -146,9 +167,10 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
-        "config": {"workload": "config2: L=48 PP=8 DP=4 M=16, 1 failed node, exhaustive search over all 3 strategies",
-                   "plan_indices": n_plans, "partitions": n_part_total, "failed_nodes": sc["failed_nodes"],
-                   "families": [{k: f[k] for k in ("strategy", "stages", "n_part", "n_reroute")} for f in fams]},
+        "config": {"workload": label + ", exhaustive search over all strategies",
+                   "scenarios": len(handles), "plans_scored_per_step": n_plans, "plan_indices": plan_indices,
+                   "partitions": n_part_total, "failed_nodes": sc["failed_nodes"] if len(handles) == 1 else "all",
+                   "families": [{k: f[k] for k in ("strategy", "stages", "n_part", "n_reroute")} for f in work[0]]},
         "time_to_best_plan_ms": ttb_ms, "load_ms": load_ms,
         "partition_evals_per_s": n_part_total / (ms_per_step * 1e-3),
         "recurrence_cells_per_s": cells / (ms_per_step * 1e-3),
@@ -158,16 +180,16 @@ def main():
                      "peak": ALU_PEAK_TOPS, "unit": "TOP/s (int32 lane operations)", "frac": achieved / ALU_PEAK_TOPS,
                      "measured_valu_rates_tops": probes,
                      "frac_of_measured_cell_rate": achieved / probes["max_add_cell_chain"],
-                     "traffic": None, "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": ops_launch,
-                     "feasible_partitions": timing["feasible"][dom], "partitions": fam["n_part"],
+                     "traffic": None, "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": float(ops[dom]),
+                     "feasible_partitions": float(feasible[dom]),
                      "algorithmic_ops_per_feasible_partition": ops_light + ops_heavy,
                      "algorithmic_ops_per_infeasible_partition": ops_light},
-        "feasible_partitions_per_strategy": timing["feasible"],
+        "feasible_partitions_per_strategy": [float(x) for x in feasible],
     }
 
     if not args.no_cpu_baseline:
         from oracle import oracle as O
-        o = O.Scenario(sc)
+        o = O.Scenario(scenarios[0])
         spent = 0.0
         per_family = []
         for f in o.families:               # the same three strategies, a slice from the middle of each rank space
@@ -187,7 +209,9 @@ def main():
             spent += t + t_cal
         # whole-job rate of the oracle: time it would need for the full space at these per-family rates
         full_s = sum(t * (o.family(s)["n_part"] / n) for s, n, ev, t in per_family)
-        out["cpu_baseline"] = {"value": o.n_plans / full_s, "unit": "plans/s", "cores": 1, "kind": "oracle",
+        o_plans = sum(f["n_part"] * (sum(r for _, r in handles[0].reroute_shape()) if f["strategy"] == 2 and handles[0].reroute_shape() else 1)
+                      for f in o.families)
+        out["cpu_baseline"] = {"value": o_plans / full_s, "unit": "plans/s", "cores": 1, "kind": "oracle",
                                "sample": "oracle search over %s partitions from the middle of the rank space of strategies %s (%.1f s of CPU work), "
                                          "extrapolated per strategy to the full space" %
                                          ([n for _, n, _, _ in per_family], [s for s, _, _, _ in per_family], spent),

@@ -168,6 +168,10 @@ int chm_get_timing(const chm_scenario *s, chm_timing *out);
  * with length[i] stages and micro_batches[i] micro-batches.  Host only; for work accounting. */
 int chm_family_classes(const chm_scenario *s, int32_t strategy, int32_t *n, int32_t *length, int32_t *micro_batches);
 
+/* Shape of the reroute space: *n_affected stages lost nodes; stage a has peers[a] surviving peers
+ * and n_vectors[a] valid reroute vectors (arrays of 4).  Host only; for work accounting. */
+int chm_reroute_shape(const chm_scenario *s, int32_t *n_affected, int32_t *peers, uint64_t *n_vectors);
+
 /* Measures a VALU integer issue rate of the current device with a register-only kernel and
  * returns executed int32 lane operations per second.  kind 0: independent v_add_u32; kind 1:
  * independent v_max_i32; kind 2: the recurrence cell (v_max_i32 + v_add_u32 in one dependent

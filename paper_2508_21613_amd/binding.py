@@ -17,7 +17,7 @@ INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
            "chm_search_range", "chm_search_ranks", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
-           "chm_valu_probe", "chm_free_scenario",
+           "chm_reroute_shape", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
 
@@ -80,6 +80,7 @@ def lib():
         L.chm_set_timing.argtypes = [vp, C.c_int32]
         L.chm_get_timing.argtypes = [vp, C.POINTER(Timing)]
         L.chm_family_classes.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+        L.chm_reroute_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
         L.chm_valu_probe.argtypes = [C.c_int32, C.c_uint32, C.POINTER(C.c_double), vp]
         L.chm_free_scenario.argtypes = [vp]
         L.chm_free_scenario.restype = None
@@ -242,6 +243,13 @@ class Scenario:
         ln, mb = (C.c_int32 * 16)(), (C.c_int32 * 16)()
         _check(lib().chm_family_classes(self._h, strategy, C.byref(n), ln, mb))
         return [(int(ln[i]), int(mb[i])) for i in range(n.value)]
+
+    def reroute_shape(self):
+        """[(surviving peers, valid reroute vectors)] per stage that lost nodes"""
+        n = C.c_int32()
+        peers, vecs = (C.c_int32 * 4)(), (C.c_uint64 * 4)()
+        _check(lib().chm_reroute_shape(self._h, C.byref(n), peers, vecs))
+        return [(int(peers[a]), int(vecs[a])) for a in range(n.value)]
 
     def set_timing(self, on=True):
         _check(lib().chm_set_timing(self._h, 1 if on else 0))

@@ -7,7 +7,7 @@ enum {
   FAST_MAX_P = 8,            // peers per affected stage the specialised sweeps are instantiated for
   FAST_FUSED_R = 4096,       // up to this many reroute vectors (all stages) the sweep runs inside the search kernel
   FAST_SPLIT_R = 1 << 23,    // up to this many per stage the vectors are tabulated and swept by a kernel of their own
-  FAST_SUB = 1 << 18         // partitions per pass of the split path (bounds its scratch memory)
+  FAST_SUB = 1 << 16         // partitions per pass of the split and scoring paths (bounds their scratch memory)
 };
 
 // One pipeline class in the form the specialised kernels read (all int32).
@@ -60,5 +60,12 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
 // written to d_out[0..n_aff).  Same return convention as fast_search.
 int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t part_rank,
                         uint64_t *d_out, void *stream);
+// Scores plan indices [local_first, local_first+count) of the rerouting family (indices local to
+// the family) into d_costs: one pass of the search kernel stores each partition's cost without
+// penalties and its peer stage times, then one lane per plan index adds the penalty of its
+// reroute vectors (looked up in the rank-ordered table) and stores the cost.  Same return
+// convention as fast_search.
+int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t local_first,
+                       uint64_t count, int64_t *d_costs, void *stream);
 void fast_release(FastState *f);
 #endif

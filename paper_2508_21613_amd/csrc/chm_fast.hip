@@ -32,6 +32,20 @@ namespace {
 
 constexpr int BLOCK = 256;
 
+// The scenario tables are never written while a search kernel runs.  Reading them through the
+// constant address space tells the compiler so: uniform reads become scalar loads (wide
+// s_load_dwordx16 for the reroute rows) even though the kernel also stores costs to global memory.
+#define CHM_CONST __attribute__((address_space(4)))
+typedef const CHM_CONST DevScenario *ScnPtr;
+typedef const CHM_CONST FastTables *TabPtr;
+typedef const CHM_CONST FastFamily *FamPtr;
+typedef const CHM_CONST FastClass *ClsPtr;
+typedef const CHM_CONST uint32_t *RowPtr;
+template <typename T>
+__device__ __forceinline__ const CHM_CONST T *as_const(const T *p) {
+  return (const CHM_CONST T *)(uintptr_t)p;
+}
+
 __device__ __forceinline__ int imax32(int a, int b) { return a > b ? a : b; }
 __device__ __forceinline__ int imin32(int a, int b) { return a < b ? a : b; }
 
@@ -103,15 +117,15 @@ __device__ __forceinline__ int makespan32(const int (&F)[N], const int (&B)[N], 
 }
 
 template <int N>
-__device__ __forceinline__ int class_time(const FastClass &c, int (&F)[N], int (&B)[N]) {
-  if (!c.unit) {
+__device__ __forceinline__ int class_time(ClsPtr c, int (&F)[N], int (&B)[N]) {
+  if (!c->unit) {
 #pragma unroll
     for (int j = 0; j < N; ++j) {
-      F[j] = scale32(F[j], c.q[j]);
-      B[j] = scale32(B[j], c.q[j]);
+      F[j] = scale32(F[j], c->q[j]);
+      B[j] = scale32(B[j], c->q[j]);
     }
   }
-  return makespan32<N>(F, B, c.M) + c.comm_total;
+  return makespan32<N>(F, B, c->M) + c->comm_total;
 }
 
 // min over all reroute vectors of one stage of max_i r_i * w_i.  Rows are stored with a
@@ -119,11 +133,11 @@ __device__ __forceinline__ int class_time(const FastClass &c, int (&F)[N], int (
 // that put every orphaned micro-batch on every peer (never better than a valid row), so four
 // rows are fetched by one wide scalar load and scored back to back.
 template <int P>
-__device__ __forceinline__ uint32_t sweep_vectors(const uint32_t *__restrict__ rows, uint32_t n_rows_padded, const uint32_t (&w)[P]) {
+__device__ __forceinline__ uint32_t sweep_vectors(RowPtr rows, uint32_t n_rows_padded, const uint32_t (&w)[P]) {
   constexpr int STRIDE = P <= 4 ? 4 : 8;
   uint32_t best = 0xffffffffu;
   for (uint32_t r = 0; r < n_rows_padded; r += 4) {
-    const uint32_t *row = rows + (size_t)r * STRIDE;
+    RowPtr row = rows + (size_t)r * STRIDE;
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       uint32_t pen = 0;
@@ -172,11 +186,15 @@ template <int SP, int STRAT>
 __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
   constexpr int K = SP - 1;
   __shared__ int4 T[DEV_MAX_L + 1];            // prefix sums: forward, backward, memory
+  __shared__ uint64_t BN[(K > 0 ? K : 1) * DEV_MAX_L];   // BN[(i-1)*128 + x] = C(x, i), i = 1..K
   __shared__ uint64_t wave_keys[BLOCK / 64];
-  const DevScenario *__restrict__ scn = a.s.scn;
-  const FastFamily &ff = a.tab->fam[STRAT];
+  extern __shared__ int64_t cost_tile[];       // BLOCK * per_lane costs when a cost store with per_lane > 1 is asked for
+  const ScnPtr scn = as_const(a.s.scn);
+  const TabPtr tab = as_const(a.tab);
+  const FamPtr ff = &tab->fam[STRAT];
   const int L = scn->L;
   for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], 0);
+  for (int i = threadIdx.x; i < K * DEV_MAX_L; i += BLOCK) BN[i] = scn->binom[1 + i / DEV_MAX_L][i % DEV_MAX_L];
   __syncthreads();
 
   const uint32_t lane_id = blockIdx.x * BLOCK + threadIdx.x;
@@ -196,12 +214,24 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
       listed_ok = rem < scn->fam[STRAT].n_part;
       if (!listed_ok) rem = 0;
     }
+    // combinadic digits from the LDS copy of the binomial table; four candidates are probed at a
+    // time (independent LDS reads) so that the scan is not one dependent load per step
     int x = L - 2;
 #pragma unroll
     for (int i = K; i >= 1; --i) {
-      while (scn->binom[i][x] > rem) --x;
+      const uint64_t *col = BN + (i - 1) * DEV_MAX_L;
+      for (;;) {
+        int over = 0;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int xi = x - j;
+          over += (xi >= 0 && col[xi >= 0 ? xi : 0] > rem) ? 1 : 0;   // C(.,i) grows with x: the first `over` probes exceed rem
+        }
+        x -= over;
+        if (over < 4) break;
+      }
       c[i] = x + 1;
-      rem -= scn->binom[i][x];
+      rem -= col[x];
       --x;
     }
   }
@@ -237,7 +267,7 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
     const uint64_t ok_mask = __builtin_amdgcn_ballot_w64(ok);
     n_fit += (uint32_t)__popcll(ok_mask);
     if (ok_mask != 0) {
-      int t_step = ff.fixed_step;
+      int t_step = ff->fixed_step;
       int missing = 0;
       if (STRAT != 1) {
         // weights the stage-j node must fetch: stage size minus what it already holds; prefix
@@ -247,10 +277,10 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
 #pragma unroll
         for (int j = 0; j < SP; ++j) {
           const int wh = wl + ms[j];
-          have += imax32(0, imin32(wh, ff.w0[j + 1]) - imax32(wl, ff.w0[j]));
+          have += imax32(0, imin32(wh, ff->w0[j + 1]) - imax32(wl, ff->w0[j]));
           wl = wh;
         }
-        missing = ff.w_total - have;
+        missing = ff->w_total - have;
       }
       if (STRAT == 0) {
         int fd[SP], bd[SP];
@@ -259,20 +289,20 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
           fd[j] = fs[j] + fs[(j + 1) % SP];
           bd[j] = bs[j] + bs[(j + 1) % SP];
         }
-        for (int ci = 0; ci < ff.n_cls; ++ci) {
-          const FastClass &cl = ff.cls[ci];
+        for (int ci = 0; ci < ff->n_cls; ++ci) {
+          const ClsPtr cl = &ff->cls[ci];
           int T_c;
-          if (cl.n == SP) {
+          if (cl->n == SP) {
             int F[SP], B[SP];
 #pragma unroll
             for (int j = 0; j < SP; ++j) { F[j] = fd[j]; B[j] = bd[j]; }
             T_c = class_time<SP>(cl, F, B);
-          } else if (SP >= 2 && cl.n == SP - 1) {
+          } else if (SP >= 2 && cl->n == SP - 1) {
             constexpr int N = SP >= 2 ? SP - 1 : 1;
             int F[N], B[N];
 #pragma unroll
             for (int j = 0; j < N; ++j) {
-              const bool before = j < cl.dead0;
+              const bool before = j < cl->dead0;
               F[j] = before ? fd[j] : fd[(j + 1) % SP];
               B[j] = before ? bd[j] : bd[(j + 1) % SP];
             }
@@ -282,7 +312,7 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
             int F[N], B[N];
 #pragma unroll
             for (int j = 0; j < N; ++j) {
-              const bool b0 = j < cl.dead0, b1 = j + 1 < cl.dead1;
+              const bool b0 = j < cl->dead0, b1 = j + 1 < cl->dead1;
               F[j] = b0 ? fd[j] : (b1 ? fd[(j + 1) % SP] : fd[(j + 2) % SP]);
               B[j] = b0 ? bd[j] : (b1 ? bd[(j + 1) % SP] : bd[(j + 2) % SP]);
             }
@@ -291,8 +321,8 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
           t_step = imax32(t_step, T_c);
         }
       } else {
-        for (int ci = 0; ci < ff.n_cls; ++ci) {
-          const FastClass &cl = ff.cls[ci];
+        for (int ci = 0; ci < ff->n_cls; ++ci) {
+          const ClsPtr cl = &ff->cls[ci];
           int F[SP], B[SP];
 #pragma unroll
           for (int j = 0; j < SP; ++j) { F[j] = fs[j]; B[j] = bs[j]; }
@@ -302,10 +332,10 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
 #pragma unroll
             for (int j = 0; j < SP; ++j) {
               const int wh = wl + ms[j];
-              have += imax32(0, imin32(wh, cl.whi[j]) - imax32(wl, cl.wlo[j]));
+              have += imax32(0, imin32(wh, cl->whi[j]) - imax32(wl, cl->wlo[j]));
               wl = wh;
             }
-            missing = imax32(missing, ff.w_total - have);
+            missing = imax32(missing, ff->w_total - have);
           }
         }
       }
@@ -320,8 +350,8 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
             b_st = sa == j ? bs[j] : b_st;
           }
           const int p = scn->aff_peers[st];
-          const uint32_t *rows = a.vecs + a.tab->vec_off[st];
-          const uint32_t n_rows = a.tab->vec_rows[st];
+          const RowPtr rows = as_const(a.vecs) + tab->vec_off[st];
+          const uint32_t n_rows = tab->vec_rows[st];
           uint32_t pen = 0;
 #define CHM_SWEEP(P)                                                                            \
   case P: {                                                                                     \
@@ -366,7 +396,13 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
       if (STRAT == 2 && a.base_out != nullptr && ok) a.base_out[run_first + it] = cost;
     }
     if (STRAT == 2 && a.base_out != nullptr && !ok && it < run_len) a.base_out[run_first + it] = ~0ull;
-    if (a.s.costs_out != nullptr && it < run_len) a.s.costs_out[run_first + it] = ok ? (int64_t)cost : CHM_INF_COST;
+    if (a.s.costs_out != nullptr) {
+      // per_lane == 1: the store is coalesced as it is; longer runs go through an LDS tile
+      // (laid out in output order) and are written out together after the loop
+      const int64_t v = ok ? (int64_t)cost : CHM_INF_COST;
+      if (a.per_lane == 1) { if (it < run_len) a.s.costs_out[run_first] = v; }
+      else cost_tile[threadIdx.x * a.per_lane + it] = v;
+    }
     // ---- next partition in rank order: bump the lowest cut that has room, reset those below
     {
       bool done = false;
@@ -379,6 +415,13 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
     }
   }
 
+  if (a.s.costs_out != nullptr && a.per_lane > 1) {
+    __syncthreads();
+    const uint64_t block_first = (uint64_t)blockIdx.x * BLOCK * a.per_lane;
+    const uint32_t n_tile = BLOCK * a.per_lane;
+    for (uint32_t i = threadIdx.x; i < n_tile; i += BLOCK)
+      if (block_first + i < a.s.part_count) a.s.costs_out[block_first + i] = cost_tile[i];
+  }
   uint64_t key = best_cost == ~0ull ? CHM_KEY_NONE
                                     : ((best_cost << a.s.idx_bits) | (run_first + best_it));
   if (STRAT == 2 && a.base_out != nullptr) key = CHM_KEY_NONE;   // the combine kernel takes the argmin
@@ -445,7 +488,7 @@ __global__ void __launch_bounds__(BLOCK) k_sweep(const uint32_t *__restrict__ ro
   for (int i = 0; i < P; ++i) w[i] = live ? weights[(size_t)part * (DEV_MAX_AFF * 8) + a * 8 + i] : 1u;
   const uint32_t first = blockIdx.y * rows_per_chunk;
   const uint32_t n = first >= n_rows_padded ? 0u : (n_rows_padded - first < rows_per_chunk ? n_rows_padded - first : rows_per_chunk);
-  const uint32_t pen = sweep_vectors<P>(rows + (size_t)first * STRIDE, n, w);
+  const uint32_t pen = sweep_vectors<P>(as_const(rows) + (size_t)first * STRIDE, n, w);
   if (live && n) atomicMin(&pen_best[(size_t)part * DEV_MAX_AFF + a], pen);
 }
 
@@ -506,6 +549,46 @@ __global__ void __launch_bounds__(BLOCK) k_winner_rows(const uint32_t *__restric
   }
 }
 
+struct ExpandArgs {
+  const uint64_t *base;         // [partition of the pass] cost without penalties, ~0 = does not fit
+  const uint32_t *weights;      // [partition of the pass][affected stage][8]
+  const uint32_t *rows[DEV_MAX_AFF];
+  uint64_t R[DEV_MAX_AFF];      // valid reroute vectors per affected stage
+  int32_t stride[DEV_MAX_AFF], peers[DEV_MAX_AFF];
+  int32_t n_aff;
+  uint64_t R_joint, K;
+  uint64_t local_first, count;  // plan indices local to the family
+  uint64_t part_base;           // first partition of the pass
+  int64_t *costs;
+};
+
+// one lane per plan index: split the index into (partition, per-stage reroute ranks), look the
+// vectors up, add the penalties to the partition's base cost, store (coalesced)
+__global__ void __launch_bounds__(BLOCK) k_expand(ExpandArgs a) {
+  const uint64_t gid = (uint64_t)blockIdx.x * BLOCK + threadIdx.x;
+  if (gid >= a.count) return;
+  const uint64_t local = a.local_first + gid;
+  const uint64_t part = local / a.R_joint;
+  uint64_t rr = local - part * a.R_joint;
+  const uint64_t pl = part - a.part_base;
+  const uint64_t base = a.base[pl];
+  uint64_t pen = 0;
+  for (int s = a.n_aff - 1; s >= 0; --s) {          // last affected stage is least significant
+    const uint64_t q = rr / a.R[s];
+    const uint64_t r = rr - q * a.R[s];
+    rr = q;
+    const uint32_t *row = a.rows[s] + r * (uint64_t)a.stride[s];
+    const uint32_t *w = a.weights + pl * (DEV_MAX_AFF * 8) + s * 8;
+    uint32_t m = 0;
+    for (int i = 0; i < a.peers[s]; ++i) {
+      const uint32_t v = base != ~0ull ? __umul24(row[i], w[i]) : 0u;
+      m = m > v ? m : v;
+    }
+    pen += m;
+  }
+  a.costs[gid] = base == ~0ull ? CHM_INF_COST : (int64_t)(base + a.K * pen);
+}
+
 __global__ void k_fill_u32(uint32_t *p, uint32_t n, uint32_t v) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -532,10 +615,10 @@ int by_peers(int p, Fn fn) {
 }
 
 template <int STRAT>
-int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, hipStream_t st) {
+int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, uint32_t tile_bytes, hipStream_t st) {
 #define CHM_CASE(SPV)                                                                         \
   case SPV:                                                                                   \
-    hipLaunchKernelGGL((k_fast_search<SPV, STRAT>), dim3(blocks), dim3(BLOCK), 0, st, a);     \
+    hipLaunchKernelGGL((k_fast_search<SPV, STRAT>), dim3(blocks), dim3(BLOCK), tile_bytes, st, a); \
     return 0;
   switch (sp) {
     CHM_CASE(2) CHM_CASE(3) CHM_CASE(4) CHM_CASE(5) CHM_CASE(6) CHM_CASE(7) CHM_CASE(8)
@@ -627,7 +710,7 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     }
     up = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
   }
-  if (up && f->split) {
+  if (up && f->usable[2] && h.n_aff > 0) {
     up = up && hipMalloc((void **)&f->d_base, (size_t)FAST_SUB * sizeof(uint64_t)) == hipSuccess;
     up = up && hipMalloc((void **)&f->d_weights, (size_t)FAST_SUB * DEV_MAX_AFF * 8 * sizeof(uint32_t)) == hipSuccess;
     up = up && hipMalloc((void **)&f->d_pen, (size_t)FAST_SUB * DEV_MAX_AFF * sizeof(uint32_t)) == hipSuccess;
@@ -650,15 +733,17 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   const uint64_t lanes_wanted = 256ull * 4 * 8 * 64;
   uint64_t per = a.part_count / lanes_wanted;
   per = std::max<uint64_t>(1, std::min<uint64_t>(per, 32));
-  if (a.ranks != nullptr || a.costs_out != nullptr) per = 1;     // one partition per lane: coalesced cost stores
+  if (a.ranks != nullptr) per = 1;                               // a list has no successor to walk to
+  else if (a.costs_out != nullptr) per = std::min<uint64_t>(per, 8);   // bounds the LDS tile of the cost store
   fl.per_lane = (uint32_t)per;
+  const uint32_t tile_bytes = (a.costs_out != nullptr && per > 1) ? (uint32_t)(BLOCK * per * sizeof(int64_t)) : 0u;
   const uint64_t lanes = (a.part_count + per - 1) / per;
   const uint32_t blocks = (uint32_t)((lanes + BLOCK - 1) / BLOCK);
   const int sp = h.fam[a.strategy].stages;
   int rc;
-  if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, st);
-  else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, st);
-  else rc = launch_by_stages<2>(sp, fl, blocks, st);
+  if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, tile_bytes, st);
+  else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, tile_bytes, st);
+  else rc = launch_by_stages<2>(sp, fl, blocks, tile_bytes, st);
   if (rc) return rc;
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
@@ -741,6 +826,62 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
   }
   hipLaunchKernelGGL(k_keys_to_ranks, dim3(1), dim3(64), 0, st, f->d_rowkey, d_out, h.n_aff);
   return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t local_first,
+                       uint64_t count, int64_t *d_costs, void *stream) {
+  if (!f->usable[2] || h.n_aff == 0 || !f->d_base) return 1;
+  if (count == 0) return 0;
+  hipStream_t st = (hipStream_t)stream;
+  const FastTables &t = f->h_tables;
+  const uint64_t R = h.fam[2].n_reroute;
+  ExpandArgs e;
+  memset(&e, 0, sizeof(e));
+  e.base = f->d_base;
+  e.weights = f->d_weights;
+  e.n_aff = h.n_aff;
+  for (int s = 0; s < h.n_aff; ++s) {
+    e.rows[s] = f->d_vecs + t.vec_off[s];
+    e.R[s] = h.aff_R[s];
+    e.stride[s] = h.aff_peers[s] <= 4 ? 4 : 8;
+    e.peers[s] = h.aff_peers[s];
+  }
+  e.R_joint = R;
+  e.K = (uint64_t)h.K;
+  const uint64_t last = local_first + count - 1;
+  const uint64_t part_lo = local_first / R, part_hi = last / R;
+  for (uint64_t p = part_lo; p <= part_hi; p += FAST_SUB) {
+    const uint64_t np = std::min<uint64_t>(FAST_SUB, part_hi - p + 1);
+    SearchLaunch sub;
+    memset(&sub, 0, sizeof(sub));
+    sub.scn = d_scn;
+    sub.strategy = 2;
+    sub.part_first = p;
+    sub.part_count = (uint32_t)np;
+    sub.idx_bits = 1;
+    sub.result = f->d_rowkey;            // not written in this mode
+    sub.feasible = f->d_rowkey + 1;      // scratch counter, not read
+    int rc = launch_search(f, h, sub, f->d_base, f->d_weights, st);
+    if (rc) return rc;
+    // the plan indices of this pass: those of partitions [p, p+np) clipped to the request
+    const uint64_t lo = std::max<uint64_t>(local_first, p * R);
+    const uint64_t hi = std::min<uint64_t>(last, (p + np) * R - 1);
+    e.local_first = lo;
+    e.count = hi - lo + 1;
+    e.part_base = p;
+    e.costs = d_costs + (lo - local_first);
+    for (uint64_t done = 0; done < e.count;) {       // keep each grid below 2^31 blocks
+      ExpandArgs part = e;
+      part.local_first = e.local_first + done;
+      part.count = std::min<uint64_t>(e.count - done, 1ull << 36);
+      part.costs = e.costs + done;
+      const uint32_t blocks = (uint32_t)((part.count + BLOCK - 1) / BLOCK);
+      hipLaunchKernelGGL(k_expand, dim3(blocks), dim3(BLOCK), 0, st, part);
+      done += part.count;
+    }
+    if (hipGetLastError() != hipSuccess) return -1;
+  }
+  return 0;
 }
 
 void fast_release(FastState *f) {

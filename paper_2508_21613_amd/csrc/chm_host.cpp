@@ -521,6 +521,11 @@ extern "C" int chm_score_plans(chm_scenario *s, uint64_t first, uint64_t count, 
       if (rc) return rc;
       continue;
     }
+    {
+      const int rc = f.strategy == 2 ? fast_score_reroute(&s->fast, s->h, s->d_scn, a - fb, b - a, d_costs + (a - first), hip_stream) : 1;
+      if (rc < 0) return CHM_ERR_HIP;
+      if (rc == 0) continue;             // > 0: shape not covered, the generic kernel below scores it
+    }
     // split very long ranges so that the grid stays within 2^31 blocks
     for (uint64_t p = a; p < b;) {
       const uint64_t n = std::min<uint64_t>(b - p, 1ull << 36);
@@ -622,6 +627,16 @@ extern "C" int chm_family_classes(const chm_scenario *s, int32_t strategy, int32
   const DevFamily &f = s->h.fam[strategy];
   *n = f.n_cls;
   for (int i = 0; i < f.n_cls; ++i) { length[i] = f.cls[i].n; micro_batches[i] = f.cls[i].M; }
+  return CHM_OK;
+}
+
+extern "C" int chm_reroute_shape(const chm_scenario *s, int32_t *n_affected, int32_t *peers, uint64_t *n_vectors) {
+  if (!s || !n_affected || !peers || !n_vectors) return CHM_ERR_ARG;
+  *n_affected = s->h.n_aff;
+  for (int a = 0; a < DEV_MAX_AFF; ++a) {
+    peers[a] = a < s->h.n_aff ? s->h.aff_peers[a] : 0;
+    n_vectors[a] = a < s->h.n_aff ? s->h.aff_R[a] : 0;
+  }
   return CHM_OK;
 }
 
