@@ -34,6 +34,11 @@ struct FastTables {
   // 4 (up to 4 peers) or 8 dwords, and the row count is padded to a multiple of 4
   uint32_t vec_off[DEV_MAX_AFF];  // offset (in uint32) of stage a's rows in vecs[]
   uint32_t vec_rows[DEV_MAX_AFF]; // rows including the padding
+  // the same vectors as runs: all vectors that share their first P-2 entries are consecutive in
+  // rank order, the entry before last counts up from `lo` and the last one down.  A run is 8
+  // dwords: [0..5] the shared entries, [6] = lo | (sum of the last two entries << 16), [7] = length
+  uint32_t run_off[DEV_MAX_AFF];  // offset (in uint32) of stage a's runs in runs[]
+  uint32_t run_count[DEV_MAX_AFF];
 };
 
 struct FastState {
@@ -42,6 +47,7 @@ struct FastState {
   FastTables h_tables;
   FastTables *d_tables = nullptr;
   uint32_t *d_vecs = nullptr;
+  uint32_t *d_runs = nullptr;
   // scratch of the split path, FAST_SUB partitions at a time
   uint64_t *d_base = nullptr;               // cost without penalties, ~0 for a partition that does not fit
   uint32_t *d_weights = nullptr;            // [partition][affected stage][8] peer stage times

@@ -128,26 +128,61 @@ __device__ __forceinline__ int class_time(ClsPtr c, int (&F)[N], int (&B)[N]) {
   return makespan32<N>(F, B, c->M) + c->comm_total;
 }
 
-// min over all reroute vectors of one stage of max_i r_i * w_i.  Rows are stored with a
-// stride of 4 (P <= 4) or 8 dwords and the row count is padded to a multiple of 4 with rows
-// that put every orphaned micro-batch on every peer (never better than a valid row), so four
-// rows are fetched by one wide scalar load and scored back to back.
+// min over all reroute vectors of one stage of max_i r_i * w_i, run by run (see FastTables):
+// within a run only the last two entries change, by +1 and -1, so their products are carried
+// by an add and a subtract and every vector costs those two, one v_max3_u32 and a share of a
+// v_min3_u32.  Runs are read through scalar loads; all control flow is uniform.
 template <int P>
-__device__ __forceinline__ uint32_t sweep_vectors(RowPtr rows, uint32_t n_rows_padded, const uint32_t (&w)[P]) {
-  constexpr int STRIDE = P <= 4 ? 4 : 8;
+__device__ __forceinline__ uint32_t sweep_runs(RowPtr runs, uint32_t n_runs, const uint32_t (&w)[P]) {
   uint32_t best = 0xffffffffu;
-  for (uint32_t r = 0; r < n_rows_padded; r += 4) {
-    RowPtr row = rows + (size_t)r * STRIDE;
+  if (P == 1) {                       // a single peer takes everything: one vector, one run of length 1
+    if (n_runs) best = __umul24(runs[6] >> 16, w[0]);
+    return best;
+  }
+  constexpr int Q = P >= 2 ? P - 2 : 0;
+  const uint32_t wa = w[P >= 2 ? P - 2 : 0], wb = w[P - 1];
+  if (n_runs == 0) return best;
+  // the descriptor of the next run is fetched while the current one is swept
+  uint32_t d[8];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      uint32_t pen = 0;
+  for (int i = 0; i < 8; ++i) d[i] = runs[i];
+  for (uint32_t r = 0; r < n_runs; ++r) {
+    uint32_t nx[8];
+    RowPtr nd = runs + (size_t)(r + 1 < n_runs ? r + 1 : r) * 8;
 #pragma unroll
-      for (int i = 0; i < P; ++i) {
-        const uint32_t v = __umul24(row[u * STRIDE + i], w[i]);
-        pen = pen > v ? pen : v;
-      }
-      best = best < pen ? best : pen;
+    for (int i = 0; i < 8; ++i) nx[i] = nd[i];
+    uint32_t pre = 0;
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+      const uint32_t v = __umul24(d[i], w[i]);
+      pre = pre > v ? pre : v;
     }
+    const uint32_t lo = d[6] & 0xffffu, rem = d[6] >> 16;
+    uint32_t cnt = d[7];
+    uint32_t x = __umul24(lo, wa), y = __umul24(rem - lo, wb);
+    // the shared entries' maximum is the same for the whole run: it is folded in once, after the
+    // minimum over the run of max(x, y).  The two products are stepped with one add and one
+    // subtract per vector (kept as written: the compiler would otherwise rebuild each of them
+    // from multiples of the step, which costs more instructions).
+    uint32_t run_best = 0xffffffffu;
+    for (; cnt >= 4; cnt -= 4) {
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const uint32_t pen = x > y ? x : y;
+        run_best = run_best < pen ? run_best : pen;
+        asm volatile("v_add_u32 %0, %0, %2\n\tv_sub_u32 %1, %1, %3" : "+v"(x), "+v"(y) : "v"(wa), "v"(wb));
+      }
+    }
+    for (; cnt > 0; --cnt) {
+      const uint32_t pen = x > y ? x : y;
+      run_best = run_best < pen ? run_best : pen;
+      x += wa;
+      y -= wb;
+    }
+    run_best = run_best > pre ? run_best : pre;
+    best = best < run_best ? best : run_best;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) d[i] = nx[i];
   }
   return best;
 }
@@ -175,6 +210,7 @@ struct FastLaunch {
   SearchLaunch s;
   const FastTables *tab;
   const uint32_t *vecs;
+  const uint32_t *runs;
   uint32_t per_lane;            // consecutive partition ranks per lane
   // split rerouting path: instead of sweeping the reroute vectors itself the kernel stores, per
   // partition, the cost without penalties and the peer stage times (null: fused sweep)
@@ -350,8 +386,8 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
             b_st = sa == j ? bs[j] : b_st;
           }
           const int p = scn->aff_peers[st];
-          const RowPtr rows = as_const(a.vecs) + tab->vec_off[st];
-          const uint32_t n_rows = tab->vec_rows[st];
+          const RowPtr runs = as_const(a.runs) + tab->run_off[st];
+          const uint32_t n_runs = tab->run_count[st];
           uint32_t pen = 0;
 #define CHM_SWEEP(P)                                                                            \
   case P: {                                                                                     \
@@ -360,7 +396,7 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
       const uint32_t q = scn->aff_q[st][i];                                                     \
       w[i] = (uint32_t)(scale32(f_st, q) + scale32(b_st, q));                                   \
     }                                                                                           \
-    pen = sweep_vectors<P>(rows, n_rows, w);                                                    \
+    pen = sweep_runs<P>(runs, n_runs, w);                                                       \
   } break;
           switch (p) {
             CHM_SWEEP(1) CHM_SWEEP(2) CHM_SWEEP(3) CHM_SWEEP(4)
@@ -474,21 +510,20 @@ __global__ void __launch_bounds__(BLOCK) k_make_rows(const DevScenario *__restri
   }
 }
 
-// best penalty of one affected stage for 256 partitions (one per lane) over one chunk of rows
+// best penalty of one affected stage for 256 partitions (one per lane) over one chunk of runs
 template <int P>
-__global__ void __launch_bounds__(BLOCK) k_sweep(const uint32_t *__restrict__ rows, uint32_t n_rows_padded, uint32_t rows_per_chunk,
+__global__ void __launch_bounds__(BLOCK) k_sweep(const uint32_t *__restrict__ runs, uint32_t n_runs, uint32_t runs_per_chunk,
                                                  const uint64_t *__restrict__ base, const uint32_t *__restrict__ weights,
                                                  uint32_t *__restrict__ pen_best, uint32_t part_count, int a) {
-  constexpr int STRIDE = P <= 4 ? 4 : 8;
   const uint32_t part = blockIdx.x * BLOCK + threadIdx.x;
   const bool live = part < part_count && base[part < part_count ? part : 0] != ~0ull;
   if (__builtin_amdgcn_ballot_w64(live) == 0) return;       // a wave of partitions that do not fit
   uint32_t w[P];
 #pragma unroll
   for (int i = 0; i < P; ++i) w[i] = live ? weights[(size_t)part * (DEV_MAX_AFF * 8) + a * 8 + i] : 1u;
-  const uint32_t first = blockIdx.y * rows_per_chunk;
-  const uint32_t n = first >= n_rows_padded ? 0u : (n_rows_padded - first < rows_per_chunk ? n_rows_padded - first : rows_per_chunk);
-  const uint32_t pen = sweep_vectors<P>(as_const(rows) + (size_t)first * STRIDE, n, w);
+  const uint32_t first = blockIdx.y * runs_per_chunk;
+  const uint32_t n = first >= n_runs ? 0u : (n_runs - first < runs_per_chunk ? n_runs - first : runs_per_chunk);
+  const uint32_t pen = sweep_runs<P>(as_const(runs) + (size_t)first * 8, n, w);
   if (live && n) atomicMin(&pen_best[(size_t)part * DEV_MAX_AFF + a], pen);
 }
 
@@ -699,7 +734,68 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     }
     f->usable[k] = ok;
   }
+  // run tables (host enumeration in rank order: shared entries lexicographic, see FastTables)
+  std::vector<uint32_t> runs;
+  if (f->usable[2]) {
+    for (int a = 0; a < h.n_aff && f->usable[2]; ++a) {
+      int same = -1;
+      for (int b = 0; b < a; ++b)
+        if (h.aff_peers[b] == h.aff_peers[a] && h.aff_total[b] == h.aff_total[a]) same = b;
+      if (same >= 0) { t->run_off[a] = t->run_off[same]; t->run_count[a] = t->run_count[same]; continue; }
+      const int p = h.aff_peers[a], total = h.aff_total[a];
+      const int cap = h.rcap > 0 ? h.rcap : total;
+      t->run_off[a] = (uint32_t)runs.size();
+      uint64_t vectors = 0;
+      uint32_t n_runs = 0;
+      const int q = p >= 2 ? p - 2 : 0;                    // shared entries per run
+      std::vector<int> pre(q + 1, 0);
+      // odometer over the shared entries in lexicographic order
+      int rem = total;
+      int pos = 0;
+      bool fresh = true;                                   // entering position `pos` from the left
+      for (;;) {
+        if (pos == q) {
+          const int tail = p >= 2 ? 2 : 1;                 // entries left to fill
+          const int lo = p >= 2 ? std::max(0, rem - cap) : rem, hi = p >= 2 ? std::min(cap, rem) : rem;
+          if (lo <= hi && rem <= tail * cap) {
+            uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int i = 0; i < q; ++i) d[i] = (uint32_t)pre[i];
+            d[6] = (uint32_t)lo | ((uint32_t)rem << 16);
+            d[7] = (uint32_t)(hi - lo + 1);
+            runs.insert(runs.end(), d, d + 8);
+            vectors += d[7];
+            ++n_runs;
+          }
+          // step back to the previous position and advance it
+          --pos;
+          if (pos < 0) break;
+          rem += pre[pos];
+          ++pre[pos];
+          fresh = false;
+          continue;
+        }
+        if (fresh) pre[pos] = 0;
+        if (pre[pos] > std::min(cap, rem)) {               // exhausted this position
+          --pos;
+          if (pos < 0) break;
+          rem += pre[pos];
+          ++pre[pos];
+          fresh = false;
+          continue;
+        }
+        rem -= pre[pos];
+        ++pos;
+        fresh = true;
+      }
+      t->run_count[a] = n_runs;
+      if (vectors != h.aff_R[a]) f->usable[2] = false;     // table and count must agree
+    }
+    if (!f->usable[2]) f->split = false;
+  }
+  if (runs.empty()) runs.assign(8, 0);
   bool up = hipMalloc((void **)&f->d_tables, sizeof(FastTables)) == hipSuccess;
+  up = up && hipMalloc((void **)&f->d_runs, runs.size() * sizeof(uint32_t)) == hipSuccess;
+  up = up && hipMemcpy(f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
   up = up && hipMalloc((void **)&f->d_vecs, vec_words * sizeof(uint32_t)) == hipSuccess;
   up = up && hipMemcpy(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice) == hipSuccess;
   if (up && f->usable[2]) {
@@ -727,6 +823,7 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   fl.s = a;
   fl.tab = f->d_tables;
   fl.vecs = f->d_vecs;
+  fl.runs = f->d_runs;
   fl.base_out = base_out;
   fl.weights_out = weights_out;
   // enough lanes to fill 256 CUs with several waves per SIMD, runs long enough to amortise unranking
@@ -769,17 +866,16 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
     hipLaunchKernelGGL(k_fill_u32, dim3((n_pen + 255) / 256), dim3(256), 0, st, f->d_pen, n_pen, 0xffffffffu);
     const uint32_t bx = (sub.part_count + BLOCK - 1) / BLOCK;
     for (int s = 0; s < h.n_aff; ++s) {
-      const uint32_t n_rows = t.vec_rows[s];
-      // about 8192 workgroups in total, chunks of at least 1024 rows, multiples of 4
-      uint32_t chunks = std::max<uint32_t>(1, std::min<uint32_t>(8192 / bx + 1, n_rows / 1024 + 1));
+      const uint32_t n_runs = t.run_count[s];
+      // about 8192 workgroups in total, chunks of at least 64 runs
+      uint32_t chunks = std::max<uint32_t>(1, std::min<uint32_t>(8192 / bx + 1, n_runs / 64 + 1));
       chunks = std::min<uint32_t>(chunks, 65535);
-      uint32_t per_chunk = (n_rows + chunks - 1) / chunks;
-      per_chunk = (per_chunk + 3) / 4 * 4;
-      chunks = (n_rows + per_chunk - 1) / per_chunk;
-      const uint32_t *rows = f->d_vecs + t.vec_off[s];
+      const uint32_t per_chunk = (n_runs + chunks - 1) / chunks;
+      chunks = (n_runs + per_chunk - 1) / per_chunk;
+      const uint32_t *runs = f->d_runs + t.run_off[s];
       rc = by_peers(h.aff_peers[s], [&](auto tag) {
         constexpr int P = decltype(tag)::value;
-        hipLaunchKernelGGL((k_sweep<P>), dim3(bx, chunks), dim3(BLOCK), 0, st, rows, n_rows, per_chunk, f->d_base,
+        hipLaunchKernelGGL((k_sweep<P>), dim3(bx, chunks), dim3(BLOCK), 0, st, runs, n_runs, per_chunk, f->d_base,
                            f->d_weights, f->d_pen, sub.part_count, s);
         return 0;
       });
@@ -890,8 +986,10 @@ void fast_release(FastState *f) {
   if (f->d_weights) (void)hipFree(f->d_weights);
   if (f->d_base) (void)hipFree(f->d_base);
   if (f->d_vecs) (void)hipFree(f->d_vecs);
+  if (f->d_runs) (void)hipFree(f->d_runs);
   if (f->d_tables) (void)hipFree(f->d_tables);
   f->d_rowkey = nullptr; f->d_pen = nullptr; f->d_weights = nullptr; f->d_base = nullptr;
   f->d_vecs = nullptr;
+  f->d_runs = nullptr;
   f->d_tables = nullptr;
 }
