@@ -223,7 +223,7 @@ extern "C" void orc_layout_p0(int32_t L, int32_t S, int32_t *bounds) {
 // ---------------------------------------------------------------------------------------
 struct orc_scenario {
   int L, S, D, M;
-  std::vector<int64_t> fwd, bwd, mem, pf, pb, pw;       // prefix sums have L+1 entries
+  std::vector<int64_t> fwd, bwd, mem, pf, pb, pw, pa;   // prefix sums have L+1 entries (pa: activations)
   std::vector<uint32_t> q;                              // [D*S]
   std::vector<char> failed;                             // [D*S]
   int64_t comm, cap, K, reconf[3], xfer;
@@ -250,7 +250,7 @@ const orc_family *family_of(const orc_scenario *s, int strategy) {
   return nullptr;
 }
 
-struct StageSums { std::vector<int64_t> f, b, m; std::vector<int> lo; };
+struct StageSums { std::vector<int64_t> f, b, m, a; std::vector<int> lo; };
 
 StageSums stage_sums(const orc_scenario *s, int k, const uint8_t *cuts) {
   StageSums r;
@@ -261,9 +261,14 @@ StageSums stage_sums(const orc_scenario *s, int k, const uint8_t *cuts) {
     r.f.push_back(s->pf[r.lo[j + 1]] - s->pf[r.lo[j]]);
     r.b.push_back(s->pb[r.lo[j + 1]] - s->pb[r.lo[j]]);
     r.m.push_back(s->pw[r.lo[j + 1]] - s->pw[r.lo[j]]);
+    r.a.push_back(s->pa[r.lo[j + 1]] - s->pa[r.lo[j]]);
   }
   return r;
 }
+
+// peak memory of the node at position i of an n-stage pipeline (Memory Estimator,
+// eq. (peak_memory_decomposed)): static part + (n - i) micro-batches' worth of activations
+int64_t peak_memory(int64_t static_mib, int64_t act_mib, int n, int i) { return static_mib + (int64_t)(n - i) * act_mib; }
 
 bool cuts_valid(const orc_scenario *s, int k, const uint8_t *cuts) {
   int prev = 0;
@@ -279,7 +284,7 @@ int64_t healthy_step_B(const orc_scenario *s) {
     if (s->fail_in_replica[d]) continue;
     std::vector<int64_t> F(s->S), B(s->S);
     for (int j = 0; j < s->S; ++j) {
-      if (s->pw[s->p0[j + 1]] - s->pw[s->p0[j]] > s->cap) return ORC_INF;
+      if (peak_memory(s->pw[s->p0[j + 1]] - s->pw[s->p0[j]], s->pa[s->p0[j + 1]] - s->pa[s->p0[j]], s->S, j) > s->cap) return ORC_INF;
       F[j] = orc_scale_q16(s->pf[s->p0[j + 1]] - s->pf[s->p0[j]], s->qof(d, j));
       B[j] = orc_scale_q16(s->pb[s->p0[j + 1]] - s->pb[s->p0[j]], s->qof(d, j));
     }
@@ -297,8 +302,15 @@ int64_t base_cost_terms(const orc_scenario *s, int strategy, int k, const uint8_
   StageSums st = stage_sums(s, k, cuts);
   int64_t t_step = 0, missing = 0;
   if (strategy == 0) {            // redundant computation: own stage + successor's on every node
-    for (int j = 0; j < S; ++j)
-      if (st.m[j] + st.m[(j + 1) % S] > s->cap) return ORC_INF;
+    for (int d = 0; d < s->D; ++d) {        // every surviving node holds its own stage and its successor's
+      int n = S - s->fail_in_replica[d], pos = 0;
+      for (int j = 0; j < S; ++j) {
+        if (s->dead(d, j)) continue;
+        int nx = (j + 1) % S;
+        if (peak_memory(st.m[j] + st.m[nx], st.a[j] + st.a[nx], n, pos) > s->cap) return ORC_INF;
+        ++pos;
+      }
+    }
     for (int d = 0; d < s->D; ++d) {
       std::vector<int64_t> F, B;
       for (int j = 0; j < S; ++j) {
@@ -314,7 +326,7 @@ int64_t base_cost_terms(const orc_scenario *s, int strategy, int k, const uint8_
       missing += orc_missing_interval(s->pw.data(), st.lo[j], st.lo[j + 1], s->p0[j], s->p0[j + 1]);
   } else if (strategy == 1) {     // failed pipelines re-partitioned onto their surviving nodes
     const int SB = s->SB;
-    for (int j = 0; j < SB; ++j) if (st.m[j] > s->cap) return ORC_INF;
+    for (int j = 0; j < SB; ++j) if (peak_memory(st.m[j], st.a[j], SB, j) > s->cap) return ORC_INF;
     t_step = healthy_step_B(s);
     if (t_step == ORC_INF) return ORC_INF;
     for (int d = 0; d < s->D; ++d) {
@@ -332,7 +344,7 @@ int64_t base_cost_terms(const orc_scenario *s, int strategy, int k, const uint8_
       missing = std::max(missing, miss_d);   // pipelines move their weights in parallel
     }
   } else {                        // data rerouting: every pipeline keeps S stages and M micro-batches
-    for (int j = 0; j < S; ++j) if (st.m[j] > s->cap) return ORC_INF;
+    for (int j = 0; j < S; ++j) if (peak_memory(st.m[j], st.a[j], S, j) > s->cap) return ORC_INF;
     for (int d = 0; d < s->D; ++d) {
       std::vector<int64_t> F(S), B(S);
       for (int j = 0; j < S; ++j) {
@@ -481,13 +493,15 @@ extern "C" int orc_open(const orc_desc *d, orc_scenario **out) {
   s->comm = d->comm_us; s->cap = d->mem_cap_mib; s->K = d->horizon_steps; s->xfer = d->xfer_us_per_mib;
   s->reroute_cap = d->reroute_cap;
   for (int i = 0; i < 3; ++i) s->reconf[i] = d->reconf_us[i];
-  s->pf.assign(s->L + 1, 0); s->pb.assign(s->L + 1, 0); s->pw.assign(s->L + 1, 0);
+  s->pf.assign(s->L + 1, 0); s->pb.assign(s->L + 1, 0); s->pw.assign(s->L + 1, 0); s->pa.assign(s->L + 1, 0);
   for (int l = 0; l < s->L; ++l) {
     if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0) { delete s; return ORC_ERR_ARG; }
     s->fwd.push_back(d->fwd_us[l]); s->bwd.push_back(d->bwd_us[l]); s->mem.push_back(d->mem_mib[l]);
     s->pf[l + 1] = s->pf[l] + d->fwd_us[l];
     s->pb[l + 1] = s->pb[l] + d->bwd_us[l];
     s->pw[l + 1] = s->pw[l] + d->mem_mib[l];
+    if (d->act_mib && d->act_mib[l] < 0) { delete s; return ORC_ERR_ARG; }
+    s->pa[l + 1] = s->pa[l] + (d->act_mib ? d->act_mib[l] : 0);
   }
   const int nodes = s->D * s->S;
   uint32_t qmax = 65536;

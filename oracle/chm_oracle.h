@@ -16,7 +16,10 @@
  *     the equation after eq. (original_step_time).
  *   - data rerouting penalty: eq. (recycle_step_time) and (recycle_step_time_multi).
  *   - batch distribution over pipelines: Planner subsection, "Batch Distribution".
- *   - OOM filter: Planner "Layer Distribution" + Memory Estimator.
+ *   - OOM filter: Planner "Layer Distribution" + Memory Estimator, eq. (peak_memory_decomposed):
+ *     peak of the node at position i (0-based) of an n-stage pipeline = static memory of its
+ *     layers + (n - i) x activation memory of its layers; with no activation table the peak
+ *     is the static sum.
  *   - transition time = restart constant + weight transfer: Estimator subsection,
  *     paragraph on dynamic parallelism; negligible for rerouting.
  *   - argmin with first-strict-minimum: Algorithm 1, get_execution_plan.
@@ -50,6 +53,7 @@ typedef struct {
   int32_t comm_us, mem_cap_mib, reroute_cap, horizon_steps;
   int32_t reconf_us[3];
   int32_t xfer_us_per_mib;
+  const int32_t *act_mib;                     /* [L] activation memory per micro-batch in flight; NULL = none */
 } orc_desc;
 
 typedef struct { uint64_t offset, n_part, n_reroute; int32_t stages, strategy; } orc_family;

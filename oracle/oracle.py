@@ -36,7 +36,7 @@ class Desc(C.Structure):
                 ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
                 ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32), ("reroute_cap", C.c_int32),
                 ("horizon_steps", C.c_int32), ("reconf_us", C.c_int32 * 3),
-                ("xfer_us_per_mib", C.c_int32)]
+                ("xfer_us_per_mib", C.c_int32), ("act_mib", C.POINTER(C.c_int32))]
 
 
 class Family(C.Structure):
@@ -211,6 +211,10 @@ class Scenario:
         for i in range(3):
             d.reconf_us[i] = sc["reconf_us"][i]
         d.xfer_us_per_mib = sc["xfer_us_per_mib"]
+        if sc.get("act_mib") is not None:
+            a = np.ascontiguousarray(sc["act_mib"], dtype=np.int32)
+            self._keep.append(a)
+            d.act_mib = _ptr(a, C.c_int32)
         h = C.c_void_p()
         rc = lib().orc_open(C.byref(d), C.byref(h))
         if rc:

@@ -68,7 +68,8 @@ def speed_factors(seed, D, S, lo=0.85, hi=1.15):
 
 
 def scenario(L, PP, DP, M, fwd, bwd, mem, failed, comm_us, mem_cap_mib, speed=None, **kw):
-    sc = dict(L=L, PP=PP, DP=DP, M=M, fwd_us=fwd, bwd_us=bwd, mem_mib=mem, speed_q16=speed,
+    """kw may carry act_mib (per-layer activation memory per micro-batch in flight) and any default override"""
+    sc = dict(L=L, PP=PP, DP=DP, M=M, fwd_us=fwd, bwd_us=bwd, mem_mib=mem, speed_q16=speed, act_mib=None,
               failed_nodes=[int(x) for x in failed], comm_us=comm_us, mem_cap_mib=mem_cap_mib)
     sc.update(DEFAULTS)
     sc.update(kw)
@@ -141,6 +142,14 @@ def random_partitions(seed, stream, n, L, k):
     keys = _mix(seed, stream, n * (L - 1)).reshape(n, L - 1)
     order = np.argsort(keys, axis=1, kind="stable")[:, :k]
     return (np.sort(order, axis=1) + 1).astype(np.uint8)
+
+
+def with_activations(sc, seed, lo=20, hi=60, cap_scale=1.0):
+    """the same scenario with a per-layer activation table U{lo..hi} MiB and a cap raised to leave a
+    comparable share of the partitions feasible under the position-dependent peak"""
+    act = randint(seed, 21, sc["L"], lo, hi).astype(np.int32)
+    extra = int(act.sum()) * (sc["PP"] + 1) // (2 * sc["PP"])
+    return dict(sc, act_mib=act, mem_cap_mib=int((sc["mem_cap_mib"] + extra) * cap_scale))
 
 
 def small_random(seed, L=None, PP=None, DP=None, M=None, n_failed=None, hetero=None, cap=None):

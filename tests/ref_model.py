@@ -105,6 +105,8 @@ class Model:
         self.f = [int(x) for x in sc["fwd_us"]]
         self.b = [int(x) for x in sc["bwd_us"]]
         self.m = [int(x) for x in sc["mem_mib"]]
+        act = sc.get("act_mib")
+        self.a = [int(x) for x in act] if act is not None else [0] * len(self.m)
         q = sc.get("speed_q16")
         self.q = [[int(q[d * self.S + s]) if q is not None else 65536 for s in range(self.S)] for d in range(self.D)]
         self.dead = [[(d * self.S + s) in sc["failed_nodes"] for s in range(self.S)] for d in range(self.D)]
@@ -143,10 +145,19 @@ class Model:
         fs = [self.seg(self.f, bounds[j], bounds[j + 1]) for j in range(n)]
         bs = [self.seg(self.b, bounds[j], bounds[j + 1]) for j in range(n)]
         ms = [self.seg(self.m, bounds[j], bounds[j + 1]) for j in range(n)]
+        av = [self.seg(self.a, bounds[j], bounds[j + 1]) for j in range(n)]
         cap, comm = sc["mem_cap_mib"], sc["comm_us"]
+
+        def peak(static, act, length, pos):      # Memory Estimator: static + (stages - position) x activations
+            return static + (length - pos) * act
+
         if strategy == 0:
-            if any(ms[j] + ms[(j + 1) % S] > cap for j in range(S)):
-                return INF
+            for d in range(D):
+                alive = [j for j in range(S) if not self.dead[d][j]]
+                for pos, j in enumerate(alive):
+                    nx = (j + 1) % S
+                    if peak(ms[j] + ms[nx], av[j] + av[nx], len(alive), pos) > cap:
+                        return INF
             t = 0
             for d in range(D):
                 alive = [j for j in range(S) if not self.dead[d][j]]
@@ -155,12 +166,13 @@ class Model:
                 t = max(t, dag_makespan(F, B, M) + (len(alive) - 1) * comm)
             miss = sum(self.missing(bounds[j], bounds[j + 1], self.p0[j], self.p0[j + 1]) for j in range(S))
         elif strategy == 1:
-            if any(x > cap for x in ms):
+            if any(peak(ms[j], av[j], n, j) > cap for j in range(n)):
                 return INF
             t, miss = 0, 0
             for d in range(D):
                 if self.fail_rep[d] == 0:
-                    if any(self.seg(self.m, self.p0[j], self.p0[j + 1]) > cap for j in range(S)):
+                    if any(peak(self.seg(self.m, self.p0[j], self.p0[j + 1]), self.seg(self.a, self.p0[j], self.p0[j + 1]), S, j) > cap
+                           for j in range(S)):
                         return INF
                     F = [scale(self.seg(self.f, self.p0[j], self.p0[j + 1]), self.q[d][j]) for j in range(S)]
                     B = [scale(self.seg(self.b, self.p0[j], self.p0[j + 1]), self.q[d][j]) for j in range(S)]
@@ -173,7 +185,7 @@ class Model:
                     miss = max(miss, sum(self.missing(bounds[j], bounds[j + 1], self.p0[host[j]], self.p0[host[j] + 1])
                                          for j in range(n)))
         else:
-            if any(x > cap for x in ms):
+            if any(peak(ms[j], av[j], S, j) > cap for j in range(S)):
                 return INF
             t = 0
             for d in range(D):

@@ -424,3 +424,71 @@ def test_generators_are_reproducible_and_in_range():
     assert cuts.shape == (1000, 15) and (np.diff(cuts.astype(int), axis=1) > 0).all()
     assert cuts.min() >= 1 and cuts.max() <= 95
     assert len(synth.config5_failure_sets()) == 32 + 496
+
+
+# ----------------------------------------------------------------------------- memory model
+def mem_scenario(cap, failed=(), S=4, per=3, static=100, act=10, D=2, **kw):
+    L = S * per
+    return synth.scenario(L, S, D, 4, np.full(L, 10, np.int32), np.full(L, 20, np.int32), np.full(L, static, np.int32),
+                          list(failed), 0, cap, act_mib=np.full(L, act, np.int32), reconf_us=(0, 0, 0), xfer_us_per_mib=0, **kw)
+
+
+def test_peak_memory_formula_of_the_paper():
+    """static + (stages - i) x activations per stage, i from 0: the cap that just admits a split is its largest peak"""
+    g = golden()
+    even = [int(x) for x in g["peak_memory_4_stages_3_layers"].split(",")]
+    skew = [int(x) for x in g["peak_memory_split_2_3_3_4"].split(",")]
+    assert even == [3 * 100 + (4 - i) * 3 * 10 for i in range(4)]
+    for cuts, peaks in (([3, 6, 9], even), ([2, 5, 8], skew)):
+        assert O.Scenario(mem_scenario(max(peaks))).plan_cost(2, cuts) != O.INF
+        assert O.Scenario(mem_scenario(max(peaks) - 1)).plan_cost(2, cuts) == O.INF
+    # the binding stage is the first one for the even split and the last one for the skewed split
+    assert O.Scenario(mem_scenario(439)).plan_cost(2, [3, 6, 9]) != O.INF
+    assert O.Scenario(mem_scenario(439)).plan_cost(2, [2, 5, 8]) == O.INF
+
+
+def test_peak_memory_per_strategy():
+    # re-partition onto 3 stages: position counts from the new pipeline length
+    sc = mem_scenario(10 ** 6, failed=[1])
+    s = O.Scenario(sc)
+    assert s.family(1)["stages"] == 3
+    peaks = [4 * 100 + (3 - 0) * 40, 4 * 100 + (3 - 1) * 40, 4 * 100 + (3 - 2) * 40]       # 4 layers per new stage
+    assert O.Scenario(dict(sc, mem_cap_mib=max(peaks))).plan_cost(1, [4, 8]) != O.INF
+    # the healthy pipeline keeps 4 stages of 3 layers: 420 at its first stage, below the 520 of the new layout
+    assert O.Scenario(dict(sc, mem_cap_mib=max(peaks) - 1)).plan_cost(1, [4, 8]) == O.INF
+    # redundant computation: own + successor's layers; in the pipeline that lost stage 1 the chain has 3 nodes
+    # healthy pipeline: node 0 holds stages 0,1: 600 + 4 x 60 = 840 (largest)
+    assert O.Scenario(dict(sc, mem_cap_mib=840)).plan_cost(0, [3, 6, 9]) != O.INF
+    assert O.Scenario(dict(sc, mem_cap_mib=839)).plan_cost(0, [3, 6, 9]) == O.INF
+    # with every pipeline short of a node the chains are 3 long: node 0 at position 0 of 3: 600 + 3 x 60 = 780
+    both = mem_scenario(10 ** 6, failed=[1, 4 + 2])
+    assert O.Scenario(dict(both, mem_cap_mib=780)).plan_cost(0, [3, 6, 9]) != O.INF
+    assert O.Scenario(dict(both, mem_cap_mib=779)).plan_cost(0, [3, 6, 9]) == O.INF
+
+
+def test_no_activation_table_means_static_memory_only():
+    for sc in SMALL[:6]:
+        a = O.Scenario(sc)
+        b = O.Scenario(dict(sc, act_mib=np.zeros(sc["L"], np.int32)))
+        assert (a.score(0, a.n_plans) == b.score(0, b.n_plans)).all()
+
+
+SMALL_ACT = [synth.with_activations(sc, 3000 + i) for i, sc in enumerate(SMALL)]
+
+
+@pytest.mark.parametrize("i", range(len(SMALL_ACT)))
+def test_costs_with_activation_memory_match_the_independent_model(i):
+    sc = SMALL_ACT[i]
+    model = R.Model(sc)
+    s = O.Scenario(sc)
+    want = model.all_costs()
+    got = s.score(0, s.n_plans)
+    assert [int(x) for x in got] == want
+    # activations only ever remove plans, and costs of the remaining ones do not change
+    plain = O.Scenario(dict(sc, act_mib=None)).score(0, s.n_plans)
+    assert ((got == plain) | (got == O.INF)).all()
+    rc, best = s.search(7)
+    if (got == O.INF).all():
+        assert rc == O.ERR_NO_FEASIBLE
+    else:
+        assert rc == 0 and best["index"] == int(np.argmin(got))
