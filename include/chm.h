@@ -44,7 +44,7 @@
  *     of extra micro-batches per surviving peer (entries >= 0, sum = lost nodes * M, each
  *     <= reroute_cap if that is positive).
  *   cost = horizon_steps * t_step + reconf_us[strategy] + xfer_us_per_mib * (MiB of weights
- *     the new layout must fetch); INT64_MAX for a plan that exceeds mem_cap_mib on a stage.
+ *     the new layout must fetch); INT64_MAX for a plan whose peak memory exceeds mem_cap_mib on a node.
  */
 #ifndef CHM_H
 #define CHM_H
@@ -85,6 +85,10 @@ typedef struct {
   int32_t horizon_steps;              /* training steps until the next failure is expected, >= 1     */
   int32_t reconf_us[3];               /* per-strategy restart constant, >= 0                         */
   int32_t xfer_us_per_mib;            /* weight-transfer cost rate, >= 0                             */
+  const int32_t *act_mib;             /* [L] activation memory per micro-batch in flight, each >= 0; NULL = none.
+                                         With it mem_mib is the static part (weights, optimizer states, gradients) and
+                                         the node at position i (from 0) of an n-stage pipeline peaks at
+                                         static + (n - i) * activations (Memory Estimator, eq. peak_memory_decomposed) */
 } chm_scenario_desc;
 
 typedef struct { uint64_t offset, n_part, n_reroute; int32_t stages, strategy; } chm_family;

@@ -28,7 +28,7 @@ class Desc(C.Structure):
                 ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
                 ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32), ("reroute_cap", C.c_int32),
                 ("horizon_steps", C.c_int32), ("reconf_us", C.c_int32 * 3),
-                ("xfer_us_per_mib", C.c_int32)]
+                ("xfer_us_per_mib", C.c_int32), ("act_mib", C.POINTER(C.c_int32))]
 
 
 class Family(C.Structure):
@@ -150,6 +150,10 @@ class Scenario:
         for i in range(3):
             d.reconf_us[i] = sc["reconf_us"][i]
         d.xfer_us_per_mib = sc["xfer_us_per_mib"]
+        if sc.get("act_mib") is not None:
+            a = np.ascontiguousarray(sc["act_mib"], dtype=np.int32)
+            keep.append(a)
+            d.act_mib = a.ctypes.data_as(C.POINTER(C.c_int32))
         self._h = C.c_void_p()
         _check(lib().chm_load_scenario(C.byref(d), C.byref(self._h)))
         sp = Space()

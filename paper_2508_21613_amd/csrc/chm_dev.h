@@ -28,6 +28,11 @@ struct DevFamily {
   int32_t doubled;              // 1: every node also runs its ring successor's stage (strategy 0)
   uint64_t n_part, n_reroute;
   int64_t fixed_step;           // step time of the pipelines the plan does not touch (strategy 1), else 0
+  // peak memory of the node(s) running partition stage j = static + mem_coef[j] * activations, where
+  // mem_coef[j] is the largest (pipeline length - position) over the pipelines that have such a node
+  // (-1: no pipeline has one, the stage is not checked).  For strategy 0 both quantities include the
+  // ring successor's stage.
+  int32_t mem_coef[DEV_MAX_S];
   DevClass cls[DEV_MAX_CLS];
 };
 
@@ -37,7 +42,8 @@ struct DevScenario {
   int64_t reconf[3];
   int32_t p0[DEV_MAX_S + 1];    // fault-free layout: stage j = layers [p0[j], p0[j+1])
   int32_t rcap;                 // reroute cap (<=0: none)
-  int64_t pf[DEV_MAX_L + 1], pb[DEV_MAX_L + 1], pw[DEV_MAX_L + 1];   // prefix sums
+  int64_t pf[DEV_MAX_L + 1], pb[DEV_MAX_L + 1], pw[DEV_MAX_L + 1];   // prefix sums: forward, backward, static memory
+  int64_t pa[DEV_MAX_L + 1];                                          // prefix sums: activation memory
   // rerouting: stages that lost nodes
   int32_t n_aff;
   int32_t aff_stage[DEV_MAX_AFF], aff_peers[DEV_MAX_AFF], aff_total[DEV_MAX_AFF];

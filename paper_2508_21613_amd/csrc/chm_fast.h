@@ -25,6 +25,8 @@ struct FastFamily {
   int32_t fixed_step;             // strategy 1: step time of the untouched pipelines
   int32_t w0[DEV_MAX_S + 1];      // memory prefix at the fault-free stage bounds
   int32_t w_total;                // memory of the whole model
+  int32_t mem_coef[DEV_MAX_S];    // see DevFamily::mem_coef
+  int32_t has_act;                // 0: no activation table, the peak is the static sum
   FastClass cls[DEV_MAX_CLS];
 };
 

@@ -221,7 +221,7 @@ struct FastLaunch {
 template <int SP, int STRAT>
 __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
   constexpr int K = SP - 1;
-  __shared__ int4 T[DEV_MAX_L + 1];            // prefix sums: forward, backward, memory
+  __shared__ int4 T[DEV_MAX_L + 1];            // prefix sums: forward, backward, static memory, activation memory
   __shared__ uint64_t BN[(K > 0 ? K : 1) * DEV_MAX_L];   // BN[(i-1)*128 + x] = C(x, i), i = 1..K
   __shared__ uint64_t wave_keys[BLOCK / 64];
   extern __shared__ int64_t cost_tile[];       // BLOCK * per_lane costs when a cost store with per_lane > 1 is asked for
@@ -229,7 +229,7 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
   const TabPtr tab = as_const(a.tab);
   const FamPtr ff = &tab->fam[STRAT];
   const int L = scn->L;
-  for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], 0);
+  for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], (int)scn->pa[i]);
   for (int i = threadIdx.x; i < K * DEV_MAX_L; i += BLOCK) BN[i] = scn->binom[1 + i / DEV_MAX_L][i % DEV_MAX_L];
   __syncthreads();
 
@@ -279,7 +279,7 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
 
   for (uint32_t it = 0; it < a.per_lane; ++it) {
     // ---- stage sums from the LDS prefix table
-    int fs[SP], bs[SP], ms[SP];
+    int fs[SP], bs[SP], ms[SP], as[SP];
     {
       int4 lo = make_int4(0, 0, 0, 0);
 #pragma unroll
@@ -288,15 +288,28 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
         fs[j] = hi.x - lo.x;
         bs[j] = hi.y - lo.y;
         ms[j] = hi.z - lo.z;
+        as[j] = hi.w - lo.w;
         lo = hi;
       }
     }
     // ---- memory filter
     int mmax = 0;
+    if (ff->has_act) {
 #pragma unroll
-    for (int j = 0; j < SP; ++j) {
-      const int m = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
-      mmax = imax32(mmax, m);
+      for (int j = 0; j < SP; ++j) {
+        // peak = static + (pipeline length - position) * activations of the most demanding node of stage j
+        const int coef = ff->mem_coef[j];
+        const int st = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
+        const int ac = STRAT == 0 ? as[j] + as[(j + 1) % SP] : as[j];
+        const int m = st + (int)__umul24((uint32_t)ac, (uint32_t)(coef < 0 ? 0 : coef));
+        mmax = imax32(mmax, coef < 0 ? 0 : m);
+      }
+    } else {
+#pragma unroll
+      for (int j = 0; j < SP; ++j) {
+        const int m = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
+        mmax = imax32(mmax, ff->mem_coef[j] < 0 ? 0 : m);
+      }
     }
     const bool ok = (mmax <= cap) && (it < run_len) && listed_ok;
     uint64_t cost = (uint64_t)CHM_INF_COST;
@@ -671,6 +684,9 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
   for (bool &u : f->usable) u = false;
   f->split = false;
   if (!int32_ok) return 0;
+  // memory side of the int32 kernels: doubled static sums plus the largest activation term stay below
+  // 2^31, and the (doubled) activation sums fit the 24-bit multiply
+  if (2 * h.pw[h.L] + 2 * h.pa[h.L] * (int64_t)DEV_MAX_S >= (1ll << 31) || 2 * h.pa[h.L] >= (1ll << 24)) return 0;
   // 24-bit multiplies in the reroute sweep need peer stage times below 2^24
   uint32_t q_aff = 65536;
   for (int a = 0; a < h.n_aff; ++a)
@@ -688,6 +704,8 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     ff.n_cls = fam.n_cls;
     ff.fixed_step = (int32_t)fam.fixed_step;
     ff.w_total = (int32_t)h.pw[h.L];
+    for (int j = 0; j < DEV_MAX_S; ++j) ff.mem_coef[j] = fam.mem_coef[j];
+    ff.has_act = h.pa[h.L] > 0 ? 1 : 0;
     for (int j = 0; j <= h.S; ++j) ff.w0[j] = (int32_t)h.pw[h.p0[j]];
     for (int ci = 0; ci < fam.n_cls && ok; ++ci) {
       const DevClass &c = fam.cls[ci];

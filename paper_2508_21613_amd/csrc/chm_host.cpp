@@ -119,7 +119,7 @@ int validate(const chm_scenario_desc *d) {
   if (d->comm_us < 0 || d->mem_cap_mib < 1 || d->horizon_steps < 1 || d->xfer_us_per_mib < 0) return CHM_ERR_ARG;
   for (int i = 0; i < 3; ++i) if (d->reconf_us[i] < 0) return CHM_ERR_ARG;
   for (int l = 0; l < d->L; ++l)
-    if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0) return CHM_ERR_ARG;
+    if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0 || (d->act_mib && d->act_mib[l] < 0)) return CHM_ERR_ARG;
   const int nodes = d->DP * d->PP;
   if (d->speed_q16)
     for (int n = 0; n < nodes; ++n)
@@ -144,6 +144,7 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
     h.pf[l + 1] = h.pf[l] + d->fwd_us[l];
     h.pb[l + 1] = h.pb[l] + d->bwd_us[l];
     h.pw[l + 1] = h.pw[l] + d->mem_mib[l];
+    h.pa[l + 1] = h.pa[l] + (d->act_mib ? d->act_mib[l] : 0);
   }
   for (int sgi = 0, pos = 0; sgi < S; ++sgi) {      // fault-free layout: extra layers on the last stages
     pos += L / S + (sgi >= S - L % S ? 1 : 0);
@@ -254,6 +255,14 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
     }
   }
   if (s->comp.empty()) s->comp.push_back(1);
+  // ---- per partition stage, the largest (pipeline length - position) among the nodes that run it
+  for (int k = 0; k < 3; ++k) {
+    DevFamily &f = h.fam[k];
+    for (int j = 0; j < DEV_MAX_S; ++j) f.mem_coef[j] = -1;
+    for (int ci = 0; ci < f.n_cls; ++ci)
+      for (int j = 0; j < f.cls[ci].n; ++j)
+        f.mem_coef[f.cls[ci].src[j]] = std::max<int32_t>(f.mem_coef[f.cls[ci].src[j]], f.cls[ci].n - j);
+  }
 
   // ---- plan index space
   memset(&s->space, 0, sizeof(s->space));

@@ -95,11 +95,15 @@ __device__ __forceinline__ bool eval_base(const DevScenario *scn, const DevFamil
   bool ok = true;
   for (int j = 0; j < SP; ++j) {
     int64_t m = scn->pw[cuts.get(j + 1)] - scn->pw[cuts.get(j)];
+    int64_t act = scn->pa[cuts.get(j + 1)] - scn->pa[cuts.get(j)];
     if (fam.doubled) {
       const int nx = (j + 1 == SP) ? 0 : j + 1;
       m += scn->pw[cuts.get(nx + 1)] - scn->pw[cuts.get(nx)];
+      act += scn->pa[cuts.get(nx + 1)] - scn->pa[cuts.get(nx)];
     }
-    ok = ok && (m <= scn->cap);
+    // peak = static + (pipeline length - position) * activations, for the most demanding node of this stage
+    const int coef = fam.mem_coef[j];
+    ok = ok && (coef < 0 || m + (int64_t)coef * act <= scn->cap);
   }
   if (!ok) return false;
 
@@ -282,7 +286,7 @@ __global__ void k_fixed_pipelines(DevScenario *scn) {
       F[j] = 0; B[j] = 0;
       if (j < cls.n) {
         const int lo = scn->p0[j], hi = scn->p0[j + 1];
-        if (scn->pw[hi] - scn->pw[lo] > scn->cap) fits = false;
+        if (scn->pw[hi] - scn->pw[lo] + (int64_t)(cls.n - j) * (scn->pa[hi] - scn->pa[lo]) > scn->cap) fits = false;
         F[j] = scale_q16(scn->pf[hi] - scn->pf[lo], cls.q[j]);
         B[j] = scale_q16(scn->pb[hi] - scn->pb[lo], cls.q[j]);
       }

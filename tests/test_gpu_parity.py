@@ -63,9 +63,12 @@ SMALL.append(_two_lost_in_one_pipeline())
 SMALL.append(dict(_two_lost_in_one_pipeline(), failed_nodes=[0, 3, 8], M=3))
 
 
-@pytest.mark.parametrize("i", range(len(SMALL)))
+SMALL_ACT = [synth.with_activations(sc, 3000 + i) for i, sc in enumerate(SMALL)]
+
+
+@pytest.mark.parametrize("i", range(2 * len(SMALL)))
 def test_small_scenarios_every_cost_and_argmin(B, i):
-    sc = SMALL[i]
+    sc = SMALL[i] if i < len(SMALL) else SMALL_ACT[i - len(SMALL)]      # second half: with activation memory
     print("small scenario", i, {k: sc[k] for k in ("L", "PP", "DP", "M", "failed_nodes", "reroute_cap")}, flush=True)
     o = O.Scenario(sc)
     g = B.Scenario(sc)
@@ -111,9 +114,11 @@ def windows(o, rng, n_windows, width):
     return out
 
 
-@pytest.mark.parametrize("name", ["config2", "config3", "config5_single", "config5_double"])
+@pytest.mark.parametrize("name", ["config2", "config3", "config5_single", "config5_double", "config2_act", "config3_act"])
 def test_seeded_windows_of_the_large_configs(B, name):
     sc = {"config2": synth.config2, "config3": synth.config3,
+          "config2_act": lambda: synth.with_activations(synth.config2(), 77),
+          "config3_act": lambda: synth.with_activations(synth.config3(), 78),
           "config5_single": lambda: synth.config5([13]),
           "config5_double": lambda: synth.config5([5, 26])}[name]()
     print(name, "failed", sc["failed_nodes"], flush=True)
