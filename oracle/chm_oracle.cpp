@@ -218,6 +218,54 @@ extern "C" void orc_layout_p0(int32_t L, int32_t S, int32_t *bounds) {
   for (int s = 0; s < S; ++s) bounds[s + 1] = bounds[s] + base + (s >= S - extra ? 1 : 0);
 }
 
+// Kuhn-Munkres (Hungarian) algorithm: minimum total cost of assigning n nodes (rows) to n
+// positions (columns), one to one.  Rows are added one at a time; for each new row the cheapest
+// augmenting path is grown Dijkstra-style over reduced costs cost - u[row] - v[col], the
+// potentials u, v are raised by the step that makes the next column tight, and the matching
+// is flipped along the path once a free column is reached.
+extern "C" int64_t orc_min_assignment(int32_t n, const int64_t *cost, int32_t *position_of_node) {
+  if (n <= 0 || !cost) return 0;
+  const int64_t BIG = INT64_MAX / 4;
+  std::vector<int64_t> u(n, 0), v(n + 1, 0);
+  std::vector<int> row_of_col(n + 1, -1);        // column n is the virtual start column of a new row
+  for (int r = 0; r < n; ++r) {
+    std::vector<int64_t> slack(n + 1, BIG);      // cheapest reduced cost seen so far into each column
+    std::vector<int> prev_col(n + 1, n);         // column from which that cheapest edge leaves (via its row)
+    std::vector<char> in_tree(n + 1, 0);
+    row_of_col[n] = r;
+    int c0 = n;
+    for (;;) {
+      in_tree[c0] = 1;
+      const int r0 = row_of_col[c0];
+      int64_t step = BIG;
+      int c_next = -1;
+      for (int c = 0; c < n; ++c) {
+        if (in_tree[c]) continue;
+        const int64_t red = cost[(size_t)r0 * n + c] - u[r0] - v[c];
+        if (red < slack[c]) { slack[c] = red; prev_col[c] = c0; }
+        if (slack[c] < step) { step = slack[c]; c_next = c; }
+      }
+      for (int c = 0; c <= n; ++c) {
+        if (in_tree[c]) { u[row_of_col[c]] += step; v[c] -= step; }
+        else slack[c] -= step;
+      }
+      c0 = c_next;
+      if (row_of_col[c0] < 0) break;             // reached a free column: augment
+    }
+    while (c0 != n) {
+      const int pc = prev_col[c0];
+      row_of_col[c0] = row_of_col[pc];
+      c0 = pc;
+    }
+  }
+  int64_t total = 0;
+  for (int c = 0; c < n; ++c) {
+    total += cost[(size_t)row_of_col[c] * n + c];
+    if (position_of_node) position_of_node[row_of_col[c]] = c;
+  }
+  return total;
+}
+
 // ---------------------------------------------------------------------------------------
 // scenario
 // ---------------------------------------------------------------------------------------
@@ -228,6 +276,7 @@ struct orc_scenario {
   std::vector<char> failed;                             // [D*S]
   int64_t comm, cap, K, reconf[3], xfer;
   int reroute_cap;
+  int transfer_assign;                                  // strategy 1: 1 = least-transfer node-to-stage assignment
   std::vector<int> p0;                                  // [S+1]
   // failed-node distribution
   std::vector<int> fail_in_replica, fail_in_stage;      // [D], [S]
@@ -334,12 +383,18 @@ int64_t base_cost_terms(const orc_scenario *s, int strategy, int k, const uint8_
       std::vector<int> host;      // old stage index of the node that runs new stage j
       for (int j = 0; j < S; ++j) if (!s->dead(d, j)) host.push_back(j);
       std::vector<int64_t> F(SB), B(SB);
-      int64_t miss_d = 0;
       for (int j = 0; j < SB; ++j) {
         F[j] = orc_scale_q16(st.f[j], s->qof(d, host[j]));
         B[j] = orc_scale_q16(st.b[j], s->qof(d, host[j]));
-        miss_d += orc_missing_interval(s->pw.data(), st.lo[j], st.lo[j + 1], s->p0[host[j]], s->p0[host[j] + 1]);
       }
+      // Cost[i][j]: MiB the i-th surviving node must fetch to hold new stage j (Restorer, "Weight Transfer")
+      std::vector<int64_t> fetch((size_t)SB * SB);
+      for (int i = 0; i < SB; ++i)
+        for (int j = 0; j < SB; ++j)
+          fetch[(size_t)i * SB + j] = orc_missing_interval(s->pw.data(), st.lo[j], st.lo[j + 1], s->p0[host[i]], s->p0[host[i] + 1]);
+      int64_t miss_d = 0;
+      if (s->transfer_assign) miss_d = orc_min_assignment(SB, fetch.data(), nullptr);
+      else for (int j = 0; j < SB; ++j) miss_d += fetch[(size_t)j * SB + j];
       t_step = std::max(t_step, orc_makespan_1f1b(SB, F.data(), B.data(), s->mb_B[d]) + (int64_t)(SB - 1) * s->comm);
       missing = std::max(missing, miss_d);   // pipelines move their weights in parallel
     }
@@ -485,13 +540,14 @@ extern "C" int orc_open(const orc_desc *d, orc_scenario **out) {
       d->DP < 1 || d->DP > ORC_MAX_DP || d->M < 1 || d->M > ORC_MAX_M ||
       d->n_failed < 0 || d->n_failed > ORC_MAX_FAILED || !d->fwd_us || !d->bwd_us || !d->mem_mib ||
       (d->n_failed > 0 && !d->failed_nodes) || d->comm_us < 0 || d->mem_cap_mib < 1 ||
-      d->horizon_steps < 1 || d->xfer_us_per_mib < 0)
+      d->horizon_steps < 1 || d->xfer_us_per_mib < 0 || d->transfer_assign < 0 || d->transfer_assign > 1)
     return ORC_ERR_ARG;
   for (int i = 0; i < 3; ++i) if (d->reconf_us[i] < 0) return ORC_ERR_ARG;
   orc_scenario *s = new orc_scenario();
   s->L = d->L; s->S = d->PP; s->D = d->DP; s->M = d->M;
   s->comm = d->comm_us; s->cap = d->mem_cap_mib; s->K = d->horizon_steps; s->xfer = d->xfer_us_per_mib;
   s->reroute_cap = d->reroute_cap;
+  s->transfer_assign = d->transfer_assign;
   for (int i = 0; i < 3; ++i) s->reconf[i] = d->reconf_us[i];
   s->pf.assign(s->L + 1, 0); s->pb.assign(s->L + 1, 0); s->pw.assign(s->L + 1, 0); s->pa.assign(s->L + 1, 0);
   for (int l = 0; l < s->L; ++l) {

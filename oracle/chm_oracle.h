@@ -22,6 +22,11 @@
  *     is the static sum.
  *   - transition time = restart constant + weight transfer: Estimator subsection,
  *     paragraph on dynamic parallelism; negligible for rerouting.
+ *   - which surviving node takes which new stage (transfer_assign = 1): Restorer subsection,
+ *     "Weight Transfer": the assignment of least total transfer over the cost matrix
+ *     Cost[i][j] = what node i must fetch to become the j-th node of the new pipeline,
+ *     by the Kuhn-Munkres algorithm.  The step time keeps the survivors in stage order (the
+ *     paper's nodes are identical, so its estimator does not depend on the assignment).
  *   - argmin with first-strict-minimum: Algorithm 1, get_execution_plan.
  *
  * Pure conventions with no counterpart in the paper ("parity unpinned": only
@@ -54,6 +59,8 @@ typedef struct {
   int32_t reconf_us[3];
   int32_t xfer_us_per_mib;
   const int32_t *act_mib;                     /* [L] activation memory per micro-batch in flight; NULL = none */
+  int32_t transfer_assign;                    /* re-partition strategy: 0 = the j-th surviving node hosts new stage j,
+                                                 1 = the node-to-stage assignment with the least total weight transfer */
 } orc_desc;
 
 typedef struct { uint64_t offset, n_part, n_reroute; int32_t stages, strategy; } orc_family;
@@ -81,6 +88,11 @@ int64_t  orc_makespan_1f1b(int32_t S, const int64_t *F, const int64_t *B, int32_
 int64_t  orc_missing_interval(const int64_t *pw, int32_t a, int32_t b, int32_t a0, int32_t b0);
 void     orc_distribute_batch(int32_t D, int32_t total, const int32_t *nodes, int32_t *out);
 void     orc_layout_p0(int32_t L, int32_t S, int32_t *bounds /* [S+1] */);
+/* Minimum total cost of a one-to-one assignment of n nodes to n positions (Restorer, "Weight
+ * Transfer": Kuhn-Munkres on the n x n matrix Cost[i][j] = cost for node i to become the j-th
+ * node of the new plan).  cost is row-major, cost[i*n+j] >= 0; position_of_node (nullable)
+ * receives one optimal assignment. */
+int64_t  orc_min_assignment(int32_t n, const int64_t *cost, int32_t *position_of_node);
 
 /* --- scenario level ------------------------------------------------------------------- */
 typedef struct orc_scenario orc_scenario;

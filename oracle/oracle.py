@@ -36,7 +36,8 @@ class Desc(C.Structure):
                 ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
                 ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32), ("reroute_cap", C.c_int32),
                 ("horizon_steps", C.c_int32), ("reconf_us", C.c_int32 * 3),
-                ("xfer_us_per_mib", C.c_int32), ("act_mib", C.POINTER(C.c_int32))]
+                ("xfer_us_per_mib", C.c_int32), ("act_mib", C.POINTER(C.c_int32)),
+                ("transfer_assign", C.c_int32)]
 
 
 class Family(C.Structure):
@@ -76,6 +77,7 @@ def lib():
             "orc_missing_interval": (C.c_int64, [i64p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]),
             "orc_distribute_batch": (None, [C.c_int32, C.c_int32, i32p, i32p]),
             "orc_layout_p0": (None, [C.c_int32, C.c_int32, i32p]),
+            "orc_min_assignment": (C.c_int64, [C.c_int32, i64p, i32p]),
             "orc_open": (C.c_int, [C.POINTER(Desc), C.POINTER(C.c_void_p)]),
             "orc_close": (None, [C.c_void_p]),
             "orc_plan_space": (C.c_int, [C.c_void_p, C.POINTER(Space)]),
@@ -175,6 +177,15 @@ def layout_p0(L, S):
     return [int(x) for x in out]
 
 
+def min_assignment(cost):
+    """(minimum total, position of every node) for a square cost matrix cost[node][position]"""
+    c = np.ascontiguousarray(cost, dtype=np.int64)
+    assert c.ndim == 2 and c.shape[0] == c.shape[1]
+    pos = np.zeros(c.shape[0], dtype=np.int32)
+    total = lib().orc_min_assignment(c.shape[0], _ptr(c, C.c_int64), _ptr(pos, C.c_int32))
+    return int(total), [int(x) for x in pos]
+
+
 def _plan_dict(p):
     k = p.stages - 1
     d = {"index": int(p.index), "cost": int(p.cost), "strategy": int(p.strategy), "stages": int(p.stages),
@@ -187,7 +198,8 @@ def _plan_dict(p):
 class Scenario:
     """One failure scenario held by the oracle.  `sc` is a dict as produced by the seeded
     input generators: L, PP, DP, M, fwd_us, bwd_us, mem_mib, speed_q16 (or None),
-    failed_nodes, comm_us, mem_cap_mib, reroute_cap, horizon_steps, reconf_us, xfer_us_per_mib."""
+    failed_nodes, comm_us, mem_cap_mib, reroute_cap, horizon_steps, reconf_us, xfer_us_per_mib,
+    act_mib (or None), transfer_assign (0/1)."""
 
     def __init__(self, sc):
         self._keep = []
@@ -215,6 +227,7 @@ class Scenario:
             a = np.ascontiguousarray(sc["act_mib"], dtype=np.int32)
             self._keep.append(a)
             d.act_mib = _ptr(a, C.c_int32)
+        d.transfer_assign = int(sc.get("transfer_assign", 0))
         h = C.c_void_p()
         rc = lib().orc_open(C.byref(d), C.byref(h))
         if rc:

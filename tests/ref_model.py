@@ -182,8 +182,13 @@ class Model:
                     F = [scale(fs[j], self.q[d][host[j]]) for j in range(n)]
                     B = [scale(bs[j], self.q[d][host[j]]) for j in range(n)]
                     t = max(t, dag_makespan(F, B, self.mbB[d]) + (n - 1) * comm)
-                    miss = max(miss, sum(self.missing(bounds[j], bounds[j + 1], self.p0[host[j]], self.p0[host[j] + 1])
-                                         for j in range(n)))
+                    fetch = [[self.missing(bounds[j], bounds[j + 1], self.p0[host[i]], self.p0[host[i] + 1]) for j in range(n)]
+                             for i in range(n)]                 # fetch[i][j]: survivor i becomes the node of new stage j
+                    if sc.get("transfer_assign", 0):            # Restorer: the one-to-one assignment of least total transfer
+                        miss_d = min(sum(fetch[perm[j]][j] for j in range(n)) for perm in itertools.permutations(range(n)))
+                    else:
+                        miss_d = sum(fetch[j][j] for j in range(n))
+                    miss = max(miss, miss_d)
         else:
             if any(peak(ms[j], av[j], S, j) > cap for j in range(S)):
                 return INF

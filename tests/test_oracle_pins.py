@@ -492,3 +492,118 @@ def test_costs_with_activation_memory_match_the_independent_model(i):
         assert rc == O.ERR_NO_FEASIBLE
     else:
         assert rc == 0 and best["index"] == int(np.argmin(got))
+
+
+# ----------------------------------------------------------------------------- least-transfer assignment
+def brute_assignment(c):
+    n = len(c)
+    return min(sum(c[p[j]][j] for j in range(n)) for p in itertools.permutations(range(n)))
+
+
+def test_min_assignment_matches_brute_force_and_the_library_routine():
+    """Restorer, "Weight Transfer": Kuhn-Munkres on a cost matrix = the minimum over all one-to-one
+    assignments (brute force for n <= 7) = scipy's linear_sum_assignment (n up to 31)"""
+    from scipy.optimize import linear_sum_assignment
+    rng = np.random.default_rng(11)
+    for trial in range(400):
+        n = int(rng.integers(1, 8))
+        hi = int(rng.choice([2, 5, 60, 10 ** 9]))               # many ties, few ties, large values
+        c = rng.integers(0, hi, (n, n))
+        total, pos = O.min_assignment(c)
+        assert total == brute_assignment(c.tolist()), c
+        assert sorted(pos) == list(range(n)) and sum(int(c[i, pos[i]]) for i in range(n)) == total
+    for trial in range(60):
+        n = int(rng.integers(8, 32))
+        c = rng.integers(0, 10 ** 6, (n, n))
+        r, k = linear_sum_assignment(c)
+        total, pos = O.min_assignment(c)
+        assert total == int(c[r, k].sum())
+        assert sorted(pos) == list(range(n)) and sum(int(c[i, pos[i]]) for i in range(n)) == total
+    # structure: a permuted zero diagonal costs nothing; a constant added to a row or a column shifts the optimum by it
+    for n in (1, 4, 9):
+        perm = rng.permutation(n)
+        c = rng.integers(1, 100, (n, n))
+        c[np.arange(n), perm] = 0
+        assert O.min_assignment(c) == (0, [int(x) for x in perm])
+        d = rng.integers(0, 50, (n, n))
+        base = O.min_assignment(d)[0]
+        d[n // 2, :] += 7
+        d[:, 0] += 3
+        assert O.min_assignment(d)[0] == base + 10
+    # not symmetric in its arguments: rows are nodes, columns are positions
+    assert O.min_assignment([[0, 9], [0, 1]]) == (1, [0, 1])
+    assert O.min_assignment([[0, 0], [9, 1]]) == (1, [0, 1])
+
+
+def test_weight_transfer_matrix_of_the_paper_example():
+    """the 3x3 -> 2x4 example of the Restorer: cost entries as the paper counts them, and the
+    cheapest migration of the eight remaining nodes"""
+    g = golden()
+    unit = [1] * 9
+    old = [(0, 3), (3, 6), (6, 9)]                     # stages (1,2,3) (4,5,6) (7,8,9) as half-open index ranges
+    new = [(0, 2), (2, 4), (4, 6), (6, 9)]             # (1,2) (3,4) (5,6) (7,8,9)
+    fetch = lambda o, n: O.missing_interval(unit, n[0], n[1], o[0], o[1])
+    assert fetch(old[0], new[0]) == int(g["transfer_123_to_12"])
+    assert fetch(old[0], new[1]) == int(g["transfer_123_to_34"])
+    assert fetch(old[1], new[1]) == int(g["transfer_456_to_34"])
+    assert fetch(old[1], new[2]) == int(g["transfer_456_to_56"])
+    assert fetch(old[2], new[3]) == int(g["transfer_789_to_789"])
+    assert fetch(old[0], new[3]) == int(g["transfer_123_to_789"])
+    # eight survivors (the lost node held the middle stage), eight positions of the new 2 x 4 layout
+    nodes = [old[0], old[1], old[2], old[0], old[2], old[0], old[1], old[2]]
+    positions = new + new
+    c = [[fetch(o, n) for n in positions] for o in nodes]
+    total, pos = O.min_assignment(c)
+    # three nodes hold (7,8,9) but only two positions do, so one of them moves to a two-layer stage and
+    # fetches both layers; three nodes hold (1,2,3), two take (1,2) for free and the third takes (3,4) for 1
+    assert total == brute_assignment(c) == 3
+    assert sum(c[i][pos[i]] for i in range(8)) == 3
+
+
+SMALL_KM = [dict(sc, transfer_assign=1) for sc in SMALL] + [
+    dict(synth.small_random(2020, L=11, PP=5, DP=2, M=3, n_failed=1, hetero=True), transfer_assign=1),
+    dict(synth.small_random(2021, L=12, PP=6, DP=3, M=2, n_failed=2, hetero=False), transfer_assign=1),
+]
+
+
+@pytest.mark.parametrize("i", range(len(SMALL_KM)))
+def test_costs_with_least_transfer_assignment_match_the_independent_model(i):
+    sc = SMALL_KM[i]
+    model = R.Model(sc)
+    s = O.Scenario(sc)
+    want = model.all_costs()
+    assert s.n_plans == len(want)
+    assert [int(x) for x in s.score(0, s.n_plans)] == want
+    # the assignment never costs more than keeping the survivors in stage order, and only strategy 1 changes
+    plain = O.Scenario(dict(sc, transfer_assign=0)).score(0, s.n_plans)
+    got = s.score(0, s.n_plans)
+    assert (got <= plain).all()
+    for f in s.families:
+        if f["strategy"] != 1:
+            lo = f["offset"]
+            assert (got[lo:lo + f["n_part"] * f["n_reroute"]] == plain[lo:lo + f["n_part"] * f["n_reroute"]]).all()
+
+
+def test_least_transfer_assignment_changes_some_plan_and_is_validated():
+    changed = 0
+    for sc in SMALL_KM:
+        a = O.Scenario(sc).score(0, O.Scenario(sc).n_plans)
+        b = O.Scenario(dict(sc, transfer_assign=0)).score(0, len(a))
+        changed += int((a < b).sum())
+    assert changed > 0
+    with pytest.raises(O.OracleError) as e:
+        O.Scenario(dict(SMALL[0], transfer_assign=2))
+    assert e.value.code == O.ERR_ARG
+    # Worked by hand: 12 unit layers, 4 stages, pipeline 0 lost stage 2, so its survivors hold [0,3) [3,6) [9,12).
+    fwd = np.full(12, 10, np.int32)
+    sc = synth.scenario(12, 4, 2, 4, fwd, 2 * fwd, np.ones(12, np.int32), [2], 0, 100, reconf_us=(0, 0, 0),
+                        xfer_us_per_mib=1, horizon_steps=1, transfer_assign=1)
+    s, p = O.Scenario(sc), O.Scenario(dict(sc, transfer_assign=0))
+    # new stages [0,1) [1,3) [3,12): layers to fetch, node x stage = [[0,0,9],[1,2,6],[1,2,6]].  In stage order
+    # 0+2+6 = 8; letting the first node take [1,3) and the second [0,1) gives 0+1+6 = 7, the optimum.
+    assert p.plan_cost(1, [1, 3]) - s.plan_cost(1, [1, 3]) == 8 - 7
+    # new stages [0,9) [9,11) [11,12): [[6,2,1],[6,2,1],[9,0,0]]; stage order 6+2+0 = 8, optimum 6+1+0 = 7
+    # (the last node takes [9,11), which it already holds, the second one the single layer [11,12))
+    assert p.plan_cost(1, [9, 11]) - s.plan_cost(1, [9, 11]) == 8 - 7
+    # new stages [0,3) [3,6) [6,12): the survivors keep their own layers in stage order, 0+0+3, nothing is cheaper
+    assert p.plan_cost(1, [3, 6]) == s.plan_cost(1, [3, 6])
