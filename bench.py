@@ -34,6 +34,10 @@ def algorithmic_ops(fam, feasible):
     light = 4 * S
     heavy = sum(4 * n_c * m_c + 2 * n_c + 2 for n_c, m_c in fam["classes"]) + 4 * S + 2
     heavy += sum(R * 2 * p for R, p in zip(fam["R"], fam["peers"]))
+    if fam.get("assign") and fam["strategy"] == 1:
+        # least-transfer assignment: the two-index recurrence over (survivor, new stage) pairs, per cell
+        # the overlap (min, max, subtract, clamp) and one add and two max
+        heavy += sum(7 * n_c * n_c for n_c, _ in fam["classes"])
     return fam["n_part"] * light + feasible * heavy, light, heavy
 
 
@@ -47,6 +51,9 @@ def main():
     ap.add_argument("--ttb-runs", type=int, default=10)
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config5"],
                     help="config2 (the 32-card shape) is the benchmark; the others are for profiling")
+    ap.add_argument("--transfer-assign", type=int, default=0, choices=[0, 1],
+                    help="1: the re-partition strategy counts the weights to fetch under the least-transfer "
+                         "assignment of survivors to new stages (default 0: survivors in stage order)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -74,7 +81,9 @@ def main():
                     lambda: [synth.config5(fs) for fs in synth.config5_failure_sets()]),
     }
     label, make = workloads[args.workload]
-    scenarios = make()
+    scenarios = [dict(sc, transfer_assign=args.transfer_assign) for sc in make()]
+    if args.transfer_assign:
+        label += ", least-transfer assignment"
     t0 = time.perf_counter()
     handles = [B.Scenario(sc) for sc in scenarios]
     load_ms = (time.perf_counter() - t0) * 1e3
@@ -89,6 +98,7 @@ def main():
             d["classes"] = g.family_classes(f["strategy"])
             d["peers"] = [p for p, _ in shape] if f["strategy"] == 2 else []
             d["R"] = [r for _, r in shape] if f["strategy"] == 2 else []
+            d["assign"] = args.transfer_assign
             fams.append(d)
         return fams
 

@@ -89,6 +89,11 @@ typedef struct {
                                          With it mem_mib is the static part (weights, optimizer states, gradients) and
                                          the node at position i (from 0) of an n-stage pipeline peaks at
                                          static + (n - i) * activations (Memory Estimator, eq. peak_memory_decomposed) */
+  int32_t transfer_assign;            /* re-partition strategy, which surviving node hosts which new stage when the weights
+                                         to fetch are counted: 0 = the j-th survivor (in stage order) hosts new stage j;
+                                         1 = the one-to-one assignment with the least total transfer (Restorer, "Weight
+                                         Transfer": minimum-cost matching on Cost[i][j] = MiB node i must fetch to hold new
+                                         stage j).  The step time keeps the survivors in stage order in both cases. */
 } chm_scenario_desc;
 
 typedef struct { uint64_t offset, n_part, n_reroute; int32_t stages, strategy; } chm_family;

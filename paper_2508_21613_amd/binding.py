@@ -28,7 +28,8 @@ class Desc(C.Structure):
                 ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
                 ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32), ("reroute_cap", C.c_int32),
                 ("horizon_steps", C.c_int32), ("reconf_us", C.c_int32 * 3),
-                ("xfer_us_per_mib", C.c_int32), ("act_mib", C.POINTER(C.c_int32))]
+                ("xfer_us_per_mib", C.c_int32), ("act_mib", C.POINTER(C.c_int32)),
+                ("transfer_assign", C.c_int32)]
 
 
 class Family(C.Structure):
@@ -154,6 +155,7 @@ class Scenario:
             a = np.ascontiguousarray(sc["act_mib"], dtype=np.int32)
             keep.append(a)
             d.act_mib = a.ctypes.data_as(C.POINTER(C.c_int32))
+        d.transfer_assign = int(sc.get("transfer_assign", 0))
         self._h = C.c_void_p()
         _check(lib().chm_load_scenario(C.byref(d), C.byref(self._h)))
         sp = Space()

@@ -27,6 +27,7 @@ struct FastFamily {
   int32_t w_total;                // memory of the whole model
   int32_t mem_coef[DEV_MAX_S];    // see DevFamily::mem_coef
   int32_t has_act;                // 0: no activation table, the peak is the static sum
+  int32_t assign;                 // strategy 1: 1 = least-total-transfer assignment of survivors to new stages
   FastClass cls[DEV_MAX_CLS];
 };
 

@@ -377,12 +377,38 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
           for (int j = 0; j < SP; ++j) { F[j] = fs[j]; B[j] = bs[j]; }
           t_step = imax32(t_step, class_time<SP>(cl, F, B));
           if (STRAT == 1) {
-            int have = 0, wl = 0;
+            int have = 0;
+            if (ff->assign) {
+              // least-transfer assignment = largest total overlap of a non-crossing matching of survivors
+              // and new stages (both are in layer order, see best_overlap in chm_kernels.hip); one row of
+              // the two-index recurrence lives in registers.  A negative raw overlap needs no clamp:
+              // diag + (negative) < diag <= G[j], which is already among the operands of the max.
+              int G[SP + 1];
 #pragma unroll
-            for (int j = 0; j < SP; ++j) {
-              const int wh = wl + ms[j];
-              have += imax32(0, imin32(wh, cl->whi[j]) - imax32(wl, cl->wlo[j]));
-              wl = wh;
+              for (int j = 0; j <= SP; ++j) G[j] = 0;
+#pragma unroll
+              for (int i = 0; i < SP; ++i) {
+                const int wlo_i = cl->wlo[i], whi_i = cl->whi[i];
+                int diag = 0, wl = 0;
+#pragma unroll
+                for (int j = 0; j < SP; ++j) {
+                  const int wh = wl + ms[j];
+                  const int above = G[j + 1];
+                  const int cand = diag + (imin32(wh, whi_i) - imax32(wl, wlo_i));
+                  G[j + 1] = imax32(imax32(above, G[j]), cand);
+                  diag = above;
+                  wl = wh;
+                }
+              }
+              have = G[SP];
+            } else {
+              int wl = 0;
+#pragma unroll
+              for (int j = 0; j < SP; ++j) {
+                const int wh = wl + ms[j];
+                have += imax32(0, imin32(wh, cl->whi[j]) - imax32(wl, cl->wlo[j]));
+                wl = wh;
+              }
             }
             missing = imax32(missing, ff->w_total - have);
           }
@@ -706,6 +732,7 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     ff.w_total = (int32_t)h.pw[h.L];
     for (int j = 0; j < DEV_MAX_S; ++j) ff.mem_coef[j] = fam.mem_coef[j];
     ff.has_act = h.pa[h.L] > 0 ? 1 : 0;
+    ff.assign = h.assign;
     for (int j = 0; j <= h.S; ++j) ff.w0[j] = (int32_t)h.pw[h.p0[j]];
     for (int ci = 0; ci < fam.n_cls && ok; ++ci) {
       const DevClass &c = fam.cls[ci];

@@ -117,6 +117,7 @@ int validate(const chm_scenario_desc *d) {
     return CHM_ERR_ARG;
   if (!d->fwd_us || !d->bwd_us || !d->mem_mib || (d->n_failed > 0 && !d->failed_nodes)) return CHM_ERR_ARG;
   if (d->comm_us < 0 || d->mem_cap_mib < 1 || d->horizon_steps < 1 || d->xfer_us_per_mib < 0) return CHM_ERR_ARG;
+  if (d->transfer_assign < 0 || d->transfer_assign > 1) return CHM_ERR_ARG;
   for (int i = 0; i < 3; ++i) if (d->reconf_us[i] < 0) return CHM_ERR_ARG;
   for (int l = 0; l < d->L; ++l)
     if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0 || (d->act_mib && d->act_mib[l] < 0)) return CHM_ERR_ARG;
@@ -140,6 +141,7 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
   h.comm = d->comm_us; h.cap = d->mem_cap_mib; h.K = d->horizon_steps; h.xfer = d->xfer_us_per_mib;
   for (int i = 0; i < 3; ++i) h.reconf[i] = d->reconf_us[i];
   h.rcap = d->reroute_cap;
+  h.assign = d->transfer_assign;
   for (int l = 0; l < L; ++l) {
     h.pf[l + 1] = h.pf[l] + d->fwd_us[l];
     h.pb[l + 1] = h.pb[l] + d->bwd_us[l];

@@ -84,6 +84,39 @@ __device__ __forceinline__ int64_t missing_interval(const DevScenario *scn, int 
   return need - have;
 }
 
+// Least-transfer assignment of a pipeline's surviving nodes to its new stages (Restorer, "Weight
+// Transfer").  A node that takes stage j fetches the stage's layers it does not hold, so the least
+// total transfer is the model size minus the largest total overlap of a one-to-one assignment.
+// Nodes (by their fault-free stage) and new stages are both in layer order and each side is
+// disjoint, so two pairs with a non-zero overlap never cross; pairs without overlap can complete
+// any matching.  The optimum is therefore the best non-crossing matching, a two-index recurrence:
+// G[i][j] = max(G[i-1][j], G[i][j-1], G[i-1][j-1] + overlap(node i-1, stage j-1)), kept as one row.
+template <int SMAX>
+__device__ __forceinline__ int64_t best_overlap(const DevScenario *scn, const DevClass &cls, Cuts<SMAX> cuts) {
+  int64_t G[SMAX + 1];
+#pragma unroll
+  for (int j = 0; j <= SMAX; ++j) G[j] = 0;
+  for (int i = 0; i < cls.n; ++i) {
+    const int lo_i = scn->p0[cls.host[i]], hi_i = scn->p0[cls.host[i] + 1];
+    int64_t diag = 0;
+#pragma unroll
+    for (int j = 0; j < SMAX; ++j) {
+      if (j < cls.n) {
+        const int a = cuts.get(j), b = cuts.get(j + 1);
+        const int lo = a > lo_i ? a : lo_i, hi = b < hi_i ? b : hi_i;
+        const int64_t ov = hi > lo ? scn->pw[hi] - scn->pw[lo] : 0;
+        const int64_t above = G[j + 1];
+        G[j + 1] = imax(imax(above, G[j]), diag + ov);
+        diag = above;
+      }
+    }
+  }
+  int64_t best = 0;
+#pragma unroll
+  for (int j = 0; j <= SMAX; ++j) best = (j == cls.n) ? G[j] : best;
+  return best;
+}
+
 // Everything of a plan's cost except the rerouting penalty.  Returns false when the plan
 // does not fit in memory.
 template <int SMAX>
@@ -139,6 +172,7 @@ __device__ __forceinline__ bool eval_base(const DevScenario *scn, const DevFamil
         }
       }
     }
+    if (fam.strategy == 1 && scn->assign) miss = scn->pw[scn->L] - best_overlap<SMAX>(scn, cls, cuts);
     const int64_t T = makespan_generic<SMAX>(F, B, cls.n, cls.M) + (int64_t)(cls.n - 1) * scn->comm;
     t_step = imax(t_step, T);
     missing = imax(missing, miss);

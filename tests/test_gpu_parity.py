@@ -64,12 +64,15 @@ SMALL.append(dict(_two_lost_in_one_pipeline(), failed_nodes=[0, 3, 8], M=3))
 
 
 SMALL_ACT = [synth.with_activations(sc, 3000 + i) for i, sc in enumerate(SMALL)]
+# least-transfer assignment of survivors to new stages, alternately without and with activation memory
+SMALL_KM = [dict(SMALL_ACT[i] if i % 2 else sc, transfer_assign=1) for i, sc in enumerate(SMALL)]
+ALL_SMALL = SMALL + SMALL_ACT + SMALL_KM
 
 
-@pytest.mark.parametrize("i", range(2 * len(SMALL)))
+@pytest.mark.parametrize("i", range(len(ALL_SMALL)))
 def test_small_scenarios_every_cost_and_argmin(B, i):
-    sc = SMALL[i] if i < len(SMALL) else SMALL_ACT[i - len(SMALL)]      # second half: with activation memory
-    print("small scenario", i, {k: sc[k] for k in ("L", "PP", "DP", "M", "failed_nodes", "reroute_cap")}, flush=True)
+    sc = ALL_SMALL[i]
+    print("small scenario", i, {k: sc.get(k) for k in ("L", "PP", "DP", "M", "failed_nodes", "reroute_cap", "transfer_assign")}, flush=True)
     o = O.Scenario(sc)
     g = B.Scenario(sc)
     assert g.families == o.families and g.n_plans == o.n_plans
@@ -114,9 +117,14 @@ def windows(o, rng, n_windows, width):
     return out
 
 
-@pytest.mark.parametrize("name", ["config2", "config3", "config5_single", "config5_double", "config2_act", "config3_act"])
+@pytest.mark.parametrize("name", ["config2", "config3", "config5_single", "config5_double", "config2_act", "config3_act",
+                                  "config2_assign", "config3_assign", "config5_double_assign"])
 def test_seeded_windows_of_the_large_configs(B, name):
     sc = {"config2": synth.config2, "config3": synth.config3,
+          "config2_assign": lambda: dict(synth.config2(), transfer_assign=1),
+          "config3_assign": lambda: dict(synth.with_activations(synth.config3(), 79), transfer_assign=1),
+          "config5_double_assign": lambda: dict(synth.config5([3, 30]), transfer_assign=1),
+
           "config2_act": lambda: synth.with_activations(synth.config2(), 77),
           "config3_act": lambda: synth.with_activations(synth.config3(), 78),
           "config5_single": lambda: synth.config5([13]),
@@ -125,7 +133,12 @@ def test_seeded_windows_of_the_large_configs(B, name):
     o, g = O.Scenario(sc), B.Scenario(sc)
     assert g.families == o.families and g.n_plans == o.n_plans
     rng = np.random.default_rng(42)
-    for first, count in windows(o, rng, 6, 700):
+    width = 700 if o.n_plans > 1400 else o.n_plans // 2
+    wins = windows(o, rng, 6, width)
+    if name.endswith("_assign"):                    # the assignment only changes the re-partition strategy: look there
+        f1 = o.family(1)
+        wins += [(f1["offset"] + int(rng.integers(0, f1["n_part"] - width)), width) for _ in range(6)]
+    for first, count in wins:
         want = o.score(first, count)
         got = gpu_scores(B, g, first, count)
         assert (got == want).all(), (first, np.flatnonzero(got != want)[:5])
@@ -140,9 +153,10 @@ def test_seeded_windows_of_the_large_configs(B, name):
             assert rc_g == rc_o and same_plan(best_g, best_o), (f, first, best_g, best_o)
 
 
-def test_config4_explicit_partitions(B):
+@pytest.mark.parametrize("cap,assign", [(6000, 0), (synth.CONFIG4_CAP_30PCT, 0), (synth.CONFIG4_CAP_30PCT, 1)])
+def test_config4_explicit_partitions(B, cap, assign):
     import torch
-    sc = synth.config4()
+    sc = dict(synth.config4(mem_cap_mib=cap), transfer_assign=assign)
     o, g = O.Scenario(sc), B.Scenario(sc)
     assert g.families == o.families
     n = 3000
@@ -163,11 +177,12 @@ def test_config4_explicit_partitions(B):
     assert got[1] == B.INFEASIBLE and got[0] == o.score_ranks(1, [0])[0]
 
 
-def test_full_size_search_config2(B):
+@pytest.mark.parametrize("assign", [0, 1])
+def test_full_size_search_config2(B, assign):
     """the 32-card shape, whole space, in the launch configuration the benchmark times:
     the winner is re-scored plan by plan by the oracle, is compared with the oracle's argmin
     over the windows around it, and must not be beaten by any plan of a seeded sample."""
-    sc = synth.config2()
+    sc = dict(synth.config2(), transfer_assign=assign)
     o, g = O.Scenario(sc), B.Scenario(sc)
     rc, best = g.search_best(7)
     assert rc == 0
