@@ -164,6 +164,18 @@ int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void
 int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part_first, uint64_t part_count,
                      chm_best *out, void *hip_stream);
 
+/* Migration scheme of one plan of the re-partition strategy (Restorer, "Weight Transfer"): for the
+ * partition with rank part_rank and pipeline `pipeline` (one that lost nodes), *n_nodes = its
+ * surviving nodes, node_stage[i] = fault-free stage of the i-th of them (ascending), stage_of_node[i]
+ * = the new stage that node hosts, *fetch_mib = MiB of weights the nodes fetch in total (the figure
+ * the plan's cost charges, maximised over the pipelines that lost nodes).  With transfer_assign = 1
+ * this is an assignment of least total transfer (one of them when several tie), with 0 the survivors
+ * in stage order.  Arrays of 32 bytes each, host memory.  The scheme is computed on the device;
+ * synchronises hip_stream.  Errors: CHM_ERR_UNRECOVERABLE (the strategy does not exist for this
+ * failure set), CHM_ERR_ARG (pipeline out of range or intact), CHM_ERR_RANGE, CHM_ERR_HIP. */
+int chm_transfer_plan(chm_scenario *s, uint64_t part_rank, int32_t pipeline, int32_t *n_nodes,
+                      uint8_t *node_stage, uint8_t *stage_of_node, int64_t *fetch_mib, void *hip_stream);
+
 /* Host-only structural decoding of a plan index (cost is not evaluated and is set to 0). */
 int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out);
 

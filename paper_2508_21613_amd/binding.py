@@ -17,7 +17,7 @@ INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
            "chm_search_range", "chm_search_ranks", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
-           "chm_reroute_shape", "chm_valu_probe", "chm_free_scenario",
+           "chm_reroute_shape", "chm_transfer_plan", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
 
@@ -256,6 +256,14 @@ class Scenario:
         peers, vecs = (C.c_int32 * 4)(), (C.c_uint64 * 4)()
         _check(lib().chm_reroute_shape(self._h, C.byref(n), peers, vecs))
         return [(int(peers[a]), int(vecs[a])) for a in range(n.value)]
+
+    def transfer_plan(self, part_rank, pipeline, stream=None):
+        """chm_transfer_plan: (fault-free stage of every surviving node, new stage it hosts, MiB fetched in total)"""
+        n, mib = C.c_int32(), C.c_int64()
+        node_stage, stage_of_node = (C.c_uint8 * 32)(), (C.c_uint8 * 32)()
+        _check(lib().chm_transfer_plan(self._h, C.c_uint64(part_rank), pipeline, C.byref(n), node_stage, stage_of_node,
+                                       C.byref(mib), _stream_ptr(stream)))
+        return [int(node_stage[i]) for i in range(n.value)], [int(stage_of_node[i]) for i in range(n.value)], int(mib.value)
 
     def set_timing(self, on=True):
         _check(lib().chm_set_timing(self._h, 1 if on else 0))

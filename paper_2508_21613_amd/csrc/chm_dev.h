@@ -93,4 +93,9 @@ int chmk_rank_cuts(const DevScenario *d_scn, int k, const uint8_t *d_cuts, uint6
 int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank,
                         uint64_t *d_out, int32_t smax, void *stream);
 
+// migration scheme of one pipeline (n survivors, host[i] = fault-free stage of survivor i) for one
+// partition of strategy 1: new stage per survivor to d_stage_of_node[0..n), total MiB to *d_fetch_mib
+int chmk_transfer_plan(const DevScenario *d_scn, uint64_t part_rank, int32_t n, const uint8_t *host,
+                       uint8_t *d_stage_of_node, int64_t *d_fetch_mib, void *stream);
+
 #endif

@@ -37,6 +37,7 @@ struct chm_scenario {
   DevScenario h;                         // host copy of what the device holds
   std::vector<uint64_t> comp;            // reroute count tables, all affected stages back to back
   std::vector<std::vector<int>> peers;   // per affected stage: surviving replicas, ascending
+  std::vector<std::vector<uint8_t>> survivors;   // per pipeline: fault-free stage indices of its surviving nodes, ascending
   chm_space space;
   int device = 0;
   int smax = 4;                          // template bucket of the generic kernels
@@ -46,6 +47,7 @@ struct chm_scenario {
   uint64_t *d_comp = nullptr;
   uint64_t *d_slots = nullptr;           // argmin words, one per launched chunk
   uint64_t *d_winner = nullptr;          // best reroute rank per affected stage
+  uint64_t *d_xfer = nullptr;            // migration scheme: 8 bytes MiB to fetch + DEV_MAX_S bytes of stage indices
   uint64_t *h_pinned = nullptr;          // pinned staging for the two small device-to-host copies
   uint32_t n_slots = 0;
   bool timing = false;
@@ -178,6 +180,10 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
     ++lost_in_stage[n % S];
   }
 
+  s->survivors.assign(D, std::vector<uint8_t>());
+  for (int dd = 0; dd < D; ++dd)
+    for (int j = 0; j < S; ++j)
+      if (!dead[dd][j]) s->survivors[dd].push_back((uint8_t)j);
   // ---- strategy 0: redundant computation; needs the ring predecessor of every failed node
   bool has0 = S >= 2;
   for (int dd = 0; dd < D; ++dd)
@@ -308,6 +314,7 @@ void release(chm_scenario *s) {
   fast_release(&s->fast);
   for (auto &e : s->ev) if (e) (void)hipEventDestroy(e);
   if (s->h_pinned) (void)hipHostFree(s->h_pinned);
+  if (s->d_xfer) (void)hipFree(s->d_xfer);
   if (s->d_winner) (void)hipFree(s->d_winner);
   if (s->d_slots) (void)hipFree(s->d_slots);
   if (s->d_comp) (void)hipFree(s->d_comp);
@@ -493,6 +500,7 @@ extern "C" int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **o
   ok = ok && hipMalloc((void **)&s->d_comp, s->comp.size() * sizeof(uint64_t)) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_slots, (MAX_SLOTS + 3) * sizeof(uint64_t)) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_winner, DEV_MAX_AFF * sizeof(uint64_t)) == hipSuccess;
+  ok = ok && hipMalloc((void **)&s->d_xfer, sizeof(uint64_t) + DEV_MAX_S) == hipSuccess;
   ok = ok && hipHostMalloc((void **)&s->h_pinned, (MAX_SLOTS + 3) * sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
   ok = ok && hipMemcpy(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice) == hipSuccess;
   ok = ok && hipMemcpy(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice) == hipSuccess;
@@ -601,6 +609,28 @@ extern "C" int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part
   std::vector<Job> jobs;
   jobs.push_back({strategy, part_first, part_count, nullptr, nullptr});
   return run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream);
+}
+
+extern "C" int chm_transfer_plan(chm_scenario *s, uint64_t part_rank, int32_t pipeline, int32_t *n_nodes,
+                                 uint8_t *node_stage, uint8_t *stage_of_node, int64_t *fetch_mib, void *hip_stream) {
+  if (!s || !n_nodes || !node_stage || !stage_of_node || !fetch_mib) return CHM_ERR_ARG;
+  const chm_family *f = find_family(s, 1);
+  if (!f) return CHM_ERR_UNRECOVERABLE;
+  if (pipeline < 0 || pipeline >= s->h.D) return CHM_ERR_ARG;
+  const std::vector<uint8_t> &sv = s->survivors[pipeline];
+  if ((int)sv.size() == s->h.S) return CHM_ERR_ARG;          // this pipeline lost nothing: it keeps its layout
+  if (part_rank >= f->n_part) return CHM_ERR_RANGE;
+  HIP_TRY(hipSetDevice(s->device));
+  hipStream_t st = (hipStream_t)hip_stream;
+  uint8_t *d_stage = (uint8_t *)(s->d_xfer + 1);
+  if (chmk_transfer_plan(s->d_scn, part_rank, (int32_t)sv.size(), sv.data(), d_stage, (int64_t *)s->d_xfer, st)) return CHM_ERR_HIP;
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_xfer, sizeof(uint64_t) + DEV_MAX_S, hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  *n_nodes = (int32_t)sv.size();
+  *fetch_mib = (int64_t)s->h_pinned[0];
+  const uint8_t *got = (const uint8_t *)(s->h_pinned + 1);
+  for (size_t i = 0; i < sv.size(); ++i) { node_stage[i] = sv[i]; stage_of_node[i] = got[i]; }
+  return CHM_OK;
 }
 
 extern "C" int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out) {

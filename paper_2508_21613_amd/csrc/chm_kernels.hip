@@ -427,6 +427,58 @@ __global__ void __launch_bounds__(BLOCK) k_reroute_winner(const DevScenario *scn
   out[a] = rk;
 }
 
+// Migration scheme of one pipeline for one partition of the re-partition strategy: which new stage
+// each surviving node hosts and how much it all has to fetch.  One lane; the whole table of the
+// non-crossing matching recurrence (see best_overlap) is kept in LDS and walked back from its last
+// cell: a step that changes neither index pairs node i-1 with stage j-1.  Nodes left unpaired take
+// the stages left over, in ascending order (they hold nothing of them either way).
+struct SurvivorList { int32_t n; uint8_t host[DEV_MAX_S]; };
+
+__global__ void __launch_bounds__(64) k_transfer_plan(const DevScenario *scn, uint64_t part_rank, SurvivorList sv,
+                                                      uint8_t *stage_of_node, int64_t *fetch_mib) {
+  __shared__ int32_t cut_cols[DEV_MAX_S + 2][BLOCK];
+  __shared__ int64_t G[DEV_MAX_S + 1][DEV_MAX_S + 1];
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const int n = sv.n;
+  Cuts<DEV_MAX_S> cuts{cut_cols, 0};
+  unrank_partition<DEV_MAX_S>(scn, n - 1, part_rank, cuts);
+  int stage_of[DEV_MAX_S];
+  for (int i = 0; i < n; ++i) stage_of[i] = i;
+  if (scn->assign) {
+    for (int i = 0; i <= n; ++i) { G[i][0] = 0; G[0][i] = 0; }
+    for (int i = 1; i <= n; ++i) {
+      const int lo_i = scn->p0[sv.host[i - 1]], hi_i = scn->p0[sv.host[i - 1] + 1];
+      for (int j = 1; j <= n; ++j) {
+        const int a = cuts.get(j - 1), b = cuts.get(j);
+        const int lo = a > lo_i ? a : lo_i, hi = b < hi_i ? b : hi_i;
+        const int64_t ov = hi > lo ? scn->pw[hi] - scn->pw[lo] : 0;
+        G[i][j] = imax(imax(G[i - 1][j], G[i][j - 1]), G[i - 1][j - 1] + ov);
+      }
+    }
+    bool node_done[DEV_MAX_S], stage_taken[DEV_MAX_S];
+    for (int i = 0; i < n; ++i) { node_done[i] = false; stage_taken[i] = false; }
+    for (int i = n, j = n; i > 0 && j > 0;) {
+      if (G[i][j] == G[i - 1][j]) --i;
+      else if (G[i][j] == G[i][j - 1]) --j;
+      else { stage_of[i - 1] = j - 1; node_done[i - 1] = true; stage_taken[j - 1] = true; --i; --j; }
+    }
+    int next_free = 0;
+    for (int i = 0; i < n; ++i) {
+      if (node_done[i]) continue;
+      while (stage_taken[next_free]) ++next_free;
+      stage_of[i] = next_free;
+      stage_taken[next_free] = true;
+    }
+  }
+  int64_t total = 0;
+  for (int i = 0; i < n; ++i) {
+    const int j = stage_of[i];
+    total += missing_interval(scn, cuts.get(j), cuts.get(j + 1), scn->p0[sv.host[i]], scn->p0[sv.host[i] + 1]);
+    stage_of_node[i] = (uint8_t)j;
+  }
+  *fetch_mib = total;
+}
+
 // partition rank of explicit cut positions (inverse of unrank_partition); cuts[n][k] row-major.
 // Cuts that are not strictly increasing within 1..L-1 give UINT64_MAX.
 __global__ void __launch_bounds__(BLOCK) k_rank_cuts(const DevScenario *scn, int k, const uint8_t *cuts, uint64_t n,
@@ -508,6 +560,16 @@ int chmk_search(const SearchLaunch &a, int32_t smax, void *stream) {
     hipLaunchKernelGGL(k_search<SMAX>, dim3(blocks), dim3(BLOCK), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
   });
+}
+
+int chmk_transfer_plan(const DevScenario *d_scn, uint64_t part_rank, int32_t n, const uint8_t *host,
+                       uint8_t *d_stage_of_node, int64_t *d_fetch_mib, void *stream) {
+  SurvivorList sv;
+  sv.n = n;
+  for (int i = 0; i < DEV_MAX_S; ++i) sv.host[i] = i < n ? host[i] : 0;
+  hipLaunchKernelGGL(k_transfer_plan, dim3(1), dim3(64), 0, (hipStream_t)stream, d_scn, part_rank, sv, d_stage_of_node,
+                     d_fetch_mib);
+  return (int)hipGetLastError();
 }
 
 int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank, uint64_t *d_out,

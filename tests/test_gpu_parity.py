@@ -207,6 +207,51 @@ def test_full_size_search_config2(B, assign):
                 assert (w["cost"], w["index"]) >= (best_f["cost"], best_f["index"])
 
 
+def test_migration_scheme_of_the_re_partition_strategy(B):
+    """chm_transfer_plan: the assignment must be one-to-one, fetch exactly what it reports, and that
+    total must be the oracle's minimum over all assignments (transfer_assign = 1) or the stage-order
+    total (0).  Several optimal assignments can exist, so only the total is compared."""
+    rng = np.random.default_rng(21)
+    cases = [dict(sc, transfer_assign=a) for a in (1, 0) for sc in (SMALL[3], SMALL[24], SMALL[30], SMALL[33], SMALL[38], SMALL[39])]
+    cases += [dict(synth.config2(), transfer_assign=1), dict(synth.config5([3, 30]), transfer_assign=1),
+              dict(synth.config4(mem_cap_mib=synth.CONFIG4_CAP_30PCT), transfer_assign=1)]
+    checked = improved = 0
+    for sc in cases:
+        g, o = B.Scenario(sc), O.Scenario(sc)
+        f = o.family(1)
+        if f is None:
+            continue
+        S, L, n = sc["PP"], sc["L"], f["stages"]
+        p0 = O.layout_p0(L, S)
+        lost = sorted({x // S for x in sc["failed_nodes"]})
+        print("migration scheme", {k: sc[k] for k in ("L", "PP", "DP", "failed_nodes", "transfer_assign")}, flush=True)
+        ranks = [0, f["n_part"] - 1] + [int(rng.integers(0, f["n_part"])) for _ in range(12)]
+        for d in lost:
+            alive = [j for j in range(S) if d * S + j not in sc["failed_nodes"]]
+            for r in ranks:
+                node_stage, stage_of, mib = g.transfer_plan(r, d)
+                assert node_stage == alive and sorted(stage_of) == list(range(n))
+                b = [0] + O.partition_unrank(L, n - 1, r) + [L]
+                fetch = [[O.missing_interval(sc["mem_mib"], b[j], b[j + 1], p0[h], p0[h + 1]) for j in range(n)] for h in alive]
+                assert sum(fetch[i][stage_of[i]] for i in range(n)) == mib
+                in_order = sum(fetch[j][j] for j in range(n))
+                if sc["transfer_assign"]:
+                    assert mib == O.min_assignment(fetch)[0] <= in_order
+                    improved += mib < in_order
+                else:
+                    assert mib == in_order and stage_of == list(range(n))
+                checked += 1
+        intact = [d for d in range(sc["DP"]) if d not in lost]
+        if intact:
+            with pytest.raises(B.ChmError) as e:
+                g.transfer_plan(0, intact[0])
+            assert e.value.code == B.ERR_ARG
+        with pytest.raises(B.ChmError) as e:
+            g.transfer_plan(f["n_part"], lost[0])
+        assert e.value.code == B.ERR_RANGE
+    assert checked > 150 and improved > 0
+
+
 def test_error_paths_and_degenerate_cases(B):
     import torch
     sc = SMALL[2]
