@@ -767,3 +767,118 @@ extern "C" int orc_search_joint(const orc_scenario *s, uint64_t first, uint64_t 
   }
   return best->cost == ORC_INF ? ORC_ERR_NO_FEASIBLE : ORC_OK;
 }
+
+// ---------------------------------------------------------------------------------------
+// re-planning over DP/PP degrees (Algorithm 1)
+// ---------------------------------------------------------------------------------------
+extern "C" int orc_integer_partition(int32_t n, int32_t dp, int32_t pp_min, int32_t pp_max, int32_t *lengths) {
+  if (dp < 1 || n < dp) return 0;
+  const int base = n / dp, extra = n % dp;
+  for (int p = 0; p < dp; ++p) {
+    lengths[p] = base + (p >= dp - extra ? 1 : 0);
+    if (lengths[p] < pp_min || lengths[p] > pp_max) return 0;
+  }
+  return 1;
+}
+
+extern "C" int64_t orc_best_split(int32_t L, const int32_t *fwd_us, const int32_t *bwd_us, const int32_t *mem_mib,
+                                  const int32_t *act_mib, int32_t n, int32_t M, int32_t mem_cap_mib, uint8_t *cuts) {
+  if (n < 1 || n > L || n > ORC_MAX_PP) return ORC_INF;
+  const uint64_t count = orc_binom(L - 1, n - 1);
+  int64_t best = ORC_INF;
+  uint8_t c[ORC_MAX_PP];
+  for (uint64_t rank = 0; rank < count; ++rank) {
+    orc_partition_unrank(L, n - 1, rank, c);
+    std::vector<int64_t> F(n, 0), B(n, 0);
+    bool fits = true;
+    for (int j = 0; j < n; ++j) {
+      const int lo = j == 0 ? 0 : c[j - 1], hi = j == n - 1 ? L : c[j];
+      int64_t stat = 0, act = 0;
+      for (int l = lo; l < hi; ++l) {
+        F[j] += fwd_us[l]; B[j] += bwd_us[l];
+        stat += mem_mib[l]; act += act_mib ? act_mib[l] : 0;
+      }
+      if (peak_memory(stat, act, n, j) > mem_cap_mib) fits = false;
+    }
+    if (!fits) continue;
+    const int64_t t = orc_makespan_1f1b(n, F.data(), B.data(), M);
+    if (t < best) { best = t; if (cuts) std::memcpy(cuts, c, (size_t)(n - 1)); }
+  }
+  return best;
+}
+
+extern "C" int orc_replan(const orc_replan_desc *d, orc_replan_plan *out) {
+  if (!d || !out) return ORC_ERR_ARG;
+  std::memset(out, 0, sizeof(*out));
+  if (d->L < 1 || d->L > ORC_MAX_L || !d->fwd_us || !d->bwd_us || !d->mem_mib || d->old_dp < 1 || d->old_dp > ORC_MAX_DP ||
+      d->old_pp < 1 || d->old_pp > ORC_MAX_PP || d->old_pp > d->L || d->n_failed < 0 || (d->n_failed > 0 && !d->failed_nodes) ||
+      d->dp_min < 1 || d->dp_max < d->dp_min || d->dp_max > ORC_MAX_DP || d->pp_min < 1 || d->pp_max < d->pp_min ||
+      d->pp_max > ORC_MAX_PP || d->micro_batches < 1 || d->comm_us < 0 || d->mem_cap_mib < 1 || d->horizon_us < 1 ||
+      d->restart_us < 0 || d->xfer_us_per_mib < 0)
+    return ORC_ERR_ARG;
+  for (int l = 0; l < d->L; ++l)
+    if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0 || (d->act_mib && d->act_mib[l] < 0)) return ORC_ERR_ARG;
+  const int old_nodes = d->old_dp * d->old_pp;
+  std::vector<char> dead(old_nodes, 0);
+  for (int i = 0; i < d->n_failed; ++i) {
+    const int n = d->failed_nodes[i];
+    if (n < 0 || n >= old_nodes || dead[n]) return ORC_ERR_ARG;
+    dead[n] = 1;
+  }
+  std::vector<int> p0(d->old_pp + 1);
+  orc_layout_p0(d->L, d->old_pp, p0.data());
+  std::vector<int64_t> pw(d->L + 1, 0);
+  for (int l = 0; l < d->L; ++l) pw[l + 1] = pw[l] + d->mem_mib[l];
+  std::vector<int> held_lo, held_hi;            // what every surviving node holds, in node-id order
+  for (int n = 0; n < old_nodes; ++n)
+    if (!dead[n]) { held_lo.push_back(p0[n % d->old_pp]); held_hi.push_back(p0[n % d->old_pp + 1]); }
+  const int N = (int)held_lo.size();
+
+  bool have = false;
+  i128 best_gain = 0;                           // H - t_trans of the best candidate so far
+  int64_t best_step = 1;
+  for (int dp = d->dp_min; dp <= d->dp_max; ++dp) {
+    int32_t len[ORC_MAX_DP], mb[ORC_MAX_DP];
+    if (!orc_integer_partition(N, dp, d->pp_min, d->pp_max, len)) continue;
+    bool usable = d->micro_batches >= dp;
+    for (int p = 0; p < dp; ++p) usable = usable && len[p] <= d->L;
+    if (!usable) continue;
+    ++out->n_candidates;
+    orc_distribute_batch(dp, d->micro_batches, len, mb);
+    orc_replan_plan cand;
+    std::memset(&cand, 0, sizeof(cand));
+    cand.dp = dp;
+    bool fits = true;
+    for (int p = 0; p < dp && fits; ++p) {
+      cand.length[p] = len[p]; cand.micro_batches[p] = mb[p];
+      const int64_t t = orc_best_split(d->L, d->fwd_us, d->bwd_us, d->mem_mib, d->act_mib, len[p], mb[p], d->mem_cap_mib, cand.cuts[p]);
+      if (t == ORC_INF) { fits = false; break; }
+      cand.pipeline_us[p] = t + (int64_t)(len[p] - 1) * d->comm_us;
+      cand.t_step_us = std::max(cand.t_step_us, cand.pipeline_us[p]);
+    }
+    if (!fits) continue;
+    // positions of the new layout, pipeline by pipeline, stage by stage
+    std::vector<int> pos_lo, pos_hi;
+    for (int p = 0; p < dp; ++p)
+      for (int j = 0; j < len[p]; ++j) {
+        pos_lo.push_back(j == 0 ? 0 : cand.cuts[p][j - 1]);
+        pos_hi.push_back(j == len[p] - 1 ? d->L : cand.cuts[p][j]);
+      }
+    std::vector<int64_t> fetch((size_t)N * N);
+    for (int i = 0; i < N; ++i)
+      for (int j = 0; j < N; ++j)
+        fetch[(size_t)i * N + j] = orc_missing_interval(pw.data(), pos_lo[j], pos_hi[j], held_lo[i], held_hi[i]);
+    cand.fetch_mib = orc_min_assignment(N, fetch.data(), nullptr);
+    cand.t_trans_us = d->restart_us + (int64_t)d->xfer_us_per_mib * cand.fetch_mib;
+    // (H - t_trans) / t_step, larger is better; exact comparison by cross-multiplication
+    const i128 gain = (i128)d->horizon_us - cand.t_trans_us;
+    if (!have || gain * best_step > best_gain * cand.t_step_us) {
+      const int32_t seen = out->n_candidates;
+      *out = cand;
+      out->n_candidates = seen;
+      out->found = 1;
+      have = true; best_gain = gain; best_step = cand.t_step_us;
+    }
+  }
+  return ORC_OK;
+}

@@ -117,6 +117,55 @@ int  orc_search_range(const orc_scenario *s, int32_t strategy, uint64_t part_fir
 /* plain joint sweep over every index in [first, first+count): slow, for tiny cases */
 int  orc_search_joint(const orc_scenario *s, uint64_t first, uint64_t count, orc_plan *best);
 
+/* --- re-planning over DP/PP degrees (Algorithm 1) ---------------------------------------
+ * Planner, "Execution Plan Search" and Algorithm 1 (get_parallel_strategy, get_execution_plan),
+ * for identical nodes as in the paper.  The surviving nodes are re-laid out as dp pipelines for
+ * every dp in [dp_min, dp_max]: integer_partition splits the node count as evenly as possible
+ * (the longer pipelines last, as in the paper's 7 nodes -> lengths 2,2,3), a candidate is kept
+ * when every length lies in [pp_min, pp_max]; distribute_batch shares the step's micro-batches
+ * in proportion to the pipeline lengths; split_layers picks, per pipeline, the contiguous split
+ * of the layers with the least 1F1B time among those that fit in memory (here: over ALL
+ * C(L-1, n-1) splits, first minimum in rank order; the paper enumerates only the placements of
+ * the remainder layers); the step time is the slowest pipeline (+ comm per stage boundary).
+ * The transition time is restart + xfer x (least total weight transfer over all one-to-one
+ * assignments of the surviving nodes to the positions of the new layout, Kuhn-Munkres).
+ * Candidates are ranked by the objective of the "Optimization Problem" paragraph: throughput x
+ * effective time ratio = B / t_step x (H - t_trans) / H with H the (constant) time between two
+ * faults, compared exactly by cross-multiplication; ties keep the smaller dp. */
+typedef struct {
+  int32_t L;
+  const int32_t *fwd_us, *bwd_us, *mem_mib, *act_mib;   /* [L]; act_mib may be NULL */
+  int32_t old_dp, old_pp;                     /* grid before the failure: node d*old_pp+s holds stage s of the even layout */
+  int32_t n_failed;
+  const int32_t *failed_nodes;
+  int32_t dp_min, dp_max, pp_min, pp_max;     /* R_dp, R_pp */
+  int32_t micro_batches;                      /* N_m of one step, over all pipelines */
+  int32_t comm_us, mem_cap_mib;
+  int64_t horizon_us;                         /* H */
+  int32_t restart_us, xfer_us_per_mib;
+} orc_replan_desc;
+
+typedef struct {
+  int32_t found;                              /* 0: no candidate has a layout that fits */
+  int32_t n_candidates;                       /* (dp, lengths) pairs that passed the range checks */
+  int32_t dp;
+  int32_t length[ORC_MAX_DP], micro_batches[ORC_MAX_DP];
+  uint8_t cuts[ORC_MAX_DP][32];               /* per pipeline: cuts[0..length-2] */
+  int64_t pipeline_us[ORC_MAX_DP];            /* 1F1B time + comm of every pipeline */
+  int64_t t_step_us, fetch_mib, t_trans_us;
+} orc_replan_plan;
+
+/* lengths of dp pipelines over n nodes, as even as possible, the longer ones last; returns 0
+ * when dp > n or a length falls outside [pp_min, pp_max] */
+int  orc_integer_partition(int32_t n, int32_t dp, int32_t pp_min, int32_t pp_max, int32_t *lengths);
+/* best contiguous split of the layers over n stages for a pipeline with M micro-batches
+ * (tables as in orc_replan_desc): least orc_makespan_1f1b among the splits whose every stage
+ * fits (static + (n - i) x activations <= cap), first minimum in partition-rank order.  Returns
+ * ORC_INF when nothing fits. */
+int64_t orc_best_split(int32_t L, const int32_t *fwd_us, const int32_t *bwd_us, const int32_t *mem_mib,
+                       const int32_t *act_mib, int32_t n, int32_t M, int32_t mem_cap_mib, uint8_t *cuts);
+int  orc_replan(const orc_replan_desc *d, orc_replan_plan *out);
+
 #ifdef __cplusplus
 }
 #endif

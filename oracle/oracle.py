@@ -40,6 +40,24 @@ class Desc(C.Structure):
                 ("transfer_assign", C.c_int32)]
 
 
+class ReplanDesc(C.Structure):
+    _fields_ = [("L", C.c_int32),
+                ("fwd_us", C.POINTER(C.c_int32)), ("bwd_us", C.POINTER(C.c_int32)),
+                ("mem_mib", C.POINTER(C.c_int32)), ("act_mib", C.POINTER(C.c_int32)),
+                ("old_dp", C.c_int32), ("old_pp", C.c_int32),
+                ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
+                ("dp_min", C.c_int32), ("dp_max", C.c_int32), ("pp_min", C.c_int32), ("pp_max", C.c_int32),
+                ("micro_batches", C.c_int32), ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32),
+                ("horizon_us", C.c_int64), ("restart_us", C.c_int32), ("xfer_us_per_mib", C.c_int32)]
+
+
+class ReplanPlan(C.Structure):
+    _fields_ = [("found", C.c_int32), ("n_candidates", C.c_int32), ("dp", C.c_int32),
+                ("length", C.c_int32 * 16), ("micro_batches", C.c_int32 * 16),
+                ("cuts", (C.c_uint8 * 32) * 16), ("pipeline_us", C.c_int64 * 16),
+                ("t_step_us", C.c_int64), ("fetch_mib", C.c_int64), ("t_trans_us", C.c_int64)]
+
+
 class Family(C.Structure):
     _fields_ = [("offset", C.c_uint64), ("n_part", C.c_uint64), ("n_reroute", C.c_uint64),
                 ("stages", C.c_int32), ("strategy", C.c_int32)]
@@ -78,6 +96,9 @@ def lib():
             "orc_distribute_batch": (None, [C.c_int32, C.c_int32, i32p, i32p]),
             "orc_layout_p0": (None, [C.c_int32, C.c_int32, i32p]),
             "orc_min_assignment": (C.c_int64, [C.c_int32, i64p, i32p]),
+            "orc_integer_partition": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p]),
+            "orc_best_split": (C.c_int64, [C.c_int32, i32p, i32p, i32p, i32p, C.c_int32, C.c_int32, C.c_int32, u8p]),
+            "orc_replan": (C.c_int, [C.POINTER(ReplanDesc), C.POINTER(ReplanPlan)]),
             "orc_open": (C.c_int, [C.POINTER(Desc), C.POINTER(C.c_void_p)]),
             "orc_close": (None, [C.c_void_p]),
             "orc_plan_space": (C.c_int, [C.c_void_p, C.POINTER(Space)]),
@@ -184,6 +205,62 @@ def min_assignment(cost):
     pos = np.zeros(c.shape[0], dtype=np.int32)
     total = lib().orc_min_assignment(c.shape[0], _ptr(c, C.c_int64), _ptr(pos, C.c_int32))
     return int(total), [int(x) for x in pos]
+
+
+def integer_partition(n, dp, pp_min, pp_max):
+    """pipeline lengths, or None when the split is impossible within the range"""
+    out = np.zeros(max(int(dp), 1), dtype=np.int32)
+    ok = lib().orc_integer_partition(n, dp, pp_min, pp_max, _ptr(out, C.c_int32))
+    return [int(x) for x in out[:dp]] if ok else None
+
+
+def best_split(fwd, bwd, mem, act, n, M, cap):
+    """(least 1F1B time or INF, cuts) over all contiguous splits into n stages that fit"""
+    f, b, m = (np.ascontiguousarray(x, dtype=np.int32) for x in (fwd, bwd, mem))
+    a = np.ascontiguousarray(act, dtype=np.int32) if act is not None else None
+    cuts = np.zeros(32, dtype=np.uint8)
+    t = lib().orc_best_split(len(f), _ptr(f, C.c_int32), _ptr(b, C.c_int32), _ptr(m, C.c_int32),
+                             _ptr(a, C.c_int32) if a is not None else None, n, M, cap, _ptr(cuts, C.c_uint8))
+    return int(t), [int(x) for x in cuts[:n - 1]]
+
+
+def replan_dict(p):
+    """plain dict of a re-planning result structure (field names shared by oracle and library)"""
+    if not p.found:
+        return {"found": False, "n_candidates": int(p.n_candidates)}
+    dp = int(p.dp)
+    return {"found": True, "n_candidates": int(p.n_candidates), "dp": dp,
+            "length": [int(p.length[i]) for i in range(dp)],
+            "micro_batches": [int(p.micro_batches[i]) for i in range(dp)],
+            "cuts": [[int(p.cuts[i][j]) for j in range(p.length[i] - 1)] for i in range(dp)],
+            "pipeline_us": [int(p.pipeline_us[i]) for i in range(dp)],
+            "t_step_us": int(p.t_step_us), "fetch_mib": int(p.fetch_mib), "t_trans_us": int(p.t_trans_us)}
+
+
+def replan(rp):
+    """orc_replan on a dict as produced by the seeded generators (synth.replan_case)"""
+    keep = []
+    d = ReplanDesc()
+    d.L = rp["L"]
+    for name in ("fwd_us", "bwd_us", "mem_mib", "act_mib"):
+        if rp.get(name) is None:
+            continue
+        a = np.ascontiguousarray(rp[name], dtype=np.int32)
+        keep.append(a)
+        setattr(d, name, _ptr(a, C.c_int32))
+    f = np.ascontiguousarray(rp.get("failed_nodes", []), dtype=np.int32)
+    keep.append(f)
+    d.n_failed = len(f)
+    if len(f):
+        d.failed_nodes = _ptr(f, C.c_int32)
+    for name in ("old_dp", "old_pp", "dp_min", "dp_max", "pp_min", "pp_max", "micro_batches", "comm_us",
+                 "mem_cap_mib", "horizon_us", "restart_us", "xfer_us_per_mib"):
+        setattr(d, name, int(rp[name]))
+    out = ReplanPlan()
+    rc = lib().orc_replan(C.byref(d), C.byref(out))
+    if rc:
+        raise OracleError(rc)
+    return replan_dict(out)
 
 
 def _plan_dict(p):

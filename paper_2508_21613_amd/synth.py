@@ -171,3 +171,21 @@ def small_random(seed, L=None, PP=None, DP=None, M=None, n_failed=None, hetero=N
         kw["reroute_cap"] = cap
     return scenario(L, PP, DP, M, fwd, bwd, mem, sorted(int(x) for x in nodes), 100 + int(r[7] % 100), mem_cap,
                     speed=speed, **kw)
+
+
+def replan_case(seed, L, old_dp, old_pp, failed, micro_batches, dp_range, pp_range, comm_us=150, cap_scale=2.2,
+                horizon_us=1_000_000_000, restart_us=8_000_000, xfer_us_per_mib=100, act=False, dist="uniform"):
+    """inputs of one re-planning over DP/PP degrees: seeded layer tables, the old grid with its failed
+    nodes, the DP and PP ranges to search, the step's micro-batch count and the transition constants"""
+    fwd, bwd, mem = layer_tables(seed, L, dist=dist)
+    n_left = old_dp * old_pp - len(failed)
+    shortest = max(1, min(pp_range[1], n_left // max(1, dp_range[0])))
+    rp = dict(L=L, fwd_us=fwd, bwd_us=bwd, mem_mib=mem, act_mib=None, old_dp=old_dp, old_pp=old_pp,
+              failed_nodes=[int(x) for x in failed], dp_min=dp_range[0], dp_max=dp_range[1], pp_min=pp_range[0],
+              pp_max=pp_range[1], micro_batches=micro_batches, comm_us=comm_us,
+              mem_cap_mib=int(int(mem.sum()) * cap_scale / max(1, min(old_pp, shortest))),
+              horizon_us=horizon_us, restart_us=restart_us, xfer_us_per_mib=xfer_us_per_mib)
+    if act:
+        rp["act_mib"] = randint(seed, 21, L, 20, 60).astype(np.int32)
+        rp["mem_cap_mib"] += int(rp["act_mib"].sum())
+    return rp

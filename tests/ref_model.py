@@ -216,3 +216,63 @@ class Model:
             for c in colex_partitions(self.L, self.S - 1):
                 out += [self.cost(2, c, rr) for rr in joint]
         return out
+
+
+# ----------------------------------------------------------------------------- re-planning (Algorithm 1)
+def replan(rp):
+    """Independent evaluation of the search over DP/PP degrees: even integer partition of the node
+    count, proportional micro-batches, per pipeline the best split by explicit-graph longest path,
+    least-transfer matching by scipy, candidates ranked with exact fractions."""
+    from fractions import Fraction
+    from scipy.optimize import linear_sum_assignment
+    import numpy as np
+    L = rp["L"]
+    f, b, m = ([int(x) for x in rp[k]] for k in ("fwd_us", "bwd_us", "mem_mib"))
+    a = [int(x) for x in rp["act_mib"]] if rp.get("act_mib") is not None else [0] * L
+    old_pp = rp["old_pp"]
+    p0 = layout_p0(L, old_pp)
+    held = [(p0[n % old_pp], p0[n % old_pp + 1]) for n in range(rp["old_dp"] * old_pp) if n not in rp["failed_nodes"]]
+    N = len(held)
+    best, n_cand = None, 0
+    for dp in range(rp["dp_min"], rp["dp_max"] + 1):
+        if dp > N:
+            continue
+        lens = sorted([N // dp] * (dp - N % dp) + [N // dp + 1] * (N % dp))
+        if min(lens) < rp["pp_min"] or max(lens) > rp["pp_max"] or max(lens) > L or rp["micro_batches"] < dp:
+            continue
+        n_cand += 1
+        mb = distribute(rp["micro_batches"], lens)
+        plan, ok = [], True
+        for n, M in zip(lens, mb):
+            choice = None
+            for cuts in colex_partitions(L, n - 1):
+                bounds = [0] + list(cuts) + [L]
+                if any(sum(m[bounds[j]:bounds[j + 1]]) + (n - j) * sum(a[bounds[j]:bounds[j + 1]]) > rp["mem_cap_mib"] for j in range(n)):
+                    continue
+                t = dag_makespan([sum(f[bounds[j]:bounds[j + 1]]) for j in range(n)],
+                                 [sum(b[bounds[j]:bounds[j + 1]]) for j in range(n)], M)
+                if choice is None or t < choice[0]:
+                    choice = (t, list(cuts))
+            if choice is None:
+                ok = False
+                break
+            plan.append(choice)
+        if not ok:
+            continue
+        pipeline_us = [t + (n - 1) * rp["comm_us"] for (t, _), n in zip(plan, lens)]
+        t_step = max(pipeline_us)
+        pos = []
+        for (t, cuts), n in zip(plan, lens):
+            bounds = [0] + cuts + [L]
+            pos += [(bounds[j], bounds[j + 1]) for j in range(n)]
+        cost = np.array([[sum(m[l] for l in range(lo, hi) if not (hl <= l < hh)) for (lo, hi) in pos] for (hl, hh) in held])
+        r, c = linear_sum_assignment(cost)
+        fetch = int(cost[r, c].sum())
+        t_trans = rp["restart_us"] + rp["xfer_us_per_mib"] * fetch
+        score = Fraction(rp["horizon_us"] - t_trans, t_step)
+        if best is None or score > best[0]:
+            best = (score, {"found": True, "dp": dp, "length": lens, "micro_batches": mb, "cuts": [c for _, c in plan],
+                            "pipeline_us": pipeline_us, "t_step_us": t_step, "fetch_mib": fetch, "t_trans_us": t_trans})
+    if best is None:
+        return {"found": False, "n_candidates": n_cand}
+    return dict(best[1], n_candidates=n_cand)

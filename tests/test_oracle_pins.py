@@ -607,3 +607,104 @@ def test_least_transfer_assignment_changes_some_plan_and_is_validated():
     assert p.plan_cost(1, [9, 11]) - s.plan_cost(1, [9, 11]) == 8 - 7
     # new stages [0,3) [3,6) [6,12): the survivors keep their own layers in stage order, 0+0+3, nothing is cheaper
     assert p.plan_cost(1, [3, 6]) == s.plan_cost(1, [3, 6])
+
+
+# ----------------------------------------------------------------------------- re-planning over DP/PP degrees
+def test_integer_partition_of_the_node_count():
+    g = golden()
+    assert O.integer_partition(7, 3, 1, 8) == [int(x) for x in g["lengths_7_nodes_3_pipelines"].split(",")]
+    assert O.integer_partition(32, 4, 1, 16) == [8, 8, 8, 8]
+    assert O.integer_partition(31, 4, 1, 16) == [7, 8, 8, 8]
+    assert O.integer_partition(31, 5, 1, 16) == [6, 6, 6, 6, 7]
+    assert O.integer_partition(31, 4, 8, 16) is None          # a pipeline of 7 is below the range
+    assert O.integer_partition(31, 4, 1, 7) is None           # pipelines of 8 are above it
+    assert O.integer_partition(3, 4, 1, 8) is None            # more pipelines than nodes
+    for n in range(1, 40):
+        for dp in range(1, n + 1):
+            lens = O.integer_partition(n, dp, 1, 64)
+            assert sum(lens) == n and max(lens) - min(lens) <= 1 and lens == sorted(lens)
+
+
+def test_best_split_closed_forms_and_memory_filter():
+    """uniform layers, n | L, a cap of exactly L/n layers: only the even split fits and its time is
+    eq. (original_step_time); without the cap the result is the minimum over all splits (brute force
+    with the explicit-graph longest path) and never worse than the even split"""
+    for n, k, M in [(2, 3, 4), (3, 2, 5), (4, 3, 2), (6, 2, 7), (1, 5, 3)]:
+        L = n * k
+        f, b = np.full(L, 700, np.int32), np.full(L, 1500, np.int32)
+        t, cuts = O.best_split(f, b, np.ones(L, np.int32), None, n, M, k)
+        assert t == (M + n - 1) * k * 2200 and cuts == [k * j for j in range(1, n)]
+        free, free_cuts = O.best_split(f, b, np.ones(L, np.int32), None, n, M, 10 ** 6)
+        times = [R.dag_makespan([700 * (hi - lo) for lo, hi in zip((0,) + c, c + (L,))],
+                                [1500 * (hi - lo) for lo, hi in zip((0,) + c, c + (L,))], M) for c in R.colex_partitions(L, n - 1)]
+        assert free == min(times) <= t and list(R.colex_partitions(L, n - 1)[times.index(min(times))]) == free_cuts
+    # the memory cap forbids the even split: stages of at most 2 layers do not exist for 7 layers over 3 stages
+    L = 7
+    f, b, m = np.full(L, 10, np.int32), np.full(L, 20, np.int32), np.full(L, 100, np.int32)
+    assert O.best_split(f, b, m, None, 3, 4, 200)[0] == O.INF
+    t, cuts = O.best_split(f, b, m, None, 3, 4, 300)
+    assert sorted(np.diff([0] + cuts + [L]).tolist()) == [2, 2, 3] and t != O.INF
+    # position-dependent peak: with activations the first stage may hold fewer layers than the last
+    a = np.full(L, 50, np.int32)
+    t2, cuts2 = O.best_split(f, b, m, a, 3, 4, 500)     # stage i of 3 peaks at layers * (100 + (3 - i) * 50)
+    sizes = np.diff([0] + cuts2 + [L]).tolist()
+    assert all(sz * (100 + (3 - i) * 50) <= 500 for i, sz in enumerate(sizes)) and sizes == [2, 2, 3]
+
+
+REPLAN = [
+    synth.replan_case(5, 10, 3, 3, [4], 12, (1, 4), (1, 6)),
+    synth.replan_case(6, 9, 2, 4, [1], 16, (1, 4), (1, 8), act=True),
+    synth.replan_case(7, 12, 4, 2, [3], 16, (2, 5), (1, 4)),                      # the paper's 8 -> 7 cards
+    synth.replan_case(8, 11, 3, 3, [0, 5], 9, (1, 5), (1, 7), horizon_us=20_000_000),
+    synth.replan_case(9, 8, 2, 3, [2, 3, 4], 6, (1, 3), (1, 3), act=True),
+    synth.replan_case(10, 13, 2, 5, [7], 10, (1, 3), (2, 6), dist="lognormal"),
+    synth.replan_case(11, 10, 3, 2, [], 12, (1, 6), (1, 6)),                       # nothing failed: may keep or change the grid
+    synth.replan_case(12, 9, 3, 3, [8], 7, (2, 4), (1, 5), xfer_us_per_mib=5000, horizon_us=60_000_000),
+    synth.replan_case(13, 12, 3, 4, [2, 6], 3, (1, 5), (1, 10)),                   # fewer micro-batches than some dp
+    synth.replan_case(14, 10, 2, 4, [0], 8, (1, 4), (1, 7), cap_scale=0.9),        # tight memory
+]
+
+
+@pytest.mark.parametrize("i", range(len(REPLAN)))
+def test_replan_matches_the_independent_model(i):
+    rp = REPLAN[i]
+    got, want = O.replan(rp), R.replan(rp)
+    assert got == want
+    if got["found"]:
+        assert got["t_step_us"] == max(got["pipeline_us"]) and sum(got["micro_batches"]) == rp["micro_batches"]
+        n_left = rp["old_dp"] * rp["old_pp"] - len(rp["failed_nodes"])
+        assert sum(got["length"]) == n_left
+        pf, pb = np.cumsum([0] + list(rp["fwd_us"])), np.cumsum([0] + list(rp["bwd_us"]))
+        for n, M, cuts, t in zip(got["length"], got["micro_batches"], got["cuts"], got["pipeline_us"]):
+            bnd = [0] + cuts + [rp["L"]]
+            F = [int(pf[bnd[j + 1]] - pf[bnd[j]]) for j in range(n)]
+            B = [int(pb[bnd[j + 1]] - pb[bnd[j]]) for j in range(n)]
+            assert O.makespan_1f1b(F, B, M) + (n - 1) * rp["comm_us"] == t
+
+
+def test_replan_objective_trades_step_time_against_transition_time():
+    """Optimization Problem: B / t_step x (H - t_trans) / H.  A long time between faults favours the
+    fastest step, a short one the cheapest transition; the same grid with nothing to move costs only the restart."""
+    rp = synth.replan_case(12, 9, 3, 3, [8], 7, (2, 4), (1, 5), xfer_us_per_mib=5000)
+    chosen = {}
+    for H in (10 ** 7 * 3, 10 ** 8, 10 ** 9, 10 ** 11):
+        got = O.replan(dict(rp, horizon_us=H))
+        assert got == R.replan(dict(rp, horizon_us=H))
+        chosen[H] = (got["dp"], got["t_step_us"], got["t_trans_us"])
+    assert len(set(chosen.values())) > 1, chosen
+    hs = sorted(chosen)
+    assert chosen[hs[-1]][1] <= chosen[hs[0]][1] and chosen[hs[0]][2] <= chosen[hs[-1]][2]
+    # no failure, only the old grid allowed, uniform layers and a cap of three layers per node: the old layout is the
+    # only one that fits, it is found again and nothing is fetched
+    L = 12
+    same = dict(synth.replan_case(1, L, 3, 4, [], 12, (3, 3), (4, 4)), fwd_us=np.full(L, 500, np.int32),
+                bwd_us=np.full(L, 900, np.int32), mem_mib=np.full(L, 10, np.int32), mem_cap_mib=30)
+    got = O.replan(same)
+    assert got["dp"] == 3 and got["length"] == [4, 4, 4] and got["cuts"] == [[3, 6, 9]] * 3
+    assert got["fetch_mib"] == 0 and got["t_trans_us"] == same["restart_us"]
+    assert got["t_step_us"] == (4 + 4 - 1) * 3 * 1400 + 3 * same["comm_us"]
+    # nothing fits / no candidate in range
+    assert O.replan(dict(same, mem_cap_mib=1)) == {"found": False, "n_candidates": 1}
+    assert O.replan(dict(same, pp_min=5, pp_max=5)) == {"found": False, "n_candidates": 0}
+    with pytest.raises(O.OracleError):
+        O.replan(dict(same, dp_min=0))
