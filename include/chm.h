@@ -200,6 +200,49 @@ int chm_reroute_shape(const chm_scenario *s, int32_t *n_affected, int32_t *peers
  * Used by the benchmark to put measured rates beside its nominal roofline peak. */
 int chm_valu_probe(int32_t kind, uint32_t iters, double *lane_ops_per_s, void *hip_stream);
 
+/* ---- Re-planning over DP/PP degrees (Planner, "Execution Plan Search" and Algorithm 1) --------------
+ * Identical nodes, as in the paper.  The nodes that survive are re-laid out as dp pipelines for every dp
+ * in [dp_min, dp_max]: the node count is split as evenly as possible (integer_partition; the longer
+ * pipelines last, 7 nodes over 3 pipelines = 2,2,3), a candidate is kept when every pipeline length lies
+ * in [pp_min, pp_max]; the step's micro-batches are shared in proportion to the lengths (distribute_batch);
+ * for every pipeline ALL contiguous splits of the layers over its stages are scored on the device (1F1B
+ * recurrence, memory filter) and the first minimum in partition-rank order is taken (split_layers; the
+ * paper enumerates only the placements of the remainder layers); the step time is the slowest pipeline,
+ * with comm_us per stage boundary.  Transition time = restart_us + xfer_us_per_mib x the least total MiB
+ * the nodes must fetch over all one-to-one assignments of surviving nodes to positions of the new layout
+ * (Restorer, "Weight Transfer"; solved on the device).  Candidates are ranked by the objective of the
+ * "Optimization Problem" paragraph, throughput x effective time ratio = B / t_step x (H - t_trans) / H,
+ * compared exactly; ties keep the smaller dp. */
+typedef struct {
+  int32_t L;                                  /* layers, 1..128 */
+  const int32_t *fwd_us, *bwd_us, *mem_mib;   /* [L], host; as in chm_scenario_desc */
+  const int32_t *act_mib;                     /* [L] or NULL */
+  int32_t old_dp, old_pp;                     /* grid before the failure: node d*old_pp+s holds stage s of the even layout */
+  int32_t n_failed;                           /* 0 .. old_dp*old_pp */
+  const int32_t *failed_nodes;                /* [n_failed] distinct node ids */
+  int32_t dp_min, dp_max;                     /* R_dp, within 1..16 */
+  int32_t pp_min, pp_max;                     /* R_pp, within 1..32 */
+  int32_t micro_batches;                      /* N_m of one step over all pipelines, >= 1; a pipeline gets at most 256 */
+  int32_t comm_us, mem_cap_mib;
+  int64_t horizon_us;                         /* H: time between two faults (transition + training), >= 1 */
+  int32_t restart_us, xfer_us_per_mib;
+} chm_replan_desc;
+
+typedef struct {
+  int32_t found;                              /* 0: no candidate in range has a layout that fits in memory */
+  int32_t n_candidates;                       /* (dp, lengths) pairs that passed the range checks */
+  int32_t dp;
+  int32_t length[16], micro_batches[16];      /* per pipeline of the chosen plan */
+  uint8_t cuts[16][32];                       /* per pipeline: cuts[0..length-2] */
+  int64_t pipeline_us[16];                    /* 1F1B time + comm of every pipeline */
+  int64_t t_step_us, fetch_mib, t_trans_us;
+} chm_replan_plan;
+
+/* Runs the search above.  All pointers are host pointers; tables are copied.  Synchronises hip_stream.
+ * Errors: CHM_ERR_ARG, CHM_ERR_OVERFLOW (a split space or cost bound beyond 62 bits), CHM_ERR_HIP.
+ * No candidate / nothing fits is not an error: CHM_OK with out->found = 0. */
+int chm_replan(const chm_replan_desc *desc, chm_replan_plan *out, void *hip_stream);
+
 void chm_free_scenario(chm_scenario *s);
 const char *chm_strerror(int code);
 

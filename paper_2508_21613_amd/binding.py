@@ -17,7 +17,7 @@ INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
            "chm_search_range", "chm_search_ranks", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
-           "chm_reroute_shape", "chm_transfer_plan", "chm_valu_probe", "chm_free_scenario",
+           "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
 
@@ -45,6 +45,24 @@ class Best(C.Structure):
     _fields_ = [("index", C.c_uint64), ("cost", C.c_int64), ("strategy", C.c_int32),
                 ("stages", C.c_int32), ("cuts", C.c_uint8 * 32), ("n_affected", C.c_int32),
                 ("affected_stage", C.c_int32 * 4), ("reroute", (C.c_uint16 * 16) * 4)]
+
+
+class ReplanDesc(C.Structure):
+    _fields_ = [("L", C.c_int32),
+                ("fwd_us", C.POINTER(C.c_int32)), ("bwd_us", C.POINTER(C.c_int32)),
+                ("mem_mib", C.POINTER(C.c_int32)), ("act_mib", C.POINTER(C.c_int32)),
+                ("old_dp", C.c_int32), ("old_pp", C.c_int32),
+                ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
+                ("dp_min", C.c_int32), ("dp_max", C.c_int32), ("pp_min", C.c_int32), ("pp_max", C.c_int32),
+                ("micro_batches", C.c_int32), ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32),
+                ("horizon_us", C.c_int64), ("restart_us", C.c_int32), ("xfer_us_per_mib", C.c_int32)]
+
+
+class ReplanPlan(C.Structure):
+    _fields_ = [("found", C.c_int32), ("n_candidates", C.c_int32), ("dp", C.c_int32),
+                ("length", C.c_int32 * 16), ("micro_batches", C.c_int32 * 16),
+                ("cuts", (C.c_uint8 * 32) * 16), ("pipeline_us", C.c_int64 * 16),
+                ("t_step_us", C.c_int64), ("fetch_mib", C.c_int64), ("t_trans_us", C.c_int64)]
 
 
 class Timing(C.Structure):
@@ -82,6 +100,9 @@ def lib():
         L.chm_get_timing.argtypes = [vp, C.POINTER(Timing)]
         L.chm_family_classes.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.chm_reroute_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
+        L.chm_transfer_plan.argtypes = [vp, C.c_uint64, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_uint8 * 32),
+                                        C.POINTER(C.c_uint8 * 32), C.POINTER(C.c_int64), vp]
+        L.chm_replan.argtypes = [C.POINTER(ReplanDesc), C.POINTER(ReplanPlan), vp]
         L.chm_valu_probe.argtypes = [C.c_int32, C.c_uint32, C.POINTER(C.c_double), vp]
         L.chm_free_scenario.argtypes = [vp]
         L.chm_free_scenario.restype = None
@@ -124,6 +145,39 @@ def valu_probe(kind, iters=4000, stream=None):
     out = C.c_double()
     _check(lib().chm_valu_probe(kind, iters, C.byref(out), _stream_ptr(stream)))
     return float(out.value)
+
+
+def replan(rp, stream=None):
+    """chm_replan: search over DP/PP degrees for the nodes that survive (Algorithm 1).  `rp` is a dict with the
+    fields of chm_replan_desc; returns a dict with the fields of chm_replan_plan."""
+    keep = []
+    d = ReplanDesc()
+    d.L = rp["L"]
+    for name in ("fwd_us", "bwd_us", "mem_mib", "act_mib"):
+        if rp.get(name) is None:
+            continue
+        a = np.ascontiguousarray(rp[name], dtype=np.int32)
+        keep.append(a)
+        setattr(d, name, a.ctypes.data_as(C.POINTER(C.c_int32)))
+    f = np.ascontiguousarray(rp.get("failed_nodes", []), dtype=np.int32)
+    keep.append(f)
+    d.n_failed = len(f)
+    if len(f):
+        d.failed_nodes = f.ctypes.data_as(C.POINTER(C.c_int32))
+    for name in ("old_dp", "old_pp", "dp_min", "dp_max", "pp_min", "pp_max", "micro_batches", "comm_us",
+                 "mem_cap_mib", "horizon_us", "restart_us", "xfer_us_per_mib"):
+        setattr(d, name, int(rp[name]))
+    p = ReplanPlan()
+    _check(lib().chm_replan(C.byref(d), C.byref(p), _stream_ptr(stream)))
+    if not p.found:
+        return {"found": False, "n_candidates": int(p.n_candidates)}
+    dp = int(p.dp)
+    return {"found": True, "n_candidates": int(p.n_candidates), "dp": dp,
+            "length": [int(p.length[i]) for i in range(dp)],
+            "micro_batches": [int(p.micro_batches[i]) for i in range(dp)],
+            "cuts": [[int(p.cuts[i][j]) for j in range(p.length[i] - 1)] for i in range(dp)],
+            "pipeline_us": [int(p.pipeline_us[i]) for i in range(dp)],
+            "t_step_us": int(p.t_step_us), "fetch_mib": int(p.fetch_mib), "t_trans_us": int(p.t_trans_us)}
 
 
 class Scenario:
@@ -261,7 +315,7 @@ class Scenario:
         """chm_transfer_plan: (fault-free stage of every surviving node, new stage it hosts, MiB fetched in total)"""
         n, mib = C.c_int32(), C.c_int64()
         node_stage, stage_of_node = (C.c_uint8 * 32)(), (C.c_uint8 * 32)()
-        _check(lib().chm_transfer_plan(self._h, C.c_uint64(part_rank), pipeline, C.byref(n), node_stage, stage_of_node,
+        _check(lib().chm_transfer_plan(self._h, C.c_uint64(part_rank), pipeline, C.byref(n), C.byref(node_stage), C.byref(stage_of_node),
                                        C.byref(mib), _stream_ptr(stream)))
         return [int(node_stage[i]) for i in range(n.value)], [int(stage_of_node[i]) for i in range(n.value)], int(mib.value)
 

@@ -12,6 +12,7 @@
 #include "../../include/chm.h"
 #include "chm_dev.h"
 #include "chm_fast.h"
+#include "chm_internal.h"
 
 namespace {
 
@@ -484,17 +485,10 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
   return CHM_OK;
 }
 
-}  // namespace
 
-extern "C" int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **out) {
-  if (!out) return CHM_ERR_ARG;
-  *out = nullptr;
-  int rc = validate(desc);
-  if (rc) return rc;
-  chm_scenario *s = new (std::nothrow) chm_scenario();
-  if (!s) return CHM_ERR_HIP;
-  rc = build_model(desc, s);
-  if (rc) { delete s; return rc; }
+// Allocates the device side of a scenario whose host model is complete and uploads its tables.
+// Takes ownership of s: on failure it is released and *out stays null.
+int upload_scenario(chm_scenario *s, chm_scenario **out) {
   bool ok = hipGetDevice(&s->device) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_scn, sizeof(DevScenario)) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_comp, s->comp.size() * sizeof(uint64_t)) == hipSuccess;
@@ -514,6 +508,59 @@ extern "C" int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **o
   if (!ok) { release(s); return CHM_ERR_HIP; }
   *out = s;
   return CHM_OK;
+}
+
+}  // namespace
+
+extern "C" int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **out) {
+  if (!out) return CHM_ERR_ARG;
+  *out = nullptr;
+  int rc = validate(desc);
+  if (rc) return rc;
+  chm_scenario *s = new (std::nothrow) chm_scenario();
+  if (!s) return CHM_ERR_HIP;
+  rc = build_model(desc, s);
+  if (rc) { delete s; return rc; }
+  return upload_scenario(s, out);
+}
+
+void chm_internal_share_micro_batches(int D, int total, const int *nodes, int *out) { share_micro_batches(D, total, nodes, out); }
+
+// A scenario that holds one stand-alone pipeline of n stages and M micro-batches on identical
+// nodes: its only family is the re-partition one (a single pipeline class, no untouched
+// pipelines), with horizon 1 and no transition terms, so a plan's cost is the pipeline's 1F1B
+// time plus comm per stage boundary and chm_search_best returns the best split of the layers.
+int chm_internal_load_pipeline(int32_t L, const int32_t *fwd_us, const int32_t *bwd_us, const int32_t *mem_mib,
+                               const int32_t *act_mib, int32_t n, int32_t M, int32_t comm_us, int32_t mem_cap_mib,
+                               chm_scenario **out) {
+  *out = nullptr;
+  chm_scenario_desc d;
+  memset(&d, 0, sizeof(d));
+  d.L = L; d.PP = n; d.DP = 1; d.M = M;
+  d.fwd_us = fwd_us; d.bwd_us = bwd_us; d.mem_mib = mem_mib; d.act_mib = act_mib;
+  d.comm_us = comm_us; d.mem_cap_mib = mem_cap_mib; d.horizon_steps = 1;
+  int rc = validate(&d);
+  if (rc) return rc;
+  chm_scenario *s = new (std::nothrow) chm_scenario();
+  if (!s) return CHM_ERR_HIP;
+  rc = build_model(&d, s);          // no failure: strategies 0 and 2 of the intact pipeline; replaced below
+  if (rc) { delete s; return rc; }
+  DevScenario &h = s->h;
+  for (int k = 0; k < 3; ++k) { DevFamily &f = h.fam[k]; memset(&f, 0, sizeof(f)); for (int j = 0; j < DEV_MAX_S; ++j) f.mem_coef[j] = -1; }
+  h.n_aff = 0; h.n_fixed = 0;
+  DevFamily &f = h.fam[1];
+  f.strategy = 1; f.stages = n; f.doubled = 0; f.n_cls = 1; f.n_reroute = 1;
+  f.n_part = h.binom[n - 1][L - 1];
+  DevClass &c = f.cls[0];
+  c.n = n; c.M = M;
+  for (int j = 0; j < n; ++j) { c.src[j] = (uint8_t)j; c.host[j] = (uint8_t)j; c.q[j] = 65536u; f.mem_coef[j] = n - j; }
+  memset(&s->space, 0, sizeof(s->space));
+  if (f.n_part == UINT64_MAX || f.n_part >= (1ull << 62)) { delete s; return CHM_ERR_OVERFLOW; }
+  s->space.n_families = 1;
+  s->space.fam[0].offset = 0; s->space.fam[0].n_part = f.n_part; s->space.fam[0].n_reroute = 1;
+  s->space.fam[0].stages = n; s->space.fam[0].strategy = 1;
+  s->space.n_plans = f.n_part;
+  return upload_scenario(s, out);
 }
 
 extern "C" int chm_plan_space(const chm_scenario *s, chm_space *out) {

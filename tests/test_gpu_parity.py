@@ -252,6 +252,49 @@ def test_migration_scheme_of_the_re_partition_strategy(B):
     assert checked > 150 and improved > 0
 
 
+REPLAN = [
+    synth.replan_case(5, 10, 3, 3, [4], 12, (1, 4), (1, 6)),
+    synth.replan_case(6, 9, 2, 4, [1], 16, (1, 4), (1, 8), act=True),
+    synth.replan_case(7, 12, 4, 2, [3], 16, (2, 5), (1, 4)),
+    synth.replan_case(8, 11, 3, 3, [0, 5], 9, (1, 5), (1, 7), horizon_us=20_000_000),
+    synth.replan_case(9, 8, 2, 3, [2, 3, 4], 6, (1, 3), (1, 3), act=True),
+    synth.replan_case(10, 13, 2, 5, [7], 10, (1, 3), (2, 6), dist="lognormal"),
+    synth.replan_case(11, 10, 3, 2, [], 12, (1, 6), (1, 6)),
+    synth.replan_case(12, 9, 3, 3, [8], 7, (2, 4), (1, 5), xfer_us_per_mib=5000, horizon_us=60_000_000),
+    synth.replan_case(13, 12, 3, 4, [2, 6], 3, (1, 5), (1, 10)),
+    synth.replan_case(14, 10, 2, 4, [0], 8, (1, 4), (1, 7), cap_scale=0.9),
+    synth.replan_case(15, 14, 4, 4, [5, 10], 24, (2, 7), (1, 7), act=True),               # 14 nodes, up to 7 pipelines
+    synth.replan_case(16, 16, 8, 4, [0, 9, 18, 27], 64, (5, 9), (2, 6)),                   # 28 nodes
+    synth.replan_case(17, 12, 16, 4, list(range(0, 64, 7)), 96, (12, 16), (3, 5)),         # 54 nodes, 16 pipelines
+    synth.replan_case(18, 6, 2, 2, [0, 1, 2, 3], 4, (1, 2), (1, 2)),                       # nothing survived
+]
+
+
+@pytest.mark.parametrize("i", range(len(REPLAN)))
+def test_replan_over_dp_pp_degrees(B, i):
+    """chm_replan against the oracle's Algorithm 1: every field of the chosen plan is an integer that
+    both sides fix uniquely (first minimum in rank order per pipeline, smaller dp on ties)"""
+    rp = REPLAN[i]
+    print("replan", i, {k: rp[k] for k in ("L", "old_dp", "old_pp", "failed_nodes", "dp_min", "dp_max", "pp_min", "pp_max", "micro_batches")}, flush=True)
+    want = O.replan(rp)
+    got = B.replan(rp)
+    assert got == want, (got, want)
+    for H in (3 * 10 ** 7, 10 ** 11):
+        assert B.replan(dict(rp, horizon_us=H)) == O.replan(dict(rp, horizon_us=H))
+
+
+def test_replan_argument_checks(B):
+    rp = REPLAN[0]
+    for key, val in [("dp_min", 0), ("dp_max", 17), ("pp_max", 33), ("micro_batches", 0), ("horizon_us", 0), ("failed_nodes", [1, 1]),
+                     ("failed_nodes", [9])]:
+        with pytest.raises(B.ChmError) as e:
+            B.replan(dict(rp, **{key: val}))
+        assert e.value.code == B.ERR_ARG
+        with pytest.raises(O.OracleError):
+            O.replan(dict(rp, **{key: val}))
+    assert B.replan(dict(rp, mem_cap_mib=1)) == O.replan(dict(rp, mem_cap_mib=1)) == {"found": False, "n_candidates": 3}
+
+
 def test_error_paths_and_degenerate_cases(B):
     import torch
     sc = SMALL[2]
