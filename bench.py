@@ -41,6 +41,55 @@ def algorithmic_ops(fam, feasible):
     return fam["n_part"] * light + feasible * heavy, light, heavy
 
 
+def bench_replan(args, note, B, synth):
+    """A step = one chm_replan over the 31 surviving nodes of the 32-card shape: every contiguous split of the
+    48 layers for every pipeline length the DP range 2..6 produces within 4..12 stages, the least-transfer
+    assignment of the 31 nodes per candidate, and the exact ratio objective."""
+    import torch
+    rp = synth.replan32()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            B.replan(rp, stream=stream)
+            note("warm-up step %d done" % i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        search_ms = assign_ms = 0.0
+        for _ in range(args.steps):
+            plan, st = B.replan(rp, stream=stream, with_stats=True)
+            search_ms += st["search_ms"]
+            assign_ms += st["assign_ms"]
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0
+    ms = wall * 1e3 / args.steps
+    search_ms /= args.steps
+    assign_ms /= args.steps
+    achieved = st["algorithmic_ops"] / (search_ms * 1e-3) / 1e12
+    out = {"metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
+           "value": st["splits_scored"] / (ms * 1e-3), "unit": "plans/s", "n_gpus": 1, "steps": args.steps,
+           "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+           "dtype": "int32", "data": "synthetic",
+           "config": {"workload": "replan32: L=48, 31 of 32 nodes survive, DP 2..6, PP 4..12, 64 micro-batches per step; "
+                                  "every contiguous split per pipeline length", "splits_scored_per_step": st["splits_scored"],
+                      "splits_feasible": st["splits_feasible"], "candidates": plan["n_candidates"]},
+           "time_to_best_plan_ms": ms, "search_kernels_ms": search_ms, "assignment_kernels_ms": assign_ms,
+           "best": plan,
+           "roofline": {"bound": "alu", "kernel": "split search (all pipeline lengths)", "achieved": achieved,
+                        "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
+                        "algorithmic_ops_per_launch": st["algorithmic_ops"]}}
+    if not args.no_cpu_baseline:
+        from oracle import oracle as O
+        # the oracle's exhaustive split of the shortest pipeline length of the candidates (a bounded sample)
+        n, M = 6, 12
+        t0 = time.perf_counter()
+        O.best_split(rp["fwd_us"], rp["bwd_us"], rp["mem_mib"], None, n, M, rp["mem_cap_mib"])
+        t = time.perf_counter() - t0
+        n_splits = O.binom(rp["L"] - 1, n - 1)
+        out["cpu_baseline"] = {"value": n_splits / t, "unit": "plans/s", "cores": 1, "kind": "oracle",
+                               "sample": "oracle best split over all %d splits into %d stages, %d micro-batches (%.1f s)" % (n_splits, n, M, t)}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -49,8 +98,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--ttb-runs", type=int, default=10)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config5"],
-                    help="config2 (the 32-card shape) is the benchmark; the others are for profiling")
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config5", "replan32"],
+                    help="config2 (the 32-card shape) is the benchmark; the others are for profiling; replan32 times "
+                         "chm_replan (search over DP/PP degrees) for the 31 nodes that survive in config2")
     ap.add_argument("--transfer-assign", type=int, default=0, choices=[0, 1],
                     help="1: the re-partition strategy counts the weights to fetch under the least-transfer "
                          "assignment of survivors to new stages (default 0: survivors in stage order)")
@@ -73,6 +123,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     torch.cuda.set_device(0)
+    if args.workload == "replan32":
+        return bench_replan(args, note, B, synth)
     workloads = {
         "config1": ("config1: L=32 PP=4 DP=2 M=8, 1 failed node", lambda: [synth.config1()]),
         "config2": ("config2: L=48 PP=8 DP=4 M=16, 1 failed node", lambda: [synth.config2()]),

@@ -236,6 +236,11 @@ typedef struct {
   uint8_t cuts[16][32];                       /* per pipeline: cuts[0..length-2] */
   int64_t pipeline_us[16];                    /* 1F1B time + comm of every pipeline */
   int64_t t_step_us, fetch_mib, t_trans_us;
+  /* work accounting of the call (all candidates, not only the chosen one) */
+  uint64_t splits_scored;                     /* contiguous splits scored by the search kernels */
+  uint64_t splits_feasible;                   /* of which passed the memory filter */
+  double algorithmic_ops;                     /* 4n per split + (4nM + 6n + 4) per split that fits, n stages, M micro-batches */
+  float search_ms, assign_ms;                 /* HIP-event time of the split-search kernels / of the assignment kernels */
 } chm_replan_plan;
 
 /* Runs the search above.  All pointers are host pointers; tables are copied.  Synchronises hip_stream.

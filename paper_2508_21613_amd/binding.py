@@ -62,7 +62,9 @@ class ReplanPlan(C.Structure):
     _fields_ = [("found", C.c_int32), ("n_candidates", C.c_int32), ("dp", C.c_int32),
                 ("length", C.c_int32 * 16), ("micro_batches", C.c_int32 * 16),
                 ("cuts", (C.c_uint8 * 32) * 16), ("pipeline_us", C.c_int64 * 16),
-                ("t_step_us", C.c_int64), ("fetch_mib", C.c_int64), ("t_trans_us", C.c_int64)]
+                ("t_step_us", C.c_int64), ("fetch_mib", C.c_int64), ("t_trans_us", C.c_int64),
+                ("splits_scored", C.c_uint64), ("splits_feasible", C.c_uint64), ("algorithmic_ops", C.c_double),
+                ("search_ms", C.c_float), ("assign_ms", C.c_float)]
 
 
 class Timing(C.Structure):
@@ -147,9 +149,10 @@ def valu_probe(kind, iters=4000, stream=None):
     return float(out.value)
 
 
-def replan(rp, stream=None):
+def replan(rp, stream=None, with_stats=False):
     """chm_replan: search over DP/PP degrees for the nodes that survive (Algorithm 1).  `rp` is a dict with the
-    fields of chm_replan_desc; returns a dict with the fields of chm_replan_plan."""
+    fields of chm_replan_desc; returns a dict with the plan fields of chm_replan_plan (and, with_stats, a second
+    dict with the work accounting of the call)."""
     keep = []
     d = ReplanDesc()
     d.L = rp["L"]
@@ -169,6 +172,13 @@ def replan(rp, stream=None):
         setattr(d, name, int(rp[name]))
     p = ReplanPlan()
     _check(lib().chm_replan(C.byref(d), C.byref(p), _stream_ptr(stream)))
+    stats = {"splits_scored": int(p.splits_scored), "splits_feasible": int(p.splits_feasible),
+             "algorithmic_ops": float(p.algorithmic_ops), "search_ms": float(p.search_ms), "assign_ms": float(p.assign_ms)}
+    plan = _replan_dict(p)
+    return (plan, stats) if with_stats else plan
+
+
+def _replan_dict(p):
     if not p.found:
         return {"found": False, "n_candidates": int(p.n_candidates)}
     dp = int(p.dp)

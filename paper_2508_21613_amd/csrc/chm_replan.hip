@@ -122,6 +122,12 @@ struct Scratch {
 
 struct SplitResult { int rc; int64_t cost; uint8_t cuts[32]; };
 
+struct Events {
+  hipEvent_t a = nullptr, b = nullptr;
+  bool ok() { return hipEventCreate(&a) == hipSuccess && hipEventCreate(&b) == hipSuccess; }
+  ~Events() { if (a) (void)hipEventDestroy(a); if (b) (void)hipEventDestroy(b); }
+};
+
 int check(const chm_replan_desc *d) {
   if (!d) return CHM_ERR_ARG;
   if (d->L < 1 || d->L > CHM_MAX_L || !d->fwd_us || !d->bwd_us || !d->mem_mib) return CHM_ERR_ARG;
@@ -180,6 +186,11 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
     if (!ok) return CHM_ERR_HIP;
   }
 
+  Events ev;
+  if (!ev.ok()) return CHM_ERR_HIP;
+  uint64_t splits_scored = 0, splits_feasible = 0;
+  double algorithmic_ops = 0;
+  float search_ms = 0, assign_ms = 0;
   std::map<std::pair<int, int>, SplitResult> best_split;      // (stages, micro-batches) -> best split of the layers
   bool have = false;
   __int128 best_gain = 0;
@@ -211,8 +222,16 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
                                           d->mem_cap_mib, &pipe);
         if (r.rc) return r.rc;
         chm_best b;
+        chm_timing tm;
+        (void)chm_set_timing(pipe, 1);
         r.rc = chm_search_best(pipe, 1u << 1, &b, hip_stream);
+        (void)chm_get_timing(pipe, &tm);
         chm_free_scenario(pipe);
+        splits_scored += tm.partitions[1];
+        splits_feasible += tm.feasible[1];
+        search_ms += tm.family_ms[1];
+        algorithmic_ops += 4.0 * len[p] * (double)tm.partitions[1] +
+                           (4.0 * len[p] * mb[p] + 6.0 * len[p] + 4.0) * (double)tm.feasible[1];
         if (r.rc != CHM_OK && r.rc != CHM_ERR_NO_FEASIBLE) return r.rc;
         r.cost = b.cost;
         memcpy(r.cuts, b.cuts, sizeof(r.cuts));
@@ -237,10 +256,14 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
     if (hipMemcpyAsync(sc.d_pos, pos.data(), pos.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) != hipSuccess) return CHM_ERR_HIP;
     AssignArgs a;
     a.n = N; a.L = L; a.held = sc.d_held; a.pos = sc.d_pos; a.pw = sc.d_pw; a.total = sc.d_total; a.position_of_node = sc.d_assign;
+    if (hipEventRecord(ev.a, st) != hipSuccess) return CHM_ERR_HIP;
     hipLaunchKernelGGL(k_min_assignment, dim3(1), dim3(64), 0, st, a);
-    if (hipGetLastError() != hipSuccess) return CHM_ERR_HIP;
+    if (hipGetLastError() != hipSuccess || hipEventRecord(ev.b, st) != hipSuccess) return CHM_ERR_HIP;
     if (hipMemcpyAsync(sc.h_total, sc.d_total, sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess) return CHM_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return CHM_ERR_HIP;     // also keeps `pos` alive until the copy is done
+    float ms = 0;
+    if (hipEventElapsedTime(&ms, ev.a, ev.b) != hipSuccess) return CHM_ERR_HIP;
+    assign_ms += ms;
     cand.fetch_mib = *sc.h_total;
     cand.t_trans_us = (int64_t)d->restart_us + (int64_t)d->xfer_us_per_mib * cand.fetch_mib;
     // (H - t_trans) / t_step, larger is better; exact comparison by cross-multiplication
@@ -253,5 +276,10 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
       have = true; best_gain = gain; best_step = cand.t_step_us;
     }
   }
+  out->splits_scored = splits_scored;
+  out->splits_feasible = splits_feasible;
+  out->algorithmic_ops = algorithmic_ops;
+  out->search_ms = search_ms;
+  out->assign_ms = assign_ms;
   return CHM_OK;
 }

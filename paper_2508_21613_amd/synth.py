@@ -189,3 +189,15 @@ def replan_case(seed, L, old_dp, old_pp, failed, micro_batches, dp_range, pp_ran
         rp["act_mib"] = randint(seed, 21, L, 20, 60).astype(np.int32)
         rp["mem_cap_mib"] += int(rp["act_mib"].sum())
     return rp
+
+
+def replan32(seed=BASE_SEED + 2, dp_range=(2, 6), pp_range=(4, 12)):
+    """Re-planning of the 32-card shape after its one failure: the tables, failed node, comm and cap of
+    config2; DP within 2 of the old 4, pipelines of 4..12 stages; 64 micro-batches per step; the time
+    between two faults is 2048 fault-free steps of about 415 ms."""
+    sc = config2(seed)
+    return dict(L=sc["L"], fwd_us=sc["fwd_us"], bwd_us=sc["bwd_us"], mem_mib=sc["mem_mib"], act_mib=None,
+                old_dp=sc["DP"], old_pp=sc["PP"], failed_nodes=sc["failed_nodes"], dp_min=dp_range[0], dp_max=dp_range[1],
+                pp_min=pp_range[0], pp_max=pp_range[1], micro_batches=sc["DP"] * sc["M"], comm_us=sc["comm_us"],
+                mem_cap_mib=sc["mem_cap_mib"], horizon_us=2048 * 415_400, restart_us=sc["reconf_us"][1],
+                xfer_us_per_mib=sc["xfer_us_per_mib"])
