@@ -266,6 +266,27 @@ extern "C" int64_t orc_min_assignment(int32_t n, const int64_t *cost, int32_t *p
   return total;
 }
 
+extern "C" int32_t orc_comm_rounds(int32_t L, int32_t n_devices, const uint8_t *holds) {
+  if (L < 1) return 0;
+  std::vector<std::vector<char>> adj(L, std::vector<char>(L, 0));
+  for (int dev = 0; dev < n_devices; ++dev)
+    for (int a = 0; a < L; ++a)
+      for (int b = 0; b < L; ++b)
+        if (a != b && holds[(size_t)dev * L + a] && holds[(size_t)dev * L + b]) adj[a][b] = 1;
+  std::vector<int> colour(L, -1);
+  int used = 0;
+  for (int l = 0; l < L; ++l) {
+    std::vector<char> taken(L + 1, 0);
+    for (int o = 0; o < l; ++o)
+      if (adj[l][o]) taken[colour[o]] = 1;
+    int c = 0;
+    while (taken[c]) ++c;
+    colour[l] = c;
+    used = std::max(used, c + 1);
+  }
+  return used;
+}
+
 // ---------------------------------------------------------------------------------------
 // scenario
 // ---------------------------------------------------------------------------------------
@@ -277,6 +298,7 @@ struct orc_scenario {
   int64_t comm, cap, K, reconf[3], xfer;
   int reroute_cap;
   int transfer_assign;                                  // strategy 1: 1 = least-transfer node-to-stage assignment
+  int64_t allreduce;                                    // time of one round of gradient communication, 0 = not modelled
   std::vector<int> p0;                                  // [S+1]
   // failed-node distribution
   std::vector<int> fail_in_replica, fail_in_stage;      // [D], [S]
@@ -423,6 +445,30 @@ int64_t base_cost_terms(const orc_scenario *s, int strategy, int k, const uint8_
       }
     }
   }
+  if (s->allreduce > 0) {
+    // which layers every device holds under this plan (see the header), then the colouring
+    std::vector<uint8_t> holds;
+    int n_dev = 0;
+    auto add_device = [&](int lo, int hi, int lo2, int hi2) {
+      holds.resize((size_t)(n_dev + 1) * s->L, 0);
+      for (int l = lo; l < hi; ++l) holds[(size_t)n_dev * s->L + l] = 1;
+      for (int l = lo2; l < hi2; ++l) holds[(size_t)n_dev * s->L + l] = 1;
+      ++n_dev;
+    };
+    for (int d = 0; d < s->D; ++d) {
+      if (strategy == 1 && s->fail_in_replica[d]) {
+        for (int j = 0; j < s->SB; ++j) add_device(st.lo[j], st.lo[j + 1], 0, 0);
+        continue;
+      }
+      for (int j = 0; j < S; ++j) {
+        if (s->dead(d, j)) continue;
+        if (strategy == 0) add_device(st.lo[j], st.lo[j + 1], st.lo[(j + 1) % S], st.lo[(j + 1) % S + 1]);
+        else if (strategy == 1) add_device(s->p0[j], s->p0[j + 1], 0, 0);
+        else add_device(st.lo[j], st.lo[j + 1], 0, 0);
+      }
+    }
+    t_step += s->allreduce * orc_comm_rounds(s->L, n_dev, holds.data());
+  }
   *t_step_out = t_step;
   *reconf_out = s->reconf[strategy] + s->xfer * missing;
   return 0;
@@ -540,7 +586,8 @@ extern "C" int orc_open(const orc_desc *d, orc_scenario **out) {
       d->DP < 1 || d->DP > ORC_MAX_DP || d->M < 1 || d->M > ORC_MAX_M ||
       d->n_failed < 0 || d->n_failed > ORC_MAX_FAILED || !d->fwd_us || !d->bwd_us || !d->mem_mib ||
       (d->n_failed > 0 && !d->failed_nodes) || d->comm_us < 0 || d->mem_cap_mib < 1 ||
-      d->horizon_steps < 1 || d->xfer_us_per_mib < 0 || d->transfer_assign < 0 || d->transfer_assign > 1)
+      d->horizon_steps < 1 || d->xfer_us_per_mib < 0 || d->transfer_assign < 0 || d->transfer_assign > 1 ||
+      d->allreduce_us < 0)
     return ORC_ERR_ARG;
   for (int i = 0; i < 3; ++i) if (d->reconf_us[i] < 0) return ORC_ERR_ARG;
   orc_scenario *s = new orc_scenario();
@@ -548,6 +595,7 @@ extern "C" int orc_open(const orc_desc *d, orc_scenario **out) {
   s->comm = d->comm_us; s->cap = d->mem_cap_mib; s->K = d->horizon_steps; s->xfer = d->xfer_us_per_mib;
   s->reroute_cap = d->reroute_cap;
   s->transfer_assign = d->transfer_assign;
+  s->allreduce = d->allreduce_us;
   for (int i = 0; i < 3; ++i) s->reconf[i] = d->reconf_us[i];
   s->pf.assign(s->L + 1, 0); s->pb.assign(s->L + 1, 0); s->pw.assign(s->L + 1, 0); s->pa.assign(s->L + 1, 0);
   for (int l = 0; l < s->L; ++l) {
@@ -632,7 +680,7 @@ extern "C" int orc_open(const orc_desc *d, orc_scenario **out) {
   s->space.n_plans = off;
   // --- cost bound: a makespan never exceeds (M+S-1) x the largest stage time ---
   i128 tot_fb = (i128)(s->pf[s->L] + s->pb[s->L]) * 2 * ((qmax + 65535) / 65536);
-  i128 t_max = (i128)(s->D * s->M + s->S - 1) * tot_fb + (i128)s->S * s->comm;
+  i128 t_max = (i128)(s->D * s->M + s->S - 1) * tot_fb + (i128)s->S * s->comm + (i128)s->L * s->allreduce;
   i128 pen_max = (i128)ORC_MAX_FAILED * (ORC_MAX_FAILED * s->M) * tot_fb;
   i128 reconf_max = (i128)std::max(std::max(s->reconf[0], s->reconf[1]), s->reconf[2]) + (i128)s->xfer * s->pw[s->L];
   if ((i128)s->K * (t_max + pen_max) + reconf_max >= ((i128)1 << 62)) overflow = true;
@@ -814,7 +862,7 @@ extern "C" int orc_replan(const orc_replan_desc *d, orc_replan_plan *out) {
       d->old_pp < 1 || d->old_pp > ORC_MAX_PP || d->old_pp > d->L || d->n_failed < 0 || (d->n_failed > 0 && !d->failed_nodes) ||
       d->dp_min < 1 || d->dp_max < d->dp_min || d->dp_max > ORC_MAX_DP || d->pp_min < 1 || d->pp_max < d->pp_min ||
       d->pp_max > ORC_MAX_PP || d->micro_batches < 1 || d->comm_us < 0 || d->mem_cap_mib < 1 || d->horizon_us < 1 ||
-      d->restart_us < 0 || d->xfer_us_per_mib < 0)
+      d->restart_us < 0 || d->xfer_us_per_mib < 0 || d->allreduce_us < 0)
     return ORC_ERR_ARG;
   for (int l = 0; l < d->L; ++l)
     if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0 || (d->act_mib && d->act_mib[l] < 0)) return ORC_ERR_ARG;
@@ -864,6 +912,13 @@ extern "C" int orc_replan(const orc_replan_desc *d, orc_replan_plan *out) {
         pos_lo.push_back(j == 0 ? 0 : cand.cuts[p][j - 1]);
         pos_hi.push_back(j == len[p] - 1 ? d->L : cand.cuts[p][j]);
       }
+    if (d->allreduce_us > 0) {                // one device per position of the new layout
+      std::vector<uint8_t> holds((size_t)N * d->L, 0);
+      for (int j = 0; j < N; ++j)
+        for (int l = pos_lo[j]; l < pos_hi[j]; ++l) holds[(size_t)j * d->L + l] = 1;
+      cand.comm_rounds = orc_comm_rounds(d->L, N, holds.data());
+      cand.t_step_us += (int64_t)d->allreduce_us * cand.comm_rounds;
+    }
     std::vector<int64_t> fetch((size_t)N * N);
     for (int i = 0; i < N; ++i)
       for (int j = 0; j < N; ++j)

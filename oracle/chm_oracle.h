@@ -27,6 +27,12 @@
  *     Cost[i][j] = what node i must fetch to become the j-th node of the new pipeline,
  *     by the Kuhn-Munkres algorithm.  The step time keeps the survivors in stage order (the
  *     paper's nodes are identical, so its estimator does not depend on the assignment).
+ *   - rounds of gradient communication (allreduce_us > 0): Restorer subsection, "Asymmetric
+ *     Communication": greedy colouring of the layer graph whose edges join layers held by one
+ *     device; the step time grows by rounds x allreduce_us.  Devices of a plan: redundant
+ *     computation - every surviving node holds its stage and its ring successor's; re-partition
+ *     - the untouched pipelines' nodes hold the fault-free stages, the j-th survivor of a failed
+ *     pipeline holds new stage j; rerouting - every surviving node holds its stage.
  *   - argmin with first-strict-minimum: Algorithm 1, get_execution_plan.
  *
  * Pure conventions with no counterpart in the paper ("parity unpinned": only
@@ -61,6 +67,7 @@ typedef struct {
   const int32_t *act_mib;                     /* [L] activation memory per micro-batch in flight; NULL = none */
   int32_t transfer_assign;                    /* re-partition strategy: 0 = the j-th surviving node hosts new stage j,
                                                  1 = the node-to-stage assignment with the least total weight transfer */
+  int32_t allreduce_us;                       /* time of one round of data-parallel gradient communication; 0 = not modelled */
 } orc_desc;
 
 typedef struct { uint64_t offset, n_part, n_reroute; int32_t stages, strategy; } orc_family;
@@ -93,6 +100,12 @@ void     orc_layout_p0(int32_t L, int32_t S, int32_t *bounds /* [S+1] */);
  * node of the new plan).  cost is row-major, cost[i*n+j] >= 0; position_of_node (nullable)
  * receives one optimal assignment. */
 int64_t  orc_min_assignment(int32_t n, const int64_t *cost, int32_t *position_of_node);
+/* Rounds of data-parallel communication (Restorer, "Asymmetric Communication"): every layer is a
+ * vertex, two layers are joined when some device holds both, layers of one colour communicate in
+ * the same round.  Greedy colouring: layers in index order, each takes the smallest colour that no
+ * already coloured neighbour has; the result is the number of colours used.  holds is row-major
+ * [n_devices][L], non-zero where the device holds the layer. */
+int32_t  orc_comm_rounds(int32_t L, int32_t n_devices, const uint8_t *holds);
 
 /* --- scenario level ------------------------------------------------------------------- */
 typedef struct orc_scenario orc_scenario;
@@ -143,6 +156,7 @@ typedef struct {
   int32_t comm_us, mem_cap_mib;
   int64_t horizon_us;                         /* H */
   int32_t restart_us, xfer_us_per_mib;
+  int32_t allreduce_us;                       /* per communication round, added to the step time after the splits are chosen */
 } orc_replan_desc;
 
 typedef struct {
@@ -152,7 +166,8 @@ typedef struct {
   int32_t length[ORC_MAX_DP], micro_batches[ORC_MAX_DP];
   uint8_t cuts[ORC_MAX_DP][32];               /* per pipeline: cuts[0..length-2] */
   int64_t pipeline_us[ORC_MAX_DP];            /* 1F1B time + comm of every pipeline */
-  int64_t t_step_us, fetch_mib, t_trans_us;
+  int64_t t_step_us, fetch_mib, t_trans_us;   /* t_step includes comm_rounds x allreduce_us */
+  int32_t comm_rounds;
 } orc_replan_plan;
 
 /* lengths of dp pipelines over n nodes, as even as possible, the longer ones last; returns 0

@@ -37,7 +37,7 @@ class Desc(C.Structure):
                 ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32), ("reroute_cap", C.c_int32),
                 ("horizon_steps", C.c_int32), ("reconf_us", C.c_int32 * 3),
                 ("xfer_us_per_mib", C.c_int32), ("act_mib", C.POINTER(C.c_int32)),
-                ("transfer_assign", C.c_int32)]
+                ("transfer_assign", C.c_int32), ("allreduce_us", C.c_int32)]
 
 
 class ReplanDesc(C.Structure):
@@ -48,14 +48,16 @@ class ReplanDesc(C.Structure):
                 ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
                 ("dp_min", C.c_int32), ("dp_max", C.c_int32), ("pp_min", C.c_int32), ("pp_max", C.c_int32),
                 ("micro_batches", C.c_int32), ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32),
-                ("horizon_us", C.c_int64), ("restart_us", C.c_int32), ("xfer_us_per_mib", C.c_int32)]
+                ("horizon_us", C.c_int64), ("restart_us", C.c_int32), ("xfer_us_per_mib", C.c_int32),
+                ("allreduce_us", C.c_int32)]
 
 
 class ReplanPlan(C.Structure):
     _fields_ = [("found", C.c_int32), ("n_candidates", C.c_int32), ("dp", C.c_int32),
                 ("length", C.c_int32 * 16), ("micro_batches", C.c_int32 * 16),
                 ("cuts", (C.c_uint8 * 32) * 16), ("pipeline_us", C.c_int64 * 16),
-                ("t_step_us", C.c_int64), ("fetch_mib", C.c_int64), ("t_trans_us", C.c_int64)]
+                ("t_step_us", C.c_int64), ("fetch_mib", C.c_int64), ("t_trans_us", C.c_int64),
+                ("comm_rounds", C.c_int32)]
 
 
 class Family(C.Structure):
@@ -99,6 +101,7 @@ def lib():
             "orc_integer_partition": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, i32p]),
             "orc_best_split": (C.c_int64, [C.c_int32, i32p, i32p, i32p, i32p, C.c_int32, C.c_int32, C.c_int32, u8p]),
             "orc_replan": (C.c_int, [C.POINTER(ReplanDesc), C.POINTER(ReplanPlan)]),
+            "orc_comm_rounds": (C.c_int32, [C.c_int32, C.c_int32, u8p]),
             "orc_open": (C.c_int, [C.POINTER(Desc), C.POINTER(C.c_void_p)]),
             "orc_close": (None, [C.c_void_p]),
             "orc_plan_space": (C.c_int, [C.c_void_p, C.POINTER(Space)]),
@@ -207,6 +210,13 @@ def min_assignment(cost):
     return int(total), [int(x) for x in pos]
 
 
+def comm_rounds(holds):
+    """greedy colouring rounds for a (devices x layers) 0/1 array of which device holds which layer"""
+    h = np.ascontiguousarray(holds, dtype=np.uint8)
+    assert h.ndim == 2
+    return int(lib().orc_comm_rounds(h.shape[1], h.shape[0], _ptr(h, C.c_uint8)))
+
+
 def integer_partition(n, dp, pp_min, pp_max):
     """pipeline lengths, or None when the split is impossible within the range"""
     out = np.zeros(max(int(dp), 1), dtype=np.int32)
@@ -234,7 +244,8 @@ def replan_dict(p):
             "micro_batches": [int(p.micro_batches[i]) for i in range(dp)],
             "cuts": [[int(p.cuts[i][j]) for j in range(p.length[i] - 1)] for i in range(dp)],
             "pipeline_us": [int(p.pipeline_us[i]) for i in range(dp)],
-            "t_step_us": int(p.t_step_us), "fetch_mib": int(p.fetch_mib), "t_trans_us": int(p.t_trans_us)}
+            "t_step_us": int(p.t_step_us), "fetch_mib": int(p.fetch_mib), "t_trans_us": int(p.t_trans_us),
+            "comm_rounds": int(p.comm_rounds)}
 
 
 def replan(rp):
@@ -256,6 +267,7 @@ def replan(rp):
     for name in ("old_dp", "old_pp", "dp_min", "dp_max", "pp_min", "pp_max", "micro_batches", "comm_us",
                  "mem_cap_mib", "horizon_us", "restart_us", "xfer_us_per_mib"):
         setattr(d, name, int(rp[name]))
+    d.allreduce_us = int(rp.get("allreduce_us", 0))
     out = ReplanPlan()
     rc = lib().orc_replan(C.byref(d), C.byref(out))
     if rc:
@@ -305,6 +317,7 @@ class Scenario:
             self._keep.append(a)
             d.act_mib = _ptr(a, C.c_int32)
         d.transfer_assign = int(sc.get("transfer_assign", 0))
+        d.allreduce_us = int(sc.get("allreduce_us", 0))
         h = C.c_void_p()
         rc = lib().orc_open(C.byref(d), C.byref(h))
         if rc:

@@ -98,6 +98,19 @@ def distribute(total, nodes):
         out[empty[0]] += 1
 
 
+def greedy_rounds(L, devices):
+    """Restorer, "Asymmetric Communication": colour the layers in index order with the smallest colour not
+    used by an earlier layer that shares a device; `devices` is a list of sets of layers"""
+    colour = {}
+    for l in range(L):
+        seen = {colour[o] for dev in devices if l in dev for o in dev if o < l}
+        c = 0
+        while c in seen:
+            c += 1
+        colour[l] = c
+    return max(colour.values()) + 1 if colour else 0
+
+
 class Model:
     def __init__(self, sc):
         self.sc = sc
@@ -202,6 +215,20 @@ class Model:
                 t += max(rr[a][i] * (scale(fs[s], self.q[d][s]) + scale(bs[s], self.q[d][s]))
                          for i, d in enumerate(self.peers[a]))
             miss = sum(self.missing(bounds[j], bounds[j + 1], self.p0[j], self.p0[j + 1]) for j in range(S))
+        if sc.get("allreduce_us", 0):
+            stage = [set(range(bounds[j], bounds[j + 1])) for j in range(n)]
+            devices = []
+            for d in range(D):
+                alive = [j for j in range(S) if not self.dead[d][j]]
+                if strategy == 0:
+                    devices += [stage[j] | stage[(j + 1) % S] for j in alive]
+                elif strategy == 1 and self.fail_rep[d]:
+                    devices += stage
+                elif strategy == 1:
+                    devices += [set(range(self.p0[j], self.p0[j + 1])) for j in range(S)]
+                else:
+                    devices += [stage[j] for j in alive]
+            t += sc["allreduce_us"] * greedy_rounds(self.L, devices)
         return self.K * t + sc["reconf_us"][strategy] + sc["xfer_us_per_mib"] * miss
 
     def all_costs(self):
@@ -265,6 +292,10 @@ def replan(rp):
         for (t, cuts), n in zip(plan, lens):
             bounds = [0] + cuts + [L]
             pos += [(bounds[j], bounds[j + 1]) for j in range(n)]
+        rounds = 0
+        if rp.get("allreduce_us", 0):
+            rounds = greedy_rounds(L, [set(range(lo, hi)) for lo, hi in pos])
+            t_step += rp["allreduce_us"] * rounds
         cost = np.array([[sum(m[l] for l in range(lo, hi) if not (hl <= l < hh)) for (lo, hi) in pos] for (hl, hh) in held])
         r, c = linear_sum_assignment(cost)
         fetch = int(cost[r, c].sum())
@@ -272,7 +303,8 @@ def replan(rp):
         score = Fraction(rp["horizon_us"] - t_trans, t_step)
         if best is None or score > best[0]:
             best = (score, {"found": True, "dp": dp, "length": lens, "micro_batches": mb, "cuts": [c for _, c in plan],
-                            "pipeline_us": pipeline_us, "t_step_us": t_step, "fetch_mib": fetch, "t_trans_us": t_trans})
+                            "pipeline_us": pipeline_us, "t_step_us": t_step, "fetch_mib": fetch, "t_trans_us": t_trans,
+                            "comm_rounds": rounds})
     if best is None:
         return {"found": False, "n_candidates": n_cand}
     return dict(best[1], n_candidates=n_cand)

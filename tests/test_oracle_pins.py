@@ -708,3 +708,105 @@ def test_replan_objective_trades_step_time_against_transition_time():
     assert O.replan(dict(same, pp_min=5, pp_max=5)) == {"found": False, "n_candidates": 0}
     with pytest.raises(O.OracleError):
         O.replan(dict(same, dp_min=0))
+
+
+# ----------------------------------------------------------------------------- rounds of gradient communication
+def chromatic_number(L, devices):
+    adj = [[any(a in d and b in d for d in devices) and a != b for b in range(L)] for a in range(L)]
+    for k in range(1, L + 1):
+        for col in itertools.product(range(k), repeat=L):
+            if all(not adj[a][b] or col[a] != col[b] for a in range(L) for b in range(a)):
+                return k
+    return L
+
+
+def holds_matrix(L, devices):
+    h = np.zeros((len(devices), L), dtype=np.uint8)
+    for i, d in enumerate(devices):
+        h[i, sorted(d)] = 1
+    return h
+
+
+def test_comm_rounds_greedy_colouring():
+    """Restorer, "Asymmetric Communication".  The greedy colouring is proper by construction; it can never use
+    fewer colours than the chromatic number or than the layers of the fullest device, nor more than the largest
+    degree + 1; for devices that hold contiguous layer ranges (any mix of contiguous splits) the graph is an
+    interval graph and left-to-right greedy is optimal: rounds = layers of the fullest device."""
+    rng = np.random.default_rng(17)
+    for trial in range(60):
+        L = int(rng.integers(2, 8))
+        devices = [set(int(x) for x in rng.choice(L, size=int(rng.integers(1, L + 1)), replace=False)) for _ in range(int(rng.integers(1, 5)))]
+        got = O.comm_rounds(holds_matrix(L, devices))
+        assert got == R.greedy_rounds(L, devices)
+        chi = chromatic_number(L, devices)
+        degree = max(len(set().union(*[d for d in devices if l in d] or [set()]) - {l}) for l in range(L))
+        assert max(len(d) for d in devices) <= chi <= got <= degree + 1
+    for trial in range(40):                             # unions of contiguous splits of the same layers
+        L = int(rng.integers(3, 9))
+        devices = []
+        for _ in range(int(rng.integers(1, 4))):
+            cuts = sorted(rng.choice(np.arange(1, L), size=int(rng.integers(0, L - 1)), replace=False).tolist())
+            b = [0] + cuts + [L]
+            devices += [set(range(b[j], b[j + 1])) for j in range(len(b) - 1)]
+        got = O.comm_rounds(holds_matrix(L, devices))
+        assert got == max(len(d) for d in devices) == chromatic_number(L, devices)
+    # one device per layer: everything in one round; one device with everything: one round per layer
+    assert O.comm_rounds(np.eye(5, dtype=np.uint8)) == 1
+    assert O.comm_rounds(np.ones((1, 7), dtype=np.uint8)) == 7
+    # a ring of three devices holding layers {0,1} {1,2} {2,0}: a triangle needs three rounds although no device holds three
+    assert O.comm_rounds(holds_matrix(3, [{0, 1}, {1, 2}, {2, 0}])) == 3
+    # greedy in index order is not optimal in general
+    crown = [{0, 3}, {1, 2}, {2, 3}]                    # edges 0-3, 1-2, 2-3: bipartite, but greedy gives 0,0,1,2 -> 3 colours
+    assert O.comm_rounds(holds_matrix(4, crown)) == 3 and chromatic_number(4, crown) == 2
+
+
+SMALL_AR = [dict(sc, allreduce_us=300 + 40 * i) for i, sc in enumerate(SMALL)] + [
+    dict(synth.small_random(2030, L=9, PP=3, DP=2, M=3, n_failed=1, hetero=False), allreduce_us=1000, transfer_assign=1),
+    dict(synth.small_random(2031, L=8, PP=2, DP=2, M=4, n_failed=1, hetero=True), allreduce_us=777),      # two-stage ring
+    dict(synth.small_random(2032, L=10, PP=5, DP=1, M=3, n_failed=1, hetero=False), allreduce_us=500),     # a single pipeline
+]
+
+
+@pytest.mark.parametrize("i", range(len(SMALL_AR)))
+def test_costs_with_communication_rounds_match_the_independent_model(i):
+    sc = SMALL_AR[i]
+    model, s = R.Model(sc), O.Scenario(sc)
+    want = model.all_costs()
+    assert s.n_plans == len(want)
+    got = s.score(0, s.n_plans)
+    assert [int(x) for x in got] == want
+    plain = O.Scenario(dict(sc, allreduce_us=0)).score(0, s.n_plans)
+    feasible = plain != O.INF
+    extra = (got[feasible] - plain[feasible]) // (sc["horizon_steps"] * sc["allreduce_us"])
+    assert ((got[feasible] - plain[feasible]) % (sc["horizon_steps"] * sc["allreduce_us"]) == 0).all()
+    assert (extra >= 1).all() and (extra <= sc["L"]).all() and (got[~feasible] == O.INF).all()
+
+
+def test_communication_rounds_closed_forms():
+    """hand-worked colourings: rerouting devices hold one stage each (rounds = layers of the largest stage);
+    redundant-computation devices hold two ring-adjacent stages (an even ring alternates two colour blocks,
+    an odd ring of three needs a third block)"""
+    S, D, M, per, f, b, ar = 4, 2, 4, 3, 100, 200, 1000
+    sc = uniform_scenario(S, D, M, per, f, b, [], reconf_us=(0, 0, 0), horizon_steps=1, allreduce_us=ar)
+    s, p = O.Scenario(sc), O.Scenario(dict(sc, allreduce_us=0))
+    assert s.plan_cost(2, even_cuts(S, per)) - p.plan_cost(2, even_cuts(S, per)) == per * ar
+    assert s.plan_cost(2, [1, 2, 3]) - p.plan_cost(2, [1, 2, 3]) == (S * per - 3) * ar       # the last stage holds all but three
+    # redundant computation, 4 stages of 3: stages get colours 0-2, 3-5, 0-2, 3-5 -> 6 rounds = layers of one node
+    assert s.plan_cost(0, even_cuts(S, per)) - p.plan_cost(0, even_cuts(S, per)) == 2 * per * ar
+    # 3 stages of 2 form an odd ring: colours 0-1, 2-3, 4-5 -> 6 rounds although every node holds only 4 layers
+    sc3 = uniform_scenario(3, 2, 4, 2, f, b, [], reconf_us=(0, 0, 0), horizon_steps=1, allreduce_us=ar)
+    s3, p3 = O.Scenario(sc3), O.Scenario(dict(sc3, allreduce_us=0))
+    assert s3.plan_cost(0, [2, 4]) - p3.plan_cost(0, [2, 4]) == 6 * ar
+    with pytest.raises(O.OracleError):
+        O.Scenario(dict(sc, allreduce_us=-1))
+
+
+def test_replan_with_communication_rounds():
+    for i, rp in enumerate(REPLAN[:8]):
+        rp = dict(rp, allreduce_us=2000 + 500 * i)
+        got = O.replan(rp)
+        assert got == R.replan(rp)
+        if got["found"]:
+            sizes = [hi - lo for n, cuts in zip(got["length"], got["cuts"]) for lo, hi in zip([0] + cuts, cuts + [rp["L"]])]
+            assert got["comm_rounds"] == max(sizes)
+            assert got["t_step_us"] == max(got["pipeline_us"]) + rp["allreduce_us"] * got["comm_rounds"]
