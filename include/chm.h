@@ -94,6 +94,14 @@ typedef struct {
                                          1 = the one-to-one assignment with the least total transfer (Restorer, "Weight
                                          Transfer": minimum-cost matching on Cost[i][j] = MiB node i must fetch to hold new
                                          stage j).  The step time keeps the survivors in stage order in both cases. */
+  int32_t allreduce_us;               /* time of one round of data-parallel gradient communication, >= 0; 0 = not modelled.
+                                         The step time of a plan grows by rounds x allreduce_us, rounds = colours the greedy
+                                         colouring (layers in index order, smallest free colour) gives the graph whose vertices
+                                         are the layers and whose edges join layers held by one device (Restorer, "Asymmetric
+                                         Communication").  Devices: redundant computation - every surviving node holds its
+                                         stage and its ring successor's; re-partition - nodes of untouched pipelines hold the
+                                         fault-free stages, the j-th survivor of a failed pipeline holds new stage j;
+                                         rerouting - every surviving node holds its stage. */
 } chm_scenario_desc;
 
 typedef struct { uint64_t offset, n_part, n_reroute; int32_t stages, strategy; } chm_family;
@@ -226,6 +234,8 @@ typedef struct {
   int32_t comm_us, mem_cap_mib;
   int64_t horizon_us;                         /* H: time between two faults (transition + training), >= 1 */
   int32_t restart_us, xfer_us_per_mib;
+  int32_t allreduce_us;                       /* per round of gradient communication (see chm_scenario_desc), added to the
+                                                 step time of a candidate after its splits are chosen; 0 = not modelled */
 } chm_replan_desc;
 
 typedef struct {
@@ -235,7 +245,8 @@ typedef struct {
   int32_t length[16], micro_batches[16];      /* per pipeline of the chosen plan */
   uint8_t cuts[16][32];                       /* per pipeline: cuts[0..length-2] */
   int64_t pipeline_us[16];                    /* 1F1B time + comm of every pipeline */
-  int64_t t_step_us, fetch_mib, t_trans_us;
+  int64_t t_step_us, fetch_mib, t_trans_us;   /* t_step_us includes comm_rounds x allreduce_us */
+  int32_t comm_rounds;                        /* 0 when allreduce_us is 0 */
   /* work accounting of the call (all candidates, not only the chosen one) */
   uint64_t splits_scored;                     /* contiguous splits scored by the search kernels */
   uint64_t splits_feasible;                   /* of which passed the memory filter */

@@ -29,7 +29,7 @@ class Desc(C.Structure):
                 ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32), ("reroute_cap", C.c_int32),
                 ("horizon_steps", C.c_int32), ("reconf_us", C.c_int32 * 3),
                 ("xfer_us_per_mib", C.c_int32), ("act_mib", C.POINTER(C.c_int32)),
-                ("transfer_assign", C.c_int32)]
+                ("transfer_assign", C.c_int32), ("allreduce_us", C.c_int32)]
 
 
 class Family(C.Structure):
@@ -55,7 +55,8 @@ class ReplanDesc(C.Structure):
                 ("n_failed", C.c_int32), ("failed_nodes", C.POINTER(C.c_int32)),
                 ("dp_min", C.c_int32), ("dp_max", C.c_int32), ("pp_min", C.c_int32), ("pp_max", C.c_int32),
                 ("micro_batches", C.c_int32), ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32),
-                ("horizon_us", C.c_int64), ("restart_us", C.c_int32), ("xfer_us_per_mib", C.c_int32)]
+                ("horizon_us", C.c_int64), ("restart_us", C.c_int32), ("xfer_us_per_mib", C.c_int32),
+                ("allreduce_us", C.c_int32)]
 
 
 class ReplanPlan(C.Structure):
@@ -63,6 +64,7 @@ class ReplanPlan(C.Structure):
                 ("length", C.c_int32 * 16), ("micro_batches", C.c_int32 * 16),
                 ("cuts", (C.c_uint8 * 32) * 16), ("pipeline_us", C.c_int64 * 16),
                 ("t_step_us", C.c_int64), ("fetch_mib", C.c_int64), ("t_trans_us", C.c_int64),
+                ("comm_rounds", C.c_int32),
                 ("splits_scored", C.c_uint64), ("splits_feasible", C.c_uint64), ("algorithmic_ops", C.c_double),
                 ("search_ms", C.c_float), ("assign_ms", C.c_float)]
 
@@ -170,6 +172,7 @@ def replan(rp, stream=None, with_stats=False):
     for name in ("old_dp", "old_pp", "dp_min", "dp_max", "pp_min", "pp_max", "micro_batches", "comm_us",
                  "mem_cap_mib", "horizon_us", "restart_us", "xfer_us_per_mib"):
         setattr(d, name, int(rp[name]))
+    d.allreduce_us = int(rp.get("allreduce_us", 0))
     p = ReplanPlan()
     _check(lib().chm_replan(C.byref(d), C.byref(p), _stream_ptr(stream)))
     stats = {"splits_scored": int(p.splits_scored), "splits_feasible": int(p.splits_feasible),
@@ -187,7 +190,8 @@ def _replan_dict(p):
             "micro_batches": [int(p.micro_batches[i]) for i in range(dp)],
             "cuts": [[int(p.cuts[i][j]) for j in range(p.length[i] - 1)] for i in range(dp)],
             "pipeline_us": [int(p.pipeline_us[i]) for i in range(dp)],
-            "t_step_us": int(p.t_step_us), "fetch_mib": int(p.fetch_mib), "t_trans_us": int(p.t_trans_us)}
+            "t_step_us": int(p.t_step_us), "fetch_mib": int(p.fetch_mib), "t_trans_us": int(p.t_trans_us),
+            "comm_rounds": int(p.comm_rounds)}
 
 
 class Scenario:
@@ -220,6 +224,7 @@ class Scenario:
             keep.append(a)
             d.act_mib = a.ctypes.data_as(C.POINTER(C.c_int32))
         d.transfer_assign = int(sc.get("transfer_assign", 0))
+        d.allreduce_us = int(sc.get("allreduce_us", 0))
         self._h = C.c_void_p()
         _check(lib().chm_load_scenario(C.byref(d), C.byref(self._h)))
         sp = Space()

@@ -43,6 +43,9 @@ struct DevScenario {
   int32_t p0[DEV_MAX_S + 1];    // fault-free layout: stage j = layers [p0[j], p0[j+1])
   int32_t rcap;                 // reroute cap (<=0: none)
   int32_t assign;               // strategy 1: 1 = least-total-transfer assignment of survivors to new stages
+  int64_t allreduce;            // time of one round of gradient communication (0: not modelled)
+  int32_t p0_max_layers;        // layers of the largest stage of the fault-free layout
+  uint32_t node_exists;         // bit s: some pipeline still has its node of stage s (strategy 0's devices)
   int64_t pf[DEV_MAX_L + 1], pb[DEV_MAX_L + 1], pw[DEV_MAX_L + 1];   // prefix sums: forward, backward, static memory
   int64_t pa[DEV_MAX_L + 1];                                          // prefix sums: activation memory
   // rerouting: stages that lost nodes

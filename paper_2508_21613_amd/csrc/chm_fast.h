@@ -28,6 +28,9 @@ struct FastFamily {
   int32_t mem_coef[DEV_MAX_S];    // see DevFamily::mem_coef
   int32_t has_act;                // 0: no activation table, the peak is the static sum
   int32_t assign;                 // strategy 1: 1 = least-total-transfer assignment of survivors to new stages
+  int32_t allreduce;              // time of one round of gradient communication (0: not modelled)
+  int32_t fixed_layers;           // strategy 1: layers of the largest stage on a node of an untouched pipeline, else 0
+  uint32_t node_exists;           // strategy 0: bit s = some pipeline still has its node of stage s
   FastClass cls[DEV_MAX_CLS];
 };
 

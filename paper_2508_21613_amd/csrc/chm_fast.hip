@@ -189,6 +189,50 @@ __device__ __forceinline__ uint32_t sweep_runs(RowPtr runs, uint32_t n_runs, con
 
 __device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
 
+// 1-based position of the n-th set bit of x (1 <= n <= popcount(x)): which half holds it is decided
+// by a population count, six times
+__device__ __forceinline__ int nth_set_bit(uint64_t x, int n) {
+  const uint32_t lo = (uint32_t)x, hi = (uint32_t)(x >> 32);
+  int c = __popc(lo);
+  bool up = n > c;
+  uint32_t w = up ? hi : lo;
+  int r = up ? n - c : n;
+  int pos = up ? 32 : 0;
+#pragma unroll
+  for (int sh = 16; sh >= 1; sh >>= 1) {
+    const uint32_t part = w & ((1u << sh) - 1u);
+    c = __popc(part);
+    up = r > c;
+    w = up ? (w >> sh) : part;
+    r = up ? r - c : r;
+    pos += up ? sh : 0;
+  }
+  return pos + 1;
+}
+
+// Rounds of gradient communication under redundant computation (see comm_rounds in chm_kernels.hip):
+// the colour set of stage s = the n_s lowest colours not used by stage s-1 (if its node exists) nor,
+// for the last stage, by stage 0 (if the last node exists); sets are 64-bit masks, L <= 64.
+template <int SP>
+__device__ __forceinline__ int ring_rounds(const int (&c)[SP + 1], uint32_t node_exists) {
+  uint64_t prev = 0, first = 0;
+  int rounds = 0;
+#pragma unroll
+  for (int s = 0; s < SP; ++s) {
+    const int n = c[s + 1] - c[s];
+    uint64_t f = 0;
+    if (s >= 1) f |= ((node_exists >> (s - 1)) & 1u) ? prev : 0ull;
+    if (s >= 1 && s == SP - 1) f |= ((node_exists >> s) & 1u) ? first : 0ull;
+    const int p = nth_set_bit(~f, n);
+    const uint64_t low = p >= 64 ? ~0ull : ((1ull << p) - 1ull);
+    const uint64_t cur = ~f & low;
+    rounds = imax32(rounds, p);
+    if (s == 0) first = cur;
+    prev = cur;
+  }
+  return rounds;
+}
+
 template <int CTRL>
 __device__ __forceinline__ uint64_t dpp_min(uint64_t v) {
   const int lo = __builtin_amdgcn_update_dpp((int)(uint32_t)v, (int)(uint32_t)v, CTRL, 0xF, 0xF, false);
@@ -413,6 +457,18 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
             missing = imax32(missing, ff->w_total - have);
           }
         }
+      }
+      if (ff->allreduce > 0) {
+        // rounds of gradient communication: largest stage on any device, or the ring colouring when nodes hold two stages
+        int rounds;
+        if (STRAT == 0) {
+          rounds = ring_rounds<SP>(c, ff->node_exists);
+        } else {
+          rounds = ff->fixed_layers;
+#pragma unroll
+          for (int j = 0; j < SP; ++j) rounds = imax32(rounds, c[j + 1] - c[j]);
+        }
+        t_step += ff->allreduce * rounds;
       }
       if (STRAT == 2 && a.base_out == nullptr) {
         // every reroute vector of every stage that lost nodes
@@ -733,6 +789,10 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     for (int j = 0; j < DEV_MAX_S; ++j) ff.mem_coef[j] = fam.mem_coef[j];
     ff.has_act = h.pa[h.L] > 0 ? 1 : 0;
     ff.assign = h.assign;
+    ff.allreduce = (int32_t)h.allreduce;
+    ff.fixed_layers = (k == 1 && h.n_fixed > 0) ? h.p0_max_layers : 0;
+    ff.node_exists = h.node_exists;
+    if (k == 0 && h.allreduce > 0 && h.L > 64) continue;     // colour masks of the specialised kernel hold 64 colours
     for (int j = 0; j <= h.S; ++j) ff.w0[j] = (int32_t)h.pw[h.p0[j]];
     for (int ci = 0; ci < fam.n_cls && ok; ++ci) {
       const DevClass &c = fam.cls[ci];

@@ -120,7 +120,7 @@ int validate(const chm_scenario_desc *d) {
     return CHM_ERR_ARG;
   if (!d->fwd_us || !d->bwd_us || !d->mem_mib || (d->n_failed > 0 && !d->failed_nodes)) return CHM_ERR_ARG;
   if (d->comm_us < 0 || d->mem_cap_mib < 1 || d->horizon_steps < 1 || d->xfer_us_per_mib < 0) return CHM_ERR_ARG;
-  if (d->transfer_assign < 0 || d->transfer_assign > 1) return CHM_ERR_ARG;
+  if (d->transfer_assign < 0 || d->transfer_assign > 1 || d->allreduce_us < 0) return CHM_ERR_ARG;
   for (int i = 0; i < 3; ++i) if (d->reconf_us[i] < 0) return CHM_ERR_ARG;
   for (int l = 0; l < d->L; ++l)
     if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0 || (d->act_mib && d->act_mib[l] < 0)) return CHM_ERR_ARG;
@@ -145,6 +145,7 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
   for (int i = 0; i < 3; ++i) h.reconf[i] = d->reconf_us[i];
   h.rcap = d->reroute_cap;
   h.assign = d->transfer_assign;
+  h.allreduce = d->allreduce_us;
   for (int l = 0; l < L; ++l) {
     h.pf[l + 1] = h.pf[l] + d->fwd_us[l];
     h.pb[l + 1] = h.pb[l] + d->bwd_us[l];
@@ -181,6 +182,11 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
     ++lost_in_stage[n % S];
   }
 
+  for (int j = 0; j < S; ++j) {
+    h.p0_max_layers = std::max(h.p0_max_layers, h.p0[j + 1] - h.p0[j]);
+    for (int dd = 0; dd < D; ++dd)
+      if (!dead[dd][j]) h.node_exists |= 1u << j;
+  }
   s->survivors.assign(D, std::vector<uint8_t>());
   for (int dd = 0; dd < D; ++dd)
     for (int j = 0; j < S; ++j)
@@ -294,7 +300,7 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
   // ---- bounds.  A pipeline time never exceeds (M + n - 1) x its largest stage time, a stage
   // time never exceeds twice the whole model (redundant computation) times the slowest factor.
   const u128 stage_max = (u128)(h.pf[L] + h.pb[L]) * 2 * ((qmax + 65535) / 65536);
-  const u128 t_max = (u128)(D * M + S - 1) * stage_max + (u128)S * h.comm;
+  const u128 t_max = (u128)(D * M + S - 1) * stage_max + (u128)S * h.comm + (u128)L * h.allreduce;
   const u128 pen_max = (u128)CHM_MAX_FAILED * (CHM_MAX_FAILED * M) * stage_max;
   const u128 reconf_max = (u128)std::max(std::max(h.reconf[0], h.reconf[1]), h.reconf[2]) + (u128)h.xfer * h.pw[L];
   const u128 cost_max = (u128)h.K * (t_max + pen_max) + reconf_max;

@@ -117,6 +117,49 @@ __device__ __forceinline__ int64_t best_overlap(const DevScenario *scn, const De
   return best;
 }
 
+// Rounds of gradient communication of a plan (Restorer, "Asymmetric Communication"): colours the
+// greedy colouring in layer order gives the graph that joins layers held by one device.
+// Re-partition and rerouting: every device holds one contiguous stage (of the plan's split or of the
+// fault-free layout); the layers before l that share a device with l then form one contiguous run
+// inside a single stage, all with distinct colours, so l gets a colour below that stage's size and
+// the count is the size of the largest stage on any device.
+// Redundant computation: a node holds its stage and its ring successor's.  Stage s meets, among the
+// stages coloured before it, stage s-1 (through node s-1) and, for the last stage, stage 0 (through
+// the last node); its layers take the lowest colours those stages do not use, in order.  Colour sets
+// are bit masks (L <= 128 colours).
+template <int SMAX>
+__device__ __forceinline__ int comm_rounds(const DevScenario *scn, const DevFamily &fam, Cuts<SMAX> cuts) {
+  const int SP = fam.stages;
+  int rounds = 0;
+  if (fam.strategy != 0) {
+    for (int j = 0; j < SP; ++j) {
+      const int n = cuts.get(j + 1) - cuts.get(j);
+      rounds = n > rounds ? n : rounds;
+    }
+    if (fam.strategy == 1 && scn->n_fixed > 0) rounds = scn->p0_max_layers > rounds ? scn->p0_max_layers : rounds;
+    return rounds;
+  }
+  uint64_t prev_lo = 0, prev_hi = 0, first_lo = 0, first_hi = 0;
+  for (int s = 0; s < SP; ++s) {
+    const int n = cuts.get(s + 1) - cuts.get(s);
+    uint64_t f_lo = 0, f_hi = 0;
+    if (s >= 1 && ((scn->node_exists >> (s - 1)) & 1u)) { f_lo |= prev_lo; f_hi |= prev_hi; }
+    if (s >= 1 && s == SP - 1 && ((scn->node_exists >> s) & 1u)) { f_lo |= first_lo; f_hi |= first_hi; }
+    uint64_t c_lo = 0, c_hi = 0;
+    int taken = 0;
+    for (int bit = 0; bit < 128 && taken < n; ++bit) {
+      const bool used = bit < 64 ? ((f_lo >> bit) & 1ull) : ((f_hi >> (bit - 64)) & 1ull);
+      if (used) continue;
+      if (bit < 64) c_lo |= 1ull << bit; else c_hi |= 1ull << (bit - 64);
+      ++taken;
+      rounds = bit + 1 > rounds ? bit + 1 : rounds;
+    }
+    if (s == 0) { first_lo = c_lo; first_hi = c_hi; }
+    prev_lo = c_lo; prev_hi = c_hi;
+  }
+  return rounds;
+}
+
 // Everything of a plan's cost except the rerouting penalty.  Returns false when the plan
 // does not fit in memory.
 template <int SMAX>
@@ -177,6 +220,7 @@ __device__ __forceinline__ bool eval_base(const DevScenario *scn, const DevFamil
     t_step = imax(t_step, T);
     missing = imax(missing, miss);
   }
+  if (scn->allreduce > 0) t_step += scn->allreduce * (int64_t)comm_rounds<SMAX>(scn, fam, cuts);
   *t_step_out = t_step;
   *reconf_out = scn->reconf[fam.strategy] + scn->xfer * missing;
   return true;

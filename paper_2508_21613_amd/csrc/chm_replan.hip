@@ -23,6 +23,7 @@ struct AssignArgs {
   const int64_t *pw;                           // [L+1] device: prefix sums of per-layer memory
   int64_t *total;                              // device: least total MiB
   int32_t *position_of_node;                   // [n] device: one optimal assignment
+  int32_t *rounds;                             // device: layers of the largest position = rounds of gradient communication
 };
 
 // Minimum-cost one-to-one assignment (Kuhn-Munkres with potentials), one wavefront.  Rows (nodes)
@@ -102,14 +103,22 @@ __global__ void __launch_bounds__(64) k_min_assignment(AssignArgs a) {
     part += pw[p_hi[c]] - pw[p_lo[c]] - (hi > lo ? pw[hi] - pw[lo] : 0);
     a.position_of_node[i] = c;
   }
-  for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, 64);
-  if (lane == 0) *a.total = part;
+  // every position holds one contiguous range of layers, so the greedy colouring of the layer graph
+  // (Restorer, "Asymmetric Communication") needs exactly as many rounds as the largest position has layers
+  int most = 0;
+  for (int c = lane; c < n; c += 64) most = p_hi[c] - p_lo[c] > most ? p_hi[c] - p_lo[c] : most;
+  for (int off = 32; off > 0; off >>= 1) {
+    part += __shfl_xor(part, off, 64);
+    const int other = __shfl_xor(most, off, 64);
+    most = other > most ? other : most;
+  }
+  if (lane == 0) { *a.total = part; *a.rounds = most; }
 }
 
 struct Scratch {
   int32_t *d_held = nullptr, *d_pos = nullptr, *d_assign = nullptr;
-  int64_t *d_pw = nullptr, *d_total = nullptr;
-  int64_t *h_total = nullptr;                  // pinned
+  int64_t *d_pw = nullptr, *d_total = nullptr; // d_total: [0] least total MiB, [1] rounds (int32 in its low half)
+  int64_t *h_total = nullptr;                  // pinned, two words
   ~Scratch() {
     if (d_held) (void)hipFree(d_held);
     if (d_pos) (void)hipFree(d_pos);
@@ -136,7 +145,7 @@ int check(const chm_replan_desc *d) {
   if (d->dp_min < 1 || d->dp_max < d->dp_min || d->dp_max > CHM_MAX_DP) return CHM_ERR_ARG;
   if (d->pp_min < 1 || d->pp_max < d->pp_min || d->pp_max > CHM_MAX_PP) return CHM_ERR_ARG;
   if (d->micro_batches < 1 || d->comm_us < 0 || d->mem_cap_mib < 1 || d->horizon_us < 1 || d->restart_us < 0 ||
-      d->xfer_us_per_mib < 0)
+      d->xfer_us_per_mib < 0 || d->allreduce_us < 0)
     return CHM_ERR_ARG;
   for (int l = 0; l < d->L; ++l)
     if (d->fwd_us[l] < 1 || d->bwd_us[l] < 1 || d->mem_mib[l] < 0 || (d->act_mib && d->act_mib[l] < 0)) return CHM_ERR_ARG;
@@ -178,8 +187,8 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
     ok = ok && hipMalloc((void **)&sc.d_pos, held.size() * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc((void **)&sc.d_assign, (size_t)N * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc((void **)&sc.d_pw, pw.size() * sizeof(int64_t)) == hipSuccess;
-    ok = ok && hipMalloc((void **)&sc.d_total, sizeof(int64_t)) == hipSuccess;
-    ok = ok && hipHostMalloc((void **)&sc.h_total, sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipMalloc((void **)&sc.d_total, 2 * sizeof(int64_t)) == hipSuccess;
+    ok = ok && hipHostMalloc((void **)&sc.h_total, 2 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
     ok = ok && hipMemcpyAsync(sc.d_held, held.data(), held.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) == hipSuccess;
     ok = ok && hipMemcpyAsync(sc.d_pw, pw.data(), pw.size() * sizeof(int64_t), hipMemcpyHostToDevice, st) == hipSuccess;
     ok = ok && hipStreamSynchronize(st) == hipSuccess;
@@ -256,15 +265,22 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
     if (hipMemcpyAsync(sc.d_pos, pos.data(), pos.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) != hipSuccess) return CHM_ERR_HIP;
     AssignArgs a;
     a.n = N; a.L = L; a.held = sc.d_held; a.pos = sc.d_pos; a.pw = sc.d_pw; a.total = sc.d_total; a.position_of_node = sc.d_assign;
+    a.rounds = (int32_t *)(sc.d_total + 1);
     if (hipEventRecord(ev.a, st) != hipSuccess) return CHM_ERR_HIP;
     hipLaunchKernelGGL(k_min_assignment, dim3(1), dim3(64), 0, st, a);
     if (hipGetLastError() != hipSuccess || hipEventRecord(ev.b, st) != hipSuccess) return CHM_ERR_HIP;
-    if (hipMemcpyAsync(sc.h_total, sc.d_total, sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess) return CHM_ERR_HIP;
+    if (hipMemcpyAsync(sc.h_total, sc.d_total, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, st) != hipSuccess) return CHM_ERR_HIP;
     if (hipStreamSynchronize(st) != hipSuccess) return CHM_ERR_HIP;     // also keeps `pos` alive until the copy is done
     float ms = 0;
     if (hipEventElapsedTime(&ms, ev.a, ev.b) != hipSuccess) return CHM_ERR_HIP;
     assign_ms += ms;
-    cand.fetch_mib = *sc.h_total;
+    cand.fetch_mib = sc.h_total[0];
+    if (d->allreduce_us > 0) {
+      int32_t rounds;
+      memcpy(&rounds, &sc.h_total[1], sizeof(rounds));
+      cand.comm_rounds = rounds;
+      cand.t_step_us += (int64_t)d->allreduce_us * rounds;
+    }
     cand.t_trans_us = (int64_t)d->restart_us + (int64_t)d->xfer_us_per_mib * cand.fetch_mib;
     // (H - t_trans) / t_step, larger is better; exact comparison by cross-multiplication
     const __int128 gain = (__int128)d->horizon_us - cand.t_trans_us;

@@ -66,13 +66,15 @@ SMALL.append(dict(_two_lost_in_one_pipeline(), failed_nodes=[0, 3, 8], M=3))
 SMALL_ACT = [synth.with_activations(sc, 3000 + i) for i, sc in enumerate(SMALL)]
 # least-transfer assignment of survivors to new stages, alternately without and with activation memory
 SMALL_KM = [dict(SMALL_ACT[i] if i % 2 else sc, transfer_assign=1) for i, sc in enumerate(SMALL)]
-ALL_SMALL = SMALL + SMALL_ACT + SMALL_KM
+# rounds of gradient communication in the step time, on top of the three variants above in turn
+SMALL_AR = [dict((SMALL, SMALL_ACT, SMALL_KM)[i % 3][i], allreduce_us=250 + 35 * i) for i in range(len(SMALL))]
+ALL_SMALL = SMALL + SMALL_ACT + SMALL_KM + SMALL_AR
 
 
 @pytest.mark.parametrize("i", range(len(ALL_SMALL)))
 def test_small_scenarios_every_cost_and_argmin(B, i):
     sc = ALL_SMALL[i]
-    print("small scenario", i, {k: sc.get(k) for k in ("L", "PP", "DP", "M", "failed_nodes", "reroute_cap", "transfer_assign")}, flush=True)
+    print("small scenario", i, {k: sc.get(k) for k in ("L", "PP", "DP", "M", "failed_nodes", "reroute_cap", "transfer_assign", "allreduce_us")}, flush=True)
     o = O.Scenario(sc)
     g = B.Scenario(sc)
     assert g.families == o.families and g.n_plans == o.n_plans
@@ -118,12 +120,16 @@ def windows(o, rng, n_windows, width):
 
 
 @pytest.mark.parametrize("name", ["config2", "config3", "config5_single", "config5_double", "config2_act", "config3_act",
-                                  "config2_assign", "config3_assign", "config5_double_assign"])
+                                  "config2_assign", "config3_assign", "config5_double_assign",
+                                  "config2_allreduce", "config3_allreduce", "config5_double_allreduce"])
 def test_seeded_windows_of_the_large_configs(B, name):
     sc = {"config2": synth.config2, "config3": synth.config3,
           "config2_assign": lambda: dict(synth.config2(), transfer_assign=1),
           "config3_assign": lambda: dict(synth.with_activations(synth.config3(), 79), transfer_assign=1),
           "config5_double_assign": lambda: dict(synth.config5([3, 30]), transfer_assign=1),
+          "config2_allreduce": lambda: dict(synth.config2(), allreduce_us=1500),
+          "config3_allreduce": lambda: dict(synth.with_activations(synth.config3(), 80), allreduce_us=900, transfer_assign=1),
+          "config5_double_allreduce": lambda: dict(synth.config5([6, 7]), allreduce_us=2500),
 
           "config2_act": lambda: synth.with_activations(synth.config2(), 77),
           "config3_act": lambda: synth.with_activations(synth.config3(), 78),
@@ -153,10 +159,11 @@ def test_seeded_windows_of_the_large_configs(B, name):
             assert rc_g == rc_o and same_plan(best_g, best_o), (f, first, best_g, best_o)
 
 
-@pytest.mark.parametrize("cap,assign", [(6000, 0), (synth.CONFIG4_CAP_30PCT, 0), (synth.CONFIG4_CAP_30PCT, 1)])
-def test_config4_explicit_partitions(B, cap, assign):
+@pytest.mark.parametrize("cap,assign,allreduce", [(6000, 0, 0), (synth.CONFIG4_CAP_30PCT, 0, 0), (synth.CONFIG4_CAP_30PCT, 1, 0),
+                                                  (synth.CONFIG4_CAP_30PCT, 0, 1200)])
+def test_config4_explicit_partitions(B, cap, assign, allreduce):
     import torch
-    sc = dict(synth.config4(mem_cap_mib=cap), transfer_assign=assign)
+    sc = dict(synth.config4(mem_cap_mib=cap), transfer_assign=assign, allreduce_us=allreduce)
     o, g = O.Scenario(sc), B.Scenario(sc)
     assert g.families == o.families
     n = 3000
@@ -177,12 +184,12 @@ def test_config4_explicit_partitions(B, cap, assign):
     assert got[1] == B.INFEASIBLE and got[0] == o.score_ranks(1, [0])[0]
 
 
-@pytest.mark.parametrize("assign", [0, 1])
-def test_full_size_search_config2(B, assign):
+@pytest.mark.parametrize("assign,allreduce", [(0, 0), (1, 0), (0, 1500)])
+def test_full_size_search_config2(B, assign, allreduce):
     """the 32-card shape, whole space, in the launch configuration the benchmark times:
     the winner is re-scored plan by plan by the oracle, is compared with the oracle's argmin
     over the windows around it, and must not be beaten by any plan of a seeded sample."""
-    sc = dict(synth.config2(), transfer_assign=assign)
+    sc = dict(synth.config2(), transfer_assign=assign, allreduce_us=allreduce)
     o, g = O.Scenario(sc), B.Scenario(sc)
     rc, best = g.search_best(7)
     assert rc == 0
@@ -281,6 +288,8 @@ def test_replan_over_dp_pp_degrees(B, i):
     assert got == want, (got, want)
     for H in (3 * 10 ** 7, 10 ** 11):
         assert B.replan(dict(rp, horizon_us=H)) == O.replan(dict(rp, horizon_us=H))
+    ar = dict(rp, allreduce_us=1500 + 300 * i)
+    assert B.replan(ar) == O.replan(ar)
 
 
 def test_replan_argument_checks(B):
