@@ -54,62 +54,76 @@ __device__ __forceinline__ int scale32(int x, uint32_t q) {
   return (int)(((uint64_t)(uint32_t)x * q + 32768u) >> 16);
 }
 
-// 1F1B pipeline time of N stages, M micro-batches; F, B per stage.  Round t: forward t on
-// all stages in stage order, then backward t-(N-1-s) on stage s.
+// 1F1B pipeline time of N stages, M micro-batches; F, B per stage.  Round t: forward t on all
+// stages in stage order, then backward t-(N-1-s) on stage s (see chm_kernels.hip).  The clocks are
+// kept relative to the forward chain: e[s] = (time stage s is free) - (F[0] + ... + F[s-1]).  In
+// that frame the forward of stage s ends at x[s] = max(e[s], x[s-1]) with no add at all, and the
+// backward that stage s-1 runs right after its own forward takes the max of the same two values,
+// so it leaves e[s-1] = x[s] + (F[s-1] + B[s-1]).  A round of N forwards and N backwards is N-1
+// v_max_i32 and N v_add_u32.  The cool-down rounds (backwards only) run on plain clocks again.
 template <int N>
 __device__ __forceinline__ int makespan32(const int (&F)[N], const int (&B)[N], int M) {
-  int E[N];
-#pragma unroll
-  for (int s = 0; s < N; ++s) E[s] = 0;
+  if (N == 1) return M * (F[0] + B[0]);
   if (M >= N - 1) {
-    // warm-up rounds 0..N-2: every stage runs a forward, stages >= N-1-t also a backward
+    // e[s] = (time stage s is free) - (forward time of stages 0..s-1); C = forward + backward of a stage
+    int e[N], C[N];
 #pragma unroll
-    for (int t = 0; t < N - 1; ++t) {
-      int x = 0;
+    for (int s = 0; s < N; ++s) C[s] = F[s] + B[s];
+    // round 0: forward 0 runs down the empty pipeline, the last stage follows it with backward 0
 #pragma unroll
-      for (int s = 0; s < N; ++s) {
-        const int old = E[s];
-        E[s] = (s == 0 ? E[s] : imax32(E[s], x)) + F[s];
-        x = E[s];
-        if (s == N - 1) E[s] += B[s];
-        if (s >= 1 && s - 1 >= N - 1 - t) E[s - 1] = imax32(E[s - 1], old) + B[s - 1];
+    for (int s = 0; s < N; ++s) e[s] = s == N - 1 ? C[s] : F[s];
+    // warm-up rounds 1..N-2: every stage runs a forward, stages >= N-1-t also a backward
+#pragma unroll
+    for (int t = 1; t < N - 1; ++t) {
+      int x = e[0];
+#pragma unroll
+      for (int s = 1; s < N; ++s) {
+        const int xs = imax32(e[s], x);
+        e[s - 1] = (s - 1 >= N - 1 - t) ? xs + C[s - 1] : x + F[s - 1];
+        x = xs;
       }
+      e[N - 1] = x + C[N - 1];
     }
-    // steady rounds N-1..M-1: one forward and one backward on every stage
-    for (int t = N - 1; t < M; ++t) {
-      int x = 0;
+    // steady rounds: one forward and one backward on every stage
+    for (int t = (N - 1 > 1 ? N - 1 : 1); t < M; ++t) {
+      int x = e[0];
 #pragma unroll
-      for (int s = 0; s < N; ++s) {
-        const int old = E[s];
-        E[s] = (s == 0 ? E[s] : imax32(E[s], x)) + F[s];
-        x = E[s];
-        if (s == N - 1) E[s] += B[s];
-        if (s >= 1) E[s - 1] = imax32(E[s - 1], old) + B[s - 1];
+      for (int s = 1; s < N; ++s) {
+        x = imax32(e[s], x);
+        e[s - 1] = x + C[s - 1];
       }
+      e[N - 1] = x + C[N - 1];
     }
-    // cool-down rounds: backwards only, stage s while s <= N-2-u
+    // back to plain clocks, then the cool-down rounds: backwards only, stage s while s <= N-2-u
+    int E[N];
+    int pf = 0;
+#pragma unroll
+    for (int s = 0; s < N; ++s) { E[s] = e[s] + pf; pf += F[s]; }
 #pragma unroll
     for (int u = 0; u < N - 1; ++u) {
 #pragma unroll
       for (int s = 0; s < N - 1 - u; ++s) E[s] = imax32(E[s], E[s + 1]) + B[s];
     }
-  } else {
-    // fewer micro-batches than warm-up slots: same rounds with (uniform) predicates
-    for (int t = 0; t < M + N - 1; ++t) {
-      const bool fwd = t < M;
-      int x = 0;
+    return E[0];
+  }
+  int E[N];
 #pragma unroll
-      for (int s = 0; s < N; ++s) {
-        const int old = E[s];
-        if (fwd) {
-          E[s] = imax32(E[s], x) + F[s];
-          x = E[s];
-          if (s == N - 1) E[s] += B[s];
-        }
-        if (s >= 1) {
-          const int j = t - N + s;
-          if (j >= 0 && j < M) E[s - 1] = imax32(E[s - 1], old) + B[s - 1];
-        }
+  for (int s = 0; s < N; ++s) E[s] = 0;
+  // fewer micro-batches than warm-up slots: plain clocks, rounds with (uniform) predicates
+  for (int t = 0; t < M + N - 1; ++t) {
+    const bool fwd = t < M;
+    int x = 0;
+#pragma unroll
+    for (int s = 0; s < N; ++s) {
+      const int old = E[s];
+      if (fwd) {
+        E[s] = imax32(E[s], x) + F[s];
+        x = E[s];
+        if (s == N - 1) E[s] += B[s];
+      }
+      if (s >= 1) {
+        const int j = t - N + s;
+        if (j >= 0 && j < M) E[s - 1] = imax32(E[s - 1], old) + B[s - 1];
       }
     }
   }
