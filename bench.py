@@ -22,6 +22,11 @@ if ROOT not in sys.path:
 # v_mul_u32_u24, which the path needs, issue at half of it (chm_valu_probe measures both).
 ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
+# HBM bytes per launch of the config-2 search kernels, per strategy, from the rocprofv3 --pmc runs summarised in
+# profiles/search_kernels_config2.md: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (KiB; the factors come from the
+# 1 GiB calibration copy of the same runs).  Counters cannot be read from inside this process.
+CONFIG2_TRAFFIC_BYTES = {0: (138.1 * 2.0 + 1090.0) * 1024, 1: (105.5 * 2.0 + 319.7) * 1024, 2: (135.2 * 2.0 + 1185.0) * 1024}
+
 
 def algorithmic_ops(fam, feasible):
     """Integer operations the method needs for one search launch of a strategy (not what the kernel
@@ -41,12 +46,24 @@ def algorithmic_ops(fam, feasible):
     return fam["n_part"] * light + feasible * heavy, light, heavy
 
 
+def copy_calibration():
+    """one plain 1 GiB device copy: the known-size reference for scaling FETCH_SIZE / WRITE_SIZE"""
+    import torch
+    src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    torch.cuda.synchronize()
+    del src, dst
+
+
 def bench_replan(args, note, B, synth):
     """A step = one chm_replan over the 31 surviving nodes of the 32-card shape: every contiguous split of the
     48 layers for every pipeline length the DP range 2..6 produces within 4..12 stages, the least-transfer
     assignment of the 31 nodes per candidate, and the exact ratio objective."""
     import torch
     rp = synth.replan32()
+    if args.copy_calibration:
+        copy_calibration()
     stream = torch.cuda.Stream()
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
@@ -96,7 +113,7 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--ttb-runs", type=int, default=10)
     ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config5", "replan32"],
                     help="config2 (the 32-card shape) is the benchmark; the others are for profiling; replan32 times "
@@ -157,11 +174,7 @@ def main():
     work = [family_work(g) for g in handles]
 
     if args.copy_calibration:
-        src = torch.zeros(1 << 28, dtype=torch.int32, device="cuda")
-        dst = torch.empty_like(src)
-        dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        copy_calibration()
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
             for g in handles:
@@ -239,10 +252,11 @@ def main():
         "kernel_ms_per_strategy": [float(x) for x in fam_ms],
         "best": {"index": best["index"], "cost": best["cost"], "strategy": best["strategy"], "cuts": best["cuts"]},
         "roofline": {"bound": "alu", "kernel": "search, strategy %d" % dom, "achieved": achieved,
-                     "peak": ALU_PEAK_TOPS, "unit": "TOP/s (int32 lane operations)", "frac": achieved / ALU_PEAK_TOPS,
+                     "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS,
                      "measured_valu_rates_tops": probes,
                      "frac_of_measured_cell_rate": achieved / probes["max_add_cell_chain"],
-                     "traffic": None, "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": float(ops[dom]),
+                     "traffic": CONFIG2_TRAFFIC_BYTES[dom] if args.workload == "config2" and not args.transfer_assign else None,
+                     "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": float(ops[dom]),
                      "feasible_partitions": float(feasible[dom]),
                      "algorithmic_ops_per_feasible_partition": ops_light + ops_heavy,
                      "algorithmic_ops_per_infeasible_partition": ops_light},
