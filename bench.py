@@ -121,6 +121,9 @@ def main():
     ap.add_argument("--transfer-assign", type=int, default=0, choices=[0, 1],
                     help="1: the re-partition strategy counts the weights to fetch under the least-transfer "
                          "assignment of survivors to new stages (default 0: survivors in stage order)")
+    ap.add_argument("--plan-cache", default=None,
+                    help="write the best plan of every scenario of the workload to this file, one JSON object per "
+                         "line (the cache of pre-computed plans the Planner keeps for possible failures)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -186,15 +189,24 @@ def main():
         stream.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
+        plans = [None] * len(handles)
         for _ in range(args.steps):
-            for g in handles:
+            for i, g in enumerate(handles):
                 rc, best = g.search_best(7, stream=stream)
+                plans[i] = (rc, best)
                 fam_ms += np.array(g.get_timing()["family_ms"])
         stream.synchronize()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     fam_ms /= args.steps
+    if args.plan_cache:
+        with open(args.plan_cache, "w") as fh:
+            for sc_i, (rc_i, best_i) in zip(scenarios, plans):
+                fh.write(json.dumps({"failed_nodes": sc_i["failed_nodes"], "rc": rc_i, "index": best_i["index"], "cost": best_i["cost"],
+                                     "strategy": best_i["strategy"], "cuts": best_i["cuts"],
+                                     "reroute": best_i["reroute"] if best_i["strategy"] == 2 else None}) + "\n")
+        note("best plan of %d scenario(s) written to %s" % (len(plans), args.plan_cache))
     note("timed %d steps: %.3f ms per step, kernel ms per strategy %s" % (args.steps, ms_per_step, fam_ms))
 
     # work done per step, from the library's own counters of the last search on every handle

@@ -73,8 +73,12 @@ struct SearchLaunch {
   uint64_t part_first;          // first partition rank of this chunk
   uint32_t part_count;          // partitions in this chunk (< 2^idx_bits)
   int32_t idx_bits;             // low bits of the packed key hold the chunk-local partition index
-  uint64_t *result;             // device word, atomicMin target: (cost << idx_bits) | local index
-  uint64_t *feasible;           // device counter: partitions that passed the memory filter (atomicAdd)
+  // Atomics of many workgroups on one address serialise in the memory system (about 10 ns each), so both
+  // targets are spread over slot_mask + 1 words, slot_stride words apart (separate cache lines): workgroup b
+  // uses word (b & slot_mask) * slot_stride.  The host takes the minimum / the sum over the words.
+  uint64_t *result;             // device words, atomicMin target: (cost << idx_bits) | local index
+  uint64_t *feasible;           // device counters: partitions that passed the memory filter (atomicAdd)
+  uint32_t slot_mask, slot_stride;
   // list mode: partition i of the chunk is ranks[i] (any order, a rank outside the family counts as
   // infeasible) instead of part_first + i; part_first is then ignored
   const uint64_t *ranks;

@@ -264,6 +264,36 @@ __device__ __forceinline__ uint64_t wave_min(uint64_t v) {
   return v;
 }
 
+// Combinadic digits of `rem` (a partition rank): for i = K..1 the largest x with C(x, i) <= rem.
+// C(., i) grows with x, so each digit is found by a four-way search over [i-1, previous digit - 1]:
+// three independent table probes per step, the range shrinks to a quarter; all lanes take the same
+// number of steps (no divergence), `steps` = 3 for up to 64 candidates, 4 for up to 256.
+template <int K>
+__device__ __forceinline__ void unrank_digits(uint64_t rem, int L, int steps, const uint64_t *table, int (&c)[K + 2]) {
+  // table[(i-1) * DEV_MAX_L + x] = C(x, i)
+  auto column = [table](int i, int x) { return table[(i - 1) * DEV_MAX_L + x]; };
+  int hi = L - 2;
+#pragma unroll
+  for (int i = K; i >= 1; --i) {
+    int lo = i - 1;                                  // C(i-1, i) = 0 <= rem always
+    for (int s = 0; s < steps; ++s) {
+      const int q = (hi - lo + 4) >> 2;              // ceil((range size) / 4), 0 only when hi < lo
+      const int m1 = lo + q, m2 = m1 + q, m3 = m2 + q;
+      const bool a1 = m1 <= hi && column(i, m1 <= hi ? m1 : hi) <= rem;
+      const bool a2 = m2 <= hi && column(i, m2 <= hi ? m2 : hi) <= rem;
+      const bool a3 = m3 <= hi && column(i, m3 <= hi ? m3 : hi) <= rem;
+      // the answer lies in [lo, m1-1], [m1, m2-1], [m2, m3-1] or [m3, hi]
+      const int nlo = a3 ? m3 : (a2 ? m2 : (a1 ? m1 : lo));
+      const int nhi = a3 ? hi : (a2 ? m3 - 1 : (a1 ? m2 - 1 : m1 - 1));
+      lo = nlo;
+      hi = nhi < hi ? nhi : hi;
+    }
+    c[i] = lo + 1;
+    rem -= column(i, lo);
+    hi = lo - 1;
+  }
+}
+
 struct FastLaunch {
   SearchLaunch s;
   const FastTables *tab;
@@ -276,12 +306,16 @@ struct FastLaunch {
   uint32_t *weights_out;
 };
 
+// Waves per SIMD the register allocator is asked to keep possible: up to 8 stages the kernels fit 96
+// vector registers (5 waves); deeper pipelines hold more live stage sums and clocks and get what they need.
 template <int SP, int STRAT>
-__global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
+__global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SP <= 8 ? 5 : 1)))
+k_fast_search(FastLaunch a) {
   constexpr int K = SP - 1;
   __shared__ int4 T[DEV_MAX_L + 1];            // prefix sums: forward, backward, static memory, activation memory
   __shared__ uint64_t BN[(K > 0 ? K : 1) * DEV_MAX_L];   // BN[(i-1)*128 + x] = C(x, i), i = 1..K
   __shared__ uint64_t wave_keys[BLOCK / 64];
+  __shared__ uint32_t wave_fit[BLOCK / 64];
   extern __shared__ int64_t cost_tile[];       // BLOCK * per_lane costs when a cost store with per_lane > 1 is asked for
   const ScnPtr scn = as_const(a.s.scn);
   const TabPtr tab = as_const(a.tab);
@@ -308,26 +342,8 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
       listed_ok = rem < scn->fam[STRAT].n_part;
       if (!listed_ok) rem = 0;
     }
-    // combinadic digits from the LDS copy of the binomial table; four candidates are probed at a
-    // time (independent LDS reads) so that the scan is not one dependent load per step
-    int x = L - 2;
-#pragma unroll
-    for (int i = K; i >= 1; --i) {
-      const uint64_t *col = BN + (i - 1) * DEV_MAX_L;
-      for (;;) {
-        int over = 0;
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          const int xi = x - j;
-          over += (xi >= 0 && col[xi >= 0 ? xi : 0] > rem) ? 1 : 0;   // C(.,i) grows with x: the first `over` probes exceed rem
-        }
-        x -= over;
-        if (over < 4) break;
-      }
-      c[i] = x + 1;
-      rem -= col[x];
-      --x;
-    }
+    // combinadic digits from the LDS copy of the binomial table
+    unrank_digits<K>(rem, L, (L - 1) <= 64 ? 3 : 4, BN, c);
   }
 
   const int cap = (int)scn->cap;
@@ -572,14 +588,17 @@ __global__ void __launch_bounds__(BLOCK) k_fast_search(FastLaunch a) {
   if (STRAT == 2 && a.base_out != nullptr) key = CHM_KEY_NONE;   // the combine kernel takes the argmin
   key = wave_min(key);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (lane == 0 && n_fit) atomicAdd((unsigned long long *)a.s.feasible, (unsigned long long)n_fit);
-  if (lane == 0) wave_keys[wave] = key;
+  if (lane == 0) { wave_keys[wave] = key; wave_fit[wave] = n_fit; }
   __syncthreads();
   if (threadIdx.x == 0) {
+    // one atomic of each kind per workgroup, spread over several words (see SearchLaunch)
+    const uint32_t slot = (blockIdx.x & a.s.slot_mask) * a.s.slot_stride;
     uint64_t k = wave_keys[0];
+    uint32_t fit = wave_fit[0];
 #pragma unroll
-    for (int i = 1; i < BLOCK / 64; ++i) k = umin64(k, wave_keys[i]);
-    if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)a.s.result, (unsigned long long)k);
+    for (int i = 1; i < BLOCK / 64; ++i) { k = umin64(k, wave_keys[i]); fit += wave_fit[i]; }
+    if (fit) atomicAdd((unsigned long long *)a.s.feasible + slot, (unsigned long long)fit);
+    if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)a.s.result + slot, (unsigned long long)k);
   }
 }
 
@@ -945,9 +964,12 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   fl.runs = f->d_runs;
   fl.base_out = base_out;
   fl.weights_out = weights_out;
-  // enough lanes to fill 256 CUs with several waves per SIMD, runs long enough to amortise unranking
-  const uint64_t lanes_wanted = 256ull * 4 * 8 * 64;
-  uint64_t per = a.part_count / lanes_wanted;
+  // Run length per lane.  Large spaces: about 30 workgroups per compute unit (six rounds of the five that are
+  // resident), which evens out the tail, with runs of at most 32 partitions.  Smaller spaces: runs of 4 as long
+  // as that still gives every resident wave slot (256 CUs x 5 workgroups x 256 lanes) a lane, then shorter.
+  const uint64_t lanes_balanced = 256ull * 30 * BLOCK, lanes_resident = 256ull * 5 * BLOCK;
+  uint64_t per = a.part_count / lanes_balanced;
+  if (per < 4) per = std::min<uint64_t>(4, a.part_count / lanes_resident);
   per = std::max<uint64_t>(1, std::min<uint64_t>(per, 32));
   if (a.ranks != nullptr) per = 1;                               // a list has no successor to walk to
   else if (a.costs_out != nullptr) per = std::min<uint64_t>(per, 8);   // bounds the LDS tile of the cost store

@@ -59,7 +59,10 @@ struct chm_scenario {
 
 namespace {
 
-enum { MAX_SLOTS = 1 << 16 };
+// Argmin words and feasibility counters of one search call live in one device buffer of SLOT_WORDS words.
+// Each launched chunk and each of the three counters owns SLOT_WAYS words, SLOT_STRIDE words apart, when the
+// call has few enough chunks for that; otherwise one word each.
+enum { MAX_SLOTS = 1 << 16, SLOT_WORDS = (1 << 16) + 64, SLOT_WAYS = 16, SLOT_STRIDE = 16 };
 
 const chm_family *find_family(const chm_scenario *s, int strategy) {
   for (int i = 0; i < s->space.n_families; ++i)
@@ -403,23 +406,28 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
     return CHM_ERR_NO_FEASIBLE;
   }
   if (slots.size() > MAX_SLOTS) return CHM_ERR_OVERFLOW;
-  if (chmk_fill_u64(s->d_slots, (uint32_t)slots.size(), CHM_KEY_NONE, st)) return CHM_ERR_HIP;
-  uint64_t *d_count = s->d_slots + slots.size();          // three feasibility counters right behind the slots
-  if (chmk_fill_u64(d_count, 3, 0, st)) return CHM_ERR_HIP;
+  const bool spread = (slots.size() + 3) * SLOT_WAYS * SLOT_STRIDE <= SLOT_WORDS;
+  const uint32_t ways = spread ? SLOT_WAYS : 1, stride = spread ? SLOT_STRIDE : 1;
+  const uint32_t chunk_words = ways * stride;              // words one chunk (or one counter) owns
+  const uint32_t key_words = (uint32_t)slots.size() * chunk_words;
+  if (chmk_fill_u64(s->d_slots, key_words, CHM_KEY_NONE, st)) return CHM_ERR_HIP;
+  uint64_t *d_count = s->d_slots + key_words;              // three feasibility counters right behind the argmin words
+  if (chmk_fill_u64(d_count, 3 * chunk_words, 0, st)) return CHM_ERR_HIP;
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;
   int ev_i = 1;
   int ev_of[3] = {-1, -1, -1};
   for (const Job &j : jobs) {
-    const DevFamily &fam = s->h.fam[j.strategy];
     for (uint64_t done = 0; done < j.count; done += chunk, ++si) {
       SearchLaunch a;
       a.scn = s->d_scn; a.comp = s->d_comp; a.strategy = j.strategy;
       a.part_first = j.first + done;
       a.part_count = (uint32_t)std::min<uint64_t>(chunk, j.count - done);
       a.idx_bits = s->idx_bits;
-      a.result = s->d_slots + si;
-      a.feasible = d_count + j.strategy;
+      a.result = s->d_slots + si * chunk_words;
+      a.feasible = d_count + (size_t)j.strategy * chunk_words;
+      a.slot_mask = ways - 1;
+      a.slot_stride = stride;
       a.ranks = j.ranks ? j.ranks + done : nullptr;
       a.costs_out = j.costs ? j.costs + done : nullptr;
       int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
@@ -430,13 +438,13 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
     uint64_t per_part = 1;
     if (j.strategy == 2 && s->h.n_aff) { per_part = 0; for (int a = 0; a < s->h.n_aff; ++a) per_part += s->h.aff_R[a]; }
     s->last.evaluations[j.strategy] += j.count * per_part;
-    (void)fam;
     if (s->timing && ev_i < 7) { HIP_TRY(hipEventRecord(s->ev[ev_i], st)); ev_of[j.strategy] = ev_i; ++ev_i; }
   }
   if (!out) return CHM_OK;
-  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (slots.size() + 3) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (size_t)(key_words + 3 * chunk_words) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
-  for (int k = 0; k < 3; ++k) s->last.feasible[k] = s->h_pinned[slots.size() + k];
+  for (int k = 0; k < 3; ++k)
+    for (uint32_t w = 0; w < ways; ++w) s->last.feasible[k] += s->h_pinned[key_words + (size_t)k * chunk_words + (size_t)w * stride];
   if (s->timing) {
     int prev = 0;
     for (int k = 0; k < 3; ++k) {
@@ -454,12 +462,12 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
   int best_strategy = -1;
   uint64_t best_part = 0;
   const uint64_t *best_list = nullptr;
-  size_t slot_i = 0;
   std::vector<const uint64_t *> slot_list;
   for (const Job &j : jobs)
     for (uint64_t done = 0; done < j.count; done += chunk) slot_list.push_back(j.ranks);
   for (size_t i = 0; i < slots.size(); ++i) {
-    const uint64_t key = s->h_pinned[i];
+    uint64_t key = CHM_KEY_NONE;
+    for (uint32_t w = 0; w < ways; ++w) key = std::min(key, s->h_pinned[i * chunk_words + (size_t)w * stride]);
     if (key == CHM_KEY_NONE) continue;
     const int64_t cost = (int64_t)(key >> slots[i].idx_bits);
     if (cost < best_cost) {
@@ -469,7 +477,6 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
       best_list = slot_list[i];
     }
   }
-  (void)slot_i;
   if (best_strategy < 0) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
   if (best_list) {
     // list job: best_part is a position in the caller's list; fetch the partition rank behind it
@@ -498,10 +505,10 @@ int upload_scenario(chm_scenario *s, chm_scenario **out) {
   bool ok = hipGetDevice(&s->device) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_scn, sizeof(DevScenario)) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_comp, s->comp.size() * sizeof(uint64_t)) == hipSuccess;
-  ok = ok && hipMalloc((void **)&s->d_slots, (MAX_SLOTS + 3) * sizeof(uint64_t)) == hipSuccess;
+  ok = ok && hipMalloc((void **)&s->d_slots, (size_t)SLOT_WORDS * sizeof(uint64_t)) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_winner, DEV_MAX_AFF * sizeof(uint64_t)) == hipSuccess;
   ok = ok && hipMalloc((void **)&s->d_xfer, sizeof(uint64_t) + DEV_MAX_S) == hipSuccess;
-  ok = ok && hipHostMalloc((void **)&s->h_pinned, (MAX_SLOTS + 3) * sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
+  ok = ok && hipHostMalloc((void **)&s->h_pinned, (size_t)SLOT_WORDS * sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
   ok = ok && hipMemcpy(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice) == hipSuccess;
   ok = ok && hipMemcpy(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice) == hipSuccess;
   for (auto &e : s->ev) ok = ok && hipEventCreate(&e) == hipSuccess;

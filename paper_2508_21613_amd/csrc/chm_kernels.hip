@@ -450,9 +450,10 @@ __global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
       if (a.costs_out) a.costs_out[gid] = (int64_t)cost;
     }
   }
+  const uint32_t slot = (blockIdx.x & a.slot_mask) * a.slot_stride;
   const uint64_t n_fit = __popcll(__ballot(fits));
-  if ((threadIdx.x & 63) == 0 && n_fit) atomicAdd((unsigned long long *)a.feasible, (unsigned long long)n_fit);
-  block_min_to_global(key, a.result);
+  if ((threadIdx.x & 63) == 0 && n_fit) atomicAdd((unsigned long long *)a.feasible + slot, (unsigned long long)n_fit);
+  block_min_to_global(key, a.result + slot);
 }
 
 template <int SMAX>
