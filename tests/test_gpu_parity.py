@@ -292,6 +292,66 @@ def test_replan_over_dp_pp_degrees(B, i):
     assert B.replan(ar) == O.replan(ar)
 
 
+def test_full_size_replan_of_the_32_card_shape(B):
+    """chm_replan at the size the benchmark times (31 surviving nodes, 6.7e9 splits).  The oracle cannot
+    enumerate the deep pipelines, so: every reported pipeline time is recomputed by the oracle from the
+    reported cuts; the splits of the 5- and 6-stage pipelines are compared with the oracle's exhaustive best
+    split; no single cut of any chosen split can be moved by one layer to a faster split that fits; the
+    transfer volume equals the oracle's Kuhn-Munkres optimum on the 31 x 31 fetch matrix; and the chosen
+    candidate maximises (H - t_trans) / t_step over the per-dp results, exactly."""
+    from fractions import Fraction
+    rp = dict(synth.replan32(), allreduce_us=1800)
+    L = rp["L"]
+    pf, pb = np.cumsum([0] + list(rp["fwd_us"])), np.cumsum([0] + list(rp["bwd_us"]))
+    pw = np.cumsum([0] + list(rp["mem_mib"]))
+    p0 = O.layout_p0(L, rp["old_pp"])
+    held = [(p0[n % rp["old_pp"]], p0[n % rp["old_pp"] + 1]) for n in range(rp["old_dp"] * rp["old_pp"]) if n not in rp["failed_nodes"]]
+
+    def pipeline_time(n, M, cuts):
+        b = [0] + cuts + [L]
+        if any(pw[b[j + 1]] - pw[b[j]] > rp["mem_cap_mib"] for j in range(n)):
+            return None
+        return O.makespan_1f1b([int(pf[b[j + 1]] - pf[b[j]]) for j in range(n)], [int(pb[b[j + 1]] - pb[b[j]]) for j in range(n)], M) \
+            + (n - 1) * rp["comm_us"]
+
+    per_dp = {}
+    for dp in range(rp["dp_min"], rp["dp_max"] + 1):
+        got = B.replan(dict(rp, dp_min=dp, dp_max=dp))
+        print("replan32 dp", dp, got.get("length"), got.get("t_step_us"), got.get("fetch_mib"), flush=True)
+        if not got["found"]:
+            assert O.integer_partition(len(held), dp, rp["pp_min"], rp["pp_max"]) is None
+            continue
+        per_dp[dp] = got
+        assert got["length"] == O.integer_partition(len(held), dp, rp["pp_min"], rp["pp_max"])
+        assert got["micro_batches"] == O.distribute_batch(rp["micro_batches"], got["length"])
+        sizes = []
+        for n, M, cuts, t in zip(got["length"], got["micro_batches"], got["cuts"], got["pipeline_us"]):
+            assert pipeline_time(n, M, cuts) == t
+            for i in range(n - 1):                                   # no faster neighbour one layer away
+                for delta in (-1, 1):
+                    c2 = list(cuts)
+                    c2[i] += delta
+                    if c2 != sorted(set(c2)) or c2[0] < 1 or c2[-1] > L - 1:
+                        continue
+                    t2 = pipeline_time(n, M, c2)
+                    assert t2 is None or t2 > t or (t2 == t and O.partition_rank(c2) > O.partition_rank(cuts))
+            if n <= 6:                                               # the oracle's own exhaustive split
+                want_t, want_cuts = O.best_split(rp["fwd_us"], rp["bwd_us"], rp["mem_mib"], None, n, M, rp["mem_cap_mib"])
+                assert (want_t + (n - 1) * rp["comm_us"], want_cuts) == (t, cuts)
+            b = [0] + cuts + [L]
+            sizes += [b[j + 1] - b[j] for j in range(n)]
+        assert got["comm_rounds"] == max(sizes)
+        assert got["t_step_us"] == max(got["pipeline_us"]) + rp["allreduce_us"] * got["comm_rounds"]
+        pos = [(lo, hi) for n, cuts in zip(got["length"], got["cuts"]) for lo, hi in zip([0] + cuts, cuts + [L])]
+        fetch = [[O.missing_interval(rp["mem_mib"], lo, hi, hl, hh) for lo, hi in pos] for hl, hh in held]
+        assert got["fetch_mib"] == O.min_assignment(fetch)[0]
+        assert got["t_trans_us"] == rp["restart_us"] + rp["xfer_us_per_mib"] * got["fetch_mib"]
+    whole = B.replan(rp)
+    best_dp = max(sorted(per_dp), key=lambda dp: (Fraction(rp["horizon_us"] - per_dp[dp]["t_trans_us"], per_dp[dp]["t_step_us"]), -dp))
+    assert whole["n_candidates"] == len(per_dp)
+    assert {k: v for k, v in whole.items() if k != "n_candidates"} == {k: v for k, v in per_dp[best_dp].items() if k != "n_candidates"}
+
+
 def test_replan_argument_checks(B):
     rp = REPLAN[0]
     for key, val in [("dp_min", 0), ("dp_max", 17), ("pp_max", 33), ("micro_batches", 0), ("horizon_us", 0), ("failed_nodes", [1, 1]),
