@@ -107,6 +107,55 @@ def bench_replan(args, note, B, synth):
     print(json.dumps(out))
 
 
+def bench_score(args, note, B, synth):
+    """A step = chm_score_plans over three windows of 2^27 consecutive plan indices of config 2, one inside
+    every strategy's index range: the cost of every plan index is stored (8 bytes per plan), so this
+    is the one part of the path that is bound by HBM writes."""
+    import torch
+    g = B.Scenario(synth.config2())
+    n = 1 << 27
+    out = torch.empty(n, dtype=torch.int64, device="cuda")
+    if args.copy_calibration:
+        copy_calibration()
+    firsts = [f["offset"] + min(f["n_part"] * f["n_reroute"] - n, (f["n_part"] * f["n_reroute"]) // 3) for f in g.families]
+    firsts = [max(f["offset"], x) for f, x in zip(g.families, firsts)]
+    counts = [min(n, f["n_part"] * f["n_reroute"]) for f in g.families]
+    stream = torch.cuda.Stream()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(len(firsts) + 1)]
+    ms = [0.0] * len(firsts)
+    with torch.cuda.stream(stream):
+        for i in range(args.warmup):
+            for first, cnt in zip(firsts, counts):
+                g.score_plans(first, cnt, out=out, stream=stream)
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            ev[0].record(stream)
+            for k, (first, cnt) in enumerate(zip(firsts, counts)):
+                g.score_plans(first, cnt, out=out, stream=stream)
+                ev[k + 1].record(stream)
+            stream.synchronize()
+            for k in range(len(firsts)):
+                ms[k] += ev[k].elapsed_time(ev[k + 1])
+        wall = time.perf_counter() - t0
+    ms = [m / args.steps for m in ms]
+    total = sum(counts)
+    dom = max(range(len(ms)), key=lambda k: ms[k])
+    gbs = [8.0 * c / (m * 1e-3) / 1e9 for c, m in zip(counts, ms)]
+    out_json = {"metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
+                "value": total / (wall / args.steps), "unit": "plans/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+                "dtype": "int32", "data": "synthetic",
+                "config": {"workload": "score2: chm_score_plans over 2^27 consecutive plan indices inside each strategy of config 2",
+                           "plan_indices_per_step": total, "windows": [{"strategy": f["strategy"], "first": x, "count": c}
+                                                                      for f, x, c in zip(g.families, firsts, counts)]},
+                "ms_per_strategy": ms, "store_gb_per_s_per_strategy": gbs,
+                "roofline": {"bound": "hbm", "kernel": "cost store, strategy %d" % g.families[dom]["strategy"], "achieved": gbs[dom],
+                             "peak": 8000.0, "unit": "GB/s", "frac": gbs[dom] / 8000.0, "traffic": None,
+                             "algorithmic_bytes_per_launch": 8.0 * counts[dom]}}
+    print(json.dumps(out_json))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -115,7 +164,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--ttb-runs", type=int, default=10)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config5", "replan32"],
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config5", "replan32", "score2"],
                     help="config2 (the 32-card shape) is the benchmark; the others are for profiling; replan32 times "
                          "chm_replan (search over DP/PP degrees) for the 31 nodes that survive in config2")
     ap.add_argument("--transfer-assign", type=int, default=0, choices=[0, 1],
@@ -145,6 +194,8 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "replan32":
         return bench_replan(args, note, B, synth)
+    if args.workload == "score2":
+        return bench_score(args, note, B, synth)
     workloads = {
         "config1": ("config1: L=32 PP=4 DP=2 M=8, 1 failed node", lambda: [synth.config1()]),
         "config2": ("config2: L=48 PP=8 DP=4 M=16, 1 failed node", lambda: [synth.config2()]),

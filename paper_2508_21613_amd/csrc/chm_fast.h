@@ -7,7 +7,7 @@ enum {
   FAST_MAX_P = 8,            // peers per affected stage the specialised sweeps are instantiated for
   FAST_FUSED_R = 4096,       // up to this many reroute vectors (all stages) the sweep runs inside the search kernel
   FAST_SPLIT_R = 1 << 23,    // up to this many per stage the vectors are tabulated and swept by a kernel of their own
-  FAST_SUB = 1 << 16         // partitions per pass of the split and scoring paths (bounds their scratch memory)
+  FAST_SUB = 1 << 18         // partitions per pass of the split and scoring paths (bounds their scratch memory: 38 MB)
 };
 
 // One pipeline class in the form the specialised kernels read (all int32).
@@ -54,7 +54,7 @@ struct FastState {
   FastTables *d_tables = nullptr;
   uint32_t *d_vecs = nullptr;
   uint32_t *d_runs = nullptr;
-  // scratch of the split path, FAST_SUB partitions at a time
+  // scratch of the split and scoring paths, FAST_SUB partitions at a time; allocated when first needed
   uint64_t *d_base = nullptr;               // cost without penalties, ~0 for a partition that does not fit
   uint32_t *d_weights = nullptr;            // [partition][affected stage][8] peer stage times
   uint32_t *d_pen = nullptr;                // [partition][4] best penalty per affected stage

@@ -752,6 +752,76 @@ __global__ void __launch_bounds__(BLOCK) k_expand(ExpandArgs a) {
   a.costs[gid] = base == ~0ull ? CHM_INF_COST : (int64_t)(base + a.K * pen);
 }
 
+// The same with 32-bit index arithmetic, for reroute spaces below 2^31 vectors per partition and launches
+// of at most 2^31 plan indices: the host passes the partition (relative to the pass) and the reroute rank of
+// the launch's first plan index, so a lane divides first_rr + gid, which fits 32 bits.
+struct ExpandArgs32 {
+  const uint64_t *base;
+  const uint32_t *weights;
+  const uint32_t *rows[DEV_MAX_AFF];
+  uint32_t R[DEV_MAX_AFF];
+  int32_t stride[DEV_MAX_AFF], peers[DEV_MAX_AFF];
+  int32_t n_aff;
+  uint32_t R_joint, first_part, first_rr, count;
+  uint64_t K;
+  int64_t *costs;
+};
+
+// Plan indices per workgroup: EXPAND_PER consecutive tiles of BLOCK.  A lane computes its EXPAND_PER costs
+// first and stores them back to back at the end: memory operations of a wave complete in order, so a load
+// issued after a store would wait for that store to be acknowledged (microseconds when HBM is saturated
+// with writes), and with one 512-byte store in flight per wave the kernel stayed below 1.5 TB/s.
+constexpr int EXPAND_PER = 8;
+
+__device__ __forceinline__ int64_t expand_one(const ExpandArgs32 &a, uint32_t gid) {
+  const uint32_t idx = a.first_rr + gid;
+  const uint32_t q = idx / a.R_joint;
+  uint32_t rr = idx - q * a.R_joint;
+  const uint32_t pl = a.first_part + q;
+  const uint64_t base = a.base[pl];
+  uint64_t pen = 0;
+  // unrolled over the (at most four) affected stages so that the per-stage launch arguments are read with
+  // constant offsets; rows are padded to 4 or 8 entries with zeros, so whole rows are read
+#pragma unroll
+  for (int s = DEV_MAX_AFF - 1; s >= 0; --s) {      // last affected stage is least significant
+    if (s < a.n_aff) {
+      uint32_t r = rr;
+      if (s > 0) {                                  // the first stage takes what is left: no division
+        const uint32_t qq = rr / a.R[s];
+        r = rr - qq * a.R[s];
+        rr = qq;
+      }
+      const uint32_t *w = a.weights + (size_t)pl * (DEV_MAX_AFF * 8) + s * 8;
+      const uint32_t *row = a.rows[s] + (size_t)r * (uint32_t)a.stride[s];
+      uint32_t m = 0;
+      if (a.stride[s] == 4) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) m = max(m, __umul24(row[i], w[i]));
+      } else {
+#pragma unroll
+        for (int i = 0; i < 8; ++i) m = max(m, __umul24(row[i], w[i]));
+      }
+      pen += m;
+    }
+  }
+  return base == ~0ull ? CHM_INF_COST : (int64_t)(base + a.K * pen);
+}
+
+__global__ void __launch_bounds__(BLOCK) k_expand32(ExpandArgs32 a) {
+  const uint32_t first = blockIdx.x * (EXPAND_PER * BLOCK) + threadIdx.x;
+  int64_t cost[EXPAND_PER];
+#pragma unroll
+  for (int rep = 0; rep < EXPAND_PER; ++rep) {
+    const uint32_t gid = first + rep * BLOCK;
+    cost[rep] = expand_one(a, gid < a.count ? gid : a.count - 1);   // lanes past the end redo the last index
+  }
+#pragma unroll
+  for (int rep = 0; rep < EXPAND_PER; ++rep) {
+    const uint32_t gid = first + rep * BLOCK;
+    if (gid < a.count) a.costs[gid] = cost[rep];
+  }
+}
+
 __global__ void k_fill_u32(uint32_t *p, uint32_t n, uint32_t v) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -944,16 +1014,22 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     }
     up = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
   }
-  if (up && f->usable[2] && h.n_aff > 0) {
-    up = up && hipMalloc((void **)&f->d_base, (size_t)FAST_SUB * sizeof(uint64_t)) == hipSuccess;
-    up = up && hipMalloc((void **)&f->d_weights, (size_t)FAST_SUB * DEV_MAX_AFF * 8 * sizeof(uint32_t)) == hipSuccess;
-    up = up && hipMalloc((void **)&f->d_pen, (size_t)FAST_SUB * DEV_MAX_AFF * sizeof(uint32_t)) == hipSuccess;
-  }
   if (up && f->usable[2]) up = hipMalloc((void **)&f->d_rowkey, DEV_MAX_AFF * sizeof(uint64_t)) == hipSuccess;
   return up ? 0 : 1;
 }
 
 namespace {
+
+// scratch of the split rerouting path and of plan-index scoring: per partition of a pass the cost without
+// penalties, the peer stage times and the best penalty per affected stage
+bool ensure_scratch(FastState *f) {
+  if (f->d_base && f->d_weights && f->d_pen) return true;
+  bool ok = true;
+  if (!f->d_base) ok = ok && hipMalloc((void **)&f->d_base, (size_t)FAST_SUB * sizeof(uint64_t)) == hipSuccess;
+  if (!f->d_weights) ok = ok && hipMalloc((void **)&f->d_weights, (size_t)FAST_SUB * DEV_MAX_AFF * 8 * sizeof(uint32_t)) == hipSuccess;
+  if (!f->d_pen) ok = ok && hipMalloc((void **)&f->d_pen, (size_t)FAST_SUB * DEV_MAX_AFF * sizeof(uint32_t)) == hipSuccess;
+  return ok;
+}
 
 int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uint64_t *base_out, uint32_t *weights_out,
                   hipStream_t st) {
@@ -994,6 +1070,7 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
   hipStream_t st = (hipStream_t)stream;
   if (!(a.strategy == 2 && f->split)) return launch_search(f, h, a, nullptr, nullptr, st);
   if (a.ranks != nullptr || a.costs_out != nullptr) return 1;   // the generic kernel handles lists for this shape
+  if (!ensure_scratch(f)) return -1;
   // split rerouting path, FAST_SUB partitions per pass: base costs and peer stage times, then one
   // sweep per affected stage over (partition blocks x row chunks), then the combine / argmin
   const FastTables &t = f->h_tables;
@@ -1033,6 +1110,7 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
                         uint64_t *d_out, void *stream) {
   (void)d_scn;
   if (!f->usable[2] || !f->split || h.n_aff == 0) return 1;
+  if (!ensure_scratch(f)) return -1;
   hipStream_t st = (hipStream_t)stream;
   // peer stage times of the winning partition (one-partition pass of the search kernel in split mode)
   SearchLaunch one;
@@ -1067,8 +1145,9 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
 
 int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t local_first,
                        uint64_t count, int64_t *d_costs, void *stream) {
-  if (!f->usable[2] || h.n_aff == 0 || !f->d_base) return 1;
+  if (!f->usable[2] || h.n_aff == 0) return 1;
   if (count == 0) return 0;
+  if (!ensure_scratch(f)) return -1;
   hipStream_t st = (hipStream_t)stream;
   const FastTables &t = f->h_tables;
   const uint64_t R = h.fam[2].n_reroute;
@@ -1107,6 +1186,25 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
     e.count = hi - lo + 1;
     e.part_base = p;
     e.costs = d_costs + (lo - local_first);
+    if (R < (1ull << 31)) {
+      // 32-bit index arithmetic: launches of at most 2^31 - 2^20 plan indices
+      for (uint64_t done = 0; done < e.count;) {
+        const uint64_t first = e.local_first + done;
+        ExpandArgs32 x;
+        memset(&x, 0, sizeof(x));
+        x.base = e.base; x.weights = e.weights; x.n_aff = e.n_aff; x.K = e.K;
+        for (int s = 0; s < h.n_aff; ++s) { x.rows[s] = e.rows[s]; x.R[s] = (uint32_t)e.R[s]; x.stride[s] = e.stride[s]; x.peers[s] = e.peers[s]; }
+        x.R_joint = (uint32_t)R;
+        x.first_part = (uint32_t)(first / R - p);
+        x.first_rr = (uint32_t)(first % R);
+        x.count = (uint32_t)std::min<uint64_t>(e.count - done, (1ull << 31) - (1ull << 20));
+        x.costs = e.costs + done;
+        hipLaunchKernelGGL(k_expand32, dim3((x.count + BLOCK * EXPAND_PER - 1) / (BLOCK * EXPAND_PER)), dim3(BLOCK), 0, st, x);
+        done += x.count;
+      }
+      if (hipGetLastError() != hipSuccess) return -1;
+      continue;
+    }
     for (uint64_t done = 0; done < e.count;) {       // keep each grid below 2^31 blocks
       ExpandArgs part = e;
       part.local_first = e.local_first + done;
