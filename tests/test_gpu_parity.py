@@ -364,6 +364,45 @@ def test_replan_argument_checks(B):
     assert B.replan(dict(rp, mem_cap_mib=1)) == O.replan(dict(rp, mem_cap_mib=1)) == {"found": False, "n_candidates": 3}
 
 
+def test_large_costs_run_in_64_bit(B):
+    """layer times of seconds and hundreds of micro-batches: step times beyond 2^31 us, so the library must take
+    its 64-bit kernels; every cost and the argmin still match the oracle, and a cost bound beyond 62 bits is
+    refused by both sides"""
+    rng = np.random.default_rng(31)
+    for i, (L, PP, DP, M, failed) in enumerate([(9, 3, 2, 200, [1]), (12, 4, 3, 256, [2, 9]), (10, 5, 2, 150, [7]), (20, 18, 2, 90, [3])]):
+        fwd = rng.integers(8_000_000, 12_000_000, L).astype(np.int32)
+        bwd = (2 * fwd.astype(np.int64) * rng.uniform(0.9, 1.1, L)).astype(np.int32)
+        mem = rng.integers(400, 600, L).astype(np.int32)
+        speed = rng.integers(40_000, 600_000, DP * PP).astype(np.uint32)          # 0.6x .. 9x slower nodes
+        sc = synth.scenario(L, PP, DP, M, fwd, bwd, mem, failed, 150, int(mem.sum() * 2.5 / PP), speed=speed,
+                            horizon_steps=64, reroute_cap=M // 2 + 40, allreduce_us=(0, 5_000_000)[i % 2], transfer_assign=i % 2)
+        print("large costs", i, L, PP, DP, M, failed, flush=True)
+        o, g = O.Scenario(sc), B.Scenario(sc)
+        assert g.families == o.families and g.n_plans == o.n_plans
+        n = min(o.n_plans, 20000)
+        want = o.score(0, n)
+        feasible = want[want != O.INF]
+        assert feasible.size and feasible.max() > 2 ** 40          # far beyond what 32-bit step times could give
+        got = gpu_scores(B, g, 0, n)
+        assert (got == want).all(), np.flatnonzero(got != want)[:10]
+        for f in o.families:
+            size = f["n_part"] * f["n_reroute"]
+            first, count = f["offset"] + size // 2, min(4000, size - size // 2)
+            assert (gpu_scores(B, g, first, count) == o.score(first, count)).all()
+            width = min(f["n_part"], 300)
+            rc_o, best_o, _ = o.search_range(f["strategy"], 0, width)
+            rc_g, best_g = g.search_range(f["strategy"], 0, width)
+            assert rc_g == rc_o and same_plan(best_g, best_o)
+    huge = synth.scenario(8, 2, 2, 256, np.full(8, 2 ** 31 - 1, np.int32), np.full(8, 2 ** 31 - 1, np.int32), np.ones(8, np.int32),
+                          [0], 0, 100, speed=np.full(4, 2 ** 20, np.uint32), horizon_steps=2 ** 31 - 1)
+    with pytest.raises(B.ChmError) as e:
+        B.Scenario(huge)
+    assert e.value.code == B.ERR_OVERFLOW
+    with pytest.raises(O.OracleError) as e2:
+        O.Scenario(huge)
+    assert e2.value.code == O.ERR_OVERFLOW
+
+
 def test_error_paths_and_degenerate_cases(B):
     import torch
     sc = SMALL[2]
