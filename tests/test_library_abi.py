@@ -28,10 +28,27 @@ def test_every_declared_entry_point_is_exported():
     assert sorted(B.SYMBOLS) == names
 
 
-def test_struct_layouts_match_the_header():
+def test_struct_layouts_match_the_header(tmp_path):
+    """sizes and field offsets of every structure of the binding against what a C compiler makes of include/chm.h"""
+    import subprocess
+    structs = {"chm_scenario_desc": B.Desc, "chm_family": B.Family, "chm_space": B.Space, "chm_best": B.Best,
+               "chm_timing": B.Timing, "chm_replan_desc": B.ReplanDesc, "chm_replan_plan": B.ReplanPlan}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "chm.h"', 'int main(void) {']
+    for cname, cls in structs.items():
+        lines.append('  printf("%s %%zu\\n", sizeof(%s));' % (cname, cname))
+        for field, _ in cls._fields_:
+            lines.append('  printf("%s.%s %%zu\\n", offsetof(%s, %s));' % (cname, field, cname, field))
+    lines += ['  return 0;', '}']
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), "-o", str(exe), str(src)], check=True)
+    want = dict(line.split() for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.splitlines())
+    for cname, cls in structs.items():
+        assert C.sizeof(cls) == int(want[cname]), cname
+        for field, _ in cls._fields_:
+            assert getattr(cls, field).offset == int(want["%s.%s" % (cname, field)]), (cname, field)
     assert C.sizeof(B.Family) == 32 and C.sizeof(B.Space) == 8 + 3 * 32 + 8
-    assert C.sizeof(B.Best) == 8 + 8 + 4 + 4 + 32 + 4 + 16 + 128 + 4   # trailing padding to 8 bytes
-    assert C.sizeof(B.Desc) == 16 + 4 * 8 + 8 + 8 + 4 * 4 + 12 + 4 + 0 or C.sizeof(B.Desc) % 8 == 0
 
 
 def test_error_strings_and_argument_checks_need_no_device():
@@ -60,3 +77,16 @@ def test_no_cpu_fallback_without_a_device():
     with pytest.raises(B.ChmError) as e:
         B.Scenario(synth.small_random(1))
     assert e.value.code == B.ERR_HIP
+    with pytest.raises(B.ChmError) as e:
+        B.replan(synth.replan_case(5, 10, 3, 3, [4], 12, (1, 4), (1, 6)), stream=0)
+    assert e.value.code == B.ERR_HIP
+
+
+def test_replan_argument_checks_need_no_device():
+    rp = synth.replan_case(5, 10, 3, 3, [4], 12, (1, 4), (1, 6))
+    for key, val in [("L", 0), ("old_pp", 0), ("old_dp", 17), ("dp_min", 0), ("dp_max", 17), ("pp_min", 0), ("pp_max", 33),
+                     ("micro_batches", 0), ("horizon_us", 0), ("failed_nodes", [1, 1]), ("failed_nodes", [9]), ("mem_cap_mib", 0),
+                     ("allreduce_us", -1), ("fwd_us", np.zeros(10, np.int32))]:
+        with pytest.raises(B.ChmError) as e:
+            B.replan(dict(rp, **{key: val}), stream=0)
+        assert e.value.code == B.ERR_ARG, key
