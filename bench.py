@@ -34,11 +34,13 @@ def algorithmic_ops(fam, feasible):
     partition that passes the memory filter in addition: per pipeline class one max and one add
     per recurrence cell (2 x stages x micro-batches cells), 2 Q16 scalings per stage, the
     comm add and the max over pipelines; 4 per stage for the weight-fetch volume; 2 for the cost;
-    and per reroute vector one multiply per peer, the max over peers and the compare."""
+    per stage that lost nodes the products (extra micro-batches x peer stage time) for every count
+    0..orphans, one add each, which all reroute vectors share; and per reroute vector the max over
+    its peers' products and the compare."""
     S = fam["stages"]
     light = 4 * S
     heavy = sum(4 * n_c * m_c + 2 * n_c + 2 for n_c, m_c in fam["classes"]) + 4 * S + 2
-    heavy += sum(R * 2 * p for R, p in zip(fam["R"], fam["peers"]))
+    heavy += sum(R * p + p * t for R, p, t in zip(fam["R"], fam["peers"], fam["orphans"]))
     if fam.get("assign") and fam["strategy"] == 1:
         # least-transfer assignment: the two-index recurrence over (survivor, new stage) pairs, per cell
         # the overlap (min, max, subtract, clamp) and one add and two max
@@ -213,11 +215,16 @@ def main():
     note("%d scenario(s) loaded in %.1f ms" % (len(handles), load_ms))
     stream = torch.cuda.Stream()
 
-    def family_work(g):
+    def family_work(g, sc):
         shape = g.reroute_shape()
+        lost = {}
+        for node in sc["failed_nodes"]:
+            lost[node % sc["PP"]] = lost.get(node % sc["PP"], 0) + 1
+        orphans = [lost[s] * sc["M"] for s in sorted(lost)]     # per stage that lost nodes, ascending
         fams = []
         for f in g.families:
             d = dict(f)
+            d["orphans"] = orphans if f["strategy"] == 2 else []
             d["classes"] = g.family_classes(f["strategy"])
             d["peers"] = [p for p, _ in shape] if f["strategy"] == 2 else []
             d["R"] = [r for _, r in shape] if f["strategy"] == 2 else []
@@ -225,7 +232,7 @@ def main():
             fams.append(d)
         return fams
 
-    work = [family_work(g) for g in handles]
+    work = [family_work(g, sc) for g, sc in zip(handles, scenarios)]
 
     if args.copy_calibration:
         copy_calibration()

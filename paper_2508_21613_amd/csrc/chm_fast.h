@@ -45,6 +45,9 @@ struct FastTables {
   // dwords: [0..5] the shared entries, [6] = lo | (sum of the last two entries << 16), [7] = length
   uint32_t run_off[DEV_MAX_AFF];  // offset (in uint32) of stage a's runs in runs[]
   uint32_t run_count[DEV_MAX_AFF];
+  // small uncapped reroute spaces have a sweep unrolled at compile time (see sweep_products):
+  // peers * 256 + orphaned micro-batches when such a sweep exists for stage a, else 0
+  uint32_t unrolled_shape[DEV_MAX_AFF];
 };
 
 struct FastState {

@@ -201,6 +201,42 @@ __device__ __forceinline__ uint32_t sweep_runs(RowPtr runs, uint32_t n_runs, con
   return best;
 }
 
+// min over ALL vectors of P non-negative entries summing to T (no cap) of max_i r_i * w_i, with the vector
+// loop unrolled at compile time: the products r * w_i (r = 0..T) of the last two peers are built once with
+// adds, the first peer's product is carried along its (outer) loop, after which a vector costs one
+// v_max3_u32 (two peers: v_max_u32) and half a v_min3_u32.  For P = 2, 3 and small T.
+template <int P, int T>
+__device__ __forceinline__ uint32_t sweep_products(const uint32_t (&w)[P]) {
+  static_assert(P == 2 || P == 3, "two or three peers");
+  uint32_t last[T + 1], mid[P == 3 ? T + 1 : 1];
+  last[0] = 0;
+  mid[0] = 0;
+#pragma unroll
+  for (int r = 1; r <= T; ++r) {
+    last[r] = last[r - 1] + w[P - 1];
+    if (P == 3) mid[r] = mid[r - 1] + w[1];
+  }
+  uint32_t best = 0xffffffffu, first = 0;
+#pragma unroll
+  for (int r0 = 0; r0 <= T; ++r0) {
+    if (P == 2) {
+      const uint32_t b = last[T - r0];
+      const uint32_t pen = first > b ? first : b;
+      best = best < pen ? best : pen;
+    } else {
+#pragma unroll
+      for (int r1 = 0; r1 <= T - r0; ++r1) {
+        const uint32_t b = mid[P == 3 ? r1 : 0], c = last[T - r0 - r1];
+        uint32_t pen = first > b ? first : b;
+        pen = pen > c ? pen : c;
+        best = best < pen ? best : pen;
+      }
+    }
+    first += w[0];
+  }
+  return best;
+}
+
 __device__ __forceinline__ uint64_t umin64(uint64_t a, uint64_t b) { return a < b ? a : b; }
 
 // 1-based position of the n-th set bit of x (1 <= n <= popcount(x)): which half holds it is decided
@@ -514,6 +550,27 @@ k_fast_search(FastLaunch a) {
           const RowPtr runs = as_const(a.runs) + tab->run_off[st];
           const uint32_t n_runs = tab->run_count[st];
           uint32_t pen = 0;
+          const uint32_t shape = tab->unrolled_shape[st];
+          if (shape != 0) {
+            // small uncapped spaces: sweep unrolled at compile time over a table of products
+#define CHM_UNROLLED(P, T)                                                                      \
+  case (P) * 256 + (T): {                                                                       \
+    uint32_t w[P];                                                                              \
+    _Pragma("unroll") for (int i = 0; i < P; ++i) {                                             \
+      const uint32_t q = scn->aff_q[st][i];                                                     \
+      w[i] = (uint32_t)(scale32(f_st, q) + scale32(b_st, q));                                   \
+    }                                                                                           \
+    pen = sweep_products<P, T>(w);                                                              \
+  } break;
+            switch (shape) {
+              CHM_UNROLLED(2, 8) CHM_UNROLLED(2, 16) CHM_UNROLLED(2, 32)
+              CHM_UNROLLED(3, 8) CHM_UNROLLED(3, 16)
+              default: break;
+            }
+#undef CHM_UNROLLED
+            t_step += (int)pen;
+            continue;
+          }
 #define CHM_SWEEP(P)                                                                            \
   case P: {                                                                                     \
     uint32_t w[P];                                                                              \
@@ -949,7 +1006,10 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
       int same = -1;
       for (int b = 0; b < a; ++b)
         if (h.aff_peers[b] == h.aff_peers[a] && h.aff_total[b] == h.aff_total[a]) same = b;
-      if (same >= 0) { t->run_off[a] = t->run_off[same]; t->run_count[a] = t->run_count[same]; continue; }
+      if (same >= 0) {
+        t->run_off[a] = t->run_off[same]; t->run_count[a] = t->run_count[same]; t->unrolled_shape[a] = t->unrolled_shape[same];
+        continue;
+      }
       const int p = h.aff_peers[a], total = h.aff_total[a];
       const int cap = h.rcap > 0 ? h.rcap : total;
       t->run_off[a] = (uint32_t)runs.size();
@@ -997,6 +1057,10 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
       }
       t->run_count[a] = n_runs;
       if (vectors != h.aff_R[a]) f->usable[2] = false;     // table and count must agree
+      if (h.rcap <= 0 || h.rcap >= total) {                // uncapped: every composition is valid
+        const bool have = (p == 2 && (total == 8 || total == 16 || total == 32)) || (p == 3 && (total == 8 || total == 16));
+        if (have) t->unrolled_shape[a] = (uint32_t)p * 256u + (uint32_t)total;
+      }
     }
     if (!f->usable[2]) f->split = false;
   }
