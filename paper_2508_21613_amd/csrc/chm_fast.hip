@@ -54,6 +54,11 @@ __device__ __forceinline__ int scale32(int x, uint32_t q) {
   return (int)(((uint64_t)(uint32_t)x * q + 32768u) >> 16);
 }
 
+// forward + backward time of a stage on a peer with factor q (uniform): nominal peers need no scaling
+__device__ __forceinline__ uint32_t peer_time(int f, int b, uint32_t q) {
+  return q == 65536u ? (uint32_t)(f + b) : (uint32_t)(scale32(f, q) + scale32(b, q));
+}
+
 // 1F1B pipeline time of N stages, M micro-batches; F, B per stage.  Round t: forward t on all
 // stages in stage order, then backward t-(N-1-s) on stage s (see chm_kernels.hip).  The clocks are
 // kept relative to the forward chain: e[s] = (time stage s is free) - (F[0] + ... + F[s-1]).  In
@@ -558,7 +563,7 @@ k_fast_search(FastLaunch a) {
     uint32_t w[P];                                                                              \
     _Pragma("unroll") for (int i = 0; i < P; ++i) {                                             \
       const uint32_t q = scn->aff_q[st][i];                                                     \
-      w[i] = (uint32_t)(scale32(f_st, q) + scale32(b_st, q));                                   \
+      w[i] = peer_time(f_st, b_st, q);                                                          \
     }                                                                                           \
     pen = sweep_products<P, T>(w);                                                              \
   } break;
@@ -576,7 +581,7 @@ k_fast_search(FastLaunch a) {
     uint32_t w[P];                                                                              \
     _Pragma("unroll") for (int i = 0; i < P; ++i) {                                             \
       const uint32_t q = scn->aff_q[st][i];                                                     \
-      w[i] = (uint32_t)(scale32(f_st, q) + scale32(b_st, q));                                   \
+      w[i] = peer_time(f_st, b_st, q);                                                          \
     }                                                                                           \
     pen = sweep_runs<P>(runs, n_runs, w);                                                       \
   } break;
@@ -604,7 +609,7 @@ k_fast_search(FastLaunch a) {
             const int p = scn->aff_peers[st];
             for (int i = 0; i < p; ++i) {
               const uint32_t q = scn->aff_q[st][i];
-              wout[st * 8 + i] = (uint32_t)(scale32(f_st, q) + scale32(b_st, q));
+              wout[st * 8 + i] = peer_time(f_st, b_st, q);
             }
           }
         }
