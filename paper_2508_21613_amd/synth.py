@@ -201,3 +201,13 @@ def replan32(seed=BASE_SEED + 2, dp_range=(2, 6), pp_range=(4, 12)):
                 pp_min=pp_range[0], pp_max=pp_range[1], micro_batches=sc["DP"] * sc["M"], comm_us=sc["comm_us"],
                 mem_cap_mib=sc["mem_cap_mib"], horizon_us=2048 * 415_400, restart_us=sc["reconf_us"][1],
                 xfer_us_per_mib=sc["xfer_us_per_mib"])
+
+
+def replan_tie():
+    """a re-planning input whose candidates with 2 and with 4 pipelines tie exactly in the objective: four unit
+    layers (forward 100, backward 200), four nodes, four micro-batches, nothing to transfer, comm 100 and 350 per
+    communication round: 2 x 2 stages take 6 x 300 + 100 + 2 x 350, 4 x 1 stage take 4 x 300 + 4 x 350, both 2600"""
+    L = 4
+    return dict(L=L, fwd_us=np.full(L, 100, np.int32), bwd_us=np.full(L, 200, np.int32), mem_mib=np.full(L, 10, np.int32),
+                act_mib=None, old_dp=2, old_pp=2, failed_nodes=[], dp_min=1, dp_max=4, pp_min=1, pp_max=4, micro_batches=4,
+                comm_us=100, mem_cap_mib=1000, horizon_us=10 ** 9, restart_us=0, xfer_us_per_mib=0, allreduce_us=350)

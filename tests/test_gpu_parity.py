@@ -274,6 +274,7 @@ REPLAN = [
     synth.replan_case(16, 16, 8, 4, [0, 9, 18, 27], 64, (5, 9), (2, 6)),                   # 28 nodes
     synth.replan_case(17, 12, 16, 4, list(range(0, 64, 7)), 96, (12, 16), (3, 5)),         # 54 nodes, 16 pipelines
     synth.replan_case(18, 6, 2, 2, [0, 1, 2, 3], 4, (1, 2), (1, 2)),                       # nothing survived
+    synth.replan_tie(),                                                                     # two candidates tie exactly
 ]
 
 

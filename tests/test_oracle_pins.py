@@ -801,6 +801,16 @@ def test_communication_rounds_closed_forms():
         O.Scenario(dict(sc, allreduce_us=-1))
 
 
+def test_replan_ties_keep_the_smaller_dp():
+    rp = synth.replan_tie()
+    got = O.replan(rp)
+    assert got == R.replan(rp)
+    assert got["dp"] == 2 and got["t_step_us"] == 2600 and got["t_trans_us"] == 0 and got["n_candidates"] == 4
+    four = O.replan(dict(rp, dp_min=4))
+    assert four["dp"] == 4 and four["t_step_us"] == 2600            # the tie is real
+    assert O.replan(dict(rp, dp_min=1, dp_max=1))["t_step_us"] == 7 * 300 + 3 * 100 + 350
+
+
 def test_replan_with_communication_rounds():
     for i, rp in enumerate(REPLAN[:8]):
         rp = dict(rp, allreduce_us=2000 + 500 * i)
