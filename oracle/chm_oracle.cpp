@@ -483,12 +483,17 @@ int64_t stage_penalty(const std::vector<int64_t> &w, const uint16_t *r) {
 }
 
 int64_t full_cost(const orc_scenario *s, int strategy, int k, const uint8_t *cuts,
-                  const std::vector<std::vector<uint16_t>> &rr /* per affected stage, per peer */) {
+                  const std::vector<std::vector<uint16_t>> &rr /* per affected stage, per peer */,
+                  int64_t *t_step_out = nullptr, int64_t *t_trans_out = nullptr) {
   int64_t t_step, reconf;
   std::vector<std::vector<int64_t>> w;
+  if (t_step_out) *t_step_out = 0;
+  if (t_trans_out) *t_trans_out = 0;
   if (base_cost_terms(s, strategy, k, cuts, &t_step, &reconf, &w) == ORC_INF) return ORC_INF;
   if (strategy == 2)
     for (size_t a = 0; a < s->affected.size(); ++a) t_step += stage_penalty(w[a], rr[a].data());
+  if (t_step_out) *t_step_out = t_step;
+  if (t_trans_out) *t_trans_out = reconf;
   return s->K * t_step + reconf;
 }
 
@@ -572,7 +577,11 @@ int search_family_range(const orc_scenario *s, const orc_family *f, uint64_t fir
       if (!ok) continue;
     }
     int64_t cost = s->K * t_step + reconf;
-    if (cost < best->cost) fill_plan(s, f, pr, rr_rank, cost, best);
+    if (cost < best->cost) {
+      fill_plan(s, f, pr, rr_rank, cost, best);
+      best->t_step_us = t_step;
+      best->t_trans_us = reconf;
+    }
   }
   return ORC_OK;
 }
@@ -714,7 +723,7 @@ extern "C" int orc_decode(const orc_scenario *s, uint64_t index, orc_plan *out) 
       s->comps[a].unrank(rr[a], r.data());
       vec.push_back(r);
     }
-    out->cost = full_cost(s, f->strategy, f->stages - 1, out->cuts, vec);
+    out->cost = full_cost(s, f->strategy, f->stages - 1, out->cuts, vec, &out->t_step_us, &out->t_trans_us);
     return ORC_OK;
   }
   return ORC_ERR_RANGE;

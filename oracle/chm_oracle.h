@@ -79,6 +79,8 @@ typedef struct {
   int32_t n_affected;          /* affected stages (ascending) for the rerouting family     */
   int32_t affected_stage[4];
   uint16_t reroute[4][16];     /* reroute[a][d] = extra micro-batches on replica d (0 for a failed node) */
+  int64_t t_step_us;           /* estimated step time of the plan (0 when it does not fit)  */
+  int64_t t_trans_us;          /* its transition time; cost = horizon_steps * t_step_us + t_trans_us */
 } orc_plan;
 
 /* --- building blocks, exposed so that tests can pin each one on its own ---------------- */

@@ -72,7 +72,8 @@ class Space(C.Structure):
 class Plan(C.Structure):
     _fields_ = [("index", C.c_uint64), ("cost", C.c_int64), ("strategy", C.c_int32),
                 ("stages", C.c_int32), ("cuts", C.c_uint8 * 32), ("n_affected", C.c_int32),
-                ("affected_stage", C.c_int32 * 4), ("reroute", (C.c_uint16 * 16) * 4)]
+                ("affected_stage", C.c_int32 * 4), ("reroute", (C.c_uint16 * 16) * 4),
+                ("t_step_us", C.c_int64), ("t_trans_us", C.c_int64)]
 
 
 _lib = None
@@ -280,7 +281,8 @@ def _plan_dict(p):
     d = {"index": int(p.index), "cost": int(p.cost), "strategy": int(p.strategy), "stages": int(p.stages),
          "cuts": [int(p.cuts[i]) for i in range(k)], "n_affected": int(p.n_affected),
          "affected_stage": [int(p.affected_stage[a]) for a in range(p.n_affected)],
-         "reroute": [[int(p.reroute[a][d]) for d in range(16)] for a in range(p.n_affected)]}
+         "reroute": [[int(p.reroute[a][d]) for d in range(16)] for a in range(p.n_affected)],
+         "t_step_us": int(p.t_step_us), "t_trans_us": int(p.t_trans_us)}
     return d
 
 

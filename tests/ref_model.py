@@ -152,6 +152,11 @@ class Model:
         return sum(self.m[l] for l in range(a, b) if not (a0 <= l < b0))
 
     def cost(self, strategy, cuts, rr=()):
+        terms = self.terms(strategy, cuts, rr)
+        return INF if terms is None else self.K * terms[0] + terms[1]
+
+    def terms(self, strategy, cuts, rr=()):
+        """(step time, transition time) of a plan, None when it does not fit in memory"""
         sc, S, D, M = self.sc, self.S, self.D, self.M
         bounds = [0] + list(cuts) + [self.L]
         n = len(bounds) - 1
@@ -170,7 +175,7 @@ class Model:
                 for pos, j in enumerate(alive):
                     nx = (j + 1) % S
                     if peak(ms[j] + ms[nx], av[j] + av[nx], len(alive), pos) > cap:
-                        return INF
+                        return None
             t = 0
             for d in range(D):
                 alive = [j for j in range(S) if not self.dead[d][j]]
@@ -180,13 +185,13 @@ class Model:
             miss = sum(self.missing(bounds[j], bounds[j + 1], self.p0[j], self.p0[j + 1]) for j in range(S))
         elif strategy == 1:
             if any(peak(ms[j], av[j], n, j) > cap for j in range(n)):
-                return INF
+                return None
             t, miss = 0, 0
             for d in range(D):
                 if self.fail_rep[d] == 0:
                     if any(peak(self.seg(self.m, self.p0[j], self.p0[j + 1]), self.seg(self.a, self.p0[j], self.p0[j + 1]), S, j) > cap
                            for j in range(S)):
-                        return INF
+                        return None
                     F = [scale(self.seg(self.f, self.p0[j], self.p0[j + 1]), self.q[d][j]) for j in range(S)]
                     B = [scale(self.seg(self.b, self.p0[j], self.p0[j + 1]), self.q[d][j]) for j in range(S)]
                     t = max(t, dag_makespan(F, B, self.mbB[d]) + (S - 1) * comm)
@@ -204,7 +209,7 @@ class Model:
                     miss = max(miss, miss_d)
         else:
             if any(peak(ms[j], av[j], S, j) > cap for j in range(S)):
-                return INF
+                return None
             t = 0
             for d in range(D):
                 qq = [65536 if self.dead[d][j] else self.q[d][j] for j in range(S)]
@@ -229,7 +234,7 @@ class Model:
                 else:
                     devices += [stage[j] for j in alive]
             t += sc["allreduce_us"] * greedy_rounds(self.L, devices)
-        return self.K * t + sc["reconf_us"][strategy] + sc["xfer_us_per_mib"] * miss
+        return t, sc["reconf_us"][strategy] + sc["xfer_us_per_mib"] * miss
 
     def all_costs(self):
         """cost of every plan in global index order"""

@@ -307,6 +307,16 @@ def test_every_plan_cost_matches_the_independent_model(i):
         assert p["cost"] == want[idx]
         rr = p["reroute"] if p["strategy"] == 2 else None
         assert s.plan_cost(p["strategy"], p["cuts"], rr) == want[idx]
+        # the estimated step time and the transition time are reported separately as well
+        vecs = [[p["reroute"][a][d] for d in model.peers[a]] for a in range(p["n_affected"])] if p["strategy"] == 2 else ()
+        terms = model.terms(p["strategy"], p["cuts"], vecs)
+        assert (p["t_step_us"], p["t_trans_us"]) == (terms if terms is not None else (0, 0))
+        if terms is not None:
+            assert sc["horizon_steps"] * p["t_step_us"] + p["t_trans_us"] == p["cost"]
+    rc, best = s.search(7)
+    if rc == 0:
+        assert best["cost"] == sc["horizon_steps"] * best["t_step_us"] + best["t_trans_us"] == min(want)
+        assert (best["t_step_us"], best["t_trans_us"]) == (s.decode(best["index"])["t_step_us"], s.decode(best["index"])["t_trans_us"])
 
 
 @pytest.mark.parametrize("i", range(len(SMALL)))
