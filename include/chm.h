@@ -115,6 +115,9 @@ typedef struct {
   int32_t n_affected;          /* rerouting only: stages that lost nodes, ascending                   */
   int32_t affected_stage[4];
   uint16_t reroute[4][16];     /* reroute[a][d] = extra micro-batches on pipeline d for affected stage a */
+  int64_t t_step_us;           /* estimated step time of the plan (Estimator), 0 when nothing feasible was found or
+                                  the plan was only decoded                                               */
+  int64_t t_trans_us;          /* its transition time; cost = horizon_steps * t_step_us + t_trans_us      */
 } chm_best;
 
 /* Per-call kernel timings (milliseconds between HIP events on the caller's stream),

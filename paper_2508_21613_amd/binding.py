@@ -44,7 +44,8 @@ class Space(C.Structure):
 class Best(C.Structure):
     _fields_ = [("index", C.c_uint64), ("cost", C.c_int64), ("strategy", C.c_int32),
                 ("stages", C.c_int32), ("cuts", C.c_uint8 * 32), ("n_affected", C.c_int32),
-                ("affected_stage", C.c_int32 * 4), ("reroute", (C.c_uint16 * 16) * 4)]
+                ("affected_stage", C.c_int32 * 4), ("reroute", (C.c_uint16 * 16) * 4),
+                ("t_step_us", C.c_int64), ("t_trans_us", C.c_int64)]
 
 
 class ReplanDesc(C.Structure):
@@ -134,7 +135,8 @@ def _best_dict(b):
     return {"index": int(b.index), "cost": int(b.cost), "strategy": int(b.strategy), "stages": int(b.stages),
             "cuts": [int(b.cuts[i]) for i in range(k)], "n_affected": int(b.n_affected),
             "affected_stage": [int(b.affected_stage[a]) for a in range(b.n_affected)],
-            "reroute": [[int(b.reroute[a][d]) for d in range(16)] for a in range(b.n_affected)]}
+            "reroute": [[int(b.reroute[a][d]) for d in range(16)] for a in range(b.n_affected)],
+            "t_step_us": int(b.t_step_us), "t_trans_us": int(b.t_trans_us)}
 
 
 def _stream_ptr(stream):

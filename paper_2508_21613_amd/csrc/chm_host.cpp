@@ -495,6 +495,12 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
     for (int a = 0; a < s->h.n_aff; ++a) rr[a] = s->h_pinned[a];
   }
   fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
+  // the winner's step time and transition time, re-evaluated on the device
+  if (chmk_plan_terms(s->d_scn, s->d_comp, best_strategy, best_part, rr, (int64_t *)s->d_xfer, s->smax, st)) return CHM_ERR_HIP;
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_xfer, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipStreamSynchronize(st));
+  out->t_step_us = (int64_t)s->h_pinned[0];
+  out->t_trans_us = (int64_t)s->h_pinned[1];
   return CHM_OK;
 }
 

@@ -478,6 +478,7 @@ __global__ void __launch_bounds__(BLOCK) k_reroute_winner(const DevScenario *scn
 // cell: a step that changes neither index pairs node i-1 with stage j-1.  Nodes left unpaired take
 // the stages left over, in ascending order (they hold nothing of them either way).
 struct SurvivorList { int32_t n; uint8_t host[DEV_MAX_S]; };
+struct PlanRanks { uint64_t r[DEV_MAX_AFF]; };      // reroute rank per affected stage
 
 __global__ void __launch_bounds__(64) k_transfer_plan(const DevScenario *scn, uint64_t part_rank, SurvivorList sv,
                                                       uint8_t *stage_of_node, int64_t *fetch_mib) {
@@ -522,6 +523,28 @@ __global__ void __launch_bounds__(64) k_transfer_plan(const DevScenario *scn, ui
     stage_of_node[i] = (uint8_t)j;
   }
   *fetch_mib = total;
+}
+
+// step time and transition time of ONE plan (the winner of a search), by the generic 64-bit evaluation:
+// out[0] = t_step, out[1] = transition time; both 0 when the plan does not fit
+template <int SMAX>
+__global__ void __launch_bounds__(BLOCK) k_plan_terms(const DevScenario *scn, const uint64_t *comp, int strategy,
+                                                      uint64_t part_rank, PlanRanks rr, int64_t *out) {
+  __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  const DevFamily &fam = scn->fam[strategy];
+  Cuts<SMAX> cuts{cut_cols, 0};
+  unrank_partition<SMAX>(scn, fam.stages - 1, part_rank, cuts);
+  int64_t t_step = 0, reconf = 0;
+  if (eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf)) {
+    if (strategy == 2)
+      for (int a = 0; a < scn->n_aff; ++a) t_step += penalty_of_rank<SMAX>(scn, comp, cuts, a, rr.r[a]);
+  } else {
+    t_step = 0;
+    reconf = 0;
+  }
+  out[0] = t_step;
+  out[1] = reconf;
 }
 
 // partition rank of explicit cut positions (inverse of unrank_partition); cuts[n][k] row-major.
@@ -615,6 +638,18 @@ int chmk_transfer_plan(const DevScenario *d_scn, uint64_t part_rank, int32_t n, 
   hipLaunchKernelGGL(k_transfer_plan, dim3(1), dim3(64), 0, (hipStream_t)stream, d_scn, part_rank, sv, d_stage_of_node,
                      d_fetch_mib);
   return (int)hipGetLastError();
+}
+
+int chmk_plan_terms(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy, uint64_t part_rank,
+                    const uint64_t *rr_ranks, int64_t *d_out, int32_t smax, void *stream) {
+  PlanRanks rr;
+  for (int a = 0; a < DEV_MAX_AFF; ++a) rr.r[a] = rr_ranks[a];
+  return dispatch_smax(smax, [&](auto tag) {
+    constexpr int SMAX = decltype(tag)::value;
+    hipLaunchKernelGGL(k_plan_terms<SMAX>, dim3(1), dim3(BLOCK), 0, (hipStream_t)stream, d_scn, d_comp, strategy, part_rank,
+                       rr, d_out);
+    return (int)hipGetLastError();
+  });
 }
 
 int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank, uint64_t *d_out,
