@@ -262,6 +262,15 @@ typedef struct {
  * No candidate / nothing fits is not an error: CHM_OK with out->found = 0. */
 int chm_replan(const chm_replan_desc *desc, chm_replan_plan *out, void *hip_stream);
 
+/* Ranks two plans by the objective of the "Optimization Problem" paragraph, throughput x effective time
+ * ratio = B / t_step x (H - t_trans) / H for the same global batch B and time H between two faults: returns
+ * 1 when plan a is better, -1 when plan b is better, 0 on an exact tie (compared by cross-multiplication in
+ * 128 bits).  Lets a caller choose between the winner of chm_search_best (recovery inside the DP x PP grid)
+ * and that of chm_replan (new DP/PP degrees) from their t_step_us / t_trans_us.  Host only.  Step times
+ * must be positive; CHM_ERR_ARG (-1 is a valid answer, so errors are reported as -100) otherwise. */
+int chm_compare_objective(int64_t t_step_a_us, int64_t t_trans_a_us, int64_t t_step_b_us, int64_t t_trans_b_us,
+                          int64_t horizon_us);
+
 void chm_free_scenario(chm_scenario *s);
 const char *chm_strerror(int code);
 

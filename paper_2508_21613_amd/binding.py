@@ -17,7 +17,7 @@ INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
            "chm_search_range", "chm_search_ranks", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
-           "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_valu_probe", "chm_free_scenario",
+           "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
 
@@ -108,6 +108,7 @@ def lib():
         L.chm_transfer_plan.argtypes = [vp, C.c_uint64, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_uint8 * 32),
                                         C.POINTER(C.c_uint8 * 32), C.POINTER(C.c_int64), vp]
         L.chm_replan.argtypes = [C.POINTER(ReplanDesc), C.POINTER(ReplanPlan), vp]
+        L.chm_compare_objective.argtypes = [C.c_int64] * 5
         L.chm_valu_probe.argtypes = [C.c_int32, C.c_uint32, C.POINTER(C.c_double), vp]
         L.chm_free_scenario.argtypes = [vp]
         L.chm_free_scenario.restype = None
@@ -151,6 +152,14 @@ def valu_probe(kind, iters=4000, stream=None):
     out = C.c_double()
     _check(lib().chm_valu_probe(kind, iters, C.byref(out), _stream_ptr(stream)))
     return float(out.value)
+
+
+def compare_objective(a, b, horizon_us):
+    """chm_compare_objective on two plan dicts carrying t_step_us and t_trans_us: 1 if a is better, -1 if b, 0 on a tie"""
+    rc = lib().chm_compare_objective(a["t_step_us"], a["t_trans_us"], b["t_step_us"], b["t_trans_us"], horizon_us)
+    if rc == -100:
+        raise ChmError(ERR_ARG, strerror(ERR_ARG))
+    return rc
 
 
 def replan(rp, stream=None, with_stats=False):

@@ -154,6 +154,15 @@ int check(const chm_replan_desc *d) {
 
 }  // namespace
 
+extern "C" int chm_compare_objective(int64_t t_step_a_us, int64_t t_trans_a_us, int64_t t_step_b_us, int64_t t_trans_b_us,
+                                     int64_t horizon_us) {
+  if (t_step_a_us < 1 || t_step_b_us < 1 || horizon_us < 1) return -100;
+  // (H - trans_a) / step_a  versus  (H - trans_b) / step_b
+  const __int128 lhs = ((__int128)horizon_us - t_trans_a_us) * t_step_b_us;
+  const __int128 rhs = ((__int128)horizon_us - t_trans_b_us) * t_step_a_us;
+  return lhs > rhs ? 1 : (lhs < rhs ? -1 : 0);
+}
+
 extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *hip_stream) {
   if (!out) return CHM_ERR_ARG;
   memset(out, 0, sizeof(*out));

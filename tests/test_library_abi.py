@@ -82,6 +82,26 @@ def test_no_cpu_fallback_without_a_device():
     assert e.value.code == B.ERR_HIP
 
 
+def test_objective_comparison_is_exact():
+    """Optimization Problem: (H - t_trans) / t_step, compared without rounding"""
+    from fractions import Fraction
+    rng = np.random.default_rng(3)
+    for _ in range(2000):
+        H = int(rng.integers(1, 2 ** 50))
+        a = {"t_step_us": int(rng.integers(1, 2 ** 40)), "t_trans_us": int(rng.integers(0, 2 ** 50))}
+        b = {"t_step_us": int(rng.integers(1, 2 ** 40)), "t_trans_us": int(rng.integers(0, 2 ** 50))}
+        fa, fb = Fraction(H - a["t_trans_us"], a["t_step_us"]), Fraction(H - b["t_trans_us"], b["t_step_us"])
+        assert B.compare_objective(a, b, H) == (fa > fb) - (fa < fb)
+    # differences far below double precision, and exact ties
+    big = 2 ** 61
+    assert B.compare_objective({"t_step_us": big, "t_trans_us": 0}, {"t_step_us": big + 1, "t_trans_us": 0}, big) == 1
+    assert B.compare_objective({"t_step_us": 3, "t_trans_us": 10}, {"t_step_us": 6, "t_trans_us": 0}, 20) == 0
+    assert B.compare_objective({"t_step_us": 2, "t_trans_us": 40}, {"t_step_us": 1, "t_trans_us": 30}, 20) == 0   # -10 and -10
+    assert B.compare_objective({"t_step_us": 2, "t_trans_us": 50}, {"t_step_us": 1, "t_trans_us": 30}, 20) == -1  # -15 and -10
+    with pytest.raises(B.ChmError):
+        B.compare_objective({"t_step_us": 0, "t_trans_us": 0}, {"t_step_us": 1, "t_trans_us": 0}, 5)
+
+
 def test_replan_argument_checks_need_no_device():
     rp = synth.replan_case(5, 10, 3, 3, [4], 12, (1, 4), (1, 6))
     for key, val in [("L", 0), ("old_pp", 0), ("old_dp", 17), ("dp_min", 0), ("dp_max", 17), ("pp_min", 0), ("pp_max", 33),
