@@ -158,6 +158,70 @@ def bench_score(args, note, B, synth):
     print(json.dumps(out_json))
 
 
+def bench_lists(args, note, B, synth):
+    """config 4: 2^24 seeded random partitions per strategy (L=96, PP=16, DP=2, M=64, one failure, cap chosen
+    for about 30 % infeasible plans).  A step = one chm_search_cuts per strategy over its list of cut
+    positions, with the cost of every entry stored."""
+    import numpy as np
+    import torch
+    sc = synth.config4(mem_cap_mib=synth.CONFIG4_CAP_30PCT)
+    g = B.Scenario(sc)
+    n, chunk = 1 << 24, 1 << 20
+    lists = {}
+    for f in g.families:
+        k = f["stages"] - 1
+        d_cuts = torch.empty((n, k), dtype=torch.uint8, device="cuda")
+        for c0 in range(0, n, chunk):
+            cuts = synth.random_partitions(synth.BASE_SEED + 4, 1000 * f["strategy"] + c0 // chunk, chunk, sc["L"], k)
+            d_cuts[c0:c0 + chunk] = torch.from_numpy(cuts).cuda()
+        lists[f["strategy"]] = d_cuts
+        note("strategy %d: %d partitions ready" % (f["strategy"], n))
+    costs = torch.empty(n, dtype=torch.int64, device="cuda")
+    stream = torch.cuda.Stream()
+    g.set_timing(True)
+    fam_ms = np.zeros(3)
+    feasible = np.zeros(3)
+    with torch.cuda.stream(stream):
+        torch.cuda.synchronize()
+        for _ in range(args.warmup):
+            for st, d_cuts in lists.items():
+                g.search_cuts(st, d_cuts, costs=costs, stream=stream)
+        stream.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            for st, d_cuts in lists.items():
+                rc, best, pos = g.search_cuts(st, d_cuts, costs=costs, stream=stream)
+                tm = g.get_timing()
+                fam_ms[st] += tm["family_ms"][st]
+                feasible[st] = tm["feasible"][st]
+        stream.synchronize()
+        wall = time.perf_counter() - t0
+    fam_ms /= args.steps
+    ms = wall * 1e3 / args.steps
+    ops = np.zeros(3)
+    for f in g.families:
+        fam = dict(f, classes=g.family_classes(f["strategy"]), n_part=n, assign=0,
+                   peers=[p for p, _ in g.reroute_shape()] if f["strategy"] == 2 else [],
+                   R=[r for _, r in g.reroute_shape()] if f["strategy"] == 2 else [],
+                   orphans=[sc["M"]] if f["strategy"] == 2 else [])
+        ops[f["strategy"]] = algorithmic_ops(fam, feasible[f["strategy"]])[0]
+    dom = int(np.argmax(fam_ms))
+    achieved = ops[dom] / (fam_ms[dom] * 1e-3) / 1e12
+    evals = sum(n * (sum(r for _, r in g.reroute_shape()) if f["strategy"] == 2 else 1) for f in g.families)
+    print(json.dumps({"metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
+                      "value": evals / (ms * 1e-3), "unit": "plans/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+                      "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
+                      "data": "synthetic",
+                      "config": {"workload": "config4: L=96 PP=16 DP=2 M=64, 1 failed node, 2^24 random partitions per strategy "
+                                             "(explicit lists), cap %d MiB" % sc["mem_cap_mib"],
+                                 "partitions_per_strategy": n, "plans_scored_per_step": evals, "failed_nodes": sc["failed_nodes"]},
+                      "kernel_ms_per_strategy": [float(x) for x in fam_ms],
+                      "feasible_partitions_per_strategy": [float(x) for x in feasible],
+                      "roofline": {"bound": "alu", "kernel": "list search, strategy %d" % dom, "achieved": achieved,
+                                   "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
+                                   "algorithmic_ops_per_launch": float(ops[dom])}}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -166,7 +230,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=20.0)
     ap.add_argument("--ttb-runs", type=int, default=10)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config5", "replan32", "score2"],
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5", "replan32", "score2"],
                     help="config2 (the 32-card shape) is the benchmark; the others are for profiling; replan32 times "
                          "chm_replan (search over DP/PP degrees) for the 31 nodes that survive in config2")
     ap.add_argument("--transfer-assign", type=int, default=0, choices=[0, 1],
@@ -198,6 +262,8 @@ def main():
         return bench_replan(args, note, B, synth)
     if args.workload == "score2":
         return bench_score(args, note, B, synth)
+    if args.workload == "config4":
+        return bench_lists(args, note, B, synth)
     workloads = {
         "config1": ("config1: L=32 PP=4 DP=2 M=8, 1 failed node", lambda: [synth.config1()]),
         "config2": ("config2: L=48 PP=8 DP=4 M=16, 1 failed node", lambda: [synth.config2()]),

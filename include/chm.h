@@ -162,6 +162,12 @@ int chm_rank_partitions(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts
 int chm_search_ranks(chm_scenario *s, int32_t strategy, const uint64_t *d_part_ranks, uint64_t n,
                      int64_t *d_costs, chm_best *out, uint64_t *position, void *hip_stream);
 
+/* The same for partitions given by their cut positions: d_cuts (device, uint8) holds n rows of
+ * (stages-1) ascending cut positions, as for chm_rank_partitions; a malformed row counts as a partition
+ * that does not fit.  Skips the ranking and unranking of the list, which dominates for deep pipelines. */
+int chm_search_cuts(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts, uint64_t n,
+                    int64_t *d_costs, chm_best *out, uint64_t *position, void *hip_stream);
+
 /* Exhaustive argmin over the strategies in strategy_mask (bit k = strategy k): every
  * partition of every selected family is scored on the device; for data rerouting every
  * reroute vector of every stage that lost nodes is scored (the penalty is a sum of

@@ -16,7 +16,7 @@ OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HI
 INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
-           "chm_search_range", "chm_search_ranks", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
+           "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
            "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
@@ -99,6 +99,7 @@ def lib():
         L.chm_search_best.argtypes = [vp, C.c_uint32, C.POINTER(Best), vp]
         L.chm_search_range.argtypes = [vp, C.c_int32, C.c_uint64, C.c_uint64, C.POINTER(Best), vp]
         L.chm_search_ranks.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, C.POINTER(Best), C.POINTER(C.c_uint64), vp]
+        L.chm_search_cuts.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, C.POINTER(Best), C.POINTER(C.c_uint64), vp]
         L.chm_rank_partitions.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, vp]
         L.chm_decode_plan.argtypes = [vp, C.c_uint64, C.POINTER(Best)]
         L.chm_set_timing.argtypes = [vp, C.c_int32]
@@ -315,6 +316,19 @@ class Scenario:
         cp = C.c_void_p(costs.data_ptr()) if costs is not None else None
         rc = _check(lib().chm_search_ranks(self._h, strategy, C.c_void_p(d_ranks.data_ptr()), n, cp, C.byref(b),
                                            C.byref(pos), _stream_ptr(stream)),
+                    allowed=(ERR_NO_FEASIBLE, ERR_UNRECOVERABLE))
+        return rc, _best_dict(b), int(pos.value)
+
+    def search_cuts(self, strategy, d_cuts, costs=None, stream=None):
+        """chm_search_cuts: argmin over explicit partitions given as an (n, stages-1) uint8 CUDA tensor of cut positions"""
+        import torch
+        b = Best()
+        pos = C.c_uint64()
+        assert d_cuts.is_cuda and d_cuts.dtype == torch.uint8 and d_cuts.is_contiguous() and d_cuts.dim() == 2
+        assert d_cuts.shape[1] == self.family(strategy)["stages"] - 1
+        cp = C.c_void_p(costs.data_ptr()) if costs is not None else None
+        rc = _check(lib().chm_search_cuts(self._h, strategy, C.c_void_p(d_cuts.data_ptr()), d_cuts.shape[0], cp, C.byref(b),
+                                          C.byref(pos), _stream_ptr(stream)),
                     allowed=(ERR_NO_FEASIBLE, ERR_UNRECOVERABLE))
         return rc, _best_dict(b), int(pos.value)
 

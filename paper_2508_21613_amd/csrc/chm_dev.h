@@ -82,6 +82,9 @@ struct SearchLaunch {
   // list mode: partition i of the chunk is ranks[i] (any order, a rank outside the family counts as
   // infeasible) instead of part_first + i; part_first is then ignored
   const uint64_t *ranks;
+  // the same with the partitions given by their cut positions: row i = (stages - 1) ascending bytes (a row
+  // that is not strictly increasing within 1..L-1 counts as infeasible); at most one of ranks / cuts is set
+  const uint8_t *cuts;
   // when set, cost i of the chunk (INT64_MAX if infeasible) is also stored to costs_out[i]
   int64_t *costs_out;
 };

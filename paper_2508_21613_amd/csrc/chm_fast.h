@@ -7,7 +7,8 @@ enum {
   FAST_MAX_P = 8,            // peers per affected stage the specialised sweeps are instantiated for
   FAST_FUSED_R = 4096,       // up to this many reroute vectors (all stages) the sweep runs inside the search kernel
   FAST_SPLIT_R = 1 << 23,    // up to this many per stage the vectors are tabulated and swept by a kernel of their own
-  FAST_SUB = 1 << 18         // partitions per pass of the split and scoring paths (bounds their scratch memory: 38 MB)
+  FAST_SUB = 1 << 18,        // partitions per pass of the split and scoring paths (bounds their scratch memory: 38 MB)
+  LIST_SUB = 1 << 22         // list entries per filter + search pass of explicit lists (scratch: 80 MB)
 };
 
 // One pipeline class in the form the specialised kernels read (all int32).
@@ -62,6 +63,10 @@ struct FastState {
   uint32_t *d_weights = nullptr;            // [partition][affected stage][8] peer stage times
   uint32_t *d_pen = nullptr;                // [partition][4] best penalty per affected stage
   uint64_t *d_rowkey = nullptr;             // [4] (penalty << 32 | row) of the winning partition
+  // scratch of explicit lists, LIST_SUB entries at a time; allocated when first needed
+  void *d_cut_list = nullptr;               // [entry] cut positions of the entries that fit in memory, 16 bytes each
+  uint32_t *d_cut_pos = nullptr;            // [entry] their list positions
+  uint32_t *d_cut_count = nullptr;          // [workgroup region] how many of its slots are filled
 };
 
 // Decides per strategy whether a specialised kernel applies and uploads its tables.

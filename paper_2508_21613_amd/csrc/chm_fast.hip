@@ -335,6 +335,30 @@ __device__ __forceinline__ void unrank_digits(uint64_t rem, int L, int steps, co
   }
 }
 
+// largest peak memory over the nodes of a plan: static + (pipeline length - position) * activations of the
+// most demanding node of every stage (strategy 0: a node holds its stage and its ring successor's)
+template <int SP, int STRAT>
+__device__ __forceinline__ int largest_peak(FamPtr ff, const int (&ms)[SP], const int (&as)[SP]) {
+  int mmax = 0;
+  if (ff->has_act) {
+#pragma unroll
+    for (int j = 0; j < SP; ++j) {
+      const int coef = ff->mem_coef[j];
+      const int st = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
+      const int ac = STRAT == 0 ? as[j] + as[(j + 1) % SP] : as[j];
+      const int m = st + (int)__umul24((uint32_t)ac, (uint32_t)(coef < 0 ? 0 : coef));
+      mmax = imax32(mmax, coef < 0 ? 0 : m);
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < SP; ++j) {
+      const int m = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
+      mmax = imax32(mmax, ff->mem_coef[j] < 0 ? 0 : m);
+    }
+  }
+  return mmax;
+}
+
 struct FastLaunch {
   SearchLaunch s;
   const FastTables *tab;
@@ -345,6 +369,14 @@ struct FastLaunch {
   // partition, the cost without penalties and the peer stage times (null: fused sweep)
   uint64_t *base_out;
   uint32_t *weights_out;
+  // compacted list mode: workgroup b owns slots [b * per_lane * BLOCK, ...) of cut_list / cut_pos, of which the
+  // first cut_count[b] are filled (by k_list_filter, with the list entries that fit in memory).  In round `it`
+  // lane t evaluates slot it * BLOCK + t: the partition whose cut positions are the bytes of cut_list[slot],
+  // reported under list position cut_pos[slot].  Every lane of every wave has work except in a workgroup's
+  // last round (null: other modes)
+  const uint4 *cut_list;
+  const uint32_t *cut_pos;
+  const uint32_t *cut_count;
 };
 
 // Waves per SIMD the register allocator is asked to keep possible: up to 8 stages the kernels fit 96
@@ -362,21 +394,26 @@ k_fast_search(FastLaunch a) {
   const TabPtr tab = as_const(a.tab);
   const FamPtr ff = &tab->fam[STRAT];
   const int L = scn->L;
+  const bool compact = a.cut_list != nullptr;
+  const uint32_t n_slots = compact ? a.cut_count[blockIdx.x] : 0u;       // filled slots of this workgroup's region
+  if (compact && n_slots == 0) return;
   for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], (int)scn->pa[i]);
-  for (int i = threadIdx.x; i < K * DEV_MAX_L; i += BLOCK) BN[i] = scn->binom[1 + i / DEV_MAX_L][i % DEV_MAX_L];
+  if (!compact)                                                 // a compacted list needs no unranking
+    for (int i = threadIdx.x; i < K * DEV_MAX_L; i += BLOCK) BN[i] = scn->binom[1 + i / DEV_MAX_L][i % DEV_MAX_L];
   __syncthreads();
 
   const uint32_t lane_id = blockIdx.x * BLOCK + threadIdx.x;
   const uint64_t run_first = (uint64_t)lane_id * a.per_lane;             // chunk-local
-  const uint32_t run_len = run_first >= a.s.part_count ? 0u
+  const uint32_t run_len = (compact || run_first >= a.s.part_count) ? 0u
                            : (uint32_t)(a.s.part_count - run_first < a.per_lane ? a.s.part_count - run_first : a.per_lane);
+  const uint32_t region = blockIdx.x * a.per_lane * BLOCK;               // compact mode: first slot of this workgroup
 
   // cut positions c[1..K]; c[0] = 0 and c[SP] = L are constants
   int c[SP + 1];
   c[0] = 0;
   c[SP] = L;
   bool listed_ok = true;
-  {
+  if (!compact) {
     uint64_t rem = run_len ? a.s.part_first + run_first : 0;   // idle lanes walk from rank 0: always valid cuts
     if (a.s.ranks != nullptr && run_len) {                       // list mode (one partition per lane)
       rem = a.s.ranks[run_first];
@@ -389,10 +426,23 @@ k_fast_search(FastLaunch a) {
 
   const int cap = (int)scn->cap;
   uint64_t best_cost = ~0ull;
-  uint32_t best_it = 0;
+  uint64_t best_pos = 0;        // output position (chunk-local partition index or list position) of the lane's best
   uint32_t n_fit = 0;           // wave-uniform count of partitions that pass the memory filter
 
   for (uint32_t it = 0; it < a.per_lane; ++it) {
+    bool live = it < run_len;             // this lane has a partition in this round
+    uint64_t pos = run_first + it;        // where its result is reported
+    if (compact) {
+      if (it * BLOCK >= n_slots) break;   // uniform: the region is used up
+      const uint32_t slot = it * BLOCK + threadIdx.x;
+      live = slot < n_slots;
+      // lanes past the end take the first partition (cuts 1..K): always valid
+      const uint4 packed = live ? a.cut_list[region + slot] : make_uint4(0x04030201u, 0x08070605u, 0x0c0b0a09u, 0x000f0e0du);
+      const uint32_t words[4] = {packed.x, packed.y, packed.z, packed.w};
+#pragma unroll
+      for (int i = 1; i <= K; ++i) c[i] = (int)((words[(i - 1) >> 2] >> (8 * ((i - 1) & 3))) & 0xffu);
+      pos = live ? a.cut_pos[region + slot] : 0;
+    }
     // ---- stage sums from the LDS prefix table
     int fs[SP], bs[SP], ms[SP], as[SP];
     {
@@ -408,25 +458,8 @@ k_fast_search(FastLaunch a) {
       }
     }
     // ---- memory filter
-    int mmax = 0;
-    if (ff->has_act) {
-#pragma unroll
-      for (int j = 0; j < SP; ++j) {
-        // peak = static + (pipeline length - position) * activations of the most demanding node of stage j
-        const int coef = ff->mem_coef[j];
-        const int st = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
-        const int ac = STRAT == 0 ? as[j] + as[(j + 1) % SP] : as[j];
-        const int m = st + (int)__umul24((uint32_t)ac, (uint32_t)(coef < 0 ? 0 : coef));
-        mmax = imax32(mmax, coef < 0 ? 0 : m);
-      }
-    } else {
-#pragma unroll
-      for (int j = 0; j < SP; ++j) {
-        const int m = STRAT == 0 ? ms[j] + ms[(j + 1) % SP] : ms[j];
-        mmax = imax32(mmax, ff->mem_coef[j] < 0 ? 0 : m);
-      }
-    }
-    const bool ok = (mmax <= cap) && (it < run_len) && listed_ok;
+    const int mmax = largest_peak<SP, STRAT>(ff, ms, as);
+    const bool ok = (mmax <= cap) && live && listed_ok;
     uint64_t cost = (uint64_t)CHM_INF_COST;
     const uint64_t ok_mask = __builtin_amdgcn_ballot_w64(ok);
     n_fit += (uint32_t)__popcll(ok_mask);
@@ -615,7 +648,7 @@ k_fast_search(FastLaunch a) {
         }
       }
       cost = (uint64_t)scn->K * (uint32_t)t_step + (uint64_t)scn->reconf[STRAT] + (uint64_t)scn->xfer * (uint32_t)missing;
-      if (ok && cost < best_cost) { best_cost = cost; best_it = it; }
+      if (ok && cost < best_cost) { best_cost = cost; best_pos = pos; }
       if (STRAT == 2 && a.base_out != nullptr && ok) a.base_out[run_first + it] = cost;
     }
     if (STRAT == 2 && a.base_out != nullptr && !ok && it < run_len) a.base_out[run_first + it] = ~0ull;
@@ -623,11 +656,11 @@ k_fast_search(FastLaunch a) {
       // per_lane == 1: the store is coalesced as it is; longer runs go through an LDS tile
       // (laid out in output order) and are written out together after the loop
       const int64_t v = ok ? (int64_t)cost : CHM_INF_COST;
-      if (a.per_lane == 1) { if (it < run_len) a.s.costs_out[run_first] = v; }
+      if (a.per_lane == 1 || compact) { if (live) a.s.costs_out[pos] = v; }
       else cost_tile[threadIdx.x * a.per_lane + it] = v;
     }
     // ---- next partition in rank order: bump the lowest cut that has room, reset those below
-    {
+    if (!compact) {
       bool done = false;
 #pragma unroll
       for (int i = 1; i <= K; ++i) {
@@ -638,7 +671,7 @@ k_fast_search(FastLaunch a) {
     }
   }
 
-  if (a.s.costs_out != nullptr && a.per_lane > 1) {
+  if (a.s.costs_out != nullptr && a.per_lane > 1 && !compact) {
     __syncthreads();
     const uint64_t block_first = (uint64_t)blockIdx.x * BLOCK * a.per_lane;
     const uint32_t n_tile = BLOCK * a.per_lane;
@@ -646,7 +679,7 @@ k_fast_search(FastLaunch a) {
       if (block_first + i < a.s.part_count) a.s.costs_out[block_first + i] = cost_tile[i];
   }
   uint64_t key = best_cost == ~0ull ? CHM_KEY_NONE
-                                    : ((best_cost << a.s.idx_bits) | (run_first + best_it));
+                                    : ((best_cost << a.s.idx_bits) | best_pos);
   if (STRAT == 2 && a.base_out != nullptr) key = CHM_KEY_NONE;   // the combine kernel takes the argmin
   key = wave_min(key);
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -662,6 +695,106 @@ k_fast_search(FastLaunch a) {
     if (fit) atomicAdd((unsigned long long *)a.s.feasible + slot, (unsigned long long)fit);
     if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)a.s.result + slot, (unsigned long long)k);
   }
+}
+
+// ---------------------------------------------------------------------------------------
+// explicit lists: memory filter and compaction
+// ---------------------------------------------------------------------------------------
+// One lane per list entry: cut positions (given, or unranked), stage memory sums, memory filter.  An entry
+// that does not fit (or is malformed) gets its cost (infeasible) right away; the others are appended to the
+// workgroup's own region of a compact list as (cut positions packed into 16 bytes, list position).  Slots are
+// handed out through a counter in LDS: atomics of many workgroups on one global counter would serialise (about
+// 10 ns each).  The search kernel then runs over every region with all lanes busy.
+constexpr int FILTER_TILES = 16;  // tiles of BLOCK entries per workgroup = rounds of the search kernel per region
+
+struct ListFilter {
+  const DevScenario *scn;
+  const FastTables *tab;
+  const uint64_t *ranks;        // list entries of this pass, as partition ranks, or (ranks null)
+  const uint8_t *cuts;          // as rows of stages - 1 cut positions
+  uint32_t n;                   // entries in this pass
+  uint32_t pos_base;            // list position (chunk-local) of entry 0 of this pass
+  int64_t *costs_out;           // chunk-local cost array (nullable)
+  uint4 *cut_list;              // [workgroup][FILTER_TILES * BLOCK]
+  uint32_t *cut_pos;            // likewise
+  uint32_t *cut_count;          // [workgroup] filled slots
+};
+
+template <int SP, int STRAT>
+__global__ void __launch_bounds__(BLOCK) k_list_filter(ListFilter a) {
+  constexpr int K = SP - 1;
+  __shared__ int4 T[DEV_MAX_L + 1];
+  __shared__ uint64_t BN[(K > 0 ? K : 1) * DEV_MAX_L];
+  __shared__ uint32_t filled;
+  const ScnPtr scn = as_const(a.scn);
+  const FamPtr ff = &as_const(a.tab)->fam[STRAT];
+  const int L = scn->L;
+  for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], (int)scn->pa[i]);
+  if (a.cuts == nullptr)
+    for (int i = threadIdx.x; i < K * DEV_MAX_L; i += BLOCK) BN[i] = scn->binom[1 + i / DEV_MAX_L][i % DEV_MAX_L];
+  if (threadIdx.x == 0) filled = 0;
+  __syncthreads();
+  const uint32_t region = blockIdx.x * (FILTER_TILES * BLOCK);
+  for (int tile = 0; tile < FILTER_TILES; ++tile) {
+    const uint32_t gid = region + tile * BLOCK + threadIdx.x;
+    if (gid - threadIdx.x >= a.n) break;                        // uniform: this tile and the next ones are empty
+    const bool live = gid < a.n;
+    int c[SP + 1];
+    c[0] = 0;
+    c[SP] = L;
+    bool valid = live;
+    if (a.cuts != nullptr) {
+      // explicit cut positions; a row that does not increase strictly within 1..L-1 is replaced by 1..K
+      const uint8_t *row = a.cuts + (size_t)(live ? gid : 0) * K;
+      int prev = 0;
+#pragma unroll
+      for (int i = 1; i <= K; ++i) {
+        c[i] = row[i - 1];
+        valid = valid && c[i] > prev && c[i] <= L - 1;
+        prev = c[i];
+      }
+      if (!valid) {
+#pragma unroll
+        for (int i = 1; i <= K; ++i) c[i] = i;
+      }
+    } else {
+      uint64_t rem = live ? a.ranks[gid] : 0;
+      valid = live && rem < scn->fam[STRAT].n_part;
+      if (!valid) rem = 0;
+      unrank_digits<K>(rem, L, (L - 1) <= 64 ? 3 : 4, BN, c);
+    }
+    int ms[SP], as[SP];
+    {
+      int lo_m = 0, lo_a = 0;
+#pragma unroll
+      for (int j = 0; j < SP; ++j) {
+        const int4 hi = T[c[j + 1]];
+        ms[j] = hi.z - lo_m;
+        as[j] = hi.w - lo_a;
+        lo_m = hi.z;
+        lo_a = hi.w;
+      }
+    }
+    const bool ok = valid && largest_peak<SP, STRAT>(ff, ms, as) <= (int)scn->cap;
+    if (live && !ok && a.costs_out != nullptr) a.costs_out[a.pos_base + gid] = CHM_INF_COST;
+    const uint64_t mask = __builtin_amdgcn_ballot_w64(ok);
+    if (mask != 0) {
+      const int lane = threadIdx.x & 63;
+      uint32_t base = 0;
+      if (lane == 0) base = atomicAdd(&filled, (uint32_t)__popcll(mask));
+      base = __shfl(base, 0, 64);
+      if (ok) {
+        const uint32_t slot = region + base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+        uint32_t words[4] = {0, 0, 0, 0};
+#pragma unroll
+        for (int i = 1; i <= K; ++i) words[(i - 1) >> 2] |= (uint32_t)c[i] << (8 * ((i - 1) & 3));
+        a.cut_list[slot] = make_uint4(words[0], words[1], words[2], words[3]);
+        a.cut_pos[slot] = a.pos_base + gid;
+      }
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) a.cut_count[blockIdx.x] = filled;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -923,6 +1056,20 @@ int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, uint32_t tile
 #undef CHM_CASE
 }
 
+template <int STRAT>
+int filter_by_stages(int sp, const ListFilter &a, uint32_t blocks, hipStream_t st) {
+#define CHM_CASE(SPV)                                                                         \
+  case SPV:                                                                                   \
+    hipLaunchKernelGGL((k_list_filter<SPV, STRAT>), dim3(blocks), dim3(BLOCK), 0, st, a);      \
+    return 0;
+  switch (sp) {
+    CHM_CASE(2) CHM_CASE(3) CHM_CASE(4) CHM_CASE(5) CHM_CASE(6) CHM_CASE(7) CHM_CASE(8)
+    CHM_CASE(9) CHM_CASE(10) CHM_CASE(11) CHM_CASE(12) CHM_CASE(13) CHM_CASE(14) CHM_CASE(15) CHM_CASE(16)
+    default: return 1;
+  }
+#undef CHM_CASE
+}
+
 bool stages_covered(int sp) { return sp >= 2 && sp <= 16; }
 
 }  // namespace
@@ -1100,10 +1247,61 @@ bool ensure_scratch(FastState *f) {
   return ok;
 }
 
+bool ensure_list_scratch(FastState *f) {
+  if (f->d_cut_list && f->d_cut_pos && f->d_cut_count) return true;
+  bool ok = true;
+  if (!f->d_cut_list) ok = ok && hipMalloc(&f->d_cut_list, (size_t)LIST_SUB * sizeof(uint4)) == hipSuccess;
+  if (!f->d_cut_pos) ok = ok && hipMalloc((void **)&f->d_cut_pos, (size_t)LIST_SUB * sizeof(uint32_t)) == hipSuccess;
+  if (!f->d_cut_count) ok = ok && hipMalloc((void **)&f->d_cut_count, (size_t)(LIST_SUB / (BLOCK * FILTER_TILES)) * sizeof(uint32_t)) == hipSuccess;
+  return ok;
+}
+
+// Explicit list of partition ranks: per pass of LIST_SUB entries, filter + compaction, then the search kernel
+// over the entries that fit.
+int launch_list(FastState *f, const DevScenario &h, const SearchLaunch &a, hipStream_t st) {
+  if (!ensure_list_scratch(f)) return -1;
+  const int sp = h.fam[a.strategy].stages;
+  for (uint32_t done = 0; done < a.part_count; done += LIST_SUB) {
+    const uint32_t n = std::min<uint32_t>(LIST_SUB, a.part_count - done);
+    const uint32_t blocks = (n + BLOCK * FILTER_TILES - 1) / (BLOCK * FILTER_TILES);   // one workgroup per region, both kernels
+    ListFilter lf;
+    lf.scn = a.scn; lf.tab = f->d_tables; lf.n = n; lf.pos_base = done;
+    lf.ranks = a.ranks ? a.ranks + done : nullptr;
+    lf.cuts = a.cuts ? a.cuts + (size_t)done * (size_t)(sp - 1) : nullptr;
+    lf.costs_out = a.costs_out; lf.cut_list = (uint4 *)f->d_cut_list; lf.cut_pos = f->d_cut_pos; lf.cut_count = f->d_cut_count;
+    int rc = a.strategy == 0 ? filter_by_stages<0>(sp, lf, blocks, st)
+             : a.strategy == 1 ? filter_by_stages<1>(sp, lf, blocks, st) : filter_by_stages<2>(sp, lf, blocks, st);
+    if (rc) return rc;
+    FastLaunch fl;
+    fl.s = a;
+    fl.s.ranks = nullptr;
+    fl.s.cuts = nullptr;
+    fl.s.part_first = 0;
+    fl.s.part_count = n;
+    fl.tab = f->d_tables;
+    fl.vecs = f->d_vecs;
+    fl.runs = f->d_runs;
+    fl.per_lane = FILTER_TILES;           // rounds per region
+    fl.base_out = nullptr;
+    fl.weights_out = nullptr;
+    fl.cut_list = (const uint4 *)f->d_cut_list;
+    fl.cut_pos = f->d_cut_pos;
+    fl.cut_count = f->d_cut_count;
+    rc = a.strategy == 0 ? launch_by_stages<0>(sp, fl, blocks, 0, st)
+         : a.strategy == 1 ? launch_by_stages<1>(sp, fl, blocks, 0, st) : launch_by_stages<2>(sp, fl, blocks, 0, st);
+    if (rc) return rc;
+    if (hipGetLastError() != hipSuccess) return -1;
+  }
+  return 0;
+}
+
 int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uint64_t *base_out, uint32_t *weights_out,
                   hipStream_t st) {
   FastLaunch fl;
   fl.s = a;
+  fl.cut_list = nullptr;
+  fl.cut_pos = nullptr;
+  fl.cut_count = nullptr;
   fl.tab = f->d_tables;
   fl.vecs = f->d_vecs;
   fl.runs = f->d_runs;
@@ -1137,8 +1335,9 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
   if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return 1;
   if (a.part_count == 0) return 0;
   hipStream_t st = (hipStream_t)stream;
-  if (!(a.strategy == 2 && f->split)) return launch_search(f, h, a, nullptr, nullptr, st);
-  if (a.ranks != nullptr || a.costs_out != nullptr) return 1;   // the generic kernel handles lists for this shape
+  const bool list = a.ranks != nullptr || a.cuts != nullptr;
+  if (!(a.strategy == 2 && f->split)) return list ? launch_list(f, h, a, st) : launch_search(f, h, a, nullptr, nullptr, st);
+  if (list || a.costs_out != nullptr) return 1;   // the generic kernel handles lists for this shape
   if (!ensure_scratch(f)) return -1;
   // split rerouting path, FAST_SUB partitions per pass: base costs and peer stage times, then one
   // sweep per affected stage over (partition blocks x row chunks), then the combine / argmin
@@ -1289,6 +1488,10 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
 }
 
 void fast_release(FastState *f) {
+  if (f->d_cut_count) (void)hipFree(f->d_cut_count);
+  if (f->d_cut_pos) (void)hipFree(f->d_cut_pos);
+  if (f->d_cut_list) (void)hipFree(f->d_cut_list);
+  f->d_cut_count = nullptr; f->d_cut_pos = nullptr; f->d_cut_list = nullptr;
   if (f->d_rowkey) (void)hipFree(f->d_rowkey);
   if (f->d_pen) (void)hipFree(f->d_pen);
   if (f->d_weights) (void)hipFree(f->d_weights);

@@ -388,7 +388,8 @@ void nothing_found(chm_best *out) {
 
 // a range of partition ranks [first, first+count) of one strategy, or (ranks != null) a list of
 // `count` partition ranks in device memory; costs (nullable, device) receives one cost per entry
-struct Job { int strategy; uint64_t first, count; const uint64_t *ranks; int64_t *costs; };
+// (cuts != null: the list holds rows of cut positions instead)
+struct Job { int strategy; uint64_t first, count; const uint64_t *ranks; int64_t *costs; const uint8_t *cuts = nullptr; };
 
 // Runs the argmin over the given partition ranges (ascending plan index order).
 // With out == null the kernels are only launched (asynchronous scoring into the jobs' cost buffers).
@@ -399,7 +400,7 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
   const uint64_t chunk = 1ull << s->idx_bits;
   for (const Job &j : jobs)
     for (uint64_t done = 0; done < j.count; done += chunk)
-      slots.push_back({j.strategy, (j.ranks ? 0 : j.first) + done, s->idx_bits});
+      slots.push_back({j.strategy, ((j.ranks || j.cuts) ? 0 : j.first) + done, s->idx_bits});
   if (slots.empty()) {
     if (!out) return CHM_OK;
     nothing_found(out);
@@ -429,6 +430,7 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
       a.slot_mask = ways - 1;
       a.slot_stride = stride;
       a.ranks = j.ranks ? j.ranks + done : nullptr;
+      a.cuts = j.cuts ? j.cuts + (size_t)done * (size_t)(s->h.fam[j.strategy].stages - 1) : nullptr;
       a.costs_out = j.costs ? j.costs + done : nullptr;
       int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
       if (rc > 0) rc = chmk_search(a, s->smax, st);
@@ -461,10 +463,10 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
   int64_t best_cost = CHM_INFEASIBLE;
   int best_strategy = -1;
   uint64_t best_part = 0;
-  const uint64_t *best_list = nullptr;
-  std::vector<const uint64_t *> slot_list;
+  const Job *best_job = nullptr;
+  std::vector<const Job *> slot_job;
   for (const Job &j : jobs)
-    for (uint64_t done = 0; done < j.count; done += chunk) slot_list.push_back(j.ranks);
+    for (uint64_t done = 0; done < j.count; done += chunk) slot_job.push_back(&j);
   for (size_t i = 0; i < slots.size(); ++i) {
     uint64_t key = CHM_KEY_NONE;
     for (uint32_t w = 0; w < ways; ++w) key = std::min(key, s->h_pinned[i * chunk_words + (size_t)w * stride]);
@@ -474,14 +476,20 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
       best_cost = cost;
       best_strategy = slots[i].strategy;
       best_part = slots[i].part_first + (key & ((1ull << slots[i].idx_bits) - 1));
-      best_list = slot_list[i];
+      best_job = slot_job[i];
     }
   }
   if (best_strategy < 0) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
-  if (best_list) {
-    // list job: best_part is a position in the caller's list; fetch the partition rank behind it
+  if (best_job->ranks || best_job->cuts) {
+    // list job: best_part is a position in the caller's list; fetch (or compute, on the device) the
+    // partition rank behind it
     if (position) *position = best_part;
-    HIP_TRY(hipMemcpyAsync(s->h_pinned, best_list + best_part, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    const uint64_t *d_rank = best_job->ranks ? best_job->ranks + best_part : s->d_xfer;
+    if (best_job->cuts) {
+      const int k = s->h.fam[best_strategy].stages - 1;
+      if (chmk_rank_cuts(s->d_scn, k, best_job->cuts + (size_t)best_part * (size_t)k, 1, s->d_xfer, st)) return CHM_ERR_HIP;
+    }
+    HIP_TRY(hipMemcpyAsync(s->h_pinned, d_rank, sizeof(uint64_t), hipMemcpyDeviceToHost, st));
     HIP_TRY(hipStreamSynchronize(st));
     best_part = s->h_pinned[0];
   }
@@ -652,6 +660,21 @@ extern "C" int chm_search_ranks(chm_scenario *s, int32_t strategy, const uint64_
   if (position) *position = UINT64_MAX;
   std::vector<Job> jobs;
   if (n) jobs.push_back({strategy, 0, n, d_part_ranks, d_costs});
+  return run_search(s, jobs, out, position, (hipStream_t)hip_stream);
+}
+
+extern "C" int chm_search_cuts(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts, uint64_t n,
+                               int64_t *d_costs, chm_best *out, uint64_t *position, void *hip_stream) {
+  if (!s || !out || strategy < 0 || strategy > 2 || (n && !d_cuts)) return CHM_ERR_ARG;
+  const chm_family *f = find_family(s, strategy);
+  if (!f) { nothing_found(out); return CHM_ERR_UNRECOVERABLE; }
+  if (position) *position = UINT64_MAX;
+  std::vector<Job> jobs;
+  if (n) {
+    Job j{strategy, 0, n, nullptr, d_costs};
+    j.cuts = d_cuts;
+    jobs.push_back(j);
+  }
   return run_search(s, jobs, out, position, (hipStream_t)hip_stream);
 }
 

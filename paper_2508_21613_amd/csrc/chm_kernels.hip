@@ -430,11 +430,28 @@ __global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
   bool fits = false;
   if (gid < a.part_count) {
     Cuts<SMAX> cuts{cut_cols, (int)threadIdx.x};
-    const uint64_t part = a.ranks ? a.ranks[gid] : a.part_first + gid;
     int64_t t_step = 0, reconf = 0;
-    if (part < fam.n_part) {
-      unrank_partition<SMAX>(scn, fam.stages - 1, part, cuts);
-      fits = eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf);
+    if (a.cuts != nullptr) {
+      // explicit cut positions: copy them into the lane's column, checking that they increase within 1..L-1
+      const int k = fam.stages - 1;
+      const uint8_t *row = a.cuts + (size_t)gid * (size_t)k;
+      bool valid = true;
+      int prev = 0;
+      cuts.set(0, 0);
+      cuts.set(k + 1, scn->L);
+      for (int i = 1; i <= k; ++i) {
+        const int ci = row[i - 1];
+        valid = valid && ci > prev && ci <= scn->L - 1;
+        cuts.set(i, ci);
+        prev = ci;
+      }
+      if (valid) fits = eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf);
+    } else {
+      const uint64_t part = a.ranks ? a.ranks[gid] : a.part_first + gid;
+      if (part < fam.n_part) {
+        unrank_partition<SMAX>(scn, fam.stages - 1, part, cuts);
+        fits = eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf);
+      }
     }
     if (a.costs_out && !fits) a.costs_out[gid] = CHM_INF_COST;
     if (fits) {

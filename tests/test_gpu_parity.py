@@ -487,6 +487,10 @@ def test_rank_partitions_and_search_over_explicit_lists(B):
             assert rc == 0 and pos == int(np.argmin(want)) and best["cost"] == int(want.min())
             rc_o, best_o, _ = o.search_range(f["strategy"], int(want_ranks[pos]), 1)
             assert same_plan(best, best_o)
+            # the same list handed over as cut positions
+            costs2 = torch.empty(len(want), dtype=torch.int64, device="cuda")
+            rc2, best2, pos2 = g.search_cuts(f["strategy"], d_cuts[:len(want)].contiguous(), costs=costs2)
+            assert (rc2, pos2) == (rc, pos) and same_plan(best2, best) and torch.equal(costs2, costs)
     # malformed rows and ranks outside the family
     sc = synth.small_random(2002, L=8, PP=4, DP=2, M=5, n_failed=1, hetero=False)
     g = B.Scenario(sc)
@@ -497,6 +501,16 @@ def test_rank_partitions_and_search_over_explicit_lists(B):
     assert (r[:3] == np.uint64(2 ** 64 - 1)).all() and r[3] == 0
     rc, best, pos = g.search_ranks(f["strategy"], torch.tensor([-1, -1], dtype=torch.int64, device="cuda"))
     assert rc == B.ERR_NO_FEASIBLE and best["cost"] == B.INFEASIBLE
+    costs = torch.empty(4, dtype=torch.int64, device="cuda")
+    rc, best, pos = g.search_cuts(f["strategy"], bad, costs=costs)          # only the last row is a partition
+    want = O.Scenario(sc).score_ranks(f["strategy"], [0]) if f["n_reroute"] == 1 else None
+    got = costs.cpu().numpy()
+    assert (got[:3] == B.INFEASIBLE).all()
+    if got[3] == B.INFEASIBLE:
+        assert rc == B.ERR_NO_FEASIBLE
+    else:
+        assert rc == 0 and pos == 3 and best["cuts"] == [1, 2, 3] and best["cost"] == got[3]
+        assert want is None or got[3] == want[0]
 
 
 def test_full_size_config4_explicit_batch(B):
@@ -532,6 +546,15 @@ def test_full_size_config4_explicit_batch(B):
         # the plain scoring entry point gives the same numbers
         again = g.score_ranks(strategy, d_ranks[:100000].contiguous())
         assert torch.equal(again, costs[:100000])
+        # and so does the list handed over as cut positions (first 2^22 entries)
+        m = 1 << 22
+        d_cuts = torch.cat([torch.from_numpy(synth.random_partitions(synth.BASE_SEED + 4, 1000 * strategy + c0 // chunk, chunk, 96, k)).cuda()
+                            for c0 in range(0, m, chunk)])
+        costs2 = torch.empty(m, dtype=torch.int64, device="cuda")
+        rc2, best2, pos2 = g.search_cuts(strategy, d_cuts, costs=costs2)
+        assert torch.equal(costs2, costs[:m])
+        if not (h[:m] == B.INFEASIBLE).all():
+            assert rc2 == 0 and pos2 == int(np.argmin(h[:m])) and best2["cost"] == int(h[:m].min())
 
 
 def test_full_size_search_config3_and_config5(B):
