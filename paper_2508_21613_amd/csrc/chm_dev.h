@@ -103,10 +103,9 @@ int chmk_rank_cuts(const DevScenario *d_scn, int k, const uint8_t *d_cuts, uint6
 int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank,
                         uint64_t *d_out, int32_t smax, void *stream);
 
-// step time and transition time of one plan into d_out[0], d_out[1] (64-bit evaluation, one lane);
-// rr_ranks[a] = reroute rank of affected stage a (host array of DEV_MAX_AFF)
-int chmk_plan_terms(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy, uint64_t part_rank,
-                    const uint64_t *rr_ranks, int64_t *d_out, int32_t smax, void *stream);
+// transition time (restart + weight transfer) of one plan into d_out[0], -1 when it does not fit (one lane)
+int chmk_plan_transition(const DevScenario *d_scn, int32_t strategy, uint64_t part_rank, int64_t *d_out, int32_t smax,
+                         void *stream);
 // migration scheme of one pipeline (n survivors, host[i] = fault-free stage of survivor i) for one
 // partition of strategy 1: new stage per survivor to d_stage_of_node[0..n), total MiB to *d_fetch_mib
 int chmk_transfer_plan(const DevScenario *d_scn, uint64_t part_rank, int32_t n, const uint8_t *host,

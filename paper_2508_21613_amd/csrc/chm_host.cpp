@@ -503,12 +503,14 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
     for (int a = 0; a < s->h.n_aff; ++a) rr[a] = s->h_pinned[a];
   }
   fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
-  // the winner's step time and transition time, re-evaluated on the device
-  if (chmk_plan_terms(s->d_scn, s->d_comp, best_strategy, best_part, rr, (int64_t *)s->d_xfer, s->smax, st)) return CHM_ERR_HIP;
-  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_xfer, 2 * sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  // the winner's transition time, from the device; its step time follows from cost = horizon x step + transition
+  if (chmk_plan_transition(s->d_scn, best_strategy, best_part, (int64_t *)s->d_xfer, s->smax, st)) return CHM_ERR_HIP;
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_xfer, sizeof(int64_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
-  out->t_step_us = (int64_t)s->h_pinned[0];
-  out->t_trans_us = (int64_t)s->h_pinned[1];
+  const int64_t t_trans = (int64_t)s->h_pinned[0];
+  if (t_trans < 0 || t_trans > best_cost || (best_cost - t_trans) % s->h.K != 0) return CHM_ERR_HIP;   // cannot happen
+  out->t_trans_us = t_trans;
+  out->t_step_us = (best_cost - t_trans) / s->h.K;
   return CHM_OK;
 }
 

@@ -162,7 +162,9 @@ __device__ __forceinline__ int comm_rounds(const DevScenario *scn, const DevFami
 
 // Everything of a plan's cost except the rerouting penalty.  Returns false when the plan
 // does not fit in memory.
-template <int SMAX>
+// WITH_TIME = false leaves the pipeline recurrences out (t_step_out is then meaningless): only the memory
+// filter and the transition time.
+template <int SMAX, bool WITH_TIME = true>
 __device__ __forceinline__ bool eval_base(const DevScenario *scn, const DevFamily &fam, Cuts<SMAX> cuts,
                                           int64_t *t_step_out, int64_t *reconf_out) {
   const int SP = fam.stages;
@@ -216,11 +218,13 @@ __device__ __forceinline__ bool eval_base(const DevScenario *scn, const DevFamil
       }
     }
     if (fam.strategy == 1 && scn->assign) miss = scn->pw[scn->L] - best_overlap<SMAX>(scn, cls, cuts);
-    const int64_t T = makespan_generic<SMAX>(F, B, cls.n, cls.M) + (int64_t)(cls.n - 1) * scn->comm;
-    t_step = imax(t_step, T);
+    if (WITH_TIME) {
+      const int64_t T = makespan_generic<SMAX>(F, B, cls.n, cls.M) + (int64_t)(cls.n - 1) * scn->comm;
+      t_step = imax(t_step, T);
+    }
     missing = imax(missing, miss);
   }
-  if (scn->allreduce > 0) t_step += scn->allreduce * (int64_t)comm_rounds<SMAX>(scn, fam, cuts);
+  if (WITH_TIME && scn->allreduce > 0) t_step += scn->allreduce * (int64_t)comm_rounds<SMAX>(scn, fam, cuts);
   *t_step_out = t_step;
   *reconf_out = scn->reconf[fam.strategy] + scn->xfer * missing;
   return true;
@@ -495,7 +499,6 @@ __global__ void __launch_bounds__(BLOCK) k_reroute_winner(const DevScenario *scn
 // cell: a step that changes neither index pairs node i-1 with stage j-1.  Nodes left unpaired take
 // the stages left over, in ascending order (they hold nothing of them either way).
 struct SurvivorList { int32_t n; uint8_t host[DEV_MAX_S]; };
-struct PlanRanks { uint64_t r[DEV_MAX_AFF]; };      // reroute rank per affected stage
 
 __global__ void __launch_bounds__(64) k_transfer_plan(const DevScenario *scn, uint64_t part_rank, SurvivorList sv,
                                                       uint8_t *stage_of_node, int64_t *fetch_mib) {
@@ -542,26 +545,18 @@ __global__ void __launch_bounds__(64) k_transfer_plan(const DevScenario *scn, ui
   *fetch_mib = total;
 }
 
-// step time and transition time of ONE plan (the winner of a search), by the generic 64-bit evaluation:
-// out[0] = t_step, out[1] = transition time; both 0 when the plan does not fit
+// transition time of ONE plan (the winner of a search): out[0] = restart + weight transfer, -1 when the plan
+// does not fit.  One lane; no pipeline recurrence (the host takes the step time from cost = horizon x step +
+// transition).
 template <int SMAX>
-__global__ void __launch_bounds__(BLOCK) k_plan_terms(const DevScenario *scn, const uint64_t *comp, int strategy,
-                                                      uint64_t part_rank, PlanRanks rr, int64_t *out) {
+__global__ void __launch_bounds__(BLOCK) k_plan_transition(const DevScenario *scn, int strategy, uint64_t part_rank, int64_t *out) {
   __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
   if (threadIdx.x != 0 || blockIdx.x != 0) return;
   const DevFamily &fam = scn->fam[strategy];
   Cuts<SMAX> cuts{cut_cols, 0};
   unrank_partition<SMAX>(scn, fam.stages - 1, part_rank, cuts);
   int64_t t_step = 0, reconf = 0;
-  if (eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf)) {
-    if (strategy == 2)
-      for (int a = 0; a < scn->n_aff; ++a) t_step += penalty_of_rank<SMAX>(scn, comp, cuts, a, rr.r[a]);
-  } else {
-    t_step = 0;
-    reconf = 0;
-  }
-  out[0] = t_step;
-  out[1] = reconf;
+  out[0] = eval_base<SMAX, false>(scn, fam, cuts, &t_step, &reconf) ? reconf : -1;
 }
 
 // partition rank of explicit cut positions (inverse of unrank_partition); cuts[n][k] row-major.
@@ -657,14 +652,11 @@ int chmk_transfer_plan(const DevScenario *d_scn, uint64_t part_rank, int32_t n, 
   return (int)hipGetLastError();
 }
 
-int chmk_plan_terms(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy, uint64_t part_rank,
-                    const uint64_t *rr_ranks, int64_t *d_out, int32_t smax, void *stream) {
-  PlanRanks rr;
-  for (int a = 0; a < DEV_MAX_AFF; ++a) rr.r[a] = rr_ranks[a];
+int chmk_plan_transition(const DevScenario *d_scn, int32_t strategy, uint64_t part_rank, int64_t *d_out, int32_t smax,
+                         void *stream) {
   return dispatch_smax(smax, [&](auto tag) {
     constexpr int SMAX = decltype(tag)::value;
-    hipLaunchKernelGGL(k_plan_terms<SMAX>, dim3(1), dim3(BLOCK), 0, (hipStream_t)stream, d_scn, d_comp, strategy, part_rank,
-                       rr, d_out);
+    hipLaunchKernelGGL(k_plan_transition<SMAX>, dim3(1), dim3(BLOCK), 0, (hipStream_t)stream, d_scn, strategy, part_rank, d_out);
     return (int)hipGetLastError();
   });
 }
