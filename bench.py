@@ -239,6 +239,8 @@ def main():
     ap.add_argument("--plan-cache", default=None,
                     help="write the best plan of every scenario of the workload to this file, one JSON object per "
                          "line (the cache of pre-computed plans the Planner keeps for possible failures)")
+    ap.add_argument("--filter-compaction", type=int, default=-1, choices=[-1, 0, 1],
+                    help="chm_set_filter_compaction mode of the search workloads: -1 chosen by the library per strategy, 0 off, 1 on")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for scaling the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -299,6 +301,7 @@ def main():
         return fams
 
     work = [family_work(g, sc) for g, sc in zip(handles, scenarios)]
+    fit_share = [g.set_filter_compaction(args.filter_compaction) for g in handles][0]
 
     if args.copy_calibration:
         copy_calibration()
@@ -397,6 +400,7 @@ def main():
                      "algorithmic_ops_per_feasible_partition": ops_light + ops_heavy,
                      "algorithmic_ops_per_infeasible_partition": ops_light},
         "feasible_partitions_per_strategy": [float(x) for x in feasible],
+        "filter_compaction": {"mode": args.filter_compaction, "sampled_fit_share": fit_share},
     }
 
     if not args.no_cpu_baseline:

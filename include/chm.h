@@ -174,7 +174,9 @@ int chm_search_cuts(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts, ui
  * independent per-stage terms, so stages are swept one after the other).  Ties go to the
  * lowest plan index.  Synchronises hip_stream before returning.  Errors:
  * CHM_ERR_UNRECOVERABLE (mask selects no existing family), CHM_ERR_NO_FEASIBLE (out is
- * filled with index UINT64_MAX, cost CHM_INFEASIBLE), CHM_ERR_ARG, CHM_ERR_HIP. */
+ * filled with index UINT64_MAX, cost CHM_INFEASIBLE), CHM_ERR_OVERFLOW (the selected families hold more
+ * than 2^16 chunks of 2^idx_bits partitions, idx_bits <= 30: beyond exhaustive reach; search windows with
+ * chm_search_range or lists instead), CHM_ERR_ARG, CHM_ERR_HIP. */
 int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream);
 
 /* The same over partition ranks [part_first, part_first+part_count) of one strategy. */
@@ -200,6 +202,15 @@ int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out);
  * and reads the timings of the last such call. */
 int chm_set_timing(chm_scenario *s, int32_t on);
 int chm_get_timing(const chm_scenario *s, chm_timing *out);
+
+/* How the range search of the redundant-computation and re-partition strategies treats partitions that fail
+ * the memory filter (the OOM filter of the Estimator, "Peak Memory Usage"): mode 1 = every wavefront first
+ * collects the partitions that fit and evaluates them 64 at a time with all lanes busy; mode 0 = every lane
+ * evaluates its own partitions, lanes whose partition fails idle; mode -1 (the default) = per strategy, mode 1
+ * when fewer than 80 % of a seeded sample of partitions fit, else mode 0.  Results do not depend on the mode.
+ * share[k] (host, 3 floats, may be NULL) receives the sampled share per strategy (1.0 where no sample was
+ * taken).  Errors: CHM_ERR_ARG. */
+int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
 
 /* The distinct pipelines one plan of a strategy has to evaluate (pipelines with the same
  * nodes' speed factors, chain and micro-batch count are merged): *n of them (<= 16), each

@@ -16,7 +16,7 @@ OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HI
 INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
-           "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_get_timing", "chm_family_classes",
+           "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_set_filter_compaction", "chm_get_timing", "chm_family_classes",
            "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
@@ -103,6 +103,7 @@ def lib():
         L.chm_rank_partitions.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, vp]
         L.chm_decode_plan.argtypes = [vp, C.c_uint64, C.POINTER(Best)]
         L.chm_set_timing.argtypes = [vp, C.c_int32]
+        L.chm_set_filter_compaction.argtypes = [vp, C.c_int32, C.POINTER(C.c_float)]
         L.chm_get_timing.argtypes = [vp, C.POINTER(Timing)]
         L.chm_family_classes.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.chm_reroute_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
@@ -361,6 +362,12 @@ class Scenario:
 
     def set_timing(self, on=True):
         _check(lib().chm_set_timing(self._h, 1 if on else 0))
+
+    def set_filter_compaction(self, mode=-1):
+        """chm_set_filter_compaction: -1 automatic, 0 off, 1 on; returns the sampled share of partitions that fit, per strategy"""
+        share = (C.c_float * 3)()
+        _check(lib().chm_set_filter_compaction(self._h, mode, share))
+        return [float(x) for x in share]
 
     def get_timing(self):
         t = Timing()

@@ -54,6 +54,11 @@ struct FastTables {
 struct FastState {
   bool usable[3] = {false, false, false};   // per strategy: a specialised kernel covers this scenario
   bool split = false;                       // rerouting: vectors swept by k_sweep instead of inside the search kernel
+  // Range search of strategies 0 and 1: share of the partitions that pass the memory filter, estimated at load
+  // from FIT_SAMPLES seeded random partitions; below QUEUE_BELOW_SHARE the search compacts the partitions that
+  // fit through a ring per wave (k_fast_search, QUEUED).  queue_mode: -1 = by that estimate, 0 = never, 1 = always.
+  float fit_share[3] = {1.0f, 1.0f, 1.0f};
+  int queue_mode = -1;
   FastTables h_tables;
   FastTables *d_tables = nullptr;
   uint32_t *d_vecs = nullptr;

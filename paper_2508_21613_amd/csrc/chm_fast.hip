@@ -379,12 +379,26 @@ struct FastLaunch {
   const uint32_t *cut_count;
 };
 
+// Entries of a wave's queue of partitions that fit (QUEUED kernels): a ring of twice the wave width,
+// since a round appends at most 64 entries to fewer than 64 waiting ones.
+constexpr int QCAP = 128;
+
 // Waves per SIMD the register allocator is asked to keep possible: up to 8 stages the kernels fit 96
 // vector registers (5 waves); deeper pipelines hold more live stage sums and clocks and get what they need.
-template <int SP, int STRAT>
+//
+// QUEUED (range search of strategies 0 and 1 without cost store): lanes whose partition fails the memory
+// filter would idle through the recurrence of their wave, and consecutive ranks share their upper cuts, so
+// whole runs of a lane fail together.  Each wave therefore first only filters: every lane takes the next
+// partition of its run, and those that fit are appended (cut positions packed into bytes, position) to a
+// ring in LDS that belongs to the wave.  Whenever 64 entries wait, the wave evaluates them, one per lane,
+// with every lane busy; what is left after the last round is evaluated by a partly filled wave.  A ring is
+// written and read by one wave only, whose LDS operations complete in order: no barrier is needed.
+template <int SP, int STRAT, bool QUEUED = false>
 __global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SP <= 8 ? 5 : 1)))
 k_fast_search(FastLaunch a) {
   constexpr int K = SP - 1;
+  __shared__ uint4 q_cuts[QUEUED ? (BLOCK / 64) * QCAP : 1];
+  __shared__ uint32_t q_pos[QUEUED ? (BLOCK / 64) * QCAP : 1];
   __shared__ int4 T[DEV_MAX_L + 1];            // prefix sums: forward, backward, static memory, activation memory
   __shared__ uint64_t BN[(K > 0 ? K : 1) * DEV_MAX_L];   // BN[(i-1)*128 + x] = C(x, i), i = 1..K
   __shared__ uint64_t wave_keys[BLOCK / 64];
@@ -394,7 +408,7 @@ k_fast_search(FastLaunch a) {
   const TabPtr tab = as_const(a.tab);
   const FamPtr ff = &tab->fam[STRAT];
   const int L = scn->L;
-  const bool compact = a.cut_list != nullptr;
+  const bool compact = !QUEUED && a.cut_list != nullptr;
   const uint32_t n_slots = compact ? a.cut_count[blockIdx.x] : 0u;       // filled slots of this workgroup's region
   if (compact && n_slots == 0) return;
   for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], (int)scn->pa[i]);
@@ -415,7 +429,7 @@ k_fast_search(FastLaunch a) {
   bool listed_ok = true;
   if (!compact) {
     uint64_t rem = run_len ? a.s.part_first + run_first : 0;   // idle lanes walk from rank 0: always valid cuts
-    if (a.s.ranks != nullptr && run_len) {                       // list mode (one partition per lane)
+    if (!QUEUED && a.s.ranks != nullptr && run_len) {            // list mode (one partition per lane)
       rem = a.s.ranks[run_first];
       listed_ok = rem < scn->fam[STRAT].n_part;
       if (!listed_ok) rem = 0;
@@ -429,9 +443,66 @@ k_fast_search(FastLaunch a) {
   uint64_t best_pos = 0;        // output position (chunk-local partition index or list position) of the lane's best
   uint32_t n_fit = 0;           // wave-uniform count of partitions that pass the memory filter
 
-  for (uint32_t it = 0; it < a.per_lane; ++it) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  uint32_t q_head = 0, q_tail = 0;        // wave-uniform: entries [q_head, q_tail) of the wave's ring wait
+  // evaluation cuts: the lane's own cuts, or (QUEUED) those of the entry it takes from the ring
+  int ce[SP + 1];
+  ce[0] = 0;
+  ce[SP] = L;
+
+  for (uint32_t it = 0; it < a.per_lane + (QUEUED ? 1u : 0u); ++it) {
     bool live = it < run_len;             // this lane has a partition in this round
     uint64_t pos = run_first + it;        // where its result is reported
+    if (QUEUED) {
+      if (it < a.per_lane) {              // uniform; the extra round only drains the ring
+        // ---- filter the lane's next partition and append it to the ring if it fits
+        int ms[SP], as[SP];
+        {
+          int lo_m = 0, lo_a = 0;
+#pragma unroll
+          for (int j = 0; j < SP; ++j) {
+            const int4 hi = T[c[j + 1]];
+            ms[j] = hi.z - lo_m;
+            as[j] = hi.w - lo_a;
+            lo_m = hi.z;
+            lo_a = hi.w;
+          }
+        }
+        const bool fits = live && largest_peak<SP, STRAT>(ff, ms, as) <= cap;
+        const uint64_t fit_mask = __builtin_amdgcn_ballot_w64(fits);
+        if (fits) {
+          const uint32_t slot = (uint32_t)wave * QCAP + ((q_tail + (uint32_t)__popcll(fit_mask & ((1ull << lane) - 1ull))) & (QCAP - 1));
+          uint32_t words[4] = {0, 0, 0, 0};
+#pragma unroll
+          for (int i = 1; i <= K; ++i) words[(i - 1) >> 2] |= (uint32_t)c[i] << (8 * ((i - 1) & 3));
+          q_cuts[slot] = make_uint4(words[0], words[1], words[2], words[3]);
+          q_pos[slot] = (uint32_t)pos;
+        }
+        q_tail += (uint32_t)__popcll(fit_mask);
+        n_fit += (uint32_t)__popcll(fit_mask);
+        // next partition of the run
+        bool done = false;
+#pragma unroll
+        for (int i = 1; i <= K; ++i) {
+          const bool can = c[i] + 1 < c[i + 1];
+          c[i] = done ? c[i] : (can ? c[i] + 1 : i);
+          done = done || can;
+        }
+      }
+      const uint32_t waiting = q_tail - q_head;
+      if (waiting < 64 && !(it == a.per_lane && waiting > 0)) continue;     // uniform
+      // ---- evaluate up to 64 waiting entries, one per lane
+      const uint32_t take = waiting < 64 ? waiting : 64u;
+      live = (uint32_t)lane < take;
+      const uint32_t slot = (uint32_t)wave * QCAP + ((q_head + (uint32_t)lane) & (QCAP - 1));
+      // lanes past the end take the first partition (cuts 1..K): always valid
+      const uint4 packed = live ? q_cuts[slot] : make_uint4(0x04030201u, 0x08070605u, 0x0c0b0a09u, 0x000f0e0du);
+      const uint32_t words[4] = {packed.x, packed.y, packed.z, packed.w};
+#pragma unroll
+      for (int i = 1; i <= K; ++i) ce[i] = (int)((words[(i - 1) >> 2] >> (8 * ((i - 1) & 3))) & 0xffu);
+      pos = live ? q_pos[slot] : 0;
+      q_head += take;
+    }
     if (compact) {
       if (it * BLOCK >= n_slots) break;   // uniform: the region is used up
       const uint32_t slot = it * BLOCK + threadIdx.x;
@@ -443,13 +514,17 @@ k_fast_search(FastLaunch a) {
       for (int i = 1; i <= K; ++i) c[i] = (int)((words[(i - 1) >> 2] >> (8 * ((i - 1) & 3))) & 0xffu);
       pos = live ? a.cut_pos[region + slot] : 0;
     }
+    if (!QUEUED) {
+#pragma unroll
+      for (int i = 1; i <= K; ++i) ce[i] = c[i];
+    }
     // ---- stage sums from the LDS prefix table
     int fs[SP], bs[SP], ms[SP], as[SP];
     {
       int4 lo = make_int4(0, 0, 0, 0);
 #pragma unroll
       for (int j = 0; j < SP; ++j) {
-        const int4 hi = T[c[j + 1]];
+        const int4 hi = T[ce[j + 1]];
         fs[j] = hi.x - lo.x;
         bs[j] = hi.y - lo.y;
         ms[j] = hi.z - lo.z;
@@ -458,11 +533,11 @@ k_fast_search(FastLaunch a) {
       }
     }
     // ---- memory filter
-    const int mmax = largest_peak<SP, STRAT>(ff, ms, as);
-    const bool ok = (mmax <= cap) && live && listed_ok;
+    // (QUEUED: every entry of the ring has passed it already)
+    const bool ok = QUEUED ? live : ((largest_peak<SP, STRAT>(ff, ms, as) <= cap) && live && listed_ok);
     uint64_t cost = (uint64_t)CHM_INF_COST;
     const uint64_t ok_mask = __builtin_amdgcn_ballot_w64(ok);
-    n_fit += (uint32_t)__popcll(ok_mask);
+    if (!QUEUED) n_fit += (uint32_t)__popcll(ok_mask);
     if (ok_mask != 0) {
       int t_step = ff->fixed_step;
       int missing = 0;
@@ -566,15 +641,15 @@ k_fast_search(FastLaunch a) {
         // rounds of gradient communication: largest stage on any device, or the ring colouring when nodes hold two stages
         int rounds;
         if (STRAT == 0) {
-          rounds = ring_rounds<SP>(c, ff->node_exists);
+          rounds = ring_rounds<SP>(ce, ff->node_exists);
         } else {
           rounds = ff->fixed_layers;
 #pragma unroll
-          for (int j = 0; j < SP; ++j) rounds = imax32(rounds, c[j + 1] - c[j]);
+          for (int j = 0; j < SP; ++j) rounds = imax32(rounds, ce[j + 1] - ce[j]);
         }
         t_step += ff->allreduce * rounds;
       }
-      if (STRAT == 2 && a.base_out == nullptr) {
+      if (STRAT == 2 && (QUEUED || a.base_out == nullptr)) {
         // every reroute vector of every stage that lost nodes
         for (int st = 0; st < scn->n_aff; ++st) {
           const int sa = scn->aff_stage[st];
@@ -627,7 +702,7 @@ k_fast_search(FastLaunch a) {
           t_step += (int)pen;
         }
       }
-      if (STRAT == 2 && a.base_out != nullptr) {
+      if (!QUEUED && STRAT == 2 && a.base_out != nullptr) {
         // split path: hand the peer stage times of this partition to the sweep kernel
         if (ok) {
           uint32_t *wout = a.weights_out + (run_first + it) * (DEV_MAX_AFF * 8);
@@ -648,11 +723,14 @@ k_fast_search(FastLaunch a) {
         }
       }
       cost = (uint64_t)scn->K * (uint32_t)t_step + (uint64_t)scn->reconf[STRAT] + (uint64_t)scn->xfer * (uint32_t)missing;
-      if (ok && cost < best_cost) { best_cost = cost; best_pos = pos; }
-      if (STRAT == 2 && a.base_out != nullptr && ok) a.base_out[run_first + it] = cost;
+      // a lane meets the entries of a compacted list or of a ring in no particular order of position:
+      // there the lower position wins among equal costs; a run is walked in ascending order
+      const bool lower = (QUEUED || compact) ? (cost < best_cost || (cost == best_cost && pos < best_pos)) : cost < best_cost;
+      if (ok && lower) { best_cost = cost; best_pos = pos; }
+      if (!QUEUED && STRAT == 2 && a.base_out != nullptr && ok) a.base_out[run_first + it] = cost;
     }
-    if (STRAT == 2 && a.base_out != nullptr && !ok && it < run_len) a.base_out[run_first + it] = ~0ull;
-    if (a.s.costs_out != nullptr) {
+    if (!QUEUED && STRAT == 2 && a.base_out != nullptr && !ok && it < run_len) a.base_out[run_first + it] = ~0ull;
+    if (!QUEUED && a.s.costs_out != nullptr) {
       // per_lane == 1: the store is coalesced as it is; longer runs go through an LDS tile
       // (laid out in output order) and are written out together after the loop
       const int64_t v = ok ? (int64_t)cost : CHM_INF_COST;
@@ -660,7 +738,7 @@ k_fast_search(FastLaunch a) {
       else cost_tile[threadIdx.x * a.per_lane + it] = v;
     }
     // ---- next partition in rank order: bump the lowest cut that has room, reset those below
-    if (!compact) {
+    if (!compact && !QUEUED) {
       bool done = false;
 #pragma unroll
       for (int i = 1; i <= K; ++i) {
@@ -671,7 +749,7 @@ k_fast_search(FastLaunch a) {
     }
   }
 
-  if (a.s.costs_out != nullptr && a.per_lane > 1 && !compact) {
+  if (!QUEUED && a.s.costs_out != nullptr && a.per_lane > 1 && !compact) {
     __syncthreads();
     const uint64_t block_first = (uint64_t)blockIdx.x * BLOCK * a.per_lane;
     const uint32_t n_tile = BLOCK * a.per_lane;
@@ -680,9 +758,8 @@ k_fast_search(FastLaunch a) {
   }
   uint64_t key = best_cost == ~0ull ? CHM_KEY_NONE
                                     : ((best_cost << a.s.idx_bits) | best_pos);
-  if (STRAT == 2 && a.base_out != nullptr) key = CHM_KEY_NONE;   // the combine kernel takes the argmin
+  if (!QUEUED && STRAT == 2 && a.base_out != nullptr) key = CHM_KEY_NONE;   // the combine kernel takes the argmin
   key = wave_min(key);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   if (lane == 0) { wave_keys[wave] = key; wave_fit[wave] = n_fit; }
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -1042,11 +1119,15 @@ int by_peers(int p, Fn fn) {
   }
 }
 
+// queued: the variant that compacts the partitions that fit through a ring per wave (strategies 0 and 1)
 template <int STRAT>
-int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, uint32_t tile_bytes, hipStream_t st) {
+int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, uint32_t tile_bytes, hipStream_t st, bool queued = false) {
 #define CHM_CASE(SPV)                                                                         \
   case SPV:                                                                                   \
-    hipLaunchKernelGGL((k_fast_search<SPV, STRAT>), dim3(blocks), dim3(BLOCK), tile_bytes, st, a); \
+    if (STRAT != 2 && queued)                                                                 \
+      hipLaunchKernelGGL((k_fast_search<SPV, STRAT, (STRAT != 2)>), dim3(blocks), dim3(BLOCK), 0, st, a); \
+    else                                                                                      \
+      hipLaunchKernelGGL((k_fast_search<SPV, STRAT>), dim3(blocks), dim3(BLOCK), tile_bytes, st, a); \
     return 0;
   switch (sp) {
     CHM_CASE(2) CHM_CASE(3) CHM_CASE(4) CHM_CASE(5) CHM_CASE(6) CHM_CASE(7) CHM_CASE(8)
@@ -1071,6 +1152,50 @@ int filter_by_stages(int sp, const ListFilter &a, uint32_t blocks, hipStream_t s
 }
 
 bool stages_covered(int sp) { return sp >= 2 && sp <= 16; }
+
+// Share of uniformly drawn partitions into `sp` stages whose largest per-node peak memory stays within the cap
+// (the filter of largest_peak, on the host).  Only steers the choice between two kernels with equal results.
+constexpr int FIT_SAMPLES = 128;
+constexpr float QUEUE_BELOW_SHARE = 0.80f;
+float estimate_fit_share(const DevScenario &h, const FastFamily &ff, int strat, int sp) {
+  const int L = h.L, k = sp - 1, n = L - 1;
+  uint64_t state = 0x9e3779b97f4a7c15ull ^ ((uint64_t)L << 32) ^ ((uint64_t)sp << 8) ^ (uint64_t)strat;
+  auto next = [&state]() {                   // splitmix64
+    uint64_t z = (state += 0x9e3779b97f4a7c15ull);
+    z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+    z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+    return z ^ (z >> 31);
+  };
+  int fit = 0;
+  for (int smp = 0; smp < FIT_SAMPLES; ++smp) {
+    // k distinct cut positions out of 1..n, each subset equally likely: for j = n-k+1..n draw t from 1..j and
+    // take t, or j when t is already taken; the chosen positions are bits of a mask
+    uint64_t chosen[2] = {0, 0};
+    for (int j = n - k + 1; j <= n; ++j) {
+      const int t = 1 + (int)(((next() >> 32) * (uint64_t)j) >> 32);
+      const int pick = (chosen[t >> 6] >> (t & 63)) & 1 ? j : t;
+      chosen[pick >> 6] |= 1ull << (pick & 63);
+    }
+    int c[DEV_MAX_S + 1];
+    c[0] = 0;
+    int filled = 1;
+    for (int w = 0; w < 2; ++w)
+      for (uint64_t m = chosen[w]; m; m &= m - 1) c[filled++] = w * 64 + __builtin_ctzll(m);
+    c[sp] = L;
+    int64_t st[DEV_MAX_S], ac[DEV_MAX_S];
+    for (int s = 0; s < sp; ++s) { st[s] = h.pw[c[s + 1]] - h.pw[c[s]]; ac[s] = h.pa[c[s + 1]] - h.pa[c[s]]; }
+    int64_t peak = 0;
+    for (int s = 0; s < sp; ++s) {
+      const int coef = ff.mem_coef[s];
+      if (coef < 0) continue;
+      const int64_t a = strat == 0 ? st[s] + st[(s + 1) % sp] : st[s];
+      const int64_t b = strat == 0 ? ac[s] + ac[(s + 1) % sp] : ac[s];
+      peak = std::max(peak, a + (ff.has_act ? b * coef : 0));
+    }
+    if (peak <= (int64_t)h.cap) ++fit;
+  }
+  return (float)fit / (float)FIT_SAMPLES;
+}
 
 }  // namespace
 
@@ -1150,6 +1275,7 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
       f->split = ok && r_sum > FAST_FUSED_R;
     }
     f->usable[k] = ok;
+    if (ok && k != 2) f->fit_share[k] = estimate_fit_share(h, ff, k, fam.stages);
   }
   // run tables (host enumeration in rank order: shared entries lexicographic, see FastTables)
   std::vector<uint32_t> runs;
@@ -1321,9 +1447,12 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   const uint64_t lanes = (a.part_count + per - 1) / per;
   const uint32_t blocks = (uint32_t)((lanes + BLOCK - 1) / BLOCK);
   const int sp = h.fam[a.strategy].stages;
+  // pure range search of a family in which a good share of the partitions fails the memory filter
+  const bool queued = a.strategy != 2 && a.ranks == nullptr && a.costs_out == nullptr && base_out == nullptr &&
+                      f->queue_mode != 0 && (f->queue_mode > 0 || f->fit_share[a.strategy] < QUEUE_BELOW_SHARE);
   int rc;
-  if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, tile_bytes, st);
-  else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, tile_bytes, st);
+  if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, tile_bytes, st, queued);
+  else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, tile_bytes, st, queued);
   else rc = launch_by_stages<2>(sp, fl, blocks, tile_bytes, st);
   if (rc) return rc;
   return hipGetLastError() == hipSuccess ? 0 : -1;

@@ -398,6 +398,10 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
   s->last = chm_timing();
   std::vector<Slot> slots;
   const uint64_t chunk = 1ull << s->idx_bits;
+  // spaces that need more chunks than there are argmin slots are refused before anything is sized by them
+  uint64_t n_chunks = 0;
+  for (const Job &j : jobs) n_chunks += j.count / chunk + 1;
+  if (n_chunks > MAX_SLOTS) return CHM_ERR_OVERFLOW;
   for (const Job &j : jobs)
     for (uint64_t done = 0; done < j.count; done += chunk)
       slots.push_back({j.strategy, ((j.ranks || j.cuts) ? 0 : j.first) + done, s->idx_bits});
@@ -743,6 +747,14 @@ extern "C" int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *
 extern "C" int chm_set_timing(chm_scenario *s, int32_t on) {
   if (!s) return CHM_ERR_ARG;
   s->timing = on != 0;
+  return CHM_OK;
+}
+
+extern "C" int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share) {
+  if (!s || mode < -1 || mode > 1) return CHM_ERR_ARG;
+  s->fast.queue_mode = mode;
+  if (share)
+    for (int k = 0; k < 3; ++k) share[k] = s->fast.fit_share[k];
   return CHM_OK;
 }
 

@@ -93,6 +93,107 @@ def test_small_scenarios_every_cost_and_argmin(B, i):
         assert same_plan(d_g, d_o)
 
 
+def _uniform_layers(sc, cap):
+    """the same scenario with identical layers and free weight transfer (many plans of equal cost) and the given memory cap"""
+    L = sc["L"]
+    return dict(sc, fwd_us=[1000] * L, bwd_us=[2000] * L, mem_mib=[500] * L, mem_cap_mib=cap, act_mib=None, xfer_us_per_mib=0)
+
+
+COMPACTION = [
+    ("config2", lambda: synth.config2()),
+    ("config2_tight", lambda: dict(synth.config2(), mem_cap_mib=6600)),           # few partitions fit
+    ("config2_none_fit", lambda: dict(synth.config2(), mem_cap_mib=2000)),
+    ("config2_act_allreduce", lambda: dict(synth.with_activations(synth.config2(), 31), allreduce_us=900)),
+    ("config5_double_assign", lambda: dict(synth.config5([3, 17]), transfer_assign=1)),
+    ("config3", lambda: synth.config3()),
+    ("config4", lambda: synth.config4(mem_cap_mib=synth.CONFIG4_CAP_30PCT)),
+    ("config1_ties", lambda: _uniform_layers(synth.config1(), 9000)),
+    ("config2_ties", lambda: _uniform_layers(synth.config2(), 8000)),
+    ("small_6_stages", lambda: synth.small_random(4242, L=20, PP=6, DP=3, M=7, n_failed=1, hetero=True)),
+]
+
+
+@pytest.mark.parametrize("name", [c[0] for c in COMPACTION])
+def test_filter_compaction_modes_agree_with_the_oracle(B, name):
+    """range search of strategies 0 and 1 with the partitions that fit compacted per wavefront (mode 1) and
+    without (mode 0): same winner as the oracle on seeded windows (lowest index among equal costs), same count
+    of partitions that fit, and the same winner over the whole space in both modes."""
+    sc = dict(COMPACTION)[name]()
+    o, g = O.Scenario(sc), B.Scenario(sc)
+    g.set_timing(True)
+    rng = np.random.default_rng(11)
+    share = g.set_filter_compaction(-1)
+    print("compaction", name, "sampled share of partitions that fit", share, flush=True)
+    for f in o.families:
+        if f["strategy"] == 2:
+            continue
+        width = min(f["n_part"], 30000)
+        firsts = {0, f["n_part"] - width} | {int(rng.integers(0, f["n_part"] - width + 1)) for _ in range(3)}
+        for first in sorted(firsts):
+            rc_o, best_o, _ = o.search_range(f["strategy"], first, width)
+            fit = None
+            for mode in (1, 0):
+                g.set_filter_compaction(mode)
+                rc_g, best_g = g.search_range(f["strategy"], first, width)
+                assert rc_g == rc_o, (name, f["strategy"], first, mode, rc_g, rc_o)
+                assert same_plan(best_g, best_o), (name, f["strategy"], first, mode, best_g, best_o)
+                n_fit = g.get_timing()["feasible"][f["strategy"]]
+                assert fit is None or n_fit == fit
+                fit = n_fit
+        if f["n_part"] > 2 * 10 ** 8:          # config 4: the whole space is out of reach, the windows stand for it
+            g.set_filter_compaction(1)
+            with pytest.raises(B.ChmError) as err:
+                g.search_best(1 << f["strategy"])
+            assert err.value.code == B.ERR_OVERFLOW
+            continue
+        whole = []
+        for mode in (1, 0, -1):
+            g.set_filter_compaction(mode)
+            rc, best = g.search_best(1 << f["strategy"])
+            whole.append((rc, best, g.get_timing()["feasible"][f["strategy"]]))
+        assert whole[0][0] == whole[1][0] == whole[2][0]
+        assert same_plan(whole[0][1], whole[1][1]) and same_plan(whole[0][1], whole[2][1])
+        assert whole[0][2] == whole[1][2] == whole[2][2]
+        if whole[0][0] == 0:
+            best = whole[0][1]
+            assert o.decode(best["index"])["cost"] == best["cost"]
+            # the window around the winner: the oracle finds the same plan there, in both modes
+            part = best["index"] - f["offset"]
+            first = max(0, min(part - width // 2, f["n_part"] - width))
+            rc_o, best_o, _ = o.search_range(f["strategy"], first, width)
+            assert rc_o == 0 and same_plan(best, best_o), (name, f["strategy"], best, best_o)
+            for mode in (1, 0):
+                g.set_filter_compaction(mode)
+                rc_g, best_g = g.search_range(f["strategy"], first, width)
+                assert rc_g == 0 and same_plan(best_g, best_o)
+
+
+def test_equal_costs_in_an_explicit_list_go_to_the_lowest_position(B):
+    """a list in which the best partition occurs many times at seeded positions: the reported position is
+    the first of them, whatever order the compacted entries are evaluated in"""
+    import torch
+    for sc in (synth.config4(mem_cap_mib=synth.CONFIG4_CAP_30PCT), synth.config2()):
+        o, g = O.Scenario(sc), B.Scenario(sc)
+        for f in o.families:
+            if f["n_reroute"] != 1:
+                continue
+            k = f["stages"] - 1
+            n = 40000
+            cuts = synth.random_partitions(91, 3 + f["strategy"], n, sc["L"], k)
+            want = o.score_ranks(f["strategy"], O.partition_rank_batch(cuts))
+            if (want == O.INF).all():
+                continue
+            winner = cuts[int(np.argmin(want))].copy()
+            where = np.random.default_rng(5 + f["strategy"]).choice(np.arange(2000, n), size=300, replace=False)
+            cuts[where] = winner
+            want[where] = want.min()
+            costs = torch.empty(n, dtype=torch.int64, device="cuda")
+            rc, best, pos = g.search_cuts(f["strategy"], torch.from_numpy(cuts).cuda(), costs=costs)
+            assert rc == 0 and (costs.cpu().numpy() == want).all()
+            assert pos == int(np.argmin(want)), (f["strategy"], pos, int(np.argmin(want)))
+            assert best["cuts"] == [int(x) for x in winner] and best["cost"] == int(want.min())
+
+
 def test_config1_all_9455_plans(B):
     sc = synth.config1()
     o, g = O.Scenario(sc), B.Scenario(sc)
