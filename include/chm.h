@@ -128,6 +128,8 @@ typedef struct {
   uint64_t partitions[3];      /* partitions evaluated per strategy                                  */
   uint64_t evaluations[3];     /* (partition, reroute vector) evaluations per strategy               */
   uint64_t feasible[3];        /* partitions per strategy that passed the memory filter              */
+  uint64_t evaluated[3];       /* of those, partitions whose pipeline recurrences were run: all of
+                                * them, or fewer in a bounded search (chm_set_bounded_search)         */
 } chm_timing;
 
 /* Validates the description, builds the plan space and uploads the scenario tables
@@ -211,6 +213,20 @@ int chm_get_timing(const chm_scenario *s, chm_timing *out);
  * share[k] (host, 3 floats, may be NULL) receives the sampled share per strategy (1.0 where no sample was
  * taken).  Errors: CHM_ERR_ARG. */
 int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
+
+/* Bounded search, off by default.  on != 0: chm_search_best and chm_search_range skip a partition as soon as a
+ * lower bound of its cost (micro-batches x the largest forward + backward time of a stage, which every
+ * pipeline needs under the dependencies of eq. (transition); plus lower bounds of the communication rounds
+ * and of the reroute penalty of eq. (re-route); the transition time counted as its constant part) lies
+ * above the lowest cost evaluated so far in the same call.  The plan returned is the same, ties included:
+ * only plans that can neither win nor tie are skipped, one by one or a run of consecutive ranks at a time
+ * (the stages above the cuts that change within the run are common to all of its partitions, and so is their
+ * share of the bound).  The search starts with the ranks around the time-balanced and the memory-balanced
+ * partition of each range, so that a good cost is known early.  chm_timing.evaluated tells how many
+ * partitions were evaluated in full; chm_timing.feasible then counts only those partitions that were looked
+ * at one by one and fit.  Covers the range searches of the specialised kernels without cost store (other
+ * paths evaluate everything).  Errors: CHM_ERR_ARG. */
+int chm_set_bounded_search(chm_scenario *s, int32_t on);
 
 /* The distinct pipelines one plan of a strategy has to evaluate (pipelines with the same
  * nodes' speed factors, chain and micro-batch count are merged): *n of them (<= 16), each

@@ -16,7 +16,7 @@ OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HI
 INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
-           "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_set_filter_compaction", "chm_get_timing", "chm_family_classes",
+           "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_set_filter_compaction", "chm_set_bounded_search", "chm_get_timing", "chm_family_classes",
            "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
@@ -72,7 +72,8 @@ class ReplanPlan(C.Structure):
 
 class Timing(C.Structure):
     _fields_ = [("family_ms", C.c_float * 3), ("total_ms", C.c_float),
-                ("partitions", C.c_uint64 * 3), ("evaluations", C.c_uint64 * 3), ("feasible", C.c_uint64 * 3)]
+                ("partitions", C.c_uint64 * 3), ("evaluations", C.c_uint64 * 3), ("feasible", C.c_uint64 * 3),
+                ("evaluated", C.c_uint64 * 3)]
 
 
 class ChmError(RuntimeError):
@@ -104,6 +105,7 @@ def lib():
         L.chm_decode_plan.argtypes = [vp, C.c_uint64, C.POINTER(Best)]
         L.chm_set_timing.argtypes = [vp, C.c_int32]
         L.chm_set_filter_compaction.argtypes = [vp, C.c_int32, C.POINTER(C.c_float)]
+        L.chm_set_bounded_search.argtypes = [vp, C.c_int32]
         L.chm_get_timing.argtypes = [vp, C.POINTER(Timing)]
         L.chm_family_classes.argtypes = [vp, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
         L.chm_reroute_shape.argtypes = [vp, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_uint64)]
@@ -369,8 +371,13 @@ class Scenario:
         _check(lib().chm_set_filter_compaction(self._h, mode, share))
         return [float(x) for x in share]
 
+    def set_bounded_search(self, on=True):
+        """chm_set_bounded_search: skip partitions whose lower bound of the cost lies above the best cost found so far"""
+        _check(lib().chm_set_bounded_search(self._h, 1 if on else 0))
+
     def get_timing(self):
         t = Timing()
         _check(lib().chm_get_timing(self._h, C.byref(t)))
         return {"family_ms": [float(x) for x in t.family_ms], "total_ms": float(t.total_ms),
-                "partitions": [int(x) for x in t.partitions], "evaluations": [int(x) for x in t.evaluations], "feasible": [int(x) for x in t.feasible]}
+                "partitions": [int(x) for x in t.partitions], "evaluations": [int(x) for x in t.evaluations], "feasible": [int(x) for x in t.feasible],
+                "evaluated": [int(x) for x in t.evaluated]}

@@ -87,6 +87,12 @@ struct SearchLaunch {
   const uint8_t *cuts;
   // when set, cost i of the chunk (INT64_MAX if infeasible) is also stored to costs_out[i]
   int64_t *costs_out;
+  // Bounded search (null: every partition that fits is evaluated).  *incumbent = the lowest cost any wave of
+  // this search call has evaluated so far (atomicMin, starts at ~0); a partition whose lower bound of the
+  // cost lies above it can neither win nor tie and is skipped.  evaluated: counters like `feasible`, of the
+  // partitions whose recurrences were run.  Only the specialised range kernels honour it; others evaluate all.
+  uint64_t *incumbent = nullptr;
+  uint64_t *evaluated = nullptr;
 };
 
 // launch wrappers (defined in chm_kernels.hip); each returns a hipError_t cast to int

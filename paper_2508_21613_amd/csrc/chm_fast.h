@@ -16,6 +16,8 @@ struct FastClass {
   int32_t n, M;
   int32_t dead0, dead1;           // partition stages missing from the chain (>= stages: none)
   int32_t unit;                   // 1: every node of the chain runs at nominal speed (no scaling)
+  uint32_t q_min;                 // smallest speed factor along the chain (lower bound of the step time)
+  int32_t lb_slack;               // what rounding can take from that bound when q_min scales it (0 at nominal speed)
   int32_t comm_total;             // (n-1) * comm
   uint32_t q[DEV_MAX_S];
   int32_t wlo[DEV_MAX_S], whi[DEV_MAX_S];   // memory prefix at the bounds of the fault-free stage of node j
@@ -32,6 +34,7 @@ struct FastFamily {
   int32_t allreduce;              // time of one round of gradient communication (0: not modelled)
   int32_t fixed_layers;           // strategy 1: layers of the largest stage on a node of an untouched pipeline, else 0
   uint32_t node_exists;           // strategy 0: bit s = some pipeline still has its node of stage s
+  int32_t lb_prefix;              // 1: the sharper lower bound (24-bit multiplies are safe for these times)
   FastClass cls[DEV_MAX_CLS];
 };
 
@@ -49,6 +52,9 @@ struct FastTables {
   // small uncapped reroute spaces have a sweep unrolled at compile time (see sweep_products):
   // peers * 256 + orphaned micro-batches when such a sweep exists for stage a, else 0
   uint32_t unrolled_shape[DEV_MAX_AFF];
+  // lower bound of stage a's reroute penalty: some peer takes at least lb_mult[a] = ceil(orphans / peers)
+  // micro-batches (0 when a cap below that leaves this unclear), each at a stage time scaled by at least lb_q[a]
+  uint32_t lb_mult[DEV_MAX_AFF], lb_q[DEV_MAX_AFF];
 };
 
 struct FastState {
@@ -81,6 +87,9 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
 // value when the strategy is not covered (the caller then uses the generic kernel), or a
 // negative value on a HIP error.
 int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void *stream);
+// Whether fast_search would run this launch as a bounded search if a.incumbent were set (a range search of a
+// covered strategy without cost store whose reroute vectors, if any, are swept inside the search kernel).
+bool fast_can_bound(const FastState *f, const SearchLaunch &a);
 // Rank of the best reroute vector per affected stage of one partition of the rerouting family,
 // written to d_out[0..n_aff).  Same return convention as fast_search.
 int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t part_rank,

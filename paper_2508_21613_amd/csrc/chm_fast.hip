@@ -54,6 +54,12 @@ __device__ __forceinline__ int scale32(int x, uint32_t q) {
   return (int)(((uint64_t)(uint32_t)x * q + 32768u) >> 16);
 }
 
+// lower bound of scale32(f, q') + scale32(b, q') for any q' >= q, given x = f + b: each rounding loses less
+// than one, so the sum is at least floor(x * q / 65536) - 1
+__device__ __forceinline__ int scale_floor(int x, uint32_t q) {
+  return q == 65536u ? x : imax32(0, (int)(((uint64_t)(uint32_t)x * q) >> 16) - 1);
+}
+
 // forward + backward time of a stage on a peer with factor q (uniform): nominal peers need no scaling
 __device__ __forceinline__ uint32_t peer_time(int f, int b, uint32_t q) {
   return q == 65536u ? (uint32_t)(f + b) : (uint32_t)(scale32(f, q) + scale32(b, q));
@@ -403,6 +409,7 @@ k_fast_search(FastLaunch a) {
   __shared__ uint64_t BN[(K > 0 ? K : 1) * DEV_MAX_L];   // BN[(i-1)*128 + x] = C(x, i), i = 1..K
   __shared__ uint64_t wave_keys[BLOCK / 64];
   __shared__ uint32_t wave_fit[BLOCK / 64];
+  __shared__ uint32_t wave_eval[BLOCK / 64];
   extern __shared__ int64_t cost_tile[];       // BLOCK * per_lane costs when a cost store with per_lane > 1 is asked for
   const ScnPtr scn = as_const(a.s.scn);
   const TabPtr tab = as_const(a.tab);
@@ -445,30 +452,148 @@ k_fast_search(FastLaunch a) {
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint32_t q_head = 0, q_tail = 0;        // wave-uniform: entries [q_head, q_tail) of the wave's ring wait
+  // bounded search: the lowest cost evaluated so far, by this wave or (as of its last look) by any other
+  const bool bounded = QUEUED && a.s.incumbent != nullptr;
+  uint64_t incumbent = ~0ull;
+  uint32_t n_eval = 0;                    // wave-uniform count of partitions whose recurrences were run
+  if (bounded) incumbent = __hip_atomic_load(a.s.incumbent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  // Bounded search, a whole run at once.  Consecutive ranks differ in their lowest cuts.  When the run of a lane
+  // stays inside the block of ranks that share the cuts above the h lowest ones (its offset among the
+  // arrangements of those h cuts, plus its length, does not exceed their number C(c[h+1]-1, h)), the stages
+  // from h+1 on are the same for every partition of the run, and so is their part of the lower bound: stage s
+  // contributes M x its time + the time of all layers ahead of it, whatever the lower cuts are.  If that
+  // alone lies above the incumbent for every lane, the wave has nothing to look at.
+  bool wave_dead = false;
+  if (bounded && K >= 2) {
+    uint64_t offset = 0;
+    int first_fixed = SP;                   // stages first_fixed.. are the same throughout the run
+#pragma unroll
+    for (int h = 1; h < K; ++h) {
+      offset += BN[(h - 1) * DEV_MAX_L + (c[h] - 1)];
+      const bool stays = offset + run_len <= BN[(h - 1) * DEV_MAX_L + (c[h + 1] - 1)];
+      first_fixed = (first_fixed == SP && stays) ? h + 1 : first_fixed;
+    }
+    int pc[SP + 1];                         // forward + backward time of the layers ahead of stage s
+#pragma unroll
+    for (int s2 = 1; s2 <= SP; ++s2) { const int4 t = T[c[s2]]; pc[s2] = t.x + t.y; }
+    int lb = ff->fixed_step;
+    for (int ci = 0; ci < ff->n_cls; ++ci) {
+      const ClsPtr cl = &ff->cls[ci];
+      int v = 0;
+#pragma unroll
+      for (int s2 = 1; s2 < SP; ++s2) {
+        int vs;
+        if (STRAT == 0) {
+          // a node's own stage and its successor's; the pair that wraps around to stage 0 is left out
+          const int pair = s2 + 2 <= SP ? pc[s2 + 2 <= SP ? s2 + 2 : SP] - pc[s2] : 0;
+          vs = (s2 == cl->dead0 || s2 == cl->dead1) ? 0 : cl->M * pair;
+        } else {
+          const int own = pc[s2 + 1] - pc[s2];
+          vs = ff->lb_prefix ? (int)__umul24((uint32_t)cl->M, (uint32_t)own) + pc[s2] : cl->M * own;
+        }
+        v = imax32(v, s2 >= first_fixed ? vs : 0);
+      }
+      lb = imax32(lb, imax32(0, scale_floor(v, cl->q_min) - cl->lb_slack) + cl->comm_total);
+    }
+    const uint64_t lb_cost = (uint64_t)scn->K * (uint32_t)lb + (uint64_t)scn->reconf[STRAT];
+    const bool look = run_len != 0 && !(first_fixed < SP && lb_cost > incumbent);
+    wave_dead = __builtin_amdgcn_ballot_w64(look) == 0;
+  }
   // evaluation cuts: the lane's own cuts, or (QUEUED) those of the entry it takes from the ring
   int ce[SP + 1];
   ce[0] = 0;
   ce[SP] = L;
 
-  for (uint32_t it = 0; it < a.per_lane + (QUEUED ? 1u : 0u); ++it) {
+  for (uint32_t it = 0; it < (wave_dead ? 0u : a.per_lane + (QUEUED ? 1u : 0u)); ++it) {
     bool live = it < run_len;             // this lane has a partition in this round
     uint64_t pos = run_first + it;        // where its result is reported
     if (QUEUED) {
       if (it < a.per_lane) {              // uniform; the extra round only drains the ring
         // ---- filter the lane's next partition and append it to the ring if it fits
-        int ms[SP], as[SP];
+        int ms[SP], as[SP], cs[SP];           // cs: forward + backward time per stage
         {
-          int lo_m = 0, lo_a = 0;
+          int lo_m = 0, lo_a = 0, lo_c = 0;
 #pragma unroll
           for (int j = 0; j < SP; ++j) {
             const int4 hi = T[c[j + 1]];
             ms[j] = hi.z - lo_m;
             as[j] = hi.w - lo_a;
+            cs[j] = hi.x + hi.y - lo_c;
             lo_m = hi.z;
             lo_a = hi.w;
+            lo_c = hi.x + hi.y;
           }
         }
-        const bool fits = live && largest_peak<SP, STRAT>(ff, ms, as) <= cap;
+        bool fits = live && largest_peak<SP, STRAT>(ff, ms, as) <= cap;
+        n_fit += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(fits));
+        if (bounded) {                        // uniform
+          // Lower bound of the plan's cost.  Every stage of a pipeline runs its M forwards and M backwards one
+          // after the other, so the pipeline takes at least M x the largest (forward + backward) of its chain;
+          // rounds of gradient communication: at least the layers of the largest stage; a stage that lost
+          // nodes leaves some peer with at least ceil(orphans / peers) extra micro-batches; the weight transfer
+          // is at least zero.  Above the incumbent the partition can neither win nor tie.
+          // (Sharper where the times allow 24-bit multiplies: stage s cannot start before the forwards of the
+          // stages ahead of it and is followed by their backwards: M x its own time + the times of stages 0..s-1.)
+          int lb = ff->fixed_step;
+          if (STRAT == 0) {
+            int cd[SP];
+#pragma unroll
+            for (int j = 0; j < SP; ++j) cd[j] = cs[j] + cs[(j + 1) % SP];
+            for (int ci = 0; ci < ff->n_cls; ++ci) {
+              const ClsPtr cl = &ff->cls[ci];
+              int v = 0;
+              if (ff->lb_prefix) {
+                int pre = 0;
+#pragma unroll
+                for (int j = 0; j < SP; ++j) {
+                  const int cj = (j == cl->dead0 || j == cl->dead1) ? 0 : cd[j];
+                  v = imax32(v, (int)__umul24((uint32_t)cl->M, (uint32_t)cj) + pre);
+                  pre += cj;
+                }
+              } else {
+#pragma unroll
+                for (int j = 0; j < SP; ++j) v = imax32(v, (j == cl->dead0 || j == cl->dead1) ? 0 : cd[j]);
+                v *= cl->M;
+              }
+              lb = imax32(lb, imax32(0, scale_floor(v, cl->q_min) - cl->lb_slack) + cl->comm_total);
+            }
+          } else {
+            for (int ci = 0; ci < ff->n_cls; ++ci) {
+              const ClsPtr cl = &ff->cls[ci];
+              int v = 0;
+              if (ff->lb_prefix) {
+                int pre = 0;
+#pragma unroll
+                for (int j = 0; j < SP; ++j) {
+                  v = imax32(v, (int)__umul24((uint32_t)cl->M, (uint32_t)cs[j]) + pre);
+                  pre += cs[j];
+                }
+              } else {
+#pragma unroll
+                for (int j = 0; j < SP; ++j) v = imax32(v, cs[j]);
+                v *= cl->M;
+              }
+              lb = imax32(lb, imax32(0, scale_floor(v, cl->q_min) - cl->lb_slack) + cl->comm_total);
+            }
+          }
+          if (ff->allreduce > 0) {
+            int layers = STRAT == 0 ? 0 : ff->fixed_layers;
+#pragma unroll
+            for (int j = 0; j < SP; ++j) layers = imax32(layers, c[j + 1] - c[j]);
+            lb += ff->allreduce * layers;
+          }
+          if (STRAT == 2) {
+            for (int st = 0; st < scn->n_aff; ++st) {
+              const int sa = scn->aff_stage[st];
+              int c_st = cs[0];
+#pragma unroll
+              for (int j = 1; j < SP; ++j) c_st = sa == j ? cs[j] : c_st;
+              lb += (int)tab->lb_mult[st] * scale_floor(c_st, tab->lb_q[st]);
+            }
+          }
+          const uint64_t lb_cost = (uint64_t)scn->K * (uint32_t)lb + (uint64_t)scn->reconf[STRAT];
+          fits = fits && lb_cost <= incumbent;
+        }
         const uint64_t fit_mask = __builtin_amdgcn_ballot_w64(fits);
         if (fits) {
           const uint32_t slot = (uint32_t)wave * QCAP + ((q_tail + (uint32_t)__popcll(fit_mask & ((1ull << lane) - 1ull))) & (QCAP - 1));
@@ -479,7 +604,6 @@ k_fast_search(FastLaunch a) {
           q_pos[slot] = (uint32_t)pos;
         }
         q_tail += (uint32_t)__popcll(fit_mask);
-        n_fit += (uint32_t)__popcll(fit_mask);
         // next partition of the run
         bool done = false;
 #pragma unroll
@@ -727,6 +851,16 @@ k_fast_search(FastLaunch a) {
       // there the lower position wins among equal costs; a run is walked in ascending order
       const bool lower = (QUEUED || compact) ? (cost < best_cost || (cost == best_cost && pos < best_pos)) : cost < best_cost;
       if (ok && lower) { best_cost = cost; best_pos = pos; }
+      if (bounded) {
+        // the round's lowest cost becomes known to every wave; what the others found is picked up in turn
+        n_eval += (uint32_t)__popcll(ok_mask);
+        const uint64_t round_best = wave_min(ok ? cost : ~0ull);
+        if (round_best < incumbent) {
+          incumbent = round_best;
+          if (lane == 0) atomicMin((unsigned long long *)a.s.incumbent, (unsigned long long)round_best);
+        }
+        incumbent = umin64(incumbent, __hip_atomic_load(a.s.incumbent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+      }
       if (!QUEUED && STRAT == 2 && a.base_out != nullptr && ok) a.base_out[run_first + it] = cost;
     }
     if (!QUEUED && STRAT == 2 && a.base_out != nullptr && !ok && it < run_len) a.base_out[run_first + it] = ~0ull;
@@ -760,16 +894,17 @@ k_fast_search(FastLaunch a) {
                                     : ((best_cost << a.s.idx_bits) | best_pos);
   if (!QUEUED && STRAT == 2 && a.base_out != nullptr) key = CHM_KEY_NONE;   // the combine kernel takes the argmin
   key = wave_min(key);
-  if (lane == 0) { wave_keys[wave] = key; wave_fit[wave] = n_fit; }
+  if (lane == 0) { wave_keys[wave] = key; wave_fit[wave] = n_fit; wave_eval[wave] = n_eval; }
   __syncthreads();
   if (threadIdx.x == 0) {
     // one atomic of each kind per workgroup, spread over several words (see SearchLaunch)
     const uint32_t slot = (blockIdx.x & a.s.slot_mask) * a.s.slot_stride;
     uint64_t k = wave_keys[0];
-    uint32_t fit = wave_fit[0];
+    uint32_t fit = wave_fit[0], evaluated = wave_eval[0];
 #pragma unroll
-    for (int i = 1; i < BLOCK / 64; ++i) { k = umin64(k, wave_keys[i]); fit += wave_fit[i]; }
+    for (int i = 1; i < BLOCK / 64; ++i) { k = umin64(k, wave_keys[i]); fit += wave_fit[i]; evaluated += wave_eval[i]; }
     if (fit) atomicAdd((unsigned long long *)a.s.feasible + slot, (unsigned long long)fit);
+    if (bounded && evaluated) atomicAdd((unsigned long long *)a.s.evaluated + slot, (unsigned long long)evaluated);
     if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)a.s.result + slot, (unsigned long long)k);
   }
 }
@@ -1119,13 +1254,13 @@ int by_peers(int p, Fn fn) {
   }
 }
 
-// queued: the variant that compacts the partitions that fit through a ring per wave (strategies 0 and 1)
+// queued: the variant that compacts the partitions that fit (and, in a bounded search, may still win) through a ring per wave
 template <int STRAT>
 int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, uint32_t tile_bytes, hipStream_t st, bool queued = false) {
 #define CHM_CASE(SPV)                                                                         \
   case SPV:                                                                                   \
-    if (STRAT != 2 && queued)                                                                 \
-      hipLaunchKernelGGL((k_fast_search<SPV, STRAT, (STRAT != 2)>), dim3(blocks), dim3(BLOCK), 0, st, a); \
+    if (queued)                                                                               \
+      hipLaunchKernelGGL((k_fast_search<SPV, STRAT, true>), dim3(blocks), dim3(BLOCK), 0, st, a); \
     else                                                                                      \
       hipLaunchKernelGGL((k_fast_search<SPV, STRAT>), dim3(blocks), dim3(BLOCK), tile_bytes, st, a); \
     return 0;
@@ -1229,6 +1364,8 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     ff.allreduce = (int32_t)h.allreduce;
     ff.fixed_layers = (k == 1 && h.n_fixed > 0) ? h.p0_max_layers : 0;
     ff.node_exists = h.node_exists;
+    // 24-bit multiplies in the sharper lower bound: micro-batches x (doubled) stage time, plus the prefix, below 2^31
+    ff.lb_prefix = (2 * (h.pf[h.L] + h.pb[h.L]) < (1ll << 24)) && ((int64_t)(h.D * h.M + h.S) * 2 * (h.pf[h.L] + h.pb[h.L]) < (1ll << 31)) ? 1 : 0;
     if (k == 0 && h.allreduce > 0 && h.L > 64) continue;     // colour masks of the specialised kernel hold 64 colours
     for (int j = 0; j <= h.S; ++j) ff.w0[j] = (int32_t)h.pw[h.p0[j]];
     for (int ci = 0; ci < fam.n_cls && ok; ++ci) {
@@ -1237,12 +1374,16 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
       fc.n = c.n; fc.M = c.M; fc.comm_total = (int32_t)((c.n - 1) * h.comm);
       fc.dead0 = fc.dead1 = 1 << 20;
       fc.unit = 1;
+      fc.q_min = c.n > 0 ? c.q[0] : 65536u;
       for (int j = 0; j < c.n; ++j) {
         fc.q[j] = c.q[j];
+        fc.q_min = std::min(fc.q_min, c.q[j]);
         if (c.q[j] != 65536u) fc.unit = 0;
         fc.wlo[j] = (int32_t)h.pw[h.p0[c.host[j]]];
         fc.whi[j] = (int32_t)h.pw[h.p0[c.host[j] + 1]];
       }
+      // every one of the (M + stages) scaled stage times in the bound may round down by up to two
+      fc.lb_slack = fc.unit ? 0 : 2 * (c.M + fam.stages);
       if (k == 0) {
         // which partition stages the chain skips (at most two, the kernel handles no more)
         int n_dead = 0, dead[DEV_MAX_S];
@@ -1268,6 +1409,9 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
         for (int b = 0; b < a; ++b)
           if (h.aff_peers[b] == h.aff_peers[a] && h.aff_total[b] == h.aff_total[a]) same = b;
         t->vec_rows[a] = padded;
+        t->lb_mult[a] = (uint32_t)((h.aff_total[a] + h.aff_peers[a] - 1) / h.aff_peers[a]);
+        t->lb_q[a] = h.aff_q[a][0];
+        for (int i = 1; i < h.aff_peers[a]; ++i) t->lb_q[a] = std::min(t->lb_q[a], h.aff_q[a][i]);
         if (same >= 0) t->vec_off[a] = t->vec_off[same];
         else { t->vec_off[a] = (uint32_t)vec_words; vec_words += ((size_t)padded * stride + 15) / 16 * 16; }
         r_sum += h.aff_R[a];
@@ -1448,17 +1592,27 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   const uint32_t blocks = (uint32_t)((lanes + BLOCK - 1) / BLOCK);
   const int sp = h.fam[a.strategy].stages;
   // pure range search of a family in which a good share of the partitions fails the memory filter
-  const bool queued = a.strategy != 2 && a.ranks == nullptr && a.costs_out == nullptr && base_out == nullptr &&
-                      f->queue_mode != 0 && (f->queue_mode > 0 || f->fit_share[a.strategy] < QUEUE_BELOW_SHARE);
+  // (a bounded search needs the ring: only there a wave decides what to evaluate before it evaluates)
+  const bool pure_range = a.ranks == nullptr && a.costs_out == nullptr && base_out == nullptr;
+  const bool queued = pure_range && (a.incumbent != nullptr ||
+                                     (a.strategy != 2 && f->queue_mode != 0 &&
+                                      (f->queue_mode > 0 || f->fit_share[a.strategy] < QUEUE_BELOW_SHARE)));
+  if (!queued) { fl.s.incumbent = nullptr; fl.s.evaluated = nullptr; }
   int rc;
   if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, tile_bytes, st, queued);
   else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, tile_bytes, st, queued);
-  else rc = launch_by_stages<2>(sp, fl, blocks, tile_bytes, st);
+  else rc = launch_by_stages<2>(sp, fl, blocks, tile_bytes, st, queued);
   if (rc) return rc;
   return hipGetLastError() == hipSuccess ? 0 : -1;
 }
 
 }  // namespace
+
+bool fast_can_bound(const FastState *f, const SearchLaunch &a) {
+  if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return false;
+  if (a.ranks != nullptr || a.cuts != nullptr || a.costs_out != nullptr) return false;
+  return !(a.strategy == 2 && f->split);
+}
 
 int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void *stream) {
   if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return 1;

@@ -52,6 +52,7 @@ struct chm_scenario {
   uint64_t *h_pinned = nullptr;          // pinned staging for the two small device-to-host copies
   uint32_t n_slots = 0;
   bool timing = false;
+  bool bounded = false;         // chm_set_bounded_search
   hipEvent_t ev[8] = {};
   chm_timing last = {};
   FastState fast;                        // shape-specialised search path (chm_fast.hip)
@@ -391,10 +392,45 @@ void nothing_found(chm_best *out) {
 // (cuts != null: the list holds rows of cut positions instead)
 struct Job { int strategy; uint64_t first, count; const uint64_t *ranks; int64_t *costs; const uint8_t *cuts = nullptr; };
 
-// Runs the argmin over the given partition ranges (ascending plan index order).
+// Rank of the partition into `stages` stages whose cuts follow the quantiles of a prefix table (forward +
+// backward time, or memory): cut j at the first position where the prefix reaches j/stages of the total.
+uint64_t balanced_rank(const chm_scenario *s, int stages, const int64_t *prefix_a, const int64_t *prefix_b) {
+  const int L = s->h.L, k = stages - 1;
+  const int64_t total = prefix_a[L] + (prefix_b ? prefix_b[L] : 0);
+  uint64_t rank = 0;
+  int prev = 0;
+  for (int j = 1; j <= k; ++j) {
+    int x = prev + 1;
+    while (x < L - (stages - j) && (prefix_a[x] + (prefix_b ? prefix_b[x] : 0)) * stages < total * j) ++x;
+    rank += s->h.binom[j][x - 1];
+    prev = x;
+  }
+  return rank;
+}
+
+// Runs the argmin over the given partition ranges.
 // With out == null the kernels are only launched (asynchronous scoring into the jobs' cost buffers).
-int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint64_t *position, hipStream_t st) {
+int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, uint64_t *position, hipStream_t st) {
   HIP_TRY(hipSetDevice(s->device));
+  const bool bounded = s->bounded && out != nullptr;
+  // A bounded search prunes against the best cost found so far, so it first looks at a few partitions that
+  // are likely to be good: 64 ranks around the time-balanced and around the memory-balanced partition of
+  // every range (they are scored again as part of the range; equal plans give equal keys).
+  std::vector<Job> jobs;
+  if (bounded) {
+    for (const Job &j : given) {
+      if (j.ranks || j.cuts || j.costs || j.count < (1u << 16)) continue;
+      const int stages = s->h.fam[j.strategy].stages;
+      if (stages < 2) continue;
+      const uint64_t seeds[2] = {balanced_rank(s, stages, s->h.pf, s->h.pb), balanced_rank(s, stages, s->h.pw, nullptr)};
+      for (int i = 0; i < (seeds[0] == seeds[1] ? 1 : 2); ++i) {
+        const uint64_t lo = std::max<uint64_t>(j.first, seeds[i] >= 32 ? seeds[i] - 32 : 0);
+        const uint64_t hi = std::min<uint64_t>(j.first + j.count, seeds[i] + 32);
+        if (lo < hi) jobs.push_back(Job{j.strategy, lo, hi - lo, nullptr, nullptr});
+      }
+    }
+  }
+  jobs.insert(jobs.end(), given.begin(), given.end());
   s->last = chm_timing();
   std::vector<Slot> slots;
   const uint64_t chunk = 1ull << s->idx_bits;
@@ -411,18 +447,26 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
     return CHM_ERR_NO_FEASIBLE;
   }
   if (slots.size() > MAX_SLOTS) return CHM_ERR_OVERFLOW;
-  const bool spread = (slots.size() + 3) * SLOT_WAYS * SLOT_STRIDE <= SLOT_WORDS;
+  const bool spread = (slots.size() + 8) * SLOT_WAYS * SLOT_STRIDE <= SLOT_WORDS;
   const uint32_t ways = spread ? SLOT_WAYS : 1, stride = spread ? SLOT_STRIDE : 1;
   const uint32_t chunk_words = ways * stride;              // words one chunk (or one counter) owns
   const uint32_t key_words = (uint32_t)slots.size() * chunk_words;
   if (chmk_fill_u64(s->d_slots, key_words, CHM_KEY_NONE, st)) return CHM_ERR_HIP;
-  uint64_t *d_count = s->d_slots + key_words;              // three feasibility counters right behind the argmin words
-  if (chmk_fill_u64(d_count, 3 * chunk_words, 0, st)) return CHM_ERR_HIP;
+  // right behind the argmin words: three feasibility counters, three counters of evaluated partitions and
+  // the incumbent cost of a bounded search
+  uint64_t *d_count = s->d_slots + key_words;
+  uint64_t *d_evaluated = d_count + 3 * chunk_words;
+  uint64_t *d_seed_count = d_count + 6 * chunk_words;      // what the seed launches count (not reported)
+  uint64_t *d_incumbent = d_count + 7 * chunk_words;
+  if (chmk_fill_u64(d_count, 7 * chunk_words, 0, st)) return CHM_ERR_HIP;
+  if (chmk_fill_u64(d_incumbent, 1, ~0ull, st)) return CHM_ERR_HIP;
+  bool bounded_used[3] = {false, false, false};
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;
   int ev_i = 1;
   int ev_of[3] = {-1, -1, -1};
   for (const Job &j : jobs) {
+    const bool seed = &j - jobs.data() < (ptrdiff_t)(jobs.size() - given.size());
     for (uint64_t done = 0; done < j.count; done += chunk, ++si) {
       SearchLaunch a;
       a.scn = s->d_scn; a.comp = s->d_comp; a.strategy = j.strategy;
@@ -430,16 +474,22 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
       a.part_count = (uint32_t)std::min<uint64_t>(chunk, j.count - done);
       a.idx_bits = s->idx_bits;
       a.result = s->d_slots + si * chunk_words;
-      a.feasible = d_count + (size_t)j.strategy * chunk_words;
+      a.feasible = seed ? d_seed_count : d_count + (size_t)j.strategy * chunk_words;
       a.slot_mask = ways - 1;
       a.slot_stride = stride;
       a.ranks = j.ranks ? j.ranks + done : nullptr;
       a.cuts = j.cuts ? j.cuts + (size_t)done * (size_t)(s->h.fam[j.strategy].stages - 1) : nullptr;
       a.costs_out = j.costs ? j.costs + done : nullptr;
+      if (bounded && fast_can_bound(&s->fast, a)) {
+        a.incumbent = d_incumbent;
+        a.evaluated = seed ? d_seed_count : d_evaluated + (size_t)j.strategy * chunk_words;
+        bounded_used[j.strategy] = true;
+      }
       int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
       if (rc > 0) rc = chmk_search(a, s->smax, st);
       if (rc) return CHM_ERR_HIP;
     }
+    if (seed) continue;                                   // not part of the accounting
     s->last.partitions[j.strategy] += j.count;
     uint64_t per_part = 1;
     if (j.strategy == 2 && s->h.n_aff) { per_part = 0; for (int a = 0; a < s->h.n_aff; ++a) per_part += s->h.aff_R[a]; }
@@ -447,10 +497,16 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
     if (s->timing && ev_i < 7) { HIP_TRY(hipEventRecord(s->ev[ev_i], st)); ev_of[j.strategy] = ev_i; ++ev_i; }
   }
   if (!out) return CHM_OK;
-  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (size_t)(key_words + 3 * chunk_words) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (size_t)(key_words + 6 * chunk_words) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
   for (int k = 0; k < 3; ++k)
-    for (uint32_t w = 0; w < ways; ++w) s->last.feasible[k] += s->h_pinned[key_words + (size_t)k * chunk_words + (size_t)w * stride];
+    for (uint32_t w = 0; w < ways; ++w) {
+      s->last.feasible[k] += s->h_pinned[key_words + (size_t)k * chunk_words + (size_t)w * stride];
+      s->last.evaluated[k] += s->h_pinned[key_words + (size_t)(3 + k) * chunk_words + (size_t)w * stride];
+    }
+  // kernels that evaluate everything that fits do not count what they evaluate
+  for (int k = 0; k < 3; ++k)
+    if (!bounded_used[k]) s->last.evaluated[k] = s->last.feasible[k];
   if (s->timing) {
     int prev = 0;
     for (int k = 0; k < 3; ++k) {
@@ -463,7 +519,7 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
     }
     HIP_TRY(hipEventElapsedTime(&s->last.total_ms, s->ev[0], s->ev[prev]));
   }
-  // first strict minimum in plan-index order
+  // lowest cost; among equal costs the lowest plan index (strategy, then partition)
   int64_t best_cost = CHM_INFEASIBLE;
   int best_strategy = -1;
   uint64_t best_part = 0;
@@ -476,10 +532,12 @@ int run_search(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uin
     for (uint32_t w = 0; w < ways; ++w) key = std::min(key, s->h_pinned[i * chunk_words + (size_t)w * stride]);
     if (key == CHM_KEY_NONE) continue;
     const int64_t cost = (int64_t)(key >> slots[i].idx_bits);
-    if (cost < best_cost) {
+    const uint64_t part = slots[i].part_first + (key & ((1ull << slots[i].idx_bits) - 1));
+    if (cost < best_cost || (cost == best_cost && (slots[i].strategy < best_strategy ||
+                                                   (slots[i].strategy == best_strategy && part < best_part)))) {
       best_cost = cost;
       best_strategy = slots[i].strategy;
-      best_part = slots[i].part_first + (key & ((1ull << slots[i].idx_bits) - 1));
+      best_part = part;
       best_job = slot_job[i];
     }
   }
@@ -755,6 +813,12 @@ extern "C" int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *s
   s->fast.queue_mode = mode;
   if (share)
     for (int k = 0; k < 3; ++k) share[k] = s->fast.fit_share[k];
+  return CHM_OK;
+}
+
+extern "C" int chm_set_bounded_search(chm_scenario *s, int32_t on) {
+  if (!s) return CHM_ERR_ARG;
+  s->bounded = on != 0;
   return CHM_OK;
 }
 

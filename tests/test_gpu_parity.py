@@ -87,6 +87,16 @@ def test_small_scenarios_every_cost_and_argmin(B, i):
         rc_g, best_g = g.search_best(mask)
         assert rc_g == rc_o, (mask, rc_g, rc_o)
         assert same_plan(best_g, best_o), (mask, best_g, best_o)
+    # bounded search: the same plans, ties included
+    g.set_bounded_search(True)
+    g.set_timing(True)
+    for mask in [7] + [1 << f["strategy"] for f in o.families]:
+        rc_o, best_o = o.search(mask)
+        rc_g, best_g = g.search_best(mask)
+        assert rc_g == rc_o and same_plan(best_g, best_o), ("bounded", mask, best_g, best_o)
+        t = g.get_timing()
+        assert all(e <= f for e, f in zip(t["evaluated"], t["feasible"]))
+    g.set_bounded_search(False)
     for idx in range(0, o.n_plans, max(1, o.n_plans // 25)):
         d_o, d_g = o.decode(idx), g.decode_plan(idx)
         d_o.update(cost=0, t_step_us=0, t_trans_us=0)      # the library's decoding is structural only
@@ -166,6 +176,44 @@ def test_filter_compaction_modes_agree_with_the_oracle(B, name):
                 g.set_filter_compaction(mode)
                 rc_g, best_g = g.search_range(f["strategy"], first, width)
                 assert rc_g == 0 and same_plan(best_g, best_o)
+
+
+@pytest.mark.parametrize("name", [c[0] for c in COMPACTION])
+def test_bounded_search_returns_the_exhaustive_winner(B, name):
+    """chm_set_bounded_search skips partitions whose lower bound of the cost lies above the best cost found so
+    far: same winner as the oracle on seeded windows and as the exhaustive search over the whole space, for every
+    strategy and for all of them together; fewer partitions evaluated than fit, never more."""
+    sc = dict(COMPACTION)[name]()
+    o, g = O.Scenario(sc), B.Scenario(sc)
+    g.set_timing(True)
+    rng = np.random.default_rng(12)
+    reachable = all(f["n_part"] <= 2 * 10 ** 8 for f in o.families)
+    for f in o.families:
+        width = min(f["n_part"], 30000 if f["n_reroute"] < 1000 else 300)
+        firsts = {0, f["n_part"] - width} | {int(rng.integers(0, f["n_part"] - width + 1)) for _ in range(3)}
+        for first in sorted(firsts):
+            rc_o, best_o, _ = o.search_range(f["strategy"], first, width)
+            g.set_bounded_search(True)
+            rc_g, best_g = g.search_range(f["strategy"], first, width)
+            t = g.get_timing()
+            assert rc_g == rc_o and same_plan(best_g, best_o), (name, f["strategy"], first, best_g, best_o)
+            assert t["evaluated"][f["strategy"]] <= t["feasible"][f["strategy"]]
+            assert rc_g != 0 or t["evaluated"][f["strategy"]] >= 1
+    if not reachable:
+        return
+    masks = [7] + [1 << f["strategy"] for f in o.families]
+    for mask in masks:
+        g.set_bounded_search(False)
+        rc_e, best_e = g.search_best(mask)
+        t_e = g.get_timing()
+        g.set_bounded_search(True)
+        rc_b, best_b = g.search_best(mask)
+        t_b = g.get_timing()
+        assert rc_b == rc_e and same_plan(best_b, best_e), (name, mask, best_b, best_e)
+        assert all(b <= e for b, e in zip(t_b["feasible"], t_e["feasible"])) and t_e["evaluated"] == t_e["feasible"]
+        assert all(b <= e for b, e in zip(t_b["evaluated"], t_e["evaluated"]))
+        print("bounded", name, "mask", mask, "fit", t_b["feasible"], "evaluated", t_b["evaluated"],
+              "ms", [round(x, 3) for x in t_e["family_ms"]], "->", [round(x, 3) for x in t_b["family_ms"]], flush=True)
 
 
 def test_equal_costs_in_an_explicit_list_go_to_the_lowest_position(B):

@@ -69,6 +69,10 @@ def test_makespan_lower_bounds_and_monotonicity():
         T = O.makespan_1f1b(F, B, M)
         assert T >= M * int((F + B).max())            # the busiest stage runs M forwards and M backwards
         assert T >= int(F.sum() + B.sum())            # one micro-batch crosses every stage twice
+        # stage s waits for the forwards of the stages ahead, runs its 2M operations, and the backwards of the
+        # stages ahead follow its last one (the bound a bounded search on the GPU prunes with)
+        C = F + B
+        assert T >= max(M * int(C[s]) + int(C[:s].sum()) for s in range(S))
         assert T <= (S + M - 1) * (int(F.max()) + int(B.max()))
         s = int(rng.integers(0, S))
         F2, B2 = F.copy(), B.copy()
