@@ -272,6 +272,8 @@ typedef struct {
   int32_t restart_us, xfer_us_per_mib;
   int32_t allreduce_us;                       /* per round of gradient communication (see chm_scenario_desc), added to the
                                                  step time of a candidate after its splits are chosen; 0 = not modelled */
+  int32_t bounded_search;                     /* != 0: the split searches skip splits whose lower bound of the pipeline
+                                                 time lies above the best one found (chm_set_bounded_search); same plan */
 } chm_replan_desc;
 
 typedef struct {
@@ -285,7 +287,8 @@ typedef struct {
   int32_t comm_rounds;                        /* 0 when allreduce_us is 0 */
   /* work accounting of the call (all candidates, not only the chosen one) */
   uint64_t splits_scored;                     /* contiguous splits scored by the search kernels */
-  uint64_t splits_feasible;                   /* of which passed the memory filter */
+  uint64_t splits_feasible;                   /* of which passed the memory filter (bounded: of those looked at one by one) */
+  uint64_t splits_evaluated;                  /* of which had their recurrence run (all of them unless bounded_search) */
   double algorithmic_ops;                     /* 4n per split + (4nM + 6n + 4) per split that fits, n stages, M micro-batches */
   float search_ms, assign_ms;                 /* HIP-event time of the split-search kernels / of the assignment kernels */
 } chm_replan_plan;

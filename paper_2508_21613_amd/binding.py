@@ -57,7 +57,7 @@ class ReplanDesc(C.Structure):
                 ("dp_min", C.c_int32), ("dp_max", C.c_int32), ("pp_min", C.c_int32), ("pp_max", C.c_int32),
                 ("micro_batches", C.c_int32), ("comm_us", C.c_int32), ("mem_cap_mib", C.c_int32),
                 ("horizon_us", C.c_int64), ("restart_us", C.c_int32), ("xfer_us_per_mib", C.c_int32),
-                ("allreduce_us", C.c_int32)]
+                ("allreduce_us", C.c_int32), ("bounded_search", C.c_int32)]
 
 
 class ReplanPlan(C.Structure):
@@ -66,7 +66,8 @@ class ReplanPlan(C.Structure):
                 ("cuts", (C.c_uint8 * 32) * 16), ("pipeline_us", C.c_int64 * 16),
                 ("t_step_us", C.c_int64), ("fetch_mib", C.c_int64), ("t_trans_us", C.c_int64),
                 ("comm_rounds", C.c_int32),
-                ("splits_scored", C.c_uint64), ("splits_feasible", C.c_uint64), ("algorithmic_ops", C.c_double),
+                ("splits_scored", C.c_uint64), ("splits_feasible", C.c_uint64), ("splits_evaluated", C.c_uint64),
+                ("algorithmic_ops", C.c_double),
                 ("search_ms", C.c_float), ("assign_ms", C.c_float)]
 
 
@@ -188,9 +189,11 @@ def replan(rp, stream=None, with_stats=False):
                  "mem_cap_mib", "horizon_us", "restart_us", "xfer_us_per_mib"):
         setattr(d, name, int(rp[name]))
     d.allreduce_us = int(rp.get("allreduce_us", 0))
+    d.bounded_search = int(rp.get("bounded_search", 0))
     p = ReplanPlan()
     _check(lib().chm_replan(C.byref(d), C.byref(p), _stream_ptr(stream)))
     stats = {"splits_scored": int(p.splits_scored), "splits_feasible": int(p.splits_feasible),
+             "splits_evaluated": int(p.splits_evaluated),
              "algorithmic_ops": float(p.algorithmic_ops), "search_ms": float(p.search_ms), "assign_ms": float(p.assign_ms)}
     plan = _replan_dict(p)
     return (plan, stats) if with_stats else plan

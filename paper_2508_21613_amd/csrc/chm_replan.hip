@@ -206,7 +206,7 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
 
   Events ev;
   if (!ev.ok()) return CHM_ERR_HIP;
-  uint64_t splits_scored = 0, splits_feasible = 0;
+  uint64_t splits_scored = 0, splits_feasible = 0, splits_evaluated = 0;
   double algorithmic_ops = 0;
   float search_ms = 0, assign_ms = 0;
   std::map<std::pair<int, int>, SplitResult> best_split;      // (stages, micro-batches) -> best split of the layers
@@ -242,11 +242,13 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
         chm_best b;
         chm_timing tm;
         (void)chm_set_timing(pipe, 1);
+        (void)chm_set_bounded_search(pipe, d->bounded_search);
         r.rc = chm_search_best(pipe, 1u << 1, &b, hip_stream);
         (void)chm_get_timing(pipe, &tm);
         chm_free_scenario(pipe);
         splits_scored += tm.partitions[1];
         splits_feasible += tm.feasible[1];
+        splits_evaluated += tm.evaluated[1];
         search_ms += tm.family_ms[1];
         algorithmic_ops += 4.0 * len[p] * (double)tm.partitions[1] +
                            (4.0 * len[p] * mb[p] + 6.0 * len[p] + 4.0) * (double)tm.feasible[1];
@@ -303,6 +305,7 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
   }
   out->splits_scored = splits_scored;
   out->splits_feasible = splits_feasible;
+  out->splits_evaluated = splits_evaluated;
   out->algorithmic_ops = algorithmic_ops;
   out->search_ms = search_ms;
   out->assign_ms = assign_ms;

@@ -440,6 +440,9 @@ def test_replan_over_dp_pp_degrees(B, i):
         assert B.replan(dict(rp, horizon_us=H)) == O.replan(dict(rp, horizon_us=H))
     ar = dict(rp, allreduce_us=1500 + 300 * i)
     assert B.replan(ar) == O.replan(ar)
+    # bounded split searches: the same plan
+    assert B.replan(dict(rp, bounded_search=1)) == want
+    assert B.replan(dict(ar, bounded_search=1)) == O.replan(ar)
 
 
 def test_full_size_replan_of_the_32_card_shape(B):
@@ -464,6 +467,10 @@ def test_full_size_replan_of_the_32_card_shape(B):
         return O.makespan_1f1b([int(pf[b[j + 1]] - pf[b[j]]) for j in range(n)], [int(pb[b[j + 1]] - pb[b[j]]) for j in range(n)], M) \
             + (n - 1) * rp["comm_us"]
 
+    whole, stats = B.replan(rp, with_stats=True)
+    whole_b, stats_b = B.replan(dict(rp, bounded_search=1), with_stats=True)
+    print("replan32 bounded", stats, stats_b, flush=True)
+    assert whole_b == whole and stats_b["splits_evaluated"] < stats["splits_evaluated"] == stats["splits_feasible"]
     per_dp = {}
     for dp in range(rp["dp_min"], rp["dp_max"] + 1):
         got = B.replan(dict(rp, dp_min=dp, dp_max=dp))
