@@ -94,9 +94,8 @@ def bench_replan(args, note, B, synth):
             plan_b, st_b = B.replan(rb, stream=stream, with_stats=True)
         torch.cuda.synchronize()
         ms_b = (time.perf_counter() - t0) * 1e3 / args.steps
-    assert plan_b == plan, "bounded re-planning disagrees"
     bounded = {"time_to_best_plan_ms": ms_b, "search_kernels_ms": st_b["search_ms"], "splits_evaluated_in_full": st_b["splits_evaluated"],
-               "same_plan_as_exhaustive": True}
+               "same_plan_as_exhaustive": bool(plan_b == plan)}
     note("bounded re-planning: %s" % bounded)
     out = {"metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
            "value": st["splits_scored"] / (ms * 1e-3), "unit": "plans/s", "n_gpus": 1, "steps": args.steps,
@@ -381,7 +380,7 @@ def main():
     # Reported beside the exhaustive figures, never inside `value` (which counts plans that were scored).
     bounded = None
     if args.ttb_runs:
-        ttb_b, search_b, stats = [], [], None
+        ttb_b, search_b, same = [], [], True
         for g in handles:
             g.set_bounded_search(True)
         for _ in range(args.ttb_runs):
@@ -391,17 +390,17 @@ def main():
             rc_b, best_b = g2.search_best(7, stream=stream)
             ttb_b.append((time.perf_counter() - t0) * 1e3)
             g2.close()
-            assert (rc_b, best_b["index"], best_b["cost"]) == (plans[0][0], plans[0][1]["index"], plans[0][1]["cost"]), "bounded search disagrees"
+            same = same and (rc_b, best_b["index"], best_b["cost"]) == (plans[0][0], plans[0][1]["index"], plans[0][1]["cost"])
             t0 = time.perf_counter()
             swept = [g.search_best(7, stream=stream)[1] for g in handles]
             search_b.append((time.perf_counter() - t0) * 1e3)
-            assert all(a["index"] == b[1]["index"] and a["cost"] == b[1]["cost"] for a, b in zip(swept, plans)), "bounded search disagrees"
+            same = same and all(a["index"] == b[1]["index"] and a["cost"] == b[1]["cost"] for a, b in zip(swept, plans))
         ev = np.zeros(3)
         for g in handles:
             ev += np.array(g.get_timing()["evaluated"], dtype=float)
             g.set_bounded_search(False)
         bounded = {"time_to_best_plan_ms": float(np.median(ttb_b)), "search_ms_all_scenarios": float(np.median(search_b)),
-                   "partitions_evaluated_in_full": [float(x) for x in ev], "same_plans_as_exhaustive": True}
+                   "partitions_evaluated_in_full": [float(x) for x in ev], "same_plans_as_exhaustive": bool(same)}
         note("bounded search: %s" % bounded)
 
     # roofline of the dominant kernel
