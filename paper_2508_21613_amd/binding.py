@@ -92,6 +92,14 @@ def lib():
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise RuntimeError("libchm.so is not built: run `python -m paper_2508_21613_amd.build`")
+        # torch brings its own copy of the HIP runtime and must reach the device before the library's does:
+        # initialised the other way round, torch reports that no GPU is available
+        try:
+            import torch
+            if torch.cuda.is_available():
+                torch.cuda.init()
+        except ImportError:
+            pass
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.chm_load_scenario.argtypes = [C.POINTER(Desc), C.POINTER(vp)]

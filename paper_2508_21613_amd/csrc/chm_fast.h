@@ -2,6 +2,7 @@
 #ifndef CHM_FAST_H
 #define CHM_FAST_H
 #include "chm_dev.h"
+#include <vector>
 
 enum {
   FAST_MAX_P = 8,            // peers per affected stage the specialised sweeps are instantiated for
@@ -78,7 +79,49 @@ struct FastState {
   void *d_cut_list = nullptr;               // [entry] cut positions of the entries that fit in memory, 16 bytes each
   uint32_t *d_cut_pos = nullptr;            // [entry] their list positions
   uint32_t *d_cut_count = nullptr;          // [workgroup region] how many of its slots are filled
+  // scratch of the candidate path of the bounded search; grown to what a search needs
+  void *d_cand_list = nullptr;              // [candidate] cut positions, 16 bytes each
+  uint32_t *d_cand_pos = nullptr;           // [candidate] its index
+  uint32_t *d_cand_count = nullptr;         // [workgroup] candidates in its region of BLOCK slots
+  uint64_t cand_capacity = 0;
+  uint64_t *d_cand_ways = nullptr;          // CandidateSet::ways on the device
+  uint8_t *d_cand_low = nullptr;            // CandidateSet::low_pair on the device
+  size_t cand_ways_capacity = 0;
+  uint64_t cand_serial = 0;                 // CandidateSet::serial of the tables the device holds
 };
+
+// Bounded search, candidate path.  Every term of the lower bound of a plan's cost belongs to one stage
+// (micro-batches x its time + the time of the layers ahead of it, its memory) or, under redundant computation,
+// to one node's pair of adjacent stages, and each is monotone in where the stage (or pair) starts: with its end
+// fixed, a later start only lowers it.  The partitions whose bound does not exceed the incumbent are therefore
+// exactly those whose every stage s starts at or after low_single[s][end] and whose every pair starts at or
+// after low_pair[s][end of the pair]: a set that can be counted and enumerated without touching the others.
+// ways[s][a][b] = number of ways to place the cuts below a so that stages 0..s obey all of that, stage s being
+// layers [a, b).  Candidates are numbered in ascending partition rank (highest cut most significant).
+struct CandidateSet {
+  int stages = 0, L = 0;
+  std::vector<uint64_t> ways;               // [stages][L+1][L+1]
+  std::vector<uint8_t> low_pair;            // [stages][L+1]: lowest start of the pair (stages s, s+1) that ends at e; 0 = no such limit
+  uint64_t total = 0;                       // candidates; 0 also when the bound excludes the whole family
+  uint64_t serial = 0;                      // distinguishes the sets a process builds (the device keeps the last one uploaded)
+};
+enum {
+  CAND_DIRECT = 1 << 17,      // up to this many candidates are always enumerated (cheaper than any range search)
+  CAND_MAX = 1 << 26,         // and up to this many when the family is too large for a range search,
+  CAND_PASS = 1 << 22,        // enumerated and evaluated this many at a time
+  CAND_SAMPLE = 1 << 17       // candidates evaluated per round of tightening the incumbent (see run_search)
+};
+
+// Counts the candidates of a strategy against an incumbent cost (host).  Returns false when the strategy has no
+// specialised kernel, is swept by the split rerouting path, or the tables are out of the candidate path's limits.
+bool fast_candidates_build(const FastState *f, const DevScenario &h, int strategy, uint64_t incumbent, CandidateSet *out);
+// Enumerates the candidates on the device and runs the search kernel over them; the key written to a.result
+// carries the candidate's index.  Same return convention as fast_search.
+// Launch index i stands for candidate (a.part_first + i) * stride, a.part_count of them (at most CAND_PASS).
+int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunch &a, const CandidateSet &cs, uint64_t stride,
+                           void *stream);
+// Cut positions of candidate `index` (host).
+void fast_candidate_cuts(const CandidateSet &cs, uint64_t index, uint8_t *cuts);
 
 // Decides per strategy whether a specialised kernel applies and uploads its tables.
 // Returns 0, or non-zero on a failed HIP call.

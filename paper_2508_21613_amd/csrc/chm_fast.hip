@@ -27,6 +27,13 @@
 #include <vector>
 
 #include "chm_fast.h"
+#include "chm_pool.h"
+
+// typed front ends of the caching allocator (chm_pool.h)
+template <typename T>
+static inline bool pool_take(T *&p, size_t bytes) { p = (T *)pool_device_alloc(bytes); return p != nullptr; }
+template <typename T>
+static inline bool pool_take_pinned(T *&p, size_t bytes) { p = (T *)pool_pinned_alloc(bytes); return p != nullptr; }
 
 namespace {
 
@@ -905,6 +912,9 @@ k_fast_search(FastLaunch a) {
     for (int i = 1; i < BLOCK / 64; ++i) { k = umin64(k, wave_keys[i]); fit += wave_fit[i]; evaluated += wave_eval[i]; }
     if (fit) atomicAdd((unsigned long long *)a.s.feasible + slot, (unsigned long long)fit);
     if (bounded && evaluated) atomicAdd((unsigned long long *)a.s.evaluated + slot, (unsigned long long)evaluated);
+    // a search over a list of candidates of a bounded search makes its best cost known to what follows
+    if (!QUEUED && a.s.incumbent != nullptr && k != CHM_KEY_NONE)
+      atomicMin((unsigned long long *)a.s.incumbent, (unsigned long long)(k >> a.s.idx_bits));
     if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)a.s.result + slot, (unsigned long long)k);
   }
 }
@@ -1007,6 +1017,62 @@ __global__ void __launch_bounds__(BLOCK) k_list_filter(ListFilter a) {
   }
   __syncthreads();
   if (threadIdx.x == 0) a.cut_count[blockIdx.x] = filled;
+}
+
+// ---------------------------------------------------------------------------------------
+// bounded search: enumeration of the candidates (see CandidateSet)
+// ---------------------------------------------------------------------------------------
+struct CandidateEnum {
+  const uint64_t *ways;         // [stages][L+1][L+1]
+  const uint8_t *low_pair;      // [stages][L+1]
+  int32_t stages, L;
+  uint32_t total;               // candidates of this launch
+  uint64_t first, stride;       // launch index i stands for candidate (first + i) * stride
+  uint4 *cut_list;              // [candidate] cut positions packed into bytes
+  uint32_t *cut_pos;            // [candidate] = its index
+  uint32_t *cut_count;          // [workgroup] candidates in its region of BLOCK slots
+};
+
+// Candidate `index` of the set, in ascending partition rank: the start of the last stage is chosen first
+// (the candidates that share it form a block of ways[last][a][L] indices), then the start of the stage below
+// it among those the pair limit allows, and so on down.  Every scan is bounded by the stage above it, so the
+// cuts stay a valid partition whatever the tables hold.
+__global__ void __launch_bounds__(BLOCK) k_enumerate_candidates(CandidateEnum e) {
+  const uint32_t gid = blockIdx.x * BLOCK + threadIdx.x;
+  if (threadIdx.x == 0) {
+    const uint32_t first = blockIdx.x * BLOCK;
+    e.cut_count[blockIdx.x] = first >= e.total ? 0u : (e.total - first < BLOCK ? e.total - first : (uint32_t)BLOCK);
+  }
+  if (gid >= e.total) return;
+  const int W = e.L + 1;
+  uint64_t idx = (e.first + gid) * e.stride;
+  uint32_t words[4] = {0, 0, 0, 0};
+  int s = e.stages - 1;                   // the stage whose start is being chosen
+  int end = e.L;                          // its end
+  int start = s;                          // at least one layer for every stage below
+  for (; start < end - 1; ++start) {
+    const uint64_t blk = e.ways[((size_t)s * W + start) * W + end];
+    if (idx < blk) break;
+    idx -= blk;
+  }
+  for (;;) {
+    words[(s - 1) >> 2] |= (uint32_t)start << (8 * ((s - 1) & 3));
+    if (s == 1) break;
+    // the stage below: layers [below, start), its pair with stage s ends at `end`
+    const int lo = (int)e.low_pair[(size_t)(s - 1) * W + end];
+    int below = lo > s - 1 ? lo : s - 1;
+    for (; below < start - 1; ++below) {
+      const uint64_t blk = e.ways[((size_t)(s - 1) * W + below) * W + start];
+      if (idx < blk) break;
+      idx -= blk;
+    }
+    if (below > start - 1) below = start - 1;
+    end = start;
+    start = below;
+    --s;
+  }
+  e.cut_list[gid] = make_uint4(words[0], words[1], words[2], words[3]);
+  e.cut_pos[gid] = gid;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -1487,10 +1553,10 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     if (!f->usable[2]) f->split = false;
   }
   if (runs.empty()) runs.assign(8, 0);
-  bool up = hipMalloc((void **)&f->d_tables, sizeof(FastTables)) == hipSuccess;
-  up = up && hipMalloc((void **)&f->d_runs, runs.size() * sizeof(uint32_t)) == hipSuccess;
+  bool up = pool_take(f->d_tables, sizeof(FastTables));
+  up = up && pool_take(f->d_runs, runs.size() * sizeof(uint32_t));
   up = up && hipMemcpy(f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
-  up = up && hipMalloc((void **)&f->d_vecs, vec_words * sizeof(uint32_t)) == hipSuccess;
+  up = up && pool_take(f->d_vecs, vec_words * sizeof(uint32_t));
   up = up && hipMemcpy(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice) == hipSuccess;
   if (up && f->usable[2]) {
     for (int a = 0; a < h.n_aff; ++a) {
@@ -1500,7 +1566,7 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     }
     up = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
   }
-  if (up && f->usable[2]) up = hipMalloc((void **)&f->d_rowkey, DEV_MAX_AFF * sizeof(uint64_t)) == hipSuccess;
+  if (up && f->usable[2]) up = pool_take(f->d_rowkey, DEV_MAX_AFF * sizeof(uint64_t));
   return up ? 0 : 1;
 }
 
@@ -1511,18 +1577,18 @@ namespace {
 bool ensure_scratch(FastState *f) {
   if (f->d_base && f->d_weights && f->d_pen) return true;
   bool ok = true;
-  if (!f->d_base) ok = ok && hipMalloc((void **)&f->d_base, (size_t)FAST_SUB * sizeof(uint64_t)) == hipSuccess;
-  if (!f->d_weights) ok = ok && hipMalloc((void **)&f->d_weights, (size_t)FAST_SUB * DEV_MAX_AFF * 8 * sizeof(uint32_t)) == hipSuccess;
-  if (!f->d_pen) ok = ok && hipMalloc((void **)&f->d_pen, (size_t)FAST_SUB * DEV_MAX_AFF * sizeof(uint32_t)) == hipSuccess;
+  if (!f->d_base) ok = ok && pool_take(f->d_base, (size_t)FAST_SUB * sizeof(uint64_t));
+  if (!f->d_weights) ok = ok && pool_take(f->d_weights, (size_t)FAST_SUB * DEV_MAX_AFF * 8 * sizeof(uint32_t));
+  if (!f->d_pen) ok = ok && pool_take(f->d_pen, (size_t)FAST_SUB * DEV_MAX_AFF * sizeof(uint32_t));
   return ok;
 }
 
 bool ensure_list_scratch(FastState *f) {
   if (f->d_cut_list && f->d_cut_pos && f->d_cut_count) return true;
   bool ok = true;
-  if (!f->d_cut_list) ok = ok && hipMalloc(&f->d_cut_list, (size_t)LIST_SUB * sizeof(uint4)) == hipSuccess;
-  if (!f->d_cut_pos) ok = ok && hipMalloc((void **)&f->d_cut_pos, (size_t)LIST_SUB * sizeof(uint32_t)) == hipSuccess;
-  if (!f->d_cut_count) ok = ok && hipMalloc((void **)&f->d_cut_count, (size_t)(LIST_SUB / (BLOCK * FILTER_TILES)) * sizeof(uint32_t)) == hipSuccess;
+  if (!f->d_cut_list) ok = ok && pool_take(f->d_cut_list, (size_t)LIST_SUB * sizeof(uint4));
+  if (!f->d_cut_pos) ok = ok && pool_take(f->d_cut_pos, (size_t)LIST_SUB * sizeof(uint32_t));
+  if (!f->d_cut_count) ok = ok && pool_take(f->d_cut_count, (size_t)(LIST_SUB / (BLOCK * FILTER_TILES)) * sizeof(uint32_t));
   return ok;
 }
 
@@ -1607,6 +1673,183 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
 }
 
 }  // namespace
+
+namespace {
+int64_t scale_floor_host(int64_t x, uint32_t q) {
+  return q == 65536u ? x : std::max<int64_t>(0, ((x * (int64_t)q) >> 16) - 1);
+}
+}  // namespace
+
+bool fast_candidates_build(const FastState *f, const DevScenario &h, int k, uint64_t incumbent, CandidateSet *out) {
+  out->total = 0;
+  if (k < 0 || k > 2 || !f->usable[k] || (k == 2 && f->split) || incumbent == ~0ull) return false;
+  const FastTables &t = f->h_tables;
+  const FastFamily &ff = t.fam[k];
+  const int sp = h.fam[k].stages, L = h.L;
+  if (sp < 2 || sp > 16 || L > 255) return false;
+  const size_t W = (size_t)L + 1;
+  out->stages = sp;
+  out->L = L;
+  out->ways.assign((size_t)sp * W * W, 0);
+  out->low_pair.assign((size_t)sp * W, 0);
+  if (incumbent < (uint64_t)h.reconf[k]) return true;                     // nothing can reach it
+  const int64_t limit = (int64_t)((incumbent - (uint64_t)h.reconf[k]) / (uint64_t)h.K);   // largest step time that may still win
+  if ((int64_t)ff.fixed_step > limit) return true;
+  auto pc = [&](int x) { return h.pf[x] + h.pb[x]; };
+  // stage s = layers [b, e) taken alone (strategies 1 and 2): lower bound of the step time it implies, and its memory
+  auto single_ok = [&](int s, int b, int e) {
+    if (k == 0) return true;
+    const int coef = ff.mem_coef[s];
+    if (coef >= 0 && (h.pw[e] - h.pw[b]) + (ff.has_act ? (h.pa[e] - h.pa[b]) * coef : 0) > h.cap) return false;
+    const int64_t c = pc(e) - pc(b);
+    int64_t lb = 0;
+    for (int ci = 0; ci < ff.n_cls; ++ci) {
+      const FastClass &cl = ff.cls[ci];
+      int64_t v = (int64_t)cl.M * c + pc(b);
+      // At nominal speed also the wait before the stage's first backward counts: that one cannot start before
+      // micro-batch 0 has gone forward through every stage and backward through the stages behind this one,
+      // by which time the stage has at most run its warm-up forwards and one more (stages - 1 - s + 1 of them)
+      if (cl.unit && cl.M >= sp - s) v += std::max<int64_t>(0, (pc(L) - pc(e)) - (int64_t)(sp - 1 - s) * (h.pf[e] - h.pf[b]));
+      lb = std::max(lb, std::max<int64_t>(0, scale_floor_host(v, cl.q_min) - cl.lb_slack) + cl.comm_total);
+    }
+    if (ff.allreduce > 0) lb += (int64_t)ff.allreduce * (e - b);
+    if (k == 2)
+      for (int a = 0; a < h.n_aff; ++a)
+        if (h.aff_stage[a] == s) lb += (int64_t)t.lb_mult[a] * scale_floor_host(c, t.lb_q[a]);
+    return lb <= limit;
+  };
+  // node s of the ring under redundant computation runs stages s and s+1 = layers [a, e)
+  auto pair_ok = [&](int s, int a, int e) {
+    const int coef = ff.mem_coef[s];
+    if (coef >= 0 && (h.pw[e] - h.pw[a]) + (ff.has_act ? (h.pa[e] - h.pa[a]) * coef : 0) > h.cap) return false;
+    const int64_t c = pc(e) - pc(a);
+    for (int ci = 0; ci < ff.n_cls; ++ci) {
+      const FastClass &cl = ff.cls[ci];
+      if (s == cl.dead0 || s == cl.dead1) continue;
+      if (std::max<int64_t>(0, scale_floor_host((int64_t)cl.M * c, cl.q_min) - cl.lb_slack) + cl.comm_total > limit) return false;
+    }
+    return true;
+  };
+  if (k == 0) {
+    // both terms fall as the pair starts later: the allowed starts are those from the first one on from which all pass
+    for (int s = 0; s + 1 < sp; ++s)
+      for (int e = s + 2; e <= L; ++e) {
+        int a = e - 2;
+        while (a >= 0 && pair_ok(s, a, e)) --a;
+        out->low_pair[(size_t)s * W + e] = (uint8_t)(a + 1);              // e - 1: no start passes
+      }
+  }
+  auto ways = [&](int s, int a, int b) -> uint64_t & { return out->ways[((size_t)s * W + a) * W + b]; };
+  for (int b = 1; b <= L - (sp - 1); ++b)
+    if (single_ok(0, 0, b)) ways(0, 0, b) = 1;
+  std::vector<uint64_t> from(W + 1);
+  for (int s = 1; s < sp; ++s) {
+    for (int a = s; a <= L - (sp - s); ++a) {
+      // from[x] = ways to arrange stages 0..s-1 with stage s-1 = [x', a), x' >= x
+      from[a] = 0;
+      for (int x = a - 1; x >= 0; --x) from[x] = from[x + 1] + ways(s - 1, x, a);
+      const int b_lo = a + 1, b_hi = s == sp - 1 ? L : L - (sp - 1 - s);
+      for (int b = (s == sp - 1 ? L : b_lo); b <= b_hi; ++b) {
+        if (!single_ok(s, a, b)) continue;
+        const int lo = std::min<int>(std::max<int>(out->low_pair[(size_t)(s - 1) * W + b], s - 1), a);
+        ways(s, a, b) = from[lo];
+      }
+    }
+  }
+  uint64_t total = 0;
+  for (int a = sp - 1; a < L; ++a) total += ways(sp - 1, a, L);
+  out->total = total;
+  static uint64_t next_serial = 0;
+  out->serial = __atomic_add_fetch(&next_serial, 1, __ATOMIC_RELAXED);
+  return true;
+}
+
+void fast_candidate_cuts(const CandidateSet &cs, uint64_t idx, uint8_t *cuts) {
+  const size_t W = (size_t)cs.L + 1;
+  int s = cs.stages - 1, end = cs.L, start = s;
+  for (; start < end - 1; ++start) {
+    const uint64_t blk = cs.ways[((size_t)s * W + start) * W + end];
+    if (idx < blk) break;
+    idx -= blk;
+  }
+  for (;;) {
+    cuts[s - 1] = (uint8_t)start;
+    if (s == 1) break;
+    int below = std::max<int>(cs.low_pair[(size_t)(s - 1) * W + end], s - 1);
+    for (; below < start - 1; ++below) {
+      const uint64_t blk = cs.ways[((size_t)(s - 1) * W + below) * W + start];
+      if (idx < blk) break;
+      idx -= blk;
+    }
+    if (below > start - 1) below = start - 1;
+    end = start;
+    start = below;
+    --s;
+  }
+}
+
+int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunch &a, const CandidateSet &cs, uint64_t stride,
+                           void *stream) {
+  if (cs.total == 0 || a.part_count == 0) return 0;
+  if (a.part_count > CAND_PASS || a.idx_bits < 23 || stride < 1 || (a.part_first + a.part_count - 1) * stride >= cs.total) return 1;
+  hipStream_t st = (hipStream_t)stream;
+  const uint32_t total = a.part_count;
+  const uint32_t blocks = (total + BLOCK - 1) / BLOCK;
+  if (f->cand_capacity < total) {
+    if (f->d_cand_list) pool_release(f->d_cand_list);
+    if (f->d_cand_pos) pool_release(f->d_cand_pos);
+    if (f->d_cand_count) pool_release(f->d_cand_count);
+    f->d_cand_list = nullptr; f->d_cand_pos = nullptr; f->d_cand_count = nullptr; f->cand_capacity = 0;
+    const uint64_t cap = std::max<uint64_t>(1 << 16, (uint64_t)blocks * BLOCK);
+    bool ok = pool_take(f->d_cand_list, cap * sizeof(uint4));
+    ok = ok && pool_take(f->d_cand_pos, cap * sizeof(uint32_t));
+    ok = ok && pool_take(f->d_cand_count, cap / BLOCK * sizeof(uint32_t));
+    if (!ok) return -1;
+    f->cand_capacity = cap;
+  }
+  if (f->cand_ways_capacity < cs.ways.size()) {
+    if (f->d_cand_ways) pool_release(f->d_cand_ways);
+    if (f->d_cand_low) pool_release(f->d_cand_low);
+    f->d_cand_ways = nullptr; f->d_cand_low = nullptr; f->cand_ways_capacity = 0; f->cand_serial = 0;
+    bool ok = pool_take(f->d_cand_ways, cs.ways.size() * sizeof(uint64_t));
+    ok = ok && pool_take(f->d_cand_low, cs.ways.size());      // more than stages x (L+1)
+    if (!ok) return -1;
+    f->cand_ways_capacity = cs.ways.size();
+  }
+  if (f->cand_serial != cs.serial) {
+    // (pageable host memory: both copies have left the vectors when the calls return)
+    f->cand_serial = 0;
+    if (hipMemcpyAsync(f->d_cand_ways, cs.ways.data(), cs.ways.size() * sizeof(uint64_t), hipMemcpyHostToDevice, st) != hipSuccess) return -1;
+    if (hipMemcpyAsync(f->d_cand_low, cs.low_pair.data(), cs.low_pair.size(), hipMemcpyHostToDevice, st) != hipSuccess) return -1;
+    f->cand_serial = cs.serial;
+  }
+  CandidateEnum e;
+  e.ways = f->d_cand_ways; e.low_pair = f->d_cand_low; e.stages = cs.stages; e.L = cs.L; e.total = total; e.first = a.part_first; e.stride = stride;
+  e.cut_list = (uint4 *)f->d_cand_list; e.cut_pos = f->d_cand_pos; e.cut_count = f->d_cand_count;
+  hipLaunchKernelGGL(k_enumerate_candidates, dim3(blocks), dim3(BLOCK), 0, st, e);
+  FastLaunch fl;
+  fl.s = a;
+  fl.s.ranks = nullptr;
+  fl.s.cuts = nullptr;
+  fl.s.costs_out = nullptr;
+  fl.s.part_first = 0;
+  fl.s.part_count = total;
+  fl.s.evaluated = nullptr;
+  fl.tab = f->d_tables;
+  fl.vecs = f->d_vecs;
+  fl.runs = f->d_runs;
+  fl.per_lane = 1;                        // one round per region of BLOCK candidates
+  fl.base_out = nullptr;
+  fl.weights_out = nullptr;
+  fl.cut_list = (const uint4 *)f->d_cand_list;
+  fl.cut_pos = f->d_cand_pos;
+  fl.cut_count = f->d_cand_count;
+  const int sp = h.fam[a.strategy].stages;
+  const int rc = a.strategy == 0 ? launch_by_stages<0>(sp, fl, blocks, 0, st)
+                 : a.strategy == 1 ? launch_by_stages<1>(sp, fl, blocks, 0, st) : launch_by_stages<2>(sp, fl, blocks, 0, st);
+  if (rc) return rc;
+  return hipGetLastError() == hipSuccess ? 0 : -1;
+}
 
 bool fast_can_bound(const FastState *f, const SearchLaunch &a) {
   if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return false;
@@ -1771,17 +2014,24 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
 }
 
 void fast_release(FastState *f) {
-  if (f->d_cut_count) (void)hipFree(f->d_cut_count);
-  if (f->d_cut_pos) (void)hipFree(f->d_cut_pos);
-  if (f->d_cut_list) (void)hipFree(f->d_cut_list);
+  if (f->d_cand_low) pool_release(f->d_cand_low);
+  if (f->d_cand_ways) pool_release(f->d_cand_ways);
+  if (f->d_cand_count) pool_release(f->d_cand_count);
+  if (f->d_cand_pos) pool_release(f->d_cand_pos);
+  if (f->d_cand_list) pool_release(f->d_cand_list);
+  f->d_cand_low = nullptr; f->d_cand_ways = nullptr; f->d_cand_count = nullptr; f->d_cand_pos = nullptr; f->d_cand_list = nullptr;
+  f->cand_capacity = 0; f->cand_ways_capacity = 0;
+  if (f->d_cut_count) pool_release(f->d_cut_count);
+  if (f->d_cut_pos) pool_release(f->d_cut_pos);
+  if (f->d_cut_list) pool_release(f->d_cut_list);
   f->d_cut_count = nullptr; f->d_cut_pos = nullptr; f->d_cut_list = nullptr;
-  if (f->d_rowkey) (void)hipFree(f->d_rowkey);
-  if (f->d_pen) (void)hipFree(f->d_pen);
-  if (f->d_weights) (void)hipFree(f->d_weights);
-  if (f->d_base) (void)hipFree(f->d_base);
-  if (f->d_vecs) (void)hipFree(f->d_vecs);
-  if (f->d_runs) (void)hipFree(f->d_runs);
-  if (f->d_tables) (void)hipFree(f->d_tables);
+  if (f->d_rowkey) pool_release(f->d_rowkey);
+  if (f->d_pen) pool_release(f->d_pen);
+  if (f->d_weights) pool_release(f->d_weights);
+  if (f->d_base) pool_release(f->d_base);
+  if (f->d_vecs) pool_release(f->d_vecs);
+  if (f->d_runs) pool_release(f->d_runs);
+  if (f->d_tables) pool_release(f->d_tables);
   f->d_rowkey = nullptr; f->d_pen = nullptr; f->d_weights = nullptr; f->d_base = nullptr;
   f->d_vecs = nullptr;
   f->d_runs = nullptr;

@@ -13,6 +13,13 @@
 #include "chm_dev.h"
 #include "chm_fast.h"
 #include "chm_internal.h"
+#include "chm_pool.h"
+
+// typed front ends of the caching allocator (chm_pool.h)
+template <typename T>
+static inline bool pool_take(T *&p, size_t bytes) { p = (T *)pool_device_alloc(bytes); return p != nullptr; }
+template <typename T>
+static inline bool pool_take_pinned(T *&p, size_t bytes) { p = (T *)pool_pinned_alloc(bytes); return p != nullptr; }
 
 namespace {
 
@@ -324,12 +331,12 @@ void release(chm_scenario *s) {
   if (!s) return;
   fast_release(&s->fast);
   for (auto &e : s->ev) if (e) (void)hipEventDestroy(e);
-  if (s->h_pinned) (void)hipHostFree(s->h_pinned);
-  if (s->d_xfer) (void)hipFree(s->d_xfer);
-  if (s->d_winner) (void)hipFree(s->d_winner);
-  if (s->d_slots) (void)hipFree(s->d_slots);
-  if (s->d_comp) (void)hipFree(s->d_comp);
-  if (s->d_scn) (void)hipFree(s->d_scn);
+  if (s->h_pinned) pool_release(s->h_pinned);
+  if (s->d_xfer) pool_release(s->d_xfer);
+  if (s->d_winner) pool_release(s->d_winner);
+  if (s->d_slots) pool_release(s->d_slots);
+  if (s->d_comp) pool_release(s->d_comp);
+  if (s->d_scn) pool_release(s->d_scn);
   delete s;
 }
 
@@ -390,7 +397,13 @@ void nothing_found(chm_best *out) {
 // a range of partition ranks [first, first+count) of one strategy, or (ranks != null) a list of
 // `count` partition ranks in device memory; costs (nullable, device) receives one cost per entry
 // (cuts != null: the list holds rows of cut positions instead)
-struct Job { int strategy; uint64_t first, count; const uint64_t *ranks; int64_t *costs; const uint8_t *cuts = nullptr; };
+// (cand != null: a bounded search over the enumerated candidates of the whole family; count = their number,
+// the key carries the candidate's index, `covers` = partitions of the family for the accounting)
+struct Job {
+  int strategy; uint64_t first, count; const uint64_t *ranks; int64_t *costs; const uint8_t *cuts = nullptr;
+  const CandidateSet *cand = nullptr; uint64_t covers = 0; uint64_t stride = 1;
+  bool seed = false;            // a few ranks searched ahead of their range for a good incumbent: left out of the accounting
+};
 
 // Rank of the partition into `stages` stages whose cuts follow the quantiles of a prefix table (forward +
 // backward time, or memory): cut j at the first position where the prefix reaches j/stages of the total.
@@ -408,29 +421,24 @@ uint64_t balanced_rank(const chm_scenario *s, int stages, const int64_t *prefix_
   return rank;
 }
 
+// below this many partitions the bounded range search costs no more than counting and enumerating candidates
+constexpr uint64_t ENUMERATE_FROM = 1ull << 25;
+
+uint64_t rank_of_cuts(const chm_scenario *s, int k, const uint8_t *cuts) {
+  uint64_t rank = 0;
+  for (int i = 1; i <= k; ++i) rank += s->h.binom[i][cuts[i - 1] - 1];
+  return rank;
+}
+
 // Runs the argmin over the given partition ranges.
 // With out == null the kernels are only launched (asynchronous scoring into the jobs' cost buffers).
-int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, uint64_t *position, hipStream_t st) {
+// incumbent0: cost of a plan known before the call (a bounded search prunes against it), ~0 = none;
+// bounded: range jobs skip partitions by their lower bound.
+// light: only cost, strategy and partition of the winner are wanted (out->index = the partition's first plan
+// index; reroute vectors and time terms are left out, which saves their kernels and a synchronisation).
+int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint64_t *position, hipStream_t st,
+             uint64_t incumbent0, bool bounded, bool light = false) {
   HIP_TRY(hipSetDevice(s->device));
-  const bool bounded = s->bounded && out != nullptr;
-  // A bounded search prunes against the best cost found so far, so it first looks at a few partitions that
-  // are likely to be good: 64 ranks around the time-balanced and around the memory-balanced partition of
-  // every range (they are scored again as part of the range; equal plans give equal keys).
-  std::vector<Job> jobs;
-  if (bounded) {
-    for (const Job &j : given) {
-      if (j.ranks || j.cuts || j.costs || j.count < (1u << 16)) continue;
-      const int stages = s->h.fam[j.strategy].stages;
-      if (stages < 2) continue;
-      const uint64_t seeds[2] = {balanced_rank(s, stages, s->h.pf, s->h.pb), balanced_rank(s, stages, s->h.pw, nullptr)};
-      for (int i = 0; i < (seeds[0] == seeds[1] ? 1 : 2); ++i) {
-        const uint64_t lo = std::max<uint64_t>(j.first, seeds[i] >= 32 ? seeds[i] - 32 : 0);
-        const uint64_t hi = std::min<uint64_t>(j.first + j.count, seeds[i] + 32);
-        if (lo < hi) jobs.push_back(Job{j.strategy, lo, hi - lo, nullptr, nullptr});
-      }
-    }
-  }
-  jobs.insert(jobs.end(), given.begin(), given.end());
   s->last = chm_timing();
   std::vector<Slot> slots;
   const uint64_t chunk = 1ull << s->idx_bits;
@@ -456,17 +464,16 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
   // the incumbent cost of a bounded search
   uint64_t *d_count = s->d_slots + key_words;
   uint64_t *d_evaluated = d_count + 3 * chunk_words;
-  uint64_t *d_seed_count = d_count + 6 * chunk_words;      // what the seed launches count (not reported)
+  uint64_t *d_seed_count = d_count + 6 * chunk_words;      // what seed jobs count (not reported)
   uint64_t *d_incumbent = d_count + 7 * chunk_words;
   if (chmk_fill_u64(d_count, 7 * chunk_words, 0, st)) return CHM_ERR_HIP;
-  if (chmk_fill_u64(d_incumbent, 1, ~0ull, st)) return CHM_ERR_HIP;
+  if (chmk_fill_u64(d_incumbent, 1, incumbent0, st)) return CHM_ERR_HIP;
   bool bounded_used[3] = {false, false, false};
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;
   int ev_i = 1;
   int ev_of[3] = {-1, -1, -1};
   for (const Job &j : jobs) {
-    const bool seed = &j - jobs.data() < (ptrdiff_t)(jobs.size() - given.size());
     for (uint64_t done = 0; done < j.count; done += chunk, ++si) {
       SearchLaunch a;
       a.scn = s->d_scn; a.comp = s->d_comp; a.strategy = j.strategy;
@@ -474,26 +481,32 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
       a.part_count = (uint32_t)std::min<uint64_t>(chunk, j.count - done);
       a.idx_bits = s->idx_bits;
       a.result = s->d_slots + si * chunk_words;
-      a.feasible = seed ? d_seed_count : d_count + (size_t)j.strategy * chunk_words;
+      a.feasible = j.seed ? d_seed_count : d_count + (size_t)j.strategy * chunk_words;
       a.slot_mask = ways - 1;
       a.slot_stride = stride;
       a.ranks = j.ranks ? j.ranks + done : nullptr;
       a.cuts = j.cuts ? j.cuts + (size_t)done * (size_t)(s->h.fam[j.strategy].stages - 1) : nullptr;
       a.costs_out = j.costs ? j.costs + done : nullptr;
+      if (j.cand) {
+        a.incumbent = d_incumbent;
+        if (fast_candidates_search(&s->fast, s->h, a, *j.cand, j.stride, st)) return CHM_ERR_HIP;
+        continue;
+      }
       if (bounded && fast_can_bound(&s->fast, a)) {
         a.incumbent = d_incumbent;
-        a.evaluated = seed ? d_seed_count : d_evaluated + (size_t)j.strategy * chunk_words;
+        a.evaluated = j.seed ? d_seed_count : d_evaluated + (size_t)j.strategy * chunk_words;
         bounded_used[j.strategy] = true;
       }
       int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
       if (rc > 0) rc = chmk_search(a, s->smax, st);
       if (rc) return CHM_ERR_HIP;
     }
-    if (seed) continue;                                   // not part of the accounting
-    s->last.partitions[j.strategy] += j.count;
+    if (j.seed) continue;
+    const uint64_t covered = j.cand ? j.covers : j.count;
+    s->last.partitions[j.strategy] += covered;
     uint64_t per_part = 1;
     if (j.strategy == 2 && s->h.n_aff) { per_part = 0; for (int a = 0; a < s->h.n_aff; ++a) per_part += s->h.aff_R[a]; }
-    s->last.evaluations[j.strategy] += j.count * per_part;
+    s->last.evaluations[j.strategy] += covered * per_part;
     if (s->timing && ev_i < 7) { HIP_TRY(hipEventRecord(s->ev[ev_i], st)); ev_of[j.strategy] = ev_i; ++ev_i; }
   }
   if (!out) return CHM_OK;
@@ -532,7 +545,12 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
     for (uint32_t w = 0; w < ways; ++w) key = std::min(key, s->h_pinned[i * chunk_words + (size_t)w * stride]);
     if (key == CHM_KEY_NONE) continue;
     const int64_t cost = (int64_t)(key >> slots[i].idx_bits);
-    const uint64_t part = slots[i].part_first + (key & ((1ull << slots[i].idx_bits) - 1));
+    uint64_t part = slots[i].part_first + (key & ((1ull << slots[i].idx_bits) - 1));
+    if (slot_job[i]->cand) {                       // a candidate's index: its partition rank decides among equal costs
+      uint8_t cuts[32];
+      fast_candidate_cuts(*slot_job[i]->cand, part * slot_job[i]->stride, cuts);
+      part = rank_of_cuts(s, s->h.fam[slots[i].strategy].stages - 1, cuts);
+    }
     if (cost < best_cost || (cost == best_cost && (slots[i].strategy < best_strategy ||
                                                    (slots[i].strategy == best_strategy && part < best_part)))) {
       best_cost = cost;
@@ -556,24 +574,134 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
     best_part = s->h_pinned[0];
   }
   uint64_t rr[DEV_MAX_AFF] = {};
-  if (best_strategy == 2 && s->h.n_aff > 0) {
+  if (light) {
+    fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
+    return CHM_OK;
+  }
+  // the winner's reroute vectors (rerouting only) and its transition time, from the device, behind one
+  // synchronisation; its step time follows from cost = horizon x step + transition
+  const bool rerouted = best_strategy == 2 && s->h.n_aff > 0;
+  if (rerouted) {
     int rc = fast_reroute_winner(&s->fast, s->h, s->d_scn, best_part, s->d_winner, st);
     if (rc > 0) rc = chmk_reroute_winner(s->d_scn, s->d_comp, best_part, s->d_winner, s->smax, st);
     if (rc) return CHM_ERR_HIP;
     HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_winner, DEV_MAX_AFF * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-    HIP_TRY(hipStreamSynchronize(st));
-    for (int a = 0; a < s->h.n_aff; ++a) rr[a] = s->h_pinned[a];
   }
-  fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
-  // the winner's transition time, from the device; its step time follows from cost = horizon x step + transition
   if (chmk_plan_transition(s->d_scn, best_strategy, best_part, (int64_t *)s->d_xfer, s->smax, st)) return CHM_ERR_HIP;
-  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_xfer, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(s->h_pinned + DEV_MAX_AFF, s->d_xfer, sizeof(int64_t), hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
-  const int64_t t_trans = (int64_t)s->h_pinned[0];
+  if (rerouted)
+    for (int a = 0; a < s->h.n_aff; ++a) rr[a] = s->h_pinned[a];
+  fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
+  const int64_t t_trans = (int64_t)s->h_pinned[DEV_MAX_AFF];
   if (t_trans < 0 || t_trans > best_cost || (best_cost - t_trans) % s->h.K != 0) return CHM_ERR_HIP;   // cannot happen
   out->t_trans_us = t_trans;
   out->t_step_us = (best_cost - t_trans) / s->h.K;
   return CHM_OK;
+}
+
+// Exhaustive search, or (chm_set_bounded_search) the same argmin with the plans skipped that cannot reach it.
+// A bounded search first evaluates a few partitions that are likely to be good: 64 ranks around the
+// time-balanced and around the memory-balanced partition of every range.  Their best cost bounds everything
+// else.  A family that is searched as a whole is then reduced on the host to its candidates, the partitions
+// whose lower bound of the cost does not exceed that cost (see CandidateSet), and only those are enumerated and
+// evaluated; sub-ranges, families with too many candidates and the shapes the candidate path does not cover are
+// searched range by range with the bound applied per run and per partition.  The seeds' best plan competes
+// with the result (it is among the candidates as well; equal plans compare equal).
+int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, uint64_t *position, hipStream_t st) {
+  if (!(s->bounded && out != nullptr)) return run_jobs(s, given, out, position, st, ~0ull, false);
+  std::vector<Job> seeds;
+  for (const Job &j : given) {
+    if (j.ranks || j.cuts || j.costs || j.count < (1u << 16)) continue;
+    const int stages = s->h.fam[j.strategy].stages;
+    if (stages < 2) continue;
+    const uint64_t at[2] = {balanced_rank(s, stages, s->h.pf, s->h.pb), balanced_rank(s, stages, s->h.pw, nullptr)};
+    for (int i = 0; i < (at[0] == at[1] ? 1 : 2); ++i) {
+      const uint64_t lo = std::max<uint64_t>(j.first, at[i] >= 32 ? at[i] - 32 : 0);
+      const uint64_t hi = std::min<uint64_t>(j.first + j.count, at[i] + 32);
+      if (lo < hi) {
+        seeds.push_back(Job{j.strategy, lo, hi - lo, nullptr, nullptr});
+        seeds.back().seed = true;
+      }
+    }
+  }
+  // Families that are enumerated need the seeds' cost on the host first.  When none can be (sub-ranges, families
+  // small enough that the range search costs no more), the seeds simply run ahead of the ranges in one pass.
+  bool any_enumerable = false;
+  for (const Job &j : given)
+    any_enumerable = any_enumerable || (!j.ranks && !j.cuts && !j.costs && j.first == 0 && j.count == s->h.fam[j.strategy].n_part &&
+                                        j.count >= ENUMERATE_FROM && s->idx_bits >= 23);
+  if (!any_enumerable) {
+    std::vector<Job> all(seeds);
+    all.insert(all.end(), given.begin(), given.end());
+    return run_jobs(s, all, out, position, st, ~0ull, true);
+  }
+  chm_best seed_best;
+  int seed_rc = CHM_ERR_NO_FEASIBLE;
+  if (!seeds.empty()) {
+    seed_rc = run_jobs(s, seeds, &seed_best, nullptr, st, ~0ull, false, true);
+    if (seed_rc != CHM_OK && seed_rc != CHM_ERR_NO_FEASIBLE) return seed_rc;
+  }
+  uint64_t incumbent = seed_rc == CHM_OK ? (uint64_t)seed_best.cost : ~0ull;
+  std::vector<CandidateSet> sets(given.size());
+  std::vector<Job> jobs;
+  uint64_t skipped[3] = {0, 0, 0};                     // partitions of families the bound excludes as a whole
+  for (size_t i = 0; i < given.size(); ++i) {
+    const Job &j = given[i];
+    const bool whole = !j.ranks && !j.cuts && !j.costs && j.first == 0 && j.count == s->h.fam[j.strategy].n_part;
+    bool listed = false;
+    if (whole && incumbent != ~0ull && s->idx_bits >= 23) {
+      // A family within reach of a range search is enumerated only when its candidates are few; one beyond it,
+      // whenever they can be made few enough: while there are too many, a sample of them spread evenly over
+      // their index order is evaluated, which lowers the incumbent and with it the number of candidates.
+      // (below 2^25 partitions the range search costs no more than counting and enumerating does)
+      const bool in_reach = j.count <= (1ull << 27);
+      for (int round = 0; round < 8 && j.count >= ENUMERATE_FROM; ++round) {
+        if (!fast_candidates_build(&s->fast, s->h, j.strategy, incumbent, &sets[i])) break;
+        const uint64_t total = sets[i].total;
+        if (total <= (in_reach ? (uint64_t)CAND_DIRECT : (uint64_t)CAND_MAX)) { listed = true; break; }
+        if (in_reach) break;
+        Job sample{j.strategy, 0, CAND_SAMPLE, nullptr, nullptr};
+        sample.cand = &sets[i];
+        sample.stride = total / CAND_SAMPLE;
+        chm_best found;
+        const int rc_s = run_jobs(s, std::vector<Job>{sample}, &found, nullptr, st, incumbent, false, true);
+        if (rc_s != CHM_OK && rc_s != CHM_ERR_NO_FEASIBLE) return rc_s;
+        if (rc_s != CHM_OK || (uint64_t)found.cost >= incumbent) break;          // the sample found nothing better
+        incumbent = (uint64_t)found.cost;
+        seed_best = found;
+        seed_rc = CHM_OK;
+      }
+    }
+    if (listed) {
+      if (sets[i].total == 0) { skipped[j.strategy] += j.count; continue; }
+      for (uint64_t first = 0; first < sets[i].total; first += CAND_PASS) {
+        Job c{j.strategy, first, std::min<uint64_t>(CAND_PASS, sets[i].total - first), nullptr, nullptr};
+        c.cand = &sets[i];
+        c.covers = first == 0 ? j.count : 0;
+        jobs.push_back(c);
+      }
+    } else {
+      jobs.push_back(j);
+    }
+  }
+  int rc = run_jobs(s, jobs, out, position, st, incumbent, true);
+  if (rc != CHM_OK && rc != CHM_ERR_NO_FEASIBLE) return rc;
+  for (int k = 0; k < 3; ++k) {
+    s->last.partitions[k] += skipped[k];
+    uint64_t per_part = 1;
+    if (k == 2 && s->h.n_aff) { per_part = 0; for (int a = 0; a < s->h.n_aff; ++a) per_part += s->h.aff_R[a]; }
+    s->last.evaluations[k] += skipped[k] * per_part;
+  }
+  // The plan the incumbent came from lies inside the ranges just searched and passes every bound against its
+  // own cost, so it has been found again unless something better was.  Should it ever be missing, it is
+  // evaluated once more for its full description.
+  if (seed_rc == CHM_OK && (rc == CHM_ERR_NO_FEASIBLE || seed_best.cost < out->cost)) {
+    const chm_family *f = find_family(s, seed_best.strategy);
+    const uint64_t part = (seed_best.index - f->offset) / f->n_reroute;
+    return run_jobs(s, std::vector<Job>{Job{seed_best.strategy, part, 1, nullptr, nullptr}}, out, position, st, ~0ull, false);
+  }
+  return rc;
 }
 
 
@@ -581,12 +709,12 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
 // Takes ownership of s: on failure it is released and *out stays null.
 int upload_scenario(chm_scenario *s, chm_scenario **out) {
   bool ok = hipGetDevice(&s->device) == hipSuccess;
-  ok = ok && hipMalloc((void **)&s->d_scn, sizeof(DevScenario)) == hipSuccess;
-  ok = ok && hipMalloc((void **)&s->d_comp, s->comp.size() * sizeof(uint64_t)) == hipSuccess;
-  ok = ok && hipMalloc((void **)&s->d_slots, (size_t)SLOT_WORDS * sizeof(uint64_t)) == hipSuccess;
-  ok = ok && hipMalloc((void **)&s->d_winner, DEV_MAX_AFF * sizeof(uint64_t)) == hipSuccess;
-  ok = ok && hipMalloc((void **)&s->d_xfer, sizeof(uint64_t) + DEV_MAX_S) == hipSuccess;
-  ok = ok && hipHostMalloc((void **)&s->h_pinned, (size_t)SLOT_WORDS * sizeof(uint64_t), hipHostMallocDefault) == hipSuccess;
+  ok = ok && pool_take(s->d_scn, sizeof(DevScenario));
+  ok = ok && pool_take(s->d_comp, s->comp.size() * sizeof(uint64_t));
+  ok = ok && pool_take(s->d_slots, (size_t)SLOT_WORDS * sizeof(uint64_t));
+  ok = ok && pool_take(s->d_winner, DEV_MAX_AFF * sizeof(uint64_t));
+  ok = ok && pool_take(s->d_xfer, sizeof(uint64_t) + DEV_MAX_S);
+  ok = ok && pool_take_pinned(s->h_pinned, (size_t)SLOT_WORDS * sizeof(uint64_t));
   ok = ok && hipMemcpy(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice) == hipSuccess;
   ok = ok && hipMemcpy(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice) == hipSuccess;
   for (auto &e : s->ev) ok = ok && hipEventCreate(&e) == hipSuccess;

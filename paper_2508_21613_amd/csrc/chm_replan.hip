@@ -10,6 +10,13 @@
 #include <vector>
 
 #include "chm_internal.h"
+#include "chm_pool.h"
+
+// typed front ends of the caching allocator (chm_pool.h)
+template <typename T>
+static inline bool pool_take(T *&p, size_t bytes) { p = (T *)pool_device_alloc(bytes); return p != nullptr; }
+template <typename T>
+static inline bool pool_take_pinned(T *&p, size_t bytes) { p = (T *)pool_pinned_alloc(bytes); return p != nullptr; }
 
 namespace {
 
@@ -120,12 +127,12 @@ struct Scratch {
   int64_t *d_pw = nullptr, *d_total = nullptr; // d_total: [0] least total MiB, [1] rounds (int32 in its low half)
   int64_t *h_total = nullptr;                  // pinned, two words
   ~Scratch() {
-    if (d_held) (void)hipFree(d_held);
-    if (d_pos) (void)hipFree(d_pos);
-    if (d_assign) (void)hipFree(d_assign);
-    if (d_pw) (void)hipFree(d_pw);
-    if (d_total) (void)hipFree(d_total);
-    if (h_total) (void)hipHostFree(h_total);
+    if (d_held) pool_release(d_held);
+    if (d_pos) pool_release(d_pos);
+    if (d_assign) pool_release(d_assign);
+    if (d_pw) pool_release(d_pw);
+    if (d_total) pool_release(d_total);
+    if (h_total) pool_release(h_total);
   }
 };
 
@@ -192,12 +199,12 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
 
   Scratch sc;
   if (N > 0) {
-    bool ok = hipMalloc((void **)&sc.d_held, held.size() * sizeof(int32_t)) == hipSuccess;
-    ok = ok && hipMalloc((void **)&sc.d_pos, held.size() * sizeof(int32_t)) == hipSuccess;
-    ok = ok && hipMalloc((void **)&sc.d_assign, (size_t)N * sizeof(int32_t)) == hipSuccess;
-    ok = ok && hipMalloc((void **)&sc.d_pw, pw.size() * sizeof(int64_t)) == hipSuccess;
-    ok = ok && hipMalloc((void **)&sc.d_total, 2 * sizeof(int64_t)) == hipSuccess;
-    ok = ok && hipHostMalloc((void **)&sc.h_total, 2 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
+    bool ok = pool_take(sc.d_held, held.size() * sizeof(int32_t));
+    ok = ok && pool_take(sc.d_pos, held.size() * sizeof(int32_t));
+    ok = ok && pool_take(sc.d_assign, (size_t)N * sizeof(int32_t));
+    ok = ok && pool_take(sc.d_pw, pw.size() * sizeof(int64_t));
+    ok = ok && pool_take(sc.d_total, 2 * sizeof(int64_t));
+    ok = ok && pool_take_pinned(sc.h_total, 2 * sizeof(int64_t));
     ok = ok && hipMemcpyAsync(sc.d_held, held.data(), held.size() * sizeof(int32_t), hipMemcpyHostToDevice, st) == hipSuccess;
     ok = ok && hipMemcpyAsync(sc.d_pw, pw.data(), pw.size() * sizeof(int64_t), hipMemcpyHostToDevice, st) == hipSuccess;
     ok = ok && hipStreamSynchronize(st) == hipSuccess;

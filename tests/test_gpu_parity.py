@@ -216,6 +216,56 @@ def test_bounded_search_returns_the_exhaustive_winner(B, name):
               "ms", [round(x, 3) for x in t_e["family_ms"]], "->", [round(x, 3) for x in t_b["family_ms"]], flush=True)
 
 
+def test_bounded_search_over_the_whole_space_of_config4(B):
+    """L=96 on 16 (15) stages: 10^17 partitions per strategy, out of reach of the exhaustive search
+    (CHM_ERR_OVERFLOW).  The bounded search enumerates only the partitions whose lower bound of the cost does not
+    exceed the best seed's cost.  The oracle cannot enumerate the space either, so: the winner's cost is
+    recomputed by the oracle from its cuts, the oracle's argmin over the window of ranks around it is the same
+    plan, no plan of seeded windows elsewhere is better, and no single cut can be moved by one layer to a
+    better plan."""
+    sc = synth.config4(mem_cap_mib=synth.CONFIG4_CAP_30PCT)
+    o, g = O.Scenario(sc), B.Scenario(sc)
+    g.set_bounded_search(True)
+    g.set_timing(True)
+    rng = np.random.default_rng(21)
+    reached = 0
+    for f in o.families:
+        try:
+            rc, best = g.search_best(1 << f["strategy"])
+        except B.ChmError as err:
+            assert err.code == B.ERR_OVERFLOW
+            print("config4 whole space, strategy", f["strategy"], "too many candidates", flush=True)
+            continue
+        t = g.get_timing()
+        print("config4 whole space, strategy", f["strategy"], "rc", rc, "cost", best["cost"], "cuts", best["cuts"],
+              "candidates that fit", t["feasible"][f["strategy"]], flush=True)
+        if rc != 0:
+            continue
+        reached += 1
+        rr = best["reroute"] if best["strategy"] == 2 else None
+        assert o.plan_cost(best["strategy"], best["cuts"], rr) == best["cost"]
+        assert o.decode(best["index"])["cost"] == best["cost"]
+        part = (best["index"] - f["offset"]) // f["n_reroute"]
+        width = 20000 if f["n_reroute"] == 1 else 300
+        first = max(0, min(part - width // 2, f["n_part"] - width))
+        rc_o, best_o, _ = o.search_range(f["strategy"], first, width)
+        assert rc_o == 0 and same_plan(best, best_o)
+        for _ in range(4):
+            first = int(rng.integers(0, f["n_part"] - width))
+            rc_o, w, _ = o.search_range(f["strategy"], first, width)
+            assert rc_o != 0 or (w["cost"], w["index"]) >= (best["cost"], best["index"])
+        cuts = best["cuts"]
+        for i in range(len(cuts)):
+            for delta in (-1, 1):
+                c2 = list(cuts)
+                c2[i] += delta
+                if c2 != sorted(set(c2)) or c2[0] < 1 or c2[-1] > sc["L"] - 1:
+                    continue
+                rc_o, w, _ = o.search_range(f["strategy"], int(O.partition_rank(c2)), 1)
+                assert rc_o != 0 or (w["cost"], w["index"]) >= (best["cost"], best["index"])
+    assert reached >= 1
+
+
 def test_equal_costs_in_an_explicit_list_go_to_the_lowest_position(B):
     """a list in which the best partition occurs many times at seeded positions: the reported position is
     the first of them, whatever order the compacted entries are evaluated in"""

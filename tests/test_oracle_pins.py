@@ -73,6 +73,10 @@ def test_makespan_lower_bounds_and_monotonicity():
         # stages ahead follow its last one (the bound a bounded search on the GPU prunes with)
         C = F + B
         assert T >= max(M * int(C[s]) + int(C[:s].sum()) for s in range(S))
+        # and its first backward waits for micro-batch 0 to come back from the stages behind it, while the stage
+        # itself has run no more than its warm-up forwards and one more (holds when M covers the warm-up)
+        assert T >= max(M * int(C[s]) + int(C[:s].sum()) + max(0, int(C[s + 1:].sum()) - (S - 1 - s) * int(F[s]))
+                        for s in range(S) if M >= S - s)
         assert T <= (S + M - 1) * (int(F.max()) + int(B.max()))
         s = int(rng.integers(0, S))
         F2, B2 = F.copy(), B.copy()
