@@ -221,8 +221,12 @@ int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
  * above the lowest cost evaluated so far in the same call.  The plan returned is the same, ties included:
  * only plans that can neither win nor tie are skipped, one by one or a run of consecutive ranks at a time
  * (the stages above the cuts that change within the run are common to all of its partitions, and so is their
- * share of the bound).  The search starts with the ranks around the time-balanced and the memory-balanced
- * partition of each range, so that a good cost is known early.  chm_timing.evaluated tells how many
+ * share of the bound), or never enumerated at all: for a family searched as a whole the library counts on
+ * the host, stage by stage, the partitions whose bound stays within the best cost known, and the device
+ * enumerates and evaluates only those (this also reaches families of more than 2^46 partitions, which
+ * chm_search_best otherwise refuses with CHM_ERR_OVERFLOW, whenever at most 2^26 candidates remain).  The search
+ * starts with the ranks around the time-balanced and the memory-balanced partition of each range, so that a
+ * good cost is known early.  chm_timing.evaluated tells how many
  * partitions were evaluated in full; chm_timing.feasible then counts only those partitions that were looked
  * at one by one and fit.  Covers the range searches of the specialised kernels without cost store (other
  * paths evaluate everything).  Errors: CHM_ERR_ARG. */
