@@ -214,7 +214,8 @@ int chm_get_timing(const chm_scenario *s, chm_timing *out);
  * taken).  Errors: CHM_ERR_ARG. */
 int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
 
-/* Bounded search, off by default.  on != 0: chm_search_best and chm_search_range skip a partition as soon as a
+/* Bounded search, off by default.  on = 1 (on = 2: the same with the size thresholds below set to one
+ * partition, so that tests reach every path on small scenarios): chm_search_best and chm_search_range skip a partition as soon as a
  * lower bound of its cost (micro-batches x the largest forward + backward time of a stage, which every
  * pipeline needs under the dependencies of eq. (transition); plus lower bounds of the communication rounds
  * and of the reroute penalty of eq. (re-route); the transition time counted as its constant part) lies

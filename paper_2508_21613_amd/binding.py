@@ -384,7 +384,7 @@ class Scenario:
 
     def set_bounded_search(self, on=True):
         """chm_set_bounded_search: skip partitions whose lower bound of the cost lies above the best cost found so far"""
-        _check(lib().chm_set_bounded_search(self._h, 1 if on else 0))
+        _check(lib().chm_set_bounded_search(self._h, int(on)))
 
     def get_timing(self):
         t = Timing()

@@ -1023,7 +1023,7 @@ __global__ void __launch_bounds__(BLOCK) k_list_filter(ListFilter a) {
 // bounded search: enumeration of the candidates (see CandidateSet)
 // ---------------------------------------------------------------------------------------
 struct CandidateEnum {
-  const uint64_t *ways;         // [stages][L+1][L+1]
+  const uint64_t *ways;         // [stages][end][start]
   const uint8_t *low_pair;      // [stages][L+1]
   int32_t stages, L;
   uint32_t total;               // candidates of this launch
@@ -1051,7 +1051,7 @@ __global__ void __launch_bounds__(BLOCK) k_enumerate_candidates(CandidateEnum e)
   int end = e.L;                          // its end
   int start = s;                          // at least one layer for every stage below
   for (; start < end - 1; ++start) {
-    const uint64_t blk = e.ways[((size_t)s * W + start) * W + end];
+    const uint64_t blk = e.ways[((size_t)s * W + end) * W + start];
     if (idx < blk) break;
     idx -= blk;
   }
@@ -1062,7 +1062,7 @@ __global__ void __launch_bounds__(BLOCK) k_enumerate_candidates(CandidateEnum e)
     const int lo = (int)e.low_pair[(size_t)(s - 1) * W + end];
     int below = lo > s - 1 ? lo : s - 1;
     for (; below < start - 1; ++below) {
-      const uint64_t blk = e.ways[((size_t)(s - 1) * W + below) * W + start];
+      const uint64_t blk = e.ways[((size_t)(s - 1) * W + start) * W + below];
       if (idx < blk) break;
       idx -= blk;
     }
@@ -1739,7 +1739,7 @@ bool fast_candidates_build(const FastState *f, const DevScenario &h, int k, uint
         out->low_pair[(size_t)s * W + e] = (uint8_t)(a + 1);              // e - 1: no start passes
       }
   }
-  auto ways = [&](int s, int a, int b) -> uint64_t & { return out->ways[((size_t)s * W + a) * W + b]; };
+  auto ways = [&](int s, int a, int b) -> uint64_t & { return out->ways[((size_t)s * W + b) * W + a]; };
   for (int b = 1; b <= L - (sp - 1); ++b)
     if (single_ok(0, 0, b)) ways(0, 0, b) = 1;
   std::vector<uint64_t> from(W + 1);
@@ -1768,7 +1768,7 @@ void fast_candidate_cuts(const CandidateSet &cs, uint64_t idx, uint8_t *cuts) {
   const size_t W = (size_t)cs.L + 1;
   int s = cs.stages - 1, end = cs.L, start = s;
   for (; start < end - 1; ++start) {
-    const uint64_t blk = cs.ways[((size_t)s * W + start) * W + end];
+    const uint64_t blk = cs.ways[((size_t)s * W + end) * W + start];
     if (idx < blk) break;
     idx -= blk;
   }
@@ -1777,7 +1777,7 @@ void fast_candidate_cuts(const CandidateSet &cs, uint64_t idx, uint8_t *cuts) {
     if (s == 1) break;
     int below = std::max<int>(cs.low_pair[(size_t)(s - 1) * W + end], s - 1);
     for (; below < start - 1; ++below) {
-      const uint64_t blk = cs.ways[((size_t)(s - 1) * W + below) * W + start];
+      const uint64_t blk = cs.ways[((size_t)(s - 1) * W + start) * W + below];
       if (idx < blk) break;
       idx -= blk;
     }

@@ -59,7 +59,7 @@ struct chm_scenario {
   uint64_t *h_pinned = nullptr;          // pinned staging for the two small device-to-host copies
   uint32_t n_slots = 0;
   bool timing = false;
-  bool bounded = false;         // chm_set_bounded_search
+  int bounded = 0;              // chm_set_bounded_search: 0 off, 1 on, 2 on with seeds and enumeration at any size
   hipEvent_t ev[8] = {};
   chm_timing last = {};
   FastState fast;                        // shape-specialised search path (chm_fast.hip)
@@ -610,9 +610,10 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
 // with the result (it is among the candidates as well; equal plans compare equal).
 int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, uint64_t *position, hipStream_t st) {
   if (!(s->bounded && out != nullptr)) return run_jobs(s, given, out, position, st, ~0ull, false);
+  const uint64_t seeds_from = s->bounded == 2 ? 1 : (1u << 16), enumerate_from = s->bounded == 2 ? 1 : ENUMERATE_FROM;
   std::vector<Job> seeds;
   for (const Job &j : given) {
-    if (j.ranks || j.cuts || j.costs || j.count < (1u << 16)) continue;
+    if (j.ranks || j.cuts || j.costs || j.count < seeds_from) continue;
     const int stages = s->h.fam[j.strategy].stages;
     if (stages < 2) continue;
     const uint64_t at[2] = {balanced_rank(s, stages, s->h.pf, s->h.pb), balanced_rank(s, stages, s->h.pw, nullptr)};
@@ -630,7 +631,7 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
   bool any_enumerable = false;
   for (const Job &j : given)
     any_enumerable = any_enumerable || (!j.ranks && !j.cuts && !j.costs && j.first == 0 && j.count == s->h.fam[j.strategy].n_part &&
-                                        j.count >= ENUMERATE_FROM && s->idx_bits >= 23);
+                                        j.count >= enumerate_from && s->idx_bits >= 23);
   if (!any_enumerable) {
     std::vector<Job> all(seeds);
     all.insert(all.end(), given.begin(), given.end());
@@ -656,7 +657,7 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
       // their index order is evaluated, which lowers the incumbent and with it the number of candidates.
       // (below 2^25 partitions the range search costs no more than counting and enumerating does)
       const bool in_reach = j.count <= (1ull << 27);
-      for (int round = 0; round < 8 && j.count >= ENUMERATE_FROM; ++round) {
+      for (int round = 0; round < 8 && j.count >= enumerate_from; ++round) {
         if (!fast_candidates_build(&s->fast, s->h, j.strategy, incumbent, &sets[i])) break;
         const uint64_t total = sets[i].total;
         if (total <= (in_reach ? (uint64_t)CAND_DIRECT : (uint64_t)CAND_MAX)) { listed = true; break; }
@@ -720,7 +721,7 @@ int upload_scenario(chm_scenario *s, chm_scenario **out) {
   for (auto &e : s->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
   if (ok && s->h.fam[1].n_part) {
     // the healthy pipelines' step time under the fault-free layout is computed by the device
-    ok = chmk_fixed_pipelines(s->d_scn, nullptr) == 0 && hipDeviceSynchronize() == hipSuccess;
+    ok = chmk_fixed_pipelines(s->d_scn, s->smax, nullptr) == 0 && hipDeviceSynchronize() == hipSuccess;
     ok = ok && hipMemcpy(&s->h.fam[1].fixed_step, &s->d_scn->fam[1].fixed_step, sizeof(int64_t), hipMemcpyDeviceToHost) == hipSuccess;
   }
   ok = ok && fast_prepare(&s->fast, s->h, s->int32_ok, s->d_scn, s->d_comp) == 0;
@@ -946,7 +947,7 @@ extern "C" int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *s
 
 extern "C" int chm_set_bounded_search(chm_scenario *s, int32_t on) {
   if (!s) return CHM_ERR_ARG;
-  s->bounded = on != 0;
+  s->bounded = on == 2 ? 2 : (on != 0 ? 1 : 0);
   return CHM_OK;
 }
 

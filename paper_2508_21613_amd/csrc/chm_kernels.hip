@@ -354,17 +354,19 @@ __global__ void k_fill_u64(uint64_t *p, uint32_t n, uint64_t v) {
 }
 
 // step time of the pipelines that strategy 1 leaves in the fault-free layout
-__global__ void k_fixed_pipelines(DevScenario *scn) {
-  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+template <int SMAX>
+__global__ void __launch_bounds__(64) k_fixed_pipelines(DevScenario *scn) {
+  // one lane per untouched pipeline (at most DEV_MAX_D <= 64), then the maximum over the wave
   DevFamily &fam = scn->fam[1];
   if (fam.n_part == 0) return;
+  const int d = threadIdx.x;
   int64_t t = 0;
   bool fits = true;
-  for (int d = 0; d < scn->n_fixed; ++d) {
+  if (d < scn->n_fixed) {
     const DevClass &cls = scn->fixed[d];
-    int64_t F[DEV_MAX_S], B[DEV_MAX_S];
+    int64_t F[SMAX], B[SMAX];
 #pragma unroll
-    for (int j = 0; j < DEV_MAX_S; ++j) {
+    for (int j = 0; j < SMAX; ++j) {
       F[j] = 0; B[j] = 0;
       if (j < cls.n) {
         const int lo = scn->p0[j], hi = scn->p0[j + 1];
@@ -373,10 +375,12 @@ __global__ void k_fixed_pipelines(DevScenario *scn) {
         B[j] = scale_q16(scn->pb[hi] - scn->pb[lo], cls.q[j]);
       }
     }
-    const int64_t T = makespan_generic<DEV_MAX_S>(F, B, cls.n, cls.M) + (int64_t)(cls.n - 1) * scn->comm;
-    t = imax(t, T);
+    t = makespan_generic<SMAX>(F, B, cls.n, cls.M) + (int64_t)(cls.n - 1) * scn->comm;
   }
-  fam.fixed_step = fits ? t : CHM_INF_COST;
+  if (!fits) t = CHM_INF_COST;
+#pragma unroll
+  for (int off = 32; off >= 1; off >>= 1) t = imax(t, (int64_t)__shfl_xor((long long)t, off, 64));
+  if (threadIdx.x == 0) fam.fixed_step = t;
 }
 
 template <int SMAX>
@@ -593,9 +597,12 @@ int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream) {
   return (int)hipGetLastError();
 }
 
-int chmk_fixed_pipelines(DevScenario *d_scn, void *stream) {
-  hipLaunchKernelGGL(k_fixed_pipelines, dim3(1), dim3(64), 0, (hipStream_t)stream, d_scn);
-  return (int)hipGetLastError();
+int chmk_fixed_pipelines(DevScenario *d_scn, int32_t smax, void *stream) {
+  return dispatch_smax(smax, [&](auto tag) {
+    constexpr int SMAX = decltype(tag)::value;
+    hipLaunchKernelGGL(k_fixed_pipelines<SMAX>, dim3(1), dim3(64), 0, (hipStream_t)stream, d_scn);
+    return (int)hipGetLastError();
+  });
 }
 
 int chmk_rank_cuts(const DevScenario *d_scn, int k, const uint8_t *d_cuts, uint64_t n, uint64_t *d_ranks, void *stream) {

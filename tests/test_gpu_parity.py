@@ -87,16 +87,23 @@ def test_small_scenarios_every_cost_and_argmin(B, i):
         rc_g, best_g = g.search_best(mask)
         assert rc_g == rc_o, (mask, rc_g, rc_o)
         assert same_plan(best_g, best_o), (mask, best_g, best_o)
-    # bounded search: the same plans, ties included
-    g.set_bounded_search(True)
+    # bounded search: the same plans, ties included; mode 2 takes the seeds and the enumeration of candidates
+    # at these small sizes too
     g.set_timing(True)
-    for mask in [7] + [1 << f["strategy"] for f in o.families]:
-        rc_o, best_o = o.search(mask)
-        rc_g, best_g = g.search_best(mask)
-        assert rc_g == rc_o and same_plan(best_g, best_o), ("bounded", mask, best_g, best_o)
-        t = g.get_timing()
-        assert all(e <= f for e, f in zip(t["evaluated"], t["feasible"]))
-    g.set_bounded_search(False)
+    for mode in (1, 2):
+        g.set_bounded_search(mode)
+        for mask in [7] + [1 << f["strategy"] for f in o.families]:
+            rc_o, best_o = o.search(mask)
+            rc_g, best_g = g.search_best(mask)
+            assert rc_g == rc_o and same_plan(best_g, best_o), ("bounded", mode, mask, best_g, best_o)
+            t = g.get_timing()
+            assert all(e <= f for e, f in zip(t["evaluated"], t["feasible"]))
+        for f in o.families:
+            lo, n = f["n_part"] // 3, max(1, f["n_part"] // 2)
+            rc_o, best_o, _ = o.search_range(f["strategy"], lo, n)
+            rc_g, best_g = g.search_range(f["strategy"], lo, n)
+            assert rc_g == rc_o and same_plan(best_g, best_o), ("bounded range", mode, f["strategy"], best_g, best_o)
+    g.set_bounded_search(0)
     for idx in range(0, o.n_plans, max(1, o.n_plans // 25)):
         d_o, d_g = o.decode(idx), g.decode_plan(idx)
         d_o.update(cost=0, t_step_us=0, t_trans_us=0)      # the library's decoding is structural only
@@ -214,6 +221,29 @@ def test_bounded_search_returns_the_exhaustive_winner(B, name):
         assert all(b <= e for b, e in zip(t_b["evaluated"], t_e["evaluated"]))
         print("bounded", name, "mask", mask, "fit", t_b["feasible"], "evaluated", t_b["evaluated"],
               "ms", [round(x, 3) for x in t_e["family_ms"]], "->", [round(x, 3) for x in t_b["family_ms"]], flush=True)
+
+
+@pytest.mark.parametrize("seed", range(7000, 7030))
+def test_bounded_search_on_seeded_mid_size_scenarios(B, seed):
+    """random shapes of 10^3..10^5 partitions per strategy (heterogeneous speeds, one or two failures, in turn with
+    activation memory, least-transfer assignment and communication rounds): the bounded search, with and
+    without its size thresholds, returns the oracle's exhaustive argmin"""
+    PP = 4 + seed % 3
+    sc = synth.small_random(seed, L=PP + 10 + seed % 8, PP=PP, DP=2 + seed % 3, M=3 + seed % 14)
+    if seed % 3 == 0:
+        sc = synth.with_activations(sc, seed)
+    if seed % 4 == 0:
+        sc = dict(sc, transfer_assign=1)
+    if seed % 5 == 0:
+        sc = dict(sc, allreduce_us=300 + seed % 700)
+    print("mid-size scenario", seed, {k: sc.get(k) for k in ("L", "PP", "DP", "M", "failed_nodes")}, flush=True)
+    o, g = O.Scenario(sc), B.Scenario(sc)
+    for mask in [7] + [1 << f["strategy"] for f in o.families]:
+        rc_o, best_o = o.search(mask)
+        for mode in (1, 2):
+            g.set_bounded_search(mode)
+            rc_g, best_g = g.search_best(mask)
+            assert rc_g == rc_o and same_plan(best_g, best_o), (seed, mask, mode, best_g, best_o)
 
 
 def test_bounded_search_over_the_whole_space_of_config4(B):
