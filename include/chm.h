@@ -229,8 +229,11 @@ int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
  * starts with the ranks around the time-balanced and the memory-balanced partition of each range, so that a
  * good cost is known early.  chm_timing.evaluated tells how many
  * partitions were evaluated in full; chm_timing.feasible then counts only those partitions that were looked
- * at one by one and fit.  Covers the range searches of the specialised kernels without cost store (other
- * paths evaluate everything).  Errors: CHM_ERR_ARG. */
+ * at one by one and fit.  Where the reroute vectors of a stage are too many to sweep inside the search kernel,
+ * a bounded search finds the least penalty of eq. (re-route) from the peers' capacities instead of sweeping them
+ * (some vector stays within v exactly when the peers can take all orphaned micro-batches within v each).  Covers
+ * the range searches of the specialised kernels without cost store (other paths evaluate everything).
+ * Errors: CHM_ERR_ARG. */
 int chm_set_bounded_search(chm_scenario *s, int32_t on);
 
 /* The distinct pipelines one plan of a strategy has to evaluate (pipelines with the same

@@ -61,6 +61,9 @@ struct FastTables {
 struct FastState {
   bool usable[3] = {false, false, false};   // per strategy: a specialised kernel covers this scenario
   bool split = false;                       // rerouting: vectors swept by k_sweep instead of inside the search kernel
+  // bounded search on the split path: the least penalty of a stage is found from the peers' capacities
+  // (k_least_penalty) instead of sweeping every reroute vector; set by the caller per search
+  bool penalty_by_capacity = false;
   // Range search of strategies 0 and 1: share of the partitions that pass the memory filter, estimated at load
   // from FIT_SAMPLES seeded random partitions; below QUEUE_BELOW_SHARE the search compacts the partitions that
   // fit through a ring per wave (k_fast_search, QUEUED).  queue_mode: -1 = by that estimate, 0 = never, 1 = always.

@@ -1128,6 +1128,41 @@ __global__ void __launch_bounds__(BLOCK) k_sweep(const uint32_t *__restrict__ ru
   if (live && n) atomicMin(&pen_best[(size_t)part * DEV_MAX_AFF + a], pen);
 }
 
+// The least penalty of one affected stage without looking at the vectors one by one.  A vector r (r_i extra
+// micro-batches on peer i, r_i <= cap, sum = orphans) has penalty max_i r_i * w_i <= v exactly when r_i <=
+// floor(v / w_i) for every peer, so some vector reaches v iff sum_i min(cap, floor(v / w_i)) >= orphans.  That
+// sum grows with v: the least v that satisfies it, found by bisection, is the minimum over all vectors (it is
+// one of the products r_i * w_i, since the sum only steps there).  One lane per partition; the winner's
+// vectors are recovered afterwards as usual.
+__global__ void __launch_bounds__(BLOCK) k_least_penalty(const uint64_t *__restrict__ base, const uint32_t *__restrict__ weights,
+                                                         uint32_t *__restrict__ pen_best, uint32_t part_count, int a, int peers,
+                                                         uint32_t orphans, uint32_t cap) {
+  const uint32_t part = blockIdx.x * BLOCK + threadIdx.x;
+  if (part >= part_count || base[part] == ~0ull) return;
+  uint32_t w[FAST_MAX_P];
+  uint32_t w_max = 1;
+#pragma unroll
+  for (int i = 0; i < FAST_MAX_P; ++i) {
+    w[i] = i < peers ? weights[(size_t)part * (DEV_MAX_AFF * 8) + a * 8 + i] : 0u;
+    w_max = w[i] > w_max ? w[i] : w_max;
+  }
+  uint64_t lo = 0, hi = (uint64_t)orphans * w_max;       // every peer can take all orphans within hi (if the cap lets it)
+  while (lo < hi) {
+    const uint64_t v = lo + (hi - lo) / 2;
+    uint64_t room = 0;
+#pragma unroll
+    for (int i = 0; i < FAST_MAX_P; ++i) {
+      if (i < peers) {
+        const uint64_t fit = w[i] == 0 ? (uint64_t)cap : v / w[i];
+        room += fit < cap ? fit : (uint64_t)cap;
+      }
+    }
+    if (room >= orphans) hi = v;
+    else lo = v + 1;
+  }
+  pen_best[(size_t)part * DEV_MAX_AFF + a] = (uint32_t)lo;
+}
+
 // cost = cost without penalties + K * sum of the per-stage best penalties; argmin as usual
 __global__ void __launch_bounds__(BLOCK) k_combine(const uint64_t *__restrict__ base, const uint32_t *__restrict__ pen_best,
                                                    uint32_t part_count, int n_aff, uint64_t K, uint32_t index_base,
@@ -1877,7 +1912,12 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
     const uint32_t n_pen = sub.part_count * DEV_MAX_AFF;
     hipLaunchKernelGGL(k_fill_u32, dim3((n_pen + 255) / 256), dim3(256), 0, st, f->d_pen, n_pen, 0xffffffffu);
     const uint32_t bx = (sub.part_count + BLOCK - 1) / BLOCK;
-    for (int s = 0; s < h.n_aff; ++s) {
+    for (int s = 0; s < h.n_aff && f->penalty_by_capacity; ++s) {
+      const uint32_t total = (uint32_t)h.aff_total[s];
+      hipLaunchKernelGGL(k_least_penalty, dim3(bx), dim3(BLOCK), 0, st, f->d_base, f->d_weights, f->d_pen, sub.part_count, s,
+                         h.aff_peers[s], total, h.rcap > 0 ? (uint32_t)h.rcap : total);
+    }
+    for (int s = 0; s < h.n_aff && !f->penalty_by_capacity; ++s) {
       const uint32_t n_runs = t.run_count[s];
       // about 8192 workgroups in total, chunks of at least 64 runs
       uint32_t chunks = std::max<uint32_t>(1, std::min<uint32_t>(8192 / bx + 1, n_runs / 64 + 1));

@@ -609,6 +609,7 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
 // searched range by range with the bound applied per run and per partition.  The seeds' best plan competes
 // with the result (it is among the candidates as well; equal plans compare equal).
 int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, uint64_t *position, hipStream_t st) {
+  s->fast.penalty_by_capacity = s->bounded && out != nullptr;
   if (!(s->bounded && out != nullptr)) return run_jobs(s, given, out, position, st, ~0ull, false);
   const uint64_t seeds_from = s->bounded == 2 ? 1 : (1u << 16), enumerate_from = s->bounded == 2 ? 1 : ENUMERATE_FROM;
   std::vector<Job> seeds;

@@ -123,6 +123,8 @@ COMPACTION = [
     ("config2_act_allreduce", lambda: dict(synth.with_activations(synth.config2(), 31), allreduce_us=900)),
     ("config5_double_assign", lambda: dict(synth.config5([3, 17]), transfer_assign=1)),
     ("config3", lambda: synth.config3()),
+    ("config3_cap12", lambda: dict(synth.config3(), reroute_cap=12)),
+    ("config3_uncapped_m8", lambda: dict(synth.config3(), reroute_cap=0, M=8)),
     ("config4", lambda: synth.config4(mem_cap_mib=synth.CONFIG4_CAP_30PCT)),
     ("config1_ties", lambda: _uniform_layers(synth.config1(), 9000)),
     ("config2_ties", lambda: _uniform_layers(synth.config2(), 8000)),
