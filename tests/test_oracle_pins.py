@@ -838,3 +838,23 @@ def test_replan_with_communication_rounds():
             sizes = [hi - lo for n, cuts in zip(got["length"], got["cuts"]) for lo, hi in zip([0] + cuts, cuts + [rp["L"]])]
             assert got["comm_rounds"] == max(sizes)
             assert got["t_step_us"] == max(got["pipeline_us"]) + rp["allreduce_us"] * got["comm_rounds"]
+
+
+def test_least_reroute_penalty_equals_the_capacity_threshold():
+    """what the bounded search on the GPU relies on for large reroute spaces: the least penalty over all valid
+    vectors (enumerated here through the oracle's unranking) is the least v at which the peers together can take
+    all orphaned micro-batches, peer i at most min(cap, floor(v / w_i)) of them"""
+    rng = np.random.default_rng(23)
+    for _ in range(60):
+        p = int(rng.integers(1, 5))
+        n = int(rng.integers(1, 9))
+        cap = int(rng.integers(1, n + 1)) if rng.integers(2) else n
+        if p * cap < n:
+            continue
+        w = [int(x) for x in rng.integers(1, 4000, p)]
+        count = O.reroute_count(p, n, cap)
+        best = min(max(r * wi for r, wi in zip(O.reroute_unrank(p, n, cap, k), w)) for k in range(count))
+        v = 0
+        while sum(min(cap, v // wi) for wi in w) < n:
+            v += 1
+        assert v == best, (p, n, cap, w, v, best)
