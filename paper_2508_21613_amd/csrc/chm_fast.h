@@ -147,5 +147,6 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
 // convention as fast_search.
 int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t local_first,
                        uint64_t count, int64_t *d_costs, void *stream);
-void fast_release(FastState *f);
+// device_idle: the caller has waited for the device, the buffers can be reused at once
+void fast_release(FastState *f, bool device_idle = false);
 #endif

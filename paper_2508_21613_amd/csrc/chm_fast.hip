@@ -2053,25 +2053,25 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
   return 0;
 }
 
-void fast_release(FastState *f) {
-  if (f->d_cand_low) pool_release(f->d_cand_low);
-  if (f->d_cand_ways) pool_release(f->d_cand_ways);
-  if (f->d_cand_count) pool_release(f->d_cand_count);
-  if (f->d_cand_pos) pool_release(f->d_cand_pos);
-  if (f->d_cand_list) pool_release(f->d_cand_list);
+void fast_release(FastState *f, bool device_idle) {
+  if (f->d_cand_low) pool_release(f->d_cand_low, device_idle);
+  if (f->d_cand_ways) pool_release(f->d_cand_ways, device_idle);
+  if (f->d_cand_count) pool_release(f->d_cand_count, device_idle);
+  if (f->d_cand_pos) pool_release(f->d_cand_pos, device_idle);
+  if (f->d_cand_list) pool_release(f->d_cand_list, device_idle);
   f->d_cand_low = nullptr; f->d_cand_ways = nullptr; f->d_cand_count = nullptr; f->d_cand_pos = nullptr; f->d_cand_list = nullptr;
   f->cand_capacity = 0; f->cand_ways_capacity = 0;
-  if (f->d_cut_count) pool_release(f->d_cut_count);
-  if (f->d_cut_pos) pool_release(f->d_cut_pos);
-  if (f->d_cut_list) pool_release(f->d_cut_list);
+  if (f->d_cut_count) pool_release(f->d_cut_count, device_idle);
+  if (f->d_cut_pos) pool_release(f->d_cut_pos, device_idle);
+  if (f->d_cut_list) pool_release(f->d_cut_list, device_idle);
   f->d_cut_count = nullptr; f->d_cut_pos = nullptr; f->d_cut_list = nullptr;
-  if (f->d_rowkey) pool_release(f->d_rowkey);
-  if (f->d_pen) pool_release(f->d_pen);
-  if (f->d_weights) pool_release(f->d_weights);
-  if (f->d_base) pool_release(f->d_base);
-  if (f->d_vecs) pool_release(f->d_vecs);
-  if (f->d_runs) pool_release(f->d_runs);
-  if (f->d_tables) pool_release(f->d_tables);
+  if (f->d_rowkey) pool_release(f->d_rowkey, device_idle);
+  if (f->d_pen) pool_release(f->d_pen, device_idle);
+  if (f->d_weights) pool_release(f->d_weights, device_idle);
+  if (f->d_base) pool_release(f->d_base, device_idle);
+  if (f->d_vecs) pool_release(f->d_vecs, device_idle);
+  if (f->d_runs) pool_release(f->d_runs, device_idle);
+  if (f->d_tables) pool_release(f->d_tables, device_idle);
   f->d_rowkey = nullptr; f->d_pen = nullptr; f->d_weights = nullptr; f->d_base = nullptr;
   f->d_vecs = nullptr;
   f->d_runs = nullptr;

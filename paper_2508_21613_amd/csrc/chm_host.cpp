@@ -329,14 +329,19 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
 
 void release(chm_scenario *s) {
   if (!s) return;
-  fast_release(&s->fast);
+  // one wait for the handle's device, then every buffer goes back to the allocator without further waits
+  int current = 0;
+  const bool switched = hipGetDevice(&current) == hipSuccess && current != s->device && hipSetDevice(s->device) == hipSuccess;
+  const bool idle = hipDeviceSynchronize() == hipSuccess;
+  fast_release(&s->fast, idle);
   for (auto &e : s->ev) if (e) (void)hipEventDestroy(e);
-  if (s->h_pinned) pool_release(s->h_pinned);
-  if (s->d_xfer) pool_release(s->d_xfer);
-  if (s->d_winner) pool_release(s->d_winner);
-  if (s->d_slots) pool_release(s->d_slots);
-  if (s->d_comp) pool_release(s->d_comp);
-  if (s->d_scn) pool_release(s->d_scn);
+  if (s->h_pinned) pool_release(s->h_pinned, idle);
+  if (s->d_xfer) pool_release(s->d_xfer, idle);
+  if (s->d_winner) pool_release(s->d_winner, idle);
+  if (s->d_slots) pool_release(s->d_slots, idle);
+  if (s->d_comp) pool_release(s->d_comp, idle);
+  if (s->d_scn) pool_release(s->d_scn, idle);
+  if (switched) (void)hipSetDevice(current);
   delete s;
 }
 

@@ -57,7 +57,7 @@ void *take(size_t bytes, bool pinned) {
 void *pool_device_alloc(size_t bytes) { return take(bytes, false); }
 void *pool_pinned_alloc(size_t bytes) { return take(bytes, true); }
 
-void pool_release(void *p) {
+void pool_release(void *p, bool device_idle) {
   if (!p) return;
   Block b;
   {
@@ -68,7 +68,14 @@ void pool_release(void *p) {
     g_live.erase(it);
   }
   const bool keep = b.size <= KEEP_BLOCK_MAX;
-  if (keep) {
+  if (keep && device_idle) {
+    std::lock_guard<std::mutex> hold(g_lock);
+    if (g_kept_bytes[b.pinned] + b.size <= KEEP_TOTAL_MAX) {
+      g_kept[std::make_tuple(b.pinned ? -1 : b.device, b.pinned, b.size)].push_back(p);
+      g_kept_bytes[b.pinned] += b.size;
+      return;
+    }
+  } else if (keep) {
     // whatever still reads or writes the block has to be over before someone else gets it (hipFree waits too)
     int current = 0;
     const bool switched = hipGetDevice(&current) == hipSuccess && current != b.device && hipSetDevice(b.device) == hipSuccess;

@@ -13,6 +13,7 @@ void *pool_device_alloc(size_t bytes);
 // Pinned host memory; nullptr on failure.
 void *pool_pinned_alloc(size_t bytes);
 // Gives a block of either kind back (nullptr is ignored).  As with hipFree, work that still uses the block
-// must have finished: the call waits for the device the block belongs to before the block can be reused.
-void pool_release(void *p);
+// must have finished: the call waits for the device the block belongs to before the block can be reused,
+// unless the caller has just done so itself for all the blocks it is about to release (device_idle).
+void pool_release(void *p, bool device_idle = false);
 #endif
