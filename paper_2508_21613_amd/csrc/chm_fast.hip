@@ -160,6 +160,32 @@ __device__ __forceinline__ int class_time(ClsPtr c, int (&F)[N], int (&B)[N]) {
   return makespan32<N>(F, B, c->M) + c->comm_total;
 }
 
+// The least of max_i r_i * w_i over all valid reroute vectors (r_i <= cap, sum = orphans) without looking at
+// them: some vector stays within v exactly when sum_i min(cap, floor(v / w_i)) >= orphans, the sum grows with
+// v, and the least such v, found by bisection, is the minimum (see k_least_penalty).  Penalties are below 2^31
+// wherever these kernels run (load-time bound), so 32-bit divisions do.
+__device__ __forceinline__ uint32_t least_penalty32(const uint32_t (&w)[FAST_MAX_P], int peers, uint32_t orphans, uint32_t cap) {
+  uint32_t w_max = 1;
+#pragma unroll
+  for (int i = 0; i < FAST_MAX_P; ++i) w_max = (i < peers && w[i] > w_max) ? w[i] : w_max;
+  const uint64_t all = (uint64_t)orphans * w_max;
+  uint32_t lo = 0, hi = all > 0x7fffffffull ? 0x7fffffffu : (uint32_t)all;
+  while (lo < hi) {
+    const uint32_t v = lo + (hi - lo) / 2;
+    uint32_t room = 0;
+#pragma unroll
+    for (int i = 0; i < FAST_MAX_P; ++i) {
+      if (i < peers) {
+        const uint32_t fit = w[i] == 0 ? cap : v / w[i];
+        room += fit < cap ? fit : cap;
+      }
+    }
+    if (room >= orphans) hi = v;
+    else lo = v + 1;
+  }
+  return lo;
+}
+
 // min over all reroute vectors of one stage of max_i r_i * w_i, run by run (see FastTables):
 // within a run only the last two entries change, by +1 and -1, so their products are carried
 // by an add and a subtract and every vector costs those two, one v_max3_u32 and a share of a
@@ -390,6 +416,8 @@ struct FastLaunch {
   const uint4 *cut_list;
   const uint32_t *cut_pos;
   const uint32_t *cut_count;
+  // QUEUED kernels of the rerouting strategy: least penalty per stage from the peers' capacities instead of a sweep
+  int32_t capacity_penalty = 0;
 };
 
 // Entries of a wave's queue of partitions that fit (QUEUED kernels): a ring of twice the wave width,
@@ -532,8 +560,9 @@ k_fast_search(FastLaunch a) {
           }
         }
         bool fits = live && largest_peak<SP, STRAT>(ff, ms, as) <= cap;
-        n_fit += (uint32_t)__popcll(__builtin_amdgcn_ballot_w64(fits));
-        if (bounded) {                        // uniform
+        const uint64_t in_memory = __builtin_amdgcn_ballot_w64(fits);
+        n_fit += (uint32_t)__popcll(in_memory);
+        if (bounded && in_memory != 0) {      // uniform; nothing to bound where nothing fits
           // Lower bound of the plan's cost.  Every stage of a pipeline runs its M forwards and M backwards one
           // after the other, so the pipeline takes at least M x the largest (forward + backward) of its chain;
           // rounds of gradient communication: at least the layers of the largest stage; a stage that lost
@@ -794,6 +823,16 @@ k_fast_search(FastLaunch a) {
           const RowPtr runs = as_const(a.runs) + tab->run_off[st];
           const uint32_t n_runs = tab->run_count[st];
           uint32_t pen = 0;
+          if (QUEUED && a.capacity_penalty) {
+            // reroute spaces too large to sweep here (a bounded search does not use the sweep kernels)
+            uint32_t w[FAST_MAX_P];
+#pragma unroll
+            for (int i = 0; i < FAST_MAX_P; ++i) w[i] = i < p ? peer_time(f_st, b_st, scn->aff_q[st][i < p ? i : 0]) : 0u;
+            const uint32_t orphans = (uint32_t)scn->aff_total[st];
+            pen = least_penalty32(w, p, orphans, scn->rcap > 0 ? (uint32_t)scn->rcap : orphans);
+            t_step += (int)pen;
+            continue;
+          }
           const uint32_t shape = tab->unrolled_shape[st];
           if (shape != 0) {
             // small uncapped spaces: sweep unrolled at compile time over a table of products
@@ -1699,6 +1738,7 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
                                      (a.strategy != 2 && f->queue_mode != 0 &&
                                       (f->queue_mode > 0 || f->fit_share[a.strategy] < QUEUE_BELOW_SHARE)));
   if (!queued) { fl.s.incumbent = nullptr; fl.s.evaluated = nullptr; }
+  fl.capacity_penalty = (queued && a.strategy == 2 && f->split) ? 1 : 0;
   int rc;
   if (a.strategy == 0) rc = launch_by_stages<0>(sp, fl, blocks, tile_bytes, st, queued);
   else if (a.strategy == 1) rc = launch_by_stages<1>(sp, fl, blocks, tile_bytes, st, queued);
@@ -1889,7 +1929,7 @@ int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunc
 bool fast_can_bound(const FastState *f, const SearchLaunch &a) {
   if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return false;
   if (a.ranks != nullptr || a.cuts != nullptr || a.costs_out != nullptr) return false;
-  return !(a.strategy == 2 && f->split);
+  return true;                          // (large reroute spaces: least penalty from the peers' capacities)
 }
 
 int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void *stream) {
@@ -1898,6 +1938,8 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
   hipStream_t st = (hipStream_t)stream;
   const bool list = a.ranks != nullptr || a.cuts != nullptr;
   if (!(a.strategy == 2 && f->split)) return list ? launch_list(f, h, a, st) : launch_search(f, h, a, nullptr, nullptr, st);
+  // a bounded range search does without the sweep kernels: its queued kernel bounds and evaluates in one pass
+  if (a.incumbent != nullptr && !list && a.costs_out == nullptr) return launch_search(f, h, a, nullptr, nullptr, st);
   if (list || a.costs_out != nullptr) return 1;   // the generic kernel handles lists for this shape
   if (!ensure_scratch(f)) return -1;
   // split rerouting path, FAST_SUB partitions per pass: base costs and peer stage times, then one
