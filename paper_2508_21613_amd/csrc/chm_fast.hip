@@ -1296,20 +1296,42 @@ __global__ void __launch_bounds__(BLOCK) k_expand(ExpandArgs a) {
     }
     pen += m;
   }
-  a.costs[gid] = base == ~0ull ? CHM_INF_COST : (int64_t)(base + a.K * pen);
+  __builtin_nontemporal_store((int64_t)(base == ~0ull ? CHM_INF_COST : (int64_t)(base + a.K * pen)), &a.costs[gid]);
 }
 
 // The same with 32-bit index arithmetic, for reroute spaces below 2^31 vectors per partition and launches
 // of at most 2^31 plan indices: the host passes the partition (relative to the pass) and the reroute rank of
 // the launch's first plan index, so a lane divides first_rr + gid, which fits 32 bits.
+// Division of a 32-bit number by a divisor fixed at launch: one multiply-high, two shifts, an add and a subtract
+// (round-up method of Granlund and Montgomery), exact for every dividend; the compiler's generic 32-bit
+// division costs about five times as much.
+struct FastDiv {
+  uint32_t d, m, sh1, sh2;
+};
+static FastDiv make_fast_div(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;                               // ceil(log2 d)
+  f.m = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d) + 1u;
+  f.sh1 = l < 1 ? l : 1;
+  f.sh2 = l > 0 ? l - 1 : 0;
+  return f;
+}
+__device__ __forceinline__ uint32_t fast_div(uint32_t n, const FastDiv &f) {
+  const uint32_t t = __umulhi(f.m, n);
+  return (t + ((n - t) >> f.sh1)) >> f.sh2;
+}
+
 struct ExpandArgs32 {
   const uint64_t *base;
   const uint32_t *weights;
   const uint32_t *rows[DEV_MAX_AFF];
-  uint32_t R[DEV_MAX_AFF];
+  FastDiv R[DEV_MAX_AFF];
   int32_t stride[DEV_MAX_AFF], peers[DEV_MAX_AFF];
   int32_t n_aff;
-  uint32_t R_joint, first_part, first_rr, count;
+  FastDiv R_joint;
+  uint32_t first_part, first_rr, count;
   uint64_t K;
   int64_t *costs;
 };
@@ -1322,8 +1344,8 @@ constexpr int EXPAND_PER = 8;
 
 __device__ __forceinline__ int64_t expand_one(const ExpandArgs32 &a, uint32_t gid) {
   const uint32_t idx = a.first_rr + gid;
-  const uint32_t q = idx / a.R_joint;
-  uint32_t rr = idx - q * a.R_joint;
+  const uint32_t q = fast_div(idx, a.R_joint);
+  uint32_t rr = idx - q * a.R_joint.d;
   const uint32_t pl = a.first_part + q;
   const uint64_t base = a.base[pl];
   uint64_t pen = 0;
@@ -1334,8 +1356,8 @@ __device__ __forceinline__ int64_t expand_one(const ExpandArgs32 &a, uint32_t gi
     if (s < a.n_aff) {
       uint32_t r = rr;
       if (s > 0) {                                  // the first stage takes what is left: no division
-        const uint32_t qq = rr / a.R[s];
-        r = rr - qq * a.R[s];
+        const uint32_t qq = fast_div(rr, a.R[s]);
+        r = rr - qq * a.R[s].d;
         rr = qq;
       }
       const uint32_t *w = a.weights + (size_t)pl * (DEV_MAX_AFF * 8) + s * 8;
@@ -1355,17 +1377,29 @@ __device__ __forceinline__ int64_t expand_one(const ExpandArgs32 &a, uint32_t gi
 }
 
 __global__ void __launch_bounds__(BLOCK) k_expand32(ExpandArgs32 a) {
-  const uint32_t first = blockIdx.x * (EXPAND_PER * BLOCK) + threadIdx.x;
+  // a lane owns two neighbouring plan indices per tile of 2 * BLOCK and stores them as one 16-byte word
+  const uint32_t first = blockIdx.x * (EXPAND_PER * BLOCK) + 2 * threadIdx.x;
   int64_t cost[EXPAND_PER];
 #pragma unroll
   for (int rep = 0; rep < EXPAND_PER; ++rep) {
-    const uint32_t gid = first + rep * BLOCK;
+    const uint32_t gid = first + (rep >> 1) * (2 * BLOCK) + (rep & 1);
     cost[rep] = expand_one(a, gid < a.count ? gid : a.count - 1);   // lanes past the end redo the last index
   }
+  const bool aligned = (((uintptr_t)a.costs) & 15u) == 0;            // uniform
 #pragma unroll
-  for (int rep = 0; rep < EXPAND_PER; ++rep) {
-    const uint32_t gid = first + rep * BLOCK;
-    if (gid < a.count) a.costs[gid] = cost[rep];
+  for (int rep = 0; rep < EXPAND_PER; rep += 2) {
+    const uint32_t gid = first + (rep >> 1) * (2 * BLOCK);
+    // streamed out, never read back here
+    if (aligned && gid + 1 < a.count) {
+      typedef long long pair_t __attribute__((ext_vector_type(2)));
+      pair_t v;
+      v.x = cost[rep];
+      v.y = cost[rep + 1];
+      __builtin_nontemporal_store(v, (pair_t *)(a.costs + gid));
+    } else {
+      if (gid < a.count) __builtin_nontemporal_store(cost[rep], &a.costs[gid]);
+      if (gid + 1 < a.count) __builtin_nontemporal_store(cost[rep + 1], &a.costs[gid + 1]);
+    }
   }
 }
 
@@ -2069,8 +2103,8 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
         ExpandArgs32 x;
         memset(&x, 0, sizeof(x));
         x.base = e.base; x.weights = e.weights; x.n_aff = e.n_aff; x.K = e.K;
-        for (int s = 0; s < h.n_aff; ++s) { x.rows[s] = e.rows[s]; x.R[s] = (uint32_t)e.R[s]; x.stride[s] = e.stride[s]; x.peers[s] = e.peers[s]; }
-        x.R_joint = (uint32_t)R;
+        for (int s = 0; s < h.n_aff; ++s) { x.rows[s] = e.rows[s]; x.R[s] = make_fast_div((uint32_t)e.R[s]); x.stride[s] = e.stride[s]; x.peers[s] = e.peers[s]; }
+        x.R_joint = make_fast_div((uint32_t)R);
         x.first_part = (uint32_t)(first / R - p);
         x.first_rr = (uint32_t)(first % R);
         x.count = (uint32_t)std::min<uint64_t>(e.count - done, (1ull << 31) - (1ull << 20));
