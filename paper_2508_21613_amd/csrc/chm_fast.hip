@@ -1403,6 +1403,74 @@ __global__ void __launch_bounds__(BLOCK) k_expand32(ExpandArgs32 a) {
   }
 }
 
+// One stage lost nodes and its vector table is small: the table and the data of the partitions a workgroup's
+// plan indices belong to (cost without penalty, peer stage times) are staged in LDS first, so that the vector
+// memory path carries the stores and little else (with all three reads per plan index going through it the
+// kernel was bound by the address and data path of the CU's texture unit at about 350 G plan indices/s).
+constexpr int EXPAND_REC = 3;         // uint4 words per partition record: cost, 8 peer stage times
+
+__global__ void __launch_bounds__(BLOCK) k_expand32_lds(ExpandArgs32 a, uint32_t max_parts) {
+  extern __shared__ uint4 staged[];   // [R * stride / 4] rows, then [max_parts][EXPAND_REC] partition records
+  const uint32_t R = a.R_joint.d;
+  const uint32_t row_words = R * ((uint32_t)a.stride[0] / 4u);
+  uint4 *rec = staged + row_words;
+  const uint32_t tile_first = blockIdx.x * (EXPAND_PER * BLOCK);
+  const uint32_t tile_last = min(tile_first + EXPAND_PER * BLOCK, a.count) - 1;   // tile_first < count by the grid size
+  const uint32_t p_first = fast_div(a.first_rr + tile_first, a.R_joint);
+  const uint32_t n_parts = min(fast_div(a.first_rr + tile_last, a.R_joint) - p_first + 1, max_parts);
+  const uint4 *rows4 = (const uint4 *)a.rows[0];
+  for (uint32_t i = threadIdx.x; i < row_words; i += BLOCK) staged[i] = rows4[i];
+  for (uint32_t i = threadIdx.x; i < n_parts; i += BLOCK) {
+    const uint32_t pl = a.first_part + p_first + i;
+    const uint64_t b = a.base[pl];
+    const uint4 *w4 = (const uint4 *)(a.weights + (size_t)pl * (DEV_MAX_AFF * 8));
+    rec[i * EXPAND_REC] = make_uint4((uint32_t)b, (uint32_t)(b >> 32), 0u, 0u);
+    rec[i * EXPAND_REC + 1] = w4[0];
+    rec[i * EXPAND_REC + 2] = w4[1];
+  }
+  __syncthreads();
+  const uint32_t first = tile_first + 2 * threadIdx.x;
+  int64_t cost[EXPAND_PER];
+#pragma unroll
+  for (int rep = 0; rep < EXPAND_PER; ++rep) {
+    uint32_t gid = first + (rep >> 1) * (2 * BLOCK) + (rep & 1);
+    gid = gid < a.count ? gid : a.count - 1;                        // lanes past the end redo the last index
+    const uint32_t idx = a.first_rr + gid;
+    const uint32_t q = fast_div(idx, a.R_joint);
+    const uint32_t rr = idx - q * R;
+    uint32_t lp = q - p_first;
+    lp = lp < n_parts ? lp : n_parts - 1;
+    const uint4 head = rec[lp * EXPAND_REC], w_lo = rec[lp * EXPAND_REC + 1];
+    const uint64_t base = (uint64_t)head.x | ((uint64_t)head.y << 32);
+    uint32_t m;
+    if (a.stride[0] == 4) {
+      const uint4 row = staged[rr];
+      m = max(max(__umul24(row.x, w_lo.x), __umul24(row.y, w_lo.y)), max(__umul24(row.z, w_lo.z), __umul24(row.w, w_lo.w)));
+    } else {
+      const uint4 w_hi = rec[lp * EXPAND_REC + 2];
+      const uint4 row = staged[2 * rr], row2 = staged[2 * rr + 1];
+      m = max(max(__umul24(row.x, w_lo.x), __umul24(row.y, w_lo.y)), max(__umul24(row.z, w_lo.z), __umul24(row.w, w_lo.w)));
+      m = max(m, max(max(__umul24(row2.x, w_hi.x), __umul24(row2.y, w_hi.y)), max(__umul24(row2.z, w_hi.z), __umul24(row2.w, w_hi.w))));
+    }
+    cost[rep] = base == ~0ull ? CHM_INF_COST : (int64_t)(base + a.K * m);
+  }
+  const bool aligned = (((uintptr_t)a.costs) & 15u) == 0;            // uniform
+#pragma unroll
+  for (int rep = 0; rep < EXPAND_PER; rep += 2) {
+    const uint32_t gid = first + (rep >> 1) * (2 * BLOCK);
+    if (aligned && gid + 1 < a.count) {
+      typedef long long pair_t __attribute__((ext_vector_type(2)));
+      pair_t v;
+      v.x = cost[rep];
+      v.y = cost[rep + 1];
+      __builtin_nontemporal_store(v, (pair_t *)(a.costs + gid));
+    } else {
+      if (gid < a.count) __builtin_nontemporal_store(cost[rep], &a.costs[gid]);
+      if (gid + 1 < a.count) __builtin_nontemporal_store(cost[rep + 1], &a.costs[gid + 1]);
+    }
+  }
+}
+
 __global__ void k_fill_u32(uint32_t *p, uint32_t n, uint32_t v) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = v;
@@ -2109,7 +2177,14 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
         x.first_rr = (uint32_t)(first % R);
         x.count = (uint32_t)std::min<uint64_t>(e.count - done, (1ull << 31) - (1ull << 20));
         x.costs = e.costs + done;
-        hipLaunchKernelGGL(k_expand32, dim3((x.count + BLOCK * EXPAND_PER - 1) / (BLOCK * EXPAND_PER)), dim3(BLOCK), 0, st, x);
+        // one affected stage with a table of at most 32 KB: rows and partition data through LDS
+        const uint32_t row_bytes = (uint32_t)R * (uint32_t)x.stride[0] * 4u;
+        const uint32_t max_parts = (uint32_t)((uint64_t)BLOCK * EXPAND_PER / R) + 2;
+        if (h.n_aff == 1 && R >= 16 && row_bytes <= (32u << 10))
+          hipLaunchKernelGGL(k_expand32_lds, dim3((x.count + BLOCK * EXPAND_PER - 1) / (BLOCK * EXPAND_PER)), dim3(BLOCK),
+                             row_bytes + max_parts * EXPAND_REC * sizeof(uint4), st, x, max_parts);
+        else
+          hipLaunchKernelGGL(k_expand32, dim3((x.count + BLOCK * EXPAND_PER - 1) / (BLOCK * EXPAND_PER)), dim3(BLOCK), 0, st, x);
         done += x.count;
       }
       if (hipGetLastError() != hipSuccess) return -1;
