@@ -8,7 +8,8 @@ enum {
   FAST_MAX_P = 8,            // peers per affected stage the specialised sweeps are instantiated for
   FAST_FUSED_R = 4096,       // up to this many reroute vectors (all stages) the sweep runs inside the search kernel
   FAST_SPLIT_R = 1 << 23,    // up to this many per stage the vectors are tabulated and swept by a kernel of their own
-  FAST_SUB = 1 << 18,        // partitions per pass of the split and scoring paths (bounds their scratch memory: 38 MB)
+  FAST_SUB = 1 << 20,        // partitions per pass of the split and scoring paths (bounds their scratch memory: 152 MB;
+                             // the scratch is sized for the passes actually asked for and grows when needed)
   LIST_SUB = 1 << 22         // list entries per filter + search pass of explicit lists (scratch: 80 MB)
 };
 
@@ -78,6 +79,7 @@ struct FastState {
   uint32_t *d_weights = nullptr;            // [partition][affected stage][8] peer stage times
   uint32_t *d_pen = nullptr;                // [partition][4] best penalty per affected stage
   uint64_t *d_rowkey = nullptr;             // [4] (penalty << 32 | row) of the winning partition
+  uint32_t scratch_parts = 0;               // partitions d_base, d_weights and d_pen have room for
   // scratch of explicit lists, LIST_SUB entries at a time; allocated when first needed
   void *d_cut_list = nullptr;               // [entry] cut positions of the entries that fit in memory, 16 bytes each
   uint32_t *d_cut_pos = nullptr;            // [entry] their list positions

@@ -1750,12 +1750,17 @@ namespace {
 
 // scratch of the split rerouting path and of plan-index scoring: per partition of a pass the cost without
 // penalties, the peer stage times and the best penalty per affected stage
-bool ensure_scratch(FastState *f) {
-  if (f->d_base && f->d_weights && f->d_pen) return true;
-  bool ok = true;
-  if (!f->d_base) ok = ok && pool_take(f->d_base, (size_t)FAST_SUB * sizeof(uint64_t));
-  if (!f->d_weights) ok = ok && pool_take(f->d_weights, (size_t)FAST_SUB * DEV_MAX_AFF * 8 * sizeof(uint32_t));
-  if (!f->d_pen) ok = ok && pool_take(f->d_pen, (size_t)FAST_SUB * DEV_MAX_AFF * sizeof(uint32_t));
+bool ensure_scratch(FastState *f, uint64_t parts) {
+  const uint32_t need = (uint32_t)std::min<uint64_t>(FAST_SUB, std::max<uint64_t>(parts, 1 << 12));
+  if (f->d_base && f->d_weights && f->d_pen && f->scratch_parts >= need) return true;
+  if (f->d_pen) pool_release(f->d_pen);
+  if (f->d_weights) pool_release(f->d_weights);
+  if (f->d_base) pool_release(f->d_base);
+  f->d_pen = nullptr; f->d_weights = nullptr; f->d_base = nullptr; f->scratch_parts = 0;
+  bool ok = pool_take(f->d_base, (size_t)need * sizeof(uint64_t));
+  ok = ok && pool_take(f->d_weights, (size_t)need * DEV_MAX_AFF * 8 * sizeof(uint32_t));
+  ok = ok && pool_take(f->d_pen, (size_t)need * DEV_MAX_AFF * sizeof(uint32_t));
+  if (ok) f->scratch_parts = need;
   return ok;
 }
 
@@ -2043,7 +2048,7 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
   // a bounded range search does without the sweep kernels: its queued kernel bounds and evaluates in one pass
   if (a.incumbent != nullptr && !list && a.costs_out == nullptr) return launch_search(f, h, a, nullptr, nullptr, st);
   if (list || a.costs_out != nullptr) return 1;   // the generic kernel handles lists for this shape
-  if (!ensure_scratch(f)) return -1;
+  if (!ensure_scratch(f, a.part_count)) return -1;
   // split rerouting path, FAST_SUB partitions per pass: base costs and peer stage times, then one
   // sweep per affected stage over (partition blocks x row chunks), then the combine / argmin
   const FastTables &t = f->h_tables;
@@ -2088,7 +2093,7 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
                         uint64_t *d_out, void *stream) {
   (void)d_scn;
   if (!f->usable[2] || !f->split || h.n_aff == 0) return 1;
-  if (!ensure_scratch(f)) return -1;
+  if (!ensure_scratch(f, 1)) return -1;
   hipStream_t st = (hipStream_t)stream;
   // peer stage times of the winning partition (one-partition pass of the search kernel in split mode)
   SearchLaunch one;
@@ -2125,10 +2130,10 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
                        uint64_t count, int64_t *d_costs, void *stream) {
   if (!f->usable[2] || h.n_aff == 0) return 1;
   if (count == 0) return 0;
-  if (!ensure_scratch(f)) return -1;
   hipStream_t st = (hipStream_t)stream;
   const FastTables &t = f->h_tables;
   const uint64_t R = h.fam[2].n_reroute;
+  if (!ensure_scratch(f, (local_first + count - 1) / R - local_first / R + 1)) return -1;
   ExpandArgs e;
   memset(&e, 0, sizeof(e));
   e.base = f->d_base;
