@@ -80,6 +80,13 @@ struct FastState {
   uint32_t *d_pen = nullptr;                // [partition][4] best penalty per affected stage
   uint64_t *d_rowkey = nullptr;             // [4] (penalty << 32 | row) of the winning partition
   uint32_t scratch_parts = 0;               // partitions d_base, d_weights and d_pen have room for
+  // The run and vector tables of a rerouting family whose vectors are swept by kernels of their own (split) are
+  // large (tens of MB, milliseconds to enumerate) and a bounded search never reads them: they are built when an
+  // exhaustive search, a cost store or the recovery of a winner's vectors first asks for them.
+  bool reroute_tables_ready = false;
+  size_t vec_words = 0;                     // size of the vector table
+  const DevScenario *d_scn = nullptr;       // the handle's device tables (for that later build)
+  const uint64_t *d_comp = nullptr;
   // scratch of explicit lists, LIST_SUB entries at a time; allocated when first needed
   void *d_cut_list = nullptr;               // [entry] cut positions of the entries that fit in memory, 16 bytes each
   uint32_t *d_cut_pos = nullptr;            // [entry] their list positions

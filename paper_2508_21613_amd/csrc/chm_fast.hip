@@ -1576,6 +1576,107 @@ float estimate_fit_share(const DevScenario &h, const FastFamily &ff, int strat, 
 
 }  // namespace
 
+// Run and vector tables of the rerouting family (see FastTables): enumeration on the host, rows decoded on the
+// device, then the table block is uploaded again with the offsets and counts.  At load for families whose
+// vectors are swept inside the search kernel, on first need for the large ones.  False on a failed HIP call;
+// when table and count table disagree the strategy is handed back to the generic kernels (usable[2] = false).
+static bool build_reroute_tables(FastState *f, const DevScenario &h) {
+  FastTables *t = &f->h_tables;
+  // run tables (host enumeration in rank order: shared entries lexicographic, see FastTables)
+  std::vector<uint32_t> runs;
+  if (f->usable[2]) {
+    for (int a = 0; a < h.n_aff && f->usable[2]; ++a) {
+      int same = -1;
+      for (int b = 0; b < a; ++b)
+        if (h.aff_peers[b] == h.aff_peers[a] && h.aff_total[b] == h.aff_total[a]) same = b;
+      if (same >= 0) {
+        t->run_off[a] = t->run_off[same]; t->run_count[a] = t->run_count[same]; t->unrolled_shape[a] = t->unrolled_shape[same];
+        continue;
+      }
+      const int p = h.aff_peers[a], total = h.aff_total[a];
+      const int cap = h.rcap > 0 ? h.rcap : total;
+      t->run_off[a] = (uint32_t)runs.size();
+      uint64_t vectors = 0;
+      uint32_t n_runs = 0;
+      const int q = p >= 2 ? p - 2 : 0;                    // shared entries per run
+      std::vector<int> pre(q + 1, 0);
+      // odometer over the shared entries in lexicographic order
+      int rem = total;
+      int pos = 0;
+      bool fresh = true;                                   // entering position `pos` from the left
+      for (;;) {
+        if (pos == q) {
+          const int tail = p >= 2 ? 2 : 1;                 // entries left to fill
+          const int lo = p >= 2 ? std::max(0, rem - cap) : rem, hi = p >= 2 ? std::min(cap, rem) : rem;
+          if (lo <= hi && rem <= tail * cap) {
+            uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int i = 0; i < q; ++i) d[i] = (uint32_t)pre[i];
+            d[6] = (uint32_t)lo | ((uint32_t)rem << 16);
+            d[7] = (uint32_t)(hi - lo + 1);
+            runs.insert(runs.end(), d, d + 8);
+            vectors += d[7];
+            ++n_runs;
+          }
+          // step back to the previous position and advance it
+          --pos;
+          if (pos < 0) break;
+          rem += pre[pos];
+          ++pre[pos];
+          fresh = false;
+          continue;
+        }
+        if (fresh) pre[pos] = 0;
+        if (pre[pos] > std::min(cap, rem)) {               // exhausted this position
+          --pos;
+          if (pos < 0) break;
+          rem += pre[pos];
+          ++pre[pos];
+          fresh = false;
+          continue;
+        }
+        rem -= pre[pos];
+        ++pos;
+        fresh = true;
+      }
+      t->run_count[a] = n_runs;
+      if (vectors != h.aff_R[a]) f->usable[2] = false;     // table and count must agree
+      if (h.rcap <= 0 || h.rcap >= total) {                // uncapped: every composition is valid
+        const bool have = (p == 2 && (total == 8 || total == 16 || total == 32)) || (p == 3 && (total == 8 || total == 16));
+        if (have) t->unrolled_shape[a] = (uint32_t)p * 256u + (uint32_t)total;
+      }
+    }
+    if (!f->usable[2]) f->split = false;
+  }
+  if (!f->usable[2]) return true;
+  if (runs.empty()) runs.assign(8, 0);
+  if (f->d_runs) pool_release(f->d_runs);
+  if (f->d_vecs) pool_release(f->d_vecs);
+  f->d_runs = nullptr; f->d_vecs = nullptr;
+  bool up = pool_take(f->d_runs, runs.size() * sizeof(uint32_t));
+  up = up && hipMemcpy(f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
+  up = up && pool_take(f->d_vecs, f->vec_words * sizeof(uint32_t));
+  up = up && hipMemcpy(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice) == hipSuccess;
+  if (up) {
+    for (int a = 0; a < h.n_aff; ++a) {
+      const int stride = h.aff_peers[a] <= 4 ? 4 : 8;
+      hipLaunchKernelGGL(k_make_rows, dim3((t->vec_rows[a] + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, nullptr, f->d_scn, f->d_comp, a,
+                         f->d_vecs + t->vec_off[a], t->vec_rows[a], stride);
+    }
+    up = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+  }
+  f->reroute_tables_ready = up;
+  return up;
+}
+
+// 0: the tables are there; 1: building them showed that the specialised kernels do not cover this family;
+// negative: a HIP call failed
+static int ensure_reroute_tables(FastState *f, const DevScenario &h) {
+  if (f->reroute_tables_ready) return 0;
+  if (!f->usable[2]) return 1;
+  if (!build_reroute_tables(f, h)) return -1;
+  return f->usable[2] && f->reroute_tables_ready ? 0 : 1;
+}
+
 int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevScenario *d_scn, const uint64_t *d_comp) {
   for (bool &u : f->usable) u = false;
   f->split = false;
@@ -1663,87 +1764,18 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     f->usable[k] = ok;
     if (ok && k != 2) f->fit_share[k] = estimate_fit_share(h, ff, k, fam.stages);
   }
-  // run tables (host enumeration in rank order: shared entries lexicographic, see FastTables)
-  std::vector<uint32_t> runs;
-  if (f->usable[2]) {
-    for (int a = 0; a < h.n_aff && f->usable[2]; ++a) {
-      int same = -1;
-      for (int b = 0; b < a; ++b)
-        if (h.aff_peers[b] == h.aff_peers[a] && h.aff_total[b] == h.aff_total[a]) same = b;
-      if (same >= 0) {
-        t->run_off[a] = t->run_off[same]; t->run_count[a] = t->run_count[same]; t->unrolled_shape[a] = t->unrolled_shape[same];
-        continue;
-      }
-      const int p = h.aff_peers[a], total = h.aff_total[a];
-      const int cap = h.rcap > 0 ? h.rcap : total;
-      t->run_off[a] = (uint32_t)runs.size();
-      uint64_t vectors = 0;
-      uint32_t n_runs = 0;
-      const int q = p >= 2 ? p - 2 : 0;                    // shared entries per run
-      std::vector<int> pre(q + 1, 0);
-      // odometer over the shared entries in lexicographic order
-      int rem = total;
-      int pos = 0;
-      bool fresh = true;                                   // entering position `pos` from the left
-      for (;;) {
-        if (pos == q) {
-          const int tail = p >= 2 ? 2 : 1;                 // entries left to fill
-          const int lo = p >= 2 ? std::max(0, rem - cap) : rem, hi = p >= 2 ? std::min(cap, rem) : rem;
-          if (lo <= hi && rem <= tail * cap) {
-            uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            for (int i = 0; i < q; ++i) d[i] = (uint32_t)pre[i];
-            d[6] = (uint32_t)lo | ((uint32_t)rem << 16);
-            d[7] = (uint32_t)(hi - lo + 1);
-            runs.insert(runs.end(), d, d + 8);
-            vectors += d[7];
-            ++n_runs;
-          }
-          // step back to the previous position and advance it
-          --pos;
-          if (pos < 0) break;
-          rem += pre[pos];
-          ++pre[pos];
-          fresh = false;
-          continue;
-        }
-        if (fresh) pre[pos] = 0;
-        if (pre[pos] > std::min(cap, rem)) {               // exhausted this position
-          --pos;
-          if (pos < 0) break;
-          rem += pre[pos];
-          ++pre[pos];
-          fresh = false;
-          continue;
-        }
-        rem -= pre[pos];
-        ++pos;
-        fresh = true;
-      }
-      t->run_count[a] = n_runs;
-      if (vectors != h.aff_R[a]) f->usable[2] = false;     // table and count must agree
-      if (h.rcap <= 0 || h.rcap >= total) {                // uncapped: every composition is valid
-        const bool have = (p == 2 && (total == 8 || total == 16 || total == 32)) || (p == 3 && (total == 8 || total == 16));
-        if (have) t->unrolled_shape[a] = (uint32_t)p * 256u + (uint32_t)total;
-      }
-    }
-    if (!f->usable[2]) f->split = false;
-  }
-  if (runs.empty()) runs.assign(8, 0);
+  f->vec_words = vec_words;
+  f->d_scn = d_scn;
+  f->d_comp = d_comp;
+  f->reroute_tables_ready = false;
   bool up = pool_take(f->d_tables, sizeof(FastTables));
-  up = up && pool_take(f->d_runs, runs.size() * sizeof(uint32_t));
-  up = up && hipMemcpy(f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
-  up = up && pool_take(f->d_vecs, vec_words * sizeof(uint32_t));
+  up = up && pool_take(f->d_runs, 8 * sizeof(uint32_t));            // placeholder until the tables are built
+  up = up && hipMemset(f->d_runs, 0, 8 * sizeof(uint32_t)) == hipSuccess;
   up = up && hipMemcpy(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice) == hipSuccess;
-  if (up && f->usable[2]) {
-    for (int a = 0; a < h.n_aff; ++a) {
-      const int stride = h.aff_peers[a] <= 4 ? 4 : 8;
-      hipLaunchKernelGGL(k_make_rows, dim3((t->vec_rows[a] + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, nullptr, d_scn, d_comp, a,
-                         f->d_vecs + t->vec_off[a], t->vec_rows[a], stride);
-    }
-    up = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
-  }
   if (up && f->usable[2]) up = pool_take(f->d_rowkey, DEV_MAX_AFF * sizeof(uint64_t));
-  return up ? 0 : 1;
+  if (!up) return 1;
+  if (f->usable[2] && !f->split) return build_reroute_tables(f, h) ? 0 : 1;
+  return 0;
 }
 
 namespace {
@@ -2048,6 +2080,7 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
   // a bounded range search does without the sweep kernels: its queued kernel bounds and evaluates in one pass
   if (a.incumbent != nullptr && !list && a.costs_out == nullptr) return launch_search(f, h, a, nullptr, nullptr, st);
   if (list || a.costs_out != nullptr) return 1;   // the generic kernel handles lists for this shape
+  if (const int rc = ensure_reroute_tables(f, h)) return rc;
   if (!ensure_scratch(f, a.part_count)) return -1;
   // split rerouting path, FAST_SUB partitions per pass: base costs and peer stage times, then one
   // sweep per affected stage over (partition blocks x row chunks), then the combine / argmin
@@ -2093,6 +2126,7 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
                         uint64_t *d_out, void *stream) {
   (void)d_scn;
   if (!f->usable[2] || !f->split || h.n_aff == 0) return 1;
+  if (const int rc = ensure_reroute_tables(f, h)) return rc;
   if (!ensure_scratch(f, 1)) return -1;
   hipStream_t st = (hipStream_t)stream;
   // peer stage times of the winning partition (one-partition pass of the search kernel in split mode)
@@ -2130,6 +2164,7 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
                        uint64_t count, int64_t *d_costs, void *stream) {
   if (!f->usable[2] || h.n_aff == 0) return 1;
   if (count == 0) return 0;
+  if (const int rc = ensure_reroute_tables(f, h)) return rc;
   hipStream_t st = (hipStream_t)stream;
   const FastTables &t = f->h_tables;
   const uint64_t R = h.fam[2].n_reroute;

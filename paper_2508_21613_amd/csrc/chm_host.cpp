@@ -426,6 +426,52 @@ uint64_t balanced_rank(const chm_scenario *s, int stages, const int64_t *prefix_
   return rank;
 }
 
+// The winner's reroute vectors without the vector tables (bounded search over a large reroute space).  Peer i
+// of the stage takes (forward + backward time of the stage under the winner's cuts) x its speed factor per
+// extra micro-batch; the least penalty v is the least value at which the peers' capacities min(cap, v / w_i)
+// cover the orphans; the vector of lowest rank that stays within v is the lexicographically smallest one:
+// every peer in turn takes as little as the peers after it allow.  Its rank = the number of valid vectors that
+// are lexicographically smaller, from the count table.
+void host_reroute_ranks(const chm_scenario *s, uint64_t part_rank, uint64_t *rr) {
+  const DevScenario &h = s->h;
+  uint8_t cuts[32];
+  decode_partition(s, h.fam[2].stages - 1, part_rank, cuts);
+  for (int a = 0; a < h.n_aff; ++a) {
+    const int st = h.aff_stage[a], p = h.aff_peers[a];
+    const int lo = st == 0 ? 0 : cuts[st - 1], hi = st == h.fam[2].stages - 1 ? h.L : cuts[st];
+    const int64_t F = h.pf[hi] - h.pf[lo], B = h.pb[hi] - h.pb[lo];
+    int64_t w[DEV_MAX_D];
+    int64_t w_max = 1;
+    for (int i = 0; i < p; ++i) {
+      const int64_t q = h.aff_q[a][i];
+      w[i] = q == 65536 ? F + B : ((F * q + 32768) >> 16) + ((B * q + 32768) >> 16);
+      w_max = std::max(w_max, w[i]);
+    }
+    const int64_t orphans = h.aff_total[a], cap = h.rcap > 0 ? h.rcap : orphans;
+    auto room = [&](int64_t v, int i) { return std::min<int64_t>(cap, w[i] == 0 ? cap : v / w[i]); };
+    int64_t v_lo = 0, v_hi = orphans * w_max;
+    while (v_lo < v_hi) {
+      const int64_t v = v_lo + (v_hi - v_lo) / 2;
+      int64_t sum = 0;
+      for (int i = 0; i < p; ++i) sum += room(v, i);
+      if (sum >= orphans) v_hi = v;
+      else v_lo = v + 1;
+    }
+    const uint64_t *tab = s->comp.data() + h.comp_off[a];
+    int64_t rem = orphans;
+    uint64_t rank = 0;
+    for (int pos = 0; pos < p; ++pos) {
+      int64_t behind = 0;
+      for (int i = pos + 1; i < p; ++i) behind += room(v_lo, i);
+      const int64_t take = std::max<int64_t>(0, rem - behind);
+      const int left = p - 1 - pos;
+      for (int64_t v = 0; v < take; ++v) rank += tab[(size_t)left * h.comp_stride[a] + (size_t)(rem - v)];
+      rem -= take;
+    }
+    rr[a] = rank;
+  }
+}
+
 // below this many partitions the bounded range search costs no more than counting and enumerating candidates
 constexpr uint64_t ENUMERATE_FROM = 1ull << 25;
 
@@ -585,7 +631,11 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
   }
   // the winner's reroute vectors (rerouting only) and its transition time, from the device, behind one
   // synchronisation; its step time follows from cost = horizon x step + transition
-  const bool rerouted = best_strategy == 2 && s->h.n_aff > 0;
+  bool rerouted = best_strategy == 2 && s->h.n_aff > 0;
+  if (rerouted && s->fast.split && s->fast.usable[2] && s->fast.penalty_by_capacity) {
+    host_reroute_ranks(s, best_part, rr);         // bounded search: no vector tables
+    rerouted = false;
+  }
   if (rerouted) {
     int rc = fast_reroute_winner(&s->fast, s->h, s->d_scn, best_part, s->d_winner, st);
     if (rc > 0) rc = chmk_reroute_winner(s->d_scn, s->d_comp, best_part, s->d_winner, s->smax, st);
