@@ -858,3 +858,12 @@ def test_least_reroute_penalty_equals_the_capacity_threshold():
         while sum(min(cap, v // wi) for wi in w) < n:
             v += 1
         assert v == best, (p, n, cap, w, v, best)
+        # and the minimiser of lowest rank is the lexicographically smallest vector within v: every peer in turn
+        # takes as little as the peers after it allow
+        first = min(k for k in range(count) if max(r * wi for r, wi in zip(O.reroute_unrank(p, n, cap, k), w)) == best)
+        rem, greedy = n, []
+        for i in range(p):
+            behind = sum(min(cap, v // wj) for wj in w[i + 1:])
+            greedy.append(max(0, rem - behind))
+            rem -= greedy[-1]
+        assert list(O.reroute_unrank(p, n, cap, first)) == greedy and O.reroute_rank(p, n, cap, greedy) == first
