@@ -215,6 +215,28 @@ def bench_lists(args, note, B, synth):
         wall = time.perf_counter() - t0
     fam_ms /= args.steps
     ms = wall * 1e3 / args.steps
+    # the same argmin per list without the cost store, exhaustive and bounded (reported beside `value`)
+    winners, modes = {}, {}
+    with torch.cuda.stream(stream):
+        for mode in (0, 1):
+            g.set_bounded_search(mode)
+            for st, d_cuts in lists.items():
+                g.search_cuts(st, d_cuts, stream=stream)
+            stream.synchronize()
+            t0 = time.perf_counter()
+            evaluated = np.zeros(3)
+            for _ in range(args.steps):
+                for st, d_cuts in lists.items():
+                    rc_m, best_m, pos_m = g.search_cuts(st, d_cuts, stream=stream)
+                    winners.setdefault(st, []).append((rc_m, pos_m, best_m["cost"]))
+                    evaluated[st] = g.get_timing()["feasible"][st]
+            stream.synchronize()
+            modes[mode] = {"ms_per_step": (time.perf_counter() - t0) * 1e3 / args.steps, "entries_evaluated": [float(x) for x in evaluated]}
+        g.set_bounded_search(0)
+    bounded = {"argmin_only_ms_per_step": modes[0]["ms_per_step"], "bounded_ms_per_step": modes[1]["ms_per_step"],
+               "entries_evaluated_exhaustive": modes[0]["entries_evaluated"], "entries_evaluated_bounded": modes[1]["entries_evaluated"],
+               "same_winners": all(len(set(v)) == 1 for v in winners.values())}
+    note("list search without cost store: %s" % bounded)
     ops = np.zeros(3)
     for f in g.families:
         fam = dict(f, classes=g.family_classes(f["strategy"]), n_part=n, assign=0,
@@ -232,7 +254,7 @@ def bench_lists(args, note, B, synth):
                       "config": {"workload": "config4: L=96 PP=16 DP=2 M=64, 1 failed node, 2^24 random partitions per strategy "
                                              "(explicit lists), cap %d MiB" % sc["mem_cap_mib"],
                                  "partitions_per_strategy": n, "plans_scored_per_step": evals, "failed_nodes": sc["failed_nodes"]},
-                      "kernel_ms_per_strategy": [float(x) for x in fam_ms],
+                      "kernel_ms_per_strategy": [float(x) for x in fam_ms], "bounded_search": bounded,
                       "feasible_partitions_per_strategy": [float(x) for x in feasible],
                       "roofline": {"bound": "alu", "kernel": "list search, strategy %d" % dom, "achieved": achieved,
                                    "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,

@@ -232,8 +232,8 @@ int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
  * at one by one and fit.  Where the reroute vectors of a stage are too many to sweep inside the search kernel,
  * a bounded search finds the least penalty of eq. (re-route) from the peers' capacities instead of sweeping them
  * (some vector stays within v exactly when the peers can take all orphaned micro-batches within v each).  Covers
- * the range searches of the specialised kernels without cost store (other paths evaluate everything).
- * Errors: CHM_ERR_ARG. */
+ * the range and list searches of the specialised kernels without cost store (other paths evaluate everything;
+ * with a cost store every cost is wanted and nothing is skipped).  Errors: CHM_ERR_ARG. */
 int chm_set_bounded_search(chm_scenario *s, int32_t on);
 
 /* The distinct pipelines one plan of a strategy has to evaluate (pipelines with the same

@@ -10,7 +10,8 @@ enum {
   FAST_SPLIT_R = 1 << 23,    // up to this many per stage the vectors are tabulated and swept by a kernel of their own
   FAST_SUB = 1 << 20,        // partitions per pass of the split and scoring paths (bounds their scratch memory: 152 MB;
                              // the scratch is sized for the passes actually asked for and grows when needed)
-  LIST_SUB = 1 << 22         // list entries per filter + search pass of explicit lists (scratch: 80 MB)
+  LIST_SUB = 1 << 22,        // list entries per filter + search pass of explicit lists (scratch: 80 MB)
+  LIST_FIRST = 1 << 16       // entries of the first pass of a bounded list search
 };
 
 // One pipeline class in the form the specialised kernels read (all int32).

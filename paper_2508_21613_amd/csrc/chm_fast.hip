@@ -398,6 +398,76 @@ __device__ __forceinline__ int largest_peak(FamPtr ff, const int (&ms)[SP], cons
   return mmax;
 }
 
+// Lower bound of a plan's cost from its cuts c[0..SP] and the forward + backward time cs[] of its stages.
+template <int SP, int STRAT>
+__device__ __forceinline__ uint64_t cost_lower_bound(ScnPtr scn, TabPtr tab, FamPtr ff, const int (&cs)[SP], const int (&c)[SP + 1]) {
+    // Lower bound of the plan's cost.  Every stage of a pipeline runs its M forwards and M backwards one
+    // after the other, so the pipeline takes at least M x the largest (forward + backward) of its chain;
+    // rounds of gradient communication: at least the layers of the largest stage; a stage that lost
+    // nodes leaves some peer with at least ceil(orphans / peers) extra micro-batches; the weight transfer
+    // is at least zero.  Above the incumbent the partition can neither win nor tie.
+    // (Sharper where the times allow 24-bit multiplies: stage s cannot start before the forwards of the
+    // stages ahead of it and is followed by their backwards: M x its own time + the times of stages 0..s-1.)
+    int lb = ff->fixed_step;
+    if (STRAT == 0) {
+      int cd[SP];
+#pragma unroll
+      for (int j = 0; j < SP; ++j) cd[j] = cs[j] + cs[(j + 1) % SP];
+      for (int ci = 0; ci < ff->n_cls; ++ci) {
+        const ClsPtr cl = &ff->cls[ci];
+        int v = 0;
+        if (ff->lb_prefix) {
+          int pre = 0;
+#pragma unroll
+          for (int j = 0; j < SP; ++j) {
+            const int cj = (j == cl->dead0 || j == cl->dead1) ? 0 : cd[j];
+            v = imax32(v, (int)__umul24((uint32_t)cl->M, (uint32_t)cj) + pre);
+            pre += cj;
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < SP; ++j) v = imax32(v, (j == cl->dead0 || j == cl->dead1) ? 0 : cd[j]);
+          v *= cl->M;
+        }
+        lb = imax32(lb, imax32(0, scale_floor(v, cl->q_min) - cl->lb_slack) + cl->comm_total);
+      }
+    } else {
+      for (int ci = 0; ci < ff->n_cls; ++ci) {
+        const ClsPtr cl = &ff->cls[ci];
+        int v = 0;
+        if (ff->lb_prefix) {
+          int pre = 0;
+#pragma unroll
+          for (int j = 0; j < SP; ++j) {
+            v = imax32(v, (int)__umul24((uint32_t)cl->M, (uint32_t)cs[j]) + pre);
+            pre += cs[j];
+          }
+        } else {
+#pragma unroll
+          for (int j = 0; j < SP; ++j) v = imax32(v, cs[j]);
+          v *= cl->M;
+        }
+        lb = imax32(lb, imax32(0, scale_floor(v, cl->q_min) - cl->lb_slack) + cl->comm_total);
+      }
+    }
+    if (ff->allreduce > 0) {
+      int layers = STRAT == 0 ? 0 : ff->fixed_layers;
+#pragma unroll
+      for (int j = 0; j < SP; ++j) layers = imax32(layers, c[j + 1] - c[j]);
+      lb += ff->allreduce * layers;
+    }
+    if (STRAT == 2) {
+      for (int st = 0; st < scn->n_aff; ++st) {
+        const int sa = scn->aff_stage[st];
+        int c_st = cs[0];
+#pragma unroll
+        for (int j = 1; j < SP; ++j) c_st = sa == j ? cs[j] : c_st;
+        lb += (int)tab->lb_mult[st] * scale_floor(c_st, tab->lb_q[st]);
+      }
+    }
+    return (uint64_t)scn->K * (uint32_t)lb + (uint64_t)scn->reconf[STRAT];
+}
+
 struct FastLaunch {
   SearchLaunch s;
   const FastTables *tab;
@@ -563,71 +633,7 @@ k_fast_search(FastLaunch a) {
         const uint64_t in_memory = __builtin_amdgcn_ballot_w64(fits);
         n_fit += (uint32_t)__popcll(in_memory);
         if (bounded && in_memory != 0) {      // uniform; nothing to bound where nothing fits
-          // Lower bound of the plan's cost.  Every stage of a pipeline runs its M forwards and M backwards one
-          // after the other, so the pipeline takes at least M x the largest (forward + backward) of its chain;
-          // rounds of gradient communication: at least the layers of the largest stage; a stage that lost
-          // nodes leaves some peer with at least ceil(orphans / peers) extra micro-batches; the weight transfer
-          // is at least zero.  Above the incumbent the partition can neither win nor tie.
-          // (Sharper where the times allow 24-bit multiplies: stage s cannot start before the forwards of the
-          // stages ahead of it and is followed by their backwards: M x its own time + the times of stages 0..s-1.)
-          int lb = ff->fixed_step;
-          if (STRAT == 0) {
-            int cd[SP];
-#pragma unroll
-            for (int j = 0; j < SP; ++j) cd[j] = cs[j] + cs[(j + 1) % SP];
-            for (int ci = 0; ci < ff->n_cls; ++ci) {
-              const ClsPtr cl = &ff->cls[ci];
-              int v = 0;
-              if (ff->lb_prefix) {
-                int pre = 0;
-#pragma unroll
-                for (int j = 0; j < SP; ++j) {
-                  const int cj = (j == cl->dead0 || j == cl->dead1) ? 0 : cd[j];
-                  v = imax32(v, (int)__umul24((uint32_t)cl->M, (uint32_t)cj) + pre);
-                  pre += cj;
-                }
-              } else {
-#pragma unroll
-                for (int j = 0; j < SP; ++j) v = imax32(v, (j == cl->dead0 || j == cl->dead1) ? 0 : cd[j]);
-                v *= cl->M;
-              }
-              lb = imax32(lb, imax32(0, scale_floor(v, cl->q_min) - cl->lb_slack) + cl->comm_total);
-            }
-          } else {
-            for (int ci = 0; ci < ff->n_cls; ++ci) {
-              const ClsPtr cl = &ff->cls[ci];
-              int v = 0;
-              if (ff->lb_prefix) {
-                int pre = 0;
-#pragma unroll
-                for (int j = 0; j < SP; ++j) {
-                  v = imax32(v, (int)__umul24((uint32_t)cl->M, (uint32_t)cs[j]) + pre);
-                  pre += cs[j];
-                }
-              } else {
-#pragma unroll
-                for (int j = 0; j < SP; ++j) v = imax32(v, cs[j]);
-                v *= cl->M;
-              }
-              lb = imax32(lb, imax32(0, scale_floor(v, cl->q_min) - cl->lb_slack) + cl->comm_total);
-            }
-          }
-          if (ff->allreduce > 0) {
-            int layers = STRAT == 0 ? 0 : ff->fixed_layers;
-#pragma unroll
-            for (int j = 0; j < SP; ++j) layers = imax32(layers, c[j + 1] - c[j]);
-            lb += ff->allreduce * layers;
-          }
-          if (STRAT == 2) {
-            for (int st = 0; st < scn->n_aff; ++st) {
-              const int sa = scn->aff_stage[st];
-              int c_st = cs[0];
-#pragma unroll
-              for (int j = 1; j < SP; ++j) c_st = sa == j ? cs[j] : c_st;
-              lb += (int)tab->lb_mult[st] * scale_floor(c_st, tab->lb_q[st]);
-            }
-          }
-          const uint64_t lb_cost = (uint64_t)scn->K * (uint32_t)lb + (uint64_t)scn->reconf[STRAT];
+          const uint64_t lb_cost = cost_lower_bound<SP, STRAT>(scn, tab, ff, cs, c);
           fits = fits && lb_cost <= incumbent;
         }
         const uint64_t fit_mask = __builtin_amdgcn_ballot_w64(fits);
@@ -979,6 +985,9 @@ struct ListFilter {
   uint4 *cut_list;              // [workgroup][FILTER_TILES * BLOCK]
   uint32_t *cut_pos;            // likewise
   uint32_t *cut_count;          // [workgroup] filled slots
+  // bounded search (no cost store): entries whose lower bound of the cost lies above *incumbent (the lowest cost
+  // the passes before this one have evaluated) are dropped like those that do not fit; null = keep all that fit
+  const uint64_t *incumbent;
 };
 
 template <int SP, int STRAT>
@@ -988,8 +997,11 @@ __global__ void __launch_bounds__(BLOCK) k_list_filter(ListFilter a) {
   __shared__ uint64_t BN[(K > 0 ? K : 1) * DEV_MAX_L];
   __shared__ uint32_t filled;
   const ScnPtr scn = as_const(a.scn);
-  const FamPtr ff = &as_const(a.tab)->fam[STRAT];
+  const TabPtr tab = as_const(a.tab);
+  const FamPtr ff = &tab->fam[STRAT];
   const int L = scn->L;
+  const bool bounded = a.incumbent != nullptr && a.costs_out == nullptr;
+  const uint64_t incumbent = bounded ? __hip_atomic_load(a.incumbent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0ull;
   for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], (int)scn->pa[i]);
   if (a.cuts == nullptr)
     for (int i = threadIdx.x; i < K * DEV_MAX_L; i += BLOCK) BN[i] = scn->binom[1 + i / DEV_MAX_L][i % DEV_MAX_L];
@@ -1024,19 +1036,23 @@ __global__ void __launch_bounds__(BLOCK) k_list_filter(ListFilter a) {
       if (!valid) rem = 0;
       unrank_digits<K>(rem, L, (L - 1) <= 64 ? 3 : 4, BN, c);
     }
-    int ms[SP], as[SP];
+    int ms[SP], as[SP], cs[SP];
     {
-      int lo_m = 0, lo_a = 0;
+      int lo_m = 0, lo_a = 0, lo_c = 0;
 #pragma unroll
       for (int j = 0; j < SP; ++j) {
         const int4 hi = T[c[j + 1]];
         ms[j] = hi.z - lo_m;
         as[j] = hi.w - lo_a;
+        cs[j] = hi.x + hi.y - lo_c;
         lo_m = hi.z;
         lo_a = hi.w;
+        lo_c = hi.x + hi.y;
       }
     }
-    const bool ok = valid && largest_peak<SP, STRAT>(ff, ms, as) <= (int)scn->cap;
+    bool ok = valid && largest_peak<SP, STRAT>(ff, ms, as) <= (int)scn->cap;
+    if (bounded && incumbent != ~0ull && __builtin_amdgcn_ballot_w64(ok) != 0)      // uniform
+      ok = ok && cost_lower_bound<SP, STRAT>(scn, tab, ff, cs, c) <= incumbent;
     if (live && !ok && a.costs_out != nullptr) a.costs_out[a.pos_base + gid] = CHM_INF_COST;
     const uint64_t mask = __builtin_amdgcn_ballot_w64(ok);
     if (mask != 0) {
@@ -1810,10 +1826,14 @@ bool ensure_list_scratch(FastState *f) {
 int launch_list(FastState *f, const DevScenario &h, const SearchLaunch &a, hipStream_t st) {
   if (!ensure_list_scratch(f)) return -1;
   const int sp = h.fam[a.strategy].stages;
-  for (uint32_t done = 0; done < a.part_count; done += LIST_SUB) {
-    const uint32_t n = std::min<uint32_t>(LIST_SUB, a.part_count - done);
+  // a bounded search prunes the later passes against the best cost of the earlier ones: a short first pass
+  // makes one known early
+  const bool bounded = a.incumbent != nullptr && a.costs_out == nullptr;
+  for (uint32_t done = 0; done < a.part_count;) {
+    const uint32_t n = std::min<uint32_t>(bounded && done == 0 ? LIST_FIRST : LIST_SUB, a.part_count - done);
     const uint32_t blocks = (n + BLOCK * FILTER_TILES - 1) / (BLOCK * FILTER_TILES);   // one workgroup per region, both kernels
     ListFilter lf;
+    lf.incumbent = bounded ? a.incumbent : nullptr;
     lf.scn = a.scn; lf.tab = f->d_tables; lf.n = n; lf.pos_base = done;
     lf.ranks = a.ranks ? a.ranks + done : nullptr;
     lf.cuts = a.cuts ? a.cuts + (size_t)done * (size_t)(sp - 1) : nullptr;
@@ -1840,6 +1860,7 @@ int launch_list(FastState *f, const DevScenario &h, const SearchLaunch &a, hipSt
          : a.strategy == 1 ? launch_by_stages<1>(sp, fl, blocks, 0, st) : launch_by_stages<2>(sp, fl, blocks, 0, st);
     if (rc) return rc;
     if (hipGetLastError() != hipSuccess) return -1;
+    done += n;
   }
   return 0;
 }
@@ -2067,7 +2088,8 @@ int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunc
 
 bool fast_can_bound(const FastState *f, const SearchLaunch &a) {
   if (a.strategy < 0 || a.strategy > 2 || !f->usable[a.strategy]) return false;
-  if (a.ranks != nullptr || a.cuts != nullptr || a.costs_out != nullptr) return false;
+  if (a.costs_out != nullptr) return false;
+  if (a.ranks != nullptr || a.cuts != nullptr) return !(a.strategy == 2 && f->split);   // lists: bounded in their filter pass
   return true;                          // (large reroute spaces: least penalty from the peers' capacities)
 }
 

@@ -546,7 +546,7 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
       if (bounded && fast_can_bound(&s->fast, a)) {
         a.incumbent = d_incumbent;
         a.evaluated = j.seed ? d_seed_count : d_evaluated + (size_t)j.strategy * chunk_words;
-        bounded_used[j.strategy] = true;
+        bounded_used[j.strategy] = !(j.ranks || j.cuts);   // lists: what passes their filter is evaluated and counted as fitting
       }
       int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
       if (rc > 0) rc = chmk_search(a, s->smax, st);

@@ -322,6 +322,10 @@ def test_equal_costs_in_an_explicit_list_go_to_the_lowest_position(B):
             assert rc == 0 and (costs.cpu().numpy() == want).all()
             assert pos == int(np.argmin(want)), (f["strategy"], pos, int(np.argmin(want)))
             assert best["cuts"] == [int(x) for x in winner] and best["cost"] == int(want.min())
+            g.set_bounded_search(1)
+            rc_b, best_b, pos_b = g.search_cuts(f["strategy"], torch.from_numpy(cuts).cuda())
+            g.set_bounded_search(0)
+            assert rc_b == 0 and pos_b == pos and same_plan(best_b, best)
 
 
 def test_config1_all_9455_plans(B):
@@ -729,6 +733,14 @@ def test_rank_partitions_and_search_over_explicit_lists(B):
             costs2 = torch.empty(len(want), dtype=torch.int64, device="cuda")
             rc2, best2, pos2 = g.search_cuts(f["strategy"], d_cuts[:len(want)].contiguous(), costs=costs2)
             assert (rc2, pos2) == (rc, pos) and same_plan(best2, best) and torch.equal(costs2, costs)
+            # bounded list searches: same winner, same position
+            for mode in (1, 2):
+                g.set_bounded_search(mode)
+                rc3, best3, pos3 = g.search_ranks(f["strategy"], d_ranks)
+                rc4, best4, pos4 = g.search_cuts(f["strategy"], d_cuts[:len(want)].contiguous())
+                assert (rc3, pos3) == (rc, pos) and same_plan(best3, best), (mode, best3, best)
+                assert (rc4, pos4) == (rc, pos) and same_plan(best4, best), (mode, best4, best)
+            g.set_bounded_search(0)
     # malformed rows and ranks outside the family
     sc = synth.small_random(2002, L=8, PP=4, DP=2, M=5, n_failed=1, hetero=False)
     g = B.Scenario(sc)
@@ -793,6 +805,17 @@ def test_full_size_config4_explicit_batch(B):
         assert torch.equal(costs2, costs[:m])
         if not (h[:m] == B.INFEASIBLE).all():
             assert rc2 == 0 and pos2 == int(np.argmin(h[:m])) and best2["cost"] == int(h[:m].min())
+        # bounded list searches (no cost store): the same winner and position, by ranks and by cut positions
+        g.set_bounded_search(1)
+        g.set_timing(True)
+        rc3, best3, pos3 = g.search_ranks(strategy, d_ranks)
+        fit3 = g.get_timing()["feasible"][strategy]
+        rc4, best4, pos4 = g.search_cuts(strategy, d_cuts)
+        g.set_bounded_search(0)
+        assert (rc3, pos3) == (rc, pos) and same_plan(best3, best)
+        assert (rc4, pos4) == (rc2, pos2) and same_plan(best4, best2)
+        print("config4 strategy", strategy, "bounded list search evaluated", fit3, "of", int((h != B.INFEASIBLE).sum()), "entries that fit", flush=True)
+        assert fit3 <= int((h != B.INFEASIBLE).sum())
 
 
 def test_full_size_search_config3_and_config5(B):
