@@ -636,6 +636,12 @@ def test_large_costs_run_in_64_bit(B):
             rc_o, best_o, _ = o.search_range(f["strategy"], 0, width)
             rc_g, best_g = g.search_range(f["strategy"], 0, width)
             assert rc_g == rc_o and same_plan(best_g, best_o)
+            # a bounded search has nothing to prune with here (the bounds live in the 32-bit kernels): same result
+            for mode in (1, 2):
+                g.set_bounded_search(mode)
+                rc_b, best_b = g.search_range(f["strategy"], 0, width)
+                assert rc_b == rc_o and same_plan(best_b, best_o), (mode, best_b, best_o)
+            g.set_bounded_search(0)
     huge = synth.scenario(8, 2, 2, 256, np.full(8, 2 ** 31 - 1, np.int32), np.full(8, 2 ** 31 - 1, np.int32), np.ones(8, np.int32),
                           [0], 0, 100, speed=np.full(4, 2 ** 20, np.uint32), horizon_steps=2 ** 31 - 1)
     with pytest.raises(B.ChmError) as e:
