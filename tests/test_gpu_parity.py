@@ -848,3 +848,45 @@ def test_full_size_search_config3_and_config5(B):
         per = [g.search_best(1 << f["strategy"]) for f in o.families]
         want = min((b["cost"], b["index"]) for r, b in per if r == 0)
         assert (best_all["cost"], best_all["index"]) == want
+
+
+def test_independent_handles_on_concurrent_threads(B):
+    """different handles may be used from different threads at the same time (each on a stream of its own):
+    loads, exhaustive and bounded searches, cost stores and releases interleave, every result equals the
+    single-threaded one"""
+    import threading
+    import torch
+    scs = [synth.small_random(3100 + i, L=14 + i % 5, PP=4 + i % 3, DP=2 + i % 3, M=4 + i) for i in range(8)] + [synth.config1()]
+    want = []
+    for sc in scs:
+        g = B.Scenario(sc)
+        want.append((g.search_best(7), g.score_plans(0, min(g.n_plans, 5000)).cpu().numpy()))
+        g.close()
+    errors = []
+
+    def worker(t):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                for rep in range(6):
+                    for i, sc in enumerate(scs):
+                        if (i + rep) % 4 != t % 4 and rep % 2:
+                            continue
+                        g = B.Scenario(sc)
+                        g.set_bounded_search((rep + t) % 3)
+                        got = g.search_best(7, stream=stream)
+                        costs = g.score_plans(0, min(g.n_plans, 5000), stream=stream)
+                        stream.synchronize()
+                        if got != want[i][0] or not (costs.cpu().numpy() == want[i][1]).all():
+                            errors.append((t, rep, i))
+                        g.close()
+        except Exception as exc:                       # noqa: BLE001 - reported below
+            errors.append((t, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(4)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    assert not errors, errors[:5]
