@@ -98,6 +98,8 @@ struct SearchLaunch {
 // launch wrappers (defined in chm_kernels.hip); each returns a hipError_t cast to int
 int chmk_fixed_pipelines(DevScenario *d_scn, int32_t smax, void *stream);
 int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream);
+// d_ptr[0..keys) = CHM_KEY_NONE, the next `zeros` words = 0, the word after them = incumbent
+int chmk_init_search(uint64_t *d_ptr, uint32_t keys, uint32_t zeros, uint64_t incumbent, void *stream);
 int chmk_score(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy, uint64_t first_local,
                uint64_t count, int64_t *d_costs, int32_t smax, void *stream);
 int chmk_score_ranks(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy,

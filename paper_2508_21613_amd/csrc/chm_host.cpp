@@ -510,15 +510,13 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
   const uint32_t ways = spread ? SLOT_WAYS : 1, stride = spread ? SLOT_STRIDE : 1;
   const uint32_t chunk_words = ways * stride;              // words one chunk (or one counter) owns
   const uint32_t key_words = (uint32_t)slots.size() * chunk_words;
-  if (chmk_fill_u64(s->d_slots, key_words, CHM_KEY_NONE, st)) return CHM_ERR_HIP;
   // right behind the argmin words: three feasibility counters, three counters of evaluated partitions and
   // the incumbent cost of a bounded search
   uint64_t *d_count = s->d_slots + key_words;
   uint64_t *d_evaluated = d_count + 3 * chunk_words;
   uint64_t *d_seed_count = d_count + 6 * chunk_words;      // what seed jobs count (not reported)
   uint64_t *d_incumbent = d_count + 7 * chunk_words;
-  if (chmk_fill_u64(d_count, 7 * chunk_words, 0, st)) return CHM_ERR_HIP;
-  if (chmk_fill_u64(d_incumbent, 1, incumbent0, st)) return CHM_ERR_HIP;
+  if (chmk_init_search(s->d_slots, key_words, 7 * chunk_words, incumbent0, st)) return CHM_ERR_HIP;
   bool bounded_used[3] = {false, false, false};
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;

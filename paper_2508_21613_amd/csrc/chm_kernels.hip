@@ -353,6 +353,15 @@ __global__ void k_fill_u64(uint64_t *p, uint32_t n, uint64_t v) {
   if (i < n) p[i] = v;
 }
 
+// start of a search: `keys` argmin words to "nothing found", the `zeros` counter words behind them to 0 and the
+// word behind those (the incumbent cost of a bounded search) to `incumbent`, in one launch
+__global__ void k_init_search(uint64_t *p, uint32_t keys, uint32_t zeros, uint64_t incumbent) {
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < keys) p[i] = CHM_KEY_NONE;
+  else if (i < keys + zeros) p[i] = 0;
+  else if (i == keys + zeros) p[i] = incumbent;
+}
+
 // step time of the pipelines that strategy 1 leaves in the fault-free layout
 template <int SMAX>
 __global__ void __launch_bounds__(64) k_fixed_pipelines(DevScenario *scn) {
@@ -594,6 +603,12 @@ int dispatch_smax(int smax, Fn fn) {
 
 int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream) {
   hipLaunchKernelGGL(k_fill_u64, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, d_ptr, n, value);
+  return (int)hipGetLastError();
+}
+
+int chmk_init_search(uint64_t *d_ptr, uint32_t keys, uint32_t zeros, uint64_t incumbent, void *stream) {
+  const uint32_t n = keys + zeros + 1;
+  hipLaunchKernelGGL(k_init_search, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, d_ptr, keys, zeros, incumbent);
   return (int)hipGetLastError();
 }
 
