@@ -478,6 +478,7 @@ def main():
                    "partitions": n_part_total, "failed_nodes": sc["failed_nodes"] if len(handles) == 1 else "all",
                    "families": [{k: f[k] for k in ("strategy", "stages", "n_part", "n_reroute")} for f in work[0]]},
         "time_to_best_plan_ms": ttb_ms, "load_ms": load_ms,
+        "time_to_best_plan_bounded_ms": bounded["time_to_best_plan_ms"] if bounded else None,
         "bounded_search": bounded,
         "partition_evals_per_s": n_part_total / (ms_per_step * 1e-3),
         "recurrence_cells_per_s": cells / (ms_per_step * 1e-3),
