@@ -69,7 +69,7 @@ struct FastState {
   // Range search of strategies 0 and 1: share of the partitions that pass the memory filter, estimated at load
   // from FIT_SAMPLES seeded random partitions; below QUEUE_BELOW_SHARE the search compacts the partitions that
   // fit through a ring per wave (k_fast_search, QUEUED).  queue_mode: -1 = by that estimate, 0 = never, 1 = always.
-  float fit_share[3] = {1.0f, 1.0f, 1.0f};
+  float fit_share[3] = {1.0f, 1.0f, 1.0f};   // negative: not sampled yet (sampled when a search first asks)
   int queue_mode = -1;
   FastTables h_tables;
   FastTables *d_tables = nullptr;
@@ -146,6 +146,8 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
 // Whether fast_search would run this launch as a bounded search if a.incumbent were set (a range search of a
 // covered strategy without cost store whose reroute vectors, if any, are swept inside the search kernel).
 bool fast_can_bound(const FastState *f, const SearchLaunch &a);
+// Sampled share of partitions of a strategy that pass the memory filter (1.0 where no sample applies).
+float fast_fit_share(FastState *f, const DevScenario &h, int strategy);
 // Rank of the best reroute vector per affected stage of one partition of the rerouting family,
 // written to d_out[0..n_aff).  Same return convention as fast_search.
 int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t part_rank,

@@ -1778,7 +1778,7 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
       f->split = ok && r_sum > FAST_FUSED_R;
     }
     f->usable[k] = ok;
-    if (ok && k != 2) f->fit_share[k] = estimate_fit_share(h, ff, k, fam.stages);
+    f->fit_share[k] = (ok && k != 2) ? -1.0f : 1.0f;      // sampled on first need
   }
   f->vec_words = vec_words;
   f->d_scn = d_scn;
@@ -1896,7 +1896,7 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   const bool pure_range = a.ranks == nullptr && a.costs_out == nullptr && base_out == nullptr;
   const bool queued = pure_range && (a.incumbent != nullptr ||
                                      (a.strategy != 2 && f->queue_mode != 0 &&
-                                      (f->queue_mode > 0 || f->fit_share[a.strategy] < QUEUE_BELOW_SHARE)));
+                                      (f->queue_mode > 0 || fast_fit_share(f, h, a.strategy) < QUEUE_BELOW_SHARE)));
   if (!queued) { fl.s.incumbent = nullptr; fl.s.evaluated = nullptr; }
   fl.capacity_penalty = (queued && a.strategy == 2 && f->split) ? 1 : 0;
   int rc;
@@ -2084,6 +2084,12 @@ int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunc
                  : a.strategy == 1 ? launch_by_stages<1>(sp, fl, blocks, 0, st) : launch_by_stages<2>(sp, fl, blocks, 0, st);
   if (rc) return rc;
   return hipGetLastError() == hipSuccess ? 0 : -1;
+}
+
+float fast_fit_share(FastState *f, const DevScenario &h, int k) {
+  if (k < 0 || k > 2) return 1.0f;
+  if (f->fit_share[k] < 0.0f) f->fit_share[k] = estimate_fit_share(h, f->h_tables.fam[k], k, h.fam[k].stages);
+  return f->fit_share[k];
 }
 
 bool fast_can_bound(const FastState *f, const SearchLaunch &a) {

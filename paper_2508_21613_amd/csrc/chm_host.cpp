@@ -995,7 +995,7 @@ extern "C" int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *s
   if (!s || mode < -1 || mode > 1) return CHM_ERR_ARG;
   s->fast.queue_mode = mode;
   if (share)
-    for (int k = 0; k < 3; ++k) share[k] = s->fast.fit_share[k];
+    for (int k = 0; k < 3; ++k) share[k] = fast_fit_share(&s->fast, s->h, k);
   return CHM_OK;
 }
 
