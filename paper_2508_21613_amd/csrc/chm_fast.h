@@ -113,7 +113,8 @@ struct FastState {
 // layers [a, b).  Candidates are numbered in ascending partition rank (highest cut most significant).
 struct CandidateSet {
   int stages = 0, L = 0;
-  std::vector<uint64_t> ways;               // [stages][end b][start a], (L+1) x (L+1) per stage: a scan over the starts reads consecutive words
+  std::vector<uint64_t> ways;               // [stages][end b][start a], (L+1) x (L+1) per stage; once built, accumulated over
+                                            // the starts (entry a = ways with a start <= a), so that a block is found by bisection
   std::vector<uint8_t> low_pair;            // [stages][L+1]: lowest start of the pair (stages s, s+1) that ends at e; 0 = no such limit
   uint64_t total = 0;                       // candidates; 0 also when the bound excludes the whole family
   uint64_t serial = 0;                      // distinguishes the sets a process builds (the device keeps the last one uploaded)

@@ -1077,6 +1077,21 @@ __global__ void __launch_bounds__(BLOCK) k_list_filter(ListFilter a) {
 // ---------------------------------------------------------------------------------------
 // bounded search: enumeration of the candidates (see CandidateSet)
 // ---------------------------------------------------------------------------------------
+// row[x] = candidates (of the arrangement being refined) whose current stage starts at or before x.  Finds by
+// bisection the start in [lo, hi] whose block holds index idx, counting blocks from lo on, and leaves in idx
+// the offset inside that block (an index beyond the last block lands on hi).
+__host__ __device__ inline int candidate_start(const uint64_t *row, int lo, int hi, uint64_t &idx) {
+  const uint64_t target = idx + (lo > 0 ? row[lo - 1] : 0);
+  int a = lo, b = hi;
+  while (a < b) {
+    const int m = (a + b) >> 1;
+    if (row[m] > target) b = m;
+    else a = m + 1;
+  }
+  idx = target - (a > 0 ? row[a - 1] : 0);
+  return a;
+}
+
 struct CandidateEnum {
   const uint64_t *ways;         // [stages][end][start]
   const uint8_t *low_pair;      // [stages][L+1]
@@ -1104,24 +1119,15 @@ __global__ void __launch_bounds__(BLOCK) k_enumerate_candidates(CandidateEnum e)
   uint32_t words[4] = {0, 0, 0, 0};
   int s = e.stages - 1;                   // the stage whose start is being chosen
   int end = e.L;                          // its end
-  int start = s;                          // at least one layer for every stage below
-  for (; start < end - 1; ++start) {
-    const uint64_t blk = e.ways[((size_t)s * W + end) * W + start];
-    if (idx < blk) break;
-    idx -= blk;
-  }
+  // at least one layer for every stage below
+  int start = candidate_start(e.ways + ((size_t)s * W + end) * W, s, end - 1, idx);
   for (;;) {
     words[(s - 1) >> 2] |= (uint32_t)start << (8 * ((s - 1) & 3));
     if (s == 1) break;
     // the stage below: layers [below, start), its pair with stage s ends at `end`
     const int lo = (int)e.low_pair[(size_t)(s - 1) * W + end];
-    int below = lo > s - 1 ? lo : s - 1;
-    for (; below < start - 1; ++below) {
-      const uint64_t blk = e.ways[((size_t)(s - 1) * W + start) * W + below];
-      if (idx < blk) break;
-      idx -= blk;
-    }
-    if (below > start - 1) below = start - 1;
+    const int first = lo > s - 1 ? lo : s - 1;
+    const int below = first >= start - 1 ? start - 1 : candidate_start(e.ways + ((size_t)(s - 1) * W + start) * W, first, start - 1, idx);
     end = start;
     start = below;
     --s;
@@ -1994,6 +2000,12 @@ bool fast_candidates_build(const FastState *f, const DevScenario &h, int k, uint
   uint64_t total = 0;
   for (int a = sp - 1; a < L; ++a) total += ways(sp - 1, a, L);
   out->total = total;
+  // what the enumeration reads: per (stage, end) the counts accumulated over the starts
+  for (int s2 = 0; s2 < sp; ++s2)
+    for (int b = 0; b <= L; ++b) {
+      uint64_t *row = out->ways.data() + ((size_t)s2 * W + b) * W;
+      for (int a = 1; a <= L; ++a) row[a] += row[a - 1];
+    }
   static uint64_t next_serial = 0;
   out->serial = __atomic_add_fetch(&next_serial, 1, __ATOMIC_RELAXED);
   return true;
@@ -2001,22 +2013,13 @@ bool fast_candidates_build(const FastState *f, const DevScenario &h, int k, uint
 
 void fast_candidate_cuts(const CandidateSet &cs, uint64_t idx, uint8_t *cuts) {
   const size_t W = (size_t)cs.L + 1;
-  int s = cs.stages - 1, end = cs.L, start = s;
-  for (; start < end - 1; ++start) {
-    const uint64_t blk = cs.ways[((size_t)s * W + end) * W + start];
-    if (idx < blk) break;
-    idx -= blk;
-  }
+  int s = cs.stages - 1, end = cs.L;
+  int start = candidate_start(cs.ways.data() + ((size_t)s * W + end) * W, s, end - 1, idx);
   for (;;) {
     cuts[s - 1] = (uint8_t)start;
     if (s == 1) break;
-    int below = std::max<int>(cs.low_pair[(size_t)(s - 1) * W + end], s - 1);
-    for (; below < start - 1; ++below) {
-      const uint64_t blk = cs.ways[((size_t)(s - 1) * W + start) * W + below];
-      if (idx < blk) break;
-      idx -= blk;
-    }
-    if (below > start - 1) below = start - 1;
+    const int first = std::max<int>(cs.low_pair[(size_t)(s - 1) * W + end], s - 1);
+    const int below = first >= start - 1 ? start - 1 : candidate_start(cs.ways.data() + ((size_t)(s - 1) * W + start) * W, first, start - 1, idx);
     end = start;
     start = below;
     --s;
