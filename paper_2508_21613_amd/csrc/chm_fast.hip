@@ -972,7 +972,8 @@ k_fast_search(FastLaunch a) {
 // workgroup's own region of a compact list as (cut positions packed into 16 bytes, list position).  Slots are
 // handed out through a counter in LDS: atomics of many workgroups on one global counter would serialise (about
 // 10 ns each).  The search kernel then runs over every region with all lanes busy.
-constexpr int FILTER_TILES = 16;  // tiles of BLOCK entries per workgroup = rounds of the search kernel per region
+constexpr int FILTER_TILES = 16;        // tiles of BLOCK entries per workgroup = rounds of the search kernel per region
+constexpr int FILTER_TILES_BOUNDED = 4;  // a bounded search keeps few entries: shorter regions, more workgroups to filter with
 
 struct ListFilter {
   const DevScenario *scn;
@@ -982,7 +983,8 @@ struct ListFilter {
   uint32_t n;                   // entries in this pass
   uint32_t pos_base;            // list position (chunk-local) of entry 0 of this pass
   int64_t *costs_out;           // chunk-local cost array (nullable)
-  uint4 *cut_list;              // [workgroup][FILTER_TILES * BLOCK]
+  int32_t tiles;                // tiles of BLOCK entries per workgroup
+  uint4 *cut_list;              // [workgroup][tiles * BLOCK]
   uint32_t *cut_pos;            // likewise
   uint32_t *cut_count;          // [workgroup] filled slots
   // bounded search (no cost store): entries whose lower bound of the cost lies above *incumbent (the lowest cost
@@ -1007,8 +1009,8 @@ __global__ void __launch_bounds__(BLOCK) k_list_filter(ListFilter a) {
     for (int i = threadIdx.x; i < K * DEV_MAX_L; i += BLOCK) BN[i] = scn->binom[1 + i / DEV_MAX_L][i % DEV_MAX_L];
   if (threadIdx.x == 0) filled = 0;
   __syncthreads();
-  const uint32_t region = blockIdx.x * (FILTER_TILES * BLOCK);
-  for (int tile = 0; tile < FILTER_TILES; ++tile) {
+  const uint32_t region = blockIdx.x * ((uint32_t)a.tiles * BLOCK);
+  for (int tile = 0; tile < a.tiles; ++tile) {
     const uint32_t gid = region + tile * BLOCK + threadIdx.x;
     if (gid - threadIdx.x >= a.n) break;                        // uniform: this tile and the next ones are empty
     const bool live = gid < a.n;
@@ -1823,7 +1825,7 @@ bool ensure_list_scratch(FastState *f) {
   bool ok = true;
   if (!f->d_cut_list) ok = ok && pool_take(f->d_cut_list, (size_t)LIST_SUB * sizeof(uint4));
   if (!f->d_cut_pos) ok = ok && pool_take(f->d_cut_pos, (size_t)LIST_SUB * sizeof(uint32_t));
-  if (!f->d_cut_count) ok = ok && pool_take(f->d_cut_count, (size_t)(LIST_SUB / (BLOCK * FILTER_TILES)) * sizeof(uint32_t));
+  if (!f->d_cut_count) ok = ok && pool_take(f->d_cut_count, (size_t)(LIST_SUB / (BLOCK * FILTER_TILES_BOUNDED)) * sizeof(uint32_t));
   return ok;
 }
 
@@ -1837,8 +1839,10 @@ int launch_list(FastState *f, const DevScenario &h, const SearchLaunch &a, hipSt
   const bool bounded = a.incumbent != nullptr && a.costs_out == nullptr;
   for (uint32_t done = 0; done < a.part_count;) {
     const uint32_t n = std::min<uint32_t>(bounded && done == 0 ? LIST_FIRST : LIST_SUB, a.part_count - done);
-    const uint32_t blocks = (n + BLOCK * FILTER_TILES - 1) / (BLOCK * FILTER_TILES);   // one workgroup per region, both kernels
+    const uint32_t tiles = bounded ? FILTER_TILES_BOUNDED : FILTER_TILES;
+    const uint32_t blocks = (n + BLOCK * tiles - 1) / (BLOCK * tiles);   // one workgroup per region, both kernels
     ListFilter lf;
+    lf.tiles = (int32_t)tiles;
     lf.incumbent = bounded ? a.incumbent : nullptr;
     lf.scn = a.scn; lf.tab = f->d_tables; lf.n = n; lf.pos_base = done;
     lf.ranks = a.ranks ? a.ranks + done : nullptr;
@@ -1856,7 +1860,7 @@ int launch_list(FastState *f, const DevScenario &h, const SearchLaunch &a, hipSt
     fl.tab = f->d_tables;
     fl.vecs = f->d_vecs;
     fl.runs = f->d_runs;
-    fl.per_lane = FILTER_TILES;           // rounds per region
+    fl.per_lane = tiles;                  // rounds per region
     fl.base_out = nullptr;
     fl.weights_out = nullptr;
     fl.cut_list = (const uint4 *)f->d_cut_list;
