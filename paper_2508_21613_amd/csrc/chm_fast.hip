@@ -495,7 +495,9 @@ struct FastLaunch {
 constexpr int QCAP = 128;
 
 // Waves per SIMD the register allocator is asked to keep possible: up to 8 stages the kernels fit 96
-// vector registers (5 waves); deeper pipelines hold more live stage sums and clocks and get what they need.
+// vector registers (5 waves); deeper pipelines hold more live stage sums and clocks: asked for 3 waves they take
+// 98-112 registers at 9-10 stages (4 waves), 135-163 at 11-14 and 168 with a dozen spilled at 15-16 (left alone
+// the allocator used 147-209, 2 waves at 16 stages).
 //
 // QUEUED (range search of strategies 0 and 1 without cost store): lanes whose partition fails the memory
 // filter would idle through the recurrence of their wave, and consecutive ranks share their upper cuts, so
@@ -505,7 +507,7 @@ constexpr int QCAP = 128;
 // with every lane busy; what is left after the last round is evaluated by a partly filled wave.  A ring is
 // written and read by one wave only, whose LDS operations complete in order: no barrier is needed.
 template <int SP, int STRAT, bool QUEUED = false>
-__global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SP <= 8 ? 5 : 1)))
+__global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SP <= 8 ? 5 : 3)))
 k_fast_search(FastLaunch a) {
   constexpr int K = SP - 1;
   __shared__ uint4 q_cuts[QUEUED ? (BLOCK / 64) * QCAP : 1];
