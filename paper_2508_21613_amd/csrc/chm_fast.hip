@@ -506,9 +506,13 @@ constexpr int QCAP = 128;
 // ring in LDS that belongs to the wave.  Whenever 64 entries wait, the wave evaluates them, one per lane,
 // with every lane busy; what is left after the last round is evaluated by a partly filled wave.  A ring is
 // written and read by one wave only, whose LDS operations complete in order: no barrier is needed.
-template <int SP, int STRAT, bool QUEUED = false>
+// MODE 0: every lane evaluates its own partitions; 1: QUEUED; 2: QUEUED with the bounds of a bounded search (a
+// variant of its own: the bounds cost the plain queued kernel registers it does not have, 36 instead of 16
+// spilled bytes per lane at 8 stages and 4 % of its time).
+template <int SP, int STRAT, int MODE = 0>
 __global__ void __launch_bounds__(BLOCK) __attribute__((amdgpu_waves_per_eu(SP <= 8 ? 5 : 3)))
 k_fast_search(FastLaunch a) {
+  constexpr bool QUEUED = MODE >= 1;
   constexpr int K = SP - 1;
   __shared__ uint4 q_cuts[QUEUED ? (BLOCK / 64) * QCAP : 1];
   __shared__ uint32_t q_pos[QUEUED ? (BLOCK / 64) * QCAP : 1];
@@ -560,7 +564,7 @@ k_fast_search(FastLaunch a) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   uint32_t q_head = 0, q_tail = 0;        // wave-uniform: entries [q_head, q_tail) of the wave's ring wait
   // bounded search: the lowest cost evaluated so far, by this wave or (as of its last look) by any other
-  const bool bounded = QUEUED && a.s.incumbent != nullptr;
+  const bool bounded = MODE == 2 && a.s.incumbent != nullptr;
   uint64_t incumbent = ~0ull;
   uint32_t n_eval = 0;                    // wave-uniform count of partitions whose recurrences were run
   if (bounded) incumbent = __hip_atomic_load(a.s.incumbent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1527,8 +1531,10 @@ template <int STRAT>
 int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, uint32_t tile_bytes, hipStream_t st, bool queued = false) {
 #define CHM_CASE(SPV)                                                                         \
   case SPV:                                                                                   \
-    if (queued)                                                                               \
-      hipLaunchKernelGGL((k_fast_search<SPV, STRAT, true>), dim3(blocks), dim3(BLOCK), 0, st, a); \
+    if (queued && (STRAT == 2 || a.s.incumbent != nullptr))                                   \
+      hipLaunchKernelGGL((k_fast_search<SPV, STRAT, 2>), dim3(blocks), dim3(BLOCK), 0, st, a); \
+    else if (queued)                                                                          \
+      hipLaunchKernelGGL((k_fast_search<SPV, STRAT, (STRAT == 2 ? 2 : 1)>), dim3(blocks), dim3(BLOCK), 0, st, a); \
     else                                                                                      \
       hipLaunchKernelGGL((k_fast_search<SPV, STRAT>), dim3(blocks), dim3(BLOCK), tile_bytes, st, a); \
     return 0;
