@@ -25,7 +25,7 @@ ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 # HBM bytes per launch of the config-2 search kernels, per strategy, from the rocprofv3 --pmc runs summarised in
 # profiles/search_kernels_config2.md: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (KiB; the factors come from the
 # 1 GiB calibration copy of the same runs).  Counters cannot be read from inside this process.
-CONFIG2_TRAFFIC_BYTES = {0: (3889 * 2.0 + 10780) * 1024, 1: (133.0 * 2.0 + 510.5) * 1024, 2: (182.0 * 2.0 + 490.6) * 1024}
+CONFIG2_TRAFFIC_BYTES = {0: (178.9 * 2.0 + 4302) * 1024, 1: (133.0 * 2.0 + 510.5) * 1024, 2: (182.2 * 2.0 + 490.6) * 1024}
 
 
 def algorithmic_ops(fam, feasible):
