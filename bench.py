@@ -261,6 +261,36 @@ def bench_lists(args, note, B, synth):
                                    "algorithmic_ops_per_launch": float(ops[dom])}}))
 
 
+
+def threaded_sweep(B, handles, plans, n_threads=4, reps=3):
+    """one search per handle, the handles dealt out to n_threads host threads with a stream each (independent
+    handles may be used concurrently); returns (median ms for all handles, every plan equals `plans`)"""
+    import threading
+    import numpy as np
+    import torch
+
+    def sweep(t, out):
+        st = torch.cuda.Stream()
+        with torch.cuda.stream(st):
+            for i in range(t, len(handles), n_threads):
+                out[i] = handles[i].search_best(7, stream=st)[1]
+
+    times, same = [], True
+    for _ in range(reps):
+        found = [None] * len(handles)
+        threads = [threading.Thread(target=sweep, args=(t, found)) for t in range(n_threads)]
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for th in threads:
+            th.start()
+        for th in threads:
+            th.join()
+        times.append((time.perf_counter() - t0) * 1e3)
+        same = same and all(a is not None and a["index"] == b[1]["index"] and a["cost"] == b[1]["cost"]
+                            for a, b in zip(found, plans))
+    return float(np.median(times)), same
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -402,6 +432,13 @@ def main():
     ttb_ms = float(np.median(ttb)) if ttb else None
     note("time to best plan (load + search): %s ms" % ttb_ms)
 
+    # many scenarios: the host side of a call (launches, one synchronisation) hides behind other threads' kernels
+    threaded_exhaustive = None
+    if args.ttb_runs and len(handles) >= 8:
+        ms_t, same_t = threaded_sweep(B, handles, plans, reps=2)
+        threaded_exhaustive = {"search_ms_all_scenarios_4_threads": ms_t, "same_plans": bool(same_t)}
+        note("exhaustive search from four host threads: %s" % threaded_exhaustive)
+
     # the same with chm_set_bounded_search: same plan, most partitions skipped by a lower bound of their cost.
     # Reported beside the exhaustive figures, never inside `value` (which counts plans that were scored).
     bounded = None
@@ -428,26 +465,8 @@ def main():
         # searched from four host threads (a stream each) overlap
         threaded_ms = None
         if len(handles) >= 8:
-            import threading
-
-            def sweep(t, out):
-                st = torch.cuda.Stream()
-                with torch.cuda.stream(st):
-                    for i in range(t, len(handles), 4):
-                        out[i] = handles[i].search_best(7, stream=st)[1]
-
-            times = []
-            for _ in range(3):
-                found = [None] * len(handles)
-                threads = [threading.Thread(target=sweep, args=(t, found)) for t in range(4)]
-                t0 = time.perf_counter()
-                for th in threads:
-                    th.start()
-                for th in threads:
-                    th.join()
-                times.append((time.perf_counter() - t0) * 1e3)
-                same = same and all(a["index"] == b[1]["index"] and a["cost"] == b[1]["cost"] for a, b in zip(found, plans))
-            threaded_ms = float(np.median(times))
+            threaded_ms, same_t = threaded_sweep(B, handles, plans)
+            same = same and same_t
         for g in handles:
             g.set_bounded_search(False)
         bounded = {"time_to_best_plan_ms": float(np.median(ttb_b)), "search_ms_all_scenarios": float(np.median(search_b)),
@@ -480,6 +499,7 @@ def main():
         "time_to_best_plan_ms": ttb_ms, "load_ms": load_ms,
         "time_to_best_plan_bounded_ms": bounded["time_to_best_plan_ms"] if bounded else None,
         "bounded_search": bounded,
+        "exhaustive_search_4_threads": threaded_exhaustive,
         "partition_evals_per_s": n_part_total / (ms_per_step * 1e-3),
         "recurrence_cells_per_s": cells / (ms_per_step * 1e-3),
         "kernel_ms_per_strategy": [float(x) for x in fam_ms],
