@@ -552,7 +552,7 @@ struct StageSweep {
 void best_init(orc_plan *b) { std::memset(b, 0, sizeof(*b)); b->index = UINT64_MAX; b->cost = ORC_INF; }
 
 int search_family_range(const orc_scenario *s, const orc_family *f, uint64_t first, uint64_t count,
-                        orc_plan *best, uint64_t *evals) {
+                        orc_plan *best, uint64_t *evals, uint64_t *fitting = nullptr) {
   const int k = f->stages - 1;
   uint8_t cuts[ORC_MAX_PP];
   for (uint64_t pr = first; pr < first + count; ++pr) {
@@ -566,6 +566,7 @@ int search_family_range(const orc_scenario *s, const orc_family *f, uint64_t fir
       for (size_t a = 0; a < s->affected.size(); ++a) n_eval += s->comps[a].count();
       if (evals) *evals += s->affected.empty() ? 1 : n_eval;
       if (!ok) continue;
+      if (fitting) *fitting += 1;
       for (size_t a = 0; a < s->affected.size(); ++a) {
         StageSweep sw(s->comps[a], w[a]);
         sw.go(0, s->comps[a].total);
@@ -575,6 +576,7 @@ int search_family_range(const orc_scenario *s, const orc_family *f, uint64_t fir
     } else {
       if (evals) *evals += 1;
       if (!ok) continue;
+      if (fitting) *fitting += 1;
     }
     int64_t cost = s->K * t_step + reconf;
     if (cost < best->cost) {
@@ -810,6 +812,18 @@ extern "C" int orc_search_range(const orc_scenario *s, int32_t strategy, uint64_
   best_init(best);
   if (evals) *evals = 0;
   search_family_range(s, f, part_first, part_count, best, evals);
+  return best->cost == ORC_INF ? ORC_ERR_NO_FEASIBLE : ORC_OK;
+}
+
+extern "C" int orc_search_range_counted(const orc_scenario *s, int32_t strategy, uint64_t part_first,
+                                        uint64_t part_count, orc_plan *best, uint64_t *fitting) {
+  if (!s || !best || !fitting) return ORC_ERR_ARG;
+  const orc_family *f = family_of(s, strategy);
+  if (!f) return ORC_ERR_UNRECOVERABLE;
+  if (part_first > f->n_part || part_count > f->n_part - part_first) return ORC_ERR_RANGE;
+  best_init(best);
+  *fitting = 0;
+  search_family_range(s, f, part_first, part_count, best, nullptr, fitting);
   return best->cost == ORC_INF ? ORC_ERR_NO_FEASIBLE : ORC_OK;
 }
 

@@ -129,6 +129,9 @@ int  orc_search(const orc_scenario *s, uint32_t strategy_mask, orc_plan *best);
  * *evals receives the number of (partition, reroute vector) evaluations done. */
 int  orc_search_range(const orc_scenario *s, int32_t strategy, uint64_t part_first,
                       uint64_t part_count, orc_plan *best, uint64_t *evals);
+/* orc_search_range that also counts, in *fitting, the partitions of the range that pass the memory filter */
+int  orc_search_range_counted(const orc_scenario *s, int32_t strategy, uint64_t part_first,
+                              uint64_t part_count, orc_plan *best, uint64_t *fitting);
 /* plain joint sweep over every index in [first, first+count): slow, for tiny cases */
 int  orc_search_joint(const orc_scenario *s, uint64_t first, uint64_t count, orc_plan *best);
 

@@ -112,6 +112,7 @@ def lib():
             "orc_score_ranks": (C.c_int, [C.c_void_p, C.c_int32, u64p, C.c_uint64, i64p]),
             "orc_search": (C.c_int, [C.c_void_p, C.c_uint32, C.POINTER(Plan)]),
             "orc_search_range": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint64, C.c_uint64, C.POINTER(Plan), u64p]),
+            "orc_search_range_counted": (C.c_int, [C.c_void_p, C.c_int32, C.c_uint64, C.c_uint64, C.POINTER(Plan), u64p]),
             "orc_search_joint": (C.c_int, [C.c_void_p, C.c_uint64, C.c_uint64, C.POINTER(Plan)]),
         }
         for name, (res, args) in sig.items():
@@ -394,6 +395,13 @@ class Scenario:
         ev = C.c_uint64()
         rc = lib().orc_search_range(self._h, strategy, first, count, C.byref(p), C.byref(ev))
         return rc, _plan_dict(p), int(ev.value)
+
+    def search_range_counted(self, strategy, first, count):
+        """(return code, best plan of the range, partitions of the range that pass the memory filter)"""
+        p = Plan()
+        fit = C.c_uint64()
+        rc = lib().orc_search_range_counted(self._h, strategy, first, count, C.byref(p), C.byref(fit))
+        return rc, _plan_dict(p), int(fit.value)
 
     def search_joint(self, first=0, count=None):
         p = Plan()

@@ -1,0 +1,204 @@
+"""Writes tests/golden/full_space.json: the CPU oracle's exhaustive argmin over WHOLE plan spaces.
+
+    python tests/golden/make_full_space.py [--workers N] [--only NAME ...] [--out FILE]
+
+For every case below and every recovery strategy the oracle (oracle/, nothing else) walks all
+partition ranks of the family, sub-range by sub-range on the host cores, and the sub-range results
+are merged in rank order with a strict less-than, so the stored plan is the first minimum of the
+whole family (Algorithm 1, get_execution_plan: the argmin over all candidates).  Stored per family:
+the best plan (index, cost, cuts, reroute vectors, step and transition time) and the number of
+partitions that pass the memory filter; per case the best plan over all strategies.
+
+The GPU parity tests compare chm_search_best (exhaustive and bounded) and its feasibility counters
+with this file.  Nothing here imports or calls the HIP library; the inputs are the seeded generators.
+The file is resumable: families already present in --out are kept, so a run can be continued.
+
+Cases: config 1, config 2 and config 3 as the task states them, and failure sets of config 5 (the
+plan cache of the Planner's overhead paragraph): all 32 single failures and seeded double failures
+of every kind (two failures in one pipeline: neighbouring stages, the ring pair first/last stage,
+stages apart; the same stage in two pipelines; different stage and pipeline).
+"""
+import argparse
+import json
+import multiprocessing as mp
+import os
+import sys
+import time
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(os.path.dirname(HERE))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from oracle import oracle as O                      # noqa: E402
+from paper_2508_21613_amd import synth              # noqa: E402
+
+OUT = os.path.join(HERE, "full_space.json")
+
+
+def config5_doubles():
+    """seeded double failures of the 4 x 8 grid (node id = pipeline * 8 + stage), four of each kind"""
+    PP, DP = 8, 4
+    r = synth.randint(synth.BASE_SEED + 5, 77, 64, 0, 1 << 30)
+    it = iter(int(x) for x in r)
+    sets = []
+    for _ in range(4):                                # one pipeline, neighbouring stages
+        d, s = next(it) % DP, next(it) % (PP - 1)
+        sets.append([d * PP + s, d * PP + s + 1])
+    for d in (0, 3):                                  # one pipeline, last and first stage (neighbours on the ring)
+        sets.append([d * PP, d * PP + PP - 1])
+    for _ in range(4):                                # one pipeline, stages at least two apart (not the ring pair)
+        d, s = next(it) % DP, next(it) % (PP - 3)
+        t = s + 2 + next(it) % (PP - 2 - s - (1 if s == 0 else 0))
+        sets.append([d * PP + s, d * PP + t])
+    for _ in range(4):                                # the same stage in two pipelines
+        s, d = next(it) % PP, next(it) % DP
+        e = (d + 1 + next(it) % (DP - 1)) % DP
+        sets.append(sorted([d * PP + s, e * PP + s]))
+    for _ in range(4):                                # different stage and pipeline
+        s, d = next(it) % PP, next(it) % DP
+        t = (s + 1 + next(it) % (PP - 1)) % PP
+        e = (d + 1 + next(it) % (DP - 1)) % DP
+        sets.append(sorted([d * PP + s, e * PP + t]))
+    seen, out = set(), []
+    for f in sets:
+        if tuple(f) not in seen:
+            seen.add(tuple(f))
+            out.append(f)
+    return out
+
+
+def case_names():
+    names = ["config1", "config2", "config3"]
+    names += ["config5:%d" % a for a in range(32)]
+    names += ["config5:%d,%d" % (a, b) for a, b in config5_doubles()]
+    return names
+
+
+def case_scenario(name):
+    """the seeded scenario of a case name"""
+    if name == "config1":
+        return synth.config1()
+    if name == "config2":
+        return synth.config2()
+    if name == "config3":
+        return synth.config3()
+    if name.startswith("config5:"):
+        return synth.config5([int(x) for x in name.split(":")[1].split(",")])
+    if name.startswith("small:"):                     # small_random(seed), for the tests of this script
+        return synth.small_random(int(name.split(":")[1]))
+    raise ValueError(name)
+
+
+_open = {}
+
+
+def _range_job(job):
+    name, strategy, first, count = job
+    o = _open.get(name)
+    if o is None:
+        _open.clear()                                 # one scenario per worker at a time
+        o = _open[name] = O.Scenario(case_scenario(name))
+    rc, best, fit = o.search_range_counted(strategy, first, count)
+    return name, strategy, first, rc, best, fit
+
+
+def _slim(plan):
+    keep = ("index", "cost", "strategy", "stages", "cuts", "n_affected", "affected_stage", "t_step_us", "t_trans_us")
+    d = {k: plan[k] for k in keep}
+    d["reroute"] = [row[:16] for row in plan["reroute"]]
+    return d
+
+
+def merge_family(results):
+    """results of the sub-ranges of one family, any order -> (first minimum or None, fitting partitions)"""
+    best, fit = None, 0
+    for _, _, first, rc, plan, n in sorted(results, key=lambda r: r[2]):
+        fit += n
+        if rc == O.OK and (best is None or plan["cost"] < best["cost"]):
+            best = plan
+    return (None if best is None else _slim(best)), fit
+
+
+def best_of_families(families):
+    """strategies in ascending order, strict less-than: the lowest plan index among equal costs"""
+    best = None
+    for f in sorted(families, key=lambda f: f["strategy"]):
+        if f["best"] is not None and (best is None or f["best"]["cost"] < best["cost"]):
+            best = f["best"]
+    return best
+
+
+def full_space(names, workers, chunk_parts=None, done=None, progress=None):
+    """{name: case record} for the given cases.  chunk_parts: partitions per sub-range (default: sized so that
+    every family gives each worker several sub-ranges); done: records to keep (resume)."""
+    done = dict(done or {})
+    jobs, shapes = [], {}
+    for name in names:
+        o = O.Scenario(case_scenario(name))
+        shapes[name] = o.families
+        have = {f["strategy"] for f in done.get(name, {}).get("families", [])}
+        for f in o.families:
+            if f["strategy"] in have:
+                continue
+            n = f["n_part"]
+            per = chunk_parts or max(1, min(1 << 18, -(-n // (workers * 8))))
+            for first in range(0, n, per):
+                jobs.append((name, f["strategy"], first, min(per, n - first)))
+        o.close()
+    results = {}
+    t0 = time.time()
+    if jobs:
+        if workers > 1:
+            pool = mp.Pool(workers)
+            stream = pool.imap_unordered(_range_job, jobs, chunksize=1)
+        else:
+            pool, stream = None, map(_range_job, jobs)
+        for i, r in enumerate(stream):
+            results.setdefault((r[0], r[1]), []).append(r)
+            if progress and (i + 1) % max(1, len(jobs) // 200) == 0:
+                progress("%d / %d sub-ranges, %.0f s" % (i + 1, len(jobs), time.time() - t0))
+        if pool:
+            pool.close()
+            pool.join()
+    out = {}
+    for name in names:
+        sc = case_scenario(name)
+        rec = done.get(name, {"failed_nodes": sc["failed_nodes"], "families": []})
+        for f in shapes[name]:
+            if (name, f["strategy"]) not in results:
+                continue
+            best, fit = merge_family(results[(name, f["strategy"])])
+            rec["families"].append({"strategy": f["strategy"], "stages": f["stages"], "n_part": f["n_part"],
+                                    "n_reroute": f["n_reroute"], "feasible": fit, "best": best})
+        rec["families"].sort(key=lambda f: f["strategy"])
+        rec["best"] = best_of_families(rec["families"])
+        out[name] = rec
+    return out
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workers", type=int, default=os.cpu_count())
+    ap.add_argument("--only", nargs="*", default=None)
+    ap.add_argument("--out", default=OUT)
+    a = ap.parse_args()
+    names = a.only or case_names()
+    done = {}
+    if os.path.exists(a.out):
+        with open(a.out) as fh:
+            done = json.load(fh)["cases"]
+    doc = {"generator": "tests/golden/make_full_space.py (CPU oracle only)", "cases": dict(done)}
+    for name in names:                                # case by case, so that an interrupted run keeps what it has
+        t0 = time.time()
+        rec = full_space([name], a.workers, done=done, progress=lambda m: print("  " + m, file=sys.stderr, flush=True))
+        doc["cases"].update(rec)
+        with open(a.out + ".tmp", "w") as fh:
+            json.dump(doc, fh, indent=1, sort_keys=True)
+        os.replace(a.out + ".tmp", a.out)
+        b = rec[name]["best"]
+        print("%s: %.0f s, best %s" % (name, time.time() - t0, None if b is None else (b["index"], b["cost"])), file=sys.stderr, flush=True)
+
+
+if __name__ == "__main__":
+    main()
