@@ -61,7 +61,8 @@ enum {
   CHM_ERR_OVERFLOW = -3,       /* plan count or cost bound does not fit 62 bits            */
   CHM_ERR_UNRECOVERABLE = -4,  /* no requested strategy can recover this failure set       */
   CHM_ERR_NO_FEASIBLE = -5,    /* every plan searched exceeds the memory cap               */
-  CHM_ERR_HIP = -6             /* a HIP call failed (no device, launch or copy error)      */
+  CHM_ERR_HIP = -6,            /* a HIP call failed (no device, launch or copy error)      */
+  CHM_ERR_LIMIT = -7           /* chm_search_best_static: the search needs more scratch than its fixed buffer holds */
 };
 
 enum { CHM_MAX_L = 128, CHM_MAX_PP = 32, CHM_MAX_DP = 16, CHM_MAX_M = 256, CHM_MAX_FAILED = 4 };
@@ -180,6 +181,21 @@ int chm_search_cuts(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts, ui
  * than 2^16 chunks of 2^idx_bits partitions, idx_bits <= 30: beyond exhaustive reach; search windows with
  * chm_search_range or lists instead), CHM_ERR_ARG, CHM_ERR_HIP. */
 int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream);
+
+/* chm_search_best for callers that cannot allocate device memory while they run (code under HIP graph capture
+ * around it, tight serving loops, harnesses that forbid hipMalloc): the same exhaustive search with the same
+ * result, but every device word the call needs beyond the handle's tables - the per-chunk argmin words, the
+ * feasibility counters, the winner's reroute ranks and transition time - lives in one fixed device array of
+ * 65,664 bytes inside the library (one copy per GPU, held until the process ends) instead of buffers taken
+ * from the allocator.  The call makes no hipMalloc, hipFree or other allocating call.  Always exhaustive
+ * (chm_set_bounded_search is ignored).  Limits: at most 8,184 chunks of 2^idx_bits partitions (CHM_ERR_LIMIT
+ * beyond; with the usual idx_bits of 30 that is every space chm_search_best accepts short of 2^43 partitions),
+ * and no rerouting family whose reroute vectors are swept by kernels of their own (more than 4,096 vectors
+ * over its stages: CHM_ERR_LIMIT, use chm_search_best).  On CHM_ERR_LIMIT out is filled as for
+ * CHM_ERR_NO_FEASIBLE.  All calls on one GPU share the array, which keeps the last call's contents (the
+ * call resets what it reads): two calls that overlap in time on one GPU, from any handles or threads, race.
+ * Otherwise as chm_search_best (synchronises hip_stream; same errors). */
+int chm_search_best_static(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream);
 
 /* The same over partition ranks [part_first, part_first+part_count) of one strategy. */
 int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part_first, uint64_t part_count,

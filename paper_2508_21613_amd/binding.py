@@ -12,10 +12,10 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libchm.so")
 
-OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HIP = 0, -1, -2, -3, -4, -5, -6
+OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HIP, ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 INFEASIBLE = (1 << 63) - 1
 
-SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best",
+SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best", "chm_search_best_static",
            "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_set_filter_compaction", "chm_set_bounded_search", "chm_get_timing", "chm_family_classes",
            "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
@@ -107,6 +107,7 @@ def lib():
         L.chm_score_plans.argtypes = [vp, C.c_uint64, C.c_uint64, vp, vp]
         L.chm_score_ranks.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, vp]
         L.chm_search_best.argtypes = [vp, C.c_uint32, C.POINTER(Best), vp]
+        L.chm_search_best_static.argtypes = [vp, C.c_uint32, C.POINTER(Best), vp]
         L.chm_search_range.argtypes = [vp, C.c_int32, C.c_uint64, C.c_uint64, C.POINTER(Best), vp]
         L.chm_search_ranks.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, C.POINTER(Best), C.POINTER(C.c_uint64), vp]
         L.chm_search_cuts.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, C.POINTER(Best), C.POINTER(C.c_uint64), vp]
@@ -301,6 +302,13 @@ class Scenario:
         b = Best()
         rc = _check(lib().chm_search_best(self._h, mask, C.byref(b), _stream_ptr(stream)),
                     allowed=(ERR_NO_FEASIBLE, ERR_UNRECOVERABLE))
+        return rc, _best_dict(b)
+
+    def search_best_static(self, mask=7, stream=None):
+        """chm_search_best_static: chm_search_best with its scratch in the library's fixed device array"""
+        b = Best()
+        rc = _check(lib().chm_search_best_static(self._h, mask, C.byref(b), _stream_ptr(stream)),
+                    allowed=(ERR_NO_FEASIBLE, ERR_UNRECOVERABLE, ERR_LIMIT))
         return rc, _best_dict(b)
 
     def search_range(self, strategy, first, count, stream=None):

@@ -2,10 +2,11 @@
 // recovery strategies exist for the failure set, lays out the plan index space and the
 // device tables, and launches the scoring / search kernels.  No plan is ever scored on
 // the host: without a working HIP device every compute entry point fails with CHM_ERR_HIP.
-#include <hip/hip_runtime_api.h>
+#include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -57,7 +58,7 @@ struct chm_scenario {
   uint64_t *d_winner = nullptr;          // best reroute rank per affected stage
   uint64_t *d_xfer = nullptr;            // migration scheme: 8 bytes MiB to fetch + DEV_MAX_S bytes of stage indices
   uint64_t *h_pinned = nullptr;          // pinned staging for the two small device-to-host copies
-  uint32_t n_slots = 0;
+  uint32_t slot_words = 0;               // words d_slots has room for
   bool timing = false;
   int bounded = 0;              // chm_set_bounded_search: 0 off, 1 on, 2 on with seeds and enumeration at any size
   hipEvent_t ev[8] = {};
@@ -506,8 +507,9 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
     return CHM_ERR_NO_FEASIBLE;
   }
   if (slots.size() > MAX_SLOTS) return CHM_ERR_OVERFLOW;
-  const bool spread = (slots.size() + 8) * SLOT_WAYS * SLOT_STRIDE <= SLOT_WORDS;
+  const bool spread = (slots.size() + 8) * SLOT_WAYS * SLOT_STRIDE <= s->slot_words;
   const uint32_t ways = spread ? SLOT_WAYS : 1, stride = spread ? SLOT_STRIDE : 1;
+  if (slots.size() + 8 > s->slot_words) return CHM_ERR_LIMIT;    // (only the static buffer is that small)
   const uint32_t chunk_words = ways * stride;              // words one chunk (or one counter) owns
   const uint32_t key_words = (uint32_t)slots.size() * chunk_words;
   // right behind the argmin words: three feasibility counters, three counters of evaluated partitions and
@@ -767,6 +769,7 @@ int upload_scenario(chm_scenario *s, chm_scenario **out) {
   ok = ok && pool_take(s->d_scn, sizeof(DevScenario));
   ok = ok && pool_take(s->d_comp, s->comp.size() * sizeof(uint64_t));
   ok = ok && pool_take(s->d_slots, (size_t)SLOT_WORDS * sizeof(uint64_t));
+  s->slot_words = SLOT_WORDS;
   ok = ok && pool_take(s->d_winner, DEV_MAX_AFF * sizeof(uint64_t));
   ok = ok && pool_take(s->d_xfer, sizeof(uint64_t) + DEV_MAX_S);
   ok = ok && pool_take_pinned(s->h_pinned, (size_t)SLOT_WORDS * sizeof(uint64_t));
@@ -936,6 +939,65 @@ extern "C" int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best
   return run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream);
 }
 
+// ---- chm_search_best_static: the same search with its device scratch in a fixed array --------------------------
+// What chm_search_best keeps in buffers allocated at load (the argmin words and counters of the call, the
+// winner's reroute ranks, its transition time) lives here in one file-scope device array, so the call itself
+// allocates nothing.  Every device the library runs on holds its own copy of the array at its own address;
+// host code reaches it only through the address hipGetSymbolAddress returns, looked up once per device.
+enum {
+  STATIC_KEY_WORDS = 8192,                                  // argmin words, counters and incumbent of one call
+  STATIC_WINNER_AT = STATIC_KEY_WORDS,                      // DEV_MAX_AFF words: reroute ranks of the winner
+  STATIC_XFER_AT = STATIC_WINNER_AT + DEV_MAX_AFF,          // 8 + DEV_MAX_S bytes: transition time / migration scheme
+  STATIC_WORDS = STATIC_KEY_WORDS + 16                      // 65,664 bytes
+};
+static_assert(STATIC_XFER_AT + 1 + DEV_MAX_S / 8 <= STATIC_WORDS, "layout of the static scratch");
+static __device__ __align__(256) uint64_t scratch[STATIC_WORDS];
+
+namespace {
+enum { STATIC_MAX_DEVICES = 64 };
+std::mutex static_mutex;
+uint64_t *static_ptr[STATIC_MAX_DEVICES] = {};
+
+// device address of `scratch` on `device` (which must be current); null when the lookup fails
+uint64_t *static_scratch(int device) {
+  if (device < 0 || device >= STATIC_MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> lock(static_mutex);
+  if (!static_ptr[device]) {
+    void *p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+    static_ptr[device] = (uint64_t *)p;
+  }
+  return static_ptr[device];
+}
+}  // namespace
+
+extern "C" int chm_search_best_static(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream) {
+  if (!s || !out) return CHM_ERR_ARG;
+  std::vector<Job> jobs;
+  for (int i = 0; i < s->space.n_families; ++i) {
+    const chm_family &f = s->space.fam[i];
+    if (!(strategy_mask & (1u << f.strategy))) continue;
+    // reroute spaces that are swept by kernels of their own need per-partition scratch (tens of MB)
+    if (f.strategy == 2 && s->fast.usable[2] && s->fast.split) { nothing_found(out); return CHM_ERR_LIMIT; }
+    jobs.push_back({f.strategy, 0, f.n_part, nullptr, nullptr});
+  }
+  if (jobs.empty()) { nothing_found(out); return CHM_ERR_UNRECOVERABLE; }
+  HIP_TRY(hipSetDevice(s->device));
+  uint64_t *base = static_scratch(s->device);
+  if (!base) return CHM_ERR_HIP;
+  // the handle's own buffers step aside for the call
+  uint64_t *const own_slots = s->d_slots, *const own_winner = s->d_winner, *const own_xfer = s->d_xfer;
+  const uint32_t own_words = s->slot_words;
+  s->d_slots = base; s->slot_words = STATIC_KEY_WORDS;
+  s->d_winner = base + STATIC_WINNER_AT;
+  s->d_xfer = base + STATIC_XFER_AT;
+  s->fast.penalty_by_capacity = false;
+  const int rc = run_jobs(s, jobs, out, nullptr, (hipStream_t)hip_stream, ~0ull, false);
+  s->d_slots = own_slots; s->slot_words = own_words; s->d_winner = own_winner; s->d_xfer = own_xfer;
+  if (rc == CHM_ERR_LIMIT) nothing_found(out);
+  return rc;
+}
+
 extern "C" int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part_first, uint64_t part_count,
                                 chm_best *out, void *hip_stream) {
   if (!s || !out || strategy < 0 || strategy > 2) return CHM_ERR_ARG;
@@ -1042,6 +1104,7 @@ extern "C" const char *chm_strerror(int code) {
     case CHM_ERR_UNRECOVERABLE: return "no requested strategy can recover this failure set";
     case CHM_ERR_NO_FEASIBLE: return "every plan exceeds the memory cap";
     case CHM_ERR_HIP: return "HIP call failed";
+    case CHM_ERR_LIMIT: return "beyond the limits of the allocation-free entry point";
     default: return "unknown error";
   }
 }
