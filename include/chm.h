@@ -138,6 +138,23 @@ typedef struct {
  * CHM_ERR_HIP.  On error *out is NULL. */
 int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **out);
 
+/* Which kernels a scenario would run on, decided from the description alone (host only, no device needed; the
+ * same decision chm_load_scenario takes).  The estimator's recurrence (eq. (transition)) and its terms are
+ * evaluated in int64 by the generic kernels; the shape-specialised kernels evaluate the same integers in int32
+ * and are chosen only where load-time bounds show that no intermediate can reach 2^31 (and, for 24-bit
+ * multiplies, 2^24), in which case both give the same results.  Tests use this to place scenarios on either
+ * side of every such bound. */
+typedef struct {
+  int32_t idx_bits;              /* low bits of the packed (cost, index) argmin key */
+  int32_t int32_recurrence;      /* 1: step time + reroute penalty of every plan stays below 2^31 */
+  int32_t present[3];            /* per strategy: it can recover this failure set */
+  int32_t specialised[3];        /* per strategy: 1 = the int32 shape-specialised kernels, 0 = the generic int64 ones */
+  int32_t sharp_bound[3];        /* per strategy: the bounded search may use its sharper lower bound (24-bit multiplies) */
+  int32_t reroute_mul24;         /* peer stage times stay below 2^24 (needed by the specialised rerouting kernels) */
+  int32_t reroute_swept_apart;   /* rerouting: more than 4,096 reroute vectors, swept by kernels of their own */
+} chm_selection;
+int chm_kernel_selection(const chm_scenario_desc *desc, chm_selection *out);
+
 /* The families present for this failure set and the number of plan indices. Host only. */
 int chm_plan_space(const chm_scenario *s, chm_space *out);
 

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libchm.so")
 OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HIP, ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 INFEASIBLE = (1 << 63) - 1
 
-SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best", "chm_search_best_static",
+SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best", "chm_search_best_static", "chm_kernel_selection",
            "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_set_filter_compaction", "chm_set_bounded_search", "chm_get_timing", "chm_family_classes",
            "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
@@ -71,6 +71,12 @@ class ReplanPlan(C.Structure):
                 ("search_ms", C.c_float), ("assign_ms", C.c_float)]
 
 
+class Selection(C.Structure):
+    _fields_ = [("idx_bits", C.c_int32), ("int32_recurrence", C.c_int32), ("present", C.c_int32 * 3),
+                ("specialised", C.c_int32 * 3), ("sharp_bound", C.c_int32 * 3), ("reroute_mul24", C.c_int32),
+                ("reroute_swept_apart", C.c_int32)]
+
+
 class Timing(C.Structure):
     _fields_ = [("family_ms", C.c_float * 3), ("total_ms", C.c_float),
                 ("partitions", C.c_uint64 * 3), ("evaluations", C.c_uint64 * 3), ("feasible", C.c_uint64 * 3),
@@ -103,6 +109,7 @@ def lib():
         L = C.CDLL(LIB_PATH)
         vp = C.c_void_p
         L.chm_load_scenario.argtypes = [C.POINTER(Desc), C.POINTER(vp)]
+        L.chm_kernel_selection.argtypes = [C.POINTER(Desc), C.POINTER(Selection)]
         L.chm_plan_space.argtypes = [vp, C.POINTER(Space)]
         L.chm_score_plans.argtypes = [vp, C.c_uint64, C.c_uint64, vp, vp]
         L.chm_score_ranks.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, vp]
@@ -221,37 +228,54 @@ def _replan_dict(p):
             "comm_rounds": int(p.comm_rounds)}
 
 
+def _desc(sc):
+    """chm_scenario_desc of a scenario dict, and the arrays it points into (keep them alive for the call)"""
+    keep = []
+    d = Desc()
+    d.L, d.PP, d.DP, d.M = sc["L"], sc["PP"], sc["DP"], sc["M"]
+    for name in ("fwd_us", "bwd_us", "mem_mib"):
+        a = np.ascontiguousarray(sc[name], dtype=np.int32)
+        keep.append(a)
+        setattr(d, name, a.ctypes.data_as(C.POINTER(C.c_int32)))
+    if sc.get("speed_q16") is not None:
+        a = np.ascontiguousarray(sc["speed_q16"], dtype=np.uint32)
+        keep.append(a)
+        d.speed_q16 = a.ctypes.data_as(C.POINTER(C.c_uint32))
+    f = np.ascontiguousarray(sc.get("failed_nodes", []), dtype=np.int32)
+    keep.append(f)
+    d.n_failed = len(f)
+    if len(f):
+        d.failed_nodes = f.ctypes.data_as(C.POINTER(C.c_int32))
+    d.comm_us, d.mem_cap_mib = sc["comm_us"], sc["mem_cap_mib"]
+    d.reroute_cap, d.horizon_steps = sc.get("reroute_cap", 0), sc["horizon_steps"]
+    for i in range(3):
+        d.reconf_us[i] = sc["reconf_us"][i]
+    d.xfer_us_per_mib = sc["xfer_us_per_mib"]
+    if sc.get("act_mib") is not None:
+        a = np.ascontiguousarray(sc["act_mib"], dtype=np.int32)
+        keep.append(a)
+        d.act_mib = a.ctypes.data_as(C.POINTER(C.c_int32))
+    d.transfer_assign = int(sc.get("transfer_assign", 0))
+    d.allreduce_us = int(sc.get("allreduce_us", 0))
+    return d, keep
+
+
+def kernel_selection(sc):
+    """chm_kernel_selection: which kernels a scenario would run on (host only)"""
+    d, keep = _desc(sc)
+    out = Selection()
+    _check(lib().chm_kernel_selection(C.byref(d), C.byref(out)))
+    return {"idx_bits": int(out.idx_bits), "int32_recurrence": bool(out.int32_recurrence),
+            "present": [bool(x) for x in out.present], "specialised": [bool(x) for x in out.specialised],
+            "sharp_bound": [bool(x) for x in out.sharp_bound], "reroute_mul24": bool(out.reroute_mul24),
+            "reroute_swept_apart": bool(out.reroute_swept_apart)}
+
+
 class Scenario:
     """chm_load_scenario ... chm_free_scenario.  `sc` is a dict with the fields of chm_scenario_desc."""
 
     def __init__(self, sc):
-        keep = []
-        d = Desc()
-        d.L, d.PP, d.DP, d.M = sc["L"], sc["PP"], sc["DP"], sc["M"]
-        for name in ("fwd_us", "bwd_us", "mem_mib"):
-            a = np.ascontiguousarray(sc[name], dtype=np.int32)
-            keep.append(a)
-            setattr(d, name, a.ctypes.data_as(C.POINTER(C.c_int32)))
-        if sc.get("speed_q16") is not None:
-            a = np.ascontiguousarray(sc["speed_q16"], dtype=np.uint32)
-            keep.append(a)
-            d.speed_q16 = a.ctypes.data_as(C.POINTER(C.c_uint32))
-        f = np.ascontiguousarray(sc.get("failed_nodes", []), dtype=np.int32)
-        keep.append(f)
-        d.n_failed = len(f)
-        if len(f):
-            d.failed_nodes = f.ctypes.data_as(C.POINTER(C.c_int32))
-        d.comm_us, d.mem_cap_mib = sc["comm_us"], sc["mem_cap_mib"]
-        d.reroute_cap, d.horizon_steps = sc.get("reroute_cap", 0), sc["horizon_steps"]
-        for i in range(3):
-            d.reconf_us[i] = sc["reconf_us"][i]
-        d.xfer_us_per_mib = sc["xfer_us_per_mib"]
-        if sc.get("act_mib") is not None:
-            a = np.ascontiguousarray(sc["act_mib"], dtype=np.int32)
-            keep.append(a)
-            d.act_mib = a.ctypes.data_as(C.POINTER(C.c_int32))
-        d.transfer_assign = int(sc.get("transfer_assign", 0))
-        d.allreduce_us = int(sc.get("allreduce_us", 0))
+        d, keep = _desc(sc)
         self._h = C.c_void_p()
         _check(lib().chm_load_scenario(C.byref(d), C.byref(self._h)))
         sp = Space()

@@ -63,6 +63,7 @@ struct FastTables {
 struct FastState {
   bool usable[3] = {false, false, false};   // per strategy: a specialised kernel covers this scenario
   bool split = false;                       // rerouting: vectors swept by k_sweep instead of inside the search kernel
+  bool mul24_reroute = false;               // peer stage times stay below 2^24: the reroute sweeps may use 24-bit multiplies
   // bounded search on the split path: the least penalty of a stage is found from the peers' capacities
   // (k_least_penalty) instead of sweeping every reroute vector; set by the caller per search
   bool penalty_by_capacity = false;
@@ -137,8 +138,11 @@ int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunc
 // Cut positions of candidate `index` (host).
 void fast_candidate_cuts(const CandidateSet &cs, uint64_t index, uint8_t *cuts);
 
-// Decides per strategy whether a specialised kernel applies and uploads its tables.
-// Returns 0, or non-zero on a failed HIP call.
+// Decides per strategy whether a specialised kernel applies and fills the host copy of its tables (host only;
+// a re-partition family whose untouched pipelines do not fit is still reported as covered: its fixed step time
+// is only known once the device has computed it).
+void fast_select(FastState *f, const DevScenario &h, bool int32_ok);
+// fast_select, then uploads the tables.  Returns 0, or non-zero on a failed HIP call.
 int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevScenario *d_scn, const uint64_t *d_comp);
 // Launches the specialised search kernel for one chunk.  Returns 0 on success, a positive
 // value when the strategy is not covered (the caller then uses the generic kernel), or a

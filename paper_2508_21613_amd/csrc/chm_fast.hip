@@ -1709,20 +1709,23 @@ static int ensure_reroute_tables(FastState *f, const DevScenario &h) {
   return f->usable[2] && f->reroute_tables_ready ? 0 : 1;
 }
 
-int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevScenario *d_scn, const uint64_t *d_comp) {
+void fast_select(FastState *f, const DevScenario &h, bool int32_ok) {
   for (bool &u : f->usable) u = false;
   f->split = false;
-  if (!int32_ok) return 0;
+  f->mul24_reroute = false;
+  f->vec_words = 16;
+  memset(&f->h_tables, 0, sizeof(f->h_tables));
+  if (!int32_ok) return;
   // memory side of the int32 kernels: doubled static sums plus the largest activation term stay below
   // 2^31, and the (doubled) activation sums fit the 24-bit multiply
-  if (2 * h.pw[h.L] + 2 * h.pa[h.L] * (int64_t)DEV_MAX_S >= (1ll << 31) || 2 * h.pa[h.L] >= (1ll << 24)) return 0;
+  if (2 * h.pw[h.L] + 2 * h.pa[h.L] * (int64_t)DEV_MAX_S >= (1ll << 31) || 2 * h.pa[h.L] >= (1ll << 24)) return;
   // 24-bit multiplies in the reroute sweep need peer stage times below 2^24
   uint32_t q_aff = 65536;
   for (int a = 0; a < h.n_aff; ++a)
     for (int i = 0; i < h.aff_peers[a]; ++i) q_aff = std::max(q_aff, h.aff_q[a][i]);
   const bool w24 = (((h.pf[h.L] + h.pb[h.L]) * (int64_t)q_aff) >> 16) + 2 < (1ll << 24);
+  f->mul24_reroute = w24;
   FastTables *t = &f->h_tables;
-  memset(t, 0, sizeof(*t));
   size_t vec_words = 16;
   for (int k = 0; k < 3; ++k) {
     const DevFamily &fam = h.fam[k];
@@ -1797,6 +1800,12 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
     f->fit_share[k] = (ok && k != 2) ? -1.0f : 1.0f;      // sampled on first need
   }
   f->vec_words = vec_words;
+}
+
+int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevScenario *d_scn, const uint64_t *d_comp) {
+  fast_select(f, h, int32_ok);
+  if (!f->usable[0] && !f->usable[1] && !f->usable[2]) return 0;
+  FastTables *t = &f->h_tables;
   f->d_scn = d_scn;
   f->d_comp = d_comp;
   f->reroute_tables_ready = false;

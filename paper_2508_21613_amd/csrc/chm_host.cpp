@@ -840,6 +840,30 @@ int chm_internal_load_pipeline(int32_t L, const int32_t *fwd_us, const int32_t *
   return upload_scenario(s, out);
 }
 
+extern "C" int chm_kernel_selection(const chm_scenario_desc *desc, chm_selection *out) {
+  if (!out) return CHM_ERR_ARG;
+  memset(out, 0, sizeof(*out));
+  int rc = validate(desc);
+  if (rc) return rc;
+  chm_scenario *s = new (std::nothrow) chm_scenario();
+  if (!s) return CHM_ERR_HIP;
+  rc = build_model(desc, s);
+  if (rc == CHM_OK) {
+    fast_select(&s->fast, s->h, s->int32_ok);
+    out->idx_bits = s->idx_bits;
+    out->int32_recurrence = s->int32_ok ? 1 : 0;
+    for (int k = 0; k < 3; ++k) {
+      out->present[k] = s->h.fam[k].n_part ? 1 : 0;
+      out->specialised[k] = s->fast.usable[k] ? 1 : 0;
+      out->sharp_bound[k] = s->fast.usable[k] ? s->fast.h_tables.fam[k].lb_prefix : 0;
+    }
+    out->reroute_mul24 = s->fast.mul24_reroute ? 1 : 0;
+    out->reroute_swept_apart = s->fast.split ? 1 : 0;
+  }
+  delete s;
+  return rc;
+}
+
 extern "C" int chm_plan_space(const chm_scenario *s, chm_space *out) {
   if (!s || !out) return CHM_ERR_ARG;
   *out = s->space;
