@@ -199,11 +199,21 @@ int chm_search_cuts(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts, ui
  * chm_search_range or lists instead), CHM_ERR_ARG, CHM_ERR_HIP. */
 int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream);
 
+/* chm_search_best on n distinct handles of one device in one call (the plan cache of the Planner's overhead
+ * paragraph: the best plan for every failure set that may occur, searched ahead of time).  The searches of all
+ * handles are launched back to back on hip_stream and the host waits once for the whole batch instead of once
+ * per handle; outs[i] and codes[i] (host arrays of n) receive what chm_search_best would have returned for
+ * handles[i], bounded or exhaustive as set on each handle.  Returns CHM_OK when every search ran (codes[i] may
+ * still be CHM_ERR_NO_FEASIBLE, CHM_ERR_UNRECOVERABLE, CHM_ERR_OVERFLOW), CHM_ERR_ARG for a null or repeated
+ * handle or handles of different devices, CHM_ERR_HIP when a HIP call failed.  Synchronises hip_stream. */
+int chm_search_best_batch(chm_scenario *const *handles, int32_t n, uint32_t strategy_mask, chm_best *outs,
+                          int32_t *codes, void *hip_stream);
+
 /* chm_search_best for callers that cannot allocate device memory while they run (code under HIP graph capture
  * around it, tight serving loops, harnesses that forbid hipMalloc): the same exhaustive search with the same
  * result, but every device word the call needs beyond the handle's tables - the per-chunk argmin words, the
  * feasibility counters, the winner's reroute ranks and transition time - lives in one fixed device array of
- * 65,664 bytes inside the library (one copy per GPU, held until the process ends) instead of buffers taken
+ * 65,792 bytes inside the library (one copy per GPU, held until the process ends) instead of buffers taken
  * from the allocator.  The call makes no hipMalloc, hipFree or other allocating call.  Always exhaustive
  * (chm_set_bounded_search is ignored).  Limits: at most 8,184 chunks of 2^idx_bits partitions (CHM_ERR_LIMIT
  * beyond; with the usual idx_bits of 30 that is every space chm_search_best accepts short of 2^43 partitions),

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libchm.so")
 OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HIP, ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 INFEASIBLE = (1 << 63) - 1
 
-SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best", "chm_search_best_static", "chm_kernel_selection",
+SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best", "chm_search_best_static", "chm_search_best_batch", "chm_kernel_selection",
            "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_set_filter_compaction", "chm_set_bounded_search", "chm_get_timing", "chm_family_classes",
            "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
@@ -114,6 +114,7 @@ def lib():
         L.chm_score_plans.argtypes = [vp, C.c_uint64, C.c_uint64, vp, vp]
         L.chm_score_ranks.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, vp]
         L.chm_search_best.argtypes = [vp, C.c_uint32, C.POINTER(Best), vp]
+        L.chm_search_best_batch.argtypes = [C.POINTER(vp), C.c_int32, C.c_uint32, C.POINTER(Best), C.POINTER(C.c_int32), vp]
         L.chm_search_best_static.argtypes = [vp, C.c_uint32, C.POINTER(Best), vp]
         L.chm_search_range.argtypes = [vp, C.c_int32, C.c_uint64, C.c_uint64, C.POINTER(Best), vp]
         L.chm_search_ranks.argtypes = [vp, C.c_int32, vp, C.c_uint64, vp, C.POINTER(Best), C.POINTER(C.c_uint64), vp]
@@ -269,6 +270,16 @@ def kernel_selection(sc):
             "present": [bool(x) for x in out.present], "specialised": [bool(x) for x in out.specialised],
             "sharp_bound": [bool(x) for x in out.sharp_bound], "reroute_mul24": bool(out.reroute_mul24),
             "reroute_swept_apart": bool(out.reroute_swept_apart)}
+
+
+def search_best_batch(scenarios, mask=7, stream=None):
+    """chm_search_best_batch over a list of Scenario objects: [(code, best plan)] in the same order"""
+    n = len(scenarios)
+    handles = (C.c_void_p * max(n, 1))(*[g._h for g in scenarios])
+    outs = (Best * max(n, 1))()
+    codes = (C.c_int32 * max(n, 1))()
+    _check(lib().chm_search_best_batch(handles, n, mask, outs, codes, _stream_ptr(stream)))
+    return [(int(codes[i]), _best_dict(outs[i])) for i in range(n)]
 
 
 class Scenario:

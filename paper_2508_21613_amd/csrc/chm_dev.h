@@ -95,6 +95,29 @@ struct SearchLaunch {
   uint64_t *evaluated = nullptr;
 };
 
+// End of a search on the device (k_finish_search): which words to combine and where the result record goes.
+enum { FINISH_MAX_SLOTS = 16, FINISH_MAX_WAYS = 16 };
+// words of the result record
+enum { FINISH_COST = 0,        // winner's cost
+       FINISH_STRATEGY = 1,    // its strategy, ~0 when nothing fits
+       FINISH_PART = 2,        // its partition rank
+       FINISH_TRANS = 3,       // its transition time (int64; -1: does not fit, cannot happen for a winner)
+       FINISH_RR = 4,          // DEV_MAX_AFF words: rank of its best reroute vector per stage that lost nodes
+       FINISH_COUNTS = 8,      // 3 sums of partitions that fit, then 3 sums of partitions evaluated, per strategy
+       FINISH_WORDS = 16 };
+struct FinishArgs {
+  const DevScenario *scn;
+  const uint64_t *slots;       // argmin words: slot i owns `ways` words, `stride` words apart, from slots + i * ways * stride
+  const uint64_t *counters;    // six counters laid out like six more slots
+  uint32_t n_slots, ways, stride;
+  int32_t idx_bits;
+  int32_t sweep_winner;        // 1: a rerouting winner's best vectors are found here by a sweep of one lane per stage
+  int32_t strategy[FINISH_MAX_SLOTS];
+  uint64_t part_first[FINISH_MAX_SLOTS];
+  uint64_t *out;               // FINISH_WORDS words
+};
+int chmk_finish_search(const FinishArgs &a, int32_t smax, void *stream);
+
 // launch wrappers (defined in chm_kernels.hip); each returns a hipError_t cast to int
 int chmk_fixed_pipelines(DevScenario *d_scn, int32_t smax, void *stream);
 int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream);

@@ -43,6 +43,10 @@ struct Slot { int strategy; uint64_t part_first; int idx_bits; };
 }  // namespace
 
 struct chm_scenario {
+  chm_scenario();
+  ~chm_scenario();
+  chm_scenario(const chm_scenario &) = delete;
+  chm_scenario &operator=(const chm_scenario &) = delete;
   DevScenario h;                         // host copy of what the device holds
   std::vector<uint64_t> comp;            // reroute count tables, all affected stages back to back
   std::vector<std::vector<int>> peers;   // per affected stage: surviving replicas, ascending
@@ -57,6 +61,8 @@ struct chm_scenario {
   uint64_t *d_slots = nullptr;           // argmin words, one per launched chunk
   uint64_t *d_winner = nullptr;          // best reroute rank per affected stage
   uint64_t *d_xfer = nullptr;            // migration scheme: 8 bytes MiB to fetch + DEV_MAX_S bytes of stage indices
+  uint64_t *d_final = nullptr;           // result record of k_finish_search (FINISH_WORDS words)
+  struct chm_search_state *search = nullptr;   // the search call in flight on this handle
   uint64_t *h_pinned = nullptr;          // pinned staging for the two small device-to-host copies
   uint32_t slot_words = 0;               // words d_slots has room for
   bool timing = false;
@@ -337,6 +343,7 @@ void release(chm_scenario *s) {
   fast_release(&s->fast, idle);
   for (auto &e : s->ev) if (e) (void)hipEventDestroy(e);
   if (s->h_pinned) pool_release(s->h_pinned, idle);
+  if (s->d_final) pool_release(s->d_final, idle);
   if (s->d_xfer) pool_release(s->d_xfer, idle);
   if (s->d_winner) pool_release(s->d_winner, idle);
   if (s->d_slots) pool_release(s->d_slots, idle);
@@ -482,59 +489,83 @@ uint64_t rank_of_cuts(const chm_scenario *s, int k, const uint8_t *cuts) {
   return rank;
 }
 
-// Runs the argmin over the given partition ranges.
-// With out == null the kernels are only launched (asynchronous scoring into the jobs' cost buffers).
+// One search call in flight on a handle: what launch_jobs set up and collect_jobs needs.
+struct SearchCtx {
+  std::vector<Job> jobs;                 // (copies: a batch keeps them across the launches of other handles)
+  std::vector<Slot> slots;
+  std::vector<size_t> slot_job;          // index into jobs
+  uint32_t ways = 1, stride = 1, chunk_words = 1, key_words = 0;
+  bool bounded_used[3] = {false, false, false};
+  int ev_of[3] = {-1, -1, -1};
+  bool device_finish = false;            // the winner was picked by k_finish_search; one record waits in h_pinned
+  bool light = false;
+  bool empty = false;                    // nothing to search
+};
+
+}  // namespace
+
+struct chm_search_state { SearchCtx ctx; };
+chm_scenario::chm_scenario() : search(new (std::nothrow) chm_search_state()) {}
+chm_scenario::~chm_scenario() { delete search; }
+
+namespace {
+
+// Launches the argmin over the given partition ranges on the stream (nothing is waited for).
 // incumbent0: cost of a plan known before the call (a bounded search prunes against it), ~0 = none;
 // bounded: range jobs skip partitions by their lower bound.
 // light: only cost, strategy and partition of the winner are wanted (out->index = the partition's first plan
 // index; reroute vectors and time terms are left out, which saves their kernels and a synchronisation).
-int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint64_t *position, hipStream_t st,
-             uint64_t incumbent0, bool bounded, bool light = false) {
+// want_result: a winner will be collected (collect_jobs); otherwise the kernels only score into the jobs' buffers.
+int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result, hipStream_t st, uint64_t incumbent0, bool bounded,
+                bool light) {
   HIP_TRY(hipSetDevice(s->device));
   s->last = chm_timing();
-  std::vector<Slot> slots;
+  SearchCtx &c = s->search->ctx;
+  c = SearchCtx();
+  c.jobs = jobs;
+  c.light = light;
   const uint64_t chunk = 1ull << s->idx_bits;
   // spaces that need more chunks than there are argmin slots are refused before anything is sized by them
   uint64_t n_chunks = 0;
   for (const Job &j : jobs) n_chunks += j.count / chunk + 1;
   if (n_chunks > MAX_SLOTS) return CHM_ERR_OVERFLOW;
-  for (const Job &j : jobs)
-    for (uint64_t done = 0; done < j.count; done += chunk)
-      slots.push_back({j.strategy, ((j.ranks || j.cuts) ? 0 : j.first) + done, s->idx_bits});
-  if (slots.empty()) {
-    if (!out) return CHM_OK;
-    nothing_found(out);
-    return CHM_ERR_NO_FEASIBLE;
+  for (size_t ji = 0; ji < jobs.size(); ++ji) {
+    const Job &j = jobs[ji];
+    for (uint64_t done = 0; done < j.count; done += chunk) {
+      c.slots.push_back({j.strategy, ((j.ranks || j.cuts) ? 0 : j.first) + done, s->idx_bits});
+      c.slot_job.push_back(ji);
+    }
   }
-  if (slots.size() > MAX_SLOTS) return CHM_ERR_OVERFLOW;
-  const bool spread = (slots.size() + 8) * SLOT_WAYS * SLOT_STRIDE <= s->slot_words;
-  const uint32_t ways = spread ? SLOT_WAYS : 1, stride = spread ? SLOT_STRIDE : 1;
-  if (slots.size() + 8 > s->slot_words) return CHM_ERR_LIMIT;    // (only the static buffer is that small)
-  const uint32_t chunk_words = ways * stride;              // words one chunk (or one counter) owns
-  const uint32_t key_words = (uint32_t)slots.size() * chunk_words;
-  // right behind the argmin words: three feasibility counters, three counters of evaluated partitions and
-  // the incumbent cost of a bounded search
-  uint64_t *d_count = s->d_slots + key_words;
-  uint64_t *d_evaluated = d_count + 3 * chunk_words;
-  uint64_t *d_seed_count = d_count + 6 * chunk_words;      // what seed jobs count (not reported)
-  uint64_t *d_incumbent = d_count + 7 * chunk_words;
-  if (chmk_init_search(s->d_slots, key_words, 7 * chunk_words, incumbent0, st)) return CHM_ERR_HIP;
-  bool bounded_used[3] = {false, false, false};
+  if (c.slots.empty()) { c.empty = true; return CHM_OK; }
+  if (c.slots.size() > MAX_SLOTS) return CHM_ERR_OVERFLOW;
+  const bool spread = (c.slots.size() + 8) * SLOT_WAYS * SLOT_STRIDE <= s->slot_words;
+  c.ways = spread ? SLOT_WAYS : 1; c.stride = spread ? SLOT_STRIDE : 1;
+  if (c.slots.size() + 8 > s->slot_words) return CHM_ERR_LIMIT;    // (only the static buffer is that small)
+  c.chunk_words = c.ways * c.stride;              // words one chunk (or one counter) owns
+  c.key_words = (uint32_t)c.slots.size() * c.chunk_words;
+  // right behind the argmin words: three feasibility counters, three counters of evaluated partitions, what the
+  // seed jobs count (not reported) and the incumbent cost of a bounded search
+  uint64_t *d_count = s->d_slots + c.key_words;
+  uint64_t *d_evaluated = d_count + 3 * c.chunk_words;
+  uint64_t *d_seed_count = d_count + 6 * c.chunk_words;
+  uint64_t *d_incumbent = d_count + 7 * c.chunk_words;
+  if (chmk_init_search(s->d_slots, c.key_words, 7 * c.chunk_words, incumbent0, st)) return CHM_ERR_HIP;
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;
   int ev_i = 1;
-  int ev_of[3] = {-1, -1, -1};
+  bool plain = true;                         // range jobs only: the device can pick the winner
   for (const Job &j : jobs) {
+    plain = plain && !j.ranks && !j.cuts && !j.cand;
     for (uint64_t done = 0; done < j.count; done += chunk, ++si) {
       SearchLaunch a;
       a.scn = s->d_scn; a.comp = s->d_comp; a.strategy = j.strategy;
       a.part_first = j.first + done;
       a.part_count = (uint32_t)std::min<uint64_t>(chunk, j.count - done);
       a.idx_bits = s->idx_bits;
-      a.result = s->d_slots + si * chunk_words;
-      a.feasible = j.seed ? d_seed_count : d_count + (size_t)j.strategy * chunk_words;
-      a.slot_mask = ways - 1;
-      a.slot_stride = stride;
+      a.result = s->d_slots + si * c.chunk_words;
+      a.feasible = j.seed ? d_seed_count : d_count + (size_t)j.strategy * c.chunk_words;
+      a.slot_mask = c.ways - 1;
+      a.slot_stride = c.stride;
       a.ranks = j.ranks ? j.ranks + done : nullptr;
       a.cuts = j.cuts ? j.cuts + (size_t)done * (size_t)(s->h.fam[j.strategy].stages - 1) : nullptr;
       a.costs_out = j.costs ? j.costs + done : nullptr;
@@ -545,8 +576,8 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
       }
       if (bounded && fast_can_bound(&s->fast, a)) {
         a.incumbent = d_incumbent;
-        a.evaluated = j.seed ? d_seed_count : d_evaluated + (size_t)j.strategy * chunk_words;
-        bounded_used[j.strategy] = !(j.ranks || j.cuts);   // lists: what passes their filter is evaluated and counted as fitting
+        a.evaluated = j.seed ? d_seed_count : d_evaluated + (size_t)j.strategy * c.chunk_words;
+        c.bounded_used[j.strategy] = !(j.ranks || j.cuts);   // lists: what passes their filter is evaluated and counted as fitting
       }
       int rc = fast_search(&s->fast, s->h, a, st);      // > 0: shape not covered by a specialised kernel
       if (rc > 0) rc = chmk_search(a, s->smax, st);
@@ -558,11 +589,88 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
     uint64_t per_part = 1;
     if (j.strategy == 2 && s->h.n_aff) { per_part = 0; for (int a = 0; a < s->h.n_aff; ++a) per_part += s->h.aff_R[a]; }
     s->last.evaluations[j.strategy] += covered * per_part;
-    if (s->timing && ev_i < 7) { HIP_TRY(hipEventRecord(s->ev[ev_i], st)); ev_of[j.strategy] = ev_i; ++ev_i; }
+    if (s->timing && ev_i < 7) { HIP_TRY(hipEventRecord(s->ev[ev_i], st)); c.ev_of[j.strategy] = ev_i; ++ev_i; }
   }
-  if (!out) return CHM_OK;
-  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (size_t)(key_words + 6 * chunk_words) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
-  HIP_TRY(hipStreamSynchronize(st));
+  if (!want_result) return CHM_OK;
+  // Few chunks of plain ranges: a one-workgroup kernel behind the search kernels picks the winner, adds up the
+  // counters and computes the winner's transition time (and its best reroute vectors), so the host waits once
+  // and copies one record.  Not where the winner's vectors come from the vector tables of a large reroute space
+  // (that needs the partition on the host first).
+  bool split_sweep = false;
+  for (const Job &j : jobs)
+    split_sweep = split_sweep || (j.strategy == 2 && s->h.n_aff > 0 && s->fast.split && s->fast.usable[2] && !s->fast.penalty_by_capacity);
+  if (plain && !split_sweep && c.slots.size() <= FINISH_MAX_SLOTS && c.ways <= FINISH_MAX_WAYS) {
+    FinishArgs f;
+    memset(&f, 0, sizeof(f));
+    f.scn = s->d_scn; f.slots = s->d_slots; f.counters = d_count;
+    f.n_slots = (uint32_t)c.slots.size(); f.ways = c.ways; f.stride = c.stride; f.idx_bits = s->idx_bits;
+    f.sweep_winner = (!light && !(s->fast.split && s->fast.usable[2])) ? 1 : 0;
+    for (size_t i = 0; i < c.slots.size(); ++i) { f.strategy[i] = c.slots[i].strategy; f.part_first[i] = c.slots[i].part_first; }
+    f.out = s->d_final;
+    if (chmk_finish_search(f, s->smax, st)) return CHM_ERR_HIP;
+    HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_final, FINISH_WORDS * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    c.device_finish = true;
+    return CHM_OK;
+  }
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (size_t)(c.key_words + 6 * c.chunk_words) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  return CHM_OK;
+}
+
+// per-strategy kernel times of the call from the events launch_jobs recorded (the stream has been waited for)
+int read_timing(chm_scenario *s) {
+  const SearchCtx &c = s->search->ctx;
+  if (!s->timing) return CHM_OK;
+  int prev = 0;
+  for (int k = 0; k < 3; ++k) {
+    if (c.ev_of[k] < 0) continue;
+    float ms = 0;
+    // families are launched in strategy order, so each one's span starts at the previous event
+    HIP_TRY(hipEventElapsedTime(&ms, s->ev[prev], s->ev[c.ev_of[k]]));
+    s->last.family_ms[k] += ms;
+    prev = c.ev_of[k];
+  }
+  HIP_TRY(hipEventElapsedTime(&s->last.total_ms, s->ev[0], s->ev[prev]));
+  return CHM_OK;
+}
+
+// Second half of a search whose launch_jobs(want_result) succeeded: waits for the stream (unless the caller
+// has: synced), reads the winner and fills *out.
+int collect_jobs(chm_scenario *s, chm_best *out, uint64_t *position, hipStream_t st, bool synced) {
+  SearchCtx &c = s->search->ctx;
+  if (c.empty) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
+  HIP_TRY(hipSetDevice(s->device));
+  if (!synced) HIP_TRY(hipStreamSynchronize(st));
+  const bool light = c.light;
+  int64_t best_cost = CHM_INFEASIBLE;
+  int best_strategy = -1;
+  uint64_t best_part = 0;
+  uint64_t rr[DEV_MAX_AFF] = {};
+  if (c.device_finish) {
+    const uint64_t *rec = s->h_pinned;
+    for (int k = 0; k < 3; ++k) { s->last.feasible[k] += rec[FINISH_COUNTS + k]; s->last.evaluated[k] += rec[FINISH_COUNTS + 3 + k]; }
+    for (int k = 0; k < 3; ++k)
+      if (!c.bounded_used[k]) s->last.evaluated[k] = s->last.feasible[k];
+    if (const int rc = read_timing(s)) return rc;
+    if (rec[FINISH_STRATEGY] == ~0ull) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
+    best_cost = (int64_t)rec[FINISH_COST];
+    best_strategy = (int)rec[FINISH_STRATEGY];
+    best_part = rec[FINISH_PART];
+    if (light) {
+      fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
+      return CHM_OK;
+    }
+    if (best_strategy == 2 && s->h.n_aff > 0) {
+      if (s->fast.split && s->fast.usable[2]) host_reroute_ranks(s, best_part, rr);   // bounded search: no vector tables
+      else for (int a = 0; a < s->h.n_aff; ++a) rr[a] = rec[FINISH_RR + a];
+    }
+    fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
+    const int64_t t_trans = (int64_t)rec[FINISH_TRANS];
+    if (t_trans < 0 || t_trans > best_cost || (best_cost - t_trans) % s->h.K != 0) return CHM_ERR_HIP;   // cannot happen
+    out->t_trans_us = t_trans;
+    out->t_step_us = (best_cost - t_trans) / s->h.K;
+    return CHM_OK;
+  }
+  const uint32_t ways = c.ways, stride = c.stride, chunk_words = c.chunk_words, key_words = c.key_words;
   for (int k = 0; k < 3; ++k)
     for (uint32_t w = 0; w < ways; ++w) {
       s->last.feasible[k] += s->h_pinned[key_words + (size_t)k * chunk_words + (size_t)w * stride];
@@ -570,44 +678,28 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
     }
   // kernels that evaluate everything that fits do not count what they evaluate
   for (int k = 0; k < 3; ++k)
-    if (!bounded_used[k]) s->last.evaluated[k] = s->last.feasible[k];
-  if (s->timing) {
-    int prev = 0;
-    for (int k = 0; k < 3; ++k) {
-      if (ev_of[k] < 0) continue;
-      float ms = 0;
-      // families are launched in strategy order, so each one's span starts at the previous event
-      HIP_TRY(hipEventElapsedTime(&ms, s->ev[prev], s->ev[ev_of[k]]));
-      s->last.family_ms[k] += ms;
-      prev = ev_of[k];
-    }
-    HIP_TRY(hipEventElapsedTime(&s->last.total_ms, s->ev[0], s->ev[prev]));
-  }
+    if (!c.bounded_used[k]) s->last.evaluated[k] = s->last.feasible[k];
+  if (const int rc = read_timing(s)) return rc;
   // lowest cost; among equal costs the lowest plan index (strategy, then partition)
-  int64_t best_cost = CHM_INFEASIBLE;
-  int best_strategy = -1;
-  uint64_t best_part = 0;
   const Job *best_job = nullptr;
-  std::vector<const Job *> slot_job;
-  for (const Job &j : jobs)
-    for (uint64_t done = 0; done < j.count; done += chunk) slot_job.push_back(&j);
-  for (size_t i = 0; i < slots.size(); ++i) {
+  for (size_t i = 0; i < c.slots.size(); ++i) {
     uint64_t key = CHM_KEY_NONE;
     for (uint32_t w = 0; w < ways; ++w) key = std::min(key, s->h_pinned[i * chunk_words + (size_t)w * stride]);
     if (key == CHM_KEY_NONE) continue;
-    const int64_t cost = (int64_t)(key >> slots[i].idx_bits);
-    uint64_t part = slots[i].part_first + (key & ((1ull << slots[i].idx_bits) - 1));
-    if (slot_job[i]->cand) {                       // a candidate's index: its partition rank decides among equal costs
+    const Job &job = c.jobs[c.slot_job[i]];
+    const int64_t cost = (int64_t)(key >> c.slots[i].idx_bits);
+    uint64_t part = c.slots[i].part_first + (key & ((1ull << c.slots[i].idx_bits) - 1));
+    if (job.cand) {                                // a candidate's index: its partition rank decides among equal costs
       uint8_t cuts[32];
-      fast_candidate_cuts(*slot_job[i]->cand, part * slot_job[i]->stride, cuts);
-      part = rank_of_cuts(s, s->h.fam[slots[i].strategy].stages - 1, cuts);
+      fast_candidate_cuts(*job.cand, part * job.stride, cuts);
+      part = rank_of_cuts(s, s->h.fam[c.slots[i].strategy].stages - 1, cuts);
     }
-    if (cost < best_cost || (cost == best_cost && (slots[i].strategy < best_strategy ||
-                                                   (slots[i].strategy == best_strategy && part < best_part)))) {
+    if (cost < best_cost || (cost == best_cost && (c.slots[i].strategy < best_strategy ||
+                                                   (c.slots[i].strategy == best_strategy && part < best_part)))) {
       best_cost = cost;
-      best_strategy = slots[i].strategy;
+      best_strategy = c.slots[i].strategy;
       best_part = part;
-      best_job = slot_job[i];
+      best_job = &job;
     }
   }
   if (best_strategy < 0) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
@@ -624,7 +716,6 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
     HIP_TRY(hipStreamSynchronize(st));
     best_part = s->h_pinned[0];
   }
-  uint64_t rr[DEV_MAX_AFF] = {};
   if (light) {
     fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
     return CHM_OK;
@@ -655,6 +746,15 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
   return CHM_OK;
 }
 
+// Runs the argmin over the given partition ranges.
+// With out == null the kernels are only launched (asynchronous scoring into the jobs' cost buffers).
+int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint64_t *position, hipStream_t st,
+             uint64_t incumbent0, bool bounded, bool light = false) {
+  const int rc = launch_jobs(s, jobs, out != nullptr, st, incumbent0, bounded, light);
+  if (rc || !out) return rc;
+  return collect_jobs(s, out, position, st, false);
+}
+
 // Exhaustive search, or (chm_set_bounded_search) the same argmin with the plans skipped that cannot reach it.
 // A bounded search first evaluates a few partitions that are likely to be good: 64 ranks around the
 // time-balanced and around the memory-balanced partition of every range.  Their best cost bounds everything
@@ -663,10 +763,9 @@ int run_jobs(chm_scenario *s, const std::vector<Job> &jobs, chm_best *out, uint6
 // evaluated; sub-ranges, families with too many candidates and the shapes the candidate path does not cover are
 // searched range by range with the bound applied per run and per partition.  The seeds' best plan competes
 // with the result (it is among the candidates as well; equal plans compare equal).
-int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, uint64_t *position, hipStream_t st) {
-  s->fast.penalty_by_capacity = s->bounded && out != nullptr;
-  if (!(s->bounded && out != nullptr)) return run_jobs(s, given, out, position, st, ~0ull, false);
-  const uint64_t seeds_from = s->bounded == 2 ? 1 : (1u << 16), enumerate_from = s->bounded == 2 ? 1 : ENUMERATE_FROM;
+// seeds of a bounded search: 64 ranks around the time-balanced and the memory-balanced partition of every range
+std::vector<Job> make_seeds(const chm_scenario *s, const std::vector<Job> &given) {
+  const uint64_t seeds_from = s->bounded == 2 ? 1 : (1u << 16);
   std::vector<Job> seeds;
   for (const Job &j : given) {
     if (j.ranks || j.cuts || j.costs || j.count < seeds_from) continue;
@@ -682,13 +781,26 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
       }
     }
   }
-  // Families that are enumerated need the seeds' cost on the host first.  When none can be (sub-ranges, families
-  // small enough that the range search costs no more), the seeds simply run ahead of the ranges in one pass.
-  bool any_enumerable = false;
+  return seeds;
+}
+
+// Families that are enumerated need the seeds' cost on the host first.  When none can be (sub-ranges, families
+// small enough that the range search costs no more), the seeds simply run ahead of the ranges in one pass.
+bool any_enumerable(const chm_scenario *s, const std::vector<Job> &given) {
+  const uint64_t enumerate_from = s->bounded == 2 ? 1 : ENUMERATE_FROM;
+  bool any = false;
   for (const Job &j : given)
-    any_enumerable = any_enumerable || (!j.ranks && !j.cuts && !j.costs && j.first == 0 && j.count == s->h.fam[j.strategy].n_part &&
-                                        j.count >= enumerate_from && s->idx_bits >= 23);
-  if (!any_enumerable) {
+    any = any || (!j.ranks && !j.cuts && !j.costs && j.first == 0 && j.count == s->h.fam[j.strategy].n_part &&
+                  j.count >= enumerate_from && s->idx_bits >= 23);
+  return any;
+}
+
+int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, uint64_t *position, hipStream_t st) {
+  s->fast.penalty_by_capacity = s->bounded && out != nullptr;
+  if (!(s->bounded && out != nullptr)) return run_jobs(s, given, out, position, st, ~0ull, false);
+  const uint64_t enumerate_from = s->bounded == 2 ? 1 : ENUMERATE_FROM;
+  const std::vector<Job> seeds = make_seeds(s, given);
+  if (!any_enumerable(s, given)) {
     std::vector<Job> all(seeds);
     all.insert(all.end(), given.begin(), given.end());
     return run_jobs(s, all, out, position, st, ~0ull, true);
@@ -772,6 +884,7 @@ int upload_scenario(chm_scenario *s, chm_scenario **out) {
   s->slot_words = SLOT_WORDS;
   ok = ok && pool_take(s->d_winner, DEV_MAX_AFF * sizeof(uint64_t));
   ok = ok && pool_take(s->d_xfer, sizeof(uint64_t) + DEV_MAX_S);
+  ok = ok && pool_take(s->d_final, FINISH_WORDS * sizeof(uint64_t));
   ok = ok && pool_take_pinned(s->h_pinned, (size_t)SLOT_WORDS * sizeof(uint64_t));
   ok = ok && hipMemcpy(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice) == hipSuccess;
   ok = ok && hipMemcpy(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice) == hipSuccess;
@@ -795,7 +908,7 @@ extern "C" int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **o
   int rc = validate(desc);
   if (rc) return rc;
   chm_scenario *s = new (std::nothrow) chm_scenario();
-  if (!s) return CHM_ERR_HIP;
+  if (!s || !s->search) { delete s; return CHM_ERR_HIP; }
   rc = build_model(desc, s);
   if (rc) { delete s; return rc; }
   return upload_scenario(s, out);
@@ -819,7 +932,7 @@ int chm_internal_load_pipeline(int32_t L, const int32_t *fwd_us, const int32_t *
   int rc = validate(&d);
   if (rc) return rc;
   chm_scenario *s = new (std::nothrow) chm_scenario();
-  if (!s) return CHM_ERR_HIP;
+  if (!s || !s->search) { delete s; return CHM_ERR_HIP; }
   rc = build_model(&d, s);          // no failure: strategies 0 and 2 of the intact pipeline; replaced below
   if (rc) { delete s; return rc; }
   DevScenario &h = s->h;
@@ -846,7 +959,7 @@ extern "C" int chm_kernel_selection(const chm_scenario_desc *desc, chm_selection
   int rc = validate(desc);
   if (rc) return rc;
   chm_scenario *s = new (std::nothrow) chm_scenario();
-  if (!s) return CHM_ERR_HIP;
+  if (!s || !s->search) { delete s; return CHM_ERR_HIP; }
   rc = build_model(desc, s);
   if (rc == CHM_OK) {
     fast_select(&s->fast, s->h, s->int32_ok);
@@ -963,6 +1076,46 @@ extern "C" int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best
   return run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream);
 }
 
+extern "C" int chm_search_best_batch(chm_scenario *const *handles, int32_t n, uint32_t strategy_mask, chm_best *outs,
+                                     int32_t *codes, void *hip_stream) {
+  if (n < 0 || (n > 0 && (!handles || !outs || !codes))) return CHM_ERR_ARG;
+  std::vector<const chm_scenario *> seen(handles, handles + n);
+  std::sort(seen.begin(), seen.end());
+  for (int i = 0; i < n; ++i)
+    if (!seen[i] || (i > 0 && seen[i] == seen[i - 1]) || seen[i]->device != seen[0]->device) return CHM_ERR_ARG;
+  hipStream_t st = (hipStream_t)hip_stream;
+  std::vector<char> pending(n, 0);
+  bool any_pending = false;
+  for (int i = 0; i < n; ++i) {
+    chm_scenario *s = handles[i];
+    std::vector<Job> jobs;
+    for (int k = 0; k < s->space.n_families; ++k) {
+      const chm_family &f = s->space.fam[k];
+      if (strategy_mask & (1u << f.strategy)) jobs.push_back({f.strategy, 0, f.n_part, nullptr, nullptr});
+    }
+    if (jobs.empty()) { nothing_found(&outs[i]); codes[i] = CHM_ERR_UNRECOVERABLE; continue; }
+    // searches that need the host between two of their passes (a bounded search that enumerates candidates) run
+    // on their own; all others are launched now and collected after one wait for the whole batch
+    if (s->bounded && any_enumerable(s, jobs)) { codes[i] = run_search(s, jobs, &outs[i], nullptr, st); continue; }
+    s->fast.penalty_by_capacity = s->bounded != 0;
+    if (s->bounded) {
+      std::vector<Job> all = make_seeds(s, jobs);
+      all.insert(all.end(), jobs.begin(), jobs.end());
+      jobs.swap(all);
+    }
+    codes[i] = launch_jobs(s, jobs, true, st, ~0ull, s->bounded != 0, false);
+    if (codes[i] != CHM_OK) { nothing_found(&outs[i]); continue; }
+    if (s->search->ctx.device_finish || s->search->ctx.empty) { pending[i] = 1; any_pending = true; }
+    else codes[i] = collect_jobs(s, &outs[i], nullptr, st, false);
+  }
+  if (any_pending && hipStreamSynchronize(st) != hipSuccess) return CHM_ERR_HIP;
+  for (int i = 0; i < n; ++i)
+    if (pending[i]) codes[i] = collect_jobs(handles[i], &outs[i], nullptr, st, true);
+  for (int i = 0; i < n; ++i)
+    if (codes[i] == CHM_ERR_HIP || codes[i] == CHM_ERR_ARG) return codes[i];
+  return CHM_OK;
+}
+
 // ---- chm_search_best_static: the same search with its device scratch in a fixed array --------------------------
 // What chm_search_best keeps in buffers allocated at load (the argmin words and counters of the call, the
 // winner's reroute ranks, its transition time) lives here in one file-scope device array, so the call itself
@@ -972,9 +1125,11 @@ enum {
   STATIC_KEY_WORDS = 8192,                                  // argmin words, counters and incumbent of one call
   STATIC_WINNER_AT = STATIC_KEY_WORDS,                      // DEV_MAX_AFF words: reroute ranks of the winner
   STATIC_XFER_AT = STATIC_WINNER_AT + DEV_MAX_AFF,          // 8 + DEV_MAX_S bytes: transition time / migration scheme
-  STATIC_WORDS = STATIC_KEY_WORDS + 16                      // 65,664 bytes
+  STATIC_FINAL_AT = STATIC_KEY_WORDS + 16,                  // FINISH_WORDS words: result record of the call
+  STATIC_WORDS = STATIC_KEY_WORDS + 32                      // 65,792 bytes
 };
-static_assert(STATIC_XFER_AT + 1 + DEV_MAX_S / 8 <= STATIC_WORDS, "layout of the static scratch");
+static_assert(STATIC_XFER_AT + 1 + DEV_MAX_S / 8 <= STATIC_FINAL_AT && STATIC_FINAL_AT + FINISH_WORDS <= STATIC_WORDS,
+              "layout of the static scratch");
 static __device__ __align__(256) uint64_t scratch[STATIC_WORDS];
 
 namespace {
@@ -1010,14 +1165,15 @@ extern "C" int chm_search_best_static(chm_scenario *s, uint32_t strategy_mask, c
   uint64_t *base = static_scratch(s->device);
   if (!base) return CHM_ERR_HIP;
   // the handle's own buffers step aside for the call
-  uint64_t *const own_slots = s->d_slots, *const own_winner = s->d_winner, *const own_xfer = s->d_xfer;
+  uint64_t *const own_slots = s->d_slots, *const own_winner = s->d_winner, *const own_xfer = s->d_xfer, *const own_final = s->d_final;
   const uint32_t own_words = s->slot_words;
   s->d_slots = base; s->slot_words = STATIC_KEY_WORDS;
   s->d_winner = base + STATIC_WINNER_AT;
   s->d_xfer = base + STATIC_XFER_AT;
+  s->d_final = base + STATIC_FINAL_AT;
   s->fast.penalty_by_capacity = false;
   const int rc = run_jobs(s, jobs, out, nullptr, (hipStream_t)hip_stream, ~0ull, false);
-  s->d_slots = own_slots; s->slot_words = own_words; s->d_winner = own_winner; s->d_xfer = own_xfer;
+  s->d_slots = own_slots; s->slot_words = own_words; s->d_winner = own_winner; s->d_xfer = own_xfer; s->d_final = own_final;
   if (rc == CHM_ERR_LIMIT) nothing_found(out);
   return rc;
 }

@@ -572,6 +572,68 @@ __global__ void __launch_bounds__(BLOCK) k_plan_transition(const DevScenario *sc
   out[0] = eval_base<SMAX, false>(scn, fam, cuts, &t_step, &reconf) ? reconf : -1;
 }
 
+// End of a search on the device: the winner among the argmin words of all launched chunks (lowest cost; among
+// equal costs the lowest strategy, then the lowest partition rank: the lowest plan index), the sums of the
+// feasibility counters, the winner's transition time and, for data rerouting, the ranks of its best reroute
+// vectors, gathered into one record that the host fetches with a single copy.  One workgroup.
+template <int SMAX>
+__global__ void __launch_bounds__(BLOCK) k_finish_search(FinishArgs a) {
+  __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
+  __shared__ int32_t rv_cols[DEV_MAX_D][BLOCK];
+  __shared__ uint64_t keys[FINISH_MAX_SLOTS * FINISH_MAX_WAYS];
+  __shared__ uint64_t counts[6 * FINISH_MAX_WAYS];
+  __shared__ uint64_t win[3];                        // cost, strategy (~0: nothing found), partition rank
+  const uint32_t chunk_words = a.ways * a.stride;
+  const uint32_t t = threadIdx.x;
+  if (t < a.n_slots * a.ways) keys[t] = a.slots[(size_t)(t / a.ways) * chunk_words + (size_t)(t % a.ways) * a.stride];
+  if (t < 6 * a.ways) counts[t] = a.counters[(size_t)(t / a.ways) * chunk_words + (size_t)(t % a.ways) * a.stride];
+  __syncthreads();
+  if (t == 0) {
+    uint64_t best_cost = ~0ull, best_part = 0;
+    int best_strategy = -1;
+    for (uint32_t i = 0; i < a.n_slots; ++i) {
+      uint64_t key = CHM_KEY_NONE;
+      for (uint32_t w = 0; w < a.ways; ++w) key = umin64(key, keys[i * a.ways + w]);
+      if (key == CHM_KEY_NONE) continue;
+      const uint64_t cost = key >> a.idx_bits;
+      const uint64_t part = a.part_first[i] + (key & ((1ull << a.idx_bits) - 1ull));
+      const int strategy = a.strategy[i];
+      if (best_strategy < 0 || cost < best_cost ||
+          (cost == best_cost && (strategy < best_strategy || (strategy == best_strategy && part < best_part)))) {
+        best_cost = cost; best_strategy = strategy; best_part = part;
+      }
+    }
+    win[0] = best_cost; win[1] = best_strategy < 0 ? ~0ull : (uint64_t)best_strategy; win[2] = best_part;
+    a.out[FINISH_COST] = best_cost;
+    a.out[FINISH_STRATEGY] = win[1];
+    a.out[FINISH_PART] = best_part;
+    for (int k = 0; k < 6; ++k) {
+      uint64_t sum = 0;
+      for (uint32_t w = 0; w < a.ways; ++w) sum += counts[k * a.ways + w];
+      a.out[FINISH_COUNTS + k] = sum;
+    }
+  }
+  __syncthreads();
+  if (win[1] == ~0ull) return;
+  const int strategy = (int)win[1];
+  const uint64_t part = win[2];
+  const DevScenario *scn = a.scn;
+  const DevFamily &fam = scn->fam[strategy];
+  Cuts<SMAX> cuts{cut_cols, (int)t};
+  if (t == 0) {
+    unrank_partition<SMAX>(scn, fam.stages - 1, part, cuts);
+    int64_t t_step = 0, reconf = 0;
+    a.out[FINISH_TRANS] = (uint64_t)(eval_base<SMAX, false>(scn, fam, cuts, &t_step, &reconf) ? reconf : (int64_t)-1);
+  } else if (a.sweep_winner && strategy == 2 && t >= 64 && (int)(t - 64) < scn->n_aff) {
+    // one lane per stage that lost nodes, in the second wavefront, beside the transition time
+    const int st = (int)(t - 64);
+    unrank_partition<SMAX>(scn, fam.stages - 1, part, cuts);
+    int64_t pen; uint64_t rk;
+    sweep_stage<SMAX>(scn, cuts, st, rv_cols, &pen, &rk);
+    a.out[FINISH_RR + st] = rk;
+  }
+}
+
 // partition rank of explicit cut positions (inverse of unrank_partition); cuts[n][k] row-major.
 // Cuts that are not strictly increasing within 1..L-1 give UINT64_MAX.
 __global__ void __launch_bounds__(BLOCK) k_rank_cuts(const DevScenario *scn, int k, const uint8_t *cuts, uint64_t n,
@@ -679,6 +741,15 @@ int chmk_plan_transition(const DevScenario *d_scn, int32_t strategy, uint64_t pa
   return dispatch_smax(smax, [&](auto tag) {
     constexpr int SMAX = decltype(tag)::value;
     hipLaunchKernelGGL(k_plan_transition<SMAX>, dim3(1), dim3(BLOCK), 0, (hipStream_t)stream, d_scn, strategy, part_rank, d_out);
+    return (int)hipGetLastError();
+  });
+}
+
+int chmk_finish_search(const FinishArgs &a, int32_t smax, void *stream) {
+  if (a.n_slots == 0 || a.n_slots > FINISH_MAX_SLOTS || a.ways == 0 || a.ways > FINISH_MAX_WAYS) return (int)hipErrorInvalidValue;
+  return dispatch_smax(smax, [&](auto tag) {
+    constexpr int SMAX = decltype(tag)::value;
+    hipLaunchKernelGGL(k_finish_search<SMAX>, dim3(1), dim3(BLOCK), 0, (hipStream_t)stream, a);
     return (int)hipGetLastError();
   });
 }
