@@ -4,7 +4,9 @@ A step is one exhaustive chm_search_best over the whole plan space of the 32-car
 configuration (L=48, PP=8, DP=4, M=16, one failed node): unranking, stage sums, memory
 filter, 1F1B recurrence per pipeline class, strategy terms and argmin for every partition
 of the three strategies and every reroute vector.  The scenario tables are resident in
-HBM before the timed region.  Prints one JSON line.
+HBM before the timed region.  Prints one JSON line; with no flags that line also carries a
+`workloads` block with the other configurations (1, 3, 4, 5), the cost store and the
+re-planning search at a few steps each.
 """
 import argparse
 import json
@@ -16,16 +18,24 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+METRIC = "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)"
+
 # MI355X VALU: 256 compute units x 4 SIMDs x 32 lanes per clock x 2.4 GHz = 78.6 T int32 lane
 # operations per second (the published fp32 vector figure, 157.3 TFLOP/s, is this rate x 2 flops per
 # fused multiply-add).  Only simple operations (v_add_u32) issue at that rate; v_max_i32 and
 # v_mul_u32_u24, which the path needs, issue at half of it (chm_valu_probe measures both).
 ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 
-# HBM bytes per launch of the config-2 search kernels, per strategy, from the rocprofv3 --pmc runs summarised in
-# profiles/search_kernels_config2.md: FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (KiB; the factors come from the
-# 1 GiB calibration copy of the same runs).  Counters cannot be read from inside this process.
+# From the rocprofv3 --pmc runs summarised in profiles/search_kernels_config2.md (counters cannot be read from
+# inside this process), per strategy kernel of config 2:
+# HBM bytes per launch = FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB (factors from the 1 GiB calibration copy of the same runs)
 CONFIG2_TRAFFIC_BYTES = {0: (178.9 * 2.0 + 4302) * 1024, 1: (133.0 * 2.0 + 510.5) * 1024, 2: (182.2 * 2.0 + 490.6) * 1024}
+# executed VALU lane-instructions per partition = SQ_INSTS_VALU x 64 / partitions of the family
+CONFIG2_EXECUTED_LANE_INSTR_PER_PARTITION = {0: 560.0, 1: 469.0, 2: 755.0}
+
+
+def note(msg):
+    print("[bench] " + msg, file=sys.stderr, flush=True)
 
 
 def algorithmic_ops(fam, feasible):
@@ -58,7 +68,88 @@ def copy_calibration():
     del src, dst
 
 
-def bench_replan(args, note, B, synth):
+def host_cores():
+    """cores this process may run on (the GPU machine gives a one-GPU job a share of the host)"""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except AttributeError:
+        n = os.cpu_count() or 1
+    env = os.environ.get("OMP_NUM_THREADS")
+    if env and env.isdigit():
+        n = min(n, max(1, int(env)))
+    return n
+
+
+def oracle_all_cores(scenario, seconds, cores):
+    """The oracle searching slices from the middle of every strategy's rank space, as independent single-threaded
+    workers on `cores` host threads (one handle each; the C calls release the interpreter lock), about `seconds`
+    of wall clock.  Returns per-strategy (partitions done by all workers, evaluations, wall seconds) and the
+    seconds the oracle alone (one thread) would need for the whole space at the measured per-core rates."""
+    from concurrent.futures import ThreadPoolExecutor
+    from oracle import oracle as O
+    probe = O.Scenario(scenario)
+    fams = probe.families
+    weights = []
+    for f in fams:                                   # calibration: time per partition of every strategy, one thread
+        mid = f["n_part"] // 2
+        n0 = 1
+        while True:
+            n0 = max(1, min(n0, f["n_part"] - mid))
+            t0 = time.perf_counter()
+            probe.search_range(f["strategy"], mid, n0)
+            dt = time.perf_counter() - t0
+            if dt >= 0.05 or n0 >= 256 or n0 >= f["n_part"] - mid:
+                break
+            n0 *= 4
+        weights.append(max(dt, 1e-5) / n0)
+    total_cost = sum(w * f["n_part"] for w, f in zip(weights, fams))
+    rows = []
+    for f, w in zip(fams, weights):
+        share = max(0.1, w * f["n_part"] / total_cost * 0.8)
+        per_worker = int(max(1, min(f["n_part"] // (2 * cores) or 1, seconds * share / w)))
+        mid = f["n_part"] // 2
+        first = max(0, mid - per_worker * cores // 2)
+
+        def work(i, f=f, first=first, per_worker=per_worker):
+            o = O.Scenario(scenario)
+            lo = min(first + i * per_worker, f["n_part"] - 1)
+            n = min(per_worker, f["n_part"] - lo)
+            _, _, ev = o.search_range(f["strategy"], lo, n)
+            o.close()
+            return n, ev
+
+        t0 = time.perf_counter()
+        with ThreadPoolExecutor(max_workers=cores) as pool:
+            got = list(pool.map(work, range(cores)))
+        wall = time.perf_counter() - t0
+        rows.append({"strategy": f["strategy"], "partitions": sum(n for n, _ in got), "evaluations": sum(e for _, e in got),
+                     "wall_s": wall, "n_part": f["n_part"], "n_reroute_evals": got[0][1] / max(1, got[0][0])})
+        note("oracle: strategy %d, %d partitions on %d cores in %.2f s" % (f["strategy"], rows[-1]["partitions"], cores, wall))
+    probe.close()
+    return rows
+
+
+def cpu_baseline_record(scenario, seconds, what):
+    cores = host_cores()
+    rows = oracle_all_cores(scenario, seconds, cores)
+    # aggregate: all cores busy; per core: the same work divided by the workers
+    full_wall_s = sum(r["wall_s"] * r["n_part"] / r["partitions"] for r in rows)
+    plans = sum(r["n_part"] * r["n_reroute_evals"] for r in rows)
+    return {"value": plans / full_wall_s, "unit": "plans/s", "cores": cores, "kind": "oracle",
+            "per_core_value": plans / (full_wall_s * cores), "host_cores_available": os.cpu_count(),
+            "extrapolated": True,
+            "sample": "%s: oracle exhaustive search over %s partitions from the middle of the rank space of strategies %s, "
+                      "split over %d independent single-threaded workers (%.1f s of wall clock), extrapolated per strategy "
+                      "to the full space" % (what, [r["partitions"] for r in rows], [r["strategy"] for r in rows], cores,
+                                              sum(r["wall_s"] for r in rows)),
+            "full_space_seconds_estimate_all_cores": full_wall_s,
+            "full_space_core_seconds_estimate": full_wall_s * cores}
+
+
+# ---------------------------------------------------------------------------------------------------------
+# re-planning over DP/PP degrees
+# ---------------------------------------------------------------------------------------------------------
+def bench_replan(args, B, synth):
     """A step = one chm_replan over the 31 surviving nodes of the 32-card shape: every contiguous split of the
     48 layers for every pipeline length the DP range 2..6 produces within 4..12 stages, the least-transfer
     assignment of the 31 nodes per candidate, and the exact ratio objective."""
@@ -70,7 +161,6 @@ def bench_replan(args, note, B, synth):
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
             B.replan(rp, stream=stream)
-            note("warm-up step %d done" % i)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         search_ms = assign_ms = 0.0
@@ -97,7 +187,7 @@ def bench_replan(args, note, B, synth):
     bounded = {"time_to_best_plan_ms": ms_b, "search_kernels_ms": st_b["search_ms"], "splits_evaluated_in_full": st_b["splits_evaluated"],
                "same_plan_as_exhaustive": bool(plan_b == plan)}
     note("bounded re-planning: %s" % bounded)
-    out = {"metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
+    out = {"metric": METRIC,
            "value": st["splits_scored"] / (ms * 1e-3), "unit": "plans/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
            "dtype": "int32", "data": "synthetic",
@@ -108,7 +198,7 @@ def bench_replan(args, note, B, synth):
            "bounded_search": bounded, "best": plan,
            "roofline": {"bound": "alu", "kernel": "split search (all pipeline lengths)", "achieved": achieved,
                         "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
-                        "algorithmic_ops_per_launch": st["algorithmic_ops"]}}
+                        "kernel_ms": search_ms, "algorithmic_ops_per_launch": st["algorithmic_ops"]}}
     if not args.no_cpu_baseline:
         from oracle import oracle as O
         # the oracle's exhaustive split of the shortest pipeline length of the candidates (a bounded sample)
@@ -118,11 +208,15 @@ def bench_replan(args, note, B, synth):
         t = time.perf_counter() - t0
         n_splits = O.binom(rp["L"] - 1, n - 1)
         out["cpu_baseline"] = {"value": n_splits / t, "unit": "plans/s", "cores": 1, "kind": "oracle",
-                               "sample": "oracle best split over all %d splits into %d stages, %d micro-batches (%.1f s)" % (n_splits, n, M, t)}
-    print(json.dumps(out))
+                               "host_cores_available": os.cpu_count(),
+                               "sample": "oracle best split over all %d splits into %d stages, %d micro-batches (%.1f s, one thread)" % (n_splits, n, M, t)}
+    return out
 
 
-def bench_score(args, note, B, synth):
+# ---------------------------------------------------------------------------------------------------------
+# cost store
+# ---------------------------------------------------------------------------------------------------------
+def bench_score(args, B, synth):
     """A step = chm_score_plans over three windows of 2^27 consecutive plan indices of config 2, one inside
     every strategy's index range: the cost of every plan index is stored (8 bytes per plan), so this
     is the one part of the path that is bound by HBM writes."""
@@ -161,21 +255,49 @@ def bench_score(args, note, B, synth):
     store_bound = [k for k, f in enumerate(g.families) if f["n_reroute"] > 1]
     dom = store_bound[0] if store_bound else max(range(len(ms)), key=lambda k: ms[k])
     gbs = [8.0 * c / (m * 1e-3) / 1e9 for c, m in zip(counts, ms)]
-    out_json = {"metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
-                "value": total / (wall / args.steps), "unit": "plans/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-                "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-                "dtype": "int32", "data": "synthetic",
-                "config": {"workload": "score2: chm_score_plans over 2^27 consecutive plan indices inside each strategy of config 2",
-                           "plan_indices_per_step": total, "windows": [{"strategy": f["strategy"], "first": x, "count": c}
-                                                                      for f, x, c in zip(g.families, firsts, counts)]},
-                "ms_per_strategy": ms, "store_gb_per_s_per_strategy": gbs,
-                "roofline": {"bound": "hbm", "kernel": "cost store, strategy %d" % g.families[dom]["strategy"], "achieved": gbs[dom],
-                             "peak": 8000.0, "unit": "GB/s", "frac": gbs[dom] / 8000.0, "traffic": None,
-                             "algorithmic_bytes_per_launch": 8.0 * counts[dom]}}
-    print(json.dumps(out_json))
+    g.close()
+    return {"metric": METRIC,
+            "value": total / (wall / args.steps), "unit": "plans/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "int32", "data": "synthetic",
+            "config": {"workload": "score2: chm_score_plans over 2^27 consecutive plan indices inside each strategy of config 2",
+                       "plan_indices_per_step": total, "windows": [{"strategy": f["strategy"], "first": x, "count": c}
+                                                                  for f, x, c in zip(g.families, firsts, counts)]},
+            "ms_per_strategy": ms, "store_gb_per_s_per_strategy": gbs,
+            "roofline": {"bound": "hbm", "kernel": "cost store, strategy %d" % g.families[dom]["strategy"], "achieved": gbs[dom],
+                         "peak": 8000.0, "unit": "GB/s", "frac": gbs[dom] / 8000.0, "traffic": None, "kernel_ms": ms[dom],
+                         "algorithmic_bytes_per_launch": 8.0 * counts[dom]}}
 
 
-def bench_lists(args, note, B, synth):
+# ---------------------------------------------------------------------------------------------------------
+# explicit lists (config 4)
+# ---------------------------------------------------------------------------------------------------------
+def random_partitions_device(synth, seed, stream, n, L, k):
+    """synth.random_partitions computed on the GPU with torch (same generator, same values): n rows of k distinct
+    cut positions of 1..L-1, ascending, as a uint8 CUDA tensor.  The 64-bit mix runs in wrapping int64 arithmetic;
+    the logical right shifts are masked and the keys are compared as unsigned (sign bit flipped)."""
+    import torch
+
+    def c(v):                                    # a 64-bit constant as a (wrapped) int64
+        v &= (1 << 64) - 1
+        return v - (1 << 64) if v >= (1 << 63) else v
+
+    def shr(z, b):                               # logical shift right of the 64-bit pattern
+        return (z >> b) & ((1 << (64 - b)) - 1)
+
+    m = n * (L - 1)
+    i = torch.arange(1, m + 1, dtype=torch.int64, device="cuda")
+    base = c((seed & ((1 << 64) - 1)) * 0x9E3779B97F4A7C15 + (stream & ((1 << 64) - 1)) * 0xD1B54A32D192ED03)
+    z = i * c(0x8CB92BA72F3D8DD7) + base
+    z = (z ^ shr(z, 30)) * c(0xBF58476D1CE4E5B9)
+    z = (z ^ shr(z, 27)) * c(0x94D049BB133111EB)
+    z = z ^ shr(z, 31)
+    keys = (z ^ c(1 << 63)).view(n, L - 1)       # unsigned order as signed order
+    order = torch.argsort(keys, dim=1, stable=True)[:, :k]
+    return (torch.sort(order, dim=1).values + 1).to(torch.uint8)
+
+
+def bench_lists(args, B, synth):
     """config 4: 2^24 seeded random partitions per strategy (L=96, PP=16, DP=2, M=64, one failure, cap chosen
     for about 30 % infeasible plans).  A step = one chm_search_cuts per strategy over its list of cut
     positions, with the cost of every entry stored."""
@@ -189,10 +311,12 @@ def bench_lists(args, note, B, synth):
         k = f["stages"] - 1
         d_cuts = torch.empty((n, k), dtype=torch.uint8, device="cuda")
         for c0 in range(0, n, chunk):
-            cuts = synth.random_partitions(synth.BASE_SEED + 4, 1000 * f["strategy"] + c0 // chunk, chunk, sc["L"], k)
-            d_cuts[c0:c0 + chunk] = torch.from_numpy(cuts).cuda()
+            d_cuts[c0:c0 + chunk] = random_partitions_device(synth, synth.BASE_SEED + 4, 1000 * f["strategy"] + c0 // chunk, chunk, sc["L"], k)
+        # the generator on the device gives the very lists of the seeded host generator (checked on a few rows)
+        check = synth.random_partitions(synth.BASE_SEED + 4, 1000 * f["strategy"], 512, sc["L"], k)
+        assert (d_cuts[:512].cpu().numpy() == check).all(), "device and host list generators differ"
         lists[f["strategy"]] = d_cuts
-        note("strategy %d: %d partitions ready" % (f["strategy"], n))
+        note("config4 strategy %d: %d partitions ready" % (f["strategy"], n))
     costs = torch.empty(n, dtype=torch.int64, device="cuda")
     stream = torch.cuda.Stream()
     g.set_timing(True)
@@ -247,19 +371,47 @@ def bench_lists(args, note, B, synth):
     dom = int(np.argmax(fam_ms))
     achieved = ops[dom] / (fam_ms[dom] * 1e-3) / 1e12
     evals = sum(n * (sum(r for _, r in g.reroute_shape()) if f["strategy"] == 2 else 1) for f in g.families)
-    print(json.dumps({"metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
-                      "value": evals / (ms * 1e-3), "unit": "plans/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-                      "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
-                      "data": "synthetic",
-                      "config": {"workload": "config4: L=96 PP=16 DP=2 M=64, 1 failed node, 2^24 random partitions per strategy "
-                                             "(explicit lists), cap %d MiB" % sc["mem_cap_mib"],
-                                 "partitions_per_strategy": n, "plans_scored_per_step": evals, "failed_nodes": sc["failed_nodes"]},
-                      "kernel_ms_per_strategy": [float(x) for x in fam_ms], "bounded_search": bounded,
-                      "feasible_partitions_per_strategy": [float(x) for x in feasible],
-                      "roofline": {"bound": "alu", "kernel": "list search, strategy %d" % dom, "achieved": achieved,
-                                   "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
-                                   "algorithmic_ops_per_launch": float(ops[dom])}}))
+    out = {"metric": METRIC,
+           "value": evals / (ms * 1e-3), "unit": "plans/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+           "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32",
+           "data": "synthetic",
+           "config": {"workload": "config4: L=96 PP=16 DP=2 M=64, 1 failed node, 2^24 random partitions per strategy "
+                                  "(explicit lists), cap %d MiB" % sc["mem_cap_mib"],
+                      "partitions_per_strategy": n, "plans_scored_per_step": evals, "failed_nodes": sc["failed_nodes"]},
+           "time_to_best_plan_ms": ms, "partition_evals_per_s": 3 * n / (ms * 1e-3),
+           "kernel_ms_per_strategy": [float(x) for x in fam_ms], "bounded_search": bounded,
+           "feasible_partitions_per_strategy": [float(x) for x in feasible],
+           "roofline": {"bound": "alu", "kernel": "list search, strategy %d" % dom, "achieved": achieved,
+                        "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
+                        "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": float(ops[dom])}}
+    if not args.no_cpu_baseline:
+        # the oracle scoring the first entries of every list, on all cores
+        from concurrent.futures import ThreadPoolExecutor
+        from oracle import oracle as O
+        cores = host_cores()
+        per = 2000
+        t_all, n_all = 0.0, 0
+        for f in g.families:
+            if f["n_reroute"] != 1:
+                continue
+            ranks = O.partition_rank_batch(lists[f["strategy"]][:per * cores].cpu().numpy())
 
+            def work(i, f=f, ranks=ranks):
+                o = O.Scenario(sc)
+                o.score_ranks(f["strategy"], ranks[i * per:(i + 1) * per])
+                o.close()
+
+            t0 = time.perf_counter()
+            with ThreadPoolExecutor(max_workers=cores) as pool:
+                list(pool.map(work, range(cores)))
+            t_all += time.perf_counter() - t0
+            n_all += per * cores
+        out["cpu_baseline"] = {"value": n_all / t_all, "unit": "plans/s", "cores": cores, "kind": "oracle", "extrapolated": False,
+                               "per_core_value": n_all / t_all / cores, "host_cores_available": os.cpu_count(),
+                               "sample": "oracle cost of the first %d entries of every list, %d independent single-threaded workers (%.1f s)"
+                                         % (per * cores, cores, t_all)}
+    g.close()
+    return out
 
 
 def threaded_sweep(B, handles, plans, n_threads=4, reps=3):
@@ -291,66 +443,31 @@ def threaded_sweep(B, handles, plans, n_threads=4, reps=3):
     return float(np.median(times)), same
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=10)
-    ap.add_argument("--warmup", type=int, default=2)
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=20.0)
-    ap.add_argument("--ttb-runs", type=int, default=10)
-    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5", "replan32", "score2"],
-                    help="config2 (the 32-card shape) is the benchmark; the others are for profiling; replan32 times "
-                         "chm_replan (search over DP/PP degrees) for the 31 nodes that survive in config2")
-    ap.add_argument("--transfer-assign", type=int, default=0, choices=[0, 1],
-                    help="1: the re-partition strategy counts the weights to fetch under the least-transfer "
-                         "assignment of survivors to new stages (default 0: survivors in stage order)")
-    ap.add_argument("--plan-cache", default=None,
-                    help="write the best plan of every scenario of the workload to this file, one JSON object per "
-                         "line (the cache of pre-computed plans the Planner keeps for possible failures)")
-    ap.add_argument("--filter-compaction", type=int, default=-1, choices=[-1, 0, 1],
-                    help="chm_set_filter_compaction mode of the search workloads: -1 chosen by the library per strategy, 0 off, 1 on")
-    ap.add_argument("--copy-calibration", action="store_true",
-                    help="also run one plain 1 GiB device copy, the known-size reference for scaling the "
-                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py measures one GPU: the plan search runs on a single MI355X and nothing here shards "
-              "across devices; run with --gpus 1", file=sys.stderr)
-        sys.exit(2)
+# ---------------------------------------------------------------------------------------------------------
+# exhaustive search over whole plan spaces (configs 1, 2, 3, 5)
+# ---------------------------------------------------------------------------------------------------------
+SEARCH_WORKLOADS = {
+    "config1": ("config1: L=32 PP=4 DP=2 M=8, 1 failed node", lambda synth: [synth.config1()]),
+    "config2": ("config2: L=48 PP=8 DP=4 M=16, 1 failed node", lambda synth: [synth.config2()]),
+    "config3": ("config3: L=40 PP=4 DP=8 M=32, 2 failed nodes, Q16 speed factors, reroute cap 16", lambda synth: [synth.config3()]),
+    "config5": ("config5: L=40 PP=8 DP=4 M=16, all 32 single and 496 double node failures",
+                lambda synth: [synth.config5(fs) for fs in synth.config5_failure_sets()]),
+}
 
-    def note(msg):
-        print("[bench] " + msg, file=sys.stderr, flush=True)
 
+def bench_search(args, B, synth, name):
     import numpy as np
     import torch
-    from paper_2508_21613_amd import binding as B
-    from paper_2508_21613_amd import synth
-
-    assert torch.cuda.is_available(), "bench.py needs the MI355X"
-    torch.cuda.set_device(0)
-    if args.workload == "replan32":
-        return bench_replan(args, note, B, synth)
-    if args.workload == "score2":
-        return bench_score(args, note, B, synth)
-    if args.workload == "config4":
-        return bench_lists(args, note, B, synth)
-    workloads = {
-        "config1": ("config1: L=32 PP=4 DP=2 M=8, 1 failed node", lambda: [synth.config1()]),
-        "config2": ("config2: L=48 PP=8 DP=4 M=16, 1 failed node", lambda: [synth.config2()]),
-        "config3": ("config3: L=40 PP=4 DP=8 M=32, 2 failed nodes, Q16 speed factors, reroute cap 16", lambda: [synth.config3()]),
-        "config5": ("config5: L=40 PP=8 DP=4 M=16, all 32 single and 496 double node failures",
-                    lambda: [synth.config5(fs) for fs in synth.config5_failure_sets()]),
-    }
-    label, make = workloads[args.workload]
-    scenarios = [dict(sc, transfer_assign=args.transfer_assign) for sc in make()]
+    label, make = SEARCH_WORKLOADS[name]
+    scenarios = [dict(sc, transfer_assign=args.transfer_assign) for sc in make(synth)]
     if args.transfer_assign:
         label += ", least-transfer assignment"
     t0 = time.perf_counter()
     handles = [B.Scenario(sc) for sc in scenarios]
     load_ms = (time.perf_counter() - t0) * 1e3
-    note("%d scenario(s) loaded in %.1f ms" % (len(handles), load_ms))
+    note("%s: %d scenario(s) loaded in %.1f ms" % (name, len(handles), load_ms))
     stream = torch.cuda.Stream()
+    many = len(handles) > 1
 
     def family_work(g, sc):
         shape = g.reroute_shape()
@@ -372,38 +489,44 @@ def main():
     work = [family_work(g, sc) for g, sc in zip(handles, scenarios)]
     fit_share = [g.set_filter_compaction(args.filter_compaction) for g in handles][0]
 
+    def one_step():
+        """one search of every scenario: a single call for one scenario, one batched call for many"""
+        if many:
+            return B.search_best_batch(handles, 7, stream=stream)
+        return [handles[0].search_best(7, stream=stream)]
+
     if args.copy_calibration:
         copy_calibration()
     with torch.cuda.stream(stream):
         for i in range(args.warmup):
-            for g in handles:
-                g.search_best(7, stream=stream)
-            note("warm-up step %d done" % i)
+            one_step()
+        note("%s: warm-up done" % name)
         for g in handles:
             g.set_timing(True)
         fam_ms = np.zeros(3)
         stream.synchronize()
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        plans = [None] * len(handles)
         for _ in range(args.steps):
-            for i, g in enumerate(handles):
-                rc, best = g.search_best(7, stream=stream)
-                plans[i] = (rc, best)
+            plans = one_step()
+            for g in handles:
                 fam_ms += np.array(g.get_timing()["family_ms"])
         stream.synchronize()
         torch.cuda.synchronize()
         wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
     fam_ms /= args.steps
-    if args.plan_cache:
-        with open(args.plan_cache, "w") as fh:
+    note("%s: timed %d steps: %.3f ms per step, kernel ms per strategy %s" % (name, args.steps, ms_per_step, fam_ms))
+    cache_file = args.plan_cache
+    if cache_file is None and many and os.path.isdir(os.path.join(ROOT, "gpurun_out")):
+        cache_file = os.path.join(ROOT, "gpurun_out", "plan_cache_%s.jsonl" % name)
+    if cache_file:
+        with open(cache_file, "w") as fh:
             for sc_i, (rc_i, best_i) in zip(scenarios, plans):
                 fh.write(json.dumps({"failed_nodes": sc_i["failed_nodes"], "rc": rc_i, "index": best_i["index"], "cost": best_i["cost"],
                                      "strategy": best_i["strategy"], "cuts": best_i["cuts"],
                                      "reroute": best_i["reroute"] if best_i["strategy"] == 2 else None}) + "\n")
-        note("best plan of %d scenario(s) written to %s" % (len(plans), args.plan_cache))
-    note("timed %d steps: %.3f ms per step, kernel ms per strategy %s" % (args.steps, ms_per_step, fam_ms))
+        note("best plan of %d scenario(s) written to %s" % (len(plans), cache_file))
 
     # work done per step, from the library's own counters of the last search on every handle
     evaluations = np.zeros(3)
@@ -418,8 +541,18 @@ def main():
         for f in fams:
             ops[f["strategy"]] += algorithmic_ops(f, tm["feasible"][f["strategy"]])[0]
             n_part_total += f["n_part"]
-            cells += f["n_part"] * sum(2 * n * m for n, m in f["classes"])
+            # recurrence cells that run: the partitions that pass the memory filter, every pipeline class
+            cells += tm["feasible"][f["strategy"]] * sum(2 * n * m for n, m in f["classes"])
     n_plans = float(evaluations.sum())
+
+    # the per-call loop (one wait per scenario) beside the batched call
+    per_call_ms = None
+    if many and args.ttb_runs:
+        with torch.cuda.stream(stream):
+            t0 = time.perf_counter()
+            for g in handles:
+                g.search_best(7, stream=stream)
+            per_call_ms = (time.perf_counter() - t0) * 1e3
 
     # time-to-best-plan: load + search on a fresh handle, median over --ttb-runs (first scenario)
     ttb = []
@@ -430,14 +563,14 @@ def main():
         ttb.append((time.perf_counter() - t0) * 1e3)
         g2.close()
     ttb_ms = float(np.median(ttb)) if ttb else None
-    note("time to best plan (load + search): %s ms" % ttb_ms)
+    note("%s: time to best plan (load + search): %s ms" % (name, ttb_ms))
 
     # many scenarios: the host side of a call (launches, one synchronisation) hides behind other threads' kernels
     threaded_exhaustive = None
-    if args.ttb_runs and len(handles) >= 8:
+    if args.ttb_runs and many and args.threads:
         ms_t, same_t = threaded_sweep(B, handles, plans, reps=2)
         threaded_exhaustive = {"search_ms_all_scenarios_4_threads": ms_t, "same_plans": bool(same_t)}
-        note("exhaustive search from four host threads: %s" % threaded_exhaustive)
+        note("%s: exhaustive search from four host threads: %s" % (name, threaded_exhaustive))
 
     # the same with chm_set_bounded_search: same plan, most partitions skipped by a lower bound of their cost.
     # Reported beside the exhaustive figures, never inside `value` (which counts plans that were scored).
@@ -455,16 +588,14 @@ def main():
             g2.close()
             same = same and (rc_b, best_b["index"], best_b["cost"]) == (plans[0][0], plans[0][1]["index"], plans[0][1]["cost"])
             t0 = time.perf_counter()
-            swept = [g.search_best(7, stream=stream)[1] for g in handles]
+            swept = [b for _, b in one_step()]
             search_b.append((time.perf_counter() - t0) * 1e3)
             same = same and all(a["index"] == b[1]["index"] and a["cost"] == b[1]["cost"] for a, b in zip(swept, plans))
         ev = np.zeros(3)
         for g in handles:
             ev += np.array(g.get_timing()["evaluated"], dtype=float)
-        # a bounded search is bound by launch and synchronisation latency, not by the GPU: independent scenarios
-        # searched from four host threads (a stream each) overlap
         threaded_ms = None
-        if len(handles) >= 8:
+        if many and args.threads:
             threaded_ms, same_t = threaded_sweep(B, handles, plans)
             same = same and same_t
         for g in handles:
@@ -472,80 +603,152 @@ def main():
         bounded = {"time_to_best_plan_ms": float(np.median(ttb_b)), "search_ms_all_scenarios": float(np.median(search_b)),
                    "search_ms_all_scenarios_4_threads": threaded_ms,
                    "partitions_evaluated_in_full": [float(x) for x in ev], "same_plans_as_exhaustive": bool(same)}
-        note("bounded search: %s" % bounded)
+        note("%s: bounded search: %s" % (name, bounded))
 
     # roofline of the dominant kernel
     dom = int(np.argmax(fam_ms))
     achieved = ops[dom] / (fam_ms[dom] * 1e-3) / 1e12
     fam0 = [f for f in work[0] if f["strategy"] == dom]
     _, ops_light, ops_heavy = algorithmic_ops(fam0[0], 0) if fam0 else (0, 0, 0)
-
-    probes = {name: B.valu_probe(kind, 3000, stream=stream) / 1e12
-              for kind, name in ((0, "v_add_u32"), (1, "v_max_i32"), (2, "max_add_cell_chain"))}
-    note("measured VALU rates (T lane-ops/s): %s" % probes)
+    probes = {pname: B.valu_probe(kind, 3000, stream=stream) / 1e12
+              for kind, pname in ((0, "v_add_u32"), (1, "v_max_i32"), (2, "max_add_cell_chain"))}
+    note("%s: measured VALU rates (T lane-ops/s): %s" % (name, probes))
     sc = scenarios[0]
+    best = plans[0][1]
+    roofline = {"bound": "alu", "kernel": "search, strategy %d" % dom, "achieved": achieved,
+                "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS,
+                "frac_is": "algorithmic int32 lane operations per second (the method's max/add/compare count, whatever the kernel "
+                           "executes) over the nominal VALU peak of 256 CUs x 4 SIMDs x 32 lanes x 2.4 GHz; this is the figure "
+                           "the 50 % target is read against",
+                "measured_valu_rates_tops": probes,
+                "algorithmic_ops_over_measured_naive_cell_rate": achieved / probes["max_add_cell_chain"],
+                "algorithmic_ops_over_measured_naive_cell_rate_is": "the same numerator over the measured rate of a plain dependent "
+                    "v_max_i32 + v_add_u32 chain; above 1 because the kernel executes fewer instructions than the algorithmic count "
+                    "(one v_max serves a forward and a backward cell, the forward add folds into the frame, v_max3/v_min3 fold two operations)",
+                "traffic": CONFIG2_TRAFFIC_BYTES[dom] if name == "config2" and not args.transfer_assign else None,
+                "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": float(ops[dom] / len(handles)),
+                "feasible_partitions": float(feasible[dom]),
+                "algorithmic_ops_per_feasible_partition": ops_light + ops_heavy,
+                "algorithmic_ops_per_infeasible_partition": ops_light}
+    if name == "config2" and not args.transfer_assign:
+        per_part = CONFIG2_EXECUTED_LANE_INSTR_PER_PARTITION[dom]
+        executed = per_part * fam0[0]["n_part"] / (fam_ms[dom] * 1e-3) / 1e12
+        roofline["executed_lane_instr_per_partition"] = per_part
+        roofline["executed_valu_rate_tops"] = executed
+        roofline["executed_valu_rate_over_measured_v_max_rate"] = executed / probes["v_max_i32"]
+        roofline["executed_valu_rate_is"] = ("SQ_INSTS_VALU x 64 / partitions of the committed rocprofv3 profile x partitions / kernel time "
+                                             "of this run, against the measured issue rate of v_max_i32 (the slower of the two "
+                                             "instruction classes the kernel mixes)")
     out = {
-        "metric": "candidate plans scored/sec + time-to-best-plan per failure event (1 GPU)",
+        "metric": METRIC,
         "value": n_plans / (ms_per_step * 1e-3),
         "unit": "plans/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int32", "data": "synthetic",
-        "config": {"workload": label + ", exhaustive search over all strategies",
+        "config": {"workload": label + ", exhaustive search over all strategies" + (", one batched call for all scenarios" if many else ""),
                    "scenarios": len(handles), "plans_scored_per_step": n_plans, "plan_indices": plan_indices,
-                   "partitions": n_part_total, "failed_nodes": sc["failed_nodes"] if len(handles) == 1 else "all",
+                   "partitions": n_part_total, "failed_nodes": sc["failed_nodes"] if not many else "all",
                    "families": [{k: f[k] for k in ("strategy", "stages", "n_part", "n_reroute")} for f in work[0]]},
         "time_to_best_plan_ms": ttb_ms, "load_ms": load_ms,
+        "load_ms_is": "first handle(s) of the process: includes HIP initialisation and loading the code object; "
+                      "time_to_best_plan_ms is the warm load + search",
         "time_to_best_plan_bounded_ms": bounded["time_to_best_plan_ms"] if bounded else None,
         "bounded_search": bounded,
         "exhaustive_search_4_threads": threaded_exhaustive,
+        "per_call_loop_ms": per_call_ms,
+        "plan_cache_file": os.path.relpath(cache_file, ROOT) if cache_file else None,
+        "host_ms_outside_kernels": ms_per_step - float(fam_ms.sum()),
         "partition_evals_per_s": n_part_total / (ms_per_step * 1e-3),
         "recurrence_cells_per_s": cells / (ms_per_step * 1e-3),
         "kernel_ms_per_strategy": [float(x) for x in fam_ms],
         "best": {"index": best["index"], "cost": best["cost"], "strategy": best["strategy"], "cuts": best["cuts"]},
-        "roofline": {"bound": "alu", "kernel": "search, strategy %d" % dom, "achieved": achieved,
-                     "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS,
-                     "measured_valu_rates_tops": probes,
-                     "frac_of_measured_cell_rate": achieved / probes["max_add_cell_chain"],
-                     "traffic": CONFIG2_TRAFFIC_BYTES[dom] if args.workload == "config2" and not args.transfer_assign else None,
-                     "kernel_ms": float(fam_ms[dom]), "algorithmic_ops_per_launch": float(ops[dom]),
-                     "feasible_partitions": float(feasible[dom]),
-                     "algorithmic_ops_per_feasible_partition": ops_light + ops_heavy,
-                     "algorithmic_ops_per_infeasible_partition": ops_light},
+        "roofline": roofline,
         "feasible_partitions_per_strategy": [float(x) for x in feasible],
         "filter_compaction": {"mode": args.filter_compaction, "sampled_fit_share": fit_share},
     }
-
     if not args.no_cpu_baseline:
-        from oracle import oracle as O
-        o = O.Scenario(scenarios[0])
-        spent = 0.0
-        per_family = []
-        for f in o.families:               # the same three strategies, a slice from the middle of each rank space
-            share = max(0.1, (f["n_part"] * f["n_reroute"]) / o.n_plans * 0.8)
-            budget = args.cpu_seconds * share
-            mid = f["n_part"] // 2
-            n0 = min(500, f["n_part"] - mid)
+        out["cpu_baseline"] = cpu_baseline_record(scenarios[0], args.cpu_seconds, name + (" (first scenario)" if many else ""))
+    for g in handles:
+        g.close()
+    return out
+
+
+def summary(rec):
+    """what the `workloads` block keeps of a workload's record"""
+    keep = ("value", "unit", "steps", "ms_per_step", "time_to_best_plan_ms", "time_to_best_plan_bounded_ms", "partition_evals_per_s",
+            "recurrence_cells_per_s", "kernel_ms_per_strategy", "ms_per_strategy", "search_kernels_ms", "per_call_loop_ms",
+            "plan_cache_file", "host_ms_outside_kernels", "cpu_baseline")
+    out = {k: rec[k] for k in keep if k in rec and rec[k] is not None}
+    out["workload"] = rec["config"]["workload"]
+    r = rec["roofline"]
+    out["roofline"] = {k: r[k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "kernel_ms") if k in r}
+    if rec.get("bounded_search"):
+        b = rec["bounded_search"]
+        out["bounded_search"] = {k: b[k] for k in ("search_ms_all_scenarios", "bounded_ms_per_step", "time_to_best_plan_ms",
+                                                   "same_plans_as_exhaustive", "same_winners", "same_plan_as_exhaustive") if k in b}
+    return out
+
+
+def run_workload(name, args, B, synth):
+    if name == "replan32":
+        return bench_replan(args, B, synth)
+    if name == "score2":
+        return bench_score(args, B, synth)
+    if name == "config4":
+        return bench_lists(args, B, synth)
+    return bench_search(args, B, synth, name)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--ttb-runs", type=int, default=10)
+    ap.add_argument("--workload", default="config2", choices=["config1", "config2", "config3", "config4", "config5", "replan32", "score2"],
+                    help="config2 (the 32-card shape) is the benchmark; the others are reported in its `workloads` block and can be "
+                         "run alone for profiling; replan32 times chm_replan (search over DP/PP degrees) for the 31 nodes that "
+                         "survive in config2")
+    ap.add_argument("--no-workloads", action="store_true", help="config2 only, without the `workloads` block")
+    ap.add_argument("--threads", action="store_true", help="many scenarios: also time four host threads with a stream each")
+    ap.add_argument("--transfer-assign", type=int, default=0, choices=[0, 1],
+                    help="1: the re-partition strategy counts the weights to fetch under the least-transfer "
+                         "assignment of survivors to new stages (default 0: survivors in stage order)")
+    ap.add_argument("--plan-cache", default=None,
+                    help="write the best plan of every scenario of the workload to this file, one JSON object per "
+                         "line (the cache of pre-computed plans the Planner keeps for possible failures)")
+    ap.add_argument("--filter-compaction", type=int, default=-1, choices=[-1, 0, 1],
+                    help="chm_set_filter_compaction mode of the search workloads: -1 chosen by the library per strategy, 0 off, 1 on")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size reference for scaling the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: the plan search runs on a single MI355X and nothing here shards "
+              "across devices; run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2508_21613_amd import binding as B
+    from paper_2508_21613_amd import synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    out = run_workload(args.workload, args, B, synth)
+    if args.workload == "config2" and not args.no_workloads:
+        # the other configurations at a few steps each, with a short oracle sample
+        sub = argparse.Namespace(**vars(args))
+        sub.steps, sub.warmup, sub.ttb_runs, sub.cpu_seconds, sub.copy_calibration, sub.plan_cache = 3, 1, 3, 3.0, False, None
+        block = {}
+        for name in ("config1", "config3", "config4", "config5", "score2", "replan32"):
             t0 = time.perf_counter()
-            o.search_range(f["strategy"], mid, n0)
-            t_cal = max(time.perf_counter() - t0, 1e-4)
-            n = int(max(n0, min(f["n_part"] - mid, budget * n0 / t_cal)))
-            t0 = time.perf_counter()
-            _, _, ev = o.search_range(f["strategy"], mid, n)
-            t = time.perf_counter() - t0
-            per_family.append((f["strategy"], n, ev, t))
-            note("oracle: strategy %d, %d partitions in %.2f s" % (f["strategy"], n, t))
-            spent += t + t_cal
-        # whole-job rate of the oracle: time it would need for the full space at these per-family rates
-        full_s = sum(t * (o.family(s)["n_part"] / n) for s, n, ev, t in per_family)
-        o_plans = sum(f["n_part"] * (sum(r for _, r in handles[0].reroute_shape()) if f["strategy"] == 2 and handles[0].reroute_shape() else 1)
-                      for f in o.families)
-        out["cpu_baseline"] = {"value": o_plans / full_s, "unit": "plans/s", "cores": 1, "kind": "oracle",
-                               "sample": "oracle search over %s partitions from the middle of the rank space of strategies %s (%.1f s of CPU work), "
-                                         "extrapolated per strategy to the full space" %
-                                         ([n for _, n, _, _ in per_family], [s for s, _, _, _ in per_family], spent),
-                               "full_space_seconds_estimate": full_s}
+            block[name] = summary(run_workload(name, sub, B, synth))
+            note("workload %s done in %.1f s" % (name, time.perf_counter() - t0))
+        out["workloads"] = block
     print(json.dumps(out))
 
 
