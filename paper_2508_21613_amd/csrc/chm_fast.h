@@ -52,6 +52,12 @@ struct FastTables {
   // dwords: [0..5] the shared entries, [6] = lo | (sum of the last two entries << 16), [7] = length
   uint32_t run_off[DEV_MAX_AFF];  // offset (in uint32) of stage a's runs in runs[]
   uint32_t run_count[DEV_MAX_AFF];
+  // and as groups (three or more peers, at most 8 or 16 micro-batches per peer: see k_sweep_groups): all vectors that
+  // share their first P-3 entries.  A group is 8 dwords: [0..4] the shared entries, [5] = first value of the entry
+  // before the last two, [6] = how many consecutive values it takes, [7] = what the last three entries add up to
+  uint32_t grp_off[DEV_MAX_AFF];  // offset (in uint32) of stage a's groups in runs[]
+  uint32_t grp_count[DEV_MAX_AFF];
+  uint32_t grp_cap[DEV_MAX_AFF];  // 0: stage a has no group table; else the entry limit (8 or 16) its sweep is compiled for
   // small uncapped reroute spaces have a sweep unrolled at compile time (see sweep_products):
   // peers * 256 + orphaned micro-batches when such a sweep exists for stage a, else 0
   uint32_t unrolled_shape[DEV_MAX_AFF];
@@ -81,7 +87,9 @@ struct FastState {
   uint32_t *d_weights = nullptr;            // [partition][affected stage][8] peer stage times
   uint32_t *d_pen = nullptr;                // [partition][4] best penalty per affected stage
   uint64_t *d_rowkey = nullptr;             // [4] (penalty << 32 | row) of the winning partition
-  uint32_t scratch_parts = 0;               // partitions d_base, d_weights and d_pen have room for
+  uint32_t *d_fit_list = nullptr;           // [partition] the partitions of the pass that fit in memory, in no particular order
+  uint32_t *d_fit_count = nullptr;          // how many of them
+  uint32_t scratch_parts = 0;               // partitions d_base, d_weights, d_pen and d_fit_list have room for
   // The run and vector tables of a rerouting family whose vectors are swept by kernels of their own (split) are
   // large (tens of MB, milliseconds to enumerate) and a bounded search never reads them: they are built when an
   // exhaustive search, a cost store or the recovery of a winner's vectors first asks for them.

@@ -535,7 +535,7 @@ k_fast_search(FastLaunch a) {
   __syncthreads();
 
   const uint32_t lane_id = blockIdx.x * BLOCK + threadIdx.x;
-  const uint64_t run_first = (uint64_t)lane_id * a.per_lane;             // chunk-local
+  const uint32_t run_first = lane_id * a.per_lane;                       // chunk-local (a chunk holds at most 2^30 partitions)
   const uint32_t run_len = (compact || run_first >= a.s.part_count) ? 0u
                            : (uint32_t)(a.s.part_count - run_first < a.per_lane ? a.s.part_count - run_first : a.per_lane);
   const uint32_t region = blockIdx.x * a.per_lane * BLOCK;               // compact mode: first slot of this workgroup
@@ -558,7 +558,7 @@ k_fast_search(FastLaunch a) {
 
   const int cap = (int)scn->cap;
   uint64_t best_cost = ~0ull;
-  uint64_t best_pos = 0;        // output position (chunk-local partition index or list position) of the lane's best
+  uint32_t best_pos = 0;        // output position (chunk-local partition index or list position) of the lane's best
   uint32_t n_fit = 0;           // wave-uniform count of partitions that pass the memory filter
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -617,7 +617,7 @@ k_fast_search(FastLaunch a) {
 
   for (uint32_t it = 0; it < (wave_dead ? 0u : a.per_lane + (QUEUED ? 1u : 0u)); ++it) {
     bool live = it < run_len;             // this lane has a partition in this round
-    uint64_t pos = run_first + it;        // where its result is reported
+    uint32_t pos = run_first + it;        // where its result is reported
     if (QUEUED) {
       if (it < a.per_lane) {              // uniform; the extra round only drains the ring
         // ---- filter the lane's next partition and append it to the ring if it fits
@@ -887,7 +887,7 @@ k_fast_search(FastLaunch a) {
       if (!QUEUED && STRAT == 2 && a.base_out != nullptr) {
         // split path: hand the peer stage times of this partition to the sweep kernel
         if (ok) {
-          uint32_t *wout = a.weights_out + (run_first + it) * (DEV_MAX_AFF * 8);
+          uint32_t *wout = a.weights_out + (size_t)(run_first + it) * (DEV_MAX_AFF * 8);
           for (int st = 0; st < scn->n_aff; ++st) {
             const int sa = scn->aff_stage[st];
             int f_st = fs[0], b_st = bs[0];
@@ -949,7 +949,7 @@ k_fast_search(FastLaunch a) {
       if (block_first + i < a.s.part_count) a.s.costs_out[block_first + i] = cost_tile[i];
   }
   uint64_t key = best_cost == ~0ull ? CHM_KEY_NONE
-                                    : ((best_cost << a.s.idx_bits) | best_pos);
+                                    : ((best_cost << a.s.idx_bits) | (uint64_t)best_pos);
   if (!QUEUED && STRAT == 2 && a.base_out != nullptr) key = CHM_KEY_NONE;   // the combine kernel takes the argmin
   key = wave_min(key);
   if (lane == 0) { wave_keys[wave] = key; wave_fit[wave] = n_fit; wave_eval[wave] = n_eval; }
@@ -1196,6 +1196,117 @@ __global__ void __launch_bounds__(BLOCK) k_sweep(const uint32_t *__restrict__ ru
   const uint32_t pen = sweep_runs<P>(as_const(runs) + (size_t)first * 8, n, w);
   if (live && n) atomicMin(&pen_best[(size_t)part * DEV_MAX_AFF + a], pen);
 }
+
+// The partitions of a pass that fit in memory (base cost known), gathered into a list so that the sweep kernels
+// keep every lane busy; the order within the list is of no consequence (results go back by partition).
+__global__ void __launch_bounds__(BLOCK) k_compact_fit(const uint64_t *__restrict__ base, uint32_t part_count,
+                                                       uint32_t *__restrict__ list, uint32_t *__restrict__ count) {
+  const uint32_t part = blockIdx.x * BLOCK + threadIdx.x;
+  const bool fit = part < part_count && base[part < part_count ? part : 0] != ~0ull;
+  const uint64_t mask = __builtin_amdgcn_ballot_w64(fit);
+  if (mask == 0) return;
+  const int lane = threadIdx.x & 63;
+  uint32_t first = 0;
+  if (lane == 0) first = atomicAdd(count, (uint32_t)__popcll(mask));
+  first = __shfl(first, 0, 64);
+  if (fit) list[first + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = part;
+}
+
+// min over the pairs (a, b) with a + b = REM, 0 <= a, b <= CAP of max(A[a], B[b]): the last two entries of a reroute
+// vector, their products read from register tables at compile-time positions (one v_max_u32 and half a v_min3_u32
+// per vector)
+template <int REM, int CAP>
+__device__ __forceinline__ uint32_t pair_min(const uint32_t (&A)[CAP + 1], const uint32_t (&B)[CAP + 1]) {
+  constexpr int LO = REM > CAP ? REM - CAP : 0, HI = REM < CAP ? REM : CAP;
+  uint32_t m = 0xffffffffu;
+#pragma unroll
+  for (int a = LO; a <= HI; ++a) {
+    const uint32_t z = A[a] > B[REM - a] ? A[a] : B[REM - a];
+    m = m < z ? m : z;
+  }
+  return m;
+}
+
+// Best penalty of one affected stage for the partitions of the fit list (one per lane) over one chunk of groups.
+// Every reroute vector is scored: max over its P products (extra micro-batches x peer stage time).  The vectors
+// of a group share their first P-3 entries (their largest product is taken once per group); the entry before the
+// last two steps through consecutive values (its product is carried by an add); for each of its values the last
+// two entries run over all pairs with the remaining sum, whose products come from two register tables built once
+// per lane (r x peer time, r = 0..CAP).  Consecutive values leave consecutive remaining sums, so the code for
+// all remaining sums is laid out in descending order and a group enters it at its first one.
+#define CHM_PAIR_SUMS(X) X(32) X(31) X(30) X(29) X(28) X(27) X(26) X(25) X(24) X(23) X(22) X(21) X(20) X(19) X(18) X(17) \
+  X(16) X(15) X(14) X(13) X(12) X(11) X(10) X(9) X(8) X(7) X(6) X(5) X(4) X(3) X(2) X(1)
+template <int P, int CAP>
+__global__ void __launch_bounds__(BLOCK) k_sweep_groups(const uint32_t *__restrict__ groups, uint32_t n_groups, uint32_t groups_per_chunk,
+                                                        const uint32_t *__restrict__ fit_list, const uint32_t *__restrict__ fit_count,
+                                                        const uint32_t *__restrict__ weights, uint32_t *__restrict__ pen_best, int a) {
+  static_assert(P >= 3 && P <= 8 && (CAP == 8 || CAP == 16), "three to eight peers, entries up to 8 or 16");
+  constexpr int Q = P - 3;                            // shared entries per group
+  const uint32_t n_fit = *as_const(fit_count);
+  if (blockIdx.x * BLOCK >= n_fit) return;            // uniform: this block has no partition
+  const uint32_t slot = blockIdx.x * BLOCK + threadIdx.x;
+  const bool live = slot < n_fit;
+  const uint32_t part = fit_list[live ? slot : n_fit - 1];    // lanes past the end redo the last partition
+  uint32_t w[P];
+#pragma unroll
+  for (int i = 0; i < P; ++i) w[i] = weights[(size_t)part * (DEV_MAX_AFF * 8) + a * 8 + i];
+  uint32_t A[CAP + 1], B[CAP + 1];
+  A[0] = 0;
+  B[0] = 0;
+#pragma unroll
+  for (int r = 1; r <= CAP; ++r) { A[r] = A[r - 1] + w[P - 2]; B[r] = B[r - 1] + w[P - 1]; }
+  const uint32_t wv = w[P - 3];
+  const uint32_t first = blockIdx.y * groups_per_chunk;
+  const uint32_t n = first >= n_groups ? 0u : (n_groups - first < groups_per_chunk ? n_groups - first : groups_per_chunk);
+  if (n == 0) return;
+  const RowPtr tab = as_const(groups) + (size_t)first * 8;
+  uint32_t best = 0xffffffffu;
+  // the descriptor of the next group is fetched while the current one is swept
+  uint32_t d[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) d[i] = tab[i];
+  for (uint32_t g = 0; g < n; ++g) {
+    uint32_t nx[8];
+    const RowPtr nd = tab + (size_t)(g + 1 < n ? g + 1 : g) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) nx[i] = nd[i];
+    uint32_t pre = 0;
+#pragma unroll
+    for (int i = 0; i < Q; ++i) {
+      const uint32_t v = __umul24(d[i], w[i]);
+      pre = pre > v ? pre : v;
+    }
+    uint32_t pv = __umul24(d[5], wv);                 // product of the stepping entry
+    uint32_t left = d[6];                             // values it still takes
+    const uint32_t rem2 = d[7] - d[5];                // what the last two entries add up to at its first value
+#define CHM_PAIR_CASE(R)                                                                      \
+  case R:                                                                                     \
+    if constexpr (R <= 2 * CAP) {                                                             \
+      const uint32_t m = pair_min<(R <= 2 * CAP ? R : 0), CAP>(A, B);                         \
+      uint32_t pen = pre > pv ? pre : pv;                                                     \
+      pen = pen > m ? pen : m;                                                                \
+      best = best < pen ? best : pen;                                                         \
+      pv += wv;                                                                               \
+      if (--left == 0) break;                                                                 \
+    }                                                                                         \
+    [[fallthrough]];
+    switch (rem2) {
+      CHM_PAIR_SUMS(CHM_PAIR_CASE)
+      case 0: {
+        const uint32_t m = pair_min<0, CAP>(A, B);
+        uint32_t pen = pre > pv ? pre : pv;
+        pen = pen > m ? pen : m;
+        best = best < pen ? best : pen;
+      } break;
+      default: break;
+    }
+#undef CHM_PAIR_CASE
+#pragma unroll
+    for (int i = 0; i < 8; ++i) d[i] = nx[i];
+  }
+  if (live) atomicMin(&pen_best[(size_t)part * DEV_MAX_AFF + a], best);
+}
+#undef CHM_PAIR_SUMS
 
 // The least penalty of one affected stage without looking at the vectors one by one.  A vector r (r_i extra
 // micro-batches on peer i, r_i <= cap, sum = orphans) has penalty max_i r_i * w_i <= v exactly when r_i <=
@@ -1539,8 +1650,12 @@ int launch_by_stages(int sp, const FastLaunch &a, uint32_t blocks, uint32_t tile
       hipLaunchKernelGGL((k_fast_search<SPV, STRAT>), dim3(blocks), dim3(BLOCK), tile_bytes, st, a); \
     return 0;
   switch (sp) {
+#ifdef CHM_TUNING_SUBSET        // (-DCHM_TUNING_SUBSET: only the stage counts of the 32-card shape, for quick rebuilds while tuning)
+    CHM_CASE(7) CHM_CASE(8)
+#else
     CHM_CASE(2) CHM_CASE(3) CHM_CASE(4) CHM_CASE(5) CHM_CASE(6) CHM_CASE(7) CHM_CASE(8)
     CHM_CASE(9) CHM_CASE(10) CHM_CASE(11) CHM_CASE(12) CHM_CASE(13) CHM_CASE(14) CHM_CASE(15) CHM_CASE(16)
+#endif
     default: return 1;
   }
 #undef CHM_CASE
@@ -1553,8 +1668,12 @@ int filter_by_stages(int sp, const ListFilter &a, uint32_t blocks, hipStream_t s
     hipLaunchKernelGGL((k_list_filter<SPV, STRAT>), dim3(blocks), dim3(BLOCK), 0, st, a);      \
     return 0;
   switch (sp) {
+#ifdef CHM_TUNING_SUBSET        // (-DCHM_TUNING_SUBSET: only the stage counts of the 32-card shape, for quick rebuilds while tuning)
+    CHM_CASE(7) CHM_CASE(8)
+#else
     CHM_CASE(2) CHM_CASE(3) CHM_CASE(4) CHM_CASE(5) CHM_CASE(6) CHM_CASE(7) CHM_CASE(8)
     CHM_CASE(9) CHM_CASE(10) CHM_CASE(11) CHM_CASE(12) CHM_CASE(13) CHM_CASE(14) CHM_CASE(15) CHM_CASE(16)
+#endif
     default: return 1;
   }
 #undef CHM_CASE
@@ -1678,6 +1797,64 @@ static bool build_reroute_tables(FastState *f, const DevScenario &h) {
       }
     }
     if (!f->usable[2]) f->split = false;
+    // group tables for the sweep kernel of large reroute spaces (see k_sweep_groups)
+    for (int a = 0; a < h.n_aff && f->usable[2] && f->split; ++a) {
+      t->grp_cap[a] = 0;
+      const int p = h.aff_peers[a], total = h.aff_total[a];
+      const int cap = h.rcap > 0 ? std::min(h.rcap, total) : total;
+      if (p < 3 || (cap != 8 && cap != 16)) continue;
+      int same = -1;
+      for (int b = 0; b < a; ++b)
+        if (h.aff_peers[b] == p && h.aff_total[b] == total && t->grp_cap[b]) same = b;
+      if (same >= 0) { t->grp_off[a] = t->grp_off[same]; t->grp_count[a] = t->grp_count[same]; t->grp_cap[a] = t->grp_cap[same]; continue; }
+      const int q = p - 3;                                 // shared entries per group
+      const size_t at = runs.size();
+      uint64_t vectors = 0;
+      uint32_t n_groups = 0;
+      std::vector<int> pre(q + 1, 0);
+      // odometer over the shared entries in lexicographic order (every entry 0..cap, what is left must fit the last three)
+      int pos = 0, rem = total;
+      bool fresh = true;
+      for (;;) {
+        if (pos == q) {
+          const int lo = std::max(0, rem - 2 * cap), hi = std::min(cap, rem);
+          if (lo <= hi) {
+            uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int i = 0; i < q; ++i) d[i] = (uint32_t)pre[i];
+            d[5] = (uint32_t)lo; d[6] = (uint32_t)(hi - lo + 1); d[7] = (uint32_t)rem;
+            runs.insert(runs.end(), d, d + 8);
+            for (int v = lo; v <= hi; ++v) {
+              const int r2 = rem - v;
+              vectors += (uint64_t)(std::min(cap, r2) - std::max(0, r2 - cap) + 1);
+            }
+            ++n_groups;
+          }
+          --pos;
+          if (pos < 0) break;
+          rem += pre[pos];
+          ++pre[pos];
+          fresh = false;
+          continue;
+        }
+        if (fresh) pre[pos] = 0;
+        if (pre[pos] > std::min(cap, rem)) {
+          --pos;
+          if (pos < 0) break;
+          rem += pre[pos];
+          ++pre[pos];
+          fresh = false;
+          continue;
+        }
+        rem -= pre[pos];
+        ++pos;
+        fresh = true;
+      }
+      if (vectors == h.aff_R[a] && n_groups > 0) {
+        t->grp_off[a] = (uint32_t)at; t->grp_count[a] = n_groups; t->grp_cap[a] = (uint32_t)cap;
+      } else {
+        runs.resize(at);                                   // table and count disagree: the run sweep serves this stage
+      }
+    }
   }
   if (!f->usable[2]) return true;
   if (runs.empty()) runs.assign(8, 0);
@@ -1825,14 +2002,18 @@ namespace {
 // penalties, the peer stage times and the best penalty per affected stage
 bool ensure_scratch(FastState *f, uint64_t parts) {
   const uint32_t need = (uint32_t)std::min<uint64_t>(FAST_SUB, std::max<uint64_t>(parts, 1 << 12));
-  if (f->d_base && f->d_weights && f->d_pen && f->scratch_parts >= need) return true;
+  if (f->d_base && f->d_weights && f->d_pen && f->d_fit_list && f->d_fit_count && f->scratch_parts >= need) return true;
+  if (f->d_fit_count) pool_release(f->d_fit_count);
+  if (f->d_fit_list) pool_release(f->d_fit_list);
   if (f->d_pen) pool_release(f->d_pen);
   if (f->d_weights) pool_release(f->d_weights);
   if (f->d_base) pool_release(f->d_base);
-  f->d_pen = nullptr; f->d_weights = nullptr; f->d_base = nullptr; f->scratch_parts = 0;
+  f->d_fit_count = nullptr; f->d_fit_list = nullptr; f->d_pen = nullptr; f->d_weights = nullptr; f->d_base = nullptr; f->scratch_parts = 0;
   bool ok = pool_take(f->d_base, (size_t)need * sizeof(uint64_t));
   ok = ok && pool_take(f->d_weights, (size_t)need * DEV_MAX_AFF * 8 * sizeof(uint32_t));
   ok = ok && pool_take(f->d_pen, (size_t)need * DEV_MAX_AFF * sizeof(uint32_t));
+  ok = ok && pool_take(f->d_fit_list, (size_t)need * sizeof(uint32_t));
+  ok = ok && pool_take(f->d_fit_count, 64);
   if (ok) f->scratch_parts = need;
   return ok;
 }
@@ -2151,7 +2332,40 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
       hipLaunchKernelGGL(k_least_penalty, dim3(bx), dim3(BLOCK), 0, st, f->d_base, f->d_weights, f->d_pen, sub.part_count, s,
                          h.aff_peers[s], total, h.rcap > 0 ? (uint32_t)h.rcap : total);
     }
+    bool compacted = false;
     for (int s = 0; s < h.n_aff && !f->penalty_by_capacity; ++s) {
+      if (t.grp_cap[s] != 0) {
+        // every lane a partition that fits: the list is built once per pass
+        if (!compacted) {
+          hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, f->d_fit_count, 1u, 0u);
+          hipLaunchKernelGGL(k_compact_fit, dim3(bx), dim3(BLOCK), 0, st, f->d_base, sub.part_count, f->d_fit_list, f->d_fit_count);
+          compacted = true;
+        }
+        const uint32_t n_groups = t.grp_count[s];
+        // about 8192 workgroups in total, chunks of at least 16 groups
+        uint32_t chunks = std::max<uint32_t>(1, std::min<uint32_t>(8192 / bx + 1, n_groups / 16 + 1));
+        chunks = std::min<uint32_t>(chunks, 65535);
+        const uint32_t per_chunk = (n_groups + chunks - 1) / chunks;
+        chunks = (n_groups + per_chunk - 1) / per_chunk;
+        const uint32_t *groups = f->d_runs + t.grp_off[s];
+        const bool cap16 = t.grp_cap[s] == 16;
+        rc = by_peers(h.aff_peers[s], [&](auto tag) {
+          constexpr int P = decltype(tag)::value;
+          if constexpr (P >= 3) {
+            if (cap16)
+              hipLaunchKernelGGL((k_sweep_groups<P, 16>), dim3(bx, chunks), dim3(BLOCK), 0, st, groups, n_groups, per_chunk,
+                                 f->d_fit_list, f->d_fit_count, f->d_weights, f->d_pen, s);
+            else
+              hipLaunchKernelGGL((k_sweep_groups<P, 8>), dim3(bx, chunks), dim3(BLOCK), 0, st, groups, n_groups, per_chunk,
+                                 f->d_fit_list, f->d_fit_count, f->d_weights, f->d_pen, s);
+            return 0;
+          } else {
+            return 1;
+          }
+        });
+        if (rc) return -1;
+        continue;
+      }
       const uint32_t n_runs = t.run_count[s];
       // about 8192 workgroups in total, chunks of at least 64 runs
       uint32_t chunks = std::max<uint32_t>(1, std::min<uint32_t>(8192 / bx + 1, n_runs / 64 + 1));
@@ -2309,6 +2523,9 @@ void fast_release(FastState *f, bool device_idle) {
   if (f->d_cut_list) pool_release(f->d_cut_list, device_idle);
   f->d_cut_count = nullptr; f->d_cut_pos = nullptr; f->d_cut_list = nullptr;
   if (f->d_rowkey) pool_release(f->d_rowkey, device_idle);
+  if (f->d_fit_count) pool_release(f->d_fit_count, device_idle);
+  if (f->d_fit_list) pool_release(f->d_fit_list, device_idle);
+  f->d_fit_count = nullptr; f->d_fit_list = nullptr;
   if (f->d_pen) pool_release(f->d_pen, device_idle);
   if (f->d_weights) pool_release(f->d_weights, device_idle);
   if (f->d_base) pool_release(f->d_base, device_idle);

@@ -890,3 +890,56 @@ def test_independent_handles_on_concurrent_threads(B):
     for th in threads:
         th.join()
     assert not errors, errors[:5]
+
+
+def _reroute_case(seed, DP, M, cap, failed, L=9, PP=3):
+    fwd, bwd, mem = synth.layer_tables(seed, L)
+    return synth.scenario(L, PP, DP, M, fwd, bwd, mem, failed, 130, int(mem.sum() * 1.9 / PP),
+                          speed=synth.speed_factors(seed, DP, PP), reroute_cap=cap)
+
+
+GROUPED = [
+    ("p4_cap16_two_stages", _reroute_case(9101, 5, 32, 16, [1, 5])),          # 2 x 3,281 vectors
+    ("p5_cap16", _reroute_case(9102, 6, 32, 16, [4])),                        # 39,525
+    ("p6_cap16", _reroute_case(9103, 7, 32, 16, [8])),                        # 342,873
+    ("p7_cap16_two_stages", _reroute_case(9104, 8, 32, 16, [0, 10])),         # 2 x 2,380,833 (the shape of config 3)
+    ("p5_cap8_two_stages", _reroute_case(9105, 6, 16, 8, [2, 9])),            # 2 x 3,195
+    ("p6_cap8", _reroute_case(9106, 7, 16, 8, [7])),                          # 15,597
+    ("p7_cap8", _reroute_case(9107, 8, 16, 8, [3])),                          # 62,601
+    ("p8_cap8", _reroute_case(9108, 9, 16, 8, [13])),                         # 217,701
+    ("p6_cap12_run_sweep", _reroute_case(9109, 7, 24, 12, [5])),              # a cap the grouped sweep is not compiled for
+    ("p5_cap16_three_stages", _reroute_case(9110, 6, 32, 16, [0, 4, 8])),     # 3 x 39,525: every stage lost a node
+]
+
+
+@pytest.mark.parametrize("name", [c[0] for c in GROUPED])
+def test_large_reroute_spaces_swept_by_kernels_of_their_own(B, name):
+    """more than 4,096 reroute vectors: base pass, the partitions that fit gathered into a list, one sweep launch per
+    stage that lost nodes (grouped by shared leading entries where the cap allows), combine; exhaustive and bounded
+    against the oracle, with part of the partitions failing the memory filter"""
+    sc = dict(GROUPED)[name]
+    o, g = O.Scenario(sc), B.Scenario(sc)
+    assert g.families == o.families
+    f = o.family(2)
+    if f is None:
+        pytest.skip("rerouting cannot absorb this failure set")
+    assert f["n_reroute"] > 4096
+    g.set_timing(True)
+    rc_o, best_o, _ = o.search_range(2, 0, f["n_part"])
+    _, _, fit_o = o.search_range_counted(2, 0, f["n_part"])
+    assert 0 < fit_o < f["n_part"]                     # some partitions fit, some do not
+    for bounded in (0, 1, 2):
+        g.set_bounded_search(bounded)
+        rc, best = g.search_best(4)
+        assert rc == rc_o == 0 and same_plan(best, best_o), (name, bounded, best, best_o)
+        if bounded == 0:
+            assert g.get_timing()["feasible"][2] == fit_o
+    g.set_bounded_search(0)
+    lo, n = f["n_part"] // 4, f["n_part"] // 2
+    rc_w, best_w = g.search_range(2, lo, n)
+    rc_ow, best_ow, _ = o.search_range(2, lo, n)
+    assert rc_w == rc_ow and (rc_w != 0 or same_plan(best_w, best_ow))
+    rc_all, best_all = g.search_best(7)
+    rc_oa, best_oa = o.search(7)
+    assert rc_all == rc_oa == 0 and same_plan(best_all, best_oa)
+    g.close()
