@@ -78,6 +78,12 @@ struct FastState {
   // fit through a ring per wave (k_fast_search, QUEUED).  queue_mode: -1 = by that estimate, 0 = never, 1 = always.
   float fit_share[3] = {1.0f, 1.0f, 1.0f};   // negative: not sampled yet (sampled when a search first asks)
   int queue_mode = -1;
+  // Set by the owner of the state before fast_prepare: the stream the library's own uploads and table kernels
+  // run on (only that stream is waited for), and a call that waits until no work launched through this handle is
+  // in flight any more (made before a buffer that such work may touch is replaced).
+  void *load_stream = nullptr;
+  void (*quiesce)(void *) = nullptr;
+  void *owner = nullptr;
   FastTables h_tables;
   FastTables *d_tables = nullptr;
   uint32_t *d_vecs = nullptr;
@@ -172,6 +178,6 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
 // convention as fast_search.
 int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t local_first,
                        uint64_t count, int64_t *d_costs, void *stream);
-// device_idle: the caller has waited for the device, the buffers can be reused at once
-void fast_release(FastState *f, bool device_idle = false);
+// the caller has waited for everything launched through the handle: the buffers can be reused at once
+void fast_release(FastState *f);
 #endif

@@ -1727,6 +1727,10 @@ float estimate_fit_share(const DevScenario &h, const FastFamily &ff, int strat, 
 
 }  // namespace
 
+static void fast_quiesce(FastState *f) {
+  if (f->quiesce) f->quiesce(f->owner);
+}
+
 // Run and vector tables of the rerouting family (see FastTables): enumeration on the host, rows decoded on the
 // device, then the table block is uploaded again with the offsets and counts.  At load for families whose
 // vectors are swept inside the search kernel, on first need for the large ones.  False on a failed HIP call;
@@ -1858,21 +1862,25 @@ static bool build_reroute_tables(FastState *f, const DevScenario &h) {
   }
   if (!f->usable[2]) return true;
   if (runs.empty()) runs.assign(8, 0);
+  fast_quiesce(f);                                           // (an earlier asynchronous call may still hold the placeholder)
   if (f->d_runs) pool_release(f->d_runs);
   if (f->d_vecs) pool_release(f->d_vecs);
   f->d_runs = nullptr; f->d_vecs = nullptr;
+  // uploads and the row kernel run on the library's own stream and only that stream is waited for
+  hipStream_t ls = (hipStream_t)f->load_stream;
   bool up = pool_take(f->d_runs, runs.size() * sizeof(uint32_t));
-  up = up && hipMemcpy(f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), hipMemcpyHostToDevice) == hipSuccess;
+  up = up && hipMemcpyAsync(f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), hipMemcpyHostToDevice, ls) == hipSuccess;
   up = up && pool_take(f->d_vecs, f->vec_words * sizeof(uint32_t));
-  up = up && hipMemcpy(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice) == hipSuccess;
+  up = up && hipMemcpyAsync(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice, ls) == hipSuccess;
   if (up) {
     for (int a = 0; a < h.n_aff; ++a) {
       const int stride = h.aff_peers[a] <= 4 ? 4 : 8;
-      hipLaunchKernelGGL(k_make_rows, dim3((t->vec_rows[a] + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, nullptr, f->d_scn, f->d_comp, a,
+      hipLaunchKernelGGL(k_make_rows, dim3((t->vec_rows[a] + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, ls, f->d_scn, f->d_comp, a,
                          f->d_vecs + t->vec_off[a], t->vec_rows[a], stride);
     }
-    up = hipGetLastError() == hipSuccess && hipDeviceSynchronize() == hipSuccess;
+    up = hipGetLastError() == hipSuccess;
   }
+  up = (hipStreamSynchronize(ls) == hipSuccess) && up;       // also when something failed: `runs` must outlive its copy
   f->reroute_tables_ready = up;
   return up;
 }
@@ -1986,11 +1994,13 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
   f->d_scn = d_scn;
   f->d_comp = d_comp;
   f->reroute_tables_ready = false;
+  hipStream_t ls = (hipStream_t)f->load_stream;
   bool up = pool_take(f->d_tables, sizeof(FastTables));
   up = up && pool_take(f->d_runs, 8 * sizeof(uint32_t));            // placeholder until the tables are built
-  up = up && hipMemset(f->d_runs, 0, 8 * sizeof(uint32_t)) == hipSuccess;
-  up = up && hipMemcpy(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice) == hipSuccess;
+  if (up) hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, ls, f->d_runs, 8u, 0u);
+  up = up && hipMemcpyAsync(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice, ls) == hipSuccess;
   if (up && f->usable[2]) up = pool_take(f->d_rowkey, DEV_MAX_AFF * sizeof(uint64_t));
+  up = (hipStreamSynchronize(ls) == hipSuccess) && up;
   if (!up) return 1;
   if (f->usable[2] && !f->split) return build_reroute_tables(f, h) ? 0 : 1;
   return 0;
@@ -2003,6 +2013,7 @@ namespace {
 bool ensure_scratch(FastState *f, uint64_t parts) {
   const uint32_t need = (uint32_t)std::min<uint64_t>(FAST_SUB, std::max<uint64_t>(parts, 1 << 12));
   if (f->d_base && f->d_weights && f->d_pen && f->d_fit_list && f->d_fit_count && f->scratch_parts >= need) return true;
+  fast_quiesce(f);                                           // what is replaced may still be read by an asynchronous call
   if (f->d_fit_count) pool_release(f->d_fit_count);
   if (f->d_fit_list) pool_release(f->d_fit_list);
   if (f->d_pen) pool_release(f->d_pen);
@@ -2236,6 +2247,7 @@ int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunc
   const uint32_t total = a.part_count;
   const uint32_t blocks = (total + BLOCK - 1) / BLOCK;
   if (f->cand_capacity < total) {
+    fast_quiesce(f);
     if (f->d_cand_list) pool_release(f->d_cand_list);
     if (f->d_cand_pos) pool_release(f->d_cand_pos);
     if (f->d_cand_count) pool_release(f->d_cand_count);
@@ -2248,6 +2260,7 @@ int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunc
     f->cand_capacity = cap;
   }
   if (f->cand_ways_capacity < cs.ways.size()) {
+    fast_quiesce(f);
     if (f->d_cand_ways) pool_release(f->d_cand_ways);
     if (f->d_cand_low) pool_release(f->d_cand_low);
     f->d_cand_ways = nullptr; f->d_cand_low = nullptr; f->cand_ways_capacity = 0; f->cand_serial = 0;
@@ -2510,28 +2523,28 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
   return 0;
 }
 
-void fast_release(FastState *f, bool device_idle) {
-  if (f->d_cand_low) pool_release(f->d_cand_low, device_idle);
-  if (f->d_cand_ways) pool_release(f->d_cand_ways, device_idle);
-  if (f->d_cand_count) pool_release(f->d_cand_count, device_idle);
-  if (f->d_cand_pos) pool_release(f->d_cand_pos, device_idle);
-  if (f->d_cand_list) pool_release(f->d_cand_list, device_idle);
+void fast_release(FastState *f) {
+  if (f->d_cand_low) pool_release(f->d_cand_low);
+  if (f->d_cand_ways) pool_release(f->d_cand_ways);
+  if (f->d_cand_count) pool_release(f->d_cand_count);
+  if (f->d_cand_pos) pool_release(f->d_cand_pos);
+  if (f->d_cand_list) pool_release(f->d_cand_list);
   f->d_cand_low = nullptr; f->d_cand_ways = nullptr; f->d_cand_count = nullptr; f->d_cand_pos = nullptr; f->d_cand_list = nullptr;
   f->cand_capacity = 0; f->cand_ways_capacity = 0;
-  if (f->d_cut_count) pool_release(f->d_cut_count, device_idle);
-  if (f->d_cut_pos) pool_release(f->d_cut_pos, device_idle);
-  if (f->d_cut_list) pool_release(f->d_cut_list, device_idle);
+  if (f->d_cut_count) pool_release(f->d_cut_count);
+  if (f->d_cut_pos) pool_release(f->d_cut_pos);
+  if (f->d_cut_list) pool_release(f->d_cut_list);
   f->d_cut_count = nullptr; f->d_cut_pos = nullptr; f->d_cut_list = nullptr;
-  if (f->d_rowkey) pool_release(f->d_rowkey, device_idle);
-  if (f->d_fit_count) pool_release(f->d_fit_count, device_idle);
-  if (f->d_fit_list) pool_release(f->d_fit_list, device_idle);
+  if (f->d_rowkey) pool_release(f->d_rowkey);
+  if (f->d_fit_count) pool_release(f->d_fit_count);
+  if (f->d_fit_list) pool_release(f->d_fit_list);
   f->d_fit_count = nullptr; f->d_fit_list = nullptr;
-  if (f->d_pen) pool_release(f->d_pen, device_idle);
-  if (f->d_weights) pool_release(f->d_weights, device_idle);
-  if (f->d_base) pool_release(f->d_base, device_idle);
-  if (f->d_vecs) pool_release(f->d_vecs, device_idle);
-  if (f->d_runs) pool_release(f->d_runs, device_idle);
-  if (f->d_tables) pool_release(f->d_tables, device_idle);
+  if (f->d_pen) pool_release(f->d_pen);
+  if (f->d_weights) pool_release(f->d_weights);
+  if (f->d_base) pool_release(f->d_base);
+  if (f->d_vecs) pool_release(f->d_vecs);
+  if (f->d_runs) pool_release(f->d_runs);
+  if (f->d_tables) pool_release(f->d_tables);
   f->d_rowkey = nullptr; f->d_pen = nullptr; f->d_weights = nullptr; f->d_base = nullptr;
   f->d_vecs = nullptr;
   f->d_runs = nullptr;

@@ -69,6 +69,11 @@ struct chm_scenario {
   int bounded = 0;              // chm_set_bounded_search: 0 off, 1 on, 2 on with seeds and enumeration at any size
   hipEvent_t ev[8] = {};
   chm_timing last = {};
+  // Work launched through the handle that no call has waited for yet (the asynchronous scoring calls, a call
+  // that failed half way): per stream one event recorded behind it.  Waited for before the handle's buffers are
+  // replaced or released, so that neither needs a device-wide wait.
+  struct InFlight { hipStream_t stream; hipEvent_t event; bool busy; } in_flight[4] = {};
+  bool in_flight_overflow = false;       // more streams than slots: fall back to waiting for the device
   FastState fast;                        // shape-specialised search path (chm_fast.hip)
 };
 
@@ -78,6 +83,54 @@ namespace {
 // Each launched chunk and each of the three counters owns SLOT_WAYS words, SLOT_STRIDE words apart, when the
 // call has few enough chunks for that; otherwise one word each.
 enum { MAX_SLOTS = 1 << 16, SLOT_WORDS = (1 << 16) + 64, SLOT_WAYS = 16, SLOT_STRIDE = 16 };
+
+// The library's own stream of a device (uploads, table kernels at load): created on first use, never destroyed,
+// default priority, does not synchronise with the null stream.
+hipStream_t load_stream_of(int device) {
+  enum { MAX_DEVICES = 64 };
+  static std::mutex lock;
+  static hipStream_t streams[MAX_DEVICES] = {};
+  if (device < 0 || device >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> hold(lock);
+  if (!streams[device] && hipStreamCreateWithFlags(&streams[device], hipStreamNonBlocking) != hipSuccess) streams[device] = nullptr;
+  return streams[device];
+}
+
+// records that work launched through the handle may still be running on `st`
+void mark_in_flight(chm_scenario *s, hipStream_t st) {
+  int slot = -1;
+  for (int i = 0; i < 4; ++i)
+    if (s->in_flight[i].busy && s->in_flight[i].stream == st) slot = i;
+  for (int i = 0; i < 4 && slot < 0; ++i)
+    if (!s->in_flight[i].busy) slot = i;
+  if (slot < 0) { s->in_flight_overflow = true; return; }
+  chm_scenario::InFlight &f = s->in_flight[slot];
+  if (!f.event && hipEventCreateWithFlags(&f.event, hipEventDisableTiming) != hipSuccess) { f.event = nullptr; s->in_flight_overflow = true; return; }
+  if (hipEventRecord(f.event, st) != hipSuccess) { s->in_flight_overflow = true; return; }
+  f.stream = st;
+  f.busy = true;
+}
+
+// waits until nothing launched through the handle is running any more (the handle's device must be current)
+void quiesce(chm_scenario *s) {
+  for (int i = 0; i < 4; ++i) {
+    if (!s->in_flight[i].busy) continue;
+    if (hipEventSynchronize(s->in_flight[i].event) != hipSuccess) s->in_flight_overflow = true;
+    s->in_flight[i].busy = false;
+  }
+  if (s->in_flight_overflow) (void)hipDeviceSynchronize();
+  s->in_flight_overflow = false;
+}
+void quiesce_owner(void *owner) { quiesce((chm_scenario *)owner); }
+
+// Marks the stream of a call as possibly busy when the call ends, unless the call has waited for it itself.
+struct StreamGuard {
+  chm_scenario *s; hipStream_t st; bool armed = true;
+  StreamGuard(chm_scenario *s_, void *stream) : s(s_), st((hipStream_t)stream) {}
+  ~StreamGuard() { if (armed) mark_in_flight(s, st); }
+  // rc of a call that ends with a wait for the stream on every path that returns one of these
+  int settled(int rc) { if (rc == CHM_OK || rc == CHM_ERR_NO_FEASIBLE || rc == CHM_ERR_UNRECOVERABLE) armed = false; return rc; }
+};
 
 const chm_family *find_family(const chm_scenario *s, int strategy) {
   for (int i = 0; i < s->space.n_families; ++i)
@@ -336,19 +389,20 @@ int build_model(const chm_scenario_desc *d, chm_scenario *s) {
 
 void release(chm_scenario *s) {
   if (!s) return;
-  // one wait for the handle's device, then every buffer goes back to the allocator without further waits
+  // wait for what was launched through this handle and nothing else, then every buffer goes back to the allocator
   int current = 0;
   const bool switched = hipGetDevice(&current) == hipSuccess && current != s->device && hipSetDevice(s->device) == hipSuccess;
-  const bool idle = hipDeviceSynchronize() == hipSuccess;
-  fast_release(&s->fast, idle);
+  quiesce(s);
+  fast_release(&s->fast);
   for (auto &e : s->ev) if (e) (void)hipEventDestroy(e);
-  if (s->h_pinned) pool_release(s->h_pinned, idle);
-  if (s->d_final) pool_release(s->d_final, idle);
-  if (s->d_xfer) pool_release(s->d_xfer, idle);
-  if (s->d_winner) pool_release(s->d_winner, idle);
-  if (s->d_slots) pool_release(s->d_slots, idle);
-  if (s->d_comp) pool_release(s->d_comp, idle);
-  if (s->d_scn) pool_release(s->d_scn, idle);
+  for (auto &f : s->in_flight) if (f.event) (void)hipEventDestroy(f.event);
+  if (s->h_pinned) pool_release(s->h_pinned);
+  if (s->d_final) pool_release(s->d_final);
+  if (s->d_xfer) pool_release(s->d_xfer);
+  if (s->d_winner) pool_release(s->d_winner);
+  if (s->d_slots) pool_release(s->d_slots);
+  if (s->d_comp) pool_release(s->d_comp);
+  if (s->d_scn) pool_release(s->d_scn);
   if (switched) (void)hipSetDevice(current);
   delete s;
 }
@@ -878,6 +932,13 @@ int run_search(chm_scenario *s, const std::vector<Job> &given, chm_best *out, ui
 // Takes ownership of s: on failure it is released and *out stays null.
 int upload_scenario(chm_scenario *s, chm_scenario **out) {
   bool ok = hipGetDevice(&s->device) == hipSuccess;
+  // everything the load puts on the device goes through the library's own stream, and only that stream is waited
+  // for: searches other threads have in flight on their streams are not disturbed
+  hipStream_t ls = ok ? load_stream_of(s->device) : nullptr;
+  ok = ok && ls != nullptr;
+  s->fast.load_stream = ls;
+  s->fast.quiesce = quiesce_owner;
+  s->fast.owner = s;
   ok = ok && pool_take(s->d_scn, sizeof(DevScenario));
   ok = ok && pool_take(s->d_comp, s->comp.size() * sizeof(uint64_t));
   ok = ok && pool_take(s->d_slots, (size_t)SLOT_WORDS * sizeof(uint64_t));
@@ -886,14 +947,17 @@ int upload_scenario(chm_scenario *s, chm_scenario **out) {
   ok = ok && pool_take(s->d_xfer, sizeof(uint64_t) + DEV_MAX_S);
   ok = ok && pool_take(s->d_final, FINISH_WORDS * sizeof(uint64_t));
   ok = ok && pool_take_pinned(s->h_pinned, (size_t)SLOT_WORDS * sizeof(uint64_t));
-  ok = ok && hipMemcpy(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice) == hipSuccess;
-  ok = ok && hipMemcpy(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice) == hipSuccess;
+  ok = ok && hipMemcpyAsync(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice, ls) == hipSuccess;
+  ok = ok && hipMemcpyAsync(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice, ls) == hipSuccess;
   for (auto &e : s->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
-  if (ok && s->h.fam[1].n_part) {
+  const bool fixed = ok && s->h.fam[1].n_part;
+  if (fixed) {
     // the healthy pipelines' step time under the fault-free layout is computed by the device
-    ok = chmk_fixed_pipelines(s->d_scn, s->smax, nullptr) == 0 && hipDeviceSynchronize() == hipSuccess;
-    ok = ok && hipMemcpy(&s->h.fam[1].fixed_step, &s->d_scn->fam[1].fixed_step, sizeof(int64_t), hipMemcpyDeviceToHost) == hipSuccess;
+    ok = chmk_fixed_pipelines(s->d_scn, s->smax, ls) == 0;
+    ok = ok && hipMemcpyAsync(s->h_pinned, &s->d_scn->fam[1].fixed_step, sizeof(int64_t), hipMemcpyDeviceToHost, ls) == hipSuccess;
   }
+  if (ls) ok = (hipStreamSynchronize(ls) == hipSuccess) && ok;
+  if (ok && fixed) s->h.fam[1].fixed_step = (int64_t)s->h_pinned[0];
   ok = ok && fast_prepare(&s->fast, s->h, s->int32_ok, s->d_scn, s->d_comp) == 0;
   if (!ok) { release(s); return CHM_ERR_HIP; }
   *out = s;
@@ -987,6 +1051,7 @@ extern "C" int chm_score_plans(chm_scenario *s, uint64_t first, uint64_t count, 
   if (!s || (count && !d_costs)) return CHM_ERR_ARG;
   if (first > s->space.n_plans || count > s->space.n_plans - first) return CHM_ERR_RANGE;
   HIP_TRY(hipSetDevice(s->device));
+  StreamGuard guard(s, hip_stream);                  // asynchronous: the stream stays marked as busy
   uint64_t lo = first, hi = first + count;
   for (int i = 0; i < s->space.n_families; ++i) {
     const chm_family &f = s->space.fam[i];
@@ -1024,6 +1089,7 @@ extern "C" int chm_score_ranks(chm_scenario *s, int32_t strategy, const uint64_t
   if (f->n_reroute != 1) return CHM_ERR_ARG;
   HIP_TRY(hipSetDevice(s->device));
   if (n == 0) return CHM_OK;
+  StreamGuard guard(s, hip_stream);
   std::vector<Job> jobs;
   jobs.push_back({strategy, 0, n, d_part_ranks, d_costs});
   return run_search(s, jobs, nullptr, nullptr, (hipStream_t)hip_stream);
@@ -1035,6 +1101,7 @@ extern "C" int chm_rank_partitions(chm_scenario *s, int32_t strategy, const uint
   const chm_family *f = find_family(s, strategy);
   if (!f) return CHM_ERR_UNRECOVERABLE;
   HIP_TRY(hipSetDevice(s->device));
+  StreamGuard guard(s, hip_stream);
   if (chmk_rank_cuts(s->d_scn, f->stages - 1, d_cuts, n, d_part_ranks, hip_stream)) return CHM_ERR_HIP;
   return CHM_OK;
 }
@@ -1047,7 +1114,8 @@ extern "C" int chm_search_ranks(chm_scenario *s, int32_t strategy, const uint64_
   if (position) *position = UINT64_MAX;
   std::vector<Job> jobs;
   if (n) jobs.push_back({strategy, 0, n, d_part_ranks, d_costs});
-  return run_search(s, jobs, out, position, (hipStream_t)hip_stream);
+  StreamGuard guard(s, hip_stream);
+  return guard.settled(run_search(s, jobs, out, position, (hipStream_t)hip_stream));
 }
 
 extern "C" int chm_search_cuts(chm_scenario *s, int32_t strategy, const uint8_t *d_cuts, uint64_t n,
@@ -1062,7 +1130,8 @@ extern "C" int chm_search_cuts(chm_scenario *s, int32_t strategy, const uint8_t 
     j.cuts = d_cuts;
     jobs.push_back(j);
   }
-  return run_search(s, jobs, out, position, (hipStream_t)hip_stream);
+  StreamGuard guard(s, hip_stream);
+  return guard.settled(run_search(s, jobs, out, position, (hipStream_t)hip_stream));
 }
 
 extern "C" int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void *hip_stream) {
@@ -1073,7 +1142,8 @@ extern "C" int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best
     if (strategy_mask & (1u << f.strategy)) jobs.push_back({f.strategy, 0, f.n_part, nullptr, nullptr});
   }
   if (jobs.empty()) { nothing_found(out); return CHM_ERR_UNRECOVERABLE; }
-  return run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream);
+  StreamGuard guard(s, hip_stream);
+  return guard.settled(run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream));
 }
 
 extern "C" int chm_search_best_batch(chm_scenario *const *handles, int32_t n, uint32_t strategy_mask, chm_best *outs,
@@ -1086,6 +1156,15 @@ extern "C" int chm_search_best_batch(chm_scenario *const *handles, int32_t n, ui
   hipStream_t st = (hipStream_t)hip_stream;
   std::vector<char> pending(n, 0);
   bool any_pending = false;
+  // whatever way the call ends, every handle whose result is not final leaves its stream marked as busy
+  struct MarkAll {
+    chm_scenario *const *h; int32_t n; const int32_t *codes; hipStream_t st;
+    ~MarkAll() {
+      for (int i = 0; i < n; ++i)
+        if (codes[i] != CHM_OK && codes[i] != CHM_ERR_NO_FEASIBLE && codes[i] != CHM_ERR_UNRECOVERABLE) mark_in_flight(h[i], st);
+    }
+  } mark_all{handles, n, codes, st};
+  for (int i = 0; i < n; ++i) codes[i] = CHM_ERR_HIP;          // until the handle's search has been collected
   for (int i = 0; i < n; ++i) {
     chm_scenario *s = handles[i];
     std::vector<Job> jobs;
@@ -1172,7 +1251,8 @@ extern "C" int chm_search_best_static(chm_scenario *s, uint32_t strategy_mask, c
   s->d_xfer = base + STATIC_XFER_AT;
   s->d_final = base + STATIC_FINAL_AT;
   s->fast.penalty_by_capacity = false;
-  const int rc = run_jobs(s, jobs, out, nullptr, (hipStream_t)hip_stream, ~0ull, false);
+  StreamGuard guard(s, hip_stream);
+  const int rc = guard.settled(run_jobs(s, jobs, out, nullptr, (hipStream_t)hip_stream, ~0ull, false));
   s->d_slots = own_slots; s->slot_words = own_words; s->d_winner = own_winner; s->d_xfer = own_xfer; s->d_final = own_final;
   if (rc == CHM_ERR_LIMIT) nothing_found(out);
   return rc;
@@ -1186,7 +1266,8 @@ extern "C" int chm_search_range(chm_scenario *s, int32_t strategy, uint64_t part
   if (part_first > f->n_part || part_count > f->n_part - part_first) return CHM_ERR_RANGE;
   std::vector<Job> jobs;
   jobs.push_back({strategy, part_first, part_count, nullptr, nullptr});
-  return run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream);
+  StreamGuard guard(s, hip_stream);
+  return guard.settled(run_search(s, jobs, out, nullptr, (hipStream_t)hip_stream));
 }
 
 extern "C" int chm_transfer_plan(chm_scenario *s, uint64_t part_rank, int32_t pipeline, int32_t *n_nodes,
@@ -1201,6 +1282,7 @@ extern "C" int chm_transfer_plan(chm_scenario *s, uint64_t part_rank, int32_t pi
   HIP_TRY(hipSetDevice(s->device));
   hipStream_t st = (hipStream_t)hip_stream;
   uint8_t *d_stage = (uint8_t *)(s->d_xfer + 1);
+  StreamGuard guard(s, hip_stream);
   if (chmk_transfer_plan(s->d_scn, part_rank, (int32_t)sv.size(), sv.data(), d_stage, (int64_t *)s->d_xfer, st)) return CHM_ERR_HIP;
   HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_xfer, sizeof(uint64_t) + DEV_MAX_S, hipMemcpyDeviceToHost, st));
   HIP_TRY(hipStreamSynchronize(st));
@@ -1208,7 +1290,7 @@ extern "C" int chm_transfer_plan(chm_scenario *s, uint64_t part_rank, int32_t pi
   *fetch_mib = (int64_t)s->h_pinned[0];
   const uint8_t *got = (const uint8_t *)(s->h_pinned + 1);
   for (size_t i = 0; i < sv.size(); ++i) { node_stage[i] = sv[i]; stage_of_node[i] = got[i]; }
-  return CHM_OK;
+  return guard.settled(CHM_OK);
 }
 
 extern "C" int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out) {

@@ -12,8 +12,8 @@
 
 namespace {
 
-constexpr size_t KEEP_BLOCK_MAX = 8u << 20;      // larger blocks are never kept
-constexpr size_t KEEP_TOTAL_MAX = 96u << 20;     // bytes kept per kind over all devices
+constexpr size_t KEEP_BLOCK_MAX = 256u << 20;                 // larger blocks are never kept
+constexpr size_t KEEP_TOTAL_MAX[2] = {1024u << 20, 96u << 20};   // bytes kept over all devices: device memory, pinned host memory
 
 struct Block { int device; bool pinned; size_t size; };
 
@@ -57,7 +57,7 @@ void *take(size_t bytes, bool pinned) {
 void *pool_device_alloc(size_t bytes) { return take(bytes, false); }
 void *pool_pinned_alloc(size_t bytes) { return take(bytes, true); }
 
-void pool_release(void *p, bool device_idle) {
+void pool_release(void *p) {
   if (!p) return;
   Block b;
   {
@@ -66,28 +66,13 @@ void pool_release(void *p, bool device_idle) {
     if (it == g_live.end()) return;               // not ours
     b = it->second;
     g_live.erase(it);
-  }
-  const bool keep = b.size <= KEEP_BLOCK_MAX;
-  if (keep && device_idle) {
-    std::lock_guard<std::mutex> hold(g_lock);
-    if (g_kept_bytes[b.pinned] + b.size <= KEEP_TOTAL_MAX) {
-      g_kept[std::make_tuple(b.pinned ? -1 : b.device, b.pinned, b.size)].push_back(p);
-      g_kept_bytes[b.pinned] += b.size;
-      return;
-    }
-  } else if (keep) {
-    // whatever still reads or writes the block has to be over before someone else gets it (hipFree waits too)
-    int current = 0;
-    const bool switched = hipGetDevice(&current) == hipSuccess && current != b.device && hipSetDevice(b.device) == hipSuccess;
-    (void)hipDeviceSynchronize();
-    if (switched) (void)hipSetDevice(current);
-    std::lock_guard<std::mutex> hold(g_lock);
-    if (g_kept_bytes[b.pinned] + b.size <= KEEP_TOTAL_MAX) {
+    if (b.size <= KEEP_BLOCK_MAX && g_kept_bytes[b.pinned] + b.size <= KEEP_TOTAL_MAX[b.pinned]) {
       g_kept[std::make_tuple(b.pinned ? -1 : b.device, b.pinned, b.size)].push_back(p);
       g_kept_bytes[b.pinned] += b.size;
       return;
     }
   }
+  // beyond what is kept: back to the runtime (which waits for the device on its own)
   if (b.pinned) (void)hipHostFree(p);
   else (void)hipFree(p);
 }

@@ -126,7 +126,9 @@ struct Scratch {
   int32_t *d_held = nullptr, *d_pos = nullptr, *d_assign = nullptr;
   int64_t *d_pw = nullptr, *d_total = nullptr; // d_total: [0] least total MiB, [1] rounds (int32 in its low half)
   int64_t *h_total = nullptr;                  // pinned, two words
+  hipStream_t stream = nullptr;                // the stream every kernel and copy that touches these blocks runs on
   ~Scratch() {
+    (void)hipStreamSynchronize(stream);        // (an early return may leave work in flight)
     if (d_held) pool_release(d_held);
     if (d_pos) pool_release(d_pos);
     if (d_assign) pool_release(d_assign);
@@ -198,6 +200,7 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
     return CHM_ERR_OVERFLOW;
 
   Scratch sc;
+  sc.stream = st;
   if (N > 0) {
     bool ok = pool_take(sc.d_held, held.size() * sizeof(int32_t));
     ok = ok && pool_take(sc.d_pos, held.size() * sizeof(int32_t));

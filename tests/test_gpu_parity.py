@@ -943,3 +943,50 @@ def test_large_reroute_spaces_swept_by_kernels_of_their_own(B, name):
     rc_oa, best_oa = o.search(7)
     assert rc_all == rc_oa == 0 and same_plan(best_all, best_oa)
     g.close()
+
+
+def test_load_search_and_free_do_not_wait_for_other_streams(B):
+    """a handle is loaded, searched and freed while another handle's cost stores are queued on another stream:
+    neither the load nor the release waits for the whole device"""
+    import time
+    import torch
+    big = B.Scenario(synth.config2())
+    f0 = big.family(0)
+    count = f0["n_part"]                                 # every plan of the redundant strategy: about a millisecond per call
+    out = torch.empty(count, dtype=torch.int64, device="cuda")
+    busy, mine = torch.cuda.Stream(), torch.cuda.Stream()
+    small = synth.config1()
+    g = B.Scenario(small)
+    want = g.search_best(7, stream=mine)
+    g.close()
+    torch.cuda.synchronize()
+    for _ in range(80):
+        big.score_plans(f0["offset"], count, out=out, stream=busy)
+    # load and free alone (no kernel of the new handle has to find room on the busy device)
+    t0 = time.perf_counter()
+    loaded_while_busy = 0
+    for _ in range(6):
+        g = B.Scenario(small)
+        g.close()
+        if not busy.query():
+            loaded_while_busy += 1
+    t_load = time.perf_counter() - t0
+    # and with a search in between: its kernels share the device with the queued ones
+    searched_while_busy = 0
+    for _ in range(3):
+        g = B.Scenario(small)
+        got = g.search_best(7, stream=mine)
+        g.close()
+        assert got == want
+        if not busy.query():
+            searched_while_busy += 1
+    t_small = time.perf_counter() - t0
+    busy.synchronize()
+    t_all = time.perf_counter() - t0
+    print("six load + free rounds: %.2f ms (%d ended while the other stream ran); three more with a search: %.2f ms in all (%d); "
+          "the other stream drained after %.1f ms" % (t_load * 1e3, loaded_while_busy, t_small * 1e3, searched_while_busy, t_all * 1e3), flush=True)
+    assert loaded_while_busy >= 1
+    # the busy handle's own release waits for its own stream only, and its results are intact
+    ref = O.Scenario(synth.config2()).score(f0["offset"] + 1000, 64)
+    assert (out[1000:1064].cpu().numpy() == ref).all()
+    big.close()
