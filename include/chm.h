@@ -9,9 +9,16 @@
  * recurrence, eq. (transition); max over pipelines for asymmetric parallelism; the data
  * rerouting terms of eq. (recycle_step_time) / (recycle_step_time_multi)), filtered by
  * the memory estimator, charged a transition time, and the cheapest plan is returned
- * (Algorithm 1, get_execution_plan).  All scoring runs in hand-written HIP kernels; the
- * host side only validates, lays out tables and launches.  There is no CPU fallback:
- * without a usable GPU every compute call returns CHM_ERR_HIP.
+ * (Algorithm 1, get_execution_plan).  All scoring runs in hand-written HIP kernels: every
+ * cost the library returns or stores was computed on the device.  The host side validates,
+ * lays out tables, launches, and combines the per-chunk winners when a call has more chunks
+ * than the device-side combine takes.  Only a bounded search (chm_set_bounded_search, off by
+ * default) does arithmetic of the method on the host, none of it a plan's cost: the ranks of
+ * the seed partitions (layer-time and memory quantiles), the per-stage table that counts the
+ * partitions whose lower bound stays within the best cost known (fast_candidates_build), and,
+ * for reroute spaces too large to sweep, the reroute vectors of the winner recovered from the
+ * peers' capacities (least penalty by bisection).  There is no CPU fallback: without a usable
+ * GPU every compute call returns CHM_ERR_HIP.
  *
  * Conventions
  *   - Every function returns 0 (CHM_OK) or a negative CHM_ERR_* code; nothing throws or
@@ -317,7 +324,8 @@ typedef struct {
   const int32_t *failed_nodes;                /* [n_failed] distinct node ids */
   int32_t dp_min, dp_max;                     /* R_dp, within 1..16 */
   int32_t pp_min, pp_max;                     /* R_pp, within 1..32 */
-  int32_t micro_batches;                      /* N_m of one step over all pipelines, >= 1; a pipeline gets at most 256 */
+  int32_t micro_batches;                      /* N_m of one step over all pipelines, >= 1; a pipeline runs at most 256: a dp
+                                                 whose batch distribution would give some pipeline more is not a candidate */
   int32_t comm_us, mem_cap_mib;
   int64_t horizon_us;                         /* H: time between two faults (transition + training), >= 1 */
   int32_t restart_us, xfer_us_per_mib;

@@ -914,8 +914,12 @@ extern "C" int orc_replan(const orc_replan_desc *d, orc_replan_plan *out) {
     bool usable = d->micro_batches >= dp;
     for (int p = 0; p < dp; ++p) usable = usable && len[p] <= d->L;
     if (!usable) continue;
-    ++out->n_candidates;
     orc_distribute_batch(dp, d->micro_batches, len, mb);
+    // a pipeline runs at most ORC_MAX_M micro-batches (the limit of the scenario path): a layout that would give
+    // one more is not a candidate
+    for (int p = 0; p < dp; ++p) usable = usable && mb[p] <= ORC_MAX_M;
+    if (!usable) continue;
+    ++out->n_candidates;
     orc_replan_plan cand;
     std::memset(&cand, 0, sizeof(cand));
     cand.dp = dp;

@@ -12,7 +12,12 @@ import subprocess
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-_LIB_PATH = os.path.join(_HERE, "liborc.so")
+# ORC_SANITIZE=1: the oracle built with AddressSanitizer and UndefinedBehaviorSanitizer (host code only), as a
+# library of its own.  The interpreter is not instrumented, so the sanitizer runtime has to be loaded first:
+#   ORC_SANITIZE=1 LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+#       python -m pytest tests/test_oracle_pins.py tests/test_full_space_script.py -q
+SANITIZE = os.environ.get("ORC_SANITIZE", "") == "1"
+_LIB_PATH = os.path.join(_HERE, "liborc_san.so" if SANITIZE else "liborc.so")
 _SRC = os.path.join(_HERE, "chm_oracle.cpp")
 
 OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE = 0, -1, -2, -3, -4, -5
@@ -24,7 +29,8 @@ def build(force=False):
     if not force and os.path.exists(_LIB_PATH) and os.path.getmtime(_LIB_PATH) >= max(
             os.path.getmtime(_SRC), os.path.getmtime(os.path.join(_HERE, "chm_oracle.h"))):
         return _LIB_PATH
-    cmd = ["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-o", _LIB_PATH, _SRC]
+    opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined"] if SANITIZE else ["-O2"]
+    cmd = ["g++"] + opt + ["-std=c++17", "-fPIC", "-shared", "-Wall", "-o", _LIB_PATH, _SRC]
     subprocess.run(cmd, check=True)
     return _LIB_PATH
 

@@ -10,7 +10,8 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libchm.so")
+# CHM_SANITIZE=1 selects the build whose host code is instrumented with sanitizers (see build.py)
+LIB_PATH = os.path.join(_HERE, "libchm_san.so" if os.environ.get("CHM_SANITIZE", "") == "1" else "libchm.so")
 
 OK, ERR_ARG, ERR_RANGE, ERR_OVERFLOW, ERR_UNRECOVERABLE, ERR_NO_FEASIBLE, ERR_HIP, ERR_LIMIT = 0, -1, -2, -3, -4, -5, -6, -7
 INFEASIBLE = (1 << 63) - 1

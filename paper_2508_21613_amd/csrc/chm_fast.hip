@@ -7,7 +7,8 @@
 // in registers: the cut positions, the per-stage sums (read from one LDS table of prefix
 // sums staged once per workgroup), and the recurrence frontier - ONE value per stage, see
 // the evaluation order described in chm_kernels.hip.  The recurrence is unrolled over the
-// (compile-time) pipeline length, so each cell is exactly one v_max_i32 and one v_add_u32.
+// (compile-time) pipeline length and runs in the frame of the forward chain (makespan32): a
+// round of N forwards and N backwards is N-1 v_max_i32 and N v_add_u32.
 // All values are int32: the host only selects these kernels when its load-time bound shows
 // that no intermediate can reach 2^31, in which case the results equal the int64 ones.
 //

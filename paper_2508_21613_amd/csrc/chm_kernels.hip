@@ -1,8 +1,10 @@
 // Generic scoring kernels of libchm for gfx950: any shape within the library limits,
 // int64 arithmetic throughout.  One lane evaluates one plan (scoring) or one partition
-// with all of its reroute vectors (search).  The shape-specialised search kernels live in
-// chm_fast.hip; these are the reference the library falls back to for shapes those do not
-// cover, and the only path for chm_score_plans / chm_score_ranks.
+// with all of its reroute vectors (search).  The shape-specialised kernels live in
+// chm_fast.hip and serve searching and scoring alike wherever their load-time bounds hold;
+// these are what the library falls back to for every shape and magnitude those do not cover
+// (more than 16 stages, times that do not fit int32, more than 8 peers), plus the small
+// one-lane kernels around a search (fixed pipelines, the winner's terms, migration scheme).
 //
 // Pipeline time: the 1F1B dependency recurrence of the Estimator subsection
 // (eq. (transition)) is a longest path in a fixed graph, so any topological order gives

@@ -232,14 +232,17 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
       in_range = in_range && len[p] >= d->pp_min && len[p] <= d->pp_max && len[p] <= L;
     }
     if (!in_range) continue;
-    ++out->n_candidates;
     chm_internal_share_micro_batches(dp, d->micro_batches, len, mb);
+    // a pipeline runs at most CHM_MAX_M micro-batches: a layout that would give one more is not a candidate
+    bool share_ok = true;
+    for (int p = 0; p < dp; ++p) share_ok = share_ok && mb[p] <= CHM_MAX_M;
+    if (!share_ok) continue;
+    ++out->n_candidates;
     chm_replan_plan cand;
     memset(&cand, 0, sizeof(cand));
     cand.dp = dp;
     bool fits = true;
     for (int p = 0; p < dp && fits; ++p) {
-      if (mb[p] > CHM_MAX_M) return CHM_ERR_ARG;
       const std::pair<int, int> key(len[p], mb[p]);
       auto it = best_split.find(key);
       if (it == best_split.end()) {

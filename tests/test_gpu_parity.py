@@ -510,6 +510,9 @@ REPLAN = [
     synth.replan_case(17, 12, 16, 4, list(range(0, 64, 7)), 96, (12, 16), (3, 5)),         # 54 nodes, 16 pipelines
     synth.replan_case(18, 6, 2, 2, [0, 1, 2, 3], 4, (1, 2), (1, 2)),                       # nothing survived
     synth.replan_tie(),                                                                     # two candidates tie exactly
+    synth.replan_case(19, 12, 3, 4, [5], 700, (2, 5), (2, 6), cap_scale=4.5),       # 11 nodes, 700 micro-batches: with 2 pipelines one of them would run more than 256
+    synth.replan_case(20, 11, 3, 4, [5], 20, (2, 5), (1, 6)),       # 11 nodes: no pipeline count in range divides them
+    synth.replan_case(21, 12, 3, 4, [5], 3000, (2, 5), (2, 6), cap_scale=4.5),   # every layout overloads a pipeline: no candidate
 ]
 
 
@@ -947,45 +950,44 @@ def test_large_reroute_spaces_swept_by_kernels_of_their_own(B, name):
 
 def test_load_search_and_free_do_not_wait_for_other_streams(B):
     """a handle is loaded, searched and freed while another handle's cost stores are queued on another stream:
-    neither the load nor the release waits for the whole device"""
+    neither the load nor the release waits for the whole device.  (Streams share a few hardware queues, and work
+    behind a busy stream's on the same queue does wait for it; so the check is made against several busy
+    streams in turn and must hold for at least one: a device-wide wait would fail for all.)"""
     import time
     import torch
     big = B.Scenario(synth.config2())
     f0 = big.family(0)
     count = f0["n_part"]                                 # every plan of the redundant strategy: about a millisecond per call
     out = torch.empty(count, dtype=torch.int64, device="cuda")
-    busy, mine = torch.cuda.Stream(), torch.cuda.Stream()
+    mine = torch.cuda.Stream()
     small = synth.config1()
     g = B.Scenario(small)
     want = g.search_best(7, stream=mine)
     g.close()
     torch.cuda.synchronize()
-    for _ in range(80):
-        big.score_plans(f0["offset"], count, out=out, stream=busy)
-    # load and free alone (no kernel of the new handle has to find room on the busy device)
-    t0 = time.perf_counter()
-    loaded_while_busy = 0
-    for _ in range(6):
-        g = B.Scenario(small)
+    loaded, searched, report = 0, 0, []
+    for trial in range(6):
+        busy = torch.cuda.Stream()
+        for _ in range(30):
+            big.score_plans(f0["offset"], count, out=out, stream=busy)
+        t0 = time.perf_counter()
+        g = B.Scenario(small)                            # load and free alone
         g.close()
-        if not busy.query():
-            loaded_while_busy += 1
-    t_load = time.perf_counter() - t0
-    # and with a search in between: its kernels share the device with the queued ones
-    searched_while_busy = 0
-    for _ in range(3):
-        g = B.Scenario(small)
+        ok_load = not busy.query()
+        t_load = time.perf_counter() - t0
+        g = B.Scenario(small)                            # and with a search in between
         got = g.search_best(7, stream=mine)
         g.close()
+        ok_search = not busy.query()
+        t_search = time.perf_counter() - t0 - t_load
         assert got == want
-        if not busy.query():
-            searched_while_busy += 1
-    t_small = time.perf_counter() - t0
-    busy.synchronize()
-    t_all = time.perf_counter() - t0
-    print("six load + free rounds: %.2f ms (%d ended while the other stream ran); three more with a search: %.2f ms in all (%d); "
-          "the other stream drained after %.1f ms" % (t_load * 1e3, loaded_while_busy, t_small * 1e3, searched_while_busy, t_all * 1e3), flush=True)
-    assert loaded_while_busy >= 1
+        busy.synchronize()
+        t_all = time.perf_counter() - t0
+        loaded += ok_load
+        searched += ok_search
+        report.append("%.2f/%.2f/%.1f ms%s" % (t_load * 1e3, t_search * 1e3, t_all * 1e3, "" if ok_load else " (waited)"))
+    print("load+free / load+search+free / busy stream drained, per busy stream:", "; ".join(report), flush=True)
+    assert loaded >= 1 and searched >= 1
     # the busy handle's own release waits for its own stream only, and its results are intact
     ref = O.Scenario(synth.config2()).score(f0["offset"] + 1000, 64)
     assert (out[1000:1064].cpu().numpy() == ref).all()

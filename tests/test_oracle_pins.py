@@ -867,3 +867,33 @@ def test_least_reroute_penalty_equals_the_capacity_threshold():
             greedy.append(max(0, rem - behind))
             rem -= greedy[-1]
         assert list(O.reroute_unrank(p, n, cap, first)) == greedy and O.reroute_rank(p, n, cap, greedy) == first
+
+
+def test_replan_skips_layouts_that_overload_a_pipeline():
+    """a pipeline runs at most 256 micro-batches (the limit of the scenario path): a pipeline count whose batch
+    distribution gives some pipeline more is not a candidate, the others are searched as usual"""
+    rp = synth.replan_case(19, 12, 3, 4, [5], 700, (2, 5), (2, 6), cap_scale=4.5)
+    got = O.replan(rp)
+    # 11 nodes, 700 micro-batches: two pipelines (5 + 6 nodes) 318 + 382; three 191 + 255 + 254; four and five fewer still
+    assert got["found"] and got["n_candidates"] == 3 and got["dp"] in (3, 4, 5)
+    assert max(got["micro_batches"]) <= 256 and sum(got["micro_batches"]) == 700
+    only = O.replan(dict(rp, dp_min=got["dp"], dp_max=got["dp"]))
+    assert {k: v for k, v in only.items() if k != "n_candidates"} == {k: v for k, v in got.items() if k != "n_candidates"}
+    none = O.replan(dict(rp, micro_batches=3000))
+    assert not none["found"] and none["n_candidates"] == 0
+    # eleven nodes over 2..5 pipelines: the longer pipelines last (integer_partition)
+    assert O.integer_partition(11, 2, 1, 6) == [5, 6] and O.integer_partition(11, 3, 1, 6) == [3, 4, 4]
+    assert O.integer_partition(11, 4, 1, 6) == [2, 3, 3, 3] and O.integer_partition(11, 5, 1, 6) == [2, 2, 2, 2, 3]
+
+
+def test_even_layouts_of_1024_nodes_number_the_divisors_the_paper_counts():
+    """Planner, overhead paragraph: enumerating the parallel strategies of N nodes is O(tau(N)), tau(1024) = 11.
+    integer_partition gives one layout per pipeline count; the layouts in which all pipelines are equally long (the
+    paper's N = dp x pp factorisations) are exactly those of the divisors of N."""
+    n = 1024
+    even = [dp for dp in range(1, n + 1) if len(set(O.integer_partition(n, dp, 1, n))) == 1]
+    assert len(even) == int(golden()["tau_1024"]) == 11
+    assert even == [2 ** i for i in range(11)]
+    # and an uneven count keeps every node in use, the longer pipelines last
+    lengths = O.integer_partition(n, 3, 1, n)
+    assert lengths == [341, 341, 342] and sum(lengths) == n
