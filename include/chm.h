@@ -220,7 +220,7 @@ int chm_search_best_batch(chm_scenario *const *handles, int32_t n, uint32_t stra
  * around it, tight serving loops, harnesses that forbid hipMalloc): the same exhaustive search with the same
  * result, but every device word the call needs beyond the handle's tables - the per-chunk argmin words, the
  * feasibility counters, the winner's reroute ranks and transition time - lives in one fixed device array of
- * 65,792 bytes inside the library (one copy per GPU, held until the process ends) instead of buffers taken
+ * 65,664 bytes inside the library (one copy per GPU, held until the process ends) instead of buffers taken
  * from the allocator.  The call makes no hipMalloc, hipFree or other allocating call.  Always exhaustive
  * (chm_set_bounded_search is ignored).  Limits: at most 8,184 chunks of 2^idx_bits partitions (CHM_ERR_LIMIT
  * beyond; with the usual idx_bits of 30 that is every space chm_search_best accepts short of 2^43 partitions),

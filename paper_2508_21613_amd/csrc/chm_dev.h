@@ -112,6 +112,9 @@ struct FinishArgs {
   uint32_t n_slots, ways, stride;
   int32_t idx_bits;
   int32_t sweep_winner;        // 1: a rerouting winner's best vectors are found here by a sweep of one lane per stage
+  int32_t reset;               // 1: once read, the argmin words go back to "nothing found", the seven counters behind
+                               // them (the six summed here and the seeds' own) to 0 and the incumbent word behind those
+                               // to "none": the next search with the same layout starts without a fill kernel
   int32_t strategy[FINISH_MAX_SLOTS];
   uint64_t part_first[FINISH_MAX_SLOTS];
   uint64_t *out;               // FINISH_WORDS words

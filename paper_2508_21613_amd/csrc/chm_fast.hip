@@ -1228,38 +1228,50 @@ __device__ __forceinline__ uint32_t pair_min(const uint32_t (&A)[CAP + 1], const
   return m;
 }
 
+// pair_min for every remaining sum REM..0, stored to the lane's column of an LDS table
+template <int REM, int CAP>
+__device__ __forceinline__ void pair_minima(const uint32_t (&A)[CAP + 1], const uint32_t (&B)[CAP + 1], uint32_t (*table)[BLOCK], int tid) {
+  table[REM][tid] = pair_min<REM, CAP>(A, B);
+  if constexpr (REM > 0) pair_minima<REM - 1, CAP>(A, B, table, tid);
+}
+
 // Best penalty of one affected stage for the partitions of the fit list (one per lane) over one chunk of groups.
-// Every reroute vector is scored: max over its P products (extra micro-batches x peer stage time).  The vectors
-// of a group share their first P-3 entries (their largest product is taken once per group); the entry before the
-// last two steps through consecutive values (its product is carried by an add); for each of its values the last
-// two entries run over all pairs with the remaining sum, whose products come from two register tables built once
-// per lane (r x peer time, r = 0..CAP).  Consecutive values leave consecutive remaining sums, so the code for
-// all remaining sums is laid out in descending order and a group enters it at its first one.
-#define CHM_PAIR_SUMS(X) X(32) X(31) X(30) X(29) X(28) X(27) X(26) X(25) X(24) X(23) X(22) X(21) X(20) X(19) X(18) X(17) \
-  X(16) X(15) X(14) X(13) X(12) X(11) X(10) X(9) X(8) X(7) X(6) X(5) X(4) X(3) X(2) X(1)
+// The penalty of a reroute vector is the largest of its P products (extra micro-batches x peer stage time).  The
+// vectors of a group share their first P-3 entries, whose largest product is taken once per group.  The entry
+// before the last two steps through consecutive values (its product is carried by an add); for each of its values
+// the last two entries run over all pairs with the remaining sum, and the least of the larger of their two
+// products depends on that sum alone: the 2*CAP+1 such minima are worked out once per lane (every pair scored
+// once, products from two register tables r x peer time, r = 0..CAP) and kept in the lane's column of an LDS
+// table.  A value of the stepping entry then costs one LDS read, one v_max3_u32, one v_min_u32 and one add for
+// all vectors that share it.  All control flow is uniform (descriptors come through scalar loads).
 template <int P, int CAP>
 __global__ void __launch_bounds__(BLOCK) k_sweep_groups(const uint32_t *__restrict__ groups, uint32_t n_groups, uint32_t groups_per_chunk,
                                                         const uint32_t *__restrict__ fit_list, const uint32_t *__restrict__ fit_count,
                                                         const uint32_t *__restrict__ weights, uint32_t *__restrict__ pen_best, int a) {
   static_assert(P >= 3 && P <= 8 && (CAP == 8 || CAP == 16), "three to eight peers, entries up to 8 or 16");
   constexpr int Q = P - 3;                            // shared entries per group
+  __shared__ uint32_t pairs[2 * CAP + 1][BLOCK];      // [remaining sum][lane]: read and written by its own lane only
   const uint32_t n_fit = *as_const(fit_count);
   if (blockIdx.x * BLOCK >= n_fit) return;            // uniform: this block has no partition
+  const int tid = threadIdx.x;
   const uint32_t slot = blockIdx.x * BLOCK + threadIdx.x;
   const bool live = slot < n_fit;
   const uint32_t part = fit_list[live ? slot : n_fit - 1];    // lanes past the end redo the last partition
   uint32_t w[P];
 #pragma unroll
   for (int i = 0; i < P; ++i) w[i] = weights[(size_t)part * (DEV_MAX_AFF * 8) + a * 8 + i];
-  uint32_t A[CAP + 1], B[CAP + 1];
-  A[0] = 0;
-  B[0] = 0;
-#pragma unroll
-  for (int r = 1; r <= CAP; ++r) { A[r] = A[r - 1] + w[P - 2]; B[r] = B[r - 1] + w[P - 1]; }
-  const uint32_t wv = w[P - 3];
   const uint32_t first = blockIdx.y * groups_per_chunk;
   const uint32_t n = first >= n_groups ? 0u : (n_groups - first < groups_per_chunk ? n_groups - first : groups_per_chunk);
   if (n == 0) return;
+  {
+    uint32_t A[CAP + 1], B[CAP + 1];
+    A[0] = 0;
+    B[0] = 0;
+#pragma unroll
+    for (int r = 1; r <= CAP; ++r) { A[r] = A[r - 1] + w[P - 2]; B[r] = B[r - 1] + w[P - 1]; }
+    pair_minima<2 * CAP, CAP>(A, B, pairs, tid);
+  }
+  const uint32_t wv = w[P - 3];
   const RowPtr tab = as_const(groups) + (size_t)first * 8;
   uint32_t best = 0xffffffffu;
   // the descriptor of the next group is fetched while the current one is swept
@@ -1277,37 +1289,22 @@ __global__ void __launch_bounds__(BLOCK) k_sweep_groups(const uint32_t *__restri
       const uint32_t v = __umul24(d[i], w[i]);
       pre = pre > v ? pre : v;
     }
-    uint32_t pv = __umul24(d[5], wv);                 // product of the stepping entry
-    uint32_t left = d[6];                             // values it still takes
-    const uint32_t rem2 = d[7] - d[5];                // what the last two entries add up to at its first value
-#define CHM_PAIR_CASE(R)                                                                      \
-  case R:                                                                                     \
-    if constexpr (R <= 2 * CAP) {                                                             \
-      const uint32_t m = pair_min<(R <= 2 * CAP ? R : 0), CAP>(A, B);                         \
-      uint32_t pen = pre > pv ? pre : pv;                                                     \
-      pen = pen > m ? pen : m;                                                                \
-      best = best < pen ? best : pen;                                                         \
-      pv += wv;                                                                               \
-      if (--left == 0) break;                                                                 \
-    }                                                                                         \
-    [[fallthrough]];
-    switch (rem2) {
-      CHM_PAIR_SUMS(CHM_PAIR_CASE)
-      case 0: {
-        const uint32_t m = pair_min<0, CAP>(A, B);
-        uint32_t pen = pre > pv ? pre : pv;
-        pen = pen > m ? pen : m;
-        best = best < pen ? best : pen;
-      } break;
-      default: break;
+    uint32_t pv = __umul24(d[5], wv);                 // product of the stepping entry at its first value
+    const uint32_t cnt = d[6];                        // values it takes
+    const uint32_t rem2 = d[7] - d[5];                // what the last two entries add up to at its first value (<= 2 * CAP)
+#pragma unroll 4
+    for (uint32_t r = 0; r < cnt; ++r) {
+      const uint32_t m = pairs[rem2 - r][tid];
+      uint32_t pen = pre > pv ? pre : pv;
+      pen = pen > m ? pen : m;
+      best = best < pen ? best : pen;
+      pv += wv;
     }
-#undef CHM_PAIR_CASE
 #pragma unroll
     for (int i = 0; i < 8; ++i) d[i] = nx[i];
   }
   if (live) atomicMin(&pen_best[(size_t)part * DEV_MAX_AFF + a], best);
 }
-#undef CHM_PAIR_SUMS
 
 // The least penalty of one affected stage without looking at the vectors one by one.  A vector r (r_i extra
 // micro-batches on peer i, r_i <= cap, sum = orphans) has penalty max_i r_i * w_i <= v exactly when r_i <=
@@ -2356,8 +2353,8 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
           compacted = true;
         }
         const uint32_t n_groups = t.grp_count[s];
-        // about 8192 workgroups in total, chunks of at least 16 groups
-        uint32_t chunks = std::max<uint32_t>(1, std::min<uint32_t>(8192 / bx + 1, n_groups / 16 + 1));
+        // about 8192 workgroups in total, chunks of at least 128 groups (a lane works out its pair minima once per chunk)
+        uint32_t chunks = std::max<uint32_t>(1, std::min<uint32_t>(8192 / bx + 1, n_groups / 128 + 1));
         chunks = std::min<uint32_t>(chunks, 65535);
         const uint32_t per_chunk = (n_groups + chunks - 1) / chunks;
         chunks = (n_groups + per_chunk - 1) / per_chunk;

@@ -61,10 +61,13 @@ struct chm_scenario {
   uint64_t *d_slots = nullptr;           // argmin words, one per launched chunk
   uint64_t *d_winner = nullptr;          // best reroute rank per affected stage
   uint64_t *d_xfer = nullptr;            // migration scheme: 8 bytes MiB to fetch + DEV_MAX_S bytes of stage indices
-  uint64_t *d_final = nullptr;           // result record of k_finish_search (FINISH_WORDS words)
+  uint64_t *d_result = nullptr;          // device-side address of h_pinned: k_finish_search writes its record straight there
   struct chm_search_state *search = nullptr;   // the search call in flight on this handle
   uint64_t *h_pinned = nullptr;          // pinned staging for the two small device-to-host copies
   uint32_t slot_words = 0;               // words d_slots has room for
+  // d_slots as the last finished search left it: 0 = unknown (a fill kernel runs first); n > 0 = the words a search
+  // of n chunks in the spread layout uses are in their initial state (k_finish_search put them back)
+  uint32_t slots_ready_for = 0;
   bool timing = false;
   int bounded = 0;              // chm_set_bounded_search: 0 off, 1 on, 2 on with seeds and enumeration at any size
   hipEvent_t ev[8] = {};
@@ -397,7 +400,6 @@ void release(chm_scenario *s) {
   for (auto &e : s->ev) if (e) (void)hipEventDestroy(e);
   for (auto &f : s->in_flight) if (f.event) (void)hipEventDestroy(f.event);
   if (s->h_pinned) pool_release(s->h_pinned);
-  if (s->d_final) pool_release(s->d_final);
   if (s->d_xfer) pool_release(s->d_xfer);
   if (s->d_winner) pool_release(s->d_winner);
   if (s->d_slots) pool_release(s->d_slots);
@@ -603,7 +605,9 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
   uint64_t *d_evaluated = d_count + 3 * c.chunk_words;
   uint64_t *d_seed_count = d_count + 6 * c.chunk_words;
   uint64_t *d_incumbent = d_count + 7 * c.chunk_words;
-  if (chmk_init_search(s->d_slots, c.key_words, 7 * c.chunk_words, incumbent0, st)) return CHM_ERR_HIP;
+  const bool ready = spread && incumbent0 == ~0ull && s->slots_ready_for == (uint32_t)c.slots.size();
+  s->slots_ready_for = 0;                          // until this call's own finish kernel is in the stream
+  if (!ready && chmk_init_search(s->d_slots, c.key_words, 7 * c.chunk_words, incumbent0, st)) return CHM_ERR_HIP;
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;
   int ev_i = 1;
@@ -660,9 +664,10 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
     f.n_slots = (uint32_t)c.slots.size(); f.ways = c.ways; f.stride = c.stride; f.idx_bits = s->idx_bits;
     f.sweep_winner = (!light && !(s->fast.split && s->fast.usable[2])) ? 1 : 0;
     for (size_t i = 0; i < c.slots.size(); ++i) { f.strategy[i] = c.slots[i].strategy; f.part_first[i] = c.slots[i].part_first; }
-    f.out = s->d_final;
+    f.out = s->d_result;                       // pinned host memory: no copy behind the kernel
+    f.reset = spread ? 1 : 0;
     if (chmk_finish_search(f, s->smax, st)) return CHM_ERR_HIP;
-    HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_final, FINISH_WORDS * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+    if (spread) s->slots_ready_for = (uint32_t)c.slots.size();
     c.device_finish = true;
     return CHM_OK;
   }
@@ -693,7 +698,7 @@ int collect_jobs(chm_scenario *s, chm_best *out, uint64_t *position, hipStream_t
   SearchCtx &c = s->search->ctx;
   if (c.empty) { nothing_found(out); return CHM_ERR_NO_FEASIBLE; }
   HIP_TRY(hipSetDevice(s->device));
-  if (!synced) HIP_TRY(hipStreamSynchronize(st));
+  if (!synced && hipStreamSynchronize(st) != hipSuccess) { s->slots_ready_for = 0; return CHM_ERR_HIP; }
   const bool light = c.light;
   int64_t best_cost = CHM_INFEASIBLE;
   int best_strategy = -1;
@@ -945,8 +950,8 @@ int upload_scenario(chm_scenario *s, chm_scenario **out) {
   s->slot_words = SLOT_WORDS;
   ok = ok && pool_take(s->d_winner, DEV_MAX_AFF * sizeof(uint64_t));
   ok = ok && pool_take(s->d_xfer, sizeof(uint64_t) + DEV_MAX_S);
-  ok = ok && pool_take(s->d_final, FINISH_WORDS * sizeof(uint64_t));
   ok = ok && pool_take_pinned(s->h_pinned, (size_t)SLOT_WORDS * sizeof(uint64_t));
+  ok = ok && hipHostGetDevicePointer((void **)&s->d_result, s->h_pinned, 0) == hipSuccess && s->d_result != nullptr;
   ok = ok && hipMemcpyAsync(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice, ls) == hipSuccess;
   ok = ok && hipMemcpyAsync(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice, ls) == hipSuccess;
   for (auto &e : s->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
@@ -1204,11 +1209,9 @@ enum {
   STATIC_KEY_WORDS = 8192,                                  // argmin words, counters and incumbent of one call
   STATIC_WINNER_AT = STATIC_KEY_WORDS,                      // DEV_MAX_AFF words: reroute ranks of the winner
   STATIC_XFER_AT = STATIC_WINNER_AT + DEV_MAX_AFF,          // 8 + DEV_MAX_S bytes: transition time / migration scheme
-  STATIC_FINAL_AT = STATIC_KEY_WORDS + 16,                  // FINISH_WORDS words: result record of the call
-  STATIC_WORDS = STATIC_KEY_WORDS + 32                      // 65,792 bytes
+  STATIC_WORDS = STATIC_KEY_WORDS + 16                      // 65,664 bytes
 };
-static_assert(STATIC_XFER_AT + 1 + DEV_MAX_S / 8 <= STATIC_FINAL_AT && STATIC_FINAL_AT + FINISH_WORDS <= STATIC_WORDS,
-              "layout of the static scratch");
+static_assert(STATIC_XFER_AT + 1 + DEV_MAX_S / 8 <= STATIC_WORDS, "layout of the static scratch");
 static __device__ __align__(256) uint64_t scratch[STATIC_WORDS];
 
 namespace {
@@ -1244,16 +1247,18 @@ extern "C" int chm_search_best_static(chm_scenario *s, uint32_t strategy_mask, c
   uint64_t *base = static_scratch(s->device);
   if (!base) return CHM_ERR_HIP;
   // the handle's own buffers step aside for the call
-  uint64_t *const own_slots = s->d_slots, *const own_winner = s->d_winner, *const own_xfer = s->d_xfer, *const own_final = s->d_final;
+  uint64_t *const own_slots = s->d_slots, *const own_winner = s->d_winner, *const own_xfer = s->d_xfer;
   const uint32_t own_words = s->slot_words;
+  const uint32_t own_ready = s->slots_ready_for;
+  s->slots_ready_for = 0;                            // the shared array is filled at the start of every call
   s->d_slots = base; s->slot_words = STATIC_KEY_WORDS;
   s->d_winner = base + STATIC_WINNER_AT;
   s->d_xfer = base + STATIC_XFER_AT;
-  s->d_final = base + STATIC_FINAL_AT;
   s->fast.penalty_by_capacity = false;
   StreamGuard guard(s, hip_stream);
   const int rc = guard.settled(run_jobs(s, jobs, out, nullptr, (hipStream_t)hip_stream, ~0ull, false));
-  s->d_slots = own_slots; s->slot_words = own_words; s->d_winner = own_winner; s->d_xfer = own_xfer; s->d_final = own_final;
+  s->d_slots = own_slots; s->slot_words = own_words; s->d_winner = own_winner; s->d_xfer = own_xfer;
+  s->slots_ready_for = own_ready;
   if (rc == CHM_ERR_LIMIT) nothing_found(out);
   return rc;
 }

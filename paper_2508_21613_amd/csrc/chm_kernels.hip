@@ -16,6 +16,7 @@
 // i.e. the value E[s+1] held before this round's forward sweep overwrote it.
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <type_traits>
 
 #include "chm_dev.h"
@@ -577,18 +578,37 @@ __global__ void __launch_bounds__(BLOCK) k_plan_transition(const DevScenario *sc
 // End of a search on the device: the winner among the argmin words of all launched chunks (lowest cost; among
 // equal costs the lowest strategy, then the lowest partition rank: the lowest plan index), the sums of the
 // feasibility counters, the winner's transition time and, for data rerouting, the ranks of its best reroute
-// vectors, gathered into one record that the host fetches with a single copy.  One workgroup.
+// vectors, gathered into one record (written straight to pinned host memory when the caller passes such a
+// pointer).  One workgroup.  The kernel sits on the critical path of every search, and a single lane chasing
+// table entries through global memory pays a microsecond per dependent load, so: all lanes first copy the part of
+// the scenario ahead of the binomial table into LDS (SMAX <= 16; the one-lane steps then read LDS), and the
+// winner's partition is unranked by the first wavefront together, one table column per digit held across the
+// lanes (all columns loaded up front, the digit found with a ballot).
 template <int SMAX>
 __global__ void __launch_bounds__(BLOCK) k_finish_search(FinishArgs a) {
+  constexpr bool STAGED = SMAX <= 16;
+  constexpr int HEAD_WORDS = (int)(offsetof(DevScenario, binom) / 8);      // 8-byte words ahead of the binomial table
   __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
   __shared__ int32_t rv_cols[DEV_MAX_D][BLOCK];
   __shared__ uint64_t keys[FINISH_MAX_SLOTS * FINISH_MAX_WAYS];
   __shared__ uint64_t counts[6 * FINISH_MAX_WAYS];
   __shared__ uint64_t win[3];                        // cost, strategy (~0: nothing found), partition rank
+  __shared__ uint64_t head[STAGED ? HEAD_WORDS : 1];
   const uint32_t chunk_words = a.ways * a.stride;
   const uint32_t t = threadIdx.x;
   if (t < a.n_slots * a.ways) keys[t] = a.slots[(size_t)(t / a.ways) * chunk_words + (size_t)(t % a.ways) * a.stride];
   if (t < 6 * a.ways) counts[t] = a.counters[(size_t)(t / a.ways) * chunk_words + (size_t)(t % a.ways) * a.stride];
+  if (STAGED) {
+    const uint64_t *src = (const uint64_t *)a.scn;
+    for (int i = (int)t; i < HEAD_WORDS; i += BLOCK) head[i] = src[i];
+  }
+  if (a.reset) {
+    // every word is rewritten by the lane that has just read it (the seventh counter and the incumbent are not read here)
+    uint64_t *slots = const_cast<uint64_t *>(a.slots), *counters = const_cast<uint64_t *>(a.counters);
+    if (t < a.n_slots * a.ways) slots[(size_t)(t / a.ways) * chunk_words + (size_t)(t % a.ways) * a.stride] = CHM_KEY_NONE;
+    if (t < 7 * a.ways) counters[(size_t)(t / a.ways) * chunk_words + (size_t)(t % a.ways) * a.stride] = 0;
+    if (t == 0) counters[(size_t)7 * chunk_words] = ~0ull;
+  }
   __syncthreads();
   if (t == 0) {
     uint64_t best_cost = ~0ull, best_part = 0;
@@ -619,17 +639,49 @@ __global__ void __launch_bounds__(BLOCK) k_finish_search(FinishArgs a) {
   if (win[1] == ~0ull) return;
   const int strategy = (int)win[1];
   const uint64_t part = win[2];
-  const DevScenario *scn = a.scn;
+  // what the one-lane steps read: the LDS copy (everything they touch lies ahead of the binomial table), else global
+  const DevScenario *scn = STAGED ? (const DevScenario *)head : a.scn;
   const DevFamily &fam = scn->fam[strategy];
+  const int k = fam.stages - 1, L = scn->L;
+  // ---- unranking by the first wavefront: lane x holds C(x, i) and C(x + 64, i) of every digit i
+  if (t < 64) {
+    uint64_t rem = part;
+    int hi = L - 2;                                  // the digit is the largest x <= hi with C(x, i) <= rem
+    for (int i0 = k; i0 >= 1; i0 -= 8) {             // eight digits' columns at a time: their loads are in flight together
+      uint64_t lo_col[8], hi_col[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 - u;
+        lo_col[u] = i >= 1 ? a.scn->binom[i][t] : 0;
+        hi_col[u] = i >= 1 ? a.scn->binom[i][t + 64] : 0;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int i = i0 - u;
+        if (i >= 1) {                                // uniform
+          const uint64_t m_hi = __builtin_amdgcn_ballot_w64(hi_col[u] <= rem && (int)t + 64 <= hi);
+          const uint64_t m_lo = __builtin_amdgcn_ballot_w64(lo_col[u] <= rem && (int)t <= hi);
+          // C(i - 1, i) = 0 <= rem and i - 1 <= hi always: some lane answers
+          const int x = m_hi ? 127 - __builtin_clzll(m_hi) : 63 - __builtin_clzll(m_lo);
+          const uint64_t taken = m_hi ? __shfl(hi_col[u], x - 64, 64) : __shfl(lo_col[u], x, 64);
+          rem -= taken;
+          hi = x - 1;
+          if (t == 0) { cut_cols[i][0] = x + 1; }
+          if (t < DEV_MAX_AFF) cut_cols[i][64 + t] = x + 1;
+        }
+      }
+    }
+    if (t == 0) { cut_cols[0][0] = 0; cut_cols[k + 1][0] = L; }
+    if (t < DEV_MAX_AFF) { cut_cols[0][64 + t] = 0; cut_cols[k + 1][64 + t] = L; }
+  }
+  __syncthreads();
   Cuts<SMAX> cuts{cut_cols, (int)t};
   if (t == 0) {
-    unrank_partition<SMAX>(scn, fam.stages - 1, part, cuts);
     int64_t t_step = 0, reconf = 0;
     a.out[FINISH_TRANS] = (uint64_t)(eval_base<SMAX, false>(scn, fam, cuts, &t_step, &reconf) ? reconf : (int64_t)-1);
   } else if (a.sweep_winner && strategy == 2 && t >= 64 && (int)(t - 64) < scn->n_aff) {
     // one lane per stage that lost nodes, in the second wavefront, beside the transition time
     const int st = (int)(t - 64);
-    unrank_partition<SMAX>(scn, fam.stages - 1, part, cuts);
     int64_t pen; uint64_t rk;
     sweep_stage<SMAX>(scn, cuts, st, rv_cols, &pen, &rk);
     a.out[FINISH_RR + st] = rk;
