@@ -2094,10 +2094,13 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   fl.runs = f->d_runs;
   fl.base_out = base_out;
   fl.weights_out = weights_out;
-  // Run length per lane.  Large spaces: about 30 workgroups per compute unit (six rounds of the five that are
-  // resident), which evens out the tail, with runs of at most 32 partitions.  Smaller spaces: runs of 4 as long
-  // as that still gives every resident wave slot (256 CUs x 5 workgroups x 256 lanes) a lane, then shorter.
-  const uint64_t lanes_balanced = 256ull * 30 * BLOCK, lanes_resident = 256ull * 5 * BLOCK;
+  // Run length per lane.  Runs of at most 32 partitions (longer ones leave too few workgroups to even out the
+  // tail: 62.9 M partitions then make about 30 workgroups per compute unit, six rounds of the five that are
+  // resident); spaces below 2^25 partitions get at least 16 workgroups per compute unit and correspondingly shorter
+  // runs (measured on 10 to 15 M partitions: unranking once per 10 to 15 partitions costs less than the idle tail
+  // of fewer, longer workgroups; runs of 5 to 7 were 1 to 8 % slower).  Small spaces: runs of 4 as long as that
+  // still gives every resident wave slot (256 CUs x 5 workgroups x 256 lanes) a lane, then shorter.
+  const uint64_t lanes_balanced = 256ull * 16 * BLOCK, lanes_resident = 256ull * 5 * BLOCK;
   uint64_t per = a.part_count / lanes_balanced;
   if (per < 4) per = std::min<uint64_t>(4, a.part_count / lanes_resident);
   per = std::max<uint64_t>(1, std::min<uint64_t>(per, 32));

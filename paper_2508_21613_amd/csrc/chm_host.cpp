@@ -77,6 +77,7 @@ struct chm_scenario {
   // replaced or released, so that neither needs a device-wide wait.
   struct InFlight { hipStream_t stream; hipEvent_t event; bool busy; } in_flight[4] = {};
   bool in_flight_overflow = false;       // more streams than slots: fall back to waiting for the device
+  hipEvent_t side_start = nullptr, side_done[4] = {};   // fork / join of the library's side streams (created on first use)
   FastState fast;                        // shape-specialised search path (chm_fast.hip)
 };
 
@@ -399,6 +400,8 @@ void release(chm_scenario *s) {
   fast_release(&s->fast);
   for (auto &e : s->ev) if (e) (void)hipEventDestroy(e);
   for (auto &f : s->in_flight) if (f.event) (void)hipEventDestroy(f.event);
+  if (s->side_start) (void)hipEventDestroy(s->side_start);
+  for (auto &e : s->side_done) if (e) (void)hipEventDestroy(e);
   if (s->h_pinned) pool_release(s->h_pinned);
   if (s->d_xfer) pool_release(s->d_xfer);
   if (s->d_winner) pool_release(s->d_winner);
@@ -545,6 +548,46 @@ uint64_t rank_of_cuts(const chm_scenario *s, int k, const uint8_t *cuts) {
   return rank;
 }
 
+// The library's side streams (per device, created on first use, default priority, never destroyed).  The handles
+// of a batched search are dealt out over them, so that the last workgroups of one handle's kernels run beside the
+// first ones of the next handle's instead of leaving the device partly idle at every kernel boundary (the kernels
+// of a failure sweep take 0.1 to 0.4 ms each; the three strategies of one large search gain nothing from it:
+// measured).  The events that tie the side streams to the caller's stream belong to the batch's first handle.
+enum { SIDE_STREAMS = 4, BATCH_MIN = 8 };
+struct SideStreams { hipStream_t stream[SIDE_STREAMS]; bool ok; };
+SideStreams *side_streams_of(int device) {
+  enum { MAX_DEVICES = 64 };
+  static std::mutex lock;
+  static SideStreams all[MAX_DEVICES] = {};
+  if (device < 0 || device >= MAX_DEVICES) return nullptr;
+  std::lock_guard<std::mutex> hold(lock);
+  SideStreams &l = all[device];
+  if (!l.ok) {
+    bool ok = true;
+    for (int k = 0; k < SIDE_STREAMS && ok; ++k) ok = hipStreamCreateWithFlags(&l.stream[k], hipStreamNonBlocking) == hipSuccess;
+    l.ok = ok;
+  }
+  return l.ok ? &l : nullptr;
+}
+
+// fork: the side streams start behind what is in `st` now; join: `st` continues behind what is in them now
+bool side_fork(chm_scenario *s, SideStreams *side, hipStream_t st) {
+  bool ok = true;
+  if (!s->side_start) {
+    ok = hipEventCreateWithFlags(&s->side_start, hipEventDisableTiming) == hipSuccess;
+    for (int k = 0; k < SIDE_STREAMS && ok; ++k) ok = hipEventCreateWithFlags(&s->side_done[k], hipEventDisableTiming) == hipSuccess;
+  }
+  ok = ok && hipEventRecord(s->side_start, st) == hipSuccess;
+  for (int k = 0; k < SIDE_STREAMS && ok; ++k) ok = hipStreamWaitEvent(side->stream[k], s->side_start, 0) == hipSuccess;
+  return ok;
+}
+bool side_join(chm_scenario *s, SideStreams *side, hipStream_t st) {
+  bool ok = true;
+  for (int k = 0; k < SIDE_STREAMS; ++k)
+    ok = hipEventRecord(s->side_done[k], side->stream[k]) == hipSuccess && hipStreamWaitEvent(st, s->side_done[k], 0) == hipSuccess && ok;
+  return ok;
+}
+
 // One search call in flight on a handle: what launch_jobs set up and collect_jobs needs.
 struct SearchCtx {
   std::vector<Job> jobs;                 // (copies: a batch keeps them across the launches of other handles)
@@ -612,8 +655,8 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
   size_t si = 0;
   int ev_i = 1;
   bool plain = true;                         // range jobs only: the device can pick the winner
+  for (const Job &j : jobs) plain = plain && !j.ranks && !j.cuts && !j.cand;
   for (const Job &j : jobs) {
-    plain = plain && !j.ranks && !j.cuts && !j.cand;
     for (uint64_t done = 0; done < j.count; done += chunk, ++si) {
       SearchLaunch a;
       a.scn = s->d_scn; a.comp = s->d_comp; a.strategy = j.strategy;
@@ -1154,21 +1197,34 @@ extern "C" int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best
 extern "C" int chm_search_best_batch(chm_scenario *const *handles, int32_t n, uint32_t strategy_mask, chm_best *outs,
                                      int32_t *codes, void *hip_stream) {
   if (n < 0 || (n > 0 && (!handles || !outs || !codes))) return CHM_ERR_ARG;
+  if (n == 0) return CHM_OK;
   std::vector<const chm_scenario *> seen(handles, handles + n);
   std::sort(seen.begin(), seen.end());
   for (int i = 0; i < n; ++i)
     if (!seen[i] || (i > 0 && seen[i] == seen[i - 1]) || seen[i]->device != seen[0]->device) return CHM_ERR_ARG;
   hipStream_t st = (hipStream_t)hip_stream;
+  HIP_TRY(hipSetDevice(handles[0]->device));
+  // a large batch runs on the library's side streams, which start behind the work already in the caller's stream
+  // and which the caller's stream is made to wait for at the end (through the events of the first handle)
+  SideStreams *side = n >= BATCH_MIN ? side_streams_of(handles[0]->device) : nullptr;
+  if (side && !side_fork(handles[0], side, st)) return CHM_ERR_HIP;
+  auto stream_of = [&](int i) { return side ? side->stream[i % SIDE_STREAMS] : st; };
   std::vector<char> pending(n, 0);
-  bool any_pending = false;
-  // whatever way the call ends, every handle whose result is not final leaves its stream marked as busy
-  struct MarkAll {
-    chm_scenario *const *h; int32_t n; const int32_t *codes; hipStream_t st;
-    ~MarkAll() {
+  // whatever way the call ends: the caller's stream waits for the side streams, and every handle whose result
+  // is not final leaves the caller's stream marked as busy
+  struct Wrap {
+    chm_scenario *const *h; int32_t n; const int32_t *codes; hipStream_t st; SideStreams *side;
+    bool join() {
+      const bool ok = side ? side_join(h[0], side, st) : true;
+      side = nullptr;
+      return ok;
+    }
+    ~Wrap() {
+      (void)join();
       for (int i = 0; i < n; ++i)
         if (codes[i] != CHM_OK && codes[i] != CHM_ERR_NO_FEASIBLE && codes[i] != CHM_ERR_UNRECOVERABLE) mark_in_flight(h[i], st);
     }
-  } mark_all{handles, n, codes, st};
+  } wrap{handles, n, codes, st, side};
   for (int i = 0; i < n; ++i) codes[i] = CHM_ERR_HIP;          // until the handle's search has been collected
   for (int i = 0; i < n; ++i) {
     chm_scenario *s = handles[i];
@@ -1180,21 +1236,21 @@ extern "C" int chm_search_best_batch(chm_scenario *const *handles, int32_t n, ui
     if (jobs.empty()) { nothing_found(&outs[i]); codes[i] = CHM_ERR_UNRECOVERABLE; continue; }
     // searches that need the host between two of their passes (a bounded search that enumerates candidates) run
     // on their own; all others are launched now and collected after one wait for the whole batch
-    if (s->bounded && any_enumerable(s, jobs)) { codes[i] = run_search(s, jobs, &outs[i], nullptr, st); continue; }
+    if (s->bounded && any_enumerable(s, jobs)) { codes[i] = run_search(s, jobs, &outs[i], nullptr, stream_of(i)); continue; }
     s->fast.penalty_by_capacity = s->bounded != 0;
     if (s->bounded) {
       std::vector<Job> all = make_seeds(s, jobs);
       all.insert(all.end(), jobs.begin(), jobs.end());
       jobs.swap(all);
     }
-    codes[i] = launch_jobs(s, jobs, true, st, ~0ull, s->bounded != 0, false);
+    codes[i] = launch_jobs(s, jobs, true, stream_of(i), ~0ull, s->bounded != 0, false);
     if (codes[i] != CHM_OK) { nothing_found(&outs[i]); continue; }
-    if (s->search->ctx.device_finish || s->search->ctx.empty) { pending[i] = 1; any_pending = true; }
-    else codes[i] = collect_jobs(s, &outs[i], nullptr, st, false);
+    if (s->search->ctx.device_finish || s->search->ctx.empty) { pending[i] = 1; codes[i] = CHM_ERR_HIP; }
+    else codes[i] = collect_jobs(s, &outs[i], nullptr, stream_of(i), false);
   }
-  if (any_pending && hipStreamSynchronize(st) != hipSuccess) return CHM_ERR_HIP;
+  if (!wrap.join() || hipStreamSynchronize(st) != hipSuccess) return CHM_ERR_HIP;
   for (int i = 0; i < n; ++i)
-    if (pending[i]) codes[i] = collect_jobs(handles[i], &outs[i], nullptr, st, true);
+    if (pending[i]) codes[i] = collect_jobs(handles[i], &outs[i], nullptr, stream_of(i), true);
   for (int i = 0; i < n; ++i)
     if (codes[i] == CHM_ERR_HIP || codes[i] == CHM_ERR_ARG) return codes[i];
   return CHM_OK;
