@@ -58,6 +58,30 @@ def algorithmic_ops(fam, feasible):
     return fam["n_part"] * light + feasible * heavy, light, heavy
 
 
+def shared_prefix_ops(peers, total, cap):
+    """Operations of one partition's reroute sweep of one stage in the formulation the large-space sweep kernel uses
+    (the vectors of a group share the largest product of their first peers - 3 entries; per value of the entry before
+    the last two one add, two max and one min; the least larger-product of the last two entries per remaining sum
+    from a table built once, one max and one min per pair): the count that kernel's executed instructions are close to."""
+    cap = min(cap, total) if cap > 0 else total
+    q = peers - 3
+    if q < 0:
+        return None
+    # number of ways to fill the first q entries (each 0..cap) with a given sum
+    ways = [1] + [0] * total
+    for _ in range(q):
+        ways = [sum(ways[t - v] for v in range(0, min(cap, t) + 1)) for t in range(total + 1)]
+    groups = runs = 0
+    for used, w in enumerate(ways):
+        rest = total - used                                   # for the last three entries
+        lo, hi = max(0, rest - 2 * cap), min(cap, rest)
+        if w and lo <= hi:
+            groups += w
+            runs += w * (hi - lo + 1)
+    pairs = sum(min(cap, r) - max(0, r - cap) + 1 for r in range(2 * cap + 1))
+    return groups * max(0, 2 * q - 1) + runs * 4 + pairs * 2 + 2 * cap
+
+
 def copy_calibration():
     """one plain 1 GiB device copy: the known-size reference for scaling FETCH_SIZE / WRITE_SIZE"""
     import torch
@@ -625,6 +649,15 @@ def bench_search(args, B, synth, name):
     note("%s: measured VALU rates (T lane-ops/s): %s" % (name, probes))
     sc = scenarios[0]
     best = plans[0][1]
+    shared = None
+    if dom == 2 and fam0 and sum(fam0[0]["R"]) > 4096 and all(p >= 3 for p in fam0[0]["peers"]):
+        # large reroute spaces are swept group by group (shared leading entries): the same figure with the operations
+        # of that formulation in place of `peers` operations per reroute vector
+        per_part = [shared_prefix_ops(p, t, sc0_cap) for p, t, sc0_cap in
+                    zip(fam0[0]["peers"], fam0[0]["orphans"], [scenarios[0].get("reroute_cap", 0)] * len(fam0[0]["peers"]))]
+        if all(x is not None for x in per_part):
+            base_ops = algorithmic_ops(dict(fam0[0], R=[0] * len(fam0[0]["R"])), feasible[dom] / len(handles))[0]
+            shared = (base_ops + feasible[dom] / len(handles) * sum(per_part)) * len(handles)
     roofline = {"bound": "alu", "kernel": "search, strategy %d" % dom, "achieved": achieved,
                 "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS,
                 "frac_is": "algorithmic int32 lane operations per second (the method's max/add/compare count, whatever the kernel "
@@ -640,6 +673,14 @@ def bench_search(args, B, synth, name):
                 "feasible_partitions": float(feasible[dom]),
                 "algorithmic_ops_per_feasible_partition": ops_light + ops_heavy,
                 "algorithmic_ops_per_infeasible_partition": ops_light}
+    if shared is not None:
+        a2 = shared / (fam_ms[dom] * 1e-3) / 1e12
+        roofline["achieved_shared_prefix_accounting"] = a2
+        roofline["frac_shared_prefix_accounting"] = a2 / ALU_PEAK_TOPS
+        roofline["frac_shared_prefix_accounting_is"] = (
+            "`frac` charges every reroute vector its `peers` operations (the accounting of all workloads); this kernel takes the "
+            "largest product of the leading entries once per group of vectors and the best pair of the last two entries from a "
+            "table, so it needs far fewer: with the operations of that formulation as the numerator the fraction is this one")
     if name == "config2" and not args.transfer_assign:
         per_part = CONFIG2_EXECUTED_LANE_INSTR_PER_PARTITION[dom]
         executed = per_part * fam0[0]["n_part"] / (fam_ms[dom] * 1e-3) / 1e12
@@ -697,7 +738,8 @@ def summary(rec):
     out = {k: rec[k] for k in keep if k in rec and rec[k] is not None}
     out["workload"] = rec["config"]["workload"]
     r = rec["roofline"]
-    out["roofline"] = {k: r[k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "kernel_ms") if k in r}
+    out["roofline"] = {k: r[k] for k in ("bound", "kernel", "achieved", "peak", "unit", "frac", "kernel_ms", "achieved_shared_prefix_accounting",
+                                         "frac_shared_prefix_accounting", "frac_shared_prefix_accounting_is") if k in r}
     if rec.get("bounded_search"):
         b = rec["bounded_search"]
         out["bounded_search"] = {k: b[k] for k in ("search_ms_all_scenarios", "bounded_ms_per_step", "time_to_best_plan_ms",

@@ -10,7 +10,7 @@ enum {
   FAST_SPLIT_R = 1 << 23,    // up to this many per stage the vectors are tabulated and swept by a kernel of their own
   FAST_SUB = 1 << 20,        // partitions per pass of the split and scoring paths (bounds their scratch memory: 152 MB;
                              // the scratch is sized for the passes actually asked for and grows when needed)
-  LIST_SUB = 1 << 22,        // list entries per filter + search pass of explicit lists (scratch: 80 MB)
+  LIST_SUB = 1 << 24,        // list entries per filter + search pass of explicit lists (scratch: 336 MB when a list is that long)
   LIST_FIRST = 1 << 16       // entries of the first pass of a bounded list search
 };
 
@@ -107,6 +107,7 @@ struct FastState {
   void *d_cut_list = nullptr;               // [entry] cut positions of the entries that fit in memory, 16 bytes each
   uint32_t *d_cut_pos = nullptr;            // [entry] their list positions
   uint32_t *d_cut_count = nullptr;          // [workgroup region] how many of its slots are filled
+  uint32_t list_capacity = 0;               // entries the three have room for
   // scratch of the candidate path of the bounded search; grown to what a search needs
   void *d_cand_list = nullptr;              // [candidate] cut positions, 16 bytes each
   uint32_t *d_cand_pos = nullptr;           // [candidate] its index

@@ -2027,19 +2027,27 @@ bool ensure_scratch(FastState *f, uint64_t parts) {
   return ok;
 }
 
-bool ensure_list_scratch(FastState *f) {
-  if (f->d_cut_list && f->d_cut_pos && f->d_cut_count) return true;
-  bool ok = true;
-  if (!f->d_cut_list) ok = ok && pool_take(f->d_cut_list, (size_t)LIST_SUB * sizeof(uint4));
-  if (!f->d_cut_pos) ok = ok && pool_take(f->d_cut_pos, (size_t)LIST_SUB * sizeof(uint32_t));
-  if (!f->d_cut_count) ok = ok && pool_take(f->d_cut_count, (size_t)(LIST_SUB / (BLOCK * FILTER_TILES_BOUNDED)) * sizeof(uint32_t));
+// scratch of one pass over an explicit list of `entries` entries (at most LIST_SUB); grows when a longer pass comes
+bool ensure_list_scratch(FastState *f, uint32_t entries) {
+  uint32_t need = 1u << 16;
+  while (need < entries) need <<= 1;
+  if (f->d_cut_list && f->d_cut_pos && f->d_cut_count && f->list_capacity >= need) return true;
+  fast_quiesce(f);                                           // what is replaced may still be read by an asynchronous call
+  if (f->d_cut_count) pool_release(f->d_cut_count);
+  if (f->d_cut_pos) pool_release(f->d_cut_pos);
+  if (f->d_cut_list) pool_release(f->d_cut_list);
+  f->d_cut_count = nullptr; f->d_cut_pos = nullptr; f->d_cut_list = nullptr; f->list_capacity = 0;
+  bool ok = pool_take(f->d_cut_list, (size_t)need * sizeof(uint4));
+  ok = ok && pool_take(f->d_cut_pos, (size_t)need * sizeof(uint32_t));
+  ok = ok && pool_take(f->d_cut_count, (size_t)(need / (BLOCK * FILTER_TILES_BOUNDED) + 1) * sizeof(uint32_t));
+  if (ok) f->list_capacity = need;
   return ok;
 }
 
 // Explicit list of partition ranks: per pass of LIST_SUB entries, filter + compaction, then the search kernel
 // over the entries that fit.
 int launch_list(FastState *f, const DevScenario &h, const SearchLaunch &a, hipStream_t st) {
-  if (!ensure_list_scratch(f)) return -1;
+  if (!ensure_list_scratch(f, std::min<uint32_t>(a.part_count, LIST_SUB))) return -1;
   const int sp = h.fam[a.strategy].stages;
   // a bounded search prunes the later passes against the best cost of the earlier ones: a short first pass
   // makes one known early
@@ -2535,7 +2543,7 @@ void fast_release(FastState *f) {
   if (f->d_cut_count) pool_release(f->d_cut_count);
   if (f->d_cut_pos) pool_release(f->d_cut_pos);
   if (f->d_cut_list) pool_release(f->d_cut_list);
-  f->d_cut_count = nullptr; f->d_cut_pos = nullptr; f->d_cut_list = nullptr;
+  f->d_cut_count = nullptr; f->d_cut_pos = nullptr; f->d_cut_list = nullptr; f->list_capacity = 0;
   if (f->d_rowkey) pool_release(f->d_rowkey);
   if (f->d_fit_count) pool_release(f->d_fit_count);
   if (f->d_fit_list) pool_release(f->d_fit_list);

@@ -12,8 +12,8 @@
 
 namespace {
 
-constexpr size_t KEEP_BLOCK_MAX = 256u << 20;                 // larger blocks are never kept
-constexpr size_t KEEP_TOTAL_MAX[2] = {1024u << 20, 96u << 20};   // bytes kept over all devices: device memory, pinned host memory
+constexpr size_t KEEP_BLOCK_MAX = 512u << 20;                 // larger blocks are never kept
+constexpr size_t KEEP_TOTAL_MAX[2] = {2048ull << 20, 96u << 20};   // bytes kept over all devices: device memory, pinned host memory
 
 struct Block { int device; bool pinned; size_t size; };
 

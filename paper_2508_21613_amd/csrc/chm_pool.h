@@ -3,7 +3,7 @@
 // A scenario handle owns about a dozen buffers; hipMalloc, hipHostMalloc and hipFree cost tens to hundreds
 // of microseconds each, which is as much as a whole bounded search, and hipFree waits for the whole device.
 // Blocks released by one handle are kept (per device, by size class) and handed to the next; what is kept
-// is bounded (1 GiB of device memory, 96 MiB of pinned memory, blocks of at most 256 MiB), the rest goes back
+// is bounded (2 GiB of device memory, 96 MiB of pinned memory, blocks of at most 512 MiB), the rest goes back
 // to the runtime.  Thread-safe.
 #ifndef CHM_POOL_H
 #define CHM_POOL_H
