@@ -29,9 +29,9 @@ ALU_PEAK_TOPS = 256 * 4 * 32 * 2.4e9 / 1e12
 # From the rocprofv3 --pmc runs summarised in profiles/search_kernels_config2.md (counters cannot be read from
 # inside this process), per strategy kernel of config 2:
 # HBM bytes per launch = FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB (factors from the 1 GiB calibration copy of the same runs)
-CONFIG2_TRAFFIC_BYTES = {0: (178.9 * 2.0 + 4302) * 1024, 1: (133.0 * 2.0 + 510.5) * 1024, 2: (182.2 * 2.0 + 490.6) * 1024}
+CONFIG2_TRAFFIC_BYTES = {0: (163.9 * 2.0 + 447.6) * 1024, 1: (125.0 * 2.0 + 256.4) * 1024, 2: (186.6 * 2.0 + 475.4) * 1024}
 # executed VALU lane-instructions per partition = SQ_INSTS_VALU x 64 / partitions of the family
-CONFIG2_EXECUTED_LANE_INSTR_PER_PARTITION = {0: 560.0, 1: 469.0, 2: 755.0}
+CONFIG2_EXECUTED_LANE_INSTR_PER_PARTITION = {0: 558.0, 1: 419.0, 2: 754.0}
 
 
 def note(msg):
