@@ -211,6 +211,20 @@ def bench_replan(args, B, synth):
     bounded = {"time_to_best_plan_ms": ms_b, "search_kernels_ms": st_b["search_ms"], "splits_evaluated_in_full": st_b["splits_evaluated"],
                "same_plan_as_exhaustive": bool(plan_b == plan)}
     note("bounded re-planning: %s" % bounded)
+    # the cached plans for the loss of 1 .. 3 nodes (chm_replan_table) against three calls of chm_replan
+    order = dict(rp, failed_nodes=list(rp["failed_nodes"]) + [13, 20])
+    with torch.cuda.stream(stream):
+        B.replan_table(order, 3, stream=stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        table = B.replan_table(order, 3, stream=stream)
+        t_table = (time.perf_counter() - t0) * 1e3
+        t0 = time.perf_counter()
+        single = [B.replan(dict(order, failed_nodes=order["failed_nodes"][:n]), stream=stream) for n in (1, 2, 3)]
+        t_single = (time.perf_counter() - t0) * 1e3
+    table_rec = {"failure_order": order["failed_nodes"], "table_ms": t_table, "entry_by_entry_ms": t_single, "same_plans": bool(table == single),
+                 "dp_per_entry": [p.get("dp") for p in table]}
+    note("re-plan table for the loss of 1..3 nodes: %s" % table_rec)
     out = {"metric": METRIC,
            "value": st["splits_scored"] / (ms * 1e-3), "unit": "plans/s", "n_gpus": 1, "steps": args.steps,
            "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -219,7 +233,7 @@ def bench_replan(args, B, synth):
                                   "every contiguous split per pipeline length", "splits_scored_per_step": st["splits_scored"],
                       "splits_feasible": st["splits_feasible"], "candidates": plan["n_candidates"]},
            "time_to_best_plan_ms": ms, "search_kernels_ms": search_ms, "assignment_kernels_ms": assign_ms,
-           "bounded_search": bounded, "best": plan,
+           "bounded_search": bounded, "replan_table_1_to_3": table_rec, "best": plan,
            "roofline": {"bound": "alu", "kernel": "split search (all pipeline lengths)", "achieved": achieved,
                         "peak": ALU_PEAK_TOPS, "unit": "TOP/s", "frac": achieved / ALU_PEAK_TOPS, "traffic": None,
                         "kernel_ms": search_ms, "algorithmic_ops_per_launch": st["algorithmic_ops"]}}
@@ -734,7 +748,7 @@ def summary(rec):
     """what the `workloads` block keeps of a workload's record"""
     keep = ("value", "unit", "steps", "ms_per_step", "time_to_best_plan_ms", "time_to_best_plan_bounded_ms", "partition_evals_per_s",
             "recurrence_cells_per_s", "kernel_ms_per_strategy", "ms_per_strategy", "search_kernels_ms", "per_call_loop_ms",
-            "plan_cache_file", "kernels_one_after_the_other_ms", "cpu_baseline")
+            "plan_cache_file", "kernels_one_after_the_other_ms", "replan_table_1_to_3", "cpu_baseline")
     out = {k: rec[k] for k in keep if k in rec and rec[k] is not None}
     out["workload"] = rec["config"]["workload"]
     r = rec["roofline"]

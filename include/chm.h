@@ -357,6 +357,15 @@ typedef struct {
  * No candidate / nothing fits is not an error: CHM_OK with out->found = 0. */
 int chm_replan(const chm_replan_desc *desc, chm_replan_plan *out, void *hip_stream);
 
+/* The re-plans for the loss of 1 .. k nodes (Planner, overhead paragraph: the optimal plans for potential failure
+ * scenarios are computed ahead of time and looked up when a fault occurs; Algorithm 1, get_parallel_strategy: the
+ * loop over failure counts).  desc->failed_nodes gives the order in which the nodes are taken to fail; plans[i-1]
+ * (host array of k, k <= desc->n_failed) receives what chm_replan returns when the first i of them have failed.
+ * The best split of the layers over a pipeline of given length and micro-batch count is searched once for the whole
+ * table, so an entry's work accounting (splits_scored ...) covers only the searches no earlier entry has made.
+ * Errors as chm_replan; synchronises hip_stream. */
+int chm_replan_table(const chm_replan_desc *desc, int32_t k, chm_replan_plan *plans, void *hip_stream);
+
 /* Ranks two plans by the objective of the "Optimization Problem" paragraph, throughput x effective time
  * ratio = B / t_step x (H - t_trans) / H for the same global batch B and time H between two faults: returns
  * 1 when plan a is better, -1 when plan b is better, 0 on an exact tie (compared by cross-multiplication in

@@ -18,7 +18,7 @@ INFEASIBLE = (1 << 63) - 1
 
 SYMBOLS = ["chm_load_scenario", "chm_plan_space", "chm_score_plans", "chm_score_ranks", "chm_search_best", "chm_search_best_static", "chm_search_best_batch", "chm_kernel_selection",
            "chm_search_range", "chm_search_ranks", "chm_search_cuts", "chm_rank_partitions", "chm_decode_plan", "chm_set_timing", "chm_set_filter_compaction", "chm_set_bounded_search", "chm_get_timing", "chm_family_classes",
-           "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
+           "chm_reroute_shape", "chm_transfer_plan", "chm_replan", "chm_replan_table", "chm_compare_objective", "chm_valu_probe", "chm_free_scenario",
            "chm_strerror"]
 
 
@@ -131,6 +131,7 @@ def lib():
         L.chm_transfer_plan.argtypes = [vp, C.c_uint64, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_uint8 * 32),
                                         C.POINTER(C.c_uint8 * 32), C.POINTER(C.c_int64), vp]
         L.chm_replan.argtypes = [C.POINTER(ReplanDesc), C.POINTER(ReplanPlan), vp]
+        L.chm_replan_table.argtypes = [C.POINTER(ReplanDesc), C.c_int32, C.POINTER(ReplanPlan), vp]
         L.chm_compare_objective.argtypes = [C.c_int64] * 5
         L.chm_valu_probe.argtypes = [C.c_int32, C.c_uint32, C.POINTER(C.c_double), vp]
         L.chm_free_scenario.argtypes = [vp]
@@ -185,10 +186,8 @@ def compare_objective(a, b, horizon_us):
     return rc
 
 
-def replan(rp, stream=None, with_stats=False):
-    """chm_replan: search over DP/PP degrees for the nodes that survive (Algorithm 1).  `rp` is a dict with the
-    fields of chm_replan_desc; returns a dict with the plan fields of chm_replan_plan (and, with_stats, a second
-    dict with the work accounting of the call)."""
+def _replan_desc(rp):
+    """chm_replan_desc of a re-planning dict, and the arrays it points into"""
     keep = []
     d = ReplanDesc()
     d.L = rp["L"]
@@ -208,13 +207,34 @@ def replan(rp, stream=None, with_stats=False):
         setattr(d, name, int(rp[name]))
     d.allreduce_us = int(rp.get("allreduce_us", 0))
     d.bounded_search = int(rp.get("bounded_search", 0))
+    return d, keep
+
+
+def _replan_stats(p):
+    return {"splits_scored": int(p.splits_scored), "splits_feasible": int(p.splits_feasible),
+            "splits_evaluated": int(p.splits_evaluated),
+            "algorithmic_ops": float(p.algorithmic_ops), "search_ms": float(p.search_ms), "assign_ms": float(p.assign_ms)}
+
+
+def replan(rp, stream=None, with_stats=False):
+    """chm_replan: search over DP/PP degrees for the nodes that survive (Algorithm 1).  `rp` is a dict with the
+    fields of chm_replan_desc; returns a dict with the plan fields of chm_replan_plan (and, with_stats, a second
+    dict with the work accounting of the call)."""
+    d, keep = _replan_desc(rp)
     p = ReplanPlan()
     _check(lib().chm_replan(C.byref(d), C.byref(p), _stream_ptr(stream)))
-    stats = {"splits_scored": int(p.splits_scored), "splits_feasible": int(p.splits_feasible),
-             "splits_evaluated": int(p.splits_evaluated),
-             "algorithmic_ops": float(p.algorithmic_ops), "search_ms": float(p.search_ms), "assign_ms": float(p.assign_ms)}
     plan = _replan_dict(p)
-    return (plan, stats) if with_stats else plan
+    return (plan, _replan_stats(p)) if with_stats else plan
+
+
+def replan_table(rp, k=None, stream=None, with_stats=False):
+    """chm_replan_table: the re-plans after the first 1 .. k nodes of rp["failed_nodes"] have failed"""
+    d, keep = _replan_desc(rp)
+    k = d.n_failed if k is None else int(k)
+    plans = (ReplanPlan * max(k, 1))()
+    _check(lib().chm_replan_table(C.byref(d), k, plans, _stream_ptr(stream)))
+    out = [_replan_dict(plans[i]) for i in range(k)]
+    return (out, [_replan_stats(plans[i]) for i in range(k)]) if with_stats else out
 
 
 def _replan_dict(p):

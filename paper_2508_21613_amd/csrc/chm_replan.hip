@@ -172,7 +172,32 @@ extern "C" int chm_compare_objective(int64_t t_step_a_us, int64_t t_trans_a_us, 
   return lhs > rhs ? 1 : (lhs < rhs ? -1 : 0);
 }
 
+namespace {
+typedef std::map<std::pair<int, int>, SplitResult> SplitCache;   // (stages, micro-batches) -> best split of the layers
+int replan_core(const chm_replan_desc *d, chm_replan_plan *out, void *hip_stream, SplitCache &best_split);
+}  // namespace
+
 extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *hip_stream) {
+  SplitCache cache;
+  return replan_core(d, out, hip_stream, cache);
+}
+
+extern "C" int chm_replan_table(const chm_replan_desc *d, int32_t k, chm_replan_plan *plans, void *hip_stream) {
+  if (!d || !plans || k < 0 || k > d->n_failed) return CHM_ERR_ARG;
+  // The tables, ranges and limits are the same for every entry, so the best split of the layers over a pipeline
+  // of given length and micro-batch count is searched once for the whole table.
+  SplitCache cache;
+  for (int32_t i = 1; i <= k; ++i) {
+    chm_replan_desc di = *d;
+    di.n_failed = i;
+    const int rc = replan_core(&di, &plans[i - 1], hip_stream, cache);
+    if (rc) return rc;
+  }
+  return CHM_OK;
+}
+
+namespace {
+int replan_core(const chm_replan_desc *d, chm_replan_plan *out, void *hip_stream, SplitCache &best_split) {
   if (!out) return CHM_ERR_ARG;
   memset(out, 0, sizeof(*out));
   int rc = check(d);
@@ -219,7 +244,6 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
   uint64_t splits_scored = 0, splits_feasible = 0, splits_evaluated = 0;
   double algorithmic_ops = 0;
   float search_ms = 0, assign_ms = 0;
-  std::map<std::pair<int, int>, SplitResult> best_split;      // (stages, micro-batches) -> best split of the layers
   bool have = false;
   __int128 best_gain = 0;
   int64_t best_step = 1;
@@ -324,3 +348,4 @@ extern "C" int chm_replan(const chm_replan_desc *d, chm_replan_plan *out, void *
   out->assign_ms = assign_ms;
   return CHM_OK;
 }
+}  // namespace

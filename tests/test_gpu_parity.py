@@ -992,3 +992,44 @@ def test_load_search_and_free_do_not_wait_for_other_streams(B):
     ref = O.Scenario(synth.config2()).score(f0["offset"] + 1000, 64)
     assert (out[1000:1064].cpu().numpy() == ref).all()
     big.close()
+
+
+REPLAN_TABLES = [
+    (synth.replan_case(31, 12, 4, 4, [5, 10, 3, 12, 0], 32, (2, 6), (1, 6)), 5),
+    (synth.replan_case(32, 10, 3, 3, [4, 0, 8], 12, (1, 4), (1, 6), act=True), 3),
+    (synth.replan_case(33, 14, 2, 6, [7, 1, 10, 4], 24, (1, 4), (2, 8), dist="lognormal"), 4),
+    (synth.replan_case(34, 9, 2, 3, [2, 3, 4, 0, 1, 5], 6, (1, 3), (1, 3)), 6),          # down to nothing
+]
+
+
+@pytest.mark.parametrize("i", range(len(REPLAN_TABLES)))
+def test_replan_table_for_the_loss_of_one_to_k_nodes(B, i):
+    """chm_replan_table: the cached plans for 1 .. k lost nodes (Algorithm 1's loop over failure counts; Planner,
+    overhead paragraph) equal the oracle's re-plan of every prefix of the failure order, exhaustive and bounded, and
+    equal chm_replan called entry by entry"""
+    rp, k = REPLAN_TABLES[i]
+    want = [O.replan(dict(rp, failed_nodes=rp["failed_nodes"][:n])) for n in range(1, k + 1)]
+    got, stats = B.replan_table(rp, k, with_stats=True)
+    assert got == want, (got, want)
+    assert B.replan_table(dict(rp, bounded_search=1), k) == want
+    assert B.replan_table(dict(rp, allreduce_us=900), k) == [O.replan(dict(rp, allreduce_us=900, failed_nodes=rp["failed_nodes"][:n]))
+                                                             for n in range(1, k + 1)]
+    assert [B.replan(dict(rp, failed_nodes=rp["failed_nodes"][:n])) for n in range(1, k + 1)] == want
+    assert B.replan_table(rp, 0) == []
+    with pytest.raises(B.ChmError) as err:
+        B.replan_table(rp, len(rp["failed_nodes"]) + 1)
+    assert err.value.code == B.ERR_ARG
+    # the table searches every (pipeline length, micro-batch count) once: entry by entry the calls search at least as much
+    alone = sum(B.replan(dict(rp, failed_nodes=rp["failed_nodes"][:n]), with_stats=True)[1]["splits_scored"] for n in range(1, k + 1))
+    assert sum(s["splits_scored"] for s in stats) <= alone
+    print("replan table", i, "splits searched", sum(s["splits_scored"] for s in stats), "against", alone, "entry by entry", flush=True)
+
+
+def test_replan_table_of_the_32_card_shape(B):
+    """the table for the loss of 1 .. 3 nodes at the size the benchmark times: every entry equals chm_replan on
+    its own (whose first entry the full-size test above checks against the oracle)"""
+    rp = dict(synth.replan32(), failed_nodes=synth.replan32()["failed_nodes"] + [13, 20], bounded_search=1)
+    table = B.replan_table(rp, 3)
+    for n in range(1, 4):
+        assert table[n - 1] == B.replan(dict(rp, failed_nodes=rp["failed_nodes"][:n]))
+        assert table[n - 1]["found"]
