@@ -128,39 +128,10 @@ typedef struct {
   int64_t t_trans_us;          /* its transition time; cost = horizon_steps * t_step_us + t_trans_us      */
 } chm_best;
 
-/* Per-call kernel timings (milliseconds between HIP events on the caller's stream),
- * filled by the last chm_search_best on a handle when timing was switched on. */
-typedef struct {
-  float family_ms[3];          /* main scoring kernel(s) of strategy 0/1/2, 0 when not run           */
-  float total_ms;              /* first launch to last launch of the call                            */
-  uint64_t partitions[3];      /* partitions evaluated per strategy                                  */
-  uint64_t evaluations[3];     /* (partition, reroute vector) evaluations per strategy               */
-  uint64_t feasible[3];        /* partitions per strategy that passed the memory filter              */
-  uint64_t evaluated[3];       /* of those, partitions whose pipeline recurrences were run: all of
-                                * them, or fewer in a bounded search (chm_set_bounded_search)         */
-} chm_timing;
-
 /* Validates the description, builds the plan space and uploads the scenario tables
  * (Definition 1; Algorithm 1 inputs).  Synchronous.  Errors: CHM_ERR_ARG, CHM_ERR_OVERFLOW,
  * CHM_ERR_HIP.  On error *out is NULL. */
 int chm_load_scenario(const chm_scenario_desc *desc, chm_scenario **out);
-
-/* Which kernels a scenario would run on, decided from the description alone (host only, no device needed; the
- * same decision chm_load_scenario takes).  The estimator's recurrence (eq. (transition)) and its terms are
- * evaluated in int64 by the generic kernels; the shape-specialised kernels evaluate the same integers in int32
- * and are chosen only where load-time bounds show that no intermediate can reach 2^31 (and, for 24-bit
- * multiplies, 2^24), in which case both give the same results.  Tests use this to place scenarios on either
- * side of every such bound. */
-typedef struct {
-  int32_t idx_bits;              /* low bits of the packed (cost, index) argmin key */
-  int32_t int32_recurrence;      /* 1: step time + reroute penalty of every plan stays below 2^31 */
-  int32_t present[3];            /* per strategy: it can recover this failure set */
-  int32_t specialised[3];        /* per strategy: 1 = the int32 shape-specialised kernels, 0 = the generic int64 ones */
-  int32_t sharp_bound[3];        /* per strategy: the bounded search may use its sharper lower bound (24-bit multiplies) */
-  int32_t reroute_mul24;         /* peer stage times stay below 2^24 (needed by the specialised rerouting kernels) */
-  int32_t reroute_swept_apart;   /* rerouting: more than 4,096 reroute vectors, swept by kernels of their own */
-} chm_selection;
-int chm_kernel_selection(const chm_scenario_desc *desc, chm_selection *out);
 
 /* The families present for this failure set and the number of plan indices. Host only. */
 int chm_plan_space(const chm_scenario *s, chm_space *out);
@@ -250,20 +221,6 @@ int chm_transfer_plan(chm_scenario *s, uint64_t part_rank, int32_t pipeline, int
 /* Host-only structural decoding of a plan index (cost is not evaluated and is set to 0). */
 int chm_decode_plan(const chm_scenario *s, uint64_t index, chm_best *out);
 
-/* Switches event timing of chm_search_best / chm_search_range on or off for a handle,
- * and reads the timings of the last such call. */
-int chm_set_timing(chm_scenario *s, int32_t on);
-int chm_get_timing(const chm_scenario *s, chm_timing *out);
-
-/* How the range search of the redundant-computation and re-partition strategies treats partitions that fail
- * the memory filter (the OOM filter of the Estimator, "Peak Memory Usage"): mode 1 = every wavefront first
- * collects the partitions that fit and evaluates them 64 at a time with all lanes busy; mode 0 = every lane
- * evaluates its own partitions, lanes whose partition fails idle; mode -1 (the default) = per strategy, mode 1
- * when fewer than 80 % of a seeded sample of partitions fit, else mode 0.  Results do not depend on the mode.
- * share[k] (host, 3 floats, may be NULL) receives the sampled share per strategy (1.0 where no sample was
- * taken).  Errors: CHM_ERR_ARG. */
-int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
-
 /* Bounded search, off by default.  on = 1 (on = 2: the same with the size thresholds below set to one
  * partition, so that tests reach every path on small scenarios): chm_search_best and chm_search_range skip a partition as soon as a
  * lower bound of its cost (micro-batches x the largest forward + backward time of a stage, which every
@@ -277,7 +234,7 @@ int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
  * enumerates and evaluates only those (this also reaches families of more than 2^46 partitions, which
  * chm_search_best otherwise refuses with CHM_ERR_OVERFLOW, whenever at most 2^26 candidates remain).  The search
  * starts with the ranks around the time-balanced and the memory-balanced partition of each range, so that a
- * good cost is known early.  chm_timing.evaluated tells how many
+ * good cost is known early.  chm_timing.evaluated (chm_measure.h) tells how many
  * partitions were evaluated in full; chm_timing.feasible then counts only those partitions that were looked
  * at one by one and fit.  Where the reroute vectors of a stage are too many to sweep inside the search kernel,
  * a bounded search finds the least penalty of eq. (re-route) from the peers' capacities instead of sweeping them
@@ -285,22 +242,6 @@ int chm_set_filter_compaction(chm_scenario *s, int32_t mode, float *share);
  * the range and list searches of the specialised kernels without cost store (other paths evaluate everything;
  * with a cost store every cost is wanted and nothing is skipped).  Errors: CHM_ERR_ARG. */
 int chm_set_bounded_search(chm_scenario *s, int32_t on);
-
-/* The distinct pipelines one plan of a strategy has to evaluate (pipelines with the same
- * nodes' speed factors, chain and micro-batch count are merged): *n of them (<= 16), each
- * with length[i] stages and micro_batches[i] micro-batches.  Host only; for work accounting. */
-int chm_family_classes(const chm_scenario *s, int32_t strategy, int32_t *n, int32_t *length, int32_t *micro_batches);
-
-/* Shape of the reroute space: *n_affected stages lost nodes; stage a has peers[a] surviving peers
- * and n_vectors[a] valid reroute vectors (arrays of 4).  Host only; for work accounting. */
-int chm_reroute_shape(const chm_scenario *s, int32_t *n_affected, int32_t *peers, uint64_t *n_vectors);
-
-/* Measures a VALU integer issue rate of the current device with a register-only kernel and
- * returns executed int32 lane operations per second.  kind 0: independent v_add_u32; kind 1:
- * independent v_max_i32; kind 2: the recurrence cell (v_max_i32 + v_add_u32 in one dependent
- * chain per lane).  iters scales the run time (about 1 ms per 1000).  Synchronises hip_stream.
- * Used by the benchmark to put measured rates beside its nominal roofline peak. */
-int chm_valu_probe(int32_t kind, uint32_t iters, double *lane_ops_per_s, void *hip_stream);
 
 /* ---- Re-planning over DP/PP degrees (Planner, "Execution Plan Search" and Algorithm 1) --------------
  * Identical nodes, as in the paper.  The nodes that survive are re-laid out as dp pipelines for every dp

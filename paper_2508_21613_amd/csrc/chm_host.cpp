@@ -1,4 +1,4 @@
-// Host side of libchm: the C-ABI of include/chm.h.  Validates a scenario, derives which
+// Host side of libchm: the C-ABI of include/chm.h (and the measurement calls of include/chm_measure.h).  Validates a scenario, derives which
 // recovery strategies exist for the failure set, lays out the plan index space and the
 // device tables, and launches the scoring / search kernels.  No plan is ever scored on
 // the host: without a working HIP device every compute entry point fails with CHM_ERR_HIP.
@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "../../include/chm.h"
+#include "../../include/chm_measure.h"
 #include "chm_dev.h"
 #include "chm_fast.h"
 #include "chm_internal.h"

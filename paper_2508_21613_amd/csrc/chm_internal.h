@@ -4,6 +4,7 @@
 #include <stdint.h>
 
 #include "../../include/chm.h"
+#include "../../include/chm_measure.h"
 
 // A scenario holding one stand-alone pipeline of n stages and M micro-batches on identical nodes:
 // its only family is strategy 1, a plan's cost is the pipeline's 1F1B time + comm per stage boundary.

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include "../../include/chm.h"
+#include "../../include/chm_measure.h"
 
 namespace {
 

@@ -1,4 +1,4 @@
-"""The C-ABI library loads and exports every entry point include/chm.h declares (no GPU needed),
+"""The C-ABI library loads and exports every entry point include/*.h declares (no GPU needed),
 and the host-side validation answers without touching a device."""
 import ctypes as C
 import os
@@ -14,9 +14,15 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def declared_functions():
-    text = open(os.path.join(ROOT, "include", "chm.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(chm_[a-z_]+)\s*\(", text)))
+    names = set()
+    inc = os.path.join(ROOT, "include")
+    for header in sorted(os.listdir(inc)):
+        if not header.endswith(".h"):
+            continue
+        text = open(os.path.join(inc, header)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        names |= set(re.findall(r"\b(chm_[a-z_]+)\s*\(", text))
+    return sorted(names)
 
 
 def test_every_declared_entry_point_is_exported():
@@ -32,8 +38,8 @@ def test_struct_layouts_match_the_header(tmp_path):
     """sizes and field offsets of every structure of the binding against what a C compiler makes of include/chm.h"""
     import subprocess
     structs = {"chm_scenario_desc": B.Desc, "chm_family": B.Family, "chm_space": B.Space, "chm_best": B.Best,
-               "chm_timing": B.Timing, "chm_replan_desc": B.ReplanDesc, "chm_replan_plan": B.ReplanPlan}
-    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "chm.h"', 'int main(void) {']
+               "chm_timing": B.Timing, "chm_selection": B.Selection, "chm_replan_desc": B.ReplanDesc, "chm_replan_plan": B.ReplanPlan}
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "chm.h"', '#include "chm_measure.h"', 'int main(void) {']
     for cname, cls in structs.items():
         lines.append('  printf("%s %%zu\\n", sizeof(%s));' % (cname, cname))
         for field, _ in cls._fields_:
