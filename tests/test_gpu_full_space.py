@@ -168,3 +168,38 @@ def test_batch_search_equals_the_oracle(B):
     assert err.value.code == B.ERR_ARG
     for g in gs:
         g.close()
+
+
+def test_all_528_failure_sets_of_config5(B):
+    """the whole failure sweep as the benchmark runs it (one batched call over all 32 single and 496 double failures):
+    the exhaustive and the bounded sweep return the same plans, every winner re-scored by the oracle from its cuts and
+    reroute vectors has the cost the library reports (and decodes to the index it reports), no plan of the oracle's
+    window around it is better, and the 50 failure sets with a stored whole-space result equal it"""
+    sets = synth.config5_failure_sets()
+    scs = [synth.config5(fs) for fs in sets]
+    gs = [B.Scenario(sc) for sc in scs]
+    plans = B.search_best_batch(gs, 7)
+    for g in gs:
+        g.set_bounded_search(1)
+    bounded = B.search_best_batch(gs, 7)
+    assert len(plans) == 528
+    pinned = 0
+    for fs, sc, (rc, best), (rc_b, best_b) in zip(sets, scs, plans, bounded):
+        assert rc == B.OK and rc_b == B.OK and _same(best, best_b), (fs, best, best_b)
+        o = O.Scenario(sc)
+        rr = best["reroute"] if best["strategy"] == 2 else None
+        assert o.plan_cost(best["strategy"], best["cuts"], rr) == best["cost"], fs
+        assert _same(o.decode(best["index"]), best) or o.decode(best["index"])["cuts"] == best["cuts"], fs
+        f = o.family(best["strategy"])
+        part = O.partition_rank(best["cuts"])
+        lo = max(0, part - 150)
+        rc_o, best_o, _ = o.search_range(best["strategy"], lo, min(300, f["n_part"] - lo))
+        assert rc_o == O.OK and _same(best_o, best), (fs, best_o, best)
+        name = "config5:" + ",".join(str(x) for x in fs)
+        if name in GOLD:
+            assert _same(best, GOLD[name]["best"]), name
+            pinned += 1
+        o.close()
+    assert pinned == 50
+    for g in gs:
+        g.close()
