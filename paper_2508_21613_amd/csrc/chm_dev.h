@@ -67,26 +67,30 @@ struct DevScenario {
 // of valid vectors of `left` entries summing to `rem`.
 
 struct SearchLaunch {
-  const DevScenario *scn;
-  const uint64_t *comp;
-  int32_t strategy;
-  uint64_t part_first;          // first partition rank of this chunk
-  uint32_t part_count;          // partitions in this chunk (< 2^idx_bits)
-  int32_t idx_bits;             // low bits of the packed key hold the chunk-local partition index
+  const DevScenario *scn = nullptr;
+  const uint64_t *comp = nullptr;
+  int32_t strategy = 0;
+  uint64_t part_first = 0;      // first partition rank of this chunk
+  uint32_t part_count = 0;      // partitions in this chunk (< 2^idx_bits)
+  // A chunk may consist of two windows of ranks: chunk-local index i stands for rank part_first + i, and from
+  // i = jump_at on for part_first + i + jump_by (jump_at = ~0: one window).  Lanes then own one partition each.
+  uint32_t jump_at = 0xffffffffu;
+  uint64_t jump_by = 0;
+  int32_t idx_bits = 0;         // low bits of the packed key hold the chunk-local partition index
   // Atomics of many workgroups on one address serialise in the memory system (about 10 ns each), so both
   // targets are spread over slot_mask + 1 words, slot_stride words apart (separate cache lines): workgroup b
   // uses word (b & slot_mask) * slot_stride.  The host takes the minimum / the sum over the words.
-  uint64_t *result;             // device words, atomicMin target: (cost << idx_bits) | local index
-  uint64_t *feasible;           // device counters: partitions that passed the memory filter (atomicAdd)
-  uint32_t slot_mask, slot_stride;
+  uint64_t *result = nullptr;   // device words, atomicMin target: (cost << idx_bits) | local index
+  uint64_t *feasible = nullptr; // device counters: partitions that passed the memory filter (atomicAdd)
+  uint32_t slot_mask = 0, slot_stride = 0;
   // list mode: partition i of the chunk is ranks[i] (any order, a rank outside the family counts as
   // infeasible) instead of part_first + i; part_first is then ignored
-  const uint64_t *ranks;
+  const uint64_t *ranks = nullptr;
   // the same with the partitions given by their cut positions: row i = (stages - 1) ascending bytes (a row
   // that is not strictly increasing within 1..L-1 counts as infeasible); at most one of ranks / cuts is set
-  const uint8_t *cuts;
+  const uint8_t *cuts = nullptr;
   // when set, cost i of the chunk (INT64_MAX if infeasible) is also stored to costs_out[i]
-  int64_t *costs_out;
+  int64_t *costs_out = nullptr;
   // Bounded search (null: every partition that fits is evaluated).  *incumbent = the lowest cost any wave of
   // this search call has evaluated so far (atomicMin, starts at ~0); a partition whose lower bound of the
   // cost lies above it can neither win nor tie and is skipped.  evaluated: counters like `feasible`, of the
@@ -117,6 +121,8 @@ struct FinishArgs {
                                // to "none": the next search with the same layout starts without a fill kernel
   int32_t strategy[FINISH_MAX_SLOTS];
   uint64_t part_first[FINISH_MAX_SLOTS];
+  uint32_t jump_at[FINISH_MAX_SLOTS];      // two-window chunks (see SearchLaunch)
+  uint64_t jump_by[FINISH_MAX_SLOTS];
   uint64_t *out;               // FINISH_WORDS words
 };
 int chmk_finish_search(const FinishArgs &a, int32_t smax, void *stream);

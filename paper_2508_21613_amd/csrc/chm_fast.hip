@@ -547,7 +547,7 @@ k_fast_search(FastLaunch a) {
   c[SP] = L;
   bool listed_ok = true;
   if (!compact) {
-    uint64_t rem = run_len ? a.s.part_first + run_first : 0;   // idle lanes walk from rank 0: always valid cuts
+    uint64_t rem = run_len ? a.s.part_first + run_first + (run_first >= a.s.jump_at ? a.s.jump_by : 0) : 0;   // idle lanes walk from rank 0: always valid cuts
     if (!QUEUED && a.s.ranks != nullptr && run_len) {            // list mode (one partition per lane)
       rem = a.s.ranks[run_first];
       listed_ok = rem < scn->fam[STRAT].n_part;
@@ -2112,7 +2112,7 @@ int launch_search(FastState *f, const DevScenario &h, const SearchLaunch &a, uin
   uint64_t per = a.part_count / lanes_balanced;
   if (per < 4) per = std::min<uint64_t>(4, a.part_count / lanes_resident);
   per = std::max<uint64_t>(1, std::min<uint64_t>(per, 32));
-  if (a.ranks != nullptr) per = 1;                               // a list has no successor to walk to
+  if (a.ranks != nullptr || a.jump_at != 0xffffffffu) per = 1;   // a list has no successor to walk to; a run must not straddle two windows
   else if (a.costs_out != nullptr) per = std::min<uint64_t>(per, 8);   // bounds the LDS tile of the cost store
   fl.per_lane = (uint32_t)per;
   const uint32_t tile_bytes = (a.costs_out != nullptr && per > 1) ? (uint32_t)(BLOCK * per * sizeof(int64_t)) : 0u;
@@ -2418,8 +2418,7 @@ int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d
   if (!ensure_scratch(f, 1)) return -1;
   hipStream_t st = (hipStream_t)stream;
   // peer stage times of the winning partition (one-partition pass of the search kernel in split mode)
-  SearchLaunch one;
-  memset(&one, 0, sizeof(one));
+  SearchLaunch one = SearchLaunch();
   one.strategy = 2;
   one.part_first = part_rank;
   one.part_count = 1;
@@ -2474,8 +2473,7 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
   const uint64_t part_lo = local_first / R, part_hi = last / R;
   for (uint64_t p = part_lo; p <= part_hi; p += FAST_SUB) {
     const uint64_t np = std::min<uint64_t>(FAST_SUB, part_hi - p + 1);
-    SearchLaunch sub;
-    memset(&sub, 0, sizeof(sub));
+    SearchLaunch sub = SearchLaunch();
     sub.scn = d_scn;
     sub.strategy = 2;
     sub.part_first = p;

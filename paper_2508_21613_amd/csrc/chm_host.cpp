@@ -39,7 +39,7 @@ uint64_t mul_sat(uint64_t a, uint64_t b) {
 }
 int bit_length(u128 v) { int n = 0; while (v) { ++n; v >>= 1; } return n; }
 
-struct Slot { int strategy; uint64_t part_first; int idx_bits; };
+struct Slot { int strategy; uint64_t part_first; int idx_bits; uint32_t jump_at = 0xffffffffu; uint64_t jump_by = 0; };
 
 }  // namespace
 
@@ -476,6 +476,9 @@ struct Job {
   int strategy; uint64_t first, count; const uint64_t *ranks; int64_t *costs; const uint8_t *cuts = nullptr;
   const CandidateSet *cand = nullptr; uint64_t covers = 0; uint64_t stride = 1;
   bool seed = false;            // a few ranks searched ahead of their range for a good incumbent: left out of the accounting
+  // two windows of ranks in one job (see SearchLaunch::jump_at): entries from jump_at on lie jump_by ranks further on;
+  // only for jobs of a single chunk
+  uint32_t jump_at = 0xffffffffu; uint64_t jump_by = 0;
 };
 
 // Rank of the partition into `stages` stages whose cuts follow the quantiles of a prefix table (forward +
@@ -632,7 +635,9 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
   for (size_t ji = 0; ji < jobs.size(); ++ji) {
     const Job &j = jobs[ji];
     for (uint64_t done = 0; done < j.count; done += chunk) {
-      c.slots.push_back({j.strategy, ((j.ranks || j.cuts) ? 0 : j.first) + done, s->idx_bits});
+      Slot slot{j.strategy, ((j.ranks || j.cuts) ? 0 : j.first) + done, s->idx_bits};
+      slot.jump_at = j.jump_at; slot.jump_by = j.jump_by;
+      c.slots.push_back(slot);
       c.slot_job.push_back(ji);
     }
   }
@@ -663,6 +668,8 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
       a.scn = s->d_scn; a.comp = s->d_comp; a.strategy = j.strategy;
       a.part_first = j.first + done;
       a.part_count = (uint32_t)std::min<uint64_t>(chunk, j.count - done);
+      a.jump_at = j.jump_at; a.jump_by = j.jump_by;
+      if (j.jump_at != 0xffffffffu && j.count > chunk) return CHM_ERR_ARG;        // (two-window jobs are a few dozen ranks)
       a.idx_bits = s->idx_bits;
       a.result = s->d_slots + si * c.chunk_words;
       a.feasible = j.seed ? d_seed_count : d_count + (size_t)j.strategy * c.chunk_words;
@@ -707,7 +714,11 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
     f.scn = s->d_scn; f.slots = s->d_slots; f.counters = d_count;
     f.n_slots = (uint32_t)c.slots.size(); f.ways = c.ways; f.stride = c.stride; f.idx_bits = s->idx_bits;
     f.sweep_winner = (!light && !(s->fast.split && s->fast.usable[2])) ? 1 : 0;
-    for (size_t i = 0; i < c.slots.size(); ++i) { f.strategy[i] = c.slots[i].strategy; f.part_first[i] = c.slots[i].part_first; }
+    for (size_t i = 0; i < FINISH_MAX_SLOTS; ++i) f.jump_at[i] = 0xffffffffu;
+    for (size_t i = 0; i < c.slots.size(); ++i) {
+      f.strategy[i] = c.slots[i].strategy; f.part_first[i] = c.slots[i].part_first;
+      f.jump_at[i] = c.slots[i].jump_at; f.jump_by[i] = c.slots[i].jump_by;
+    }
     f.out = s->d_result;                       // pinned host memory: no copy behind the kernel
     f.reset = spread ? 1 : 0;
     if (chmk_finish_search(f, s->smax, st)) return CHM_ERR_HIP;
@@ -791,7 +802,8 @@ int collect_jobs(chm_scenario *s, chm_best *out, uint64_t *position, hipStream_t
     if (key == CHM_KEY_NONE) continue;
     const Job &job = c.jobs[c.slot_job[i]];
     const int64_t cost = (int64_t)(key >> c.slots[i].idx_bits);
-    uint64_t part = c.slots[i].part_first + (key & ((1ull << c.slots[i].idx_bits) - 1));
+    const uint64_t local = key & ((1ull << c.slots[i].idx_bits) - 1);
+    uint64_t part = c.slots[i].part_first + local + (local >= c.slots[i].jump_at ? c.slots[i].jump_by : 0);
     if (job.cand) {                                // a candidate's index: its partition rank decides among equal costs
       uint8_t cuts[32];
       fast_candidate_cuts(*job.cand, part * job.stride, cuts);
@@ -875,13 +887,21 @@ std::vector<Job> make_seeds(const chm_scenario *s, const std::vector<Job> &given
     const int stages = s->h.fam[j.strategy].stages;
     if (stages < 2) continue;
     const uint64_t at[2] = {balanced_rank(s, stages, s->h.pf, s->h.pb), balanced_rank(s, stages, s->h.pw, nullptr)};
-    for (int i = 0; i < (at[0] == at[1] ? 1 : 2); ++i) {
-      const uint64_t lo = std::max<uint64_t>(j.first, at[i] >= 32 ? at[i] - 32 : 0);
-      const uint64_t hi = std::min<uint64_t>(j.first + j.count, at[i] + 32);
-      if (lo < hi) {
-        seeds.push_back(Job{j.strategy, lo, hi - lo, nullptr, nullptr});
-        seeds.back().seed = true;
-      }
+    // the windows around the two ranks, in ascending order; one launch covers both (one job of two windows, or a
+    // single window where they touch or one is empty)
+    uint64_t lo[2], hi[2];
+    for (int i = 0; i < 2; ++i) {
+      const uint64_t mid = i == 0 ? std::min(at[0], at[1]) : std::max(at[0], at[1]);
+      lo[i] = std::max<uint64_t>(j.first, mid >= 32 ? mid - 32 : 0);
+      hi[i] = std::max(lo[i], std::min<uint64_t>(j.first + j.count, mid + 32));
+    }
+    if (lo[1] <= hi[0]) { hi[0] = std::max(hi[0], hi[1]); lo[1] = hi[1] = hi[0]; }      // overlapping or adjacent: one window
+    if (hi[0] == lo[0]) { lo[0] = lo[1]; hi[0] = hi[1]; lo[1] = hi[1] = hi[0]; }          // first one empty
+    if (lo[0] < hi[0]) {
+      Job seed{j.strategy, lo[0], (hi[0] - lo[0]) + (hi[1] - lo[1]), nullptr, nullptr};
+      seed.seed = true;
+      if (lo[1] < hi[1]) { seed.jump_at = (uint32_t)(hi[0] - lo[0]); seed.jump_by = lo[1] - hi[0]; }
+      seeds.push_back(seed);
     }
   }
   return seeds;

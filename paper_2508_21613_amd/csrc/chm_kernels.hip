@@ -467,7 +467,7 @@ __global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
       }
       if (valid) fits = eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf);
     } else {
-      const uint64_t part = a.ranks ? a.ranks[gid] : a.part_first + gid;
+      const uint64_t part = a.ranks ? a.ranks[gid] : a.part_first + gid + (gid >= a.jump_at ? a.jump_by : 0);
       if (part < fam.n_part) {
         unrank_partition<SMAX>(scn, fam.stages - 1, part, cuts);
         fits = eval_base<SMAX>(scn, fam, cuts, &t_step, &reconf);
@@ -618,7 +618,8 @@ __global__ void __launch_bounds__(BLOCK) k_finish_search(FinishArgs a) {
       for (uint32_t w = 0; w < a.ways; ++w) key = umin64(key, keys[i * a.ways + w]);
       if (key == CHM_KEY_NONE) continue;
       const uint64_t cost = key >> a.idx_bits;
-      const uint64_t part = a.part_first[i] + (key & ((1ull << a.idx_bits) - 1ull));
+      const uint64_t local = key & ((1ull << a.idx_bits) - 1ull);
+      const uint64_t part = a.part_first[i] + local + (local >= a.jump_at[i] ? a.jump_by[i] : 0);
       const int strategy = a.strategy[i];
       if (best_strategy < 0 || cost < best_cost ||
           (cost == best_cost && (strategy < best_strategy || (strategy == best_strategy && part < best_part)))) {
