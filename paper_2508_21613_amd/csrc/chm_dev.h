@@ -123,6 +123,11 @@ struct FinishArgs {
   uint64_t part_first[FINISH_MAX_SLOTS];
   uint32_t jump_at[FINISH_MAX_SLOTS];      // two-window chunks (see SearchLaunch)
   uint64_t jump_by[FINISH_MAX_SLOTS];
+  // At most one slot may hold the argmin over an enumerated candidate set of a bounded search: its chunk-local
+  // index is a position in cand_cuts (cut positions packed into bytes, 16 bytes per candidate, cand_k of them used),
+  // and the candidate's partition rank follows from its cuts.  cand_slot = -1: none.
+  int32_t cand_slot, cand_k;
+  const void *cand_cuts;
   uint64_t *out;               // FINISH_WORDS words
 };
 int chmk_finish_search(const FinishArgs &a, int32_t smax, void *stream);
@@ -130,8 +135,8 @@ int chmk_finish_search(const FinishArgs &a, int32_t smax, void *stream);
 // launch wrappers (defined in chm_kernels.hip); each returns a hipError_t cast to int
 int chmk_fixed_pipelines(DevScenario *d_scn, int32_t smax, void *stream);
 int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream);
-// d_ptr[0..keys) = CHM_KEY_NONE, the next `zeros` words = 0, the word after them = incumbent
-int chmk_init_search(uint64_t *d_ptr, uint32_t keys, uint32_t zeros, uint64_t incumbent, void *stream);
+// d_ptr[0..zeros) = 0, d_ptr[zeros] = incumbent, d_ptr[key_off .. key_off + keys) = CHM_KEY_NONE (key_off > zeros)
+int chmk_init_search(uint64_t *d_ptr, uint32_t zeros, uint64_t incumbent, uint32_t key_off, uint32_t keys, void *stream);
 int chmk_score(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy, uint64_t first_local,
                uint64_t count, int64_t *d_costs, int32_t smax, void *stream);
 int chmk_score_ranks(const DevScenario *d_scn, const uint64_t *d_comp, int32_t strategy,

@@ -67,7 +67,8 @@ struct chm_scenario {
   uint64_t *h_pinned = nullptr;          // pinned staging for the two small device-to-host copies
   uint32_t slot_words = 0;               // words d_slots has room for
   // d_slots as the last finished search left it: 0 = unknown (a fill kernel runs first); n > 0 = the words a search
-  // of n chunks in the spread layout uses are in their initial state (k_finish_search put them back)
+  // of up to n chunks in the spread layout uses are in their initial state (filled once, and put back by
+  // k_finish_search after every search since)
   uint32_t slots_ready_for = 0;
   bool timing = false;
   int bounded = 0;              // chm_set_bounded_search: 0 off, 1 on, 2 on with seeds and enumeration at any size
@@ -648,20 +649,44 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
   if (c.slots.size() + 8 > s->slot_words) return CHM_ERR_LIMIT;    // (only the static buffer is that small)
   c.chunk_words = c.ways * c.stride;              // words one chunk (or one counter) owns
   c.key_words = (uint32_t)c.slots.size() * c.chunk_words;
-  // right behind the argmin words: three feasibility counters, three counters of evaluated partitions, what the
-  // seed jobs count (not reported) and the incumbent cost of a bounded search
-  uint64_t *d_count = s->d_slots + c.key_words;
+  // Layout of d_slots: first three feasibility counters, three counters of evaluated partitions, what the seed jobs
+  // count (not reported) and the incumbent cost of a bounded search, one chunk's worth of words each; behind these
+  // eight the argmin words of the chunks.  (The fixed part in front lets a search find the buffer ready whatever
+  // the number of chunks of the search before it was.)
+  uint64_t *d_count = s->d_slots;
   uint64_t *d_evaluated = d_count + 3 * c.chunk_words;
   uint64_t *d_seed_count = d_count + 6 * c.chunk_words;
   uint64_t *d_incumbent = d_count + 7 * c.chunk_words;
-  const bool ready = spread && incumbent0 == ~0ull && s->slots_ready_for == (uint32_t)c.slots.size();
+  uint64_t *d_keys = s->d_slots + 8 * c.chunk_words;
+  const uint32_t n_keys = (uint32_t)c.slots.size();
+  const uint32_t ready_before = s->slots_ready_for;
+  const bool ready = spread && incumbent0 == ~0ull && n_keys <= ready_before;
   s->slots_ready_for = 0;                          // until this call's own finish kernel is in the stream
-  if (!ready && chmk_init_search(s->d_slots, c.key_words, 7 * c.chunk_words, incumbent0, st)) return CHM_ERR_HIP;
+  // (a fill in the spread layout covers at least the 16 chunks the finish kernel takes, so that later searches of
+  // other strategy masks find their words ready as well)
+  const uint32_t fill_keys = spread ? std::max<uint32_t>(n_keys, std::min<uint32_t>(FINISH_MAX_SLOTS, s->slot_words / c.chunk_words - 8)) : n_keys;
+  if (!ready && chmk_init_search(s->d_slots, 7 * c.chunk_words, incumbent0, 8 * c.chunk_words, fill_keys * c.chunk_words, st)) return CHM_ERR_HIP;
+  const uint32_t ready_after = ready ? ready_before : (spread ? fill_keys : 0);
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;
   int ev_i = 1;
   bool plain = true;                         // range jobs only: the device can pick the winner
-  for (const Job &j : jobs) plain = plain && !j.ranks && !j.cuts && !j.cand;
+  // (one enumerated candidate set of a single pass is as good as a range: the finish kernel reads the winner's cuts
+  // from the candidate list)
+  int cand_jobs = 0, cand_slot = -1, cand_strategy = -1;
+  {
+    int slot_at = 0;
+    for (const Job &j : jobs) {
+      plain = plain && !j.ranks && !j.cuts;
+      if (j.cand) {
+        ++cand_jobs;
+        cand_slot = slot_at; cand_strategy = j.strategy;
+        plain = plain && j.stride == 1 && j.count <= chunk && j.count <= (uint64_t)CAND_PASS;
+      }
+      slot_at += (int)((j.count + chunk - 1) / chunk);
+    }
+    plain = plain && cand_jobs <= 1;
+  }
   for (const Job &j : jobs) {
     for (uint64_t done = 0; done < j.count; done += chunk, ++si) {
       SearchLaunch a;
@@ -671,7 +696,7 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
       a.jump_at = j.jump_at; a.jump_by = j.jump_by;
       if (j.jump_at != 0xffffffffu && j.count > chunk) return CHM_ERR_ARG;        // (two-window jobs are a few dozen ranks)
       a.idx_bits = s->idx_bits;
-      a.result = s->d_slots + si * c.chunk_words;
+      a.result = d_keys + si * c.chunk_words;
       a.feasible = j.seed ? d_seed_count : d_count + (size_t)j.strategy * c.chunk_words;
       a.slot_mask = c.ways - 1;
       a.slot_stride = c.stride;
@@ -711,10 +736,13 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
   if (plain && !split_sweep && c.slots.size() <= FINISH_MAX_SLOTS && c.ways <= FINISH_MAX_WAYS) {
     FinishArgs f;
     memset(&f, 0, sizeof(f));
-    f.scn = s->d_scn; f.slots = s->d_slots; f.counters = d_count;
+    f.scn = s->d_scn; f.slots = d_keys; f.counters = d_count;
     f.n_slots = (uint32_t)c.slots.size(); f.ways = c.ways; f.stride = c.stride; f.idx_bits = s->idx_bits;
     f.sweep_winner = (!light && !(s->fast.split && s->fast.usable[2])) ? 1 : 0;
     for (size_t i = 0; i < FINISH_MAX_SLOTS; ++i) f.jump_at[i] = 0xffffffffu;
+    f.cand_slot = cand_jobs == 1 ? cand_slot : -1;
+    f.cand_k = cand_jobs == 1 ? s->h.fam[cand_strategy].stages - 1 : 0;
+    f.cand_cuts = cand_jobs == 1 ? s->fast.d_cand_list : nullptr;
     for (size_t i = 0; i < c.slots.size(); ++i) {
       f.strategy[i] = c.slots[i].strategy; f.part_first[i] = c.slots[i].part_first;
       f.jump_at[i] = c.slots[i].jump_at; f.jump_by[i] = c.slots[i].jump_by;
@@ -722,11 +750,11 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
     f.out = s->d_result;                       // pinned host memory: no copy behind the kernel
     f.reset = spread ? 1 : 0;
     if (chmk_finish_search(f, s->smax, st)) return CHM_ERR_HIP;
-    if (spread) s->slots_ready_for = (uint32_t)c.slots.size();
+    if (spread) s->slots_ready_for = ready_after;
     c.device_finish = true;
     return CHM_OK;
   }
-  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (size_t)(c.key_words + 6 * c.chunk_words) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
+  HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_slots, (size_t)(8 * c.chunk_words + c.key_words) * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
   return CHM_OK;
 }
 
@@ -784,11 +812,11 @@ int collect_jobs(chm_scenario *s, chm_best *out, uint64_t *position, hipStream_t
     out->t_step_us = (best_cost - t_trans) / s->h.K;
     return CHM_OK;
   }
-  const uint32_t ways = c.ways, stride = c.stride, chunk_words = c.chunk_words, key_words = c.key_words;
+  const uint32_t ways = c.ways, stride = c.stride, chunk_words = c.chunk_words;
   for (int k = 0; k < 3; ++k)
     for (uint32_t w = 0; w < ways; ++w) {
-      s->last.feasible[k] += s->h_pinned[key_words + (size_t)k * chunk_words + (size_t)w * stride];
-      s->last.evaluated[k] += s->h_pinned[key_words + (size_t)(3 + k) * chunk_words + (size_t)w * stride];
+      s->last.feasible[k] += s->h_pinned[(size_t)k * chunk_words + (size_t)w * stride];
+      s->last.evaluated[k] += s->h_pinned[(size_t)(3 + k) * chunk_words + (size_t)w * stride];
     }
   // kernels that evaluate everything that fits do not count what they evaluate
   for (int k = 0; k < 3; ++k)
@@ -798,7 +826,7 @@ int collect_jobs(chm_scenario *s, chm_best *out, uint64_t *position, hipStream_t
   const Job *best_job = nullptr;
   for (size_t i = 0; i < c.slots.size(); ++i) {
     uint64_t key = CHM_KEY_NONE;
-    for (uint32_t w = 0; w < ways; ++w) key = std::min(key, s->h_pinned[i * chunk_words + (size_t)w * stride]);
+    for (uint32_t w = 0; w < ways; ++w) key = std::min(key, s->h_pinned[(8 + i) * (size_t)chunk_words + (size_t)w * stride]);
     if (key == CHM_KEY_NONE) continue;
     const Job &job = c.jobs[c.slot_job[i]];
     const int64_t cost = (int64_t)(key >> c.slots[i].idx_bits);

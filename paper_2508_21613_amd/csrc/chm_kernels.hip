@@ -356,13 +356,13 @@ __global__ void k_fill_u64(uint64_t *p, uint32_t n, uint64_t v) {
   if (i < n) p[i] = v;
 }
 
-// start of a search: `keys` argmin words to "nothing found", the `zeros` counter words behind them to 0 and the
-// word behind those (the incumbent cost of a bounded search) to `incumbent`, in one launch
-__global__ void k_init_search(uint64_t *p, uint32_t keys, uint32_t zeros, uint64_t incumbent) {
+// start of a search: the `zeros` counter words at the front to 0, the word behind them (the incumbent cost of a bounded
+// search) to `incumbent`, and `keys` argmin words from word `key_off` on to "nothing found", in one launch
+__global__ void k_init_search(uint64_t *p, uint32_t zeros, uint64_t incumbent, uint32_t key_off, uint32_t keys) {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < keys) p[i] = CHM_KEY_NONE;
-  else if (i < keys + zeros) p[i] = 0;
-  else if (i == keys + zeros) p[i] = incumbent;
+  if (i < zeros) p[i] = 0;
+  else if (i == zeros) p[i] = incumbent;
+  if (i < keys) p[key_off + i] = CHM_KEY_NONE;
 }
 
 // step time of the pipelines that strategy 1 leaves in the fault-free layout
@@ -619,7 +619,17 @@ __global__ void __launch_bounds__(BLOCK) k_finish_search(FinishArgs a) {
       if (key == CHM_KEY_NONE) continue;
       const uint64_t cost = key >> a.idx_bits;
       const uint64_t local = key & ((1ull << a.idx_bits) - 1ull);
-      const uint64_t part = a.part_first[i] + local + (local >= a.jump_at[i] ? a.jump_by[i] : 0);
+      uint64_t part = a.part_first[i] + local + (local >= a.jump_at[i] ? a.jump_by[i] : 0);
+      if ((int)i == a.cand_slot) {
+        // a candidate's index: its partition rank = sum of C(c_i - 1, i) over its cut positions
+        const uint4 packed = ((const uint4 *)a.cand_cuts)[local];
+        const uint32_t words[4] = {packed.x, packed.y, packed.z, packed.w};
+        part = 0;
+        for (int d = 1; d <= a.cand_k; ++d) {
+          const uint32_t cut = (words[(d - 1) >> 2] >> (8 * ((d - 1) & 3))) & 0xffu;
+          part += a.scn->binom[d][cut - 1];
+        }
+      }
       const int strategy = a.strategy[i];
       if (best_strategy < 0 || cost < best_cost ||
           (cost == best_cost && (strategy < best_strategy || (strategy == best_strategy && part < best_part)))) {
@@ -723,9 +733,9 @@ int chmk_fill_u64(uint64_t *d_ptr, uint32_t n, uint64_t value, void *stream) {
   return (int)hipGetLastError();
 }
 
-int chmk_init_search(uint64_t *d_ptr, uint32_t keys, uint32_t zeros, uint64_t incumbent, void *stream) {
-  const uint32_t n = keys + zeros + 1;
-  hipLaunchKernelGGL(k_init_search, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, d_ptr, keys, zeros, incumbent);
+int chmk_init_search(uint64_t *d_ptr, uint32_t zeros, uint64_t incumbent, uint32_t key_off, uint32_t keys, void *stream) {
+  const uint32_t n = (zeros + 1 > keys ? zeros + 1 : keys);
+  hipLaunchKernelGGL(k_init_search, dim3((n + 255) / 256), dim3(256), 0, (hipStream_t)stream, d_ptr, zeros, incumbent, key_off, keys);
   return (int)hipGetLastError();
 }
 
