@@ -97,6 +97,8 @@ struct SearchLaunch {
   // partitions whose recurrences were run.  Only the specialised range kernels honour it; others evaluate all.
   uint64_t *incumbent = nullptr;
   uint64_t *evaluated = nullptr;
+  uint64_t incumbent0 = ~0ull;  // cost of a plan known before the call: what the kernels take *incumbent to be at most
+                                // (handed over as an argument, so that the device word needs no fill for it)
 };
 
 // End of a search on the device (k_finish_search): which words to combine and where the result record goes.

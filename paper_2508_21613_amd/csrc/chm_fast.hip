@@ -568,7 +568,7 @@ k_fast_search(FastLaunch a) {
   const bool bounded = MODE == 2 && a.s.incumbent != nullptr;
   uint64_t incumbent = ~0ull;
   uint32_t n_eval = 0;                    // wave-uniform count of partitions whose recurrences were run
-  if (bounded) incumbent = __hip_atomic_load(a.s.incumbent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (bounded) incumbent = umin64(a.s.incumbent0, __hip_atomic_load(a.s.incumbent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
   // Bounded search, a whole run at once.  Consecutive ranks differ in their lowest cuts.  When the run of a lane
   // stays inside the block of ranks that share the cuts above the h lowest ones (its offset among the
   // arrangements of those h cuts, plus its length, does not exceed their number C(c[h+1]-1, h)), the stages
@@ -997,6 +997,7 @@ struct ListFilter {
   // bounded search (no cost store): entries whose lower bound of the cost lies above *incumbent (the lowest cost
   // the passes before this one have evaluated) are dropped like those that do not fit; null = keep all that fit
   const uint64_t *incumbent;
+  uint64_t incumbent0;          // a cost known before the call (see SearchLaunch::incumbent0)
 };
 
 template <int SP, int STRAT>
@@ -1010,7 +1011,7 @@ __global__ void __launch_bounds__(BLOCK) k_list_filter(ListFilter a) {
   const FamPtr ff = &tab->fam[STRAT];
   const int L = scn->L;
   const bool bounded = a.incumbent != nullptr && a.costs_out == nullptr;
-  const uint64_t incumbent = bounded ? __hip_atomic_load(a.incumbent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ~0ull;
+  const uint64_t incumbent = bounded ? umin64(a.incumbent0, __hip_atomic_load(a.incumbent, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)) : ~0ull;
   for (int i = threadIdx.x; i <= L; i += BLOCK) T[i] = make_int4((int)scn->pf[i], (int)scn->pb[i], (int)scn->pw[i], (int)scn->pa[i]);
   if (a.cuts == nullptr)
     for (int i = threadIdx.x; i < K * DEV_MAX_L; i += BLOCK) BN[i] = scn->binom[1 + i / DEV_MAX_L][i % DEV_MAX_L];
@@ -2059,6 +2060,7 @@ int launch_list(FastState *f, const DevScenario &h, const SearchLaunch &a, hipSt
     ListFilter lf;
     lf.tiles = (int32_t)tiles;
     lf.incumbent = bounded ? a.incumbent : nullptr;
+    lf.incumbent0 = a.incumbent0;
     lf.scn = a.scn; lf.tab = f->d_tables; lf.n = n; lf.pos_base = done;
     lf.ranks = a.ranks ? a.ranks + done : nullptr;
     lf.cuts = a.cuts ? a.cuts + (size_t)done * (size_t)(sp - 1) : nullptr;

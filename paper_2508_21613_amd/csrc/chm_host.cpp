@@ -660,12 +660,12 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
   uint64_t *d_keys = s->d_slots + 8 * c.chunk_words;
   const uint32_t n_keys = (uint32_t)c.slots.size();
   const uint32_t ready_before = s->slots_ready_for;
-  const bool ready = spread && incumbent0 == ~0ull && n_keys <= ready_before;
+  const bool ready = spread && n_keys <= ready_before;       // (a known cost travels in the launch arguments)
   s->slots_ready_for = 0;                          // until this call's own finish kernel is in the stream
   // (a fill in the spread layout covers at least the 16 chunks the finish kernel takes, so that later searches of
   // other strategy masks find their words ready as well)
   const uint32_t fill_keys = spread ? std::max<uint32_t>(n_keys, std::min<uint32_t>(FINISH_MAX_SLOTS, s->slot_words / c.chunk_words - 8)) : n_keys;
-  if (!ready && chmk_init_search(s->d_slots, 7 * c.chunk_words, incumbent0, 8 * c.chunk_words, fill_keys * c.chunk_words, st)) return CHM_ERR_HIP;
+  if (!ready && chmk_init_search(s->d_slots, 7 * c.chunk_words, ~0ull, 8 * c.chunk_words, fill_keys * c.chunk_words, st)) return CHM_ERR_HIP;
   const uint32_t ready_after = ready ? ready_before : (spread ? fill_keys : 0);
   if (s->timing) HIP_TRY(hipEventRecord(s->ev[0], st));
   size_t si = 0;
@@ -694,6 +694,7 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
       a.part_first = j.first + done;
       a.part_count = (uint32_t)std::min<uint64_t>(chunk, j.count - done);
       a.jump_at = j.jump_at; a.jump_by = j.jump_by;
+      a.incumbent0 = incumbent0;
       if (j.jump_at != 0xffffffffu && j.count > chunk) return CHM_ERR_ARG;        // (two-window jobs are a few dozen ranks)
       a.idx_bits = s->idx_bits;
       a.result = d_keys + si * c.chunk_words;
