@@ -117,6 +117,9 @@ struct FastState {
   uint8_t *d_cand_low = nullptr;            // CandidateSet::low_pair on the device
   size_t cand_ways_capacity = 0;
   uint64_t cand_serial = 0;                 // CandidateSet::serial of the tables the device holds
+  uint8_t *h_cand_stage = nullptr;          // pinned staging of the two tables on their way to the device
+  size_t cand_stage_capacity = 0;
+  void *cand_copied = nullptr;              // hipEvent_t: the last copy out of the staging buffer is done
 };
 
 // Bounded search, candidate path.  Every term of the lower bound of a plan's cost belongs to one stage

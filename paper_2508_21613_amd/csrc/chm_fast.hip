@@ -2281,10 +2281,30 @@ int fast_candidates_search(FastState *f, const DevScenario &h, const SearchLaunc
     f->cand_ways_capacity = cs.ways.size();
   }
   if (f->cand_serial != cs.serial) {
-    // (pageable host memory: both copies have left the vectors when the calls return)
+    // The tables go through a pinned staging buffer: a copy from pageable memory keeps the host busy until the data
+    // has left (tens of microseconds for the 150 KB of the 32-card shape, during which nothing is launched), a copy
+    // from pinned memory is queued and done.  An event tells when the buffer may be written again.
     f->cand_serial = 0;
-    if (hipMemcpyAsync(f->d_cand_ways, cs.ways.data(), cs.ways.size() * sizeof(uint64_t), hipMemcpyHostToDevice, st) != hipSuccess) return -1;
-    if (hipMemcpyAsync(f->d_cand_low, cs.low_pair.data(), cs.low_pair.size(), hipMemcpyHostToDevice, st) != hipSuccess) return -1;
+    const size_t ways_bytes = cs.ways.size() * sizeof(uint64_t), low_bytes = cs.low_pair.size();
+    if (f->cand_stage_capacity < ways_bytes + low_bytes) {
+      if (f->cand_copied && hipEventSynchronize((hipEvent_t)f->cand_copied) != hipSuccess) return -1;
+      if (f->h_cand_stage) pool_release(f->h_cand_stage);
+      f->h_cand_stage = nullptr; f->cand_stage_capacity = 0;
+      if (!pool_take_pinned(f->h_cand_stage, ways_bytes + low_bytes)) return -1;
+      f->cand_stage_capacity = ways_bytes + low_bytes;
+    }
+    if (!f->cand_copied) {
+      hipEvent_t ev = nullptr;
+      if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) return -1;
+      f->cand_copied = ev;
+    } else if (hipEventSynchronize((hipEvent_t)f->cand_copied) != hipSuccess) {
+      return -1;
+    }
+    memcpy(f->h_cand_stage, cs.ways.data(), ways_bytes);
+    memcpy(f->h_cand_stage + ways_bytes, cs.low_pair.data(), low_bytes);
+    if (hipMemcpyAsync(f->d_cand_ways, f->h_cand_stage, ways_bytes, hipMemcpyHostToDevice, st) != hipSuccess) return -1;
+    if (hipMemcpyAsync(f->d_cand_low, f->h_cand_stage + ways_bytes, low_bytes, hipMemcpyHostToDevice, st) != hipSuccess) return -1;
+    if (hipEventRecord((hipEvent_t)f->cand_copied, st) != hipSuccess) return -1;
     f->cand_serial = cs.serial;
   }
   CandidateEnum e;
@@ -2533,6 +2553,10 @@ int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_
 }
 
 void fast_release(FastState *f) {
+  if (f->cand_copied) (void)hipEventDestroy((hipEvent_t)f->cand_copied);
+  f->cand_copied = nullptr;
+  if (f->h_cand_stage) pool_release(f->h_cand_stage);
+  f->h_cand_stage = nullptr; f->cand_stage_capacity = 0;
   if (f->d_cand_low) pool_release(f->d_cand_low);
   if (f->d_cand_ways) pool_release(f->d_cand_ways);
   if (f->d_cand_count) pool_release(f->d_cand_count);
