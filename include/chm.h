@@ -15,10 +15,8 @@
  * than the device-side combine takes.  Only a bounded search (chm_set_bounded_search, off by
  * default) does arithmetic of the method on the host, none of it a plan's cost: the ranks of
  * the seed partitions (layer-time and memory quantiles), the per-stage table that counts the
- * partitions whose lower bound stays within the best cost known (fast_candidates_build), and,
- * for reroute spaces too large to sweep, the reroute vectors of the winner recovered from the
- * peers' capacities (least penalty by bisection).  There is no CPU fallback: without a usable
- * GPU every compute call returns CHM_ERR_HIP.
+ * partitions whose lower bound stays within the best cost known (fast_candidates_build).
+ * There is no CPU fallback: without a usable GPU every compute call returns CHM_ERR_HIP.
  *
  * Conventions
  *   - Every function returns 0 (CHM_OK) or a negative CHM_ERR_* code; nothing throws or

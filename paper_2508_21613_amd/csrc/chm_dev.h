@@ -117,7 +117,9 @@ struct FinishArgs {
   const uint64_t *counters;    // six counters laid out like six more slots
   uint32_t n_slots, ways, stride;
   int32_t idx_bits;
-  int32_t sweep_winner;        // 1: a rerouting winner's best vectors are found here by a sweep of one lane per stage
+  int32_t sweep_winner;        // a rerouting winner's best vectors are found here: 1 = by a sweep of one lane per stage that
+                               // lost nodes, 2 = from the peers' capacities by one wavefront (spaces too large for one lane), 0 = not
+  const uint64_t *comp;        // the reroute count tables (for 2)
   int32_t reset;               // 1: once read, the argmin words go back to "nothing found", the seven counters behind
                                // them (the six summed here and the seeds' own) to 0 and the incumbent word behind those
                                // to "none": the next search with the same layout starts without a fill kernel
@@ -145,9 +147,9 @@ int chmk_score_ranks(const DevScenario *d_scn, const uint64_t *d_comp, int32_t s
                      const uint64_t *d_ranks, uint64_t n, int64_t *d_costs, int32_t smax, void *stream);
 int chmk_search(const SearchLaunch &a, int32_t smax, void *stream);
 int chmk_rank_cuts(const DevScenario *d_scn, int k, const uint8_t *d_cuts, uint64_t n, uint64_t *d_ranks, void *stream);
-// re-evaluates one partition of the rerouting family and writes, per affected stage, the
-// rank of its best reroute vector to d_out[0..n_aff)
-int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank,
+// writes, per stage that lost nodes, the rank of the best reroute vector of one partition of the rerouting family
+// to d_out[0..n_aff): by a sweep of all vectors, or (by_capacity) from the peers' capacities
+int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank, int32_t by_capacity,
                         uint64_t *d_out, int32_t smax, void *stream);
 
 // transition time (restart + weight transfer) of one plan into d_out[0], -1 when it does not fit (one lane)

@@ -100,6 +100,7 @@ struct FastState {
   // large (tens of MB, milliseconds to enumerate) and a bounded search never reads them: they are built when an
   // exhaustive search, a cost store or the recovery of a winner's vectors first asks for them.
   bool reroute_tables_ready = false;
+  bool vecs_ready = false;                  // the rank-ordered vector table (d_vecs) has been decoded
   size_t vec_words = 0;                     // size of the vector table
   const DevScenario *d_scn = nullptr;       // the handle's device tables (for that later build)
   const uint64_t *d_comp = nullptr;
@@ -171,10 +172,6 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
 bool fast_can_bound(const FastState *f, const SearchLaunch &a);
 // Sampled share of partitions of a strategy that pass the memory filter (1.0 where no sample applies).
 float fast_fit_share(FastState *f, const DevScenario &h, int strategy);
-// Rank of the best reroute vector per affected stage of one partition of the rerouting family,
-// written to d_out[0..n_aff).  Same return convention as fast_search.
-int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t part_rank,
-                        uint64_t *d_out, void *stream);
 // Scores plan indices [local_first, local_first+count) of the rerouting family (indices local to
 // the family) into d_costs: one pass of the search kernel stores each partition's cost without
 // penalties and its peer stage times, then one lane per plan index adds the penalty of its

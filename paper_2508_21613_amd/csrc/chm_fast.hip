@@ -1366,39 +1366,6 @@ __global__ void __launch_bounds__(BLOCK) k_combine(const uint64_t *__restrict__ 
   }
 }
 
-// first row with the smallest penalty for ONE partition (weights at weights[a*8 ..]); one lane per
-// four rows, key = penalty << 32 | row, so the lowest rank wins ties
-template <int P>
-__global__ void __launch_bounds__(BLOCK) k_winner_rows(const uint32_t *__restrict__ rows, uint32_t n_rows_valid,
-                                                       const uint32_t *__restrict__ weights, int a, uint64_t *out) {
-  constexpr int STRIDE = P <= 4 ? 4 : 8;
-  __shared__ uint64_t wave_keys[BLOCK / 64];
-  uint32_t w[P];
-#pragma unroll
-  for (int i = 0; i < P; ++i) w[i] = weights[a * 8 + i];
-  const uint32_t r0 = (blockIdx.x * BLOCK + threadIdx.x) * 4;
-  uint64_t key = CHM_KEY_NONE;
-  for (uint32_t r = r0; r < r0 + 4 && r < n_rows_valid; ++r) {
-    uint32_t pen = 0;
-#pragma unroll
-    for (int i = 0; i < P; ++i) {
-      const uint32_t v = __umul24(rows[(size_t)r * STRIDE + i], w[i]);
-      pen = pen > v ? pen : v;
-    }
-    key = umin64(key, ((uint64_t)pen << 32) | r);
-  }
-  key = wave_min(key);
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (lane == 0) wave_keys[wave] = key;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    uint64_t k = wave_keys[0];
-#pragma unroll
-    for (int i = 1; i < BLOCK / 64; ++i) k = umin64(k, wave_keys[i]);
-    if (k != CHM_KEY_NONE) atomicMin((unsigned long long *)&out[a], (unsigned long long)k);
-  }
-}
-
 struct ExpandArgs {
   const uint64_t *base;         // [partition of the pass] cost without penalties, ~0 = does not fit
   const uint32_t *weights;      // [partition of the pass][affected stage][8]
@@ -1616,11 +1583,6 @@ __global__ void k_fill_u32(uint32_t *p, uint32_t n, uint32_t v) {
   if (i < n) p[i] = v;
 }
 
-// out[a] = low 32 bits of key[a] (the winning row = reroute rank)
-__global__ void k_keys_to_ranks(const uint64_t *keys, uint64_t *out, int n) {
-  if ((int)threadIdx.x < n) out[threadIdx.x] = keys[threadIdx.x] & 0xffffffffull;
-}
-
 template <typename Fn>
 int by_peers(int p, Fn fn) {
   switch (p) {
@@ -1734,12 +1696,86 @@ static void fast_quiesce(FastState *f) {
 // device, then the table block is uploaded again with the offsets and counts.  At load for families whose
 // vectors are swept inside the search kernel, on first need for the large ones.  False on a failed HIP call;
 // when table and count table disagree the strategy is handed back to the generic kernels (usable[2] = false).
+// rows of the rank-ordered vector table, decoded on the device (queued on the library's stream, not waited for)
+static bool build_vector_rows(FastState *f, const DevScenario &h) {
+  const FastTables *t = &f->h_tables;
+  hipStream_t ls = (hipStream_t)f->load_stream;
+  if (!f->d_vecs && !pool_take(f->d_vecs, f->vec_words * sizeof(uint32_t))) return false;
+  for (int a = 0; a < h.n_aff; ++a) {
+    const int stride = h.aff_peers[a] <= 4 ? 4 : 8;
+    hipLaunchKernelGGL(k_make_rows, dim3((t->vec_rows[a] + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, ls, f->d_scn, f->d_comp, a,
+                       f->d_vecs + t->vec_off[a], t->vec_rows[a], stride);
+  }
+  f->vecs_ready = hipGetLastError() == hipSuccess;
+  return f->vecs_ready;
+}
+
 static bool build_reroute_tables(FastState *f, const DevScenario &h) {
   FastTables *t = &f->h_tables;
   // run tables (host enumeration in rank order: shared entries lexicographic, see FastTables)
   std::vector<uint32_t> runs;
   if (f->usable[2]) {
+    // group tables for the sweep kernel of large reroute spaces (see k_sweep_groups)
+    for (int a = 0; a < h.n_aff && f->split; ++a) {
+      t->grp_cap[a] = 0;
+      const int p = h.aff_peers[a], total = h.aff_total[a];
+      const int cap = h.rcap > 0 ? std::min(h.rcap, total) : total;
+      if (p < 3 || (cap != 8 && cap != 16)) continue;
+      int same = -1;
+      for (int b = 0; b < a; ++b)
+        if (h.aff_peers[b] == p && h.aff_total[b] == total && t->grp_cap[b]) same = b;
+      if (same >= 0) { t->grp_off[a] = t->grp_off[same]; t->grp_count[a] = t->grp_count[same]; t->grp_cap[a] = t->grp_cap[same]; continue; }
+      const int q = p - 3;                                 // shared entries per group
+      const size_t at = runs.size();
+      uint64_t vectors = 0;
+      uint32_t n_groups = 0;
+      std::vector<int> pre(q + 1, 0);
+      // odometer over the shared entries in lexicographic order (every entry 0..cap, what is left must fit the last three)
+      int pos = 0, rem = total;
+      bool fresh = true;
+      for (;;) {
+        if (pos == q) {
+          const int lo = std::max(0, rem - 2 * cap), hi = std::min(cap, rem);
+          if (lo <= hi) {
+            uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+            for (int i = 0; i < q; ++i) d[i] = (uint32_t)pre[i];
+            d[5] = (uint32_t)lo; d[6] = (uint32_t)(hi - lo + 1); d[7] = (uint32_t)rem;
+            runs.insert(runs.end(), d, d + 8);
+            for (int v = lo; v <= hi; ++v) {
+              const int r2 = rem - v;
+              vectors += (uint64_t)(std::min(cap, r2) - std::max(0, r2 - cap) + 1);
+            }
+            ++n_groups;
+          }
+          --pos;
+          if (pos < 0) break;
+          rem += pre[pos];
+          ++pre[pos];
+          fresh = false;
+          continue;
+        }
+        if (fresh) pre[pos] = 0;
+        if (pre[pos] > std::min(cap, rem)) {
+          --pos;
+          if (pos < 0) break;
+          rem += pre[pos];
+          ++pre[pos];
+          fresh = false;
+          continue;
+        }
+        rem -= pre[pos];
+        ++pos;
+        fresh = true;
+      }
+      if (vectors == h.aff_R[a] && n_groups > 0) {
+        t->grp_off[a] = (uint32_t)at; t->grp_count[a] = n_groups; t->grp_cap[a] = (uint32_t)cap;
+      } else {
+        runs.resize(at);                                   // table and count disagree: the run sweep serves this stage
+      }
+    }
+    // run tables of the stages that have no group table
     for (int a = 0; a < h.n_aff && f->usable[2]; ++a) {
+      if (t->grp_cap[a] != 0) { t->run_off[a] = 0; t->run_count[a] = 0; continue; }
       int same = -1;
       for (int b = 0; b < a; ++b)
         if (h.aff_peers[b] == h.aff_peers[a] && h.aff_total[b] == h.aff_total[a]) same = b;
@@ -1800,64 +1836,6 @@ static bool build_reroute_tables(FastState *f, const DevScenario &h) {
       }
     }
     if (!f->usable[2]) f->split = false;
-    // group tables for the sweep kernel of large reroute spaces (see k_sweep_groups)
-    for (int a = 0; a < h.n_aff && f->usable[2] && f->split; ++a) {
-      t->grp_cap[a] = 0;
-      const int p = h.aff_peers[a], total = h.aff_total[a];
-      const int cap = h.rcap > 0 ? std::min(h.rcap, total) : total;
-      if (p < 3 || (cap != 8 && cap != 16)) continue;
-      int same = -1;
-      for (int b = 0; b < a; ++b)
-        if (h.aff_peers[b] == p && h.aff_total[b] == total && t->grp_cap[b]) same = b;
-      if (same >= 0) { t->grp_off[a] = t->grp_off[same]; t->grp_count[a] = t->grp_count[same]; t->grp_cap[a] = t->grp_cap[same]; continue; }
-      const int q = p - 3;                                 // shared entries per group
-      const size_t at = runs.size();
-      uint64_t vectors = 0;
-      uint32_t n_groups = 0;
-      std::vector<int> pre(q + 1, 0);
-      // odometer over the shared entries in lexicographic order (every entry 0..cap, what is left must fit the last three)
-      int pos = 0, rem = total;
-      bool fresh = true;
-      for (;;) {
-        if (pos == q) {
-          const int lo = std::max(0, rem - 2 * cap), hi = std::min(cap, rem);
-          if (lo <= hi) {
-            uint32_t d[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-            for (int i = 0; i < q; ++i) d[i] = (uint32_t)pre[i];
-            d[5] = (uint32_t)lo; d[6] = (uint32_t)(hi - lo + 1); d[7] = (uint32_t)rem;
-            runs.insert(runs.end(), d, d + 8);
-            for (int v = lo; v <= hi; ++v) {
-              const int r2 = rem - v;
-              vectors += (uint64_t)(std::min(cap, r2) - std::max(0, r2 - cap) + 1);
-            }
-            ++n_groups;
-          }
-          --pos;
-          if (pos < 0) break;
-          rem += pre[pos];
-          ++pre[pos];
-          fresh = false;
-          continue;
-        }
-        if (fresh) pre[pos] = 0;
-        if (pre[pos] > std::min(cap, rem)) {
-          --pos;
-          if (pos < 0) break;
-          rem += pre[pos];
-          ++pre[pos];
-          fresh = false;
-          continue;
-        }
-        rem -= pre[pos];
-        ++pos;
-        fresh = true;
-      }
-      if (vectors == h.aff_R[a] && n_groups > 0) {
-        t->grp_off[a] = (uint32_t)at; t->grp_count[a] = n_groups; t->grp_cap[a] = (uint32_t)cap;
-      } else {
-        runs.resize(at);                                   // table and count disagree: the run sweep serves this stage
-      }
-    }
   }
   if (!f->usable[2]) return true;
   if (runs.empty()) runs.assign(8, 0);
@@ -1869,16 +1847,11 @@ static bool build_reroute_tables(FastState *f, const DevScenario &h) {
   hipStream_t ls = (hipStream_t)f->load_stream;
   bool up = pool_take(f->d_runs, runs.size() * sizeof(uint32_t));
   up = up && hipMemcpyAsync(f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), hipMemcpyHostToDevice, ls) == hipSuccess;
-  up = up && pool_take(f->d_vecs, f->vec_words * sizeof(uint32_t));
   up = up && hipMemcpyAsync(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice, ls) == hipSuccess;
-  if (up) {
-    for (int a = 0; a < h.n_aff; ++a) {
-      const int stride = h.aff_peers[a] <= 4 ? 4 : 8;
-      hipLaunchKernelGGL(k_make_rows, dim3((t->vec_rows[a] + BLOCK - 1) / BLOCK), dim3(BLOCK), 0, ls, f->d_scn, f->d_comp, a,
-                         f->d_vecs + t->vec_off[a], t->vec_rows[a], stride);
-    }
-    up = hipGetLastError() == hipSuccess;
-  }
+  // the vector table itself (rank-ordered rows) only serves the cost store of plan indices; where the vectors are
+  // swept by kernels of their own it is tens of MB and is built when a cost store first asks for it
+  f->vecs_ready = false;
+  if (up && !f->split) up = build_vector_rows(f, h);
   up = (hipStreamSynchronize(ls) == hipSuccess) && up;       // also when something failed: `runs` must outlive its copy
   f->reroute_tables_ready = up;
   return up;
@@ -2432,48 +2405,14 @@ int fast_search(FastState *f, const DevScenario &h, const SearchLaunch &a, void 
   return 0;
 }
 
-int fast_reroute_winner(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t part_rank,
-                        uint64_t *d_out, void *stream) {
-  (void)d_scn;
-  if (!f->usable[2] || !f->split || h.n_aff == 0) return 1;
-  if (const int rc = ensure_reroute_tables(f, h)) return rc;
-  if (!ensure_scratch(f, 1)) return -1;
-  hipStream_t st = (hipStream_t)stream;
-  // peer stage times of the winning partition (one-partition pass of the search kernel in split mode)
-  SearchLaunch one = SearchLaunch();
-  one.strategy = 2;
-  one.part_first = part_rank;
-  one.part_count = 1;
-  one.idx_bits = 1;
-  one.ranks = nullptr;
-  one.costs_out = nullptr;
-  one.result = f->d_rowkey;          // not written in split mode
-  one.feasible = f->d_rowkey;        // counter target: overwritten by the fill below
-  one.scn = d_scn;
-  int rc = launch_search(f, h, one, f->d_base, f->d_weights, st);
-  if (rc) return rc;
-  hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, st, (uint32_t *)f->d_rowkey, 2 * DEV_MAX_AFF, 0xffffffffu);
-  const FastTables &t = f->h_tables;
-  for (int s = 0; s < h.n_aff; ++s) {
-    const uint32_t n_valid = (uint32_t)h.aff_R[s];
-    const uint32_t blocks = ((n_valid + 3) / 4 + BLOCK - 1) / BLOCK;
-    const uint32_t *rows = f->d_vecs + t.vec_off[s];
-    rc = by_peers(h.aff_peers[s], [&](auto tag) {
-      constexpr int P = decltype(tag)::value;
-      hipLaunchKernelGGL((k_winner_rows<P>), dim3(blocks), dim3(BLOCK), 0, st, rows, n_valid, f->d_weights, s, f->d_rowkey);
-      return 0;
-    });
-    if (rc) return -1;
-  }
-  hipLaunchKernelGGL(k_keys_to_ranks, dim3(1), dim3(64), 0, st, f->d_rowkey, d_out, h.n_aff);
-  return hipGetLastError() == hipSuccess ? 0 : -1;
-}
-
 int fast_score_reroute(FastState *f, const DevScenario &h, const DevScenario *d_scn, uint64_t local_first,
                        uint64_t count, int64_t *d_costs, void *stream) {
   if (!f->usable[2] || h.n_aff == 0) return 1;
   if (count == 0) return 0;
   if (const int rc = ensure_reroute_tables(f, h)) return rc;
+  if (!f->vecs_ready) {
+    if (!build_vector_rows(f, h) || hipStreamSynchronize((hipStream_t)f->load_stream) != hipSuccess) return -1;
+  }
   hipStream_t st = (hipStream_t)stream;
   const FastTables &t = f->h_tables;
   const uint64_t R = h.fam[2].n_reroute;

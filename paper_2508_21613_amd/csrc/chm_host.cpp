@@ -498,52 +498,6 @@ uint64_t balanced_rank(const chm_scenario *s, int stages, const int64_t *prefix_
   return rank;
 }
 
-// The winner's reroute vectors without the vector tables (bounded search over a large reroute space).  Peer i
-// of the stage takes (forward + backward time of the stage under the winner's cuts) x its speed factor per
-// extra micro-batch; the least penalty v is the least value at which the peers' capacities min(cap, v / w_i)
-// cover the orphans; the vector of lowest rank that stays within v is the lexicographically smallest one:
-// every peer in turn takes as little as the peers after it allow.  Its rank = the number of valid vectors that
-// are lexicographically smaller, from the count table.
-void host_reroute_ranks(const chm_scenario *s, uint64_t part_rank, uint64_t *rr) {
-  const DevScenario &h = s->h;
-  uint8_t cuts[32];
-  decode_partition(s, h.fam[2].stages - 1, part_rank, cuts);
-  for (int a = 0; a < h.n_aff; ++a) {
-    const int st = h.aff_stage[a], p = h.aff_peers[a];
-    const int lo = st == 0 ? 0 : cuts[st - 1], hi = st == h.fam[2].stages - 1 ? h.L : cuts[st];
-    const int64_t F = h.pf[hi] - h.pf[lo], B = h.pb[hi] - h.pb[lo];
-    int64_t w[DEV_MAX_D];
-    int64_t w_max = 1;
-    for (int i = 0; i < p; ++i) {
-      const int64_t q = h.aff_q[a][i];
-      w[i] = q == 65536 ? F + B : ((F * q + 32768) >> 16) + ((B * q + 32768) >> 16);
-      w_max = std::max(w_max, w[i]);
-    }
-    const int64_t orphans = h.aff_total[a], cap = h.rcap > 0 ? h.rcap : orphans;
-    auto room = [&](int64_t v, int i) { return std::min<int64_t>(cap, w[i] == 0 ? cap : v / w[i]); };
-    int64_t v_lo = 0, v_hi = orphans * w_max;
-    while (v_lo < v_hi) {
-      const int64_t v = v_lo + (v_hi - v_lo) / 2;
-      int64_t sum = 0;
-      for (int i = 0; i < p; ++i) sum += room(v, i);
-      if (sum >= orphans) v_hi = v;
-      else v_lo = v + 1;
-    }
-    const uint64_t *tab = s->comp.data() + h.comp_off[a];
-    int64_t rem = orphans;
-    uint64_t rank = 0;
-    for (int pos = 0; pos < p; ++pos) {
-      int64_t behind = 0;
-      for (int i = pos + 1; i < p; ++i) behind += room(v_lo, i);
-      const int64_t take = std::max<int64_t>(0, rem - behind);
-      const int left = p - 1 - pos;
-      for (int64_t v = 0; v < take; ++v) rank += tab[(size_t)left * h.comp_stride[a] + (size_t)(rem - v)];
-      rem -= take;
-    }
-    rr[a] = rank;
-  }
-}
-
 // below this many partitions the bounded range search costs no more than counting and enumerating candidates
 constexpr uint64_t ENUMERATE_FROM = 1ull << 25;
 
@@ -729,17 +683,14 @@ int launch_jobs(chm_scenario *s, const std::vector<Job> &jobs, bool want_result,
   if (!want_result) return CHM_OK;
   // Few chunks of plain ranges: a one-workgroup kernel behind the search kernels picks the winner, adds up the
   // counters and computes the winner's transition time (and its best reroute vectors), so the host waits once
-  // and copies one record.  Not where the winner's vectors come from the vector tables of a large reroute space
-  // (that needs the partition on the host first).
-  bool split_sweep = false;
-  for (const Job &j : jobs)
-    split_sweep = split_sweep || (j.strategy == 2 && s->h.n_aff > 0 && s->fast.split && s->fast.usable[2] && !s->fast.penalty_by_capacity);
-  if (plain && !split_sweep && c.slots.size() <= FINISH_MAX_SLOTS && c.ways <= FINISH_MAX_WAYS) {
+  // and reads one record.
+  if (plain && c.slots.size() <= FINISH_MAX_SLOTS && c.ways <= FINISH_MAX_WAYS) {
     FinishArgs f;
     memset(&f, 0, sizeof(f));
     f.scn = s->d_scn; f.slots = d_keys; f.counters = d_count;
     f.n_slots = (uint32_t)c.slots.size(); f.ways = c.ways; f.stride = c.stride; f.idx_bits = s->idx_bits;
-    f.sweep_winner = (!light && !(s->fast.split && s->fast.usable[2])) ? 1 : 0;
+    f.sweep_winner = light ? 0 : ((s->fast.split && s->fast.usable[2]) ? 2 : 1);
+    f.comp = s->d_comp;
     for (size_t i = 0; i < FINISH_MAX_SLOTS; ++i) f.jump_at[i] = 0xffffffffu;
     f.cand_slot = cand_jobs == 1 ? cand_slot : -1;
     f.cand_k = cand_jobs == 1 ? s->h.fam[cand_strategy].stages - 1 : 0;
@@ -802,10 +753,8 @@ int collect_jobs(chm_scenario *s, chm_best *out, uint64_t *position, hipStream_t
       fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
       return CHM_OK;
     }
-    if (best_strategy == 2 && s->h.n_aff > 0) {
-      if (s->fast.split && s->fast.usable[2]) host_reroute_ranks(s, best_part, rr);   // bounded search: no vector tables
-      else for (int a = 0; a < s->h.n_aff; ++a) rr[a] = rec[FINISH_RR + a];
-    }
+    if (best_strategy == 2)
+      for (int a = 0; a < s->h.n_aff; ++a) rr[a] = rec[FINISH_RR + a];
     fill_plan(s, find_family(s, best_strategy), best_part, rr, best_cost, out);
     const int64_t t_trans = (int64_t)rec[FINISH_TRANS];
     if (t_trans < 0 || t_trans > best_cost || (best_cost - t_trans) % s->h.K != 0) return CHM_ERR_HIP;   // cannot happen
@@ -866,15 +815,10 @@ int collect_jobs(chm_scenario *s, chm_best *out, uint64_t *position, hipStream_t
   }
   // the winner's reroute vectors (rerouting only) and its transition time, from the device, behind one
   // synchronisation; its step time follows from cost = horizon x step + transition
-  bool rerouted = best_strategy == 2 && s->h.n_aff > 0;
-  if (rerouted && s->fast.split && s->fast.usable[2] && s->fast.penalty_by_capacity) {
-    host_reroute_ranks(s, best_part, rr);         // bounded search: no vector tables
-    rerouted = false;
-  }
+  const bool rerouted = best_strategy == 2 && s->h.n_aff > 0;
   if (rerouted) {
-    int rc = fast_reroute_winner(&s->fast, s->h, s->d_scn, best_part, s->d_winner, st);
-    if (rc > 0) rc = chmk_reroute_winner(s->d_scn, s->d_comp, best_part, s->d_winner, s->smax, st);
-    if (rc) return CHM_ERR_HIP;
+    const int32_t by_capacity = (s->fast.split && s->fast.usable[2]) ? 1 : 0;     // too many vectors for a one-lane sweep
+    if (chmk_reroute_winner(s->d_scn, s->d_comp, best_part, by_capacity, s->d_winner, s->smax, st)) return CHM_ERR_HIP;
     HIP_TRY(hipMemcpyAsync(s->h_pinned, s->d_winner, DEV_MAX_AFF * sizeof(uint64_t), hipMemcpyDeviceToHost, st));
   }
   if (chmk_plan_transition(s->d_scn, best_strategy, best_part, (int64_t *)s->d_xfer, s->smax, st)) return CHM_ERR_HIP;

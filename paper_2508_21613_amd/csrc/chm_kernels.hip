@@ -310,6 +310,74 @@ __device__ __forceinline__ void sweep_stage(const DevScenario *scn, Cuts<SMAX> c
   *best_rank = br;
 }
 
+// Rank of the best reroute vector of stage a without a sweep, by one wavefront together (all 64 lanes call this
+// with the same cuts).  A vector stays within penalty v exactly when every peer i takes at most floor(v / w_i) extra
+// micro-batches (w_i = its forward + backward time of the stage), so the least penalty is the least v at which the
+// peers' capacities min(cap, floor(v / w_i)) cover the orphans: found by a 64-way search (each lane tries one v per
+// round).  Among the vectors within it the lowest rank is the lexicographically smallest one: every peer in turn
+// takes as little as the peers after it allow; its rank = the number of valid vectors that are lexicographically
+// smaller, read off the count table (the lanes share the additions).  Equals the first minimum of the sweep
+// (sweep_stage): same penalty, lowest rank.
+template <int SMAX>
+__device__ __forceinline__ uint64_t rank_by_capacity(const DevScenario *scn, const uint64_t *comp, Cuts<SMAX> cuts, int a) {
+  const int lane = threadIdx.x & 63;
+  const int p = scn->aff_peers[a];
+  const int64_t orphans = scn->aff_total[a];
+  const int64_t cap = scn->rcap > 0 ? scn->rcap : orphans;
+  int64_t w[DEV_MAX_D];
+  int64_t w_max = 1;
+#pragma unroll
+  for (int i = 0; i < DEV_MAX_D; ++i) {
+    w[i] = i < p ? peer_weight<SMAX>(scn, cuts, a, i) : 0;
+    w_max = w[i] > w_max ? w[i] : w_max;
+  }
+  auto room = [&](int64_t v, int i) -> int64_t {
+    const int64_t fit = w[i] == 0 ? cap : v / w[i];
+    return fit < cap ? fit : cap;
+  };
+  auto covers = [&](int64_t v) -> bool {
+    int64_t sum = 0;
+#pragma unroll
+    for (int i = 0; i < DEV_MAX_D; ++i)
+      if (i < p) sum += room(v, i);
+    return sum >= orphans;
+  };
+  // least v in [lo, hi] with covers(v); covers(hi) holds (every peer could take all orphans, the cap permitting:
+  // the family exists only if the capped peers can absorb them)
+  int64_t lo = 0, hi = orphans * w_max;
+  while (lo < hi) {                                  // uniform
+    const int64_t step = (hi - lo + 62) / 63;          // lane 63 reaches hi
+    int64_t mine = lo + (int64_t)lane * step;
+    mine = mine < hi ? mine : hi;
+    const uint64_t ok = __builtin_amdgcn_ballot_w64(covers(mine));      // lane 63 (or an earlier one) stands at hi
+    const int first = __builtin_ctzll(ok);
+    const int64_t at_first = lo + (int64_t)first * step;
+    hi = at_first < hi ? at_first : hi;
+    lo = first == 0 ? hi : lo + (int64_t)(first - 1) * step + 1;
+  }
+  const int64_t v = lo;
+  const uint64_t *tab = comp + scn->comp_off[a];
+  const uint32_t stride = scn->comp_stride[a];
+  int64_t rem = orphans;
+  uint64_t rank = 0;
+  for (int pos = 0; pos < p; ++pos) {                // uniform
+    int64_t behind = 0;
+#pragma unroll
+    for (int i = 0; i < DEV_MAX_D; ++i)
+      if (i > pos && i < p) behind += room(v, i);
+    const int64_t take = rem - behind > 0 ? rem - behind : 0;
+    const uint32_t left = (uint32_t)(p - 1 - pos);
+    // vectors whose entry at this position is smaller than `take` (and whose earlier entries agree)
+    uint64_t part = 0;
+    for (int64_t t = lane; t < take; t += 64) part += tab[left * stride + (uint32_t)(rem - t)];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off, 64);
+    rank += part;
+    rem -= take;
+  }
+  return rank;
+}
+
 // ---------------------------------------------------------------------------------------
 // wave / block argmin on a packed 64-bit key
 // ---------------------------------------------------------------------------------------
@@ -493,16 +561,27 @@ __global__ void __launch_bounds__(BLOCK) k_search(SearchLaunch a) {
   block_min_to_global(key, a.result + slot);
 }
 
+// ranks of the best reroute vectors of ONE partition of the rerouting family (the winner of a search), per stage
+// that lost nodes: by a sweep of all vectors (one lane per stage), or, by_capacity, from the peers' capacities
+// (one wavefront, stage after stage: for reroute spaces too large to sweep in one lane)
 template <int SMAX>
 __global__ void __launch_bounds__(BLOCK) k_reroute_winner(const DevScenario *scn, const uint64_t *comp,
-                                                          uint64_t part_rank, uint64_t *out) {
+                                                          uint64_t part_rank, int by_capacity, uint64_t *out) {
   __shared__ int32_t cut_cols[SMAX + 2][BLOCK];
   __shared__ int32_t rv_cols[DEV_MAX_D][BLOCK];
-  (void)comp;
-  const int a = threadIdx.x;                         // one lane per affected stage
-  if (a >= scn->n_aff) return;
   const DevFamily &fam = scn->fam[2];
   Cuts<SMAX> cuts{cut_cols, (int)threadIdx.x};
+  if (by_capacity) {
+    if (threadIdx.x >= 64) return;
+    unrank_partition<SMAX>(scn, fam.stages - 1, part_rank, cuts);     // every lane into its own column
+    for (int a = 0; a < scn->n_aff; ++a) {
+      const uint64_t rk = rank_by_capacity<SMAX>(scn, comp, cuts, a);
+      if (threadIdx.x == 0) out[a] = rk;
+    }
+    return;
+  }
+  const int a = threadIdx.x;                         // one lane per affected stage
+  if (a >= scn->n_aff) return;
   unrank_partition<SMAX>(scn, fam.stages - 1, part_rank, cuts);
   int64_t pen; uint64_t rk;
   sweep_stage<SMAX>(scn, cuts, a, rv_cols, &pen, &rk);
@@ -690,12 +769,20 @@ __global__ void __launch_bounds__(BLOCK) k_finish_search(FinishArgs a) {
   if (t == 0) {
     int64_t t_step = 0, reconf = 0;
     a.out[FINISH_TRANS] = (uint64_t)(eval_base<SMAX, false>(scn, fam, cuts, &t_step, &reconf) ? reconf : (int64_t)-1);
-  } else if (a.sweep_winner && strategy == 2 && t >= 64 && (int)(t - 64) < scn->n_aff) {
+  } else if (a.sweep_winner == 1 && strategy == 2 && t >= 64 && (int)(t - 64) < scn->n_aff) {
     // one lane per stage that lost nodes, in the second wavefront, beside the transition time
     const int st = (int)(t - 64);
     int64_t pen; uint64_t rk;
     sweep_stage<SMAX>(scn, cuts, st, rv_cols, &pen, &rk);
     a.out[FINISH_RR + st] = rk;
+  } else if (a.sweep_winner == 2 && strategy == 2 && t >= 64 && t < 128) {
+    // reroute spaces too large for one lane: the second wavefront takes the stages one after the other, from
+    // the peers' capacities (all its lanes read the cuts of column 64)
+    Cuts<SMAX> shared_cuts{cut_cols, 64};
+    for (int st = 0; st < scn->n_aff; ++st) {
+      const uint64_t rk = rank_by_capacity<SMAX>(scn, a.comp, shared_cuts, st);
+      if (t == 64) a.out[FINISH_RR + st] = rk;
+    }
   }
 }
 
@@ -819,12 +906,12 @@ int chmk_finish_search(const FinishArgs &a, int32_t smax, void *stream) {
   });
 }
 
-int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank, uint64_t *d_out,
+int chmk_reroute_winner(const DevScenario *d_scn, const uint64_t *d_comp, uint64_t part_rank, int32_t by_capacity, uint64_t *d_out,
                         int32_t smax, void *stream) {
   return dispatch_smax(smax, [&](auto tag) {
     constexpr int SMAX = decltype(tag)::value;
     hipLaunchKernelGGL(k_reroute_winner<SMAX>, dim3(1), dim3(BLOCK), 0, (hipStream_t)stream, d_scn, d_comp,
-                       part_rank, d_out);
+                       part_rank, (int)by_capacity, d_out);
     return (int)hipGetLastError();
   });
 }
