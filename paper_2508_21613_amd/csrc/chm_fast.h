@@ -2,6 +2,7 @@
 #ifndef CHM_FAST_H
 #define CHM_FAST_H
 #include "chm_dev.h"
+#include "chm_pool.h"
 #include <vector>
 
 enum {
@@ -82,6 +83,7 @@ struct FastState {
   // run on (only that stream is waited for), and a call that waits until no work launched through this handle is
   // in flight any more (made before a buffer that such work may touch is replaced).
   void *load_stream = nullptr;
+  PoolStage stage;                          // pinned staging of the uploads at load (the owner's; may be empty)
   void (*quiesce)(void *) = nullptr;
   void *owner = nullptr;
   FastTables h_tables;

@@ -1846,13 +1846,14 @@ static bool build_reroute_tables(FastState *f, const DevScenario &h) {
   // uploads and the row kernel run on the library's own stream and only that stream is waited for
   hipStream_t ls = (hipStream_t)f->load_stream;
   bool up = pool_take(f->d_runs, runs.size() * sizeof(uint32_t));
-  up = up && hipMemcpyAsync(f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), hipMemcpyHostToDevice, ls) == hipSuccess;
-  up = up && hipMemcpyAsync(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice, ls) == hipSuccess;
+  up = up && pool_staged_upload(&f->stage, f->d_runs, runs.data(), runs.size() * sizeof(uint32_t), ls);
+  up = up && pool_staged_upload(&f->stage, f->d_tables, t, sizeof(FastTables), ls);
   // the vector table itself (rank-ordered rows) only serves the cost store of plan indices; where the vectors are
   // swept by kernels of their own it is tens of MB and is built when a cost store first asks for it
   f->vecs_ready = false;
   if (up && !f->split) up = build_vector_rows(f, h);
   up = (hipStreamSynchronize(ls) == hipSuccess) && up;       // also when something failed: `runs` must outlive its copy
+  f->stage.used = 0;
   f->reroute_tables_ready = up;
   return up;
 }
@@ -1968,14 +1969,18 @@ int fast_prepare(FastState *f, const DevScenario &h, bool int32_ok, const DevSce
   f->reroute_tables_ready = false;
   hipStream_t ls = (hipStream_t)f->load_stream;
   bool up = pool_take(f->d_tables, sizeof(FastTables));
-  up = up && pool_take(f->d_runs, 8 * sizeof(uint32_t));            // placeholder until the tables are built
-  if (up) hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, ls, f->d_runs, 8u, 0u);
-  up = up && hipMemcpyAsync(f->d_tables, t, sizeof(FastTables), hipMemcpyHostToDevice, ls) == hipSuccess;
   if (up && f->usable[2]) up = pool_take(f->d_rowkey, DEV_MAX_AFF * sizeof(uint64_t));
-  up = (hipStreamSynchronize(ls) == hipSuccess) && up;
-  if (!up) return 1;
-  if (f->usable[2] && !f->split) return build_reroute_tables(f, h) ? 0 : 1;
-  return 0;
+  if (up && f->usable[2] && !f->split) {
+    // the vectors are swept inside the search kernel: the (small) tables are built now, behind one wait
+    up = build_reroute_tables(f, h);
+  } else {
+    up = up && pool_take(f->d_runs, 8 * sizeof(uint32_t));          // placeholder until the tables are built (or for good)
+    if (up) hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, ls, f->d_runs, 8u, 0u);
+    up = up && pool_staged_upload(&f->stage, f->d_tables, t, sizeof(FastTables), ls);
+    up = (hipStreamSynchronize(ls) == hipSuccess) && up;
+    f->stage.used = 0;
+  }
+  return up ? 0 : 1;
 }
 
 namespace {

@@ -989,8 +989,11 @@ int upload_scenario(chm_scenario *s, chm_scenario **out) {
   ok = ok && pool_take(s->d_xfer, sizeof(uint64_t) + DEV_MAX_S);
   ok = ok && pool_take_pinned(s->h_pinned, (size_t)SLOT_WORDS * sizeof(uint64_t));
   ok = ok && hipHostGetDevicePointer((void **)&s->d_result, s->h_pinned, 0) == hipSuccess && s->d_result != nullptr;
-  ok = ok && hipMemcpyAsync(s->d_scn, &s->h, sizeof(DevScenario), hipMemcpyHostToDevice, ls) == hipSuccess;
-  ok = ok && hipMemcpyAsync(s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), hipMemcpyHostToDevice, ls) == hipSuccess;
+  // uploads go through the handle's pinned buffer (nothing else uses it before the first search); the first 64
+  // bytes stay free for the word the device sends back below
+  if (ok) { s->fast.stage.base = (unsigned char *)s->h_pinned; s->fast.stage.bytes = (size_t)SLOT_WORDS * sizeof(uint64_t); s->fast.stage.used = 64; }
+  ok = ok && pool_staged_upload(&s->fast.stage, s->d_scn, &s->h, sizeof(DevScenario), ls);
+  ok = ok && pool_staged_upload(&s->fast.stage, s->d_comp, s->comp.data(), s->comp.size() * sizeof(uint64_t), ls);
   for (auto &e : s->ev) ok = ok && hipEventCreate(&e) == hipSuccess;
   const bool fixed = ok && s->h.fam[1].n_part;
   if (fixed) {
@@ -999,6 +1002,7 @@ int upload_scenario(chm_scenario *s, chm_scenario **out) {
     ok = ok && hipMemcpyAsync(s->h_pinned, &s->d_scn->fam[1].fixed_step, sizeof(int64_t), hipMemcpyDeviceToHost, ls) == hipSuccess;
   }
   if (ls) ok = (hipStreamSynchronize(ls) == hipSuccess) && ok;
+  s->fast.stage.used = 0;
   if (ok && fixed) s->h.fam[1].fixed_step = (int64_t)s->h_pinned[0];
   ok = ok && fast_prepare(&s->fast, s->h, s->int32_ok, s->d_scn, s->d_comp) == 0;
   if (!ok) { release(s); return CHM_ERR_HIP; }

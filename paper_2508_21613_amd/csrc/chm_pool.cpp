@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <cstdint>
+#include <cstring>
 #include <map>
 #include <mutex>
 #include <tuple>
@@ -75,4 +76,17 @@ void pool_release(void *p) {
   // beyond what is kept: back to the runtime (which waits for the device on its own)
   if (b.pinned) (void)hipHostFree(p);
   else (void)hipFree(p);
+}
+
+bool pool_staged_upload(PoolStage *stage, void *dst, const void *src, size_t bytes, void *stream) {
+  const void *from = src;
+  if (stage && stage->base) {
+    const size_t at = (stage->used + 255) & ~(size_t)255;
+    if (at + bytes <= stage->bytes) {
+      memcpy(stage->base + at, src, bytes);
+      from = stage->base + at;
+      stage->used = at + bytes;
+    }
+  }
+  return hipMemcpyAsync(dst, from, bytes, hipMemcpyHostToDevice, (hipStream_t)stream) == hipSuccess;
 }
