@@ -350,6 +350,7 @@ __device__ __forceinline__ uint64_t rank_by_capacity(const DevScenario *scn, con
     int64_t mine = lo + (int64_t)lane * step;
     mine = mine < hi ? mine : hi;
     const uint64_t ok = __builtin_amdgcn_ballot_w64(covers(mine));      // lane 63 (or an earlier one) stands at hi
+    if (ok == 0) { lo = hi; break; }                 // cannot happen (covers(hi) holds); keeps the loop finite regardless
     const int first = __builtin_ctzll(ok);
     const int64_t at_first = lo + (int64_t)first * step;
     hi = at_first < hi ? at_first : hi;

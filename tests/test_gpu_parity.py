@@ -895,10 +895,10 @@ def test_independent_handles_on_concurrent_threads(B):
     assert not errors, errors[:5]
 
 
-def _reroute_case(seed, DP, M, cap, failed, L=9, PP=3):
+def _reroute_case(seed, DP, M, cap, failed, L=9, PP=3, hetero=True):
     fwd, bwd, mem = synth.layer_tables(seed, L)
     return synth.scenario(L, PP, DP, M, fwd, bwd, mem, failed, 130, int(mem.sum() * 1.9 / PP),
-                          speed=synth.speed_factors(seed, DP, PP), reroute_cap=cap)
+                          speed=synth.speed_factors(seed, DP, PP) if hetero else None, reroute_cap=cap)
 
 
 GROUPED = [
@@ -912,6 +912,10 @@ GROUPED = [
     ("p8_cap8", _reroute_case(9108, 9, 16, 8, [13])),                         # 217,701
     ("p6_cap12_run_sweep", _reroute_case(9109, 7, 24, 12, [5])),              # a cap the grouped sweep is not compiled for
     ("p5_cap16_three_stages", _reroute_case(9110, 6, 32, 16, [0, 4, 8])),     # 3 x 39,525: every stage lost a node
+    # identical peers: thousands of vectors share the least penalty, the lowest rank among them must come out
+    ("p5_cap16_identical_peers", _reroute_case(9111, 6, 32, 16, [4], hetero=False)),
+    ("p7_cap8_identical_peers_two_stages", _reroute_case(9112, 8, 16, 8, [1, 11], hetero=False)),
+    ("p6_cap12_identical_peers", _reroute_case(9113, 7, 24, 12, [5], hetero=False)),
 ]
 
 
