@@ -27,7 +27,11 @@
  *     chm_load_scenario; they may be freed as soon as it returns.
  *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).
  *   - A handle must not be used by two host threads at once; different handles are
- *     independent.  A handle belongs to the device that was current when it was loaded.
+ *     independent (loading, searching and freeing one never waits for work of another).  A
+ *     handle belongs to the device that was current when it was loaded.  The asynchronous
+ *     calls (chm_score_plans, chm_score_ranks, chm_rank_partitions) use scratch of the handle:
+ *     a later call on the same handle must be issued on the same stream, or after the caller
+ *     has waited for the earlier one.
  *   - Times are int32 microseconds, memory is int32 MiB, speed factors are Q16 time
  *     multipliers (65536 = nominal, 75366 = 15 % slower).  Costs are int64.
  *
