@@ -181,8 +181,11 @@ int chm_search_best(chm_scenario *s, uint32_t strategy_mask, chm_best *out, void
 
 /* chm_search_best on n distinct handles of one device in one call (the plan cache of the Planner's overhead
  * paragraph: the best plan for every failure set that may occur, searched ahead of time).  The searches of all
- * handles are launched back to back on hip_stream and the host waits once for the whole batch instead of once
- * per handle; outs[i] and codes[i] (host arrays of n) receive what chm_search_best would have returned for
+ * handles are launched back to back and the host waits once for the whole batch instead of once per handle.
+ * From 8 handles on they are dealt out over four streams of the library's own (default priority), which start
+ * behind the work already queued on hip_stream and which hip_stream waits for before the call returns, so that
+ * the kernels of different handles overlap at their ends; timings read with chm_get_timing then include that
+ * overlap.  outs[i] and codes[i] (host arrays of n) receive what chm_search_best would have returned for
  * handles[i], bounded or exhaustive as set on each handle.  Returns CHM_OK when every search ran (codes[i] may
  * still be CHM_ERR_NO_FEASIBLE, CHM_ERR_UNRECOVERABLE, CHM_ERR_OVERFLOW), CHM_ERR_ARG for a null or repeated
  * handle or handles of different devices, CHM_ERR_HIP when a HIP call failed.  Synchronises hip_stream. */
