@@ -13,6 +13,9 @@ The GPU parity tests compare chm_search_best (exhaustive and bounded) and its fe
 with this file.  Nothing here imports or calls the HIP library; the inputs are the seeded generators.
 The file is resumable: families already present in --out are kept, so a run can be continued.
 
+With --more N the same for N further seeded double failures of config 5, kept in full_space_more.json as slim
+records (winners' index, cost and cuts; fitting partitions).
+
 Cases: config 1, config 2 and config 3 as the task states them, and failure sets of config 5 (the
 plan cache of the Planner's overhead paragraph): all 32 single failures and seeded double failures
 of every kind (two failures in one pipeline: neighbouring stages, the ring pair first/last stage,
@@ -66,6 +69,24 @@ def config5_doubles():
             seen.add(tuple(f))
             out.append(f)
     return out
+
+
+def config5_more_doubles(n=120):
+    """n further seeded double failures of config 5 (none of config5_doubles()), for full_space_more.json"""
+    have = {tuple(f) for f in config5_doubles()}
+    pairs = [(a, b) for a in range(32) for b in range(a + 1, 32) if (a, b) not in have]
+    order = synth.randint(synth.BASE_SEED + 5, 78, len(pairs), 0, 1 << 30)
+    ranked = sorted(range(len(pairs)), key=lambda i: (int(order[i]), i))
+    return [list(pairs[i]) for i in ranked[:n]]
+
+
+def slim(rec):
+    """what full_space_more.json keeps of a case record: index, cost and cuts of the winners, fitting partitions"""
+    def plan(b):
+        return None if b is None else {"index": b["index"], "cost": b["cost"], "strategy": b["strategy"], "cuts": b["cuts"]}
+    return {"failed_nodes": rec["failed_nodes"], "best": plan(rec["best"]),
+            "families": [{"strategy": f["strategy"], "n_part": f["n_part"], "n_reroute": f["n_reroute"], "feasible": f["feasible"],
+                          "best": plan(f["best"])} for f in rec["families"]]}
 
 
 def case_names():
@@ -181,9 +202,13 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--workers", type=int, default=os.cpu_count())
     ap.add_argument("--only", nargs="*", default=None)
-    ap.add_argument("--out", default=OUT)
+    ap.add_argument("--out", default=None)
+    ap.add_argument("--more", type=int, default=0,
+                    help="instead of the main set: this many further double failures of config 5, slim records, full_space_more.json")
     a = ap.parse_args()
-    names = a.only or case_names()
+    if a.out is None:
+        a.out = os.path.join(HERE, "full_space_more.json") if a.more else OUT
+    names = a.only or (["config5:%d,%d" % (x, y) for x, y in config5_more_doubles(a.more)] if a.more else case_names())
     done = {}
     if os.path.exists(a.out):
         with open(a.out) as fh:
@@ -191,8 +216,10 @@ def main():
     doc = {"generator": "tests/golden/make_full_space.py (CPU oracle only)", "cases": dict(done)}
     for name in names:                                # case by case, so that an interrupted run keeps what it has
         t0 = time.time()
-        rec = full_space([name], a.workers, done=done, progress=lambda m: print("  " + m, file=sys.stderr, flush=True))
-        doc["cases"].update(rec)
+        if a.more and name in done:
+            continue
+        rec = full_space([name], a.workers, done=None if a.more else done, progress=lambda m: print("  " + m, file=sys.stderr, flush=True))
+        doc["cases"].update({k: slim(v) for k, v in rec.items()} if a.more else rec)
         with open(a.out + ".tmp", "w") as fh:
             json.dump(doc, fh, indent=1, sort_keys=True)
         os.replace(a.out + ".tmp", a.out)

@@ -97,3 +97,29 @@ def test_golden_file_covers_what_it_should():
 
 def sc_horizon(name):
     return MFS.case_scenario(name)["horizon_steps"]
+
+
+def test_further_stored_records_are_consistent():
+    """full_space_more.json (slim records of further double failures of config 5): every stored winner decodes to the
+    stored cuts and cost, the overall winner is the first minimum over the strategies, and none of the cases is one
+    of the main file's"""
+    path = os.path.join(HERE, "golden", "full_space_more.json")
+    if not os.path.exists(path):
+        return
+    with open(path) as fh:
+        cases = json.load(fh)["cases"]
+    with open(os.path.join(HERE, "golden", "full_space.json")) as fh:
+        main = json.load(fh)["cases"]
+    wanted = {"config5:%d,%d" % (a, b) for a, b in MFS.config5_more_doubles(len(cases))}
+    assert set(cases) <= {"config5:%d,%d" % (a, b) for a, b in MFS.config5_more_doubles(400)} and not set(cases) & set(main)
+    assert len(cases) < 8 or len(set(cases) & wanted) >= len(cases) - 8      # (a run in progress may be a few cases ahead)
+    for name, rec in cases.items():
+        o = O.Scenario(MFS.case_scenario(name))
+        assert [(f["strategy"], f["n_part"], f["n_reroute"]) for f in o.families] == \
+               [(f["strategy"], f["n_part"], f["n_reroute"]) for f in rec["families"]], name
+        assert rec["best"] == MFS.best_of_families(rec["families"])
+        for f in rec["families"]:
+            assert 0 <= f["feasible"] <= f["n_part"] and (f["best"] is None) == (f["feasible"] == 0)
+            if f["best"] is not None:
+                d = o.decode(f["best"]["index"])
+                assert d["cuts"] == f["best"]["cuts"] and d["cost"] == f["best"]["cost"] and d["strategy"] == f["strategy"]

@@ -203,3 +203,49 @@ def test_all_528_failure_sets_of_config5(B):
     assert pinned == 50
     for g in gs:
         g.close()
+
+
+_MORE = os.path.join(HERE, "golden", "full_space_more.json")
+if os.path.exists(_MORE):
+    with open(_MORE) as _fh:
+        GOLD_MORE = json.load(_fh)["cases"]
+else:
+    GOLD_MORE = {}
+
+
+def test_further_double_failures_of_config5(B):
+    """tests/golden/full_space_more.json (make_full_space.py --more): the oracle's whole-space argmin of further seeded
+    double failures of config 5, as slim records: winner per strategy and overall (index, cost, cuts) and fitting
+    partitions, against the exhaustive and the bounded batched search"""
+    if not GOLD_MORE:
+        pytest.skip("no further cases stored")
+    names = sorted(GOLD_MORE)
+    gs = [B.Scenario(MFS.case_scenario(n)) for n in names]
+    for g in gs:
+        g.set_timing(True)
+
+    def same(best, want):
+        return all(best[k] == want[k] for k in ("index", "cost", "strategy", "cuts"))
+
+    for bounded in (0, 1):
+        for g in gs:
+            g.set_bounded_search(bounded)
+        for mask in (7, 1, 2, 4):
+            res = B.search_best_batch(gs, mask)
+            for name, g, (rc, best) in zip(names, gs, res):
+                rec = GOLD_MORE[name]
+                fams = [f for f in rec["families"] if mask & (1 << f["strategy"])]
+                if not fams:
+                    assert rc == B.ERR_UNRECOVERABLE, (name, mask)
+                    continue
+                want = MFS.best_of_families(fams)
+                if want is None:
+                    assert rc == B.ERR_NO_FEASIBLE, (name, mask)
+                    continue
+                assert rc == B.OK and same(best, want), (name, mask, bounded, best, want)
+                if bounded == 0:
+                    t = g.get_timing()
+                    for f in fams:
+                        assert t["feasible"][f["strategy"]] == f["feasible"], (name, f["strategy"])
+    for g in gs:
+        g.close()
